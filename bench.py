@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoCoCo hot path on one MI355X.
+
+A "step" is one call of lococo_sequence_forward -- the whole Alg. 2 scan
+(attention, fill / convolution logits, normalisation, fusion for every block)
+-- over one synthetic sequence batch of the named workload, with all inputs
+already resident in HBM.  value = batch * L / time per step (tokens/s for one
+layer's heads).
+
+Prints ONE JSON line with the throughput, a `roofline` object for the dominant
+kernel (timed live with HIP events on the library's stream) and a
+`cpu_baseline` object (the CPU oracle timed on a bounded sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0      # MI355X dense bf16
+PEAK_FP32_VALU_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def step_flops(w, m, Bn):
+    """Algorithmic flops of one block step for ALL chains, by part (causal-exact attention)."""
+    chains = w.batch * w.n_kv_heads
+    T = m + Bn
+    attn = 4.0 * w.head_dim * Bn * (m + (Bn + 1) / 2.0) * w.group * chains
+    if m + Bn <= w.M:
+        return {"attn": attn, "conv": 0.0, "mix": 0.0}
+    conv = 2.0 * w.M * T * w.C * w.conv_width * chains
+    mix = 4.0 * w.M * T * w.head_dim * chains
+    return {"attn": attn, "conv": conv, "mix": mix}
+
+
+def scan_flops(w, plan):
+    tot = {"attn": 0.0, "conv": 0.0, "mix": 0.0}
+    for (_, ln, _, before, _, _) in plan:
+        for k_, f in step_flops(w, before, ln).items():
+            tot[k_] += f
+    return tot
+
+
+# which parts of the algorithmic work each kernel of the library carries
+KERNEL_PARTS = {
+    "attn_generic": ("attn",), "attn_mfma": ("attn",),
+    "conv_logits_generic": ("conv",), "mix_generic": ("mix",),
+    "compress_mfma": ("conv", "mix"),
+}
+KERNEL_BOUND = {  # roofline that bounds each kernel, peak, unit
+    "attn_generic": ("mfma", PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
+    "attn_mfma": ("mfma", PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
+    "conv_logits_generic": ("mfma", PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
+    "mix_generic": ("mfma", PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
+    "compress_mfma": ("mfma", PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
+}
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """Oracle (as it stands) on a bounded sample: `threads` chains, the first
+    few blocks of the scan, scaled to tokens/s of the whole layer."""
+    import numpy as np
+    from oracle import lococo_oracle as orc
+    from paper_2406_05317_amd import inputs
+    threads = min(os.cpu_count() or 1, 16)
+    chains_total = w.batch * w.n_kv_heads
+    n_chains = min(threads, chains_total)
+    cw, cb = inputs.conv_filters(w)
+    # size the sample from a one-chain, two-block probe
+    def run(nc, nseg):
+        L = min(w.L, nseg * w.B)
+        qs, ks, vs = [], [], []
+        for c in range(nc):
+            b, h = divmod(c, w.n_kv_heads)
+            q, k, v = inputs.chain_inputs(w, b, h, L)
+            qs.append(q); ks.append(k[None]); vs.append(v[None])
+        import torch
+        q = torch.cat(qs)[None]; k = torch.cat(ks)[None]; v = torch.cat(vs)[None]
+        cwx = cw if cw.dim() == 3 else cw[:1].repeat(nc, 1, 1, 1)
+        cbx = cb if cb.dim() == 1 else cb[:1].repeat(nc, 1)
+        t0 = time.perf_counter()
+        orc.sequence_forward(q, k, v, cwx, cbx, B=w.B, M=w.M, conv_in=w.conv_in, norm=w.norm,
+                             state_round=w.dtype, nthreads=nc)
+        return time.perf_counter() - t0, L
+    fills = w.M // w.B
+    t_probe, _ = run(1, fills + 1)                       # one compress step on one chain
+    nseg = int(max(fills + 1, min(w.L // w.B, fills + budget_s / max(t_probe, 1e-3))))
+    t, L = run(n_chains, nseg)
+    tokens_equiv = w.batch * L * (n_chains / chains_total)   # whole-layer tokens this work equals
+    return {"value": tokens_equiv / t, "unit": "tokens/s", "cores": n_chains, "kind": "oracle",
+            "sample": f"{n_chains} of {chains_total} chains x first {nseg} blocks ({L} tokens) of "
+                      f"{w.name}, {t:.1f} s, scaled linearly by chain count"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--impl", type=int, default=0, help="0 auto, 1 generic kernels, 2 MFMA only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-history", action="store_true",
+                    help="step-by-step schedule instead of the batched-attention one")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards over (batch, kv-head) chains "
+              "with no communication, so there is no multi-GPU figure to report. Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_05317_amd import binding as lb
+    from paper_2406_05317_amd import inputs
+    w = inputs.CONFIGS[args.workload]
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    cfg = lb.config_for(w, impl=args.impl)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    qd, kd, vd, cwd, cbd = (t.to(dev) for t in (q, k, v, cw, cb))
+    od = torch.empty_like(qd)
+    cache = lb.Cache(cfg, dev)
+    ws = lb.workspace(cfg, w.L, w.B, not args.no_history, dev)
+    plan = lb.lococo_plan(w.L, w.B, w.M)
+    flops = scan_flops(w, plan)
+
+    def step():
+        cache.c.len = 0                                  # fresh sequence (host-side state only)
+        lb.lococo_sequence_forward(cfg, qd, kd, vd, od, cwd, cbd, cache, w.B, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lb.lococo_timing_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kt = lb.lococo_timing_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = w.batch * w.L
+    value = tokens / (ms_per_step * 1e-3)
+
+    # dominant kernel = largest share of device time in the timed region
+    name = max(kt, key=lambda n: kt[n][1])
+    launches, total_ms = kt[name]
+    bound, peak, unit = KERNEL_BOUND.get(name, ("mfma", PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"))
+    part_flops = sum(flops[p] for p in KERNEL_PARTS.get(name, ())) * args.steps
+    achieved = part_flops / (total_ms * 1e-3) / 1e12 if total_ms > 0 else 0.0
+    roofline = {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "traffic": None, "launches": launches,
+                "avg_launch_us": total_ms * 1e3 / max(launches, 1),
+                "flops_per_launch": part_flops / max(launches, 1),
+                "kernel_ms_per_step": {n: kt[n][1] / args.steps for n in kt}}
+    total_flops = sum(flops.values())
+    out = {
+        "metric": "segment-step tokens/sec per layer (whole Alg. 2 scan incl. attention, conv "
+                  "logits, normalisation, fusion)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.L, "B": w.B,
+                   "M": w.M, "conv_width": w.conv_width, "conv_channels": w.C,
+                   "schedule": "step-by-step" if args.no_history else "batched-attention",
+                   "impl": args.impl},
+        "segment_step_tokens_per_s": w.batch * w.B / (ms_per_step * 1e-3 / len(plan)),
+        "mfma_util_whole_path": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,196 @@
+/*
+ * lococo.h -- C ABI of the MI355X (gfx950) LoCoCo segment-step library.
+ *
+ * The library computes, for already projected and position-encoded Q/K/V,
+ * the forward pass of the paper's Algorithm 2 ("LoCoCo attention"):
+ *
+ *   step 3   O_n = Attn([Kc, K_n], Q_n, [Vc, V_n])            (Eq. 1, Alg. 2 step 3)
+ *   IF       #cache + B <= M : append K_n, V_n to the cache     (Alg. 2, IF branch)
+ *   step 4   W = g (*) [Kc ; K_n]   (1-D convolution, Eq. 5),
+ *            w = W normalised per slot over the positions       (Eq. 6)
+ *   step 5   Kc' = w [Kc ; K_n],  Vc' = w [Vc ; V_n]            (Eq. 3, Eq. 4a/4b)
+ *
+ * and the scan of that step over a sequence cut into blocks of B tokens.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    allocates and frees no device memory; scratch comes from the caller's
+ *    `workspace` argument (see lococo_workspace_bytes).
+ *  - Struct pointers (config, cache, qkvo, plan rows) are HOST pointers.
+ *  - Layouts are row-major with head_dim contiguous.  Strides are in ELEMENTS.
+ *  - Arguments are validated synchronously; on any status other than
+ *    LOCOCO_OK nothing was enqueued and `cache` is unchanged.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream) and the call returns without synchronising.
+ *    `cache->cur` / `cache->len` are updated on the host at enqueue time.
+ *  - No C++ exception crosses the boundary.  lococo_last_error() returns a
+ *    thread-local message for the last non-OK status on this thread.
+ *  - Calls that use the same cache or workspace must be ordered by the caller
+ *    (same stream, or events).
+ *
+ * Readings of the paper fixed by this interface
+ * ---------------------------------------------
+ *  - Blocks are 0-based: block n covers tokens [n*B, min((n+1)*B, L)); the
+ *    last one may be short.
+ *  - Concatenation is cache first, then block (Alg. 2 step 3, Eq. 3), for
+ *    attention, for the convolution input and for the fusion.
+ *  - Mask: every cache slot is visible to every block query; block key j' is
+ *    visible to block query j iff j' <= j.
+ *  - Convolution: cross-correlation, zero padding (k-1)/2 on both sides,
+ *    stride 1, odd width only.
+ *  - Eq. 6 as a softmax over the positions (norm = 0) or, literally,
+ *    relu(W) / (sum relu(W) + eps) (norm = 1).
+ *  - A compress step with a partly filled cache (m < M, m + B > M) mixes the
+ *    m + B entries present.
+ */
+#ifndef LOCOCO_H
+#define LOCOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lococo_status {
+  LOCOCO_OK = 0,
+  LOCOCO_EINVAL = 1,       /* null pointer, non-positive size, bad stride, aliasing, ...    */
+  LOCOCO_EUNSUPPORTED = 2, /* well-formed but not implemented (even conv width, huge T ...) */
+  LOCOCO_ESTATE = 3,       /* cache occupancy / buffer index out of range                   */
+  LOCOCO_EHIP = 4,         /* a HIP runtime call failed; message holds hipGetErrorString    */
+  LOCOCO_EWORKSPACE = 5    /* workspace missing, misaligned or smaller than required        */
+} lococo_status;
+
+enum { LOCOCO_F32 = 0, LOCOCO_BF16 = 1 };
+enum { LOCOCO_IMPL_AUTO = 0, LOCOCO_IMPL_GENERIC = 1, LOCOCO_IMPL_MFMA = 2 };
+
+/* Problem description.  Plain data, filled by the caller. */
+typedef struct lococo_config {
+  uint32_t struct_size;   /* sizeof(lococo_config); guards against ABI skew                       */
+  int32_t dtype;          /* LOCOCO_F32 / LOCOCO_BF16: storage type of q,k,v,o, cache and filters */
+  int32_t batch;
+  int32_t n_q_heads;      /* multiple of n_kv_heads; query head h reads kv head h / group         */
+  int32_t n_kv_heads;     /* one cache and one compression per (batch, kv head) chain             */
+  int32_t head_dim;       /* d                                                                    */
+  int32_t M;              /* cache slots (Eq. 3: the compressed length)                           */
+  int32_t conv_width;     /* k, odd, >= 1 (Eq. 5; the paper's default is 21)                      */
+  int32_t conv_in;        /* 0: filters read keys only, C = d; 1: keys stacked on values along
+                             channels, C = 2d (Eq. 5 as printed), K channels first               */
+  int32_t norm;           /* 0: softmax over the positions; 1: relu(W)/(sum relu(W)+norm_eps)     */
+  int32_t impl;           /* LOCOCO_IMPL_*: AUTO picks the MFMA kernels when the shape allows,
+                             GENERIC forces the shape-agnostic kernels, MFMA fails with
+                             LOCOCO_EUNSUPPORTED when the shape does not allow them               */
+  int32_t reserved;       /* must be 0                                                            */
+  int64_t w_head_stride;  /* elements between per-kv-head filter banks; 0 = one shared bank       */
+  int64_t b_head_stride;  /* same for the bias                                                    */
+  float attn_scale;       /* 0 => 1/sqrt(head_dim)                                                */
+  float norm_eps;         /* only for norm = 1; 0 => 1e-6                                         */
+} lococo_config;
+
+/* Recurrent state of the scan: the fixed-size KV cache, double buffered. */
+typedef struct lococo_cache {
+  void* k[2];   /* each [batch, n_kv_heads, M, head_dim], contiguous, 16-byte aligned */
+  void* v[2];
+  int32_t cur;  /* which of the two buffers is live (0/1)                             */
+  int32_t len;  /* live slots 0..M, the same for every chain                          */
+} lococo_cache;
+
+/* A [batch, heads, tokens, head_dim] tensor view; head_dim contiguous. */
+typedef struct lococo_tensor {
+  void* p;
+  int64_t stride_b, stride_h, stride_t;  /* elements; stride_t >= head_dim, multiples of 8 for bf16 */
+} lococo_tensor;
+
+/* One block (or one whole sequence) of inputs and the attention output.
+ * q, o: n_q_heads heads; k, v: n_kv_heads heads.  o must not alias an input. */
+typedef struct lococo_qkvo {
+  lococo_tensor q, k, v, o;
+} lococo_qkvo;
+
+/* One row of the integer plan of a scan (Alg. 2 loop and its IF). */
+typedef struct lococo_seg {
+  int64_t start;       /* first token of the block                         */
+  int32_t len;         /* tokens in the block (B, or fewer for the last)   */
+  int32_t branch;      /* 0: fill (append), 1: compress (steps 4-5)        */
+  int32_t len_before;  /* cache occupancy seen by the attention            */
+  int32_t len_after;   /* occupancy after the step                         */
+  int32_t buf_after;   /* live buffer index after the step                 */
+  int32_t reserved;
+} lococo_seg;
+
+/* Alg. 2 loop bounds and IF, as integers.  *n_inout holds the capacity of
+ * `out` on entry (out may be NULL with capacity 0) and the number of blocks
+ * on return; at most the capacity is written.  Host pointers. */
+lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_t cur0,
+                          lococo_seg* out, int64_t* n_inout);
+
+/* Bytes of device workspace lococo_segment_step (L = B) or
+ * lococo_sequence_forward (L = sequence length) need for this shape.  Passing
+ * `history` != 0 asks for the larger size with which lococo_sequence_forward
+ * keeps every intermediate cache and runs all blocks' attention as one
+ * batched launch after the compression scan.  May return 0. */
+lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
+                                     int32_t history, size_t* out);
+
+/* Alg. 2 step 3 alone: o = Attn([Kc, K_blk], Q_blk, [Vc, V_blk]) for one block
+ * of B tokens against the live cache (cache->len slots).  Does not modify the
+ * cache.  With an empty cache this is plain causal attention (Eq. 1). */
+lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                               const lococo_cache* cache, void* stream);
+
+/* One pass of the Alg. 2 loop body: step 3, then either the fill branch or
+ * steps 4-5 (Eq. 5, Eq. 6, Eq. 4a/4b) into the other cache buffer.
+ * conv_w: [M, C, k] (device, storage dtype); conv_b: [M] or NULL.
+ * workspace: device, 256-byte aligned, ws_bytes >= lococo_workspace_bytes(cfg, B, B, 0). */
+lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                  const void* conv_w, const void* conv_b, lococo_cache* cache,
+                                  void* workspace, size_t ws_bytes, void* stream);
+
+/* The whole Alg. 2 loop over a sequence of L tokens in blocks of B, starting
+ * from `cache` (len = 0 for a fresh sequence) and leaving the final cache in
+ * it.  seq.q/o: [batch, n_q_heads, L, d]; seq.k/v: [batch, n_kv_heads, L, d].
+ * If ws_bytes >= lococo_workspace_bytes(cfg, L, B, 1) the batched-attention
+ * schedule is used, otherwise the step-by-step one; results are the same. */
+lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
+                                      int32_t B, const void* conv_w, const void* conv_b,
+                                      lococo_cache* cache, void* workspace, size_t ws_bytes,
+                                      void* stream);
+
+/* Steps 4-5 with Eq. 5's output supplied by the caller: the cache becomes
+ * normalise(logits) . [cache ; block] (Eq. 6, Eq. 4a/4b).  logits: device fp32
+ * [batch, n_kv_heads, M, T] contiguous with T = cache->len + B.  Only blk->k
+ * and blk->v are read.  Exists so that tests can drive the fusion with chosen
+ * weights (e.g. one-hot rows: token selection, the paper's "token dropping"
+ * special case).  Always compresses, whatever the occupancy. */
+lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                     const float* logits, lococo_cache* cache, void* stream);
+
+/* Optional per-kernel timing.  Between lococo_timing_begin() and
+ * lococo_timing_end() every kernel the library launches (from any thread) is
+ * bracketed by a pair of HIP events recorded on the stream it is launched on.
+ * lococo_timing_end() waits for those events and returns one row per kernel
+ * that ran: its name (static storage), the number of launches and the summed
+ * device time in milliseconds.  *n_inout: capacity of `out` on entry, rows
+ * available on return.  Host pointers.  Meant for benchmarks; not thread safe
+ * against concurrent begin/end. */
+typedef struct lococo_kernel_time {
+  const char* name;
+  int64_t launches;
+  double total_ms;
+} lococo_kernel_time;
+lococo_status lococo_timing_begin(void);
+lococo_status lococo_timing_end(lococo_kernel_time* out, int32_t* n_inout);
+
+/* Message for the last non-OK status returned on the calling thread
+ * (static thread-local storage; never NULL). */
+const char* lococo_last_error(void);
+
+/* Library version, "major.minor.patch". */
+const char* lococo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOCOCO_H */

@@ -1,0 +1,438 @@
+// Host side of the C ABI declared in lococo.h: argument validation, the
+// integer plan of the scan (Alg. 2 loop and IF), path selection and kernel
+// sequencing.  No arithmetic of the method happens here.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "lococo_internal.h"
+
+using namespace lococo;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+lococo_status fail(lococo_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+lococo_status hip_fail(hipError_t e, const char* what) {
+  return fail(LOCOCO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr, what)                         \
+  do {                                              \
+    hipError_t e_ = (expr);                         \
+    if (e_ != hipSuccess) return hip_fail(e_, what); \
+  } while (0)
+
+// ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
+enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC, K_COUNT };
+const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
+                                           "normalise_generic", "mix_generic"};
+struct TimedLaunch { int id; hipEvent_t start, stop; };
+std::mutex g_timing_mu;
+bool g_timing_on = false;
+std::vector<TimedLaunch> g_timed;
+
+// Records an event pair around the launches made while it is alive.
+struct KTimer {
+  int id;
+  hipStream_t s;
+  hipEvent_t start = nullptr, stop = nullptr;
+  KTimer(int id_, hipStream_t s_) : id(id_), s(s_) {
+    if (!g_timing_on) return;
+    if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) {
+      start = stop = nullptr;
+      return;
+    }
+    (void)hipEventRecord(start, s);
+  }
+  ~KTimer() {
+    if (!start) return;
+    (void)hipEventRecord(stop, s);
+    std::lock_guard<std::mutex> lk(g_timing_mu);
+    g_timed.push_back(TimedLaunch{id, start, stop});
+  }
+};
+
+size_t esize(int dtype) { return dtype == LOCOCO_F32 ? 4 : 2; }
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+lococo_status check_config(const lococo_config* c) {
+  if (!c) return fail(LOCOCO_EINVAL, "config is NULL");
+  if (c->struct_size != sizeof(lococo_config))
+    return fail(LOCOCO_EINVAL, "config.struct_size is %u, this library expects %zu", c->struct_size,
+                sizeof(lococo_config));
+  if (c->dtype != LOCOCO_F32 && c->dtype != LOCOCO_BF16)
+    return fail(LOCOCO_EINVAL, "config.dtype %d is neither LOCOCO_F32 nor LOCOCO_BF16", c->dtype);
+  if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->M <= 0)
+    return fail(LOCOCO_EINVAL, "batch, head counts, head_dim and M must be positive");
+  if (c->n_q_heads % c->n_kv_heads)
+    return fail(LOCOCO_EINVAL, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", c->n_q_heads,
+                c->n_kv_heads);
+  if (c->conv_width < 1) return fail(LOCOCO_EINVAL, "conv_width must be >= 1");
+  if (c->conv_width % 2 == 0)
+    return fail(LOCOCO_EUNSUPPORTED, "conv_width %d is even; only odd widths have a centred "
+                "same-length convolution", c->conv_width);
+  if (c->conv_in != 0 && c->conv_in != 1) return fail(LOCOCO_EINVAL, "conv_in must be 0 or 1");
+  if (c->norm != 0 && c->norm != 1) return fail(LOCOCO_EINVAL, "norm must be 0 or 1");
+  if (c->impl < LOCOCO_IMPL_AUTO || c->impl > LOCOCO_IMPL_MFMA)
+    return fail(LOCOCO_EINVAL, "impl must be one of LOCOCO_IMPL_*");
+  if (c->reserved != 0) return fail(LOCOCO_EINVAL, "config.reserved must be 0");
+  if (c->w_head_stride < 0 || c->b_head_stride < 0)
+    return fail(LOCOCO_EINVAL, "filter head strides must be >= 0");
+  if (!(c->attn_scale >= 0.f) || !(c->norm_eps >= 0.f) || std::isinf(c->attn_scale))
+    return fail(LOCOCO_EINVAL, "attn_scale and norm_eps must be finite and >= 0");
+  if (c->head_dim > 1024) return fail(LOCOCO_EUNSUPPORTED, "head_dim > 1024");
+  if (c->n_q_heads > 65535 || c->batch > 65535 || c->M > 65535 ||
+      (int64_t)c->batch * c->n_kv_heads > 65535)
+    return fail(LOCOCO_EUNSUPPORTED, "batch, heads, M or batch*n_kv_heads above 65535");
+  return LOCOCO_OK;
+}
+
+lococo_status check_tensor(const lococo_config* c, const lococo_tensor& t, const char* name,
+                           int64_t tokens) {
+  if (!t.p) return fail(LOCOCO_EINVAL, "%s pointer is NULL", name);
+  if (t.stride_t < c->head_dim)
+    return fail(LOCOCO_EINVAL, "%s.stride_t (%lld) is below head_dim", name, (long long)t.stride_t);
+  if (t.stride_h < 0 || t.stride_b < 0)
+    return fail(LOCOCO_EINVAL, "%s strides must be non-negative", name);
+  if (c->dtype == LOCOCO_BF16 &&
+      ((t.stride_t | t.stride_h | t.stride_b) % 8 || ((uintptr_t)t.p & 15)))
+    return fail(LOCOCO_EINVAL, "%s: bf16 tensors need 16-byte aligned pointers and strides that "
+                "are multiples of 8 elements", name);
+  if (c->dtype == LOCOCO_F32 && ((uintptr_t)t.p & 3))
+    return fail(LOCOCO_EINVAL, "%s pointer is not 4-byte aligned", name);
+  (void)tokens;
+  return LOCOCO_OK;
+}
+
+lococo_status check_cache(const lococo_config* c, const lococo_cache* ca) {
+  if (!ca) return fail(LOCOCO_EINVAL, "cache is NULL");
+  for (int i = 0; i < 2; ++i) {
+    if (!ca->k[i] || !ca->v[i]) return fail(LOCOCO_EINVAL, "cache buffer pointer is NULL");
+    if (((uintptr_t)ca->k[i] | (uintptr_t)ca->v[i]) & 15)
+      return fail(LOCOCO_EINVAL, "cache buffers must be 16-byte aligned");
+  }
+  const void* p[4] = {ca->k[0], ca->k[1], ca->v[0], ca->v[1]};
+  for (int i = 0; i < 4; ++i)
+    for (int j = i + 1; j < 4; ++j)
+      if (p[i] == p[j]) return fail(LOCOCO_EINVAL, "cache buffers alias each other");
+  if (ca->cur != 0 && ca->cur != 1) return fail(LOCOCO_ESTATE, "cache.cur is %d", ca->cur);
+  if (ca->len < 0 || ca->len > c->M)
+    return fail(LOCOCO_ESTATE, "cache.len %d is outside [0, M=%d]", ca->len, c->M);
+  return LOCOCO_OK;
+}
+
+lococo_status check_qkvo(const lococo_config* c, const lococo_qkvo* x, int64_t tokens,
+                         bool need_q_o) {
+  if (!x) return fail(LOCOCO_EINVAL, "qkvo is NULL");
+  lococo_status st;
+  if (need_q_o) {
+    if ((st = check_tensor(c, x->q, "q", tokens))) return st;
+    if ((st = check_tensor(c, x->o, "o", tokens))) return st;
+    if (x->o.p == x->q.p || x->o.p == x->k.p || x->o.p == x->v.p)
+      return fail(LOCOCO_EINVAL, "o aliases an input");
+  }
+  if ((st = check_tensor(c, x->k, "k", tokens))) return st;
+  if ((st = check_tensor(c, x->v, "v", tokens))) return st;
+  return LOCOCO_OK;
+}
+
+enum Path { PATH_GENERIC = 0, PATH_MFMA = 1 };
+
+// Which kernels take this shape.  *why is set when MFMA is refused.
+Path choose_path(const lococo_config* c, int32_t B, const char** why) {
+  (void)B;
+  *why = "the MFMA kernels are not built into this library";
+  return PATH_GENERIC;
+}
+
+lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
+  const char* why = "";
+  Path p = c->impl == LOCOCO_IMPL_GENERIC ? PATH_GENERIC : choose_path(c, B, &why);
+  if (c->impl == LOCOCO_IMPL_MFMA && p != PATH_MFMA)
+    return fail(LOCOCO_EUNSUPPORTED, "impl = MFMA requested but %s", why);
+  *out = p;
+  return LOCOCO_OK;
+}
+
+size_t generic_ws_bytes(const lococo_config* c, int32_t B) {
+  // fp32 logits [chains, M, T], T <= M + B
+  return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
+}
+
+View view_at(const lococo_tensor& t, int64_t tok, size_t es) {
+  return View{(const char*)t.p + (size_t)(tok * t.stride_t) * es, t.stride_b, t.stride_h, t.stride_t};
+}
+
+StepArgs make_args(const lococo_config* c, const lococo_qkvo* x, int64_t tok, int32_t Bn,
+                   const lococo_cache* ca, const void* conv_w, const void* conv_b, bool with_q) {
+  StepArgs a;
+  std::memset(&a, 0, sizeof(a));
+  const size_t es = esize(c->dtype);
+  if (with_q) {
+    a.q = view_at(x->q, tok, es);
+    a.o = view_at(x->o, tok, es);
+  }
+  a.k = view_at(x->k, tok, es);
+  a.v = view_at(x->v, tok, es);
+  a.cache_k = ca->k[ca->cur];
+  a.cache_v = ca->v[ca->cur];
+  a.conv_w = conv_w;
+  a.conv_b = conv_b;
+  a.w_head_stride = c->w_head_stride;
+  a.b_head_stride = c->b_head_stride;
+  a.batch = c->batch;
+  a.Hq = c->n_q_heads;
+  a.Hkv = c->n_kv_heads;
+  a.group = c->n_q_heads / c->n_kv_heads;
+  a.d = c->head_dim;
+  a.M = c->M;
+  a.m = ca->len;
+  a.Bn = Bn;
+  a.k_width = c->conv_width;
+  a.conv_in = c->conv_in;
+  a.norm = c->norm;
+  a.scale = c->attn_scale > 0.f ? c->attn_scale : 1.0f / std::sqrt((float)c->head_dim);
+  a.eps = c->norm_eps > 0.f ? c->norm_eps : 1e-6f;
+  return a;
+}
+
+lococo_status check_step_shape(const lococo_config* c, int32_t B, int32_t len) {
+  if (B <= 0) return fail(LOCOCO_EINVAL, "block length B must be positive");
+  if (B > 65535) return fail(LOCOCO_EUNSUPPORTED, "block length above 65535");
+  if ((int64_t)len + B > generic_attn_max_T())
+    return fail(LOCOCO_EUNSUPPORTED, "cache.len + B = %lld exceeds the supported %d",
+                (long long)len + B, generic_attn_max_T());
+  return LOCOCO_OK;
+}
+
+// Enqueue the attention of one block (generic path).
+lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, hipStream_t s) {
+  (void)path;
+  KTimer t(K_ATTN_GENERIC, s);
+  HIP_TRY(launch_attn_generic(c->dtype, a, s), "attention launch");
+  return LOCOCO_OK;
+}
+
+// Enqueue fill or compress of one block and update the host-side state.
+lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, lococo_cache* ca,
+                             void* ws, hipStream_t s) {
+  (void)path;
+  if (a.m + a.Bn <= a.M) {
+    a.new_k = ca->k[ca->cur];
+    a.new_v = ca->v[ca->cur];
+    KTimer t(K_FILL, s);
+    HIP_TRY(launch_fill_generic(c->dtype, a, s), "fill launch");
+    ca->len = a.m + a.Bn;
+    return LOCOCO_OK;
+  }
+  a.new_k = ca->k[ca->cur ^ 1];
+  a.new_v = ca->v[ca->cur ^ 1];
+  float* logits = (float*)ws;
+  {
+    KTimer t(K_CONV_GENERIC, s);
+    HIP_TRY(launch_conv_logits_generic(c->dtype, a, logits, s), "conv launch");
+  }
+  {
+    KTimer t(K_NORM_GENERIC, s);
+    HIP_TRY(launch_normalise_generic(a, logits, s), "normalise launch");
+  }
+  {
+    KTimer t(K_MIX_GENERIC, s);
+    HIP_TRY(launch_mix_generic(c->dtype, a, logits, 0, s), "mix launch");
+  }
+  ca->cur ^= 1;
+  ca->len = a.M;
+  return LOCOCO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lococo_last_error(void) { return g_err; }
+const char* lococo_version(void) { return "0.1.0"; }
+
+lococo_status lococo_timing_begin(void) {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  for (auto& t : g_timed) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  g_timed.clear();
+  g_timing_on = true;
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_timing_end(lococo_kernel_time* out, int32_t* n_inout) {
+  if (!n_inout) return fail(LOCOCO_EINVAL, "n_inout is NULL");
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_timing_on = false;
+  int64_t launches[K_COUNT] = {0};
+  double ms[K_COUNT] = {0.0};
+  lococo_status st = LOCOCO_OK;
+  for (auto& t : g_timed) {
+    float dt = 0.f;
+    hipError_t e = hipEventSynchronize(t.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&dt, t.start, t.stop);
+    if (e != hipSuccess && st == LOCOCO_OK) st = hip_fail(e, "timing events");
+    launches[t.id] += 1;
+    ms[t.id] += dt;
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  g_timed.clear();
+  const int32_t cap = out ? *n_inout : 0;
+  int32_t n = 0;
+  for (int id = 0; id < K_COUNT; ++id) {
+    if (!launches[id]) continue;
+    if (n < cap) out[n] = lococo_kernel_time{kKernelNames[id], launches[id], ms[id]};
+    ++n;
+  }
+  *n_inout = n;
+  return st;
+}
+
+lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_t cur0,
+                          lococo_seg* out, int64_t* n_inout) {
+  if (!n_inout) return fail(LOCOCO_EINVAL, "n_inout is NULL");
+  if (L < 0 || B <= 0 || M <= 0) return fail(LOCOCO_EINVAL, "need L >= 0, B > 0, M > 0");
+  if (len0 < 0 || len0 > M) return fail(LOCOCO_ESTATE, "len0 %d is outside [0, M=%d]", len0, M);
+  if (cur0 != 0 && cur0 != 1) return fail(LOCOCO_ESTATE, "cur0 must be 0 or 1");
+  const int64_t cap = out ? *n_inout : 0;
+  if (cap < 0) return fail(LOCOCO_EINVAL, "negative capacity");
+  const int64_t n = (L + B - 1) / B;
+  int32_t occ = len0, buf = cur0;
+  for (int64_t i = 0; i < n; ++i) {
+    const int64_t start = i * B;
+    const int32_t len = (int32_t)std::min<int64_t>(B, L - start);
+    const bool fits = (int64_t)occ + len <= M;
+    const int32_t occ_after = fits ? occ + len : M;
+    if (!fits) buf = 1 - buf;
+    if (i < cap) out[i] = lococo_seg{start, len, fits ? 0 : 1, occ, occ_after, buf, 0};
+    occ = occ_after;
+  }
+  *n_inout = n;
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
+                                     int32_t history, size_t* out) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (!out) return fail(LOCOCO_EINVAL, "out is NULL");
+  if (L < 0 || B <= 0) return fail(LOCOCO_EINVAL, "need L >= 0 and B > 0");
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  (void)history;
+  *out = generic_ws_bytes(cfg, B);
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                               const lococo_cache* cache, void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache))) return st;
+  if ((st = check_step_shape(cfg, B, cache->len))) return st;
+  if ((st = check_qkvo(cfg, blk, B, true))) return st;
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, true);
+  return enqueue_attn(cfg, path, a, (hipStream_t)stream);
+}
+
+lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                  const void* conv_w, const void* conv_b, lococo_cache* cache,
+                                  void* workspace, size_t ws_bytes, void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache))) return st;
+  if ((st = check_step_shape(cfg, B, cache->len))) return st;
+  if ((st = check_qkvo(cfg, blk, B, true))) return st;
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  const bool compress = cache->len + B > cfg->M;
+  if (compress) {
+    if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL but this step compresses");
+    const size_t need = generic_ws_bytes(cfg, B);
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)))
+      return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+                  workspace ? ws_bytes : (size_t)0);
+  }
+  StepArgs a = make_args(cfg, blk, 0, B, cache, conv_w, conv_b, true);
+  lococo_cache tmp = *cache;
+  if ((st = enqueue_attn(cfg, path, a, (hipStream_t)stream))) return st;
+  if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
+  *cache = tmp;
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
+                                      int32_t B, const void* conv_w, const void* conv_b,
+                                      lococo_cache* cache, void* workspace, size_t ws_bytes,
+                                      void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache))) return st;
+  if (L < 0) return fail(LOCOCO_EINVAL, "L must be >= 0");
+  if (B <= 0) return fail(LOCOCO_EINVAL, "block length B must be positive");
+  if (L == 0) return LOCOCO_OK;  // nothing to do; tensors may be empty
+  if ((st = check_step_shape(cfg, B, std::min<int64_t>(cfg->M, (int64_t)cache->len + L))))
+    return st;
+  if ((st = check_qkvo(cfg, seq, L, true))) return st;
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  int64_t n = 0;
+  if ((st = lococo_plan(L, B, cfg->M, cache->len, cache->cur, nullptr, &n))) return st;
+  std::vector<lococo_seg> plan((size_t)n);
+  if (n && (st = lococo_plan(L, B, cfg->M, cache->len, cache->cur, plan.data(), &n))) return st;
+  bool any_compress = false;
+  for (const auto& sg : plan) any_compress |= sg.branch == 1;
+  if (any_compress) {
+    if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL but the scan compresses");
+    const size_t need = generic_ws_bytes(cfg, B);
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)))
+      return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+                  workspace ? ws_bytes : (size_t)0);
+  }
+  lococo_cache tmp = *cache;
+  for (const auto& sg : plan) {
+    StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
+    if ((st = enqueue_attn(cfg, path, a, (hipStream_t)stream))) return st;
+    if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
+  }
+  *cache = tmp;
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                     const float* logits, lococo_cache* cache, void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache))) return st;
+  if ((st = check_step_shape(cfg, B, cache->len))) return st;
+  if ((st = check_qkvo(cfg, blk, B, false))) return st;
+  if (!logits) return fail(LOCOCO_EINVAL, "logits is NULL");
+  StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, false);
+  a.new_k = cache->k[cache->cur ^ 1];
+  a.new_v = cache->v[cache->cur ^ 1];
+  HIP_TRY(launch_mix_generic(cfg->dtype, a, logits, 1, (hipStream_t)stream), "mix launch");
+  cache->cur ^= 1;
+  cache->len = cfg->M;
+  return LOCOCO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,270 @@
+// Shape-agnostic kernels for the LoCoCo segment step: any head_dim, cache
+// size, block length and filter width, fp32 or bf16 storage, fp32 arithmetic.
+// They are the fp32 path of the library and the fallback for shapes the MFMA
+// kernels do not take.  One thread (or one workgroup) per output element,
+// straight from the definitions (Eq. 1, Eq. 4a/4b, Eq. 5, Eq. 6).
+#include "lococo_internal.h"
+
+namespace lococo {
+namespace {
+
+struct bf16_t { uint16_t x; };
+
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(bf16_t v) { return __uint_as_float((uint32_t)v.x << 16); }
+
+__device__ __forceinline__ void from_f(float f, float* out) { *out = f; }
+__device__ __forceinline__ void from_f(float f, bf16_t* out) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) { out->x = (uint16_t)((u >> 16) | 0x40); return; }  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);   // round to nearest, ties to even
+  out->x = (uint16_t)(u >> 16);
+}
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// Block-wide reductions over kThreads threads; red is kWaves floats of LDS.
+__device__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r = fmaxf(r, red[w]);
+  return r;
+}
+__device__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r += red[w];
+  return r;
+}
+
+// Row j of [cache ; block] for chain (b, hkv): cache rows first (Eq. 3 order).
+template <typename T>
+__device__ __forceinline__ const T* cat_row(const void* cache, const View& blk, int M, int d,
+                                            int m, int b, int hkv, int Hkv, int j) {
+  if (j < m) return (const T*)cache + ((int64_t)(b * Hkv + hkv) * M + j) * d;
+  return (const T*)blk.p + b * blk.sb + hkv * blk.sh + (int64_t)(j - m) * blk.st;
+}
+
+// Alg. 2 step 3 / Eq. 1: one workgroup per (query row, query head, batch).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attn_generic_k(StepArgs a) {
+  extern __shared__ float sm[];
+  float* qs = sm;                 // d
+  float* sc = sm + a.d;           // m + Bn
+  __shared__ float red[kWaves];
+  const int r = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  const int hkv = hq / a.group;
+  const int n_vis = a.m + r + 1;  // all cache slots + block keys up to the diagonal
+  const T* q = (const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)r * a.q.st;
+  for (int c = threadIdx.x; c < a.d; c += kThreads) qs[c] = to_f(q[c]);
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
+    const T* kr = cat_row<T>(a.cache_k, a.k, a.M, a.d, a.m, b, hkv, a.Hkv, j);
+    float acc = 0.f;
+    for (int c = 0; c < a.d; ++c) acc += qs[c] * to_f(kr[c]);
+    acc *= a.scale;
+    sc[j] = acc;
+    mx = fmaxf(mx, acc);
+  }
+  mx = block_max(mx, red);
+  float z = 0.f;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
+    float e = expf(sc[j] - mx);
+    sc[j] = e;
+    z += e;
+  }
+  z = block_sum(z, red);
+  __syncthreads();
+  T* o = (T*)a.o.p + b * a.o.sb + hq * a.o.sh + (int64_t)r * a.o.st;
+  for (int c = threadIdx.x; c < a.d; c += kThreads) {
+    float acc = 0.f;
+    for (int j = 0; j < n_vis; ++j) {
+      const T* vr = cat_row<T>(a.cache_v, a.v, a.M, a.d, a.m, b, hkv, a.Hkv, j);
+      acc += sc[j] * to_f(vr[c]);
+    }
+    from_f(acc / z, o + c);
+  }
+}
+
+// Alg. 2 IF branch: append the block's K and V at slots [m, m + Bn).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void fill_generic_k(StepArgs a) {
+  const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int n = a.Bn * a.d;
+  for (int e = blockIdx.x * kThreads + threadIdx.x; e < n; e += gridDim.x * kThreads) {
+    int t = e / a.d, c = e % a.d;
+    int64_t dst = ((int64_t)ch * a.M + a.m + t) * a.d + c;
+    ((T*)a.new_k)[dst] = ((const T*)a.k.p)[b * a.k.sb + hkv * a.k.sh + (int64_t)t * a.k.st + c];
+    ((T*)a.new_v)[dst] = ((const T*)a.v.p)[b * a.v.sb + hkv * a.v.sh + (int64_t)t * a.v.st + c];
+  }
+}
+
+// Eq. 5: W[i, j] = bias[i] + sum_c sum_tau Wc[i, c, tau] X[j + tau - (k-1)/2, c],
+// zero outside [0, T).  One thread per (slot i, position j).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void conv_logits_generic_k(StepArgs a, float* logits) {
+  const int Tn = a.m + a.Bn;
+  const int j = blockIdx.x * kThreads + threadIdx.x;
+  const int i = blockIdx.y, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  if (j >= Tn) return;
+  const int C = a.conv_in ? 2 * a.d : a.d;
+  const int pad = (a.k_width - 1) / 2;
+  const T* w = (const T*)a.conv_w + hkv * a.w_head_stride + (int64_t)i * C * a.k_width;
+  float acc = a.conv_b ? to_f(((const T*)a.conv_b)[hkv * a.b_head_stride + i]) : 0.f;
+  for (int t = 0; t < a.k_width; ++t) {
+    const int jj = j + t - pad;
+    if (jj < 0 || jj >= Tn) continue;
+    const T* xk = cat_row<T>(a.cache_k, a.k, a.M, a.d, a.m, b, hkv, a.Hkv, jj);
+    float s = 0.f;
+    for (int c = 0; c < a.d; ++c) s += to_f(w[c * a.k_width + t]) * to_f(xk[c]);
+    if (a.conv_in) {
+      const T* xv = cat_row<T>(a.cache_v, a.v, a.M, a.d, a.m, b, hkv, a.Hkv, jj);
+      for (int c = 0; c < a.d; ++c) s += to_f(w[(a.d + c) * a.k_width + t]) * to_f(xv[c]);
+    }
+    acc += s;
+  }
+  logits[((int64_t)ch * a.M + i) * Tn + j] = acc;
+}
+
+// Eq. 6, in place: one workgroup per (slot, chain) row of T logits.
+__global__ __launch_bounds__(kThreads) void normalise_generic_k(StepArgs a, float* logits) {
+  __shared__ float red[kWaves];
+  const int Tn = a.m + a.Bn;
+  float* row = logits + ((int64_t)blockIdx.y * a.M + blockIdx.x) * Tn;
+  if (a.norm == 0) {
+    float mx = -INFINITY;
+    for (int j = threadIdx.x; j < Tn; j += kThreads) mx = fmaxf(mx, row[j]);
+    mx = block_max(mx, red);
+    float z = 0.f;
+    for (int j = threadIdx.x; j < Tn; j += kThreads) {
+      float e = expf(row[j] - mx);
+      row[j] = e;
+      z += e;
+    }
+    z = block_sum(z, red);
+    for (int j = threadIdx.x; j < Tn; j += kThreads) row[j] /= z;
+  } else {
+    float z = 0.f;
+    for (int j = threadIdx.x; j < Tn; j += kThreads) {
+      float e = fmaxf(row[j], 0.f);
+      row[j] = e;
+      z += e;
+    }
+    z = block_sum(z, red) + a.eps;
+    for (int j = threadIdx.x; j < Tn; j += kThreads) row[j] /= z;
+  }
+}
+
+// Eq. 4a / 4b: new_k[i] = sum_j w[i, j] [Kc ; K_n]_j and the same weights for V.
+// With raw != 0 the rows of w are unnormalised logits and Eq. 6 is applied on
+// the fly (used where the caller supplies the logits and they must stay intact).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void mix_generic_k(StepArgs a, const float* w, int raw) {
+  __shared__ float red[kWaves];
+  const int Tn = a.m + a.Bn;
+  const int i = blockIdx.x, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const float* wr = w + ((int64_t)ch * a.M + i) * Tn;
+  float mx = 0.f, z = 1.f;
+  if (raw) {
+    if (a.norm == 0) {
+      mx = -INFINITY;
+      for (int j = threadIdx.x; j < Tn; j += kThreads) mx = fmaxf(mx, wr[j]);
+      mx = block_max(mx, red);
+      z = 0.f;
+      for (int j = threadIdx.x; j < Tn; j += kThreads) z += expf(wr[j] - mx);
+      z = block_sum(z, red);
+    } else {
+      z = 0.f;
+      for (int j = threadIdx.x; j < Tn; j += kThreads) z += fmaxf(wr[j], 0.f);
+      z = block_sum(z, red) + a.eps;
+    }
+  }
+  for (int e = threadIdx.x; e < 2 * a.d; e += kThreads) {
+    const bool isv = e >= a.d;
+    const int c = isv ? e - a.d : e;
+    float acc = 0.f;
+    for (int j = 0; j < Tn; ++j) {
+      const T* y = cat_row<T>(isv ? a.cache_v : a.cache_k, isv ? a.v : a.k, a.M, a.d, a.m, b, hkv,
+                              a.Hkv, j);
+      float wj = wr[j];
+      if (raw) wj = (a.norm == 0 ? expf(wj - mx) : fmaxf(wj, 0.f)) / z;
+      acc += wj * to_f(y[c]);
+    }
+    T* dst = (T*)(isv ? a.new_v : a.new_k) + ((int64_t)ch * a.M + i) * a.d + c;
+    from_f(acc, dst);
+  }
+}
+
+}  // namespace
+
+// scores (T floats) + query row (d <= 1024 floats) stay within 60 KB of LDS
+int generic_attn_max_T() { return 14336; }
+
+hipError_t launch_attn_generic(int dtype, const StepArgs& a, hipStream_t s) {
+  dim3 grid(a.Bn, a.Hq, a.batch);
+  size_t lds = sizeof(float) * (size_t)(a.d + a.m + a.Bn);
+  if (dtype == LOCOCO_F32)
+    hipLaunchKernelGGL(attn_generic_k<float>, grid, dim3(kThreads), lds, s, a);
+  else
+    hipLaunchKernelGGL(attn_generic_k<bf16_t>, grid, dim3(kThreads), lds, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s) {
+  int n = a.Bn * a.d;
+  dim3 grid((n + kThreads - 1) / kThreads, a.batch * a.Hkv);
+  if (grid.x > 64) grid.x = 64;
+  if (dtype == LOCOCO_F32)
+    hipLaunchKernelGGL(fill_generic_k<float>, grid, dim3(kThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(fill_generic_k<bf16_t>, grid, dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_logits_generic(int dtype, const StepArgs& a, float* logits, hipStream_t s) {
+  const int Tn = a.m + a.Bn;
+  dim3 grid((Tn + kThreads - 1) / kThreads, a.M, a.batch * a.Hkv);
+  if (dtype == LOCOCO_F32)
+    hipLaunchKernelGGL(conv_logits_generic_k<float>, grid, dim3(kThreads), 0, s, a, logits);
+  else
+    hipLaunchKernelGGL(conv_logits_generic_k<bf16_t>, grid, dim3(kThreads), 0, s, a, logits);
+  return hipGetLastError();
+}
+
+hipError_t launch_normalise_generic(const StepArgs& a, float* logits, hipStream_t s) {
+  dim3 grid(a.M, a.batch * a.Hkv);
+  hipLaunchKernelGGL(normalise_generic_k, grid, dim3(kThreads), 0, s, a, logits);
+  return hipGetLastError();
+}
+
+hipError_t launch_mix_generic(int dtype, const StepArgs& a, const float* w, int raw,
+                              hipStream_t s) {
+  dim3 grid(a.M, a.batch * a.Hkv);
+  if (dtype == LOCOCO_F32)
+    hipLaunchKernelGGL(mix_generic_k<float>, grid, dim3(kThreads), 0, s, a, w, raw);
+  else
+    hipLaunchKernelGGL(mix_generic_k<bf16_t>, grid, dim3(kThreads), 0, s, a, w, raw);
+  return hipGetLastError();
+}
+
+}  // namespace lococo

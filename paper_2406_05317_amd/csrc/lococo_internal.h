@@ -1,0 +1,50 @@
+// Internal declarations shared by the host API and the kernel translation
+// units of the library.  Nothing here is part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lococo.h"
+
+namespace lococo {
+
+// View of a [batch, heads, tokens, d] tensor, strides in elements.
+struct View {
+  const void* p;
+  int64_t sb, sh, st;
+};
+
+// Everything a kernel needs to know about one block step.  Pointers of the
+// q/k/v/o views already point at the first token of the block.
+struct StepArgs {
+  View q, k, v;
+  View o;                  // written
+  const void* cache_k;     // live cache  [chains, M, d]
+  const void* cache_v;
+  void* new_k;             // other buffer [chains, M, d] (compress) / live buffer (fill)
+  void* new_v;
+  const void* conv_w;      // [M, C, k] (+ w_head_stride per kv head)
+  const void* conv_b;      // [M] or null
+  int64_t w_head_stride, b_head_stride;
+  int32_t batch, Hq, Hkv, group, d, M;
+  int32_t m;               // live slots before the step
+  int32_t Bn;              // tokens in the block
+  int32_t k_width;         // conv width
+  int32_t conv_in, norm;
+  float scale, eps;
+};
+
+// ---- shape-agnostic kernels (generic_kernels.hip); dtype: LOCOCO_F32 / LOCOCO_BF16
+hipError_t launch_attn_generic(int dtype, const StepArgs& a, hipStream_t s);
+hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s);
+// logits: fp32 [chains, M, T], T = m + Bn
+hipError_t launch_conv_logits_generic(int dtype, const StepArgs& a, float* logits, hipStream_t s);
+hipError_t launch_normalise_generic(const StepArgs& a, float* logits, hipStream_t s);
+// raw != 0: w holds unnormalised logits, Eq. 6 is applied inside the kernel
+hipError_t launch_mix_generic(int dtype, const StepArgs& a, const float* w, int raw,
+                              hipStream_t s);
+// largest T = m + Bn the generic attention kernel can hold in LDS
+int generic_attn_max_T();
+
+}  // namespace lococo

@@ -1,0 +1,134 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header
+declares, its integer plan equals the oracle's and a brute-force replay of
+Alg. 2's IF, and malformed arguments come back as status codes before any
+GPU work is attempted."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import lococo_oracle as orc
+from paper_2406_05317_amd import binding as lb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lococo.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(lococo_[a-z_]+)\s*\(", hdr))
+    assert declared == set(lb.EXPORTS), declared ^ set(lb.EXPORTS)
+    L = lb.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert re.fullmatch(r"\d+\.\d+\.\d+", lb.lococo_version())
+
+
+def test_struct_layouts_match_the_header():
+    # sizes the C compiler gives for the header's structs (LP64, natural alignment)
+    assert C.sizeof(lb.lococo_config) == 72
+    assert C.sizeof(lb.lococo_cache) == 40
+    assert C.sizeof(lb.lococo_tensor) == 32
+    assert C.sizeof(lb.lococo_qkvo) == 128
+    assert C.sizeof(lb.lococo_seg) == 32
+
+
+def test_plan_is_bit_exact_against_the_oracle_and_a_replay():
+    rng = np.random.default_rng(0)
+    cases = [(256, 16, 16, 0, 0), (3584, 128, 128, 0, 0), (32768, 512, 512, 0, 0),
+             (8192, 64, 128, 0, 0), (16384, 256, 256, 0, 1), (0, 4, 4, 0, 0), (5, 16, 4, 0, 0),
+             (3482, 128, 128, 0, 0)]
+    for _ in range(300):
+        M = int(rng.integers(1, 50))
+        cases.append((int(rng.integers(0, 400)), int(rng.integers(1, 60)), M,
+                      int(rng.integers(0, M + 1)), int(rng.integers(0, 2))))
+    for L, B, M, len0, cur0 in cases:
+        got = np.array(lb.lococo_plan(L, B, M, len0, cur0), dtype=np.int64).reshape(-1, 6)
+        want = orc.plan(L, B, M, len0, cur0)
+        assert np.array_equal(got, want), (L, B, M, len0, cur0)
+        # replay of the IF, token counts only
+        m, cur = len0, cur0
+        for (start, ln, branch, before, after, buf) in got:
+            assert before == m and ln == min(B, L - start)
+            if m + ln <= M:
+                assert branch == 0 and after == m + ln and buf == cur
+            else:
+                cur ^= 1
+                assert branch == 1 and after == M and buf == cur
+            m = after
+        assert got[:, 1].sum() == L
+
+
+def _cfg(**kw):
+    import torch
+    base = dict(dtype=torch.float32, batch=1, n_q_heads=2, n_kv_heads=1, head_dim=8, M=4,
+                conv_width=3)
+    base.update(kw)
+    return lb.make_config(**base)
+
+
+def test_plan_and_config_errors_are_status_codes():
+    n = C.c_int64(0)
+    L = lb.lib()
+    assert L.lococo_plan(10, 0, 4, 0, 0, None, C.byref(n)) == lb.LOCOCO_EINVAL
+    assert L.lococo_plan(10, 2, 4, 5, 0, None, C.byref(n)) == lb.LOCOCO_ESTATE
+    assert L.lococo_plan(10, 2, 4, 0, 2, None, C.byref(n)) == lb.LOCOCO_ESTATE
+    assert L.lococo_plan(10, 2, 4, 0, 0, None, None) == lb.LOCOCO_EINVAL
+    assert b"n_inout" in L.lococo_last_error()
+    out = C.c_size_t(0)
+    for kw, status in [(dict(conv_width=4), lb.LOCOCO_EUNSUPPORTED),
+                       (dict(conv_width=0), lb.LOCOCO_EINVAL),
+                       (dict(n_q_heads=3, n_kv_heads=2), lb.LOCOCO_EINVAL),
+                       (dict(M=0), lb.LOCOCO_EINVAL), (dict(norm=2), lb.LOCOCO_EINVAL),
+                       (dict(conv_in=3), lb.LOCOCO_EINVAL), (dict(impl=7), lb.LOCOCO_EINVAL),
+                       (dict(head_dim=4096), lb.LOCOCO_EUNSUPPORTED)]:
+        cfg = _cfg(**kw)
+        assert L.lococo_workspace_bytes(C.byref(cfg), 16, 4, 0, C.byref(out)) == status, kw
+        assert len(L.lococo_last_error()) > 0
+    bad = _cfg()
+    bad.struct_size = 12
+    assert L.lococo_workspace_bytes(C.byref(bad), 16, 4, 0, C.byref(out)) == lb.LOCOCO_EINVAL
+    assert L.lococo_workspace_bytes(None, 16, 4, 0, C.byref(out)) == lb.LOCOCO_EINVAL
+    with pytest.raises(lb.LococoError):
+        lb.lococo_workspace_bytes(_cfg(conv_width=2), 16, 4)
+
+
+def test_call_argument_errors_enqueue_nothing():
+    """Null / aliased / misaligned arguments are refused on the host."""
+    L = lb.lib()
+    cfg = _cfg()
+    x = lb.lococo_qkvo()
+    cache = lb.lococo_cache()
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, None, None) == lb.LOCOCO_EINVAL
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    fake = [0x10000, 0x20000, 0x30000, 0x40000]        # never dereferenced: validation fails first
+    cache = lb.lococo_cache((C.c_void_p * 2)(fake[0], fake[0]), (C.c_void_p * 2)(fake[2], fake[3]), 0, 0)
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    assert b"alias" in L.lococo_last_error()
+    cache = lb.lococo_cache((C.c_void_p * 2)(fake[0], fake[1]), (C.c_void_p * 2)(fake[2], fake[3]), 0, 9)
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_ESTATE
+    cache.len = 0
+    cache.cur = 3
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_ESTATE
+    cache.cur = 0
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 0, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    assert b"q pointer" in L.lococo_last_error()
+    t = lb.lococo_tensor(0x50000, 64, 32, 4)           # stride_t below head_dim
+    x = lb.lococo_qkvo(t, t, t, lb.lococo_tensor(0x60000, 64, 32, 8))
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    t = lb.lococo_tensor(0x50000, 64, 32, 8)
+    x = lb.lococo_qkvo(t, t, t, t)                     # o aliases q
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    x = lb.lococo_qkvo(t, t, t, lb.lococo_tensor(0x60000, 64, 32, 8))
+    # a compressing step without filters / without workspace
+    cache.len = 4
+    assert L.lococo_segment_step(C.byref(cfg), C.byref(x), 4, None, None, C.byref(cache), None, 0,
+                                 None) == lb.LOCOCO_EINVAL
+    assert L.lococo_segment_step(C.byref(cfg), C.byref(x), 4, 0x70000, None, C.byref(cache), None, 0,
+                                 None) == lb.LOCOCO_EWORKSPACE
+    assert cache.len == 4 and cache.cur == 0           # state untouched on failure
+    assert L.lococo_mix_from_logits(C.byref(cfg), C.byref(x), 4, None, C.byref(cache),
+                                    None) == lb.LOCOCO_EINVAL
