@@ -36,9 +36,11 @@ lococo_status hip_fail(hipError_t e, const char* what) {
   } while (0)
 
 // ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
-enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC, K_COUNT };
+enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC,
+                K_REPACK, K_COMPRESS_MFMA, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
-                                           "normalise_generic", "mix_generic"};
+                                           "normalise_generic", "mix_generic", "repack_filters",
+                                           "compress_mfma"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
@@ -154,8 +156,23 @@ enum Path { PATH_GENERIC = 0, PATH_MFMA = 1 };
 // Which kernels take this shape.  *why is set when MFMA is refused.
 Path choose_path(const lococo_config* c, int32_t B, const char** why) {
   (void)B;
-  *why = "the MFMA kernels are not built into this library";
-  return PATH_GENERIC;
+  if (!compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why))
+    return PATH_GENERIC;
+  return PATH_MFMA;
+}
+
+int filter_banks(const lococo_config* c) { return c->w_head_stride ? c->n_kv_heads : 1; }
+
+int cu_count() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n = prop.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
 }
 
 lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
@@ -167,8 +184,11 @@ lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
   return LOCOCO_OK;
 }
 
-size_t generic_ws_bytes(const lococo_config* c, int32_t B) {
-  // fp32 logits [chains, M, T], T <= M + B
+// Workspace of one step.  Generic: fp32 logits [chains, M, T], T <= M + B.
+// MFMA: the repacked filter bank.
+size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
+  if (path == PATH_MFMA)
+    return align_up(compress_mfma_filter_bytes(c->M, c->conv_width, filter_banks(c)), 256);
   return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
 }
 
@@ -226,10 +246,16 @@ lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a,
   return LOCOCO_OK;
 }
 
+// Repack the filter bank into the workspace (MFMA path; once per call).
+lococo_status enqueue_repack(const lococo_config* c, const StepArgs& a, void* ws, hipStream_t s) {
+  KTimer t(K_REPACK, s);
+  HIP_TRY(launch_repack_filters(a, ws, filter_banks(c), s), "filter repack launch");
+  return LOCOCO_OK;
+}
+
 // Enqueue fill or compress of one block and update the host-side state.
 lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, lococo_cache* ca,
                              void* ws, hipStream_t s) {
-  (void)path;
   if (a.m + a.Bn <= a.M) {
     a.new_k = ca->k[ca->cur];
     a.new_v = ca->v[ca->cur];
@@ -240,6 +266,13 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
   }
   a.new_k = ca->k[ca->cur ^ 1];
   a.new_v = ca->v[ca->cur ^ 1];
+  if (path == PATH_MFMA) {
+    KTimer t(K_COMPRESS_MFMA, s);
+    HIP_TRY(launch_compress_mfma(a, ws, filter_banks(c), cu_count(), s), "compress launch");
+    ca->cur ^= 1;
+    ca->len = a.M;
+    return LOCOCO_OK;
+  }
   float* logits = (float*)ws;
   {
     KTimer t(K_CONV_GENERIC, s);
@@ -337,7 +370,7 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
   (void)history;
-  *out = generic_ws_bytes(cfg, B);
+  *out = step_ws_bytes(cfg, path, B);
   return LOCOCO_OK;
 }
 
@@ -367,13 +400,16 @@ lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* b
   const bool compress = cache->len + B > cfg->M;
   if (compress) {
     if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL but this step compresses");
-    const size_t need = generic_ws_bytes(cfg, B);
+    const size_t need = step_ws_bytes(cfg, path, B);
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)))
       return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
                   workspace ? ws_bytes : (size_t)0);
   }
   StepArgs a = make_args(cfg, blk, 0, B, cache, conv_w, conv_b, true);
   lococo_cache tmp = *cache;
+  if (compress && path == PATH_MFMA &&
+      (st = enqueue_repack(cfg, a, workspace, (hipStream_t)stream)))
+    return st;
   if ((st = enqueue_attn(cfg, path, a, (hipStream_t)stream))) return st;
   if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
   *cache = tmp;
@@ -403,12 +439,16 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   for (const auto& sg : plan) any_compress |= sg.branch == 1;
   if (any_compress) {
     if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL but the scan compresses");
-    const size_t need = generic_ws_bytes(cfg, B);
+    const size_t need = step_ws_bytes(cfg, path, B);
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)))
       return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
                   workspace ? ws_bytes : (size_t)0);
   }
   lococo_cache tmp = *cache;
+  if (any_compress && path == PATH_MFMA) {
+    StepArgs a0 = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
+    if ((st = enqueue_repack(cfg, a0, workspace, (hipStream_t)stream))) return st;
+  }
   for (const auto& sg : plan) {
     StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
     if ((st = enqueue_attn(cfg, path, a, (hipStream_t)stream))) return st;

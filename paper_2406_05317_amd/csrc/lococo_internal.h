@@ -47,4 +47,17 @@ hipError_t launch_mix_generic(int dtype, const StepArgs& a, const float* w, int 
 // largest T = m + Bn the generic attention kernel can hold in LDS
 int generic_attn_max_T();
 
+
+// ---- fused compression on MFMA (compress_mfma.hip)
+// true if the kernel takes this configuration; otherwise *why names the limit
+bool compress_mfma_supports(int dtype, int d, int M, int conv_width, int conv_in, int norm,
+                            const char** why);
+// bytes of the repacked filter bank ([bank][M][k][C] bf16) the kernel reads
+size_t compress_mfma_filter_bytes(int M, int conv_width, int banks);
+// conv_w [M][C][k] (+ w_head_stride per bank) -> wp [bank][M][k][C]
+hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s);
+// Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
+hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
+                                hipStream_t s);
+
 }  // namespace lococo

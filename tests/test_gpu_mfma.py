@@ -1,0 +1,92 @@
+"""GPU parity of the MFMA kernels (bf16, head_dim 128) against the CPU oracle:
+shapes that span several tiles, ragged tails, partly filled caches, both
+row-tile sizes of the fused compression kernel, and peaked softmaxes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lococo_oracle as orc
+from paper_2406_05317_amd import inputs
+from parity_util import compare_scan, gpu_forward, oracle_forward
+
+pytestmark = pytest.mark.gpu
+MFMA = 2
+
+
+def _w(**kw):
+    base = dict(name="mfma", dtype="bf16", batch=1, n_q_heads=4, n_kv_heads=4, head_dim=128, L=512,
+                B=128, M=128, conv_width=15, seed=7)
+    base.update(kw)
+    return inputs.Workload(**base)
+
+
+def _run(w, **kw):
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    got = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, **kw)
+    errs = compare_scan(w, got, want, what=w.name)
+    plan = orc.plan(w.L, w.B, w.M)
+    assert got[3] == plan[-1, 4] and got[4] == plan[-1, 5]
+    return errs
+
+
+@pytest.mark.parametrize("case", [
+    dict(),                                               # cfg2-shaped, cut to 4 heads / 4 blocks
+    dict(L=500),                                          # ragged last block (116 tokens)
+    dict(M=64, B=64, L=320),                              # 32-row tiles, two row tiles per chain
+    dict(M=96, B=80, L=400),                              # M % 64 != 0, T = 176 not a tile multiple
+    dict(M=128, B=96, L=480),                             # partly filled cache at the first compress (m = 96)
+    dict(M=128, B=160, L=480),                            # block larger than the cache
+    dict(M=128, B=64, L=448, batch=2, n_q_heads=6, n_kv_heads=3),   # cfg4-shaped, two fills
+    dict(M=256, B=256, L=1024, n_q_heads=8, n_kv_heads=2),          # cfg5-shaped GQA
+    dict(M=512, B=512, L=2048, n_q_heads=2, n_kv_heads=2),          # cfg3-shaped chain
+    dict(per_head_filters=True, bias_sigma=0.5),
+    dict(tok_lognormal_sigma=0.5, seed=11),
+])
+def test_mfma_scan_matches_oracle(case):
+    errs = _run(_w(**case))
+    print(case, {k: (f"{e[0]:.2e}", f"{e[1]:.2e}") for k, e in errs.items()})
+
+
+def test_mfma_64_row_tiles():
+    """Enough (chain, row tile) pairs to fill the chip, so the 64-row variant runs."""
+    _run(_w(batch=2, n_q_heads=32, n_kv_heads=32, M=256, B=128, L=512))
+
+
+@pytest.mark.parametrize("gains", [(6.0, 3.0), (10.0, 8.0)])
+def test_mfma_sharpened(gains):
+    """Peaked attention and mixing rows: wrong taps, seams or masks would show."""
+    qk, cg = gains
+    w = _w(qk_gain=qk, conv_gain=cg, L=640)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    got = gpu_forward(w, q, k, v, cw, cb, impl=MFMA)
+    compare_scan(w, got, want, what="sharp")
+    lg = orc.conv_logits(k[0, 0, :256].double().numpy(), cw.double().numpy())
+    assert orc.normalise(lg).max() > 0.05                 # far from the uniform 1/256
+
+
+def test_mfma_step_by_step_equals_sequence_call():
+    w = _w(L=640)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA)
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, step_by_step=True)
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x, y)
+    assert a[3:] == b[3:]
+
+
+def test_mfma_is_refused_for_shapes_it_does_not_take():
+    from paper_2406_05317_amd import binding as lb
+    for kw in (dict(head_dim=64), dict(conv_width=7), dict(conv_in=1), dict(norm=1), dict(M=100),
+               dict(dtype="f32")):
+        w = _w(**kw)
+        cfg = lb.config_for(w, impl=MFMA)
+        with pytest.raises(lb.LococoError) as e:
+            lb.lococo_workspace_bytes(cfg, w.L, w.B)
+        assert e.value.status == lb.LOCOCO_EUNSUPPORTED
+        # AUTO falls back to the shape-agnostic kernels
+        assert lb.lococo_workspace_bytes(lb.config_for(w, impl=0), w.L, w.B) > 0
