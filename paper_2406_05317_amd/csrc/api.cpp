@@ -37,10 +37,10 @@ lococo_status hip_fail(hipError_t e, const char* what) {
 
 // ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
 enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC,
-                K_REPACK, K_COMPRESS_MFMA, K_COUNT };
+                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
                                            "normalise_generic", "mix_generic", "repack_filters",
-                                           "compress_mfma"};
+                                           "compress_mfma", "attn_mfma"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
@@ -158,6 +158,7 @@ Path choose_path(const lococo_config* c, int32_t B, const char** why) {
   (void)B;
   if (!compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why))
     return PATH_GENERIC;
+  if (!attn_mfma_supports(c->dtype, c->head_dim, why)) return PATH_GENERIC;
   return PATH_MFMA;
 }
 
@@ -190,6 +191,17 @@ size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
   if (path == PATH_MFMA)
     return align_up(compress_mfma_filter_bytes(c->M, c->conv_width, filter_banks(c)), 256);
   return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
+}
+
+// Bytes of one history slot pair member: one cache state [chains, M, d].
+size_t state_bytes(const lococo_config* c) {
+  return (size_t)c->batch * c->n_kv_heads * c->M * c->head_dim * esize(c->dtype);
+}
+
+// Workspace of the batched-attention schedule: the step workspace followed by
+// K and V history slots for n_compress cache states.
+size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_compress) {
+  return step_ws_bytes(c, path, B) + 2 * (size_t)n_compress * align_up(state_bytes(c), 256);
 }
 
 View view_at(const lococo_tensor& t, int64_t tok, size_t es) {
@@ -238,9 +250,31 @@ lococo_status check_step_shape(const lococo_config* c, int32_t B, int32_t len) {
   return LOCOCO_OK;
 }
 
-// Enqueue the attention of one block (generic path).
+AttnArgs attn_args_one_block(const StepArgs& a) {
+  AttnArgs t;
+  std::memset(&t, 0, sizeof(t));
+  t.q = a.q; t.k = a.k; t.v = a.v; t.o = a.o;
+  t.cache_k = a.cache_k;
+  t.cache_v = a.cache_v;
+  t.L = a.Bn;
+  t.B = a.Bn;
+  t.M = a.M;
+  t.len0 = a.m;
+  t.n_fill = 0;            // block 0 sees the base cache with len0 slots
+  t.seg_first = 0;
+  t.n_seg = 1;
+  t.batch = a.batch; t.Hq = a.Hq; t.Hkv = a.Hkv; t.group = a.group;
+  t.scale = a.scale;
+  return t;
+}
+
+// Enqueue the attention of one block.
 lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, hipStream_t s) {
-  (void)path;
+  if (path == PATH_MFMA) {
+    KTimer t(K_ATTN_MFMA, s);
+    HIP_TRY(launch_attn_mfma(attn_args_one_block(a), s), "attention launch");
+    return LOCOCO_OK;
+  }
   KTimer t(K_ATTN_GENERIC, s);
   HIP_TRY(launch_attn_generic(c->dtype, a, s), "attention launch");
   return LOCOCO_OK;
@@ -369,8 +403,10 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
   if (L < 0 || B <= 0) return fail(LOCOCO_EINVAL, "need L >= 0 and B > 0");
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
-  (void)history;
-  *out = step_ws_bytes(cfg, path, B);
+  if (history && path == PATH_MFMA)
+    *out = history_ws_bytes(cfg, path, B, (L + B - 1) / B);   // every block may compress
+  else
+    *out = step_ws_bytes(cfg, path, B);
   return LOCOCO_OK;
 }
 
@@ -448,6 +484,65 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   if (any_compress && path == PATH_MFMA) {
     StepArgs a0 = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
     if ((st = enqueue_repack(cfg, a0, workspace, (hipStream_t)stream))) return st;
+  }
+  int64_t n_compress = 0, n_fill = 0;
+  for (const auto& sg : plan) n_compress += sg.branch;
+  while (n_fill < n && plan[(size_t)n_fill].branch == 0) ++n_fill;
+  if (path == PATH_MFMA && any_compress && workspace &&
+      ws_bytes >= history_ws_bytes(cfg, path, B, n_compress)) {
+    // Batched-attention schedule: run the fill / compress recurrence first, keeping every
+    // cache state, then one attention launch over all blocks, then publish the last state.
+    hipStream_t s = (hipStream_t)stream;
+    const size_t slot = align_up(state_bytes(cfg), 256);
+    char* hist_k = (char*)workspace + step_ws_bytes(cfg, path, B);
+    char* hist_v = hist_k + (size_t)n_compress * slot;
+    const void* src_k = tmp.k[tmp.cur];
+    const void* src_v = tmp.v[tmp.cur];
+    int64_t step = 0;
+    for (const auto& sg : plan) {
+      StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
+      a.m = sg.len_before;
+      if (sg.branch == 0) {
+        a.new_k = tmp.k[tmp.cur];
+        a.new_v = tmp.v[tmp.cur];
+        KTimer t(K_FILL, s);
+        HIP_TRY(launch_fill_generic(cfg->dtype, a, s), "fill launch");
+      } else {
+        a.cache_k = src_k;
+        a.cache_v = src_v;
+        a.new_k = hist_k + (size_t)step * slot;
+        a.new_v = hist_v + (size_t)step * slot;
+        KTimer t(K_COMPRESS_MFMA, s);
+        HIP_TRY(launch_compress_mfma(a, workspace, filter_banks(cfg), cu_count(), s),
+                "compress launch");
+        src_k = a.new_k;
+        src_v = a.new_v;
+        ++step;
+      }
+    }
+    {
+      StepArgs a0 = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
+      AttnArgs t = attn_args_one_block(a0);
+      t.hist_k = hist_k;
+      t.hist_v = hist_v;
+      t.hist_stride = (int64_t)(slot / esize(cfg->dtype));
+      t.L = L;
+      t.B = B;
+      t.len0 = cache->len;
+      t.n_fill = (int32_t)n_fill;
+      t.n_seg = (int32_t)n;
+      KTimer kt(K_ATTN_MFMA, s);
+      HIP_TRY(launch_attn_mfma(t, s), "attention launch");
+    }
+    const lococo_seg& last = plan.back();
+    HIP_TRY(hipMemcpyAsync(tmp.k[last.buf_after], src_k, state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+            "publishing the final cache");
+    HIP_TRY(hipMemcpyAsync(tmp.v[last.buf_after], src_v, state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+            "publishing the final cache");
+    tmp.cur = last.buf_after;
+    tmp.len = last.len_after;
+    *cache = tmp;
+    return LOCOCO_OK;
   }
   for (const auto& sg : plan) {
     StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);

@@ -35,6 +35,26 @@ struct StepArgs {
   float scale, eps;
 };
 
+// Arguments of the MFMA attention kernel: one block, or every block of a scan
+// whose intermediate caches were kept.  Block n = seg_first + (launch index)
+// covers tokens [n*B, min((n+1)*B, L)) of the q/k/v/o views.  Blocks n <= n_fill
+// see the base cache with len0 + n*B live slots (the fill phase appends in
+// place); block n > n_fill sees history slot n - n_fill - 1 with M live slots.
+struct AttnArgs {
+  View q, k, v;
+  View o;
+  const void* cache_k;     // base cache [chains, M, d]
+  const void* cache_v;
+  const void* hist_k;      // history slots, hist_stride elements apart (may be null if unused)
+  const void* hist_v;
+  int64_t hist_stride;
+  int64_t L;
+  int32_t B, M, len0, n_fill, seg_first, n_seg;
+  int32_t batch, Hq, Hkv, group;
+  int32_t qtiles;          // filled in by the launcher
+  float scale;
+};
+
 // ---- shape-agnostic kernels (generic_kernels.hip); dtype: LOCOCO_F32 / LOCOCO_BF16
 hipError_t launch_attn_generic(int dtype, const StepArgs& a, hipStream_t s);
 hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s);
@@ -59,5 +79,10 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
 // Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
                                 hipStream_t s);
+
+
+// ---- attention on MFMA (attn_mfma.hip)
+bool attn_mfma_supports(int dtype, int d, const char** why);
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 
 }  // namespace lococo

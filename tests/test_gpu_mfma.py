@@ -49,6 +49,44 @@ def test_mfma_scan_matches_oracle(case):
     print(case, {k: (f"{e[0]:.2e}", f"{e[1]:.2e}") for k, e in errs.items()})
 
 
+@pytest.mark.parametrize("case", [
+    dict(L=640),
+    dict(L=500),                                          # ragged last block
+    dict(M=128, B=96, L=480),                             # partly filled cache at the first compress
+    dict(M=128, B=64, L=448, batch=2, n_q_heads=6, n_kv_heads=3),   # two fills, GQA
+    dict(M=256, B=256, L=1024, n_q_heads=8, n_kv_heads=2),
+    dict(M=128, B=128, L=100),                            # nothing to compress: plain causal attention
+])
+def test_mfma_batched_attention_schedule(case):
+    """Keeping every intermediate cache and running all blocks' attention as one
+    launch gives the oracle's result, bit-identical to the step-by-step schedule."""
+    w = _w(**case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    compare_scan(w, a, want, what="history")
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=False)
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x[..., :a[3], :] if x.shape[2] == w.M else x,
+                           y[..., :a[3], :] if y.shape[2] == w.M else y)
+    assert a[3:] == b[3:]
+
+
+def test_mfma_resume_with_history_from_a_full_cache():
+    """A scan continued from a full cache (no fill phase) under the batched schedule."""
+    w = _w(L=768)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    full = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    L1 = 384
+    first = gpu_forward(w, q[:, :, :L1], k[:, :, :L1], v[:, :, :L1], cw, cb, impl=MFMA, history=True)
+    rest = gpu_forward(w, q[:, :, L1:], k[:, :, L1:], v[:, :, L1:], cw, cb, impl=MFMA, history=True,
+                       cache_init=(first[1], first[2], first[3]))
+    assert torch.equal(torch.cat([first[0], rest[0]], 2), full[0])
+    assert torch.equal(rest[1], full[1]) and torch.equal(rest[2], full[2]) and rest[3] == full[3]
+
+
 def test_mfma_64_row_tiles():
     """Enough (chain, row tile) pairs to fill the chip, so the 64-row variant runs."""
     _run(_w(batch=2, n_q_heads=32, n_kv_heads=32, M=256, B=128, L=512))
