@@ -21,6 +21,8 @@
 //
 // Shapes taken: head_dim = C = 128, bf16, conv_in = 0, norm = 0 (softmax),
 // M a multiple of BM; any T (tail positions are masked), any m.
+#include <cstdlib>
+
 #include "lococo_internal.h"
 
 namespace lococo {
@@ -29,9 +31,12 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kD = 128;            // head_dim = conv channels
 constexpr int kThreads = 256;
+constexpr float kLazy = 8.0f;      // softmax reference lags the row maximum by at most this much
 
 template <int BM, int BN, int KW>
 struct Geo {
@@ -40,23 +45,23 @@ struct Geo {
   static constexpr int PAD = (KW - 1) / 2;
   static constexpr int XROWS = BN + KW - 1;          // key tile rows incl. halo
   static constexpr int XSTRIDE = kD * 2 + 16;        // bytes per key-tile row (padded: conflict-free b128 reads)
-  static constexpr int YSTRIDE = BN * 2 + 16;        // bytes per column of the transposed [K|V] tile
+  static constexpr int VSTRIDE = kD * 2 + 64;        // bytes per value-tile row (conflict-free transposing reads)
   static constexpr int SSTRIDE = BN + 8;             // floats per row of a partial-logit buffer
   static constexpr int PSTRIDE = BN * 2 + 16;        // bytes per row of the bf16 probability tile
   static constexpr int XBYTES = XROWS * XSTRIDE;
-  static constexpr int YBYTES = 2 * kD * YSTRIDE;
+  static constexpr int VBYTES = BN * VSTRIDE;
   static constexpr int SBYTES = 4 * BM * SSTRIDE * 4;
   static constexpr int PBYTES = BM * PSTRIDE;
-  static constexpr int LDS = 2 * (XBYTES + YBYTES) + SBYTES + PBYTES + 2 * BM * 4;
+  static constexpr int LDS = 2 * (XBYTES + VBYTES) + SBYTES + PBYTES + 2 * BM * 4 + 16;
   static constexpr int RPW = BM / 4;                 // rows a wave owns in the softmax phase
   static constexpr int LPR = 64 / RPW;               // lanes per row there
   static constexpr int EPL = BN / LPR;               // positions per lane there
   static constexpr int XITEMS = XROWS * 16;          // 16-byte chunks of the key tile
   static constexpr int XPER = (XITEMS + kThreads - 1) / kThreads;
-  static constexpr int YITEMS = (BN / 2) * 32;       // (position pair, 16-byte chunk of K|V row)
-  static constexpr int YPER = YITEMS / kThreads;
+  static constexpr int VITEMS = BN * 16;             // 16-byte chunks of the value tile
+  static constexpr int VPER = VITEMS / kThreads;
   static_assert(BM == 32 || BM == 64, "BM");
-  static_assert(BN % 32 == 0 && YITEMS % kThreads == 0, "BN");
+  static_assert(BN % 32 == 0 && VITEMS % kThreads == 0, "BN");
   static_assert(EPL % 4 == 0, "softmax lanes read whole float4s");
 };
 
@@ -64,6 +69,15 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7fffu + ((u >> 16) & 1u);   // RNE; inputs here are finite
   return (uint16_t)(u >> 16);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s supplies the
+// address of 4 consecutive 16-bit elements; lane i of the group receives element (i % 4) of the
+// chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane s pointing at
+// (row r0 + s/4, column c0 + 4*(s%4)) of a row-major tile, lane i ends up with column c0 + i of
+// rows r0 .. r0+3: a K x N operand fragment read straight from a row-major tile.
+__device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
 // 16 bytes of row p of [cache ; block] (keys or values), zeros outside [0, T).
@@ -84,11 +98,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   using G = Geo<BM, BN, KW>;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Xs0 = smem;
-  unsigned char* Ys0 = smem + 2 * G::XBYTES;
-  float* Sred = (float*)(smem + 2 * (G::XBYTES + G::YBYTES));
+  unsigned char* Vs0 = smem + 2 * G::XBYTES;
+  float* Sred = (float*)(smem + 2 * (G::XBYTES + G::VBYTES));
   unsigned char* Ps = (unsigned char*)Sred + G::SBYTES;
   float* alphas = (float*)(Ps + G::PBYTES);
   float* lsum = alphas + BM;
+  int* rescale_flag = (int*)(lsum + BM);             // one word per wave
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
   const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
@@ -129,7 +144,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 
   // ---- staging: global -> registers -> LDS (key tile row-major with halo; [K|V] tile transposed)
   u32x4 xreg[G::XPER];
-  u32x4 yreg[G::YPER][2];
+  u32x4 vreg[G::VPER];
   auto stage_load = [&](int j0) {
 #pragma unroll
     for (int it = 0; it < G::XPER; ++it) {
@@ -139,20 +154,14 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
         xreg[it] = load_cat16(a.cache_k, a.k, a.M, a.m, T, b, hkv, a.Hkv, j0 - G::PAD + r, chunk);
     }
 #pragma unroll
-    for (int it = 0; it < G::YPER; ++it) {
+    for (int it = 0; it < G::VPER; ++it) {
       const int item = tid + it * kThreads;
-      const int pair = item % (BN / 2), chunk = item / (BN / 2);   // chunk 0..15: K, 16..31: V
-      const int p = j0 + 2 * pair;
-      const bool isv = chunk >= 16;
-      yreg[it][0] = load_cat16(isv ? a.cache_v : a.cache_k, isv ? a.v : a.k, a.M, a.m, T, b, hkv,
-                               a.Hkv, p, chunk & 15);
-      yreg[it][1] = load_cat16(isv ? a.cache_v : a.cache_k, isv ? a.v : a.k, a.M, a.m, T, b, hkv,
-                               a.Hkv, p + 1, chunk & 15);
+      vreg[it] = load_cat16(a.cache_v, a.v, a.M, a.m, T, b, hkv, a.Hkv, j0 + (item >> 4), item & 15);
     }
   };
   auto stage_store = [&](int buf) {
     unsigned char* Xs = Xs0 + buf * G::XBYTES;
-    unsigned char* Ys = Ys0 + buf * G::YBYTES;
+    unsigned char* Vs = Vs0 + buf * G::VBYTES;
 #pragma unroll
     for (int it = 0; it < G::XPER; ++it) {
       const int item = tid + it * kThreads;
@@ -160,15 +169,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       if (item < G::XITEMS) *(u32x4*)(Xs + r * G::XSTRIDE + chunk * 16) = xreg[it];
     }
 #pragma unroll
-    for (int it = 0; it < G::YPER; ++it) {
+    for (int it = 0; it < G::VPER; ++it) {
       const int item = tid + it * kThreads;
-      const int pair = item % (BN / 2), chunk = item / (BN / 2);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t lo = (yreg[it][0][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        const uint32_t hi = (yreg[it][1][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        *(uint32_t*)(Ys + (chunk * 8 + e) * G::YSTRIDE + pair * 4) = lo | (hi << 16);
-      }
+      *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it];
     }
   };
 
@@ -180,7 +183,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     const int buf = jt & 1;
     const int j0 = jt * BN;
     const unsigned char* Xs = Xs0 + buf * G::XBYTES;
-    const unsigned char* Ys = Ys0 + buf * G::YBYTES;
+    const unsigned char* Vs = Vs0 + buf * G::VBYTES;
     const bool more = jt + 1 < NT;
     if (more) stage_load(j0 + BN);
 
@@ -192,18 +195,33 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       for (int pt = 0; pt < G::PT; ++pt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[rt][pt][i] = 0.f;
+    {
+      // key operands are fetched from LDS kRing contraction steps ahead of their MFMAs
+      constexpr int NS = KW * 2;                 // contraction steps: (tap, channel half)
+      constexpr int kRing = 4;
+      bf16x8 xv[kRing][G::PT];
+      const unsigned char* xbase = Xs + l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
+      auto fetch = [&](int st) {
+        const int t = st >> 1, h = st & 1;
 #pragma unroll
-    for (int t = 0; t < KW; ++t)
+        for (int pt = 0; pt < G::PT; ++pt)
+          xv[st % kRing][pt] = *(const bf16x8*)(xbase + (pt * 32 + t) * G::XSTRIDE + h * 32);
+      };
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+      for (int st = 0; st < kRing - 1; ++st) fetch(st);
 #pragma unroll
-        for (int pt = 0; pt < G::PT; ++pt) {
-          const bf16x8 xv = *(const bf16x8*)(Xs + (pt * 32 + l31 + t) * G::XSTRIDE +
-                                            (32 * w + 16 * h + lh * 8) * 2);
+      for (int st = 0; st < NS; ++st) {
+        if (st + kRing - 1 < NS) fetch(st + kRing - 1);
+        const int t = st >> 1, h = st & 1;
+#pragma unroll
+        for (int pt = 0; pt < G::PT; ++pt)
 #pragma unroll
           for (int rt = 0; rt < G::RT; ++rt)
-            sacc[rt][pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[rt][t][h], xv, sacc[rt][pt], 0, 0, 0);
-        }
+            sacc[rt][pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[rt][t][h], xv[st % kRing][pt],
+                                                                   sacc[rt][pt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);       // keep the fetch-ahead order (the scheduler would sink the reads)
+      }
+    }
 #pragma unroll
     for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
@@ -227,16 +245,22 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           const float4 v = *(const float4*)(Sred + (ww * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
           s[e4 * 4 + 0] += v.x; s[e4 * 4 + 1] += v.y; s[e4 * 4 + 2] += v.z; s[e4 * 4 + 3] += v.w;
         }
+      if (j0 + BN > T) {                                   // tail tile: positions past T carry no weight
+#pragma unroll
+        for (int e = 0; e < G::EPL; ++e)
+          if (j0 + sp0 + e >= T) s[e] = -INFINITY;
+      }
       float mx = -INFINITY;
 #pragma unroll
-      for (int e = 0; e < G::EPL; ++e) {
-        if (j0 + sp0 + e >= T) s[e] = -INFINITY;
-        mx = fmaxf(mx, s[e]);
-      }
+      for (int e = 0; e < G::EPL; ++e) mx = fmaxf(mx, s[e]);
 #pragma unroll
       for (int o = 1; o < G::LPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      const float m_new = fmaxf(m_run, mx);               // finite: every tile has a valid position
-      const float alpha = __expf(m_run - m_new);
+      // Lazy reference point: the running reference only moves when the row maximum outgrows
+      // it by kLazy, so exp(s - ref) stays below e^kLazy and rescaling the accumulators is rare.
+      const bool bump = mx > m_run + kLazy;                // every tile has a position < T, so mx is finite
+      const float m_new = bump ? mx : m_run;
+      const float alpha = bump ? __expf(m_run - m_new) : 1.0f;
+      const bool any_bump = __any(bump);
       float psum = 0.f;
       uint16_t pb[G::EPL];
 #pragma unroll
@@ -254,31 +278,48 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
         *(uint32_t*)(Ps + srow * G::PSTRIDE + (sp0 + 2 * e2) * 2) =
             (uint32_t)pb[2 * e2] | ((uint32_t)pb[2 * e2 + 1] << 16);
       if ((l % G::LPR) == 0) alphas[srow] = alpha;
+      if (l == 0) rescale_flag[w] = any_bump;
     }
     if (more) stage_store(buf ^ 1);
     __syncthreads();
 
-    // ---- Eq. 4a/4b: rescale and accumulate P . [K | V] for this wave's 64 columns
-#pragma unroll
-    for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float al = alphas[rt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
-        oacc[rt][0][i] *= al;
-        oacc[rt][1][i] *= al;
-      }
-#pragma unroll
-    for (int ks = 0; ks < BN / 16; ++ks) {
-      bf16x8 pv[G::RT];
+    // ---- Eq. 4a/4b: (rarely) rescale, then accumulate P . [K | V] for this wave's 64 columns
+    if (rescale_flag[0] | rescale_flag[1] | rescale_flag[2] | rescale_flag[3]) {
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt)
-        pv[rt] = *(const bf16x8*)(Ps + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const bf16x8 yv = *(const bf16x8*)(Ys + (64 * w + ct * 32 + l31) * G::YSTRIDE + (ks * 16 + lh * 8) * 2);
+        for (int i = 0; i < 16; ++i) {
+          const float al = alphas[rt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
+          oacc[rt][0][i] *= al;
+          oacc[rt][1][i] *= al;
+        }
+    }
+    {
+      // wave 0/1: key columns 64w.. from the key tile (skipping its leading halo rows);
+      // wave 2/3: value columns 64(w-2).. from the value tile.  Transposing reads, see lds_read_tr.
+      const int s16 = l & 15, g2 = (l >> 4) & 1;
+      const unsigned char* ybase =
+          (w < 2 ? Xs + (G::PAD + lh * 8 + (s16 >> 2)) * G::XSTRIDE + (64 * w) * 2
+                 : Vs + (lh * 8 + (s16 >> 2)) * G::VSTRIDE + (64 * (w - 2)) * 2) +
+          (16 * g2 + 4 * (s16 & 3)) * 2;
+      const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
+#pragma unroll
+      for (int ks = 0; ks < BN / 16; ++ks) {
+        bf16x8 pv[G::RT];
 #pragma unroll
         for (int rt = 0; rt < G::RT; ++rt)
-          oacc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv[rt], yv, oacc[rt][ct], 0, 0, 0);
+          pv[rt] = *(const bf16x8*)(Ps + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          const unsigned char* yp = ybase + (ks * 16) * ystride + (ct * 32) * 2;
+          const s16x4 y0 = lds_read_tr(yp);
+          const s16x4 y1 = lds_read_tr(yp + 4 * ystride);
+          const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+          const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
+#pragma unroll
+          for (int rt = 0; rt < G::RT; ++rt)
+            oacc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv[rt], yv, oacc[rt][ct], 0, 0, 0);
+        }
       }
     }
   }
@@ -364,6 +405,9 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   const int chains = a.batch * a.Hkv;
   // 64-row tiles when they still give every compute unit a workgroup, else 32-row tiles
   const bool big = (a.M % 64 == 0) && (int64_t)chains * (a.M / 64) >= n_cu;
+  static int bn = 0;
+  if (!bn) { const char* e = getenv("LOCOCO_DEV_BN"); bn = e ? atoi(e) : 32; }
+  if (big && bn == 64) return launch_one<64, 64, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
   if (big) return launch_one<64, 32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
   return launch_one<32, 32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
 }
