@@ -44,13 +44,20 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return (a >> 16) | (b & 0xffff0000u);
 }
 
-// 16 bytes of row j of [cache ; block], zeros for j >= T.
+// 16 bytes of row j of [cache ; block].  Branch-free (address clamped below T) so that all loads
+// of a tile are in flight together; rows j >= T are zeroed when written to LDS (mask16).
 __device__ __forceinline__ u32x4 load_cat16(const uint16_t* cache_rows, const uint16_t* blk_rows,
                                             int64_t blk_st, int m, int T, int j, int chunk) {
-  u32x4 z = {0u, 0u, 0u, 0u};
-  if (j >= T) return z;
-  const uint16_t* row = j < m ? cache_rows + (int64_t)j * kD : blk_rows + (int64_t)(j - m) * blk_st;
+  const int jc = min(j, T - 1);
+  const bool in_cache = jc < m;
+  const uint16_t* row = in_cache ? cache_rows + (int64_t)jc * kD : blk_rows + (int64_t)(jc - m) * blk_st;
   return *(const u32x4*)(row + chunk * 8);
+}
+
+__device__ __forceinline__ u32x4 mask16(u32x4 v, bool keep_it) {
+  const uint32_t keep = keep_it ? 0xffffffffu : 0u;
+  v[0] &= keep; v[1] &= keep; v[2] &= keep; v[3] &= keep;
+  return v;
 }
 
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
@@ -133,29 +140,31 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
       vreg[it][1] = load_cat16(cache_v, vb, a.v.st, m, T, key0 + 2 * pair + 1, chunk);
     }
   };
-  auto stage_store = [&](int buf) {
+  auto stage_store = [&](int buf, int key0) {
     unsigned char* Ks = Ks0 + buf * KBYTES;
     unsigned char* Vs = Vs0 + buf * VBYTES;
 #pragma unroll
     for (int it = 0; it < KPER; ++it) {
       const int idx = tid + it * kThreads;
-      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = kreg[it];
+      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = mask16(kreg[it], key0 + (idx >> 4) < T);
     }
 #pragma unroll
     for (int it = 0; it < VPER; ++it) {
       const int idx = tid + it * kThreads;
       const int pair = idx % (BK / 2), chunk = idx / (BK / 2);
+      const u32x4 v0 = mask16(vreg[it][0], key0 + 2 * pair < T);
+      const u32x4 v1 = mask16(vreg[it][1], key0 + 2 * pair + 1 < T);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const uint32_t lo = (vreg[it][0][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        const uint32_t hi = (vreg[it][1][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+        const uint32_t lo = (v0[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+        const uint32_t hi = (v1[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
         *(uint32_t*)(Vs + (chunk * 8 + e) * VSTRIDE + pair * 4) = lo | (hi << 16);
       }
     }
   };
 
   stage_load(0);
-  stage_store(0);
+  stage_store(0, 0);
   __syncthreads();
 
   for (int t = 0; t < NT; ++t) {
@@ -234,7 +243,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
           }
         }
     }
-    if (more) stage_store(buf ^ 1);
+    if (more) stage_store(buf ^ 1, key0 + BK);
     __syncthreads();
   }
 

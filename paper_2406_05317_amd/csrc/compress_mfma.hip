@@ -48,7 +48,10 @@ struct Geo {
   static constexpr int VSTRIDE = kD * 2 + 64;        // bytes per value-tile row (conflict-free transposing reads)
   static constexpr int SSTRIDE = BN + 8;             // floats per row of a partial-logit buffer
   static constexpr int PSTRIDE = BN * 2 + 16;        // bytes per row of the bf16 probability tile
-  static constexpr int XBYTES = XROWS * XSTRIDE;
+  static constexpr int XITEMS = XROWS * 16;          // 16-byte chunks of the key tile
+  static constexpr int XPER = (XITEMS + kThreads - 1) / kThreads;
+  static constexpr int XALLOC = XPER * kThreads / 16;  // rows allocated: every thread stores XPER chunks, no tail test
+  static constexpr int XBYTES = XALLOC * XSTRIDE;
   static constexpr int VBYTES = BN * VSTRIDE;
   static constexpr int SBYTES = 4 * BM * SSTRIDE * 4;
   static constexpr int PBYTES = BM * PSTRIDE;
@@ -56,8 +59,6 @@ struct Geo {
   static constexpr int RPW = BM / 4;                 // rows a wave owns in the softmax phase
   static constexpr int LPR = 64 / RPW;               // lanes per row there
   static constexpr int EPL = BN / LPR;               // positions per lane there
-  static constexpr int XITEMS = XROWS * 16;          // 16-byte chunks of the key tile
-  static constexpr int XPER = (XITEMS + kThreads - 1) / kThreads;
   static constexpr int VITEMS = BN * 16;             // 16-byte chunks of the value tile
   static constexpr int VPER = VITEMS / kThreads;
   static_assert(BM == 32 || BM == 64, "BM");
@@ -80,15 +81,24 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
-// 16 bytes of row p of [cache ; block] (keys or values), zeros outside [0, T).
+// 16 bytes of row p of [cache ; block] (keys or values).  Branch-free: the address is clamped
+// into [0, T) so the loads of a tile can all be in flight together; rows outside [0, T) are
+// zeroed later, when the data is written to LDS (mask16).
 __device__ __forceinline__ u32x4 load_cat16(const void* cache, const View& blk, int M, int m, int T,
                                             int b, int hkv, int Hkv, int p, int chunk) {
-  u32x4 z = {0u, 0u, 0u, 0u};
-  if (p < 0 || p >= T) return z;
-  const uint16_t* row =
-      p < m ? (const uint16_t*)cache + ((int64_t)(b * Hkv + hkv) * M + p) * kD
-            : (const uint16_t*)blk.p + b * blk.sb + hkv * blk.sh + (int64_t)(p - m) * blk.st;
+  const int pc = min(max(p, 0), T - 1);
+  const bool in_cache = pc < m;
+  const int64_t cache_off = ((int64_t)(b * Hkv + hkv) * M + pc) * kD;
+  const int64_t blk_off = b * blk.sb + hkv * blk.sh + (int64_t)(pc - m) * blk.st;
+  const uint16_t* base = in_cache ? (const uint16_t*)cache : (const uint16_t*)blk.p;
+  const uint16_t* row = base + (in_cache ? cache_off : blk_off);
   return *(const u32x4*)(row + chunk * 8);
+}
+
+__device__ __forceinline__ u32x4 mask16(u32x4 v, bool keep_it) {
+  const uint32_t keep = keep_it ? 0xffffffffu : 0u;
+  v[0] &= keep; v[1] &= keep; v[2] &= keep; v[3] &= keep;
+  return v;
 }
 
 // wp: filters repacked as [bank][M][KW][C] bf16.
@@ -150,8 +160,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     for (int it = 0; it < G::XPER; ++it) {
       const int item = tid + it * kThreads;
       const int r = item >> 4, chunk = item & 15;
-      if (item < G::XITEMS)
-        xreg[it] = load_cat16(a.cache_k, a.k, a.M, a.m, T, b, hkv, a.Hkv, j0 - G::PAD + r, chunk);
+      xreg[it] = load_cat16(a.cache_k, a.k, a.M, a.m, T, b, hkv, a.Hkv, j0 - G::PAD + r, chunk);
     }
 #pragma unroll
     for (int it = 0; it < G::VPER; ++it) {
@@ -159,24 +168,26 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       vreg[it] = load_cat16(a.cache_v, a.v, a.M, a.m, T, b, hkv, a.Hkv, j0 + (item >> 4), item & 15);
     }
   };
-  auto stage_store = [&](int buf) {
+  auto stage_store = [&](int buf, int j0) {
     unsigned char* Xs = Xs0 + buf * G::XBYTES;
     unsigned char* Vs = Vs0 + buf * G::VBYTES;
 #pragma unroll
     for (int it = 0; it < G::XPER; ++it) {
       const int item = tid + it * kThreads;
       const int r = item >> 4, chunk = item & 15;
-      if (item < G::XITEMS) *(u32x4*)(Xs + r * G::XSTRIDE + chunk * 16) = xreg[it];
+      const int p = j0 - G::PAD + r;
+      *(u32x4*)(Xs + r * G::XSTRIDE + chunk * 16) = mask16(xreg[it], p >= 0 && p < T);
     }
 #pragma unroll
     for (int it = 0; it < G::VPER; ++it) {
       const int item = tid + it * kThreads;
-      *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it];
+      *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) =
+          mask16(vreg[it], j0 + (item >> 4) < T);
     }
   };
 
   stage_load(0);
-  stage_store(0);
+  stage_store(0, 0);
   __syncthreads();
 
   for (int jt = 0; jt < NT; ++jt) {
@@ -184,8 +195,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     const int j0 = jt * BN;
     const unsigned char* Xs = Xs0 + buf * G::XBYTES;
     const unsigned char* Vs = Vs0 + buf * G::VBYTES;
-    const bool more = jt + 1 < NT;
-    if (more) stage_load(j0 + BN);
+    stage_load(j0 + BN);     // past the last tile the clamped addresses still point into the chain
 
     // ---- Eq. 5: partial logits over this wave's channel quarter
     f32x16 sacc[G::RT][G::PT];
@@ -280,7 +290,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       if ((l % G::LPR) == 0) alphas[srow] = alpha;
       if (l == 0) rescale_flag[w] = any_bump;
     }
-    if (more) stage_store(buf ^ 1);
+    stage_store(buf ^ 1, j0 + BN);
     __syncthreads();
 
     // ---- Eq. 4a/4b: (rarely) rescale, then accumulate P . [K | V] for this wave's 64 columns
