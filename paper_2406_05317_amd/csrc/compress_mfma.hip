@@ -4,25 +4,34 @@
 // normalised weights never leave the compute unit.
 //
 // Structure.  The step is "attention with a convolution for scores": for a
-// tile of BM cache slots (rows) the kernel walks the T = m + B positions of
-// [cache ; block] in tiles of BN, computes the BM x BN logits as an implicit
-// GEMM with inner dimension C*k (each filter tap is a row-shifted view of the
-// key tile held in LDS), keeps a running row max / row sum (online softmax),
-// and accumulates P . [K | V] into a BM x 2d fp32 accumulator.
+// tile of BM cache slots the kernel walks the T = m + B positions of
+// [cache ; block] in tiles of 32, computes the logits as an implicit GEMM
+// with inner dimension C*k (each filter tap is a row-shifted view of the key
+// tile held in LDS), keeps a running reference / row sum per slot (online
+// softmax), and accumulates [K | V]^T P^T into a 2d x BM fp32 accumulator.
 //
 // Register-stationary filters.  The filter bank is the same for every
 // position, chain and step, and a compute unit's register file (512 KB) is
 // larger than its slice of the bank, so each workgroup loads its BM x (C*k)
-// filter slice into VGPRs once and streams only keys/values through LDS.
+// filter slice into registers once and streams only keys/values through LDS.
 // The four waves split the inner dimension by channel quarter (wave w owns
 // channels [32w, 32w+32) of every tap); their partial logits are summed
 // through LDS before the softmax.  For the mixing GEMM wave w owns output
 // columns [64w, 64w+64) of [K | V].
 //
+// Transposed tiles.  Both GEMMs are computed transposed (positions x slots,
+// then columns x slots) so that an MFMA lane always belongs to one slot: the
+// partial logits leave the registers as 16-byte stores, the rescale factor is
+// a per-lane scalar and the new cache rows are stored 8 bytes at a time.
+//
+// Software pipeline.  One wave per SIMD leaves nothing to switch to while a
+// wave waits, so the loop is pipelined by hand: while the MFMAs of tile i+1's
+// logits issue, the wave works through tile i's reduction, softmax and the
+// staging of later tiles in small slices pinned between the MFMAs; then, after
+// a barrier, it mixes tile i and publishes tile i+1's partial logits.
+//
 // Shapes taken: head_dim = C = 128, bf16, conv_in = 0, norm = 0 (softmax),
 // M a multiple of BM; any T (tail positions are masked), any m.
-#include <cstdlib>
-
 #include "lococo_internal.h"
 
 namespace lococo {
@@ -30,53 +39,57 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kD = 128;            // head_dim = conv channels
 constexpr int kThreads = 256;
-constexpr float kLazy = 8.0f;      // softmax reference lags the row maximum by at most this much
+constexpr int BN = 32;             // positions per tile
+constexpr float kLazy = 8.0f;      // the softmax reference lags the row maximum by at most this much
 
-template <int BM, int BN, int KW>
+template <int BM, int KW>
 struct Geo {
-  static constexpr int RT = BM / 32;                 // 32-row MFMA tiles per workgroup
-  static constexpr int PT = BN / 32;                 // 32-position MFMA tiles per iteration
+  static constexpr int RT = BM / 32;                 // 32-slot MFMA tiles per workgroup
+  static constexpr int NS = KW * 2;                  // contraction steps of a logit tile: (tap, channel half)
   static constexpr int PAD = (KW - 1) / 2;
   static constexpr int XROWS = BN + KW - 1;          // key tile rows incl. halo
-  static constexpr int XSTRIDE = kD * 2 + 16;        // bytes per key-tile row (padded: conflict-free b128 reads)
+  static constexpr int XSTRIDE = kD * 2 + 16;        // bytes per key-tile row (conflict-free 16-byte reads)
   static constexpr int VSTRIDE = kD * 2 + 64;        // bytes per value-tile row (conflict-free transposing reads)
-  static constexpr int SSTRIDE = BN + 8;             // floats per row of a partial-logit buffer
-  static constexpr int PSTRIDE = BN * 2 + 16;        // bytes per row of the bf16 probability tile
+  static constexpr int SSTRIDE = BN + 4;             // floats per slot row of a partial-logit buffer
+  static constexpr int PSTRIDE = BN * 2 + 16;        // bytes per slot row of the bf16 probability tile
   static constexpr int XITEMS = XROWS * 16;          // 16-byte chunks of the key tile
   static constexpr int XPER = (XITEMS + kThreads - 1) / kThreads;
-  static constexpr int XALLOC = XPER * kThreads / 16;  // rows allocated: every thread stores XPER chunks, no tail test
+  static constexpr int XALLOC = XPER * kThreads / 16;  // rows allocated: every thread stores XPER chunks
   static constexpr int XBYTES = XALLOC * XSTRIDE;
+  static constexpr int VPER = BN * 16 / kThreads;    // 16-byte chunks of the value tile per thread
   static constexpr int VBYTES = BN * VSTRIDE;
   static constexpr int SBYTES = 4 * BM * SSTRIDE * 4;
   static constexpr int PBYTES = BM * PSTRIDE;
-  static constexpr int LDS = 2 * (XBYTES + VBYTES) + SBYTES + PBYTES + 2 * BM * 4 + 16;
-  static constexpr int RPW = BM / 4;                 // rows a wave owns in the softmax phase
-  static constexpr int LPR = 64 / RPW;               // lanes per row there
+  static constexpr int NXBUF = 3, NVBUF = 2;
+  static constexpr int LDS = NXBUF * XBYTES + NVBUF * VBYTES + SBYTES + PBYTES + 2 * BM * 4 + 16;
+  static constexpr int RPW = BM / 4;                 // slots a wave owns in the softmax phase
+  static constexpr int LPR = 64 / RPW;               // lanes per slot there
   static constexpr int EPL = BN / LPR;               // positions per lane there
-  static constexpr int VITEMS = BN * 16;             // 16-byte chunks of the value tile
-  static constexpr int VPER = VITEMS / kThreads;
   static_assert(BM == 32 || BM == 64, "BM");
-  static_assert(BN % 32 == 0 && VITEMS % kThreads == 0, "BN");
   static_assert(EPL % 4 == 0, "softmax lanes read whole float4s");
+  static_assert(NS >= 26, "the slices of the pipelined loop are laid out over 26 contraction steps");
 };
 
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);   // RNE; inputs here are finite
-  return (uint16_t)(u >> 16);
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7fffu + ((a >> 16) & 1u);   // RNE; inputs here are finite
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xffff0000u);
 }
 
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s supplies the
 // address of 4 consecutive 16-bit elements; lane i of the group receives element (i % 4) of the
 // chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane s pointing at
 // (row r0 + s/4, column c0 + 4*(s%4)) of a row-major tile, lane i ends up with column c0 + i of
-// rows r0 .. r0+3: a K x N operand fragment read straight from a row-major tile.
+// rows r0 .. r0+3: an operand fragment (column, 4 contraction rows) straight from a row-major tile.
 __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
@@ -84,14 +97,11 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
 // 16 bytes of row p of [cache ; block] (keys or values).  Branch-free: the address is clamped
 // into [0, T) so the loads of a tile can all be in flight together; rows outside [0, T) are
 // zeroed later, when the data is written to LDS (mask16).
-__device__ __forceinline__ u32x4 load_cat16(const void* cache, const View& blk, int M, int m, int T,
-                                            int b, int hkv, int Hkv, int p, int chunk) {
+__device__ __forceinline__ u32x4 load_cat16(const uint16_t* cache_rows, const uint16_t* blk_rows,
+                                            int64_t blk_st, int m, int T, int p, int chunk) {
   const int pc = min(max(p, 0), T - 1);
   const bool in_cache = pc < m;
-  const int64_t cache_off = ((int64_t)(b * Hkv + hkv) * M + pc) * kD;
-  const int64_t blk_off = b * blk.sb + hkv * blk.sh + (int64_t)(pc - m) * blk.st;
-  const uint16_t* base = in_cache ? (const uint16_t*)cache : (const uint16_t*)blk.p;
-  const uint16_t* row = base + (in_cache ? cache_off : blk_off);
+  const uint16_t* row = in_cache ? cache_rows + (int64_t)pc * kD : blk_rows + (int64_t)(pc - m) * blk_st;
   return *(const u32x4*)(row + chunk * 8);
 }
 
@@ -102,26 +112,32 @@ __device__ __forceinline__ u32x4 mask16(u32x4 v, bool keep_it) {
 }
 
 // wp: filters repacked as [bank][M][KW][C] bf16.
-template <int BM, int BN, int KW>
+template <int BM, int KW>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
-  using G = Geo<BM, BN, KW>;
+  using G = Geo<BM, KW>;
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* Xs0 = smem;
-  unsigned char* Vs0 = smem + 2 * G::XBYTES;
-  float* Sred = (float*)(smem + 2 * (G::XBYTES + G::VBYTES));
-  unsigned char* Ps = (unsigned char*)Sred + G::SBYTES;
-  float* alphas = (float*)(Ps + G::PBYTES);
-  float* lsum = alphas + BM;
-  int* rescale_flag = (int*)(lsum + BM);             // one word per wave
+  unsigned char* Xs0 = smem;                                    // NXBUF key tiles (with halo)
+  unsigned char* Vs0 = Xs0 + G::NXBUF * G::XBYTES;              // NVBUF value tiles
+  float* Sred = (float*)(Vs0 + G::NVBUF * G::VBYTES);           // 4 partial-logit tiles [wave][slot][pos]
+  unsigned char* Ps = (unsigned char*)Sred + G::SBYTES;         // probabilities [slot][pos], bf16
+  float* alphas = (float*)(Ps + G::PBYTES);                     // rescale factor per slot
+  float* lsum = alphas + BM;                                    // final row sums
+  int* rescale_flag = (int*)(lsum + BM);                        // one word per wave
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
   const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
   const int i0 = blockIdx.x * BM;
-  const int T = a.m + a.Bn;
+  const int T = a.m + a.Bn, m = a.m;
   const int NT = (T + BN - 1) / BN;
 
-  // ---- this wave's slice of the filter bank, resident in registers for the whole kernel
+  const uint16_t* cache_k = (const uint16_t*)a.cache_k + (int64_t)ch * a.M * kD;
+  const uint16_t* cache_v = (const uint16_t*)a.cache_v + (int64_t)ch * a.M * kD;
+  const uint16_t* blk_k = (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh;
+  const uint16_t* blk_v = (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh;
+
+  // ---- this wave's slice of the filter bank, resident in registers for the whole kernel:
+  // lane (slot l31 of tile rt, channels 32w + 16h + 8*lh ..) for every tap
   bf16x8 wreg[G::RT][KW][2];
   {
     const uint16_t* wb = wp + hkv * wp_head_stride;
@@ -130,228 +146,251 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
       for (int t = 0; t < KW; ++t)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int row = i0 + rt * 32 + l31;
-          const int c = 32 * w + 16 * h + lh * 8;
-          wreg[rt][t][h] = *(const bf16x8*)(wb + ((int64_t)row * KW + t) * kD + c);
-        }
+        for (int h = 0; h < 2; ++h)
+          wreg[rt][t][h] = *(const bf16x8*)(wb + ((int64_t)(i0 + rt * 32 + l31) * KW + t) * kD +
+                                            32 * w + 16 * h + lh * 8);
   }
 
-  f32x16 oacc[G::RT][2];
+  // mixing accumulator, transposed: lane = slot rt*32 + l31, rows = columns 64w + ct*32 + (i/4)*8 + lh*4 + i%4
+  f32x16 oacc[2][G::RT];
 #pragma unroll
-  for (int rt = 0; rt < G::RT; ++rt)
+  for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
+    for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[rt][ct][i] = 0.f;
+      for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
 
-  // softmax state of the row this lane helps with (replicated over the LPR lanes of the row)
+  // softmax state of the slot this lane helps with (replicated over the LPR lanes of the slot)
   const int srow = w * G::RPW + l / G::LPR;
   const int sp0 = (l % G::LPR) * G::EPL;
   float m_run = -INFINITY, l_run = 0.f;
-  const float bias = a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv * a.b_head_stride + i0 + srow] << 16)
-                              : 0.f;
+  const float bias =
+      a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv * a.b_head_stride + i0 + srow] << 16)
+               : 0.f;
 
-  // ---- staging: global -> registers -> LDS (key tile row-major with halo; [K|V] tile transposed)
+  // ---- staging: global -> registers -> LDS (key tile with halo, value tile; both row-major)
   u32x4 xreg[G::XPER];
   u32x4 vreg[G::VPER];
-  auto stage_load = [&](int j0) {
-#pragma unroll
-    for (int it = 0; it < G::XPER; ++it) {
-      const int item = tid + it * kThreads;
-      const int r = item >> 4, chunk = item & 15;
-      xreg[it] = load_cat16(a.cache_k, a.k, a.M, a.m, T, b, hkv, a.Hkv, j0 - G::PAD + r, chunk);
-    }
-#pragma unroll
-    for (int it = 0; it < G::VPER; ++it) {
-      const int item = tid + it * kThreads;
-      vreg[it] = load_cat16(a.cache_v, a.v, a.M, a.m, T, b, hkv, a.Hkv, j0 + (item >> 4), item & 15);
-    }
+  auto load_x = [&](int it, int j0) {
+    const int item = tid + it * kThreads;
+    xreg[it] = load_cat16(cache_k, blk_k, a.k.st, m, T, j0 - G::PAD + (item >> 4), item & 15);
   };
-  auto stage_store = [&](int buf, int j0) {
-    unsigned char* Xs = Xs0 + buf * G::XBYTES;
-    unsigned char* Vs = Vs0 + buf * G::VBYTES;
-#pragma unroll
-    for (int it = 0; it < G::XPER; ++it) {
-      const int item = tid + it * kThreads;
-      const int r = item >> 4, chunk = item & 15;
-      const int p = j0 - G::PAD + r;
-      *(u32x4*)(Xs + r * G::XSTRIDE + chunk * 16) = mask16(xreg[it], p >= 0 && p < T);
-    }
-#pragma unroll
-    for (int it = 0; it < G::VPER; ++it) {
-      const int item = tid + it * kThreads;
-      *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) =
-          mask16(vreg[it], j0 + (item >> 4) < T);
-    }
+  auto load_v = [&](int it, int j0) {
+    const int item = tid + it * kThreads;
+    vreg[it] = load_cat16(cache_v, blk_v, a.v.st, m, T, j0 + (item >> 4), item & 15);
+  };
+  auto store_x = [&](int it, int j0, unsigned char* Xs) {
+    const int item = tid + it * kThreads;
+    const int r = item >> 4, p = j0 - G::PAD + r;
+    *(u32x4*)(Xs + r * G::XSTRIDE + (item & 15) * 16) = mask16(xreg[it], p >= 0 && p < T);
+  };
+  auto store_v = [&](int it, int j0, unsigned char* Vs) {
+    const int item = tid + it * kThreads;
+    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = mask16(vreg[it], j0 + (item >> 4) < T);
   };
 
-  stage_load(0);
-  stage_store(0, 0);
-  __syncthreads();
-
-  for (int jt = 0; jt < NT; ++jt) {
-    const int buf = jt & 1;
-    const int j0 = jt * BN;
-    const unsigned char* Xs = Xs0 + buf * G::XBYTES;
-    const unsigned char* Vs = Vs0 + buf * G::VBYTES;
-    stage_load(j0 + BN);     // past the last tile the clamped addresses still point into the chain
-
-    // ---- Eq. 5: partial logits over this wave's channel quarter
-    f32x16 sacc[G::RT][G::PT];
+  // Logit tile of positions [j0, j0+32) x this workgroup's slots, summed over this wave's channel
+  // quarter: sacc[rt] lane = slot rt*32 + l31, rows = positions (i/4)*8 + lh*4 + i%4.
+  // `slice(st)` is called once after the MFMAs of contraction step st.
+  f32x16 sacc[G::RT];
+  auto conv_tile = [&](const unsigned char* Xs, auto&& slice) {
+    constexpr int kRing = 4;                   // key operands are fetched kRing-1 steps ahead
+    bf16x8 xv[kRing];
+    const unsigned char* xbase = Xs + l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
+    auto fetch = [&](int st) {
+      xv[st % kRing] = *(const bf16x8*)(xbase + (st >> 1) * G::XSTRIDE + (st & 1) * 32);
+    };
 #pragma unroll
     for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
-      for (int pt = 0; pt < G::PT; ++pt)
+      for (int i = 0; i < 16; ++i) sacc[rt][i] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[rt][pt][i] = 0.f;
-    {
-      // key operands are fetched from LDS kRing contraction steps ahead of their MFMAs
-      constexpr int NS = KW * 2;                 // contraction steps: (tap, channel half)
-      constexpr int kRing = 4;
-      bf16x8 xv[kRing][G::PT];
-      const unsigned char* xbase = Xs + l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
-      auto fetch = [&](int st) {
-        const int t = st >> 1, h = st & 1;
+    for (int st = 0; st < kRing - 1; ++st) fetch(st);
 #pragma unroll
-        for (int pt = 0; pt < G::PT; ++pt)
-          xv[st % kRing][pt] = *(const bf16x8*)(xbase + (pt * 32 + t) * G::XSTRIDE + h * 32);
-      };
-#pragma unroll
-      for (int st = 0; st < kRing - 1; ++st) fetch(st);
-#pragma unroll
-      for (int st = 0; st < NS; ++st) {
-        if (st + kRing - 1 < NS) fetch(st + kRing - 1);
-        const int t = st >> 1, h = st & 1;
-#pragma unroll
-        for (int pt = 0; pt < G::PT; ++pt)
-#pragma unroll
-          for (int rt = 0; rt < G::RT; ++rt)
-            sacc[rt][pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[rt][t][h], xv[st % kRing][pt],
-                                                                   sacc[rt][pt], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);       // keep the fetch-ahead order (the scheduler would sink the reads)
-      }
-    }
-#pragma unroll
-    for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-      for (int pt = 0; pt < G::PT; ++pt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int row = rt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-          Sred[(w * BM + row) * G::SSTRIDE + pt * 32 + l31] = sacc[rt][pt][i];
-        }
-    __syncthreads();
-
-    // ---- sum the four partials, Eq. 6 as an online softmax over positions
-    {
-      float s[G::EPL];
-#pragma unroll
-      for (int e = 0; e < G::EPL; ++e) s[e] = bias;
-#pragma unroll
-      for (int ww = 0; ww < 4; ++ww)
-#pragma unroll
-        for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
-          const float4 v = *(const float4*)(Sred + (ww * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
-          s[e4 * 4 + 0] += v.x; s[e4 * 4 + 1] += v.y; s[e4 * 4 + 2] += v.z; s[e4 * 4 + 3] += v.w;
-        }
-      if (j0 + BN > T) {                                   // tail tile: positions past T carry no weight
-#pragma unroll
-        for (int e = 0; e < G::EPL; ++e)
-          if (j0 + sp0 + e >= T) s[e] = -INFINITY;
-      }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int e = 0; e < G::EPL; ++e) mx = fmaxf(mx, s[e]);
-#pragma unroll
-      for (int o = 1; o < G::LPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      // Lazy reference point: the running reference only moves when the row maximum outgrows
-      // it by kLazy, so exp(s - ref) stays below e^kLazy and rescaling the accumulators is rare.
-      const bool bump = mx > m_run + kLazy;                // every tile has a position < T, so mx is finite
-      const float m_new = bump ? mx : m_run;
-      const float alpha = bump ? __expf(m_run - m_new) : 1.0f;
-      const bool any_bump = __any(bump);
-      float psum = 0.f;
-      uint16_t pb[G::EPL];
-#pragma unroll
-      for (int e = 0; e < G::EPL; ++e) {
-        const float p = __expf(s[e] - m_new);
-        psum += p;
-        pb[e] = f2bf(p);
-      }
-#pragma unroll
-      for (int o = 1; o < G::LPR; o <<= 1) psum += __shfl_xor(psum, o, 64);
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int e2 = 0; e2 < G::EPL / 2; ++e2)
-        *(uint32_t*)(Ps + srow * G::PSTRIDE + (sp0 + 2 * e2) * 2) =
-            (uint32_t)pb[2 * e2] | ((uint32_t)pb[2 * e2 + 1] << 16);
-      if ((l % G::LPR) == 0) alphas[srow] = alpha;
-      if (l == 0) rescale_flag[w] = any_bump;
-    }
-    stage_store(buf ^ 1, j0 + BN);
-    __syncthreads();
-
-    // ---- Eq. 4a/4b: (rarely) rescale, then accumulate P . [K | V] for this wave's 64 columns
-    if (rescale_flag[0] | rescale_flag[1] | rescale_flag[2] | rescale_flag[3]) {
+    for (int st = 0; st < G::NS; ++st) {
+      if (st + kRing - 1 < G::NS) fetch(st + kRing - 1);
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float al = alphas[rt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
-          oacc[rt][0][i] *= al;
-          oacc[rt][1][i] *= al;
-        }
+        sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
+                                                           sacc[rt], 0, 0, 0);
+      slice(st);
+      __builtin_amdgcn_sched_barrier(0);       // pin the order: fetch-ahead, MFMAs, this step's slice
     }
-    {
-      // wave 0/1: key columns 64w.. from the key tile (skipping its leading halo rows);
-      // wave 2/3: value columns 64(w-2).. from the value tile.  Transposing reads, see lds_read_tr.
-      const int s16 = l & 15, g2 = (l >> 4) & 1;
-      const unsigned char* ybase =
-          (w < 2 ? Xs + (G::PAD + lh * 8 + (s16 >> 2)) * G::XSTRIDE + (64 * w) * 2
-                 : Vs + (lh * 8 + (s16 >> 2)) * G::VSTRIDE + (64 * (w - 2)) * 2) +
-          (16 * g2 + 4 * (s16 & 3)) * 2;
-      const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
+  };
+  // Publish this wave's partial logits: 16-byte stores, 4 consecutive positions of one slot each.
+  auto write_partials = [&]() {
 #pragma unroll
-      for (int ks = 0; ks < BN / 16; ++ks) {
-        bf16x8 pv[G::RT];
+    for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
-        for (int rt = 0; rt < G::RT; ++rt)
-          pv[rt] = *(const bf16x8*)(Ps + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 v = {sacc[rt][g * 4 + 0], sacc[rt][g * 4 + 1], sacc[rt][g * 4 + 2], sacc[rt][g * 4 + 3]};
+        *(f32x4*)(Sred + (w * BM + rt * 32 + l31) * G::SSTRIDE + g * 8 + lh * 4) = v;
+      }
+  };
+
+  // ---- Eq. 6 for one tile in slices: sum the four partials, online softmax with a lazy reference
+  float sv[G::EPL];
+  float mx, m_new, alpha, psum;
+  bool bump;
+  auto sm_read = [&](int ww, bool first) {
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          const unsigned char* yp = ybase + (ks * 16) * ystride + (ct * 32) * 2;
-          const s16x4 y0 = lds_read_tr(yp);
-          const s16x4 y1 = lds_read_tr(yp + 4 * ystride);
-          const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
-          const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
+    for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
+      const f32x4 v = *(const f32x4*)(Sred + (ww * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
 #pragma unroll
-          for (int rt = 0; rt < G::RT; ++rt)
-            oacc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv[rt], yv, oacc[rt][ct], 0, 0, 0);
-        }
+      for (int e = 0; e < 4; ++e) sv[e4 * 4 + e] = (first ? bias : sv[e4 * 4 + e]) + v[e];
+    }
+  };
+  auto sm_max = [&](int j0) {
+    if (j0 + BN > T) {                         // tail tile: positions past T carry no weight
+#pragma unroll
+      for (int e = 0; e < G::EPL; ++e)
+        if (j0 + sp0 + e >= T) sv[e] = -INFINITY;
+    }
+    mx = sv[0];
+#pragma unroll
+    for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
+#pragma unroll
+    for (int o = 1; o < G::LPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref) stays
+    // below e^kLazy and the accumulators are rescaled rarely.  Every tile has a position < T,
+    // so mx is finite.
+    bump = mx > m_run + kLazy;
+    m_new = bump ? mx : m_run;
+    alpha = bump ? __expf(m_run - m_new) : 1.0f;
+  };
+  auto sm_exp = [&]() {
+    psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < G::EPL; ++e) {
+      sv[e] = __expf(sv[e] - m_new);
+      psum += sv[e];
+    }
+  };
+  auto sm_finish = [&]() {
+#pragma unroll
+    for (int o = 1; o < G::LPR; o <<= 1) psum += __shfl_xor(psum, o, 64);
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    const bool any_bump = __any(bump);
+#pragma unroll
+    for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
+      u32x2 pk;
+      pk[0] = pack_bf16(sv[e4 * 4 + 0], sv[e4 * 4 + 1]);
+      pk[1] = pack_bf16(sv[e4 * 4 + 2], sv[e4 * 4 + 3]);
+      *(u32x2*)(Ps + srow * G::PSTRIDE + (sp0 + e4 * 4) * 2) = pk;
+    }
+    if ((l % G::LPR) == 0) alphas[srow] = alpha;
+    if (l == 0) rescale_flag[w] = any_bump;
+  };
+
+  // ---- Eq. 4a/4b for one tile: (rarely) rescale, then oacc += [K | V]^T P^T for this wave's columns.
+  // Wave 0/1: key columns 64w.. from the key tile (skipping its halo rows); wave 2/3: value columns.
+  auto mix_tile = [&](const unsigned char* Xs, const unsigned char* Vs) {
+    if (rescale_flag[0] | rescale_flag[1] | rescale_flag[2] | rescale_flag[3]) {
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt) {
+        const float al = alphas[rt * 32 + l31];
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[ct][rt][i] *= al;
       }
     }
+    const int s16 = l & 15, g2 = (l >> 4) & 1;
+    const unsigned char* ybase =
+        (w < 2 ? Xs + (G::PAD + lh * 8 + (s16 >> 2)) * G::XSTRIDE + (64 * w) * 2
+               : Vs + (lh * 8 + (s16 >> 2)) * G::VSTRIDE + (64 * (w - 2)) * 2) +
+        (16 * g2 + 4 * (s16 & 3)) * 2;
+    const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
+#pragma unroll
+    for (int ks = 0; ks < BN / 16; ++ks) {
+      bf16x8 pv[G::RT];
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt)
+        pv[rt] = *(const bf16x8*)(Ps + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        const unsigned char* yp = ybase + (ks * 16) * ystride + (ct * 32) * 2;
+        const s16x4 y0 = lds_read_tr(yp);
+        const s16x4 y1 = lds_read_tr(yp + 4 * ystride);
+        const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+        const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
+#pragma unroll
+        for (int rt = 0; rt < G::RT; ++rt)
+          oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[rt], oacc[ct][rt], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- prologue: tiles 0 and 1 staged, logits of tile 0 published
+#pragma unroll
+  for (int it = 0; it < G::XPER; ++it) load_x(it, 0);
+#pragma unroll
+  for (int it = 0; it < G::VPER; ++it) load_v(it, 0);
+#pragma unroll
+  for (int it = 0; it < G::XPER; ++it) store_x(it, 0, Xs0);
+#pragma unroll
+  for (int it = 0; it < G::VPER; ++it) store_v(it, 0, Vs0);
+#pragma unroll
+  for (int it = 0; it < G::XPER; ++it) load_x(it, BN);
+#pragma unroll
+  for (int it = 0; it < G::XPER; ++it) store_x(it, BN, Xs0 + G::XBYTES);
+  __syncthreads();
+  conv_tile(Xs0, [](int) {});
+  write_partials();
+  __syncthreads();
+
+  // ---- main loop.  Iteration i: [logits of tile i+1 | reduce + softmax of tile i | staging of
+  // key tile i+2 and value tile i+1] barrier [mix tile i | publish partial logits of tile i+1] barrier
+  for (int i = 0; i < NT; ++i) {
+    const int j0 = i * BN;
+    unsigned char* Xcur = Xs0 + (i % G::NXBUF) * G::XBYTES;
+    unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
+    unsigned char* Xstage = Xs0 + ((i + 2) % G::NXBUF) * G::XBYTES;
+    unsigned char* Vcur = Vs0 + (i % G::NVBUF) * G::VBYTES;
+    unsigned char* Vstage = Vs0 + ((i + 1) % G::NVBUF) * G::VBYTES;
+
+    // The tile after the last one holds only masked (zero) keys; its logits are never used.
+    conv_tile(Xnext, [&](int st) {
+      // staging loads first (longest latency), then the softmax chain, then the LDS stores
+      if (st < G::XPER) load_x(st, j0 + 2 * BN);
+      else if (st < G::XPER + G::VPER) load_v(st - G::XPER, j0 + BN);
+      if (st == 1) sm_read(0, true);
+      if (st == 3) sm_read(1, false);
+      if (st == 5) sm_read(2, false);
+      if (st == 7) sm_read(3, false);
+      if (st == 10) sm_max(j0);
+      if (st == 13) sm_exp();
+      if (st == 16) sm_finish();
+      if (st >= 18 && st < 18 + G::XPER) store_x(st - 18, j0 + 2 * BN, Xstage);
+      if (st >= 18 + G::XPER && st < 18 + G::XPER + G::VPER) store_v(st - 18 - G::XPER, j0 + BN, Vstage);
+    });
+    __syncthreads();
+    mix_tile(Xcur, Vcur);
+    write_partials();
+    __syncthreads();
   }
 
-  // ---- normalise by the row sums and store the new cache rows
+  // ---- normalise by the row sums and store the new cache rows, 4 columns (8 bytes) per store
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
   __syncthreads();
   uint16_t* nk = (uint16_t*)a.new_k + ((int64_t)ch * a.M + i0) * kD;
   uint16_t* nv = (uint16_t*)a.new_v + ((int64_t)ch * a.M + i0) * kD;
+  uint16_t* obase = (w < 2 ? nk : nv) + 64 * (w & 1);
 #pragma unroll
-  for (int rt = 0; rt < G::RT; ++rt)
+  for (int rt = 0; rt < G::RT; ++rt) {
+    const int slot = rt * 32 + l31;
+    const float inv = 1.0f / lsum[slot];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = rt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-      const float inv = 1.0f / lsum[row];
+    for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const int col = 64 * w + ct * 32 + l31;          // 0..127: K, 128..255: V
-        uint16_t* dst = (col < kD ? nk : nv) + (int64_t)row * kD + (col & (kD - 1));
-        *dst = f2bf(oacc[rt][ct][i] * inv);
+      for (int g = 0; g < 4; ++g) {
+        u32x2 pk;
+        pk[0] = pack_bf16(oacc[ct][rt][g * 4 + 0] * inv, oacc[ct][rt][g * 4 + 1] * inv);
+        pk[1] = pack_bf16(oacc[ct][rt][g * 4 + 2] * inv, oacc[ct][rt][g * 4 + 3] * inv);
+        *(u32x2*)(obase + (int64_t)slot * kD + ct * 32 + g * 8 + lh * 4) = pk;
       }
-    }
+  }
 }
 
 // [M][C][k] -> [M][k][C] per bank, so that 8 consecutive channels of one tap are 16 contiguous bytes.
@@ -367,19 +406,18 @@ __global__ void repack_filters_k(const uint16_t* w, uint16_t* wp, int M, int C, 
   }
 }
 
-template <int BM, int BN, int KW>
+template <int BM, int KW>
 hipError_t launch_one(const StepArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
-  using G = Geo<BM, BN, KW>;
+  using G = Geo<BM, KW>;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, BN, KW>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(a.M / BM, a.batch * a.Hkv);
-  hipLaunchKernelGGL((compress_mfma_k<BM, BN, KW>), grid, dim3(kThreads), G::LDS, s, a, wp,
-                     wp_head_stride);
+  hipLaunchKernelGGL((compress_mfma_k<BM, KW>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
   return hipGetLastError();
 }
 
@@ -413,13 +451,10 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
                                 hipStream_t s) {
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
   const int chains = a.batch * a.Hkv;
-  // 64-row tiles when they still give every compute unit a workgroup, else 32-row tiles
+  // 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles
   const bool big = (a.M % 64 == 0) && (int64_t)chains * (a.M / 64) >= n_cu;
-  static int bn = 0;
-  if (!bn) { const char* e = getenv("LOCOCO_DEV_BN"); bn = e ? atoi(e) : 32; }
-  if (big && bn == 64) return launch_one<64, 64, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
-  if (big) return launch_one<64, 32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
-  return launch_one<32, 32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
+  if (big) return launch_one<64, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
+  return launch_one<32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
 }
 
 }  // namespace lococo
