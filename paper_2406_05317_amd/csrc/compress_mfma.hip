@@ -25,13 +25,17 @@
 // a per-lane scalar and the new cache rows are stored 8 bytes at a time.
 //
 // Software pipeline.  One wave per SIMD leaves nothing to switch to while a
-// wave waits, so the loop is pipelined by hand: while the MFMAs of tile i+1's
-// logits issue, the wave works through tile i's reduction, softmax and the
-// staging of later tiles in small slices pinned between the MFMAs; then, after
-// a barrier, it mixes tile i and publishes tile i+1's partial logits.
+// wave waits, so the loop is pipelined by hand, three tiles deep: while the
+// MFMAs of tile i+1's logits issue, the wave works through tile i's reduction
+// and softmax, tile i-1's mixing MFMAs and the staging of later tiles, all cut
+// into small slices pinned between the logit MFMAs (loads are issued a few
+// steps before they are consumed).  Per tile there is one full barrier and one
+// light one that only orders the reuse of the partial-logit buffer.
 //
 // Shapes taken: head_dim = C = 128, bf16, conv_in = 0, norm = 0 (softmax),
 // M a multiple of BM; any T (tail positions are masked), any m.
+#include <type_traits>
+
 #include "lococo_internal.h"
 
 namespace lococo {
@@ -68,14 +72,15 @@ struct Geo {
   static constexpr int VBYTES = BN * VSTRIDE;
   static constexpr int SBYTES = 4 * BM * SSTRIDE * 4;
   static constexpr int PBYTES = BM * PSTRIDE;
-  static constexpr int NXBUF = 3, NVBUF = 2;
-  static constexpr int LDS = NXBUF * XBYTES + NVBUF * VBYTES + SBYTES + PBYTES + 2 * BM * 4 + 16;
+  static constexpr int NXBUF = 4, NVBUF = 2;           // key tiles i-1 .. i+2, value tiles i-1, i
+  static constexpr int LDS = NXBUF * XBYTES + NVBUF * VBYTES + SBYTES + 2 * PBYTES + 3 * BM * 4 + 32;
   static constexpr int RPW = BM / 4;                 // slots a wave owns in the softmax phase
   static constexpr int LPR = 64 / RPW;               // lanes per slot there
   static constexpr int EPL = BN / LPR;               // positions per lane there
   static_assert(BM == 32 || BM == 64, "BM");
   static_assert(EPL % 4 == 0, "softmax lanes read whole float4s");
   static_assert(NS >= 26, "the slices of the pipelined loop are laid out over 26 contraction steps");
+  static_assert(LDS <= 160 * 1024, "LDS budget");
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
@@ -83,6 +88,29 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   a += 0x7fffu + ((a >> 16) & 1u);   // RNE; inputs here are finite
   b += 0x7fffu + ((b >> 16) & 1u);
   return (a >> 16) | (b & 0xffff0000u);
+}
+
+// Cross-lane exchange inside groups of 4 / 8 lanes on the VALU (DPP), no LDS round trip.
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7 - i within 8 lanes
+template <int LPR>
+__device__ __forceinline__ float group_max(float v) {
+  v = fmaxf(v, dpp<kDppXor1>(v));
+  v = fmaxf(v, dpp<kDppXor2>(v));
+  if (LPR == 8) v = fmaxf(v, dpp<kDppHalfMirror>(v));
+  return v;
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp<kDppXor1>(v);
+  v += dpp<kDppXor2>(v);
+  if (LPR == 8) v += dpp<kDppHalfMirror>(v);
+  return v;
 }
 
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s supplies the
@@ -120,10 +148,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   unsigned char* Xs0 = smem;                                    // NXBUF key tiles (with halo)
   unsigned char* Vs0 = Xs0 + G::NXBUF * G::XBYTES;              // NVBUF value tiles
   float* Sred = (float*)(Vs0 + G::NVBUF * G::VBYTES);           // 4 partial-logit tiles [wave][slot][pos]
-  unsigned char* Ps = (unsigned char*)Sred + G::SBYTES;         // probabilities [slot][pos], bf16
-  float* alphas = (float*)(Ps + G::PBYTES);                     // rescale factor per slot
-  float* lsum = alphas + BM;                                    // final row sums
-  int* rescale_flag = (int*)(lsum + BM);                        // one word per wave
+  unsigned char* Ps0 = (unsigned char*)Sred + G::SBYTES;        // 2 probability tiles [slot][pos], bf16
+  float* alphas0 = (float*)(Ps0 + 2 * G::PBYTES);               // 2 x rescale factor per slot
+  float* lsum = alphas0 + 2 * BM;                               // final row sums
+  int* flags0 = (int*)(lsum + BM);                              // 2 x one word per wave
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
   const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
@@ -189,35 +217,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = mask16(vreg[it], j0 + (item >> 4) < T);
   };
 
-  // Logit tile of positions [j0, j0+32) x this workgroup's slots, summed over this wave's channel
-  // quarter: sacc[rt] lane = slot rt*32 + l31, rows = positions (i/4)*8 + lh*4 + i%4.
-  // `slice(st)` is called once after the MFMAs of contraction step st.
+  // Partial logits of one tile, summed over this wave's channel quarter:
+  // sacc[rt] lane = slot rt*32 + l31, rows = positions (i/4)*8 + lh*4 + i%4.
   f32x16 sacc[G::RT];
-  auto conv_tile = [&](const unsigned char* Xs, auto&& slice) {
-    constexpr int kRing = 4;                   // key operands are fetched kRing-1 steps ahead
-    bf16x8 xv[kRing];
-    const unsigned char* xbase = Xs + l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
-    auto fetch = [&](int st) {
-      xv[st % kRing] = *(const bf16x8*)(xbase + (st >> 1) * G::XSTRIDE + (st & 1) * 32);
-    };
-#pragma unroll
-    for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[rt][i] = 0.f;
-#pragma unroll
-    for (int st = 0; st < kRing - 1; ++st) fetch(st);
-#pragma unroll
-    for (int st = 0; st < G::NS; ++st) {
-      if (st + kRing - 1 < G::NS) fetch(st + kRing - 1);
-#pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt)
-        sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
-                                                           sacc[rt], 0, 0, 0);
-      slice(st);
-      __builtin_amdgcn_sched_barrier(0);       // pin the order: fetch-ahead, MFMAs, this step's slice
-    }
-  };
-  // Publish this wave's partial logits: 16-byte stores, 4 consecutive positions of one slot each.
+  // Publish them: 16-byte stores, 4 consecutive positions of one slot each.
   auto write_partials = [&]() {
 #pragma unroll
     for (int rt = 0; rt < G::RT; ++rt)
@@ -228,148 +231,203 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       }
   };
 
-  // ---- Eq. 6 for one tile in slices: sum the four partials, online softmax with a lazy reference
-  float sv[G::EPL];
-  float mx, m_new, alpha, psum;
-  bool bump;
-  auto sm_read = [&](int ww, bool first) {
-#pragma unroll
-    for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
-      const f32x4 v = *(const f32x4*)(Sred + (ww * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) sv[e4 * 4 + e] = (first ? bias : sv[e4 * 4 + e]) + v[e];
-    }
-  };
-  auto sm_max = [&](int j0) {
-    if (j0 + BN > T) {                         // tail tile: positions past T carry no weight
-#pragma unroll
-      for (int e = 0; e < G::EPL; ++e)
-        if (j0 + sp0 + e >= T) sv[e] = -INFINITY;
-    }
-    mx = sv[0];
-#pragma unroll
-    for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
-#pragma unroll
-    for (int o = 1; o < G::LPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-    // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref) stays
-    // below e^kLazy and the accumulators are rescaled rarely.  Every tile has a position < T,
-    // so mx is finite.
-    bump = mx > m_run + kLazy;
-    m_new = bump ? mx : m_run;
-    alpha = bump ? __expf(m_run - m_new) : 1.0f;
-  };
-  auto sm_exp = [&]() {
-    psum = 0.f;
-#pragma unroll
-    for (int e = 0; e < G::EPL; ++e) {
-      sv[e] = __expf(sv[e] - m_new);
-      psum += sv[e];
-    }
-  };
-  auto sm_finish = [&]() {
-#pragma unroll
-    for (int o = 1; o < G::LPR; o <<= 1) psum += __shfl_xor(psum, o, 64);
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    const bool any_bump = __any(bump);
-#pragma unroll
-    for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
-      u32x2 pk;
-      pk[0] = pack_bf16(sv[e4 * 4 + 0], sv[e4 * 4 + 1]);
-      pk[1] = pack_bf16(sv[e4 * 4 + 2], sv[e4 * 4 + 3]);
-      *(u32x2*)(Ps + srow * G::PSTRIDE + (sp0 + e4 * 4) * 2) = pk;
-    }
-    if ((l % G::LPR) == 0) alphas[srow] = alpha;
-    if (l == 0) rescale_flag[w] = any_bump;
-  };
+  // One pipeline stage.  With tile index i it runs, interleaved:
+  //   DoConv:    logits of tile i+1 (key tile buffer (i+1)&3) into sacc, published at the end;
+  //   DoSoftmax: reduction + softmax of tile i (partials in Sred) into Ps[i&1], alphas[i&1];
+  //              staging of key tile i+2 and value tile i;
+  //   i > 0:     mixing of tile i-1 (Ps[(i-1)&1], key tile buffer (i-1)&3, value buffer (i-1)&1).
+  // Work other than the logit MFMAs is cut into slices placed after contraction step `st`;
+  // every slice issues its loads at least two steps before the slice that consumes them.
+  auto stage = [&](int i, auto do_conv, auto do_softmax) {
+    constexpr bool DoConv = decltype(do_conv)::value, DoSoftmax = decltype(do_softmax)::value;
+    const int j0 = i * BN;
+    const unsigned char* Xnext = Xs0 + ((i + 1) & 3) * G::XBYTES;
+    const unsigned char* Xprev = Xs0 + ((i - 1) & 3) * G::XBYTES;
+    unsigned char* Xstage = Xs0 + ((i + 2) & 3) * G::XBYTES;
+    const unsigned char* Vprev = Vs0 + ((i - 1) & 1) * G::VBYTES;
+    unsigned char* Vstage = Vs0 + (i & 1) * G::VBYTES;
+    unsigned char* Pcur = Ps0 + (i & 1) * G::PBYTES;
+    const unsigned char* Pprev = Ps0 + ((i - 1) & 1) * G::PBYTES;
+    float* alpha_cur = alphas0 + (i & 1) * BM;
+    const float* alpha_prev = alphas0 + ((i - 1) & 1) * BM;
+    int* flag_cur = flags0 + (i & 1) * 4;
+    const int* flag_prev = flags0 + ((i - 1) & 1) * 4;
+    const bool do_mix = i > 0;
 
-  // ---- Eq. 4a/4b for one tile: (rarely) rescale, then oacc += [K | V]^T P^T for this wave's columns.
-  // Wave 0/1: key columns 64w.. from the key tile (skipping its halo rows); wave 2/3: value columns.
-  auto mix_tile = [&](const unsigned char* Xs, const unsigned char* Vs) {
-    if (rescale_flag[0] | rescale_flag[1] | rescale_flag[2] | rescale_flag[3]) {
+    // logits: key operands are fetched kRing-1 steps ahead of their MFMAs
+    constexpr int kRing = 4;
+    bf16x8 xv[kRing];
+    const unsigned char* xbase = Xnext + l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
+    auto fetch = [&](int st) {
+      xv[st % kRing] = *(const bf16x8*)(xbase + (st >> 1) * G::XSTRIDE + (st & 1) * 32);
+    };
+    // softmax of tile i
+    f32x4 part[2][G::EPL / 4];
+    float sv[G::EPL];
+    float mx = 0.f, m_new = 0.f, alpha = 1.f, psum = 0.f;
+    bool bump = false;
+    auto sm_issue = [&](int ww0) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int e4 = 0; e4 < G::EPL / 4; ++e4)
+          part[q][e4] = *(const f32x4*)(Sred + ((ww0 + q) * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
+    };
+    auto sm_add = [&](bool first) {
+#pragma unroll
+      for (int e4 = 0; e4 < G::EPL / 4; ++e4)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          sv[e4 * 4 + e] = (first ? bias : sv[e4 * 4 + e]) + part[0][e4][e] + part[1][e4][e];
+    };
+    // mixing of tile i-1: operand fragments, fetched two steps ahead
+    const int s16 = l & 15, g2 = (l >> 4) & 1;
+    const unsigned char* ybase =
+        (w < 2 ? Xprev + (G::PAD + lh * 8 + (s16 >> 2)) * G::XSTRIDE + (64 * w) * 2
+               : Vprev + (lh * 8 + (s16 >> 2)) * G::VSTRIDE + (64 * (w - 2)) * 2) +
+        (16 * g2 + 4 * (s16 & 3)) * 2;
+    const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
+    bf16x8 pv[G::RT];
+    s16x4 y0, y1;
+    auto mix_fetch_p = [&](int ks) {
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt)
+        pv[rt] = *(const bf16x8*)(Pprev + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
+    };
+    auto mix_fetch_y = [&](int ks, int ct) {
+      const unsigned char* yp = ybase + (ks * 16) * ystride + (ct * 32) * 2;
+      y0 = lds_read_tr(yp);
+      y1 = lds_read_tr(yp + 4 * ystride);
+    };
+    auto mix_mfma = [&](int ct) {
+      const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+      const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt)
+        oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[rt], oacc[ct][rt], 0, 0, 0);
+    };
+
+    if (DoConv) {
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) sacc[rt][q] = 0.f;
+#pragma unroll
+      for (int st = 0; st < kRing - 1; ++st) fetch(st);
+    }
+    // (rarely) rescale the accumulators for tile i-1 before its first mixing MFMA
+    if (do_mix && (flag_prev[0] | flag_prev[1] | flag_prev[2] | flag_prev[3])) {
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt) {
-        const float al = alphas[rt * 32 + l31];
+        const float al = alpha_prev[rt * 32 + l31];
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[ct][rt][i] *= al;
+          for (int q = 0; q < 16; ++q) oacc[ct][rt][q] *= al;
       }
     }
-    const int s16 = l & 15, g2 = (l >> 4) & 1;
-    const unsigned char* ybase =
-        (w < 2 ? Xs + (G::PAD + lh * 8 + (s16 >> 2)) * G::XSTRIDE + (64 * w) * 2
-               : Vs + (lh * 8 + (s16 >> 2)) * G::VSTRIDE + (64 * (w - 2)) * 2) +
-        (16 * g2 + 4 * (s16 & 3)) * 2;
-    const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
+    __builtin_amdgcn_sched_barrier(0);
+
 #pragma unroll
-    for (int ks = 0; ks < BN / 16; ++ks) {
-      bf16x8 pv[G::RT];
-#pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt)
-        pv[rt] = *(const bf16x8*)(Ps + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const unsigned char* yp = ybase + (ks * 16) * ystride + (ct * 32) * 2;
-        const s16x4 y0 = lds_read_tr(yp);
-        const s16x4 y1 = lds_read_tr(yp + 4 * ystride);
-        const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
-        const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
+    for (int st = 0; st < G::NS; ++st) {
+      if (DoConv) {
+        if (st + kRing - 1 < G::NS) fetch(st + kRing - 1);
 #pragma unroll
         for (int rt = 0; rt < G::RT; ++rt)
-          oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[rt], oacc[ct][rt], 0, 0, 0);
+          sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
+                                                             sacc[rt], 0, 0, 0);
       }
+      if (DoSoftmax) {
+        // staging loads first: they have the longest latency
+        if (st < G::XPER) load_x(st, j0 + 2 * BN);
+        else if (st < G::XPER + G::VPER) load_v(st - G::XPER, j0);
+        if (st == 0) sm_issue(0);
+        if (st == 2) { sm_add(true); sm_issue(2); }
+        if (st == 4) sm_add(false);
+        // all lanes have consumed this tile's partial logits: the buffer may be rewritten after
+        // this point (it is, at the end of the stage).  No memory fence is needed for that.
+        if (st == 5) __builtin_amdgcn_s_barrier();
+        if (st == 6) {
+          if (j0 + BN > T) {                   // tail tile: positions past T carry no weight
+#pragma unroll
+            for (int e = 0; e < G::EPL; ++e)
+              if (j0 + sp0 + e >= T) sv[e] = -INFINITY;
+          }
+          mx = sv[0];
+#pragma unroll
+          for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
+        }
+        if (st == 7) {
+          mx = group_max<G::LPR>(mx);
+          // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref)
+          // stays below e^kLazy and the accumulators are rescaled rarely.  Every tile has a
+          // position < T, so mx is finite.
+          bump = mx > m_run + kLazy;
+          m_new = bump ? mx : m_run;
+          alpha = bump ? __expf(m_run - m_new) : 1.0f;
+        }
+        if (st == 8 || st == 9) {
+          constexpr int H = G::EPL / 2;
+          const int e0 = (st - 8) * H;
+#pragma unroll
+          for (int e = 0; e < H; ++e) {
+            sv[e0 + e] = __expf(sv[e0 + e] - m_new);
+            psum += sv[e0 + e];
+          }
+        }
+        if (st == 10) {
+          psum = group_sum<G::LPR>(psum);
+          l_run = l_run * alpha + psum;
+          m_run = m_new;
+        }
+        if (st == 11) {
+          const bool any_bump = __any(bump);
+#pragma unroll
+          for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
+            u32x2 pk;
+            pk[0] = pack_bf16(sv[e4 * 4 + 0], sv[e4 * 4 + 1]);
+            pk[1] = pack_bf16(sv[e4 * 4 + 2], sv[e4 * 4 + 3]);
+            *(u32x2*)(Pcur + srow * G::PSTRIDE + (sp0 + e4 * 4) * 2) = pk;
+          }
+          if ((l % G::LPR) == 0) alpha_cur[srow] = alpha;
+          if (l == 0) flag_cur[w] = any_bump;
+        }
+        if (st >= 20 && st < 20 + G::XPER) store_x(st - 20, j0 + 2 * BN, Xstage);
+        if (st >= 20 + G::XPER && st < 20 + G::XPER + G::VPER) store_v(st - 20 - G::XPER, j0, Vstage);
+      }
+      if (do_mix) {
+        // (ks, ct) groups at steps 12..19: fetch two steps ahead of the MFMAs
+        if (st == 10) { mix_fetch_p(0); mix_fetch_y(0, 0); }
+        if (st == 12) mix_mfma(0);
+        if (st == 12) mix_fetch_y(0, 1);
+        if (st == 14) mix_mfma(1);
+        if (st == 14) { mix_fetch_p(1); mix_fetch_y(1, 0); }
+        if (st == 16) mix_mfma(0);
+        if (st == 16) mix_fetch_y(1, 1);
+        if (st == 18) mix_mfma(1);
+      }
+      __builtin_amdgcn_sched_barrier(0);       // pin the order: fetch-ahead, MFMAs, this step's slices
     }
+    if (DoConv) write_partials();
+    __syncthreads();
   };
 
-  // ---- prologue: tiles 0 and 1 staged, logits of tile 0 published
+  // ---- prologue: key tiles 0 and 1 staged, partial logits of tile 0 published
 #pragma unroll
   for (int it = 0; it < G::XPER; ++it) load_x(it, 0);
 #pragma unroll
-  for (int it = 0; it < G::VPER; ++it) load_v(it, 0);
-#pragma unroll
   for (int it = 0; it < G::XPER; ++it) store_x(it, 0, Xs0);
-#pragma unroll
-  for (int it = 0; it < G::VPER; ++it) store_v(it, 0, Vs0);
 #pragma unroll
   for (int it = 0; it < G::XPER; ++it) load_x(it, BN);
 #pragma unroll
   for (int it = 0; it < G::XPER; ++it) store_x(it, BN, Xs0 + G::XBYTES);
   __syncthreads();
-  conv_tile(Xs0, [](int) {});
-  write_partials();
-  __syncthreads();
+  stage(-1, std::true_type{}, std::false_type{});     // logits of tile 0 only
 
-  // ---- main loop.  Iteration i: [logits of tile i+1 | reduce + softmax of tile i | staging of
-  // key tile i+2 and value tile i+1] barrier [mix tile i | publish partial logits of tile i+1] barrier
-  for (int i = 0; i < NT; ++i) {
-    const int j0 = i * BN;
-    unsigned char* Xcur = Xs0 + (i % G::NXBUF) * G::XBYTES;
-    unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
-    unsigned char* Xstage = Xs0 + ((i + 2) % G::NXBUF) * G::XBYTES;
-    unsigned char* Vcur = Vs0 + (i % G::NVBUF) * G::VBYTES;
-    unsigned char* Vstage = Vs0 + ((i + 1) % G::NVBUF) * G::VBYTES;
-
-    // The tile after the last one holds only masked (zero) keys; its logits are never used.
-    conv_tile(Xnext, [&](int st) {
-      // staging loads first (longest latency), then the softmax chain, then the LDS stores
-      if (st < G::XPER) load_x(st, j0 + 2 * BN);
-      else if (st < G::XPER + G::VPER) load_v(st - G::XPER, j0 + BN);
-      if (st == 1) sm_read(0, true);
-      if (st == 3) sm_read(1, false);
-      if (st == 5) sm_read(2, false);
-      if (st == 7) sm_read(3, false);
-      if (st == 10) sm_max(j0);
-      if (st == 13) sm_exp();
-      if (st == 16) sm_finish();
-      if (st >= 18 && st < 18 + G::XPER) store_x(st - 18, j0 + 2 * BN, Xstage);
-      if (st >= 18 + G::XPER && st < 18 + G::XPER + G::VPER) store_v(st - 18 - G::XPER, j0 + BN, Vstage);
-    });
-    __syncthreads();
-    mix_tile(Xcur, Vcur);
-    write_partials();
-    __syncthreads();
-  }
+  // ---- main loop; the last two stages have no next tile / no tile to normalise
+  for (int i = 0; i + 1 < NT; ++i) stage(i, std::true_type{}, std::true_type{});
+  stage(NT - 1, std::false_type{}, std::true_type{});
+  stage(NT, std::false_type{}, std::false_type{});
 
   // ---- normalise by the row sums and store the new cache rows, 4 columns (8 bytes) per store
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
