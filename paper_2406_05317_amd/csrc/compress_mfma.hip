@@ -177,6 +177,14 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
         for (int h = 0; h < 2; ++h)
           wreg[rt][t][h] = *(const bf16x8*)(wb + ((int64_t)(i0 + rt * 32 + l31) * KW + t) * kD +
                                             32 * w + 16 * h + lh * 8);
+    // Pin the filters to the accumulation-register half of the register file: the MFMA reads
+    // them from there directly, which leaves the other 256 registers to everything else.
+#pragma unroll
+    for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+      for (int t = 0; t < KW; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) asm volatile("" : "+a"(wreg[rt][t][h]));
   }
 
   // mixing accumulator, transposed: lane = slot rt*32 + l31, rows = columns 64w + ct*32 + (i/4)*8 + lh*4 + i%4
@@ -187,6 +195,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
+  // ... and keep the accumulators in the ordinary half (the MFMA can write either).
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+    for (int rt = 0; rt < G::RT; ++rt) asm volatile("" : "+v"(oacc[ct][rt]));
 
   // softmax state of the slot this lane helps with (replicated over the LPR lanes of the slot)
   const int srow = w * G::RPW + l / G::LPR;
@@ -312,6 +325,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
         for (int q = 0; q < 16; ++q) sacc[rt][q] = 0.f;
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt) asm volatile("" : "+v"(sacc[rt]));
 #pragma unroll
       for (int st = 0; st < kRing - 1; ++st) fetch(st);
     }
