@@ -52,6 +52,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 constexpr int kD = 128;            // head_dim = conv channels
 constexpr int kThreads = 256;
 constexpr int BN = 32;             // positions per tile
+constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.0f;      // the softmax reference lags the row maximum by at most this much
 
 template <int BM, int KW>
@@ -122,24 +123,34 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
-// 16 bytes of row p of [cache ; block] (keys or values).  Branch-free: the address is clamped
-// into [0, T) so the loads of a tile can all be in flight together; rows outside [0, T) are
-// zeroed later, when the data is written to LDS (mask16).
-__device__ __forceinline__ u32x4 load_cat16(const uint16_t* cache_rows, const uint16_t* blk_rows,
-                                            int64_t blk_st, int m, int T, int p, int chunk) {
-  const int pc = min(max(p, 0), T - 1);
-  const bool in_cache = pc < m;
-  const uint16_t* row = in_cache ? cache_rows + (int64_t)pc * kD : blk_rows + (int64_t)(pc - m) * blk_st;
-  return *(const u32x4*)(row + chunk * 8);
+// [cache ; block] rows are read through two raw buffer resources, one over the live cache rows and
+// one over the block rows.  A row index outside a resource's range (negative offsets wrap to huge
+// unsigned ones) reads as zero without touching memory, so OR-ing the two loads yields row p of the
+// concatenation for 0 <= p < T and zeros elsewhere: no clamps, no selects, no masks.
+struct CatRows {
+  __amdgpu_buffer_rsrc_t cache, blk;
+  int m;            // rows in the cache part
+  int blk_stride;   // bytes between block rows
+};
+__device__ __forceinline__ CatRows make_cat(const uint16_t* cache_rows, int m, const uint16_t* blk_rows,
+                                            int64_t blk_st, int Bn) {
+  CatRows c;
+  c.cache = __builtin_amdgcn_make_buffer_rsrc((void*)cache_rows, 0, m * kD * 2, 0x00020000);
+  c.blk = __builtin_amdgcn_make_buffer_rsrc((void*)blk_rows, 0, (int)((Bn - 1) * blk_st + kD) * 2,
+                                            0x00020000);
+  c.m = m;
+  c.blk_stride = (int)blk_st * 2;
+  return c;
+}
+__device__ __forceinline__ u32x4 load_cat16(const CatRows& c, int p, int chunk) {
+  const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, 0);
+  const u32x4 b = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
+  return a | b;
 }
 
-__device__ __forceinline__ u32x4 mask16(u32x4 v, bool keep_it) {
-  const uint32_t keep = keep_it ? 0xffffffffu : 0u;
-  v[0] &= keep; v[1] &= keep; v[2] &= keep; v[3] &= keep;
-  return v;
-}
-
-// wp: filters repacked as [bank][M][KW][C] bf16.
+// wp: filters repacked in register order, [bank][M/32][wave][tap][half][lane] x 8 channels: lane l of
+// wave w holds slot (32-slot tile)*32 + l%32, channels 32w + 16*half + 8*(l/32) .. +7, so that every
+// load instruction of the prologue reads 1 KB of contiguous memory.
 template <int BM, int KW>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
@@ -159,10 +170,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   const int T = a.m + a.Bn, m = a.m;
   const int NT = (T + BN - 1) / BN;
 
-  const uint16_t* cache_k = (const uint16_t*)a.cache_k + (int64_t)ch * a.M * kD;
-  const uint16_t* cache_v = (const uint16_t*)a.cache_v + (int64_t)ch * a.M * kD;
-  const uint16_t* blk_k = (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh;
-  const uint16_t* blk_v = (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh;
+  const CatRows cat_k = make_cat((const uint16_t*)a.cache_k + (int64_t)ch * a.M * kD, m,
+                                 (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh, a.k.st, a.Bn);
+  const CatRows cat_v = make_cat((const uint16_t*)a.cache_v + (int64_t)ch * a.M * kD, m,
+                                 (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh, a.v.st, a.Bn);
 
   // ---- this wave's slice of the filter bank, resident in registers for the whole kernel:
   // lane (slot l31 of tile rt, channels 32w + 16h + 8*lh ..) for every tap
@@ -175,8 +186,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       for (int t = 0; t < KW; ++t)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-          wreg[rt][t][h] = *(const bf16x8*)(wb + ((int64_t)(i0 + rt * 32 + l31) * KW + t) * kD +
-                                            32 * w + 16 * h + lh * 8);
+          wreg[rt][t][h] =
+              *(const bf16x8*)(wb + ((((int64_t)(i0 / 32 + rt) * 4 + w) * KW + t) * 2 + h) * 512 + l * 8);
     // Pin the filters to the accumulation-register half of the register file: the MFMA reads
     // them from there directly, which leaves the other 256 registers to everything else.
 #pragma unroll
@@ -214,20 +225,21 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   u32x4 vreg[G::VPER];
   auto load_x = [&](int it, int j0) {
     const int item = tid + it * kThreads;
-    xreg[it] = load_cat16(cache_k, blk_k, a.k.st, m, T, j0 - G::PAD + (item >> 4), item & 15);
+    xreg[it] = load_cat16(cat_k, j0 - G::PAD + (item >> 4), item & 15);
   };
   auto load_v = [&](int it, int j0) {
     const int item = tid + it * kThreads;
-    vreg[it] = load_cat16(cache_v, blk_v, a.v.st, m, T, j0 + (item >> 4), item & 15);
+    vreg[it] = load_cat16(cat_v, j0 + (item >> 4), item & 15);
   };
   auto store_x = [&](int it, int j0, unsigned char* Xs) {
     const int item = tid + it * kThreads;
-    const int r = item >> 4, p = j0 - G::PAD + r;
-    *(u32x4*)(Xs + r * G::XSTRIDE + (item & 15) * 16) = mask16(xreg[it], p >= 0 && p < T);
+    (void)j0;
+    *(u32x4*)(Xs + (item >> 4) * G::XSTRIDE + (item & 15) * 16) = xreg[it];
   };
   auto store_v = [&](int it, int j0, unsigned char* Vs) {
     const int item = tid + it * kThreads;
-    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = mask16(vreg[it], j0 + (item >> 4) < T);
+    (void)j0;
+    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it];
   };
 
   // Partial logits of one tile, summed over this wave's channel quarter:
@@ -300,33 +312,28 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
                : Vprev + (lh * 8 + (s16 >> 2)) * G::VSTRIDE + (64 * (w - 2)) * 2) +
         (16 * g2 + 4 * (s16 & 3)) * 2;
     const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
-    bf16x8 pv[G::RT];
-    s16x4 y0, y1;
+    bf16x8 pv[2][G::RT];
+    s16x4 y0[2][2], y1[2][2];
     auto mix_fetch_p = [&](int ks) {
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt)
-        pv[rt] = *(const bf16x8*)(Pprev + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
+        pv[ks][rt] = *(const bf16x8*)(Pprev + (rt * 32 + l31) * G::PSTRIDE + (ks * 16 + lh * 8) * 2);
     };
     auto mix_fetch_y = [&](int ks, int ct) {
       const unsigned char* yp = ybase + (ks * 16) * ystride + (ct * 32) * 2;
-      y0 = lds_read_tr(yp);
-      y1 = lds_read_tr(yp + 4 * ystride);
+      y0[ks][ct] = lds_read_tr(yp);
+      y1[ks][ct] = lds_read_tr(yp + 4 * ystride);
     };
-    auto mix_mfma = [&](int ct) {
-      const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+    auto mix_mfma = [&](int ks, int ct) {
+      const s16x4 a0 = y0[ks][ct], a1 = y1[ks][ct];
+      const s16x8 yy = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
       const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt)
-        oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[rt], oacc[ct][rt], 0, 0, 0);
+        oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[ks][rt], oacc[ct][rt], 0, 0, 0);
     };
 
     if (DoConv) {
-#pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) sacc[rt][q] = 0.f;
-#pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt) asm volatile("" : "+v"(sacc[rt]));
 #pragma unroll
       for (int st = 0; st < kRing - 1; ++st) fetch(st);
     }
@@ -347,10 +354,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     for (int st = 0; st < G::NS; ++st) {
       if (DoConv) {
         if (st + kRing - 1 < G::NS) fetch(st + kRing - 1);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int rt = 0; rt < G::RT; ++rt)
           sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
-                                                             sacc[rt], 0, 0, 0);
+                                                             st == 0 ? zero : sacc[rt], 0, 0, 0);
       }
       if (DoSoftmax) {
         // staging loads first: they have the longest latency
@@ -386,7 +394,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           const int e0 = (st - 8) * H;
 #pragma unroll
           for (int e = 0; e < H; ++e) {
-            sv[e0 + e] = __expf(sv[e0 + e] - m_new);
+            sv[e0 + e] = __builtin_amdgcn_exp2f(fmaf(sv[e0 + e], kLog2e, -m_new * kLog2e));
             psum += sv[e0 + e];
           }
         }
@@ -411,19 +419,18 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
         if (st >= 20 + G::XPER && st < 20 + G::XPER + G::VPER) store_v(st - 20 - G::XPER, j0, Vstage);
       }
       if (do_mix) {
-        // (ks, ct) groups at steps 12..19: fetch two steps ahead of the MFMAs
-        if (st == 10) { mix_fetch_p(0); mix_fetch_y(0, 0); }
-        if (st == 12) mix_mfma(0);
-        if (st == 12) mix_fetch_y(0, 1);
-        if (st == 14) mix_mfma(1);
-        if (st == 14) { mix_fetch_p(1); mix_fetch_y(1, 0); }
-        if (st == 16) mix_mfma(0);
-        if (st == 16) mix_fetch_y(1, 1);
-        if (st == 18) mix_mfma(1);
+        // operand fragments of tile i-1's mixing, fetched well ahead of the MFMAs after the loop
+        if (st == 22) { mix_fetch_p(0); mix_fetch_p(1); }
+        if (st == 24) { mix_fetch_y(0, 0); mix_fetch_y(0, 1); }
+        if (st == 26) { mix_fetch_y(1, 0); mix_fetch_y(1, 1); }
       }
       __builtin_amdgcn_sched_barrier(0);       // pin the order: fetch-ahead, MFMAs, this step's slices
     }
+    // Mixing MFMAs of tile i-1 run while the last logit MFMAs drain; the partial logits are
+    // published in between.
+    if (do_mix) { mix_mfma(0, 0); mix_mfma(0, 1); }
     if (DoConv) write_partials();
+    if (do_mix) { mix_mfma(1, 0); mix_mfma(1, 1); }
     __syncthreads();
   };
 
@@ -466,16 +473,23 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   }
 }
 
-// [M][C][k] -> [M][k][C] per bank, so that 8 consecutive channels of one tap are 16 contiguous bytes.
+// [M][C][k] per bank -> register order (see compress_mfma_k); one thread per 16-byte chunk.
 __global__ void repack_filters_k(const uint16_t* w, uint16_t* wp, int M, int C, int KW, int banks,
                                  int64_t w_head_stride) {
-  const int64_t per = (int64_t)M * C * KW;
-  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < per * banks;
+  const int64_t chunks_per_bank = (int64_t)M * KW * (C / 8);
+  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < chunks_per_bank * banks;
        e += (int64_t)gridDim.x * blockDim.x) {
-    const int bank = (int)(e / per);
-    const int64_t r = e % per;
-    const int c = (int)(r % C), t = (int)((r / C) % KW), i = (int)(r / ((int64_t)C * KW));
-    wp[e] = w[bank * w_head_stride + ((int64_t)i * C + c) * KW + t];
+    const int bank = (int)(e / chunks_per_bank);
+    int64_t r = e % chunks_per_bank;
+    const int lane = (int)(r % 64); r /= 64;
+    const int h = (int)(r % 2); r /= 2;
+    const int t = (int)(r % KW); r /= KW;
+    const int wv = (int)(r % 4); r /= 4;
+    const int slot = (int)r * 32 + (lane & 31);
+    const int c0 = 32 * wv + 16 * h + (lane >> 5) * 8;
+    const uint16_t* src = w + bank * w_head_stride + ((int64_t)slot * C + c0) * KW + t;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) wp[e * 8 + q] = src[(int64_t)q * KW];
   }
 }
 
@@ -512,7 +526,7 @@ size_t compress_mfma_filter_bytes(int M, int conv_width, int banks) {
 }
 
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s) {
-  const int64_t n = (int64_t)banks * a.M * kD * a.k_width;
+  const int64_t n = (int64_t)banks * a.M * (kD / 8) * a.k_width;   // 16-byte chunks
   int blocks = (int)((n + 255) / 256);
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(repack_filters_k, dim3(blocks), dim3(256), 0, s, (const uint16_t*)a.conv_w,
