@@ -74,7 +74,7 @@ struct Geo {
   static constexpr int SBYTES = 4 * BM * SSTRIDE * 4;
   static constexpr int PBYTES = BM * PSTRIDE;
   static constexpr int NXBUF = 4, NVBUF = 2;           // key tiles i-1 .. i+2, value tiles i-1, i
-  static constexpr int LDS = NXBUF * XBYTES + NVBUF * VBYTES + SBYTES + 2 * PBYTES + 3 * BM * 4 + 32;
+  static constexpr int LDS = NXBUF * XBYTES + NVBUF * VBYTES + SBYTES + 2 * PBYTES + 3 * BM * 4;
   static constexpr int RPW = BM / 4;                 // slots a wave owns in the softmax phase
   static constexpr int LPR = 64 / RPW;               // lanes per slot there
   static constexpr int EPL = BN / LPR;               // positions per lane there
@@ -142,10 +142,13 @@ __device__ __forceinline__ CatRows make_cat(const uint16_t* cache_rows, int m, c
   c.blk_stride = (int)blk_st * 2;
   return c;
 }
-__device__ __forceinline__ u32x4 load_cat16(const CatRows& c, int p, int chunk) {
-  const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, 0);
-  const u32x4 b = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
-  return a | b;
+// The two halves are OR-ed only when the data is stored to LDS, many steps after the loads were issued.
+struct Cat16 { u32x4 from_cache, from_blk; };
+__device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) {
+  Cat16 r;
+  r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, 0);
+  r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
+  return r;
 }
 
 // wp: filters repacked in register order, [bank][M/32][wave][tap][half][lane] x 8 channels: lane l of
@@ -162,7 +165,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   unsigned char* Ps0 = (unsigned char*)Sred + G::SBYTES;        // 2 probability tiles [slot][pos], bf16
   float* alphas0 = (float*)(Ps0 + 2 * G::PBYTES);               // 2 x rescale factor per slot
   float* lsum = alphas0 + 2 * BM;                               // final row sums
-  int* flags0 = (int*)(lsum + BM);                              // 2 x one word per wave
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
   const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
@@ -221,8 +223,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
                : 0.f;
 
   // ---- staging: global -> registers -> LDS (key tile with halo, value tile; both row-major)
-  u32x4 xreg[G::XPER];
-  u32x4 vreg[G::VPER];
+  Cat16 xreg[G::XPER];
+  Cat16 vreg[G::VPER];
   auto load_x = [&](int it, int j0) {
     const int item = tid + it * kThreads;
     xreg[it] = load_cat16(cat_k, j0 - G::PAD + (item >> 4), item & 15);
@@ -234,12 +236,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   auto store_x = [&](int it, int j0, unsigned char* Xs) {
     const int item = tid + it * kThreads;
     (void)j0;
-    *(u32x4*)(Xs + (item >> 4) * G::XSTRIDE + (item & 15) * 16) = xreg[it];
+    *(u32x4*)(Xs + (item >> 4) * G::XSTRIDE + (item & 15) * 16) = xreg[it].from_cache | xreg[it].from_blk;
   };
   auto store_v = [&](int it, int j0, unsigned char* Vs) {
     const int item = tid + it * kThreads;
     (void)j0;
-    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it];
+    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it].from_cache | vreg[it].from_blk;
   };
 
   // Partial logits of one tile, summed over this wave's channel quarter:
@@ -263,8 +265,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   //   i > 0:     mixing of tile i-1 (Ps[(i-1)&1], key tile buffer (i-1)&3, value buffer (i-1)&1).
   // Work other than the logit MFMAs is cut into slices placed after contraction step `st`;
   // every slice issues its loads at least two steps before the slice that consumes them.
-  auto stage = [&](int i, auto do_conv, auto do_softmax) {
+  auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t) {
     constexpr bool DoConv = decltype(do_conv)::value, DoSoftmax = decltype(do_softmax)::value;
+    constexpr bool do_mix = decltype(do_mix_t)::value;
     const int j0 = i * BN;
     const unsigned char* Xnext = Xs0 + ((i + 1) & 3) * G::XBYTES;
     const unsigned char* Xprev = Xs0 + ((i - 1) & 3) * G::XBYTES;
@@ -275,9 +278,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     const unsigned char* Pprev = Ps0 + ((i - 1) & 1) * G::PBYTES;
     float* alpha_cur = alphas0 + (i & 1) * BM;
     const float* alpha_prev = alphas0 + ((i - 1) & 1) * BM;
-    int* flag_cur = flags0 + (i & 1) * 4;
-    const int* flag_prev = flags0 + ((i - 1) & 1) * 4;
-    const bool do_mix = i > 0;
 
     // logits: key operands are fetched kRing-1 steps ahead of their MFMAs
     constexpr int kRing = 4;
@@ -337,16 +337,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
       for (int st = 0; st < kRing - 1; ++st) fetch(st);
     }
-    // (rarely) rescale the accumulators for tile i-1 before its first mixing MFMA
-    if (do_mix && (flag_prev[0] | flag_prev[1] | flag_prev[2] | flag_prev[3])) {
+    // rescale factors of tile i-1 for this lane's slots, read now and used late in the stage
+    float al[G::RT];
+    if (do_mix) {
 #pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt) {
-        const float al = alpha_prev[rt * 32 + l31];
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int q = 0; q < 16; ++q) oacc[ct][rt][q] *= al;
-      }
+      for (int rt = 0; rt < G::RT; ++rt) al[rt] = alpha_prev[rt * 32 + l31];
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -404,7 +399,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           m_run = m_new;
         }
         if (st == 11) {
-          const bool any_bump = __any(bump);
 #pragma unroll
           for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
             u32x2 pk;
@@ -413,12 +407,25 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
             *(u32x2*)(Pcur + srow * G::PSTRIDE + (sp0 + e4 * 4) * 2) = pk;
           }
           if ((l % G::LPR) == 0) alpha_cur[srow] = alpha;
-          if (l == 0) flag_cur[w] = any_bump;
         }
         if (st >= 20 && st < 20 + G::XPER) store_x(st - 20, j0 + 2 * BN, Xstage);
         if (st >= 20 + G::XPER && st < 20 + G::XPER + G::VPER) store_v(st - 20 - G::XPER, j0, Vstage);
       }
       if (do_mix) {
+        // (rarely) rescale the accumulators before tile i-1 is mixed in
+        if (st == 21) {
+          bool any = false;
+#pragma unroll
+          for (int rt = 0; rt < G::RT; ++rt) any |= al[rt] != 1.0f;
+          if (__any(any)) {
+#pragma unroll
+            for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+              for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) oacc[ct][rt][q] *= al[rt];
+          }
+        }
         // operand fragments of tile i-1's mixing, fetched well ahead of the MFMAs after the loop
         if (st == 22) { mix_fetch_p(0); mix_fetch_p(1); }
         if (st == 24) { mix_fetch_y(0, 0); mix_fetch_y(0, 1); }
@@ -444,12 +451,19 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
   for (int it = 0; it < G::XPER; ++it) store_x(it, BN, Xs0 + G::XBYTES);
   __syncthreads();
-  stage(-1, std::true_type{}, std::false_type{});     // logits of tile 0 only
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  stage(-1, yes, no, no);                              // logits of tile 0 only
 
-  // ---- main loop; the last two stages have no next tile / no tile to normalise
-  for (int i = 0; i + 1 < NT; ++i) stage(i, std::true_type{}, std::true_type{});
-  stage(NT - 1, std::false_type{}, std::true_type{});
-  stage(NT, std::false_type{}, std::false_type{});
+  // ---- pipeline fill, steady state, drain
+  if (NT > 1) {
+    stage(0, yes, yes, no);
+    for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes);
+    stage(NT - 1, no, yes, yes);
+  } else {
+    stage(0, no, yes, no);
+  }
+  stage(NT, no, no, yes);
 
   // ---- normalise by the row sums and store the new cache rows, 4 columns (8 bytes) per store
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
