@@ -29,8 +29,9 @@
 // MFMAs of tile i+1's logits issue, the wave works through tile i's reduction
 // and softmax, tile i-1's mixing MFMAs and the staging of later tiles, all cut
 // into small slices pinned between the logit MFMAs (loads are issued a few
-// steps before they are consumed).  Per tile there is one full barrier and one
-// light one that only orders the reuse of the partial-logit buffer.
+// steps before they are consumed).  The two workgroup barriers of a tile sit
+// inside that MFMA stream as well, so no barrier is waited for with the matrix
+// pipe idle.
 //
 // Shapes taken: head_dim = C = 128, bf16, conv_in = 0, norm = 0 (softmax),
 // M a multiple of BM; any T (tail positions are masked), any m.
@@ -73,7 +74,7 @@ struct Geo {
   static constexpr int VBYTES = BN * VSTRIDE;
   static constexpr int SBYTES = 4 * BM * SSTRIDE * 4;
   static constexpr int PBYTES = BM * PSTRIDE;
-  static constexpr int NXBUF = 4, NVBUF = 2;           // key tiles i-1 .. i+2, value tiles i-1, i
+  static constexpr int NXBUF = 5, NVBUF = 2;           // key tiles i-1 .. i+3, value tiles i-1, i
   static constexpr int LDS = NXBUF * XBYTES + NVBUF * VBYTES + SBYTES + 2 * PBYTES + 3 * BM * 4;
   static constexpr int RPW = BM / 4;                 // slots a wave owns in the softmax phase
   static constexpr int LPR = 64 / RPW;               // lanes per slot there
@@ -84,11 +85,11 @@ struct Geo {
   static_assert(LDS <= 160 * 1024, "LDS budget");
 };
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);   // RNE; inputs here are finite
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // v_cvt_pk_bf16_f32, RNE
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Cross-lane exchange inside groups of 4 / 8 lanes on the VALU (DPP), no LDS round trip.
@@ -259,19 +260,26 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   };
 
   // One pipeline stage.  With tile index i it runs, interleaved:
-  //   DoConv:    logits of tile i+1 (key tile buffer (i+1)&3) into sacc, published at the end;
+  //   DoConv:    logits of tile i+1 (key tile buffer (i+1)%5) into sacc, published at the end;
   //   DoSoftmax: reduction + softmax of tile i (partials in Sred) into Ps[i&1], alphas[i&1];
-  //              staging of key tile i+2 and value tile i;
-  //   i > 0:     mixing of tile i-1 (Ps[(i-1)&1], key tile buffer (i-1)&3, value buffer (i-1)&1).
-  // Work other than the logit MFMAs is cut into slices placed after contraction step `st`;
-  // every slice issues its loads at least two steps before the slice that consumes them.
+  //              staging of key tile i+3 and value tile i;
+  //   DoMix:     mixing of tile i-1 (Ps[(i-1)&1], key tile buffer (i-1)%5, value buffer (i-1)&1).
+  // Work other than the logit MFMAs is cut into slices placed after contraction step `st`; every
+  // slice issues its loads a few steps before the slice that consumes them.
+  //
+  // Barriers.  B1 (step 2) publishes what the previous stage wrote to LDS -- partial logits,
+  // probabilities, rescale factors, staged tiles -- so everything read before it (the key tile of
+  // this stage's logits) was staged two stages ago.  B2 (step 9) comes after every wave has
+  // consumed this tile's partial logits; the buffer is rewritten at the end of the stage.
+  // Neither needs outstanding global loads to finish, so they are plain barriers preceded by a
+  // wait on the LDS counter only.
   auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t) {
     constexpr bool DoConv = decltype(do_conv)::value, DoSoftmax = decltype(do_softmax)::value;
-    constexpr bool do_mix = decltype(do_mix_t)::value;
+    constexpr bool DoMix = decltype(do_mix_t)::value;
     const int j0 = i * BN;
-    const unsigned char* Xnext = Xs0 + ((i + 1) & 3) * G::XBYTES;
-    const unsigned char* Xprev = Xs0 + ((i - 1) & 3) * G::XBYTES;
-    unsigned char* Xstage = Xs0 + ((i + 2) & 3) * G::XBYTES;
+    const unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
+    const unsigned char* Xprev = Xs0 + ((i + G::NXBUF - 1) % G::NXBUF) * G::XBYTES;
+    unsigned char* Xstage = Xs0 + ((i + 3) % G::NXBUF) * G::XBYTES;
     const unsigned char* Vprev = Vs0 + ((i - 1) & 1) * G::VBYTES;
     unsigned char* Vstage = Vs0 + (i & 1) * G::VBYTES;
     unsigned char* Pcur = Ps0 + (i & 1) * G::PBYTES;
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       xv[st % kRing] = *(const bf16x8*)(xbase + (st >> 1) * G::XSTRIDE + (st & 1) * 32);
     };
     // softmax of tile i
-    f32x4 part[2][G::EPL / 4];
+    f32x4 part[4][G::EPL / 4];
     float sv[G::EPL];
     float mx = 0.f, m_new = 0.f, alpha = 1.f, psum = 0.f;
     bool bump = false;
@@ -296,16 +304,16 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int e4 = 0; e4 < G::EPL / 4; ++e4)
-          part[q][e4] = *(const f32x4*)(Sred + ((ww0 + q) * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
+          part[ww0 + q][e4] = *(const f32x4*)(Sred + ((ww0 + q) * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
     };
-    auto sm_add = [&](bool first) {
+    auto sm_add = [&](int ww0) {
 #pragma unroll
       for (int e4 = 0; e4 < G::EPL / 4; ++e4)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          sv[e4 * 4 + e] = (first ? bias : sv[e4 * 4 + e]) + part[0][e4][e] + part[1][e4][e];
+          sv[e4 * 4 + e] = (ww0 == 0 ? bias : sv[e4 * 4 + e]) + part[ww0][e4][e] + part[ww0 + 1][e4][e];
     };
-    // mixing of tile i-1: operand fragments, fetched two steps ahead
+    // mixing of tile i-1: operand fragments, fetched ahead of the MFMAs that follow the loop
     const int s16 = l & 15, g2 = (l >> 4) & 1;
     const unsigned char* ybase =
         (w < 2 ? Xprev + (G::PAD + lh * 8 + (s16 >> 2)) * G::XSTRIDE + (64 * w) * 2
@@ -314,6 +322,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     const int ystride = w < 2 ? G::XSTRIDE : G::VSTRIDE;
     bf16x8 pv[2][G::RT];
     s16x4 y0[2][2], y1[2][2];
+    float al[G::RT];
     auto mix_fetch_p = [&](int ks) {
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt)
@@ -337,12 +346,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
       for (int st = 0; st < kRing - 1; ++st) fetch(st);
     }
-    // rescale factors of tile i-1 for this lane's slots, read now and used late in the stage
-    float al[G::RT];
-    if (do_mix) {
-#pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt) al[rt] = alpha_prev[rt * 32 + l31];
-    }
     __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -355,17 +358,20 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
                                                              st == 0 ? zero : sacc[rt], 0, 0, 0);
       }
+      if (st == 2) {                           // B1
+        __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): this wave's LDS stores of the last stage landed
+        __builtin_amdgcn_s_barrier();
+      }
       if (DoSoftmax) {
-        // staging loads first: they have the longest latency
-        if (st < G::XPER) load_x(st, j0 + 2 * BN);
-        else if (st < G::XPER + G::VPER) load_v(st - G::XPER, j0);
-        if (st == 0) sm_issue(0);
-        if (st == 2) { sm_add(true); sm_issue(2); }
-        if (st == 4) sm_add(false);
-        // all lanes have consumed this tile's partial logits: the buffer may be rewritten after
-        // this point (it is, at the end of the stage).  No memory fence is needed for that.
-        if (st == 5) __builtin_amdgcn_s_barrier();
-        if (st == 6) {
+        // staging loads early: they have the longest latency
+        if (st >= 3 && st < 3 + G::XPER) load_x(st - 3, j0 + 3 * BN);
+        if (st >= 3 + G::XPER && st < 3 + G::XPER + G::VPER) load_v(st - 3 - G::XPER, j0);
+        if (st == 3) sm_issue(0);
+        if (st == 4) sm_issue(2);
+        if (st == 7) sm_add(0);
+        if (st == 8) sm_add(2);
+        if (st == 9) __builtin_amdgcn_s_barrier();   // B2: the reads above have all been consumed
+        if (st == 10) {
           if (j0 + BN > T) {                   // tail tile: positions past T carry no weight
 #pragma unroll
             for (int e = 0; e < G::EPL; ++e)
@@ -375,7 +381,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
           for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
         }
-        if (st == 7) {
+        if (st == 11) {
           mx = group_max<G::LPR>(mx);
           // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref)
           // stays below e^kLazy and the accumulators are rescaled rarely.  Every tile has a
@@ -384,21 +390,21 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           m_new = bump ? mx : m_run;
           alpha = bump ? __expf(m_run - m_new) : 1.0f;
         }
-        if (st == 8 || st == 9) {
-          constexpr int H = G::EPL / 2;
-          const int e0 = (st - 8) * H;
+        if (st >= 12 && st < 16) {
+          constexpr int Q = G::EPL / 4;
+          const int e0 = (st - 12) * Q;
 #pragma unroll
-          for (int e = 0; e < H; ++e) {
+          for (int e = 0; e < Q; ++e) {
             sv[e0 + e] = __builtin_amdgcn_exp2f(fmaf(sv[e0 + e], kLog2e, -m_new * kLog2e));
             psum += sv[e0 + e];
           }
         }
-        if (st == 10) {
+        if (st == 16) {
           psum = group_sum<G::LPR>(psum);
           l_run = l_run * alpha + psum;
           m_run = m_new;
         }
-        if (st == 11) {
+        if (st == 17) {
 #pragma unroll
           for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
             u32x2 pk;
@@ -408,10 +414,14 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           }
           if ((l % G::LPR) == 0) alpha_cur[srow] = alpha;
         }
-        if (st >= 20 && st < 20 + G::XPER) store_x(st - 20, j0 + 2 * BN, Xstage);
-        if (st >= 20 + G::XPER && st < 20 + G::XPER + G::VPER) store_v(st - 20 - G::XPER, j0, Vstage);
+        if (st >= 24 && st < 24 + G::XPER) store_x(st - 24, j0 + 3 * BN, Xstage);
+        if (st >= 24 + G::XPER && st < 24 + G::XPER + G::VPER) store_v(st - 24 - G::XPER, j0, Vstage);
       }
-      if (do_mix) {
+      if (DoMix) {
+        if (st == 18) {
+#pragma unroll
+          for (int rt = 0; rt < G::RT; ++rt) al[rt] = alpha_prev[rt * 32 + l31];
+        }
         // (rarely) rescale the accumulators before tile i-1 is mixed in
         if (st == 21) {
           bool any = false;
@@ -426,30 +436,28 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
                 for (int q = 0; q < 16; ++q) oacc[ct][rt][q] *= al[rt];
           }
         }
-        // operand fragments of tile i-1's mixing, fetched well ahead of the MFMAs after the loop
         if (st == 22) { mix_fetch_p(0); mix_fetch_p(1); }
-        if (st == 24) { mix_fetch_y(0, 0); mix_fetch_y(0, 1); }
-        if (st == 26) { mix_fetch_y(1, 0); mix_fetch_y(1, 1); }
+        if (st == 23) { mix_fetch_y(0, 0); mix_fetch_y(0, 1); }
+        if (st == 25) { mix_fetch_y(1, 0); mix_fetch_y(1, 1); }
       }
       __builtin_amdgcn_sched_barrier(0);       // pin the order: fetch-ahead, MFMAs, this step's slices
     }
     // Mixing MFMAs of tile i-1 run while the last logit MFMAs drain; the partial logits are
-    // published in between.
-    if (do_mix) { mix_mfma(0, 0); mix_mfma(0, 1); }
+    // published in between.  The next stage's B1 makes them visible.
+    if (DoMix) { mix_mfma(0, 0); mix_mfma(0, 1); }
     if (DoConv) write_partials();
-    if (do_mix) { mix_mfma(1, 0); mix_mfma(1, 1); }
-    __syncthreads();
+    if (DoMix) { mix_mfma(1, 0); mix_mfma(1, 1); }
+    __builtin_amdgcn_sched_barrier(0);
   };
 
-  // ---- prologue: key tiles 0 and 1 staged, partial logits of tile 0 published
+  // ---- prologue: key tiles 0, 1 and 2 staged
 #pragma unroll
-  for (int it = 0; it < G::XPER; ++it) load_x(it, 0);
+  for (int t = 0; t < 3; ++t) {
 #pragma unroll
-  for (int it = 0; it < G::XPER; ++it) store_x(it, 0, Xs0);
+    for (int it = 0; it < G::XPER; ++it) load_x(it, t * BN);
 #pragma unroll
-  for (int it = 0; it < G::XPER; ++it) load_x(it, BN);
-#pragma unroll
-  for (int it = 0; it < G::XPER; ++it) store_x(it, BN, Xs0 + G::XBYTES);
+    for (int it = 0; it < G::XPER; ++it) store_x(it, t * BN, Xs0 + t * G::XBYTES);
+  }
   __syncthreads();
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
