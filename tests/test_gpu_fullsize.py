@@ -1,0 +1,87 @@
+"""GPU parity at the full sizes of the measured configurations, in the launch
+configuration bench.py times (one lococo_sequence_forward call with the
+batched-attention workspace).  The oracle is too slow for every chain of the
+large workloads, and chains are independent, so it recomputes sampled
+(batch, kv-head) chains over the whole scan; all chains are additionally
+checked on a truncated sequence in test_gpu_mfma.py-sized runs below."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lococo_oracle as orc
+from paper_2406_05317_amd import inputs
+from parity_util import TOL, assert_close, compare_scan, gpu_forward, oracle_forward, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_sampled_chains(w, chains, L=None):
+    L = L or w.L
+    q, k, v = inputs.qkv(w, L)
+    cw, cb = inputs.conv_filters(w)
+    got = gpu_forward(w, q, k, v, cw, cb, history=True)
+    o_g, ck_g, cv_g, ln_g, cur_g = got
+    plan = orc.plan(L, w.B, w.M)
+    assert ln_g == plan[-1, 4] and cur_g == plan[-1, 5]
+    g = w.group
+    tol = TOL[w.dtype]
+    for (b, h) in chains:
+        qs = q[b:b + 1, h * g:(h + 1) * g]
+        want = orc.sequence_forward(qs, k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1],
+                                    cw[h] if w.per_head_filters else cw, None, B=w.B, M=w.M,
+                                    state_round=w.dtype, nthreads=16)
+        # the sampled chain regenerated on its own equals its slab of the full tensors
+        qc, kc, vc = inputs.chain_inputs(w, b, h, L)
+        assert torch.equal(qc, qs[0]) and torch.equal(kc, k[b, h]) and torch.equal(vc, v[b, h])
+        e_o = assert_close(to_np(o_g[b, h * g:(h + 1) * g]), want[0][0], tol, f"{w.name} chain {b},{h} O")
+        e_k = assert_close(to_np(ck_g[b, h]), want[1][0, 0], tol, f"{w.name} chain {b},{h} cache K")
+        e_v = assert_close(to_np(cv_g[b, h]), want[2][0, 0], tol, f"{w.name} chain {b},{h} cache V")
+        print(w.name, "chain", (b, h), "max-rel / l2-rel:", e_o, e_k, e_v)
+    assert torch.isfinite(o_g.float()).all()
+    return got
+
+
+def test_cfg2_full_all_chains():
+    w = inputs.CFG2
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    got = gpu_forward(w, q, k, v, cw, cb, history=True)
+    print(compare_scan(w, got, want, what="cfg2"))
+
+
+def test_cfg3_full_sampled_chains():
+    """The benchmark workload: 32 chains x 64 blocks; three chains recomputed by the oracle."""
+    _check_sampled_chains(inputs.CFG3, [(0, 0), (0, 13), (0, 31)])
+
+
+def test_cfg3_all_chains_first_blocks():
+    w = inputs.CFG3
+    L = 4 * w.B
+    q, k, v = inputs.qkv(w, L)
+    cw, cb = inputs.conv_filters(w)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    got = gpu_forward(w, q, k, v, cw, cb, history=True)
+    compare_scan(w, got, want, what="cfg3 first 4 blocks")
+
+
+def test_cfg4_full_width_sampled_chains():
+    """All 512 chains, 16 of the 128 blocks (two fills + 14 compressions), per-token scales."""
+    w = inputs.CFG4
+    _check_sampled_chains(w, [(0, 0), (7, 19), (15, 31)], L=16 * w.B)
+
+
+def test_cfg5_gqa_full_sampled_chains():
+    _check_sampled_chains(inputs.CFG5, [(0, 0), (1, 7)])
+
+
+def test_results_do_not_depend_on_the_schedule_at_full_size():
+    w = inputs.CFG5
+    L = 8 * w.B
+    q, k, v = inputs.qkv(w, L)
+    cw, cb = inputs.conv_filters(w)
+    a = gpu_forward(w, q, k, v, cw, cb, history=True)
+    b = gpu_forward(w, q, k, v, cw, cb, history=False)
+    c = gpu_forward(w, q, k, v, cw, cb, history=True)
+    for x, y, z in zip(a[:3], b[:3], c[:3]):
+        assert torch.equal(x, y) and torch.equal(x, z)
