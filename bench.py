@@ -109,6 +109,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-history", action="store_true",
                     help="step-by-step schedule instead of the batched-attention one")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the warm-up, so "
+                         "that a rocprofv3 --pmc run has a kernel of known HBM traffic to scale "
+                         "FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over (batch, kv-head) chains "
@@ -136,6 +140,14 @@ def main():
         cache.c.len = 0                                  # fresh sequence (host-side state only)
         lb.lococo_sequence_forward(cfg, qd, kd, vd, od, cwd, cbd, cache, w.B, ws)
 
+    if args.calibration_copy_mib:
+        n = args.calibration_copy_mib << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                   # reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -168,8 +168,16 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   float* lsum = alphas0 + 2 * BM;                               // final row sums
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
-  const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
-  const int i0 = blockIdx.x * BM;
+  // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  The slot tiles of one chain
+  // all read the same keys and values, so they are given ids that land on one XCD (one L2).
+  int item = blockIdx.x;
+  {
+    const int per = gridDim.x / 8;
+    if (item < per * 8) item = (item % 8) * per + item / 8;
+  }
+  const int tiles = a.M / BM;
+  const int ch = item / tiles, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int i0 = (item % tiles) * BM;
   const int T = a.m + a.Bn, m = a.m;
   const int NT = (T + BN - 1) / BN;
 
@@ -525,7 +533,7 @@ hipError_t launch_one(const StepArgs& a, const uint16_t* wp, int64_t wp_head_str
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(a.M / BM, a.batch * a.Hkv);
+  dim3 grid((a.M / BM) * a.batch * a.Hkv);
   hipLaunchKernelGGL((compress_mfma_k<BM, KW>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
   return hipGetLastError();
 }
