@@ -63,6 +63,18 @@ KERNEL_BOUND = {  # roofline that bounds each kernel, peak, unit
 }
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and
+    workload (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or None."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read(), re.M)
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def cpu_baseline(w, budget_s=15.0):
     """Oracle (as it stands) on a bounded sample: `threads` chains, the first
     few blocks of the scan, scaled to tokens/s of the whole layer."""
@@ -169,7 +181,8 @@ def main():
     part_flops = sum(flops[p] for p in KERNEL_PARTS.get(name, ())) * args.steps
     achieved = part_flops / (total_ms * 1e-3) / 1e12 if total_ms > 0 else 0.0
     roofline = {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": None, "launches": launches,
+                "frac": achieved / peak, "traffic": measured_traffic(name, args.workload),
+                "launches": launches,
                 "avg_launch_us": total_ms * 1e3 / max(launches, 1),
                 "flops_per_launch": part_flops / max(launches, 1),
                 "kernel_ms_per_step": {n: kt[n][1] / args.steps for n in kt}}
