@@ -10,7 +10,8 @@
 // cross-lane exchange, the rescale factor is a per-lane scalar, and the
 // probabilities feed the second MFMA (O^T = V^T P^T) straight from registers.
 // The key order inside the second contraction is permuted the same way on
-// both operands so no shuffle is needed.
+// both operands so no shuffle is needed; the value operand is read with the
+// transposing LDS load straight from the row-major value tile.
 //
 // Keys are indexed over [cache ; block]: all m cache slots are visible, block
 // key j' is visible to block query j iff j' <= j; key tiles past a wave's
@@ -21,43 +22,64 @@ namespace lococo {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kD = 128;
 constexpr int kThreads = 256;
 constexpr int BQ = 128;                       // query rows per workgroup
 constexpr int BK = 64;                        // keys per tile
-constexpr int KSTRIDE = kD * 2 + 16;          // bytes per key-tile row
-constexpr int VSTRIDE = BK * 2 + 8;           // bytes per row of the transposed value tile
+constexpr int KSTRIDE = kD * 2 + 16;          // bytes per key-tile row (conflict-free 16-byte reads)
+constexpr int VSTRIDE = kD * 2 + 64;          // bytes per value-tile row (conflict-free transposing reads)
 constexpr int KBYTES = BK * KSTRIDE;
-constexpr int VBYTES = kD * VSTRIDE;
+constexpr int VBYTES = BK * VSTRIDE;
 constexpr int LDS_BYTES = 2 * (KBYTES + VBYTES);
-constexpr int KPER = BK * 16 / kThreads;      // 16-byte chunks of the key tile per thread
-constexpr int VPER = (BK / 2) * 16 / kThreads;  // (key pair, chunk) items of the value tile per thread
+constexpr int PER = BK * 16 / kThreads;       // 16-byte chunks of a key (or value) tile per thread
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazy = 8.0f;                 // the softmax reference lags the row maximum by at most this much
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // v_cvt_pk_bf16_f32, RNE
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// 16 bytes of row j of [cache ; block].  Branch-free (address clamped below T) so that all loads
-// of a tile are in flight together; rows j >= T are zeroed when written to LDS (mask16).
-__device__ __forceinline__ u32x4 load_cat16(const uint16_t* cache_rows, const uint16_t* blk_rows,
-                                            int64_t blk_st, int m, int T, int j, int chunk) {
-  const int jc = min(j, T - 1);
-  const bool in_cache = jc < m;
-  const uint16_t* row = in_cache ? cache_rows + (int64_t)jc * kD : blk_rows + (int64_t)(jc - m) * blk_st;
-  return *(const u32x4*)(row + chunk * 8);
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s supplies the
+// address of 4 consecutive 16-bit elements; lane i of the group receives element (i % 4) of the
+// chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane s pointing at
+// (row r0 + s/4, column c0 + 4*(s%4)) of a row-major tile, lane i ends up with column c0 + i of
+// rows r0 .. r0+3: an operand fragment (column, 4 contraction rows) straight from a row-major tile.
+__device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
-__device__ __forceinline__ u32x4 mask16(u32x4 v, bool keep_it) {
-  const uint32_t keep = keep_it ? 0xffffffffu : 0u;
-  v[0] &= keep; v[1] &= keep; v[2] &= keep; v[3] &= keep;
-  return v;
+// [cache ; block] rows through two raw buffer resources: an index outside a resource's range reads
+// as zero without touching memory, so OR-ing the two loads gives row j of the concatenation for
+// 0 <= j < T and zeros elsewhere.  The halves are OR-ed when the data is stored to LDS.
+struct CatRows {
+  __amdgpu_buffer_rsrc_t cache, blk;
+  int m, blk_stride;
+};
+__device__ __forceinline__ CatRows make_cat(const uint16_t* cache_rows, int m, const uint16_t* blk_rows,
+                                            int64_t blk_st, int Bn) {
+  CatRows c;
+  c.cache = __builtin_amdgcn_make_buffer_rsrc((void*)cache_rows, 0, m * kD * 2, 0x00020000);
+  c.blk = __builtin_amdgcn_make_buffer_rsrc((void*)blk_rows, 0, (int)((Bn - 1) * blk_st + kD) * 2,
+                                            0x00020000);
+  c.m = m;
+  c.blk_stride = (int)blk_st * 2;
+  return c;
+}
+struct Cat16 { u32x4 from_cache, from_blk; };
+__device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int j, int chunk) {
+  Cat16 r;
+  r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, j * (kD * 2) + chunk * 16, 0, 0);
+  r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (j - c.m) * c.blk_stride + chunk * 16, 0, 0);
+  return r;
 }
 
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
@@ -95,8 +117,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
     cache_k = (const uint16_t*)a.hist_k + slot;
     cache_v = (const uint16_t*)a.hist_v + slot;
   }
-  const uint16_t* kb = (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + start * a.k.st;
-  const uint16_t* vb = (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + start * a.v.st;
+  const CatRows cat_k =
+      make_cat(cache_k, m, (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + start * a.k.st, a.k.st, Bn);
+  const CatRows cat_v =
+      make_cat(cache_v, m, (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + start * a.v.st, a.v.st, Bn);
   const uint16_t* qb = (const uint16_t*)a.q.p + b * a.q.sb + hq * a.q.sh + start * a.q.st;
   uint16_t* ob = (uint16_t*)a.o.p + b * a.o.sb + hq * a.o.sh + start * a.o.st;
 
@@ -118,110 +142,110 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[ct][i] = 0.f;
+  // running softmax reference (in raw score units) and row sum; exp(x * scale) = exp2(x * c)
+  const float c = a.scale * kLog2e;
+  const float lazy_raw = kLazy / a.scale;
   float m_run = -INFINITY, l_run = 0.f;
 
   // keys this workgroup needs: the cache and the block up to its last query row
   const int kend = min(T, m + q0 + BQ);
   const int NT = (kend + BK - 1) / BK;
 
-  u32x4 kreg[KPER];
-  u32x4 vreg[VPER][2];
+  Cat16 kreg[PER], vreg[PER];
   auto stage_load = [&](int key0) {
 #pragma unroll
-    for (int it = 0; it < KPER; ++it) {
+    for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      kreg[it] = load_cat16(cache_k, kb, a.k.st, m, T, key0 + (idx >> 4), idx & 15);
+      kreg[it] = load_cat16(cat_k, key0 + (idx >> 4), idx & 15);
     }
 #pragma unroll
-    for (int it = 0; it < VPER; ++it) {
+    for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      const int pair = idx % (BK / 2), chunk = idx / (BK / 2);
-      vreg[it][0] = load_cat16(cache_v, vb, a.v.st, m, T, key0 + 2 * pair, chunk);
-      vreg[it][1] = load_cat16(cache_v, vb, a.v.st, m, T, key0 + 2 * pair + 1, chunk);
+      vreg[it] = load_cat16(cat_v, key0 + (idx >> 4), idx & 15);
     }
   };
-  auto stage_store = [&](int buf, int key0) {
+  auto stage_store = [&](int buf) {
     unsigned char* Ks = Ks0 + buf * KBYTES;
     unsigned char* Vs = Vs0 + buf * VBYTES;
 #pragma unroll
-    for (int it = 0; it < KPER; ++it) {
+    for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = mask16(kreg[it], key0 + (idx >> 4) < T);
-    }
-#pragma unroll
-    for (int it = 0; it < VPER; ++it) {
-      const int idx = tid + it * kThreads;
-      const int pair = idx % (BK / 2), chunk = idx / (BK / 2);
-      const u32x4 v0 = mask16(vreg[it][0], key0 + 2 * pair < T);
-      const u32x4 v1 = mask16(vreg[it][1], key0 + 2 * pair + 1 < T);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t lo = (v0[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        const uint32_t hi = (v1[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        *(uint32_t*)(Vs + (chunk * 8 + e) * VSTRIDE + pair * 4) = lo | (hi << 16);
-      }
+      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = kreg[it].from_cache | kreg[it].from_blk;
+      *(u32x4*)(Vs + (idx >> 4) * VSTRIDE + (idx & 15) * 16) = vreg[it].from_cache | vreg[it].from_blk;
     }
   };
 
   stage_load(0);
-  stage_store(0, 0);
+  stage_store(0);
   __syncthreads();
+
+  // value fragments: lane (head-dim column ct*32 + l31) x 8 keys.  The key order inside a
+  // contraction step follows the layout the probabilities already have in the score accumulator:
+  // slot j of step u is key u*16 + (j/4)*8 + lh*4 + j%4 (see below), so nothing is shuffled.
+  const int s16 = l & 15, g2 = (l >> 4) & 1;
+  const int v_lane_off = (lh * 4 + (s16 >> 2)) * VSTRIDE + (16 * g2 + 4 * (s16 & 3)) * 2;
 
   for (int t = 0; t < NT; ++t) {
     const int buf = t & 1;
     const int key0 = t * BK;
     const unsigned char* Ks = Ks0 + buf * KBYTES;
     const unsigned char* Vs = Vs0 + buf * VBYTES;
-    const bool more = t + 1 < NT;
-    if (more) stage_load(key0 + BK);
+    // past the last tile the loads are out of range of both resources: zeros, no memory traffic
+    stage_load(key0 + BK);
 
     if (key0 < m + wq0 + 32) {           // some key of the tile is visible to some query of this wave
       // ---- S^T tile: keys x queries
       f32x16 sacc[BK / 32];
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.f;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           const bf16x8 kv = *(const bf16x8*)(Ks + (kt * 32 + l31) * KSTRIDE + (ks * 16 + lh * 8) * 2);
-          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[ks], sacc[kt], 0, 0, 0);
+          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[ks], ks == 0 ? zero : sacc[kt], 0, 0, 0);
         }
       }
-      // ---- scale, mask, online softmax (everything of one query sits in one lane pair)
-      const bool need_mask = key0 + BK > m + wq0 || key0 + BK > T;
-      float mx = -INFINITY;
+      // ---- mask, online softmax with a lazy reference (everything of one query sits in one lane pair)
+      if (key0 + BK > m + wq0 || key0 + BK > T) {
+#pragma unroll
+        for (int kt = 0; kt < BK / 32; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = key0 + kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+            if (key >= T || key - m > qrow) sacc[kt][i] = -INFINITY;
+          }
+      }
+      float mx = sacc[0][0];
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          float s = sacc[kt][i] * a.scale;
-          if (need_mask) {
-            const int key = key0 + kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-            if (key >= T || key - m > qrow) s = -INFINITY;
-          }
-          sacc[kt][i] = s;
-          mx = fmaxf(mx, s);
-        }
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kt][i]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __expf(m_run - m_new);
+      // The reference only moves when the row maximum outgrows it by kLazy (in exponent units),
+      // so exp(..) stays below e^kLazy and the accumulator is rescaled rarely.
+      const bool bump = mx > m_run + lazy_raw;
+      const float m_new = bump ? mx : m_run;
+      if (__any(bump)) {
+        const float alpha = bump ? __builtin_amdgcn_exp2f((m_run - m_new) * c) : 1.0f;
+        l_run *= alpha;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
+      }
+      m_run = m_new;
+      const float mc = m_new * c;
       float psum = 0.f;
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float p = __expf(sacc[kt][i] - m_new);
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][i], c, -mc));
           sacc[kt][i] = p;
           psum += p;
         }
       psum += __shfl_xor(psum, 32, 64);
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
+      l_run += psum;
       // ---- O^T += V^T P^T; contraction slot j of step u holds key (u*16 + (j/4)*8 + lh*4 + j%4)
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt)
@@ -234,16 +258,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
           const bf16x8 pv = __builtin_bit_cast(bf16x8, pp);
 #pragma unroll
           for (int ct = 0; ct < 4; ++ct) {
-            const unsigned char* vrow = Vs + (ct * 32 + l31) * VSTRIDE + (kt * 32 + u * 16 + lh * 4) * 2;
-            const u32x2 lo = *(const u32x2*)vrow;
-            const u32x2 hi = *(const u32x2*)(vrow + 16);
-            const u32x4 vv = {lo[0], lo[1], hi[0], hi[1]};
-            oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pv,
+            const unsigned char* vp = Vs + (kt * 32 + u * 16) * VSTRIDE + (ct * 32) * 2 + v_lane_off;
+            const s16x4 y0 = lds_read_tr(vp);
+            const s16x4 y1 = lds_read_tr(vp + 8 * VSTRIDE);
+            const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+            oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, yy), pv,
                                                                oacc[ct], 0, 0, 0);
           }
         }
     }
-    if (more) stage_store(buf ^ 1, key0 + BK);
+    stage_store(buf ^ 1);
     __syncthreads();
   }
 
