@@ -59,7 +59,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
 
 // [cache ; block] rows through two raw buffer resources: an index outside a resource's range reads
 // as zero without touching memory, so OR-ing the two loads gives row j of the concatenation for
-// 0 <= j < T and zeros elsewhere.  The halves are OR-ed when the data is stored to LDS.
+// 0 <= j < T and zeros elsewhere (only tiles that straddle the seam need both).
 struct CatRows {
   __amdgpu_buffer_rsrc_t cache, blk;
   int m, blk_stride;
@@ -75,12 +75,6 @@ __device__ __forceinline__ CatRows make_cat(const uint16_t* cache_rows, int m, c
   return c;
 }
 struct Cat16 { u32x4 from_cache, from_blk; };
-__device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int j, int chunk) {
-  Cat16 r;
-  r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, j * (kD * 2) + chunk * 16, 0, 0);
-  r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (j - c.m) * c.blk_stride + chunk * 16, 0, 0);
-  return r;
-}
 
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -151,32 +145,41 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
   const int kend = min(T, m + q0 + BQ);
   const int NT = (kend + BK - 1) / BK;
 
+  // A tile that lies wholly in the cache or wholly in the block needs one load per chunk; only a
+  // tile straddling the seam issues both and ORs them.  (src: 1 = cache, 2 = block, 3 = both.)
   Cat16 kreg[PER], vreg[PER];
-  auto stage_load = [&](int key0) {
+  auto tile_src = [&](int key0) { return (key0 < m ? 1 : 0) | (key0 + BK > m ? 2 : 0); };
+  auto stage_load = [&](int key0, int src) {
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      kreg[it] = load_cat16(cat_k, key0 + (idx >> 4), idx & 15);
-    }
-#pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int idx = tid + it * kThreads;
-      vreg[it] = load_cat16(cat_v, key0 + (idx >> 4), idx & 15);
+      const int j = key0 + (idx >> 4), chunk = idx & 15;
+      if (src & 1) {
+        kreg[it].from_cache = __builtin_amdgcn_raw_buffer_load_b128(cat_k.cache, j * (kD * 2) + chunk * 16, 0, 0);
+        vreg[it].from_cache = __builtin_amdgcn_raw_buffer_load_b128(cat_v.cache, j * (kD * 2) + chunk * 16, 0, 0);
+      }
+      if (src & 2) {
+        kreg[it].from_blk = __builtin_amdgcn_raw_buffer_load_b128(cat_k.blk, (j - m) * cat_k.blk_stride + chunk * 16, 0, 0);
+        vreg[it].from_blk = __builtin_amdgcn_raw_buffer_load_b128(cat_v.blk, (j - m) * cat_v.blk_stride + chunk * 16, 0, 0);
+      }
     }
   };
-  auto stage_store = [&](int buf) {
+  auto stage_store = [&](int buf, int src) {
     unsigned char* Ks = Ks0 + buf * KBYTES;
     unsigned char* Vs = Vs0 + buf * VBYTES;
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = kreg[it].from_cache | kreg[it].from_blk;
-      *(u32x4*)(Vs + (idx >> 4) * VSTRIDE + (idx & 15) * 16) = vreg[it].from_cache | vreg[it].from_blk;
+      u32x4* kd = (u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16);
+      u32x4* vd = (u32x4*)(Vs + (idx >> 4) * VSTRIDE + (idx & 15) * 16);
+      if (src == 1) { *kd = kreg[it].from_cache; *vd = vreg[it].from_cache; }
+      else if (src == 2) { *kd = kreg[it].from_blk; *vd = vreg[it].from_blk; }
+      else { *kd = kreg[it].from_cache | kreg[it].from_blk; *vd = vreg[it].from_cache | vreg[it].from_blk; }
     }
   };
 
-  stage_load(0);
-  stage_store(0);
+  stage_load(0, tile_src(0));
+  stage_store(0, tile_src(0));
   __syncthreads();
 
   // value fragments: lane (head-dim column ct*32 + l31) x 8 keys.  The key order inside a
@@ -190,8 +193,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
     const int key0 = t * BK;
     const unsigned char* Ks = Ks0 + buf * KBYTES;
     const unsigned char* Vs = Vs0 + buf * VBYTES;
-    // past the last tile the loads are out of range of both resources: zeros, no memory traffic
-    stage_load(key0 + BK);
+    // past the last tile the loads are out of range of their resource: zeros, no memory traffic
+    const int src_next = tile_src(key0 + BK);
+    stage_load(key0 + BK, src_next);
 
     if (key0 < m + wq0 + 32) {           // some key of the tile is visible to some query of this wave
       // ---- S^T tile: keys x queries
@@ -235,17 +239,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
       }
       m_run = m_new;
       const float mc = m_new * c;
-      float psum = 0.f;
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][i], c, -mc));
-          sacc[kt][i] = p;
-          psum += p;
-        }
-      psum += __shfl_xor(psum, 32, 64);
-      l_run += psum;
+        for (int i = 0; i < 16; ++i) sacc[kt][i] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][i], c, -mc));
+      float psum = 0.f;
       // ---- O^T += V^T P^T; contraction slot j of step u holds key (u*16 + (j/4)*8 + lh*4 + j%4)
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt)
@@ -253,8 +251,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
         for (int u = 0; u < 2; ++u) {
           u32x4 pp;
 #pragma unroll
-          for (int j2 = 0; j2 < 4; ++j2)
+          for (int j2 = 0; j2 < 4; ++j2) {
             pp[j2] = pack_bf16(sacc[kt][u * 8 + 2 * j2], sacc[kt][u * 8 + 2 * j2 + 1]);
+            psum += sacc[kt][u * 8 + 2 * j2] + sacc[kt][u * 8 + 2 * j2 + 1];
+          }
           const bf16x8 pv = __builtin_bit_cast(bf16x8, pp);
 #pragma unroll
           for (int ct = 0; ct < 4; ++ct) {
@@ -266,8 +266,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
                                                                oacc[ct], 0, 0, 0);
           }
         }
+      psum += __shfl_xor(psum, 32, 64);
+      l_run += psum;
     }
-    stage_store(buf ^ 1);
+    stage_store(buf ^ 1, src_next);
     __syncthreads();
   }
 
