@@ -253,6 +253,13 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it].from_cache | vreg[it].from_blk;
   };
 
+  // Ring of key operands of the logit MFMAs, fetched kRing-1 contraction steps ahead.  kRing
+  // divides the number of steps, so the last steps of a stage fetch the first operands of the
+  // next stage into the slots that stage expects and the matrix pipe never waits at a stage start.
+  constexpr int kRing = 5;
+  static_assert(G::NS % kRing == 0, "operand ring must wrap exactly at a stage boundary");
+  bf16x8 xv[kRing];
+
   // Partial logits of one tile, summed over this wave's channel quarter:
   // sacc[rt] lane = slot rt*32 + l31, rows = positions (i/4)*8 + lh*4 + i%4.
   f32x16 sacc[G::RT];
@@ -272,12 +279,16 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   //   DoSoftmax: reduction + softmax of tile i (partials in Sred) into Ps[i&1], alphas[i&1];
   //              staging of key tile i+3 and value tile i;
   //   DoMix:     mixing of tile i-1 (Ps[(i-1)&1], key tile buffer (i-1)%5, value buffer (i-1)&1).
-  // Work other than the logit MFMAs is cut into slices placed after contraction step `st`; every
-  // slice issues its loads a few steps before the slice that consumes them.
   //
-  // Barriers.  B1 (step 2) publishes what the previous stage wrote to LDS -- partial logits,
+  // Issue model.  A wave issues in order and the matrix pipe takes one MFMA every 32 cycles, so
+  // after each MFMA there is room for about seven other instructions before the next MFMA can
+  // issue anyway.  Everything that is not a logit MFMA is therefore cut into micro-slices of a few
+  // instructions, one per MFMA ("slot" 2*st + rt), with every load issued several slots before
+  // the slice that consumes it.
+  //
+  // Barriers.  B1 (slot 5) publishes what the previous stage wrote to LDS -- partial logits,
   // probabilities, rescale factors, staged tiles -- so everything read before it (the key tile of
-  // this stage's logits) was staged two stages ago.  B2 (step 9) comes after every wave has
+  // this stage's logits) was staged two stages ago.  B2 (slot 19) comes after every wave has
   // consumed this tile's partial logits; the buffer is rewritten at the end of the stage.
   // Neither needs outstanding global loads to finish, so they are plain barriers preceded by a
   // wait on the LDS counter only.
@@ -286,6 +297,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     constexpr bool DoMix = decltype(do_mix_t)::value;
     const int j0 = i * BN;
     const unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
+    const unsigned char* Xnext2 = Xs0 + ((i + 2) % G::NXBUF) * G::XBYTES;
     const unsigned char* Xprev = Xs0 + ((i + G::NXBUF - 1) % G::NXBUF) * G::XBYTES;
     unsigned char* Xstage = Xs0 + ((i + 3) % G::NXBUF) * G::XBYTES;
     const unsigned char* Vprev = Vs0 + ((i - 1) & 1) * G::VBYTES;
@@ -295,31 +307,33 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     float* alpha_cur = alphas0 + (i & 1) * BM;
     const float* alpha_prev = alphas0 + ((i - 1) & 1) * BM;
 
-    // logits: key operands are fetched kRing-1 steps ahead of their MFMAs
-    constexpr int kRing = 4;
-    bf16x8 xv[kRing];
-    const unsigned char* xbase = Xnext + l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
+    // logits: operands of step st come from this stage's key tile, those of steps >= NS are the
+    // first operands of the next stage's tile
+    const int xlane = l31 * G::XSTRIDE + (32 * w + lh * 8) * 2;
     auto fetch = [&](int st) {
-      xv[st % kRing] = *(const bf16x8*)(xbase + (st >> 1) * G::XSTRIDE + (st & 1) * 32);
+      const unsigned char* xb = (st < G::NS ? Xnext : Xnext2) + xlane;
+      const int s2 = st < G::NS ? st : st - G::NS;
+      xv[st % kRing] = *(const bf16x8*)(xb + (s2 >> 1) * G::XSTRIDE + (s2 & 1) * 32);
     };
     // softmax of tile i
-    f32x4 part[4][G::EPL / 4];
+    constexpr int E4 = G::EPL / 4;
+    f32x4 part[4][E4];
     float sv[G::EPL];
-    float mx = 0.f, m_new = 0.f, alpha = 1.f, psum = 0.f;
+    float mx = 0.f, m_new = 0.f, mc = 0.f, alpha = 1.f, psum = 0.f;
     bool bump = false;
-    auto sm_issue = [&](int ww0) {
+    uint32_t packed[G::EPL / 2];
+    auto sm_issue = [&](int ww) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int e4 = 0; e4 < G::EPL / 4; ++e4)
-          part[ww0 + q][e4] = *(const f32x4*)(Sred + ((ww0 + q) * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
+      for (int e4 = 0; e4 < E4; ++e4)
+        part[ww][e4] = *(const f32x4*)(Sred + (ww * BM + srow) * G::SSTRIDE + sp0 + e4 * 4);
     };
-    auto sm_add = [&](int ww0) {
+    auto sm_add = [&](int ww0, int e4) {      // 4 positions: + partials ww0 and ww0+1
 #pragma unroll
-      for (int e4 = 0; e4 < G::EPL / 4; ++e4)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          sv[e4 * 4 + e] = (ww0 == 0 ? bias : sv[e4 * 4 + e]) + part[ww0][e4][e] + part[ww0 + 1][e4][e];
+      for (int e = 0; e < 4; ++e)
+        sv[e4 * 4 + e] = (ww0 == 0 ? bias : sv[e4 * 4 + e]) + part[ww0][e4][e] + part[ww0 + 1][e4][e];
+    };
+    auto sm_exp = [&](int e) {
+      sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], kLog2e, -mc));
     };
     // mixing of tile i-1: operand fragments, fetched ahead of the MFMAs that follow the loop
     const int s16 = l & 15, g2 = (l >> 4) & 1;
@@ -350,36 +364,24 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
         oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[ks][rt], oacc[ct][rt], 0, 0, 0);
     };
 
-    if (DoConv) {
-#pragma unroll
-      for (int st = 0; st < kRing - 1; ++st) fetch(st);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-#pragma unroll
-    for (int st = 0; st < G::NS; ++st) {
-      if (DoConv) {
-        if (st + kRing - 1 < G::NS) fetch(st + kRing - 1);
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int rt = 0; rt < G::RT; ++rt)
-          sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
-                                                             st == 0 ? zero : sacc[rt], 0, 0, 0);
-      }
-      if (st == 2) {                           // B1
+    // The micro-slices.  `slot` counts logit MFMAs of the stage: 0 .. RT*NS-1.
+    constexpr int kSlots = G::RT * G::NS;
+    constexpr int S = G::RT;                   // slots per contraction step
+    auto micro = [&](int slot) {
+      if (slot == 2 * S + S - 1) {             // B1
         __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): this wave's LDS stores of the last stage landed
         __builtin_amdgcn_s_barrier();
       }
       if (DoSoftmax) {
+        // partial logits of tile i: four 16/32-byte reads, then the sums, a few steps later
+        if (slot >= 3 * S && slot < 3 * S + 4) sm_issue(slot - 3 * S);
         // staging loads early: they have the longest latency
-        if (st >= 3 && st < 3 + G::XPER) load_x(st - 3, j0 + 3 * BN);
-        if (st >= 3 + G::XPER && st < 3 + G::XPER + G::VPER) load_v(st - 3 - G::XPER, j0);
-        if (st == 3) sm_issue(0);
-        if (st == 4) sm_issue(2);
-        if (st == 7) sm_add(0);
-        if (st == 8) sm_add(2);
-        if (st == 9) __builtin_amdgcn_s_barrier();   // B2: the reads above have all been consumed
-        if (st == 10) {
+        if (slot >= 5 * S && slot < 5 * S + G::XPER) load_x(slot - 5 * S, j0 + 3 * BN);
+        if (slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) load_v(slot - 5 * S - G::XPER, j0);
+        if (slot >= 8 * S && slot < 8 * S + E4) sm_add(0, slot - 8 * S);
+        if (slot >= 8 * S + E4 && slot < 8 * S + 2 * E4) sm_add(2, slot - 8 * S - E4);
+        if (slot == 8 * S + 2 * E4) __builtin_amdgcn_s_barrier();   // B2: the partial logits have been consumed
+        if (slot == 8 * S + 2 * E4 + 1) {
           if (j0 + BN > T) {                   // tail tile: positions past T carry no weight
 #pragma unroll
             for (int e = 0; e < G::EPL; ++e)
@@ -389,49 +391,60 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
           for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
         }
-        if (st == 11) {
-          mx = group_max<G::LPR>(mx);
+        if (slot == 8 * S + 2 * E4 + 2) mx = group_max<G::LPR>(mx);
+        if (slot == 8 * S + 2 * E4 + 3) {
           // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref)
           // stays below e^kLazy and the accumulators are rescaled rarely.  Every tile has a
           // position < T, so mx is finite.
           bump = mx > m_run + kLazy;
           m_new = bump ? mx : m_run;
           alpha = bump ? __expf(m_run - m_new) : 1.0f;
+          mc = m_new * kLog2e;
         }
-        if (st >= 12 && st < 16) {
-          constexpr int Q = G::EPL / 4;
-          const int e0 = (st - 12) * Q;
+        constexpr int X0 = 8 * S + 2 * E4 + 4;   // one exponential per slot
+        if (slot >= X0 && slot < X0 + G::EPL) sm_exp(slot - X0);
+        if (slot == X0 + G::EPL) {
 #pragma unroll
-          for (int e = 0; e < Q; ++e) {
-            sv[e0 + e] = __builtin_amdgcn_exp2f(fmaf(sv[e0 + e], kLog2e, -m_new * kLog2e));
-            psum += sv[e0 + e];
-          }
+          for (int e = 0; e < G::EPL; ++e) psum += sv[e];
         }
-        if (st == 16) {
+        if (slot == X0 + G::EPL + 1) {
           psum = group_sum<G::LPR>(psum);
           l_run = l_run * alpha + psum;
           m_run = m_new;
         }
-        if (st == 17) {
+        if (slot == X0 + G::EPL + 2) {
 #pragma unroll
-          for (int e4 = 0; e4 < G::EPL / 4; ++e4) {
-            u32x2 pk;
-            pk[0] = pack_bf16(sv[e4 * 4 + 0], sv[e4 * 4 + 1]);
-            pk[1] = pack_bf16(sv[e4 * 4 + 2], sv[e4 * 4 + 3]);
+          for (int e2 = 0; e2 < G::EPL / 2; ++e2) packed[e2] = pack_bf16(sv[2 * e2], sv[2 * e2 + 1]);
+        }
+        if (slot == X0 + G::EPL + 3) {
+#pragma unroll
+          for (int e4 = 0; e4 < E4; ++e4) {
+            const u32x2 pk = {packed[2 * e4], packed[2 * e4 + 1]};
             *(u32x2*)(Pcur + srow * G::PSTRIDE + (sp0 + e4 * 4) * 2) = pk;
           }
           if ((l % G::LPR) == 0) alpha_cur[srow] = alpha;
         }
-        if (st >= 24 && st < 24 + G::XPER) store_x(st - 24, j0 + 3 * BN, Xstage);
-        if (st >= 24 + G::XPER && st < 24 + G::XPER + G::VPER) store_v(st - 24 - G::XPER, j0, Vstage);
+        // staged tiles into LDS, long after their loads were issued
+        constexpr int W0 = kSlots - 2 * (G::XPER + G::VPER) - 4;
+        if (slot >= W0 && slot < W0 + 2 * G::XPER && (slot - W0) % 2 == 0)
+          store_x((slot - W0) / 2, j0 + 3 * BN, Xstage);
+        if (slot >= W0 + 2 * G::XPER && slot < W0 + 2 * (G::XPER + G::VPER) && (slot - W0) % 2 == 0)
+          store_v((slot - W0) / 2 - G::XPER, j0, Vstage);
       }
       if (DoMix) {
-        if (st == 18) {
+        constexpr int M0 = kSlots * 3 / 5;       // operand fragments of tile i-1's mixing, one fetch per slot
+        if (slot == M0) {
 #pragma unroll
           for (int rt = 0; rt < G::RT; ++rt) al[rt] = alpha_prev[rt * 32 + l31];
         }
+        if (slot == M0 + 1) mix_fetch_p(0);
+        if (slot == M0 + 2) mix_fetch_p(1);
+        if (slot == M0 + 3) mix_fetch_y(0, 0);
+        if (slot == M0 + 4) mix_fetch_y(0, 1);
+        if (slot == M0 + 5) mix_fetch_y(1, 0);
+        if (slot == M0 + 6) mix_fetch_y(1, 1);
         // (rarely) rescale the accumulators before tile i-1 is mixed in
-        if (st == 21) {
+        if (slot == M0 + 7) {
           bool any = false;
 #pragma unroll
           for (int rt = 0; rt < G::RT; ++rt) any |= al[rt] != 1.0f;
@@ -444,11 +457,28 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
                 for (int q = 0; q < 16; ++q) oacc[ct][rt][q] *= al[rt];
           }
         }
-        if (st == 22) { mix_fetch_p(0); mix_fetch_p(1); }
-        if (st == 23) { mix_fetch_y(0, 0); mix_fetch_y(0, 1); }
-        if (st == 25) { mix_fetch_y(1, 0); mix_fetch_y(1, 1); }
       }
-      __builtin_amdgcn_sched_barrier(0);       // pin the order: fetch-ahead, MFMAs, this step's slices
+    };
+
+    if (DoConv && i < 0) {                     // only the very first stage has nobody to fetch for it
+#pragma unroll
+      for (int st = 0; st < kRing - 1; ++st) fetch(st);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+    for (int st = 0; st < G::NS; ++st) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt) {
+        if (DoConv) {
+          sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[st % kRing], wreg[rt][st >> 1][st & 1],
+                                                             st == 0 ? zero : sacc[rt], 0, 0, 0);
+          if (rt == G::RT - 1) fetch(st + kRing - 1);   // the ring slot of step st-1 is free now
+        }
+        micro(st * S + rt);
+        __builtin_amdgcn_sched_barrier(0);     // pin the order: MFMA, then this slot's slice
+      }
     }
     // Mixing MFMAs of tile i-1 run while the last logit MFMAs drain; the partial logits are
     // published in between.  The next stage's B1 makes them visible.
