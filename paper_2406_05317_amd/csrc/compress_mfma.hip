@@ -277,7 +277,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   // One pipeline stage.  With tile index i it runs, interleaved:
   //   DoConv:    logits of tile i+1 (key tile buffer (i+1)%5) into sacc, published at the end;
   //   DoSoftmax: reduction + softmax of tile i (partials in Sred) into Ps[i&1], alphas[i&1];
-  //              staging of key tile i+3 and value tile i;
+  //              staging of key tile i+3 and value tile i (loaded during the previous stage);
   //   DoMix:     mixing of tile i-1 (Ps[(i-1)&1], key tile buffer (i-1)%5, value buffer (i-1)&1).
   //
   // Issue model.  A wave issues in order and the matrix pipe takes one MFMA every 32 cycles, so
@@ -375,9 +375,17 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
       if (DoSoftmax) {
         // partial logits of tile i: four 16/32-byte reads, then the sums, a few steps later
         if (slot >= 3 * S && slot < 3 * S + 4) sm_issue(slot - 3 * S);
-        // staging loads early: they have the longest latency
-        if (slot >= 5 * S && slot < 5 * S + G::XPER) load_x(slot - 5 * S, j0 + 3 * BN);
-        if (slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) load_v(slot - 5 * S - G::XPER, j0);
+        // staging: the chunks loaded during the previous stage (key tile i+3, value tile i) go to
+        // LDS, then the same registers receive key tile i+4 and value tile i+1: a whole stage
+        // of latency cover, enough for a first touch that has to come from HBM
+        if (slot >= 5 * S && slot < 5 * S + G::XPER) {
+          store_x(slot - 5 * S, j0 + 3 * BN, Xstage);
+          load_x(slot - 5 * S, j0 + 4 * BN);
+        }
+        if (slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) {
+          store_v(slot - 5 * S - G::XPER, j0, Vstage);
+          load_v(slot - 5 * S - G::XPER, j0 + BN);
+        }
         if (slot >= 8 * S && slot < 8 * S + E4) sm_add(0, slot - 8 * S);
         if (slot >= 8 * S + E4 && slot < 8 * S + 2 * E4) sm_add(2, slot - 8 * S - E4);
         if (slot == 8 * S + 2 * E4) __builtin_amdgcn_s_barrier();   // B2: the partial logits have been consumed
@@ -424,12 +432,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
           }
           if ((l % G::LPR) == 0) alpha_cur[srow] = alpha;
         }
-        // staged tiles into LDS, long after their loads were issued
-        constexpr int W0 = kSlots - 2 * (G::XPER + G::VPER) - 4;
-        if (slot >= W0 && slot < W0 + 2 * G::XPER && (slot - W0) % 2 == 0)
-          store_x((slot - W0) / 2, j0 + 3 * BN, Xstage);
-        if (slot >= W0 + 2 * G::XPER && slot < W0 + 2 * (G::XPER + G::VPER) && (slot - W0) % 2 == 0)
-          store_v((slot - W0) / 2 - G::XPER, j0, Vstage);
       }
       if (DoMix) {
         constexpr int M0 = kSlots * 3 / 5;       // operand fragments of tile i-1's mixing, one fetch per slot
@@ -488,7 +490,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // ---- prologue: key tiles 0, 1 and 2 staged
+  // ---- prologue: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way
 #pragma unroll
   for (int t = 0; t < 3; ++t) {
 #pragma unroll
@@ -496,6 +498,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 #pragma unroll
     for (int it = 0; it < G::XPER; ++it) store_x(it, t * BN, Xs0 + t * G::XBYTES);
   }
+#pragma unroll
+  for (int it = 0; it < G::XPER; ++it) load_x(it, 3 * BN);
+#pragma unroll
+  for (int it = 0; it < G::VPER; ++it) load_v(it, 0);
   __syncthreads();
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
