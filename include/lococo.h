@@ -158,6 +158,17 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
                                       lococo_cache* cache, void* workspace, size_t ws_bytes,
                                       void* stream);
 
+/* When lococo_sequence_forward runs a whole scan's compression steps in one launch, the
+ * workgroups that share a chain wait for each other between steps with a bounded number of
+ * polls.  If a wait ever ran out (it cannot while the launch has the GPU to itself), the kernel
+ * leaves early, the outputs of that call are invalid and a status word in the workspace is set.
+ * This call SYNCHRONISES with the device and returns that word in *out: 0 = fine, 1 = a wait
+ * gave up.  `workspace` is the one passed to lococo_sequence_forward (at least
+ * lococo_workspace_bytes(history = 0) bytes); the word is cleared at the start of every such call
+ * and means nothing before the first one.  Configurations the MFMA kernels do not serve never
+ * wait: *out is 0. */
+lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out);
+
 /* Steps 4-5 with Eq. 5's output supplied by the caller: the cache becomes
  * normalise(logits) . [cache ; block] (Eq. 6, Eq. 4a/4b).  logits: device fp32
  * [batch, n_kv_heads, M, T] contiguous with T = cache->len + B.  Only blk->k

@@ -21,7 +21,7 @@ LOCOCO_IMPL_AUTO, LOCOCO_IMPL_GENERIC, LOCOCO_IMPL_MFMA = 0, 1, 2
 
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
-           "lococo_version", "lococo_timing_begin", "lococo_timing_end"]
+           "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status"]
 
 
 class lococo_config(C.Structure):
@@ -86,6 +86,7 @@ def lib():
         L.lococo_sequence_forward.argtypes = [cfgp, qp, C.c_int64, C.c_int32, C.c_void_p,
                                               C.c_void_p, cap, C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_mix_from_logits.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, cap, C.c_void_p]
+        L.lococo_scan_status.argtypes = [cfgp, C.c_void_p, C.POINTER(C.c_int32)]
         L.lococo_timing_begin.argtypes = []
         L.lococo_timing_end.argtypes = [C.POINTER(lococo_kernel_time), C.POINTER(C.c_int32)]
         for n in EXPORTS[:6] + EXPORTS[8:]:
@@ -222,6 +223,13 @@ def lococo_mix_from_logits(cfg, k, v, logits, cache: Cache):
     x = _qkvo(None, k, v, None)
     _check(lib().lococo_mix_from_logits(C.byref(cfg), C.byref(x), B, logits.data_ptr(),
                                         C.byref(cache.c), _stream()))
+
+
+def lococo_scan_status(cfg, workspace) -> int:
+    """Synchronises; 0 = fine, 1 = a chain wait inside a one-launch scan gave up."""
+    out = C.c_int32(0)
+    _check(lib().lococo_scan_status(C.byref(cfg), _ptr(workspace), C.byref(out)))
+    return out.value
 
 
 def lococo_timing_begin():

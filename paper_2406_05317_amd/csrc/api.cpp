@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -187,9 +188,16 @@ lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
 
 // Workspace of one step.  Generic: fp32 logits [chains, M, T], T <= M + B.
 // MFMA: the repacked filter bank.
+size_t filter_ws_bytes(const lococo_config* c) {
+  return align_up(compress_mfma_filter_bytes(c->M, c->conv_width, filter_banks(c)), 256);
+}
+// chain sync counters + status word of the one-launch scan
+size_t scan_sync_bytes(const lococo_config* c) {
+  return align_up(compress_scan_sync_bytes(c->batch, c->n_kv_heads), 256);
+}
+// MFMA path: [repacked filters][chain sync counters + status word]; generic path: the logits.
 size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
-  if (path == PATH_MFMA)
-    return align_up(compress_mfma_filter_bytes(c->M, c->conv_width, filter_banks(c)), 256);
+  if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c);
   return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
 }
 
@@ -200,8 +208,23 @@ size_t state_bytes(const lococo_config* c) {
 
 // Workspace of the batched-attention schedule: the step workspace followed by
 // K and V history slots for n_compress cache states.
+// Layout: [step workspace][K history][V history].
 size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_compress) {
   return step_ws_bytes(c, path, B) + 2 * (size_t)n_compress * align_up(state_bytes(c), 256);
+}
+
+// Polls a waiting workgroup makes before it gives up on its chain (each poll sleeps ~256 cycles);
+// LOCOCO_SPIN_LIMIT overrides it, which is how the tests force the give-up path from the host.
+int spin_limit() {
+  const char* e = getenv("LOCOCO_SPIN_LIMIT");
+  return e ? atoi(e) : (1 << 24);
+}
+// LOCOCO_SCAN_LAUNCHES=steps forces one launch per compress step (the default is one launch for
+// the whole scan whenever every workgroup can be resident at once).
+bool scan_in_one_launch(const lococo_config* c) {
+  const char* e = getenv("LOCOCO_SCAN_LAUNCHES");
+  if (e && !strcmp(e, "steps")) return false;
+  return compress_scan_fits(c->batch, c->n_kv_heads, c->M, cu_count());
 }
 
 View view_at(const lococo_tensor& t, int64_t tok, size_t es) {
@@ -330,7 +353,23 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
 extern "C" {
 
 const char* lococo_last_error(void) { return g_err; }
-const char* lococo_version(void) { return "0.1.0"; }
+const char* lococo_version(void) { return "0.2.0"; }
+
+lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (!workspace || !out) return fail(LOCOCO_EINVAL, "workspace or out is NULL");
+  Path path;
+  if ((st = resolve_path(cfg, 1, &path))) return st;
+  if (path != PATH_MFMA) {
+    *out = 0;
+    return LOCOCO_OK;
+  }
+  const char* word = (const char*)workspace + filter_ws_bytes(cfg) +
+                     (size_t)cfg->batch * cfg->n_kv_heads * sizeof(uint32_t);
+  HIP_TRY(hipMemcpy(out, word, sizeof(int32_t), hipMemcpyDeviceToHost), "reading the scan status");
+  return LOCOCO_OK;
+}
 
 lococo_status lococo_timing_begin(void) {
   std::lock_guard<std::mutex> lk(g_timing_mu);
@@ -485,6 +524,11 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
     StepArgs a0 = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
     if ((st = enqueue_repack(cfg, a0, workspace, (hipStream_t)stream))) return st;
   }
+  if (path == PATH_MFMA && workspace && ws_bytes >= step_ws_bytes(cfg, path, B)) {
+    // the scan status of this call starts at "no wait gave up", whichever schedule runs
+    HIP_TRY(launch_scan_sync_clear((char*)workspace + filter_ws_bytes(cfg), cfg->batch, cfg->n_kv_heads,
+                                   (hipStream_t)stream), "clearing the scan counters");
+  }
   int64_t n_compress = 0, n_fill = 0;
   for (const auto& sg : plan) n_compress += sg.branch;
   while (n_fill < n && plan[(size_t)n_fill].branch == 0) ++n_fill;
@@ -494,14 +538,39 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
     // cache state, then one attention launch over all blocks, then publish the last state.
     hipStream_t s = (hipStream_t)stream;
     const size_t slot = align_up(state_bytes(cfg), 256);
+    char* sync_ws = (char*)workspace + filter_ws_bytes(cfg);
     char* hist_k = (char*)workspace + step_ws_bytes(cfg, path, B);
     char* hist_v = hist_k + (size_t)n_compress * slot;
     const void* src_k = tmp.k[tmp.cur];
     const void* src_v = tmp.v[tmp.cur];
+    const bool one_launch = scan_in_one_launch(cfg);
     int64_t step = 0;
     for (const auto& sg : plan) {
       StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
       a.m = sg.len_before;
+      if (sg.branch == 1 && one_launch) {
+        // every later block compresses too (the cache stays full): one launch runs them all,
+        // the slot tiles of a chain handing the new cache to each other through the history
+        a.cache_k = src_k;
+        a.cache_v = src_v;
+        ScanArgs sa;
+        sa.st = a;
+        sa.n_steps = (int32_t)n_compress;
+        sa.B = B;
+        sa.tokens_left = L - sg.start;
+        sa.out_k = hist_k;
+        sa.out_v = hist_v;
+        sa.out_stride = (int64_t)(slot / esize(cfg->dtype));
+        sa.sync = nullptr;
+        sa.status = nullptr;
+        sa.spin_limit = spin_limit();
+        KTimer t(K_COMPRESS_MFMA, s);
+        HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
+                "compress scan launch");
+        src_k = hist_k + (size_t)(n_compress - 1) * slot;
+        src_v = hist_v + (size_t)(n_compress - 1) * slot;
+        break;
+      }
       if (sg.branch == 0) {
         a.new_k = tmp.k[tmp.cur];
         a.new_v = tmp.v[tmp.cur];

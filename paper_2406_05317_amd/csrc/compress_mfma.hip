@@ -156,9 +156,10 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // wave w holds slot (32-slot tile)*32 + l%32, channels 32w + 16*half + 8*(l/32) .. +7, so that every
 // load instruction of the prologue reads 1 KB of contiguous memory.
 template <int BM, int KW>
-__global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const uint16_t* wp,
+__global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
+  const StepArgs& a = sa.st;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Xs0 = smem;                                    // NXBUF key tiles (with halo)
   unsigned char* Vs0 = Xs0 + G::NXBUF * G::XBYTES;              // NVBUF value tiles
@@ -178,13 +179,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   const int tiles = a.M / BM;
   const int ch = item / tiles, b = ch / a.Hkv, hkv = ch % a.Hkv;
   const int i0 = (item % tiles) * BM;
-  const int T = a.m + a.Bn, m = a.m;
-  const int NT = (T + BN - 1) / BN;
-
-  const CatRows cat_k = make_cat((const uint16_t*)a.cache_k + (int64_t)ch * a.M * kD, m,
-                                 (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh, a.k.st, a.Bn);
-  const CatRows cat_v = make_cat((const uint16_t*)a.cache_v + (int64_t)ch * a.M * kD, m,
-                                 (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh, a.v.st, a.Bn);
+  // per-step quantities, set at the top of the step loop
+  int T = 0, m = 0, NT = 0;
+  CatRows cat_k, cat_v;
 
   // ---- this wave's slice of the filter bank, resident in registers for the whole kernel:
   // lane (slot l31 of tile rt, channels 32w + 16h + 8*lh ..) for every tap
@@ -211,22 +208,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
 
   // mixing accumulator, transposed: lane = slot rt*32 + l31, rows = columns 64w + ct*32 + (i/4)*8 + lh*4 + i%4
   f32x16 oacc[2][G::RT];
-#pragma unroll
-  for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-    for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
-  // ... and keep the accumulators in the ordinary half (the MFMA can write either).
-#pragma unroll
-  for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-    for (int rt = 0; rt < G::RT; ++rt) asm volatile("" : "+v"(oacc[ct][rt]));
 
   // softmax state of the slot this lane helps with (replicated over the LPR lanes of the slot)
   const int srow = w * G::RPW + l / G::LPR;
   const int sp0 = (l % G::LPR) * G::EPL;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = 0.f, l_run = 0.f;
   const float bias =
       a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv * a.b_head_stride + i0 + srow] << 16)
                : 0.f;
@@ -490,6 +476,35 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
     __builtin_amdgcn_sched_barrier(0);
   };
 
+  __shared__ int bail;                       // a chain wait timed out: leave
+  if (tid == 0) bail = 0;
+
+  for (int step = 0; step < sa.n_steps; ++step) {
+  // ---- this step's inputs: source state, occupancy, block
+  {
+    const int64_t tok = (int64_t)step * sa.B;
+    const int Bn = step == 0 ? a.Bn : (int)(sa.tokens_left - tok < sa.B ? sa.tokens_left - tok : sa.B);
+    m = step == 0 ? a.m : a.M;
+    T = m + Bn;
+    NT = (T + BN - 1) / BN;
+    const uint16_t* src_k = step == 0 ? (const uint16_t*)a.cache_k
+                                      : (const uint16_t*)sa.out_k + (int64_t)(step - 1) * sa.out_stride;
+    const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v
+                                      : (const uint16_t*)sa.out_v + (int64_t)(step - 1) * sa.out_stride;
+    cat_k = make_cat(src_k + (int64_t)ch * a.M * kD, m,
+                     (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + tok * a.k.st, a.k.st, Bn);
+    cat_v = make_cat(src_v + (int64_t)ch * a.M * kD, m,
+                     (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + tok * a.v.st, a.v.st, Bn);
+  }
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+    for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
+  m_run = -INFINITY;
+  l_run = 0.f;
+
   // ---- prologue: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way
 #pragma unroll
   for (int t = 0; t < 3; ++t) {
@@ -520,8 +535,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
   // ---- normalise by the row sums and store the new cache rows, 4 columns (8 bytes) per store
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
   __syncthreads();
-  uint16_t* nk = (uint16_t*)a.new_k + ((int64_t)ch * a.M + i0) * kD;
-  uint16_t* nv = (uint16_t*)a.new_v + ((int64_t)ch * a.M + i0) * kD;
+  uint16_t* nk = (uint16_t*)sa.out_k + (int64_t)step * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
+  uint16_t* nv = (uint16_t*)sa.out_v + (int64_t)step * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
   uint16_t* obase = (w < 2 ? nk : nv) + 64 * (w & 1);
 #pragma unroll
   for (int rt = 0; rt < G::RT; ++rt) {
@@ -537,6 +552,32 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(StepArgs a, const
         *(u32x2*)(obase + (int64_t)slot * kD + ct * 32 + g * 8 + lh * 4) = pk;
       }
   }
+
+  // ---- the next step reads what every slot tile of this chain has just written.
+  // The barrier orders every wave's stores before thread 0's device-scope release (the counter
+  // increment); thread 0's device-scope acquire after the wait, followed by the second barrier,
+  // orders every wave's loads of the next step after the other tiles' stores.  One wave per
+  // workgroup pays for the cache write-back and invalidate instead of all four.
+  if (step + 1 < sa.n_steps) {
+    __syncthreads();
+    if (tid == 0) {
+      __hip_atomic_fetch_add(sa.sync + ch, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t target = (uint32_t)tiles * (uint32_t)(step + 1);
+      int polls = 0;
+      while (__hip_atomic_load(sa.sync + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        __builtin_amdgcn_s_sleep(2);
+        if (++polls > sa.spin_limit) {         // bounded: never spin forever on a workgroup that is not there
+          __hip_atomic_store(sa.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          bail = 1;
+          break;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    __syncthreads();
+    if (bail) break;
+  }
+  }  // step loop
 }
 
 // [M][C][k] per bank -> register order (see compress_mfma_k); one thread per 16-byte chunk.
@@ -559,8 +600,12 @@ __global__ void repack_filters_k(const uint16_t* w, uint16_t* wp, int M, int C, 
   }
 }
 
+__global__ void zero_words_k(uint32_t* p, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
+}
+
 template <int BM, int KW>
-hipError_t launch_one(const StepArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
+hipError_t launch_one(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
   using G = Geo<BM, KW>;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
@@ -569,7 +614,7 @@ hipError_t launch_one(const StepArgs& a, const uint16_t* wp, int64_t wp_head_str
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((a.M / BM) * a.batch * a.Hkv);
+  dim3 grid((a.st.M / BM) * a.st.batch * a.st.Hkv);
   hipLaunchKernelGGL((compress_mfma_k<BM, KW>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
   return hipGetLastError();
 }
@@ -600,13 +645,56 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
   return hipGetLastError();
 }
 
+namespace {
+// 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles
+bool use_big_tiles(int batch, int Hkv, int M, int n_cu) {
+  return (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
+}
+}  // namespace
+
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
                                 hipStream_t s) {
+  ScanArgs sa;
+  sa.st = a;
+  sa.n_steps = 1;
+  sa.B = a.Bn;
+  sa.tokens_left = a.Bn;
+  sa.out_k = a.new_k;
+  sa.out_v = a.new_v;
+  sa.out_stride = 0;
+  sa.sync = nullptr;
+  sa.status = nullptr;
+  sa.spin_limit = 0;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
-  const int chains = a.batch * a.Hkv;
-  // 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles
-  const bool big = (a.M % 64 == 0) && (int64_t)chains * (a.M / 64) >= n_cu;
-  if (big) return launch_one<64, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
+  if (use_big_tiles(a.batch, a.Hkv, a.M, n_cu))
+    return launch_one<64, 15>(sa, (const uint16_t*)wp, wp_head_stride, s);
+  return launch_one<32, 15>(sa, (const uint16_t*)wp, wp_head_stride, s);
+}
+
+bool compress_scan_fits(int batch, int Hkv, int M, int n_cu) {
+  const int bm = use_big_tiles(batch, Hkv, M, n_cu) ? 64 : 32;
+  // one workgroup per compute unit (LDS): every workgroup of the launch is resident at once
+  return (int64_t)batch * Hkv * (M / bm) <= n_cu;
+}
+
+size_t compress_scan_sync_bytes(int batch, int Hkv) {
+  return ((size_t)batch * Hkv + 1) * sizeof(uint32_t);
+}
+
+hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, hipStream_t s) {
+  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws, batch * Hkv + 1);
+  return hipGetLastError();
+}
+
+hipError_t launch_compress_scan(const ScanArgs& a_in, const void* wp, int banks, int n_cu,
+                                void* sync_ws, hipStream_t s) {
+  ScanArgs a = a_in;
+  const int chains = a.st.batch * a.st.Hkv;
+  a.sync = (uint32_t*)sync_ws;
+  a.status = (int32_t*)sync_ws + chains;
+  const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD : 0;
+  if (use_big_tiles(a.st.batch, a.st.Hkv, a.st.M, n_cu))
+    return launch_one<64, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
   return launch_one<32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
 }
 

@@ -35,6 +35,26 @@ struct StepArgs {
   float scale, eps;
 };
 
+// Arguments of the fused compression kernel: `n_steps` consecutive compress steps of the scan in
+// one launch.  Step 0 is described by `st` (source cache, occupancy st.m, block at the k/v views,
+// st.Bn tokens).  Step s > 0 reads the state step s-1 wrote, has a full cache (M slots) and takes
+// the block s*B tokens further on (B tokens, fewer if tokens_left runs out).  Step s writes its
+// new cache to out_k/out_v + s*out_stride elements.  Between steps the slot tiles of a chain wait
+// for each other on sync[chain] (zeroed by the caller); a wait that exceeds spin_limit polls sets
+// *status to 1 and makes the workgroup leave the kernel.
+struct ScanArgs {
+  StepArgs st;
+  int32_t n_steps;
+  int32_t B;
+  int64_t tokens_left;
+  void* out_k;
+  void* out_v;
+  int64_t out_stride;
+  uint32_t* sync;
+  int32_t* status;
+  int32_t spin_limit;
+};
+
 // Arguments of the MFMA attention kernel: one block, or every block of a scan
 // whose intermediate caches were kept.  Block n = seg_first + (launch index)
 // covers tokens [n*B, min((n+1)*B, L)) of the q/k/v/o views.  Blocks n <= n_fill
@@ -78,6 +98,16 @@ size_t compress_mfma_filter_bytes(int M, int conv_width, int banks);
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s);
 // Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
+                                hipStream_t s);
+// true if all steps of a scan can run in one launch (every workgroup resident at once)
+bool compress_scan_fits(int batch, int Hkv, int M, int n_cu);
+// bytes of the sync counters + status word the scan launch needs
+size_t compress_scan_sync_bytes(int batch, int Hkv);
+// zero them (a fill kernel, so the call may sit inside a captured graph)
+hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, hipStream_t s);
+// the same kernel over n_steps consecutive compress steps (see ScanArgs); `sync_ws` is
+// compress_scan_sync_bytes() of device memory, cleared beforehand
+hipError_t launch_compress_scan(const ScanArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
                                 hipStream_t s);
 
 

@@ -128,3 +128,39 @@ def test_mfma_is_refused_for_shapes_it_does_not_take():
         assert e.value.status == lb.LOCOCO_EUNSUPPORTED
         # AUTO falls back to the shape-agnostic kernels
         assert lb.lococo_workspace_bytes(lb.config_for(w, impl=0), w.L, w.B) > 0
+
+
+def test_one_launch_scan_equals_one_launch_per_step(monkeypatch):
+    """All compress steps of a scan in one launch (slot tiles of a chain handing the cache to each
+    other inside the kernel) against one launch per step: bit-identical."""
+    w = _w(M=256, B=128, L=1536, n_q_heads=8, n_kv_heads=8)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    monkeypatch.setenv("LOCOCO_SCAN_LAUNCHES", "steps")
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x, y)
+    assert a[3:] == b[3:]
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    compare_scan(w, a, want, what="one-launch scan")
+
+
+def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
+    """Forced from the host: with no polls allowed, the first slot tile to finish a step cannot wait
+    for its chain, leaves the kernel, and the status word says so.  Every workgroup still exits."""
+    from paper_2406_05317_amd import binding as lb
+    w = _w(M=256, B=128, L=1024, n_q_heads=4, n_kv_heads=4)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    cfg = lb.config_for(w, impl=MFMA)
+    ws = lb.workspace(cfg, w.L, w.B, True)
+    cache = lb.Cache(cfg)
+    o = torch.empty_like(q, device="cuda")
+    monkeypatch.setenv("LOCOCO_SPIN_LIMIT", "-1")
+    lb.lococo_sequence_forward(cfg, q.cuda(), k.cuda(), v.cuda(), o, cw.cuda(), cb.cuda(), cache, w.B, ws)
+    assert lb.lococo_scan_status(cfg, ws) == 1
+    monkeypatch.delenv("LOCOCO_SPIN_LIMIT")
+    cache = lb.Cache(cfg)
+    lb.lococo_sequence_forward(cfg, q.cuda(), k.cuda(), v.cuda(), o, cw.cuda(), cb.cuda(), cache, w.B, ws)
+    assert lb.lococo_scan_status(cfg, ws) == 0           # the word is cleared by the next call
