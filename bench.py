@@ -111,6 +111,60 @@ def cpu_baseline(w, budget_s=15.0):
                       f"{w.name}, {t:.1f} s, scaled linearly by chain count"}
 
 
+def decode_bench(args, w, lb, inputs, torch):
+    """Generation stage (B = 1): one segment step per token on a full cache, all sequences of the
+    batch in one call.  A step here is ONE token of every sequence."""
+    dev = "cuda"
+    w = w.replace(name=w.name + "-decode", batch=args.decode_batch, L=w.M + args.warmup + args.steps, B=1)
+    cfg = lb.config_for(w, impl=args.impl)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    qd, kd, vd, cwd, cbd = (t.to(dev) for t in (q, k, v, cw, cb))
+    od = torch.empty_like(qd)
+    cache = lb.Cache(cfg, dev)
+    # fill the cache with the first M tokens (one block, nothing to compress yet)
+    cfg_fill = lb.config_for(w.replace(B=w.M), impl=args.impl)
+    lb.lococo_sequence_forward(cfg_fill, qd[:, :, :w.M], kd[:, :, :w.M], vd[:, :, :w.M], od[:, :, :w.M], cwd, cbd,
+                               cache, w.M, lb.workspace(cfg_fill, w.M, w.M, False, dev))
+    ws = lb.workspace(cfg, 1, 1, False, dev)
+    lb.lococo_prepare_filters(cfg, cwd, ws)              # once per generation, not once per token
+    cfg.flags |= lb.LOCOCO_FLAG_FILTERS_PREPARED
+
+    def token(t):
+        lb.lococo_segment_step(cfg, qd[:, :, t:t + 1], kd[:, :, t:t + 1], vd[:, :, t:t + 1], od[:, :, t:t + 1],
+                               cwd, cbd, cache, ws)
+    t = w.M
+    for _ in range(args.warmup):
+        token(t); t += 1
+    torch.cuda.synchronize()
+    lb.lococo_timing_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        token(t); t += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kt = lb.lococo_timing_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops = step_flops(w, w.M, 1)
+    name = max(kt, key=lambda n: kt[n][1])
+    launches, total_ms = kt[name]
+    part = sum(flops[p] for p in KERNEL_PARTS.get(name, ())) * args.steps
+    achieved = part / (total_ms * 1e-3) / 1e12 if total_ms > 0 else 0.0
+    out = {"metric": "generation-stage tokens/sec per layer (segment step with B = 1: attention, conv logits, "
+                     "normalisation, fusion per token)",
+           "value": w.batch / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+           "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                      "head_dim": w.head_dim, "B": 1, "M": w.M, "conv_width": w.conv_width,
+                      "conv_channels": w.C, "impl": args.impl},
+           "roofline": {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
+                        "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                        "launches": launches, "avg_launch_us": total_ms * 1e3 / max(launches, 1),
+                        "kernel_ms_per_step": {n: kt[n][1] / args.steps for n in kt}}}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +175,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-history", action="store_true",
                     help="step-by-step schedule instead of the batched-attention one")
+    ap.add_argument("--decode-batch", type=int, default=0,
+                    help="instead of the prefill scan, time the generation stage: --steps segment steps "
+                         "with B = 1 on a full cache, for this many sequences at once (0 = off)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the warm-up, so "
                          "that a rocprofv3 --pmc run has a kernel of known HBM traffic to scale "
@@ -138,6 +195,8 @@ def main():
     w = inputs.CONFIGS[args.workload]
     dev = "cuda"
     torch.cuda.set_device(0)
+    if args.decode_batch:
+        return decode_bench(args, w, lb, inputs, torch)
     cfg = lb.config_for(w, impl=args.impl)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)

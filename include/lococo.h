@@ -67,6 +67,11 @@ enum { LOCOCO_F32 = 0, LOCOCO_BF16 = 1 };
 enum { LOCOCO_IMPL_AUTO = 0, LOCOCO_IMPL_GENERIC = 1, LOCOCO_IMPL_MFMA = 2 };
 
 /* Problem description.  Plain data, filled by the caller. */
+/* lococo_config.flags */
+#define LOCOCO_FLAG_FILTERS_PREPARED 1  /* the workspace already holds what lococo_prepare_filters made of
+                                           conv_w: steps do not repeat that work (generation stage: the
+                                           filters do not change from token to token)                    */
+
 typedef struct lococo_config {
   uint32_t struct_size;   /* sizeof(lococo_config); guards against ABI skew                       */
   int32_t dtype;          /* LOCOCO_F32 / LOCOCO_BF16: storage type of q,k,v,o, cache and filters */
@@ -82,7 +87,7 @@ typedef struct lococo_config {
   int32_t impl;           /* LOCOCO_IMPL_*: AUTO picks the MFMA kernels when the shape allows,
                              GENERIC forces the shape-agnostic kernels, MFMA fails with
                              LOCOCO_EUNSUPPORTED when the shape does not allow them               */
-  int32_t reserved;       /* must be 0                                                            */
+  int32_t flags;          /* LOCOCO_FLAG_* bits, 0 by default                                     */
   int64_t w_head_stride;  /* elements between per-kv-head filter banks; 0 = one shared bank       */
   int64_t b_head_stride;  /* same for the bias                                                    */
   float attn_scale;       /* 0 => 1/sqrt(head_dim)                                                */
@@ -133,6 +138,14 @@ lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_t
  * batched launch after the compression scan.  May return 0. */
 lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
                                      int32_t history, size_t* out);
+
+/* The filter bank in the form the kernels read (for the MFMA path: Eq. 5's [M, C, k] weights
+ * repacked into register order at the start of `workspace`; otherwise nothing).  Every call of
+ * lococo_segment_step / lococo_sequence_forward does this itself unless the configuration
+ * carries LOCOCO_FLAG_FILTERS_PREPARED, in which case the caller must have called this function
+ * on the same workspace with the same conv_w since either last changed.  Enqueued on `stream`. */
+lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_w, void* workspace,
+                                     size_t ws_bytes, void* stream);
 
 /* Alg. 2 step 3 alone: o = Attn([Kc, K_blk], Q_blk, [Vc, V_blk]) for one block
  * of B tokens against the live cache (cache->len slots).  Does not modify the

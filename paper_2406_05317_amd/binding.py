@@ -18,17 +18,19 @@ LIB_PATH = os.path.join(_PKG, "liblococo.so")
 LOCOCO_OK, LOCOCO_EINVAL, LOCOCO_EUNSUPPORTED, LOCOCO_ESTATE, LOCOCO_EHIP, LOCOCO_EWORKSPACE = range(6)
 LOCOCO_F32, LOCOCO_BF16 = 0, 1
 LOCOCO_IMPL_AUTO, LOCOCO_IMPL_GENERIC, LOCOCO_IMPL_MFMA = 0, 1, 2
+LOCOCO_FLAG_FILTERS_PREPARED = 1
 
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
-           "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status"]
+           "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status",
+           "lococo_prepare_filters"]
 
 
 class lococo_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("batch", C.c_int32),
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("M", C.c_int32), ("conv_width", C.c_int32), ("conv_in", C.c_int32),
-                ("norm", C.c_int32), ("impl", C.c_int32), ("reserved", C.c_int32),
+                ("norm", C.c_int32), ("impl", C.c_int32), ("flags", C.c_int32),
                 ("w_head_stride", C.c_int64), ("b_head_stride", C.c_int64),
                 ("attn_scale", C.c_float), ("norm_eps", C.c_float)]
 
@@ -87,6 +89,7 @@ def lib():
                                               C.c_void_p, cap, C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_mix_from_logits.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, cap, C.c_void_p]
         L.lococo_scan_status.argtypes = [cfgp, C.c_void_p, C.POINTER(C.c_int32)]
+        L.lococo_prepare_filters.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_timing_begin.argtypes = []
         L.lococo_timing_end.argtypes = [C.POINTER(lococo_kernel_time), C.POINTER(C.c_int32)]
         for n in EXPORTS[:6] + EXPORTS[8:]:
@@ -113,9 +116,9 @@ def _dtype_code(dt: torch.dtype) -> int:
 def make_config(*, dtype: torch.dtype, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
                 M: int, conv_width: int, conv_in: int = 0, norm: int = 0, impl: int = 0,
                 w_head_stride: int = 0, b_head_stride: int = 0, attn_scale: float = 0.0,
-                norm_eps: float = 0.0) -> lococo_config:
+                norm_eps: float = 0.0, flags: int = 0) -> lococo_config:
     return lococo_config(C.sizeof(lococo_config), _dtype_code(dtype), batch, n_q_heads, n_kv_heads,
-                         head_dim, M, conv_width, conv_in, norm, impl, 0, w_head_stride,
+                         head_dim, M, conv_width, conv_in, norm, impl, flags, w_head_stride,
                          b_head_stride, attn_scale, norm_eps)
 
 
@@ -223,6 +226,11 @@ def lococo_mix_from_logits(cfg, k, v, logits, cache: Cache):
     x = _qkvo(None, k, v, None)
     _check(lib().lococo_mix_from_logits(C.byref(cfg), C.byref(x), B, logits.data_ptr(),
                                         C.byref(cache.c), _stream()))
+
+
+def lococo_prepare_filters(cfg, conv_w, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lococo_prepare_filters(C.byref(cfg), _ptr(conv_w), _ptr(workspace), ws_bytes, _stream()))
 
 
 def lococo_scan_status(cfg, workspace) -> int:

@@ -38,10 +38,10 @@ lococo_status hip_fail(hipError_t e, const char* what) {
 
 // ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
 enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC,
-                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_COUNT };
+                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_ATTN_DECODE, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
                                            "normalise_generic", "mix_generic", "repack_filters",
-                                           "compress_mfma", "attn_mfma"};
+                                           "compress_mfma", "attn_mfma", "attn_decode"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
@@ -91,7 +91,7 @@ lococo_status check_config(const lococo_config* c) {
   if (c->norm != 0 && c->norm != 1) return fail(LOCOCO_EINVAL, "norm must be 0 or 1");
   if (c->impl < LOCOCO_IMPL_AUTO || c->impl > LOCOCO_IMPL_MFMA)
     return fail(LOCOCO_EINVAL, "impl must be one of LOCOCO_IMPL_*");
-  if (c->reserved != 0) return fail(LOCOCO_EINVAL, "config.reserved must be 0");
+  if (c->flags & ~LOCOCO_FLAG_FILTERS_PREPARED) return fail(LOCOCO_EINVAL, "config.flags has unknown bits set");
   if (c->w_head_stride < 0 || c->b_head_stride < 0)
     return fail(LOCOCO_EINVAL, "filter head strides must be >= 0");
   if (!(c->attn_scale >= 0.f) || !(c->norm_eps >= 0.f) || std::isinf(c->attn_scale))
@@ -293,6 +293,11 @@ AttnArgs attn_args_one_block(const StepArgs& a) {
 
 // Enqueue the attention of one block.
 lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, hipStream_t s) {
+  if (path == PATH_MFMA && attn_decode_supports(c->dtype, c->head_dim, a.Bn)) {
+    KTimer t(K_ATTN_DECODE, s);          // one query row per head: a matrix-vector product
+    HIP_TRY(launch_attn_decode(a, s), "attention launch");
+    return LOCOCO_OK;
+  }
   if (path == PATH_MFMA) {
     KTimer t(K_ATTN_MFMA, s);
     HIP_TRY(launch_attn_mfma(attn_args_one_block(a), s), "attention launch");
@@ -303,8 +308,10 @@ lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a,
   return LOCOCO_OK;
 }
 
-// Repack the filter bank into the workspace (MFMA path; once per call).
+// Repack the filter bank into the workspace (MFMA path; once per call unless the caller says
+// the workspace already holds it).
 lococo_status enqueue_repack(const lococo_config* c, const StepArgs& a, void* ws, hipStream_t s) {
+  if (c->flags & LOCOCO_FLAG_FILTERS_PREPARED) return LOCOCO_OK;
   KTimer t(K_REPACK, s);
   HIP_TRY(launch_repack_filters(a, ws, filter_banks(c), s), "filter repack launch");
   return LOCOCO_OK;
@@ -460,6 +467,28 @@ lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk,
   if ((st = resolve_path(cfg, B, &path))) return st;
   StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, true);
   return enqueue_attn(cfg, path, a, (hipStream_t)stream);
+}
+
+lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_w, void* workspace,
+                                     size_t ws_bytes, void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL");
+  Path path;
+  if ((st = resolve_path(cfg, 1, &path))) return st;
+  if (path != PATH_MFMA) return LOCOCO_OK;       // the shape-agnostic kernels read [M, C, k] as given
+  const size_t need = filter_ws_bytes(cfg);
+  if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))
+    return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+                workspace ? ws_bytes : (size_t)0);
+  StepArgs a{};
+  a.conv_w = conv_w;
+  a.w_head_stride = cfg->w_head_stride;
+  a.M = cfg->M;
+  a.k_width = cfg->conv_width;
+  lococo_config once = *cfg;
+  once.flags &= ~LOCOCO_FLAG_FILTERS_PREPARED;
+  return enqueue_repack(&once, a, workspace, (hipStream_t)stream);
 }
 
 lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,

@@ -115,4 +115,8 @@ hipError_t launch_compress_scan(const ScanArgs& a, const void* wp, int banks, in
 bool attn_mfma_supports(int dtype, int d, const char** why);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 
+// ---- attention of one new token per sequence (attn_decode.hip): bf16, head_dim 128, Bn = 1
+bool attn_decode_supports(int dtype, int d, int Bn);
+hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s);
+
 }  // namespace lococo

@@ -8,6 +8,7 @@ import re
 
 import numpy as np
 import pytest
+import torch
 
 from oracle import lococo_oracle as orc
 from paper_2406_05317_amd import binding as lb
@@ -132,3 +133,23 @@ def test_call_argument_errors_enqueue_nothing():
     assert cache.len == 4 and cache.cur == 0           # state untouched on failure
     assert L.lococo_mix_from_logits(C.byref(cfg), C.byref(x), 4, None, C.byref(cache),
                                     None) == lb.LOCOCO_EINVAL
+
+
+def test_every_export_has_its_argument_types_declared():
+    """Without argtypes ctypes passes Python ints as 32-bit C ints and truncates device pointers."""
+    L = lb.lib()
+    for name in lb.EXPORTS:
+        fn = getattr(L, name)
+        if name in ("lococo_last_error", "lococo_version"):
+            continue
+        assert fn.argtypes is not None, name
+
+
+def test_prepare_filters_rejects_bad_arguments_before_touching_the_gpu():
+    cfg = lb.make_config(dtype=torch.bfloat16, batch=1, n_q_heads=4, n_kv_heads=4, head_dim=128, M=128,
+                         conv_width=15)
+    assert lb.lib().lococo_prepare_filters(C.byref(cfg), None, None, 0, None) == lb.LOCOCO_EINVAL
+    cfg.flags = 6
+    with pytest.raises(lb.LococoError) as e:
+        lb.lococo_workspace_bytes(cfg, 128, 128)
+    assert e.value.status == lb.LOCOCO_EINVAL

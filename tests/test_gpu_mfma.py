@@ -164,3 +164,101 @@ def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
     cache = lb.Cache(cfg)
     lb.lococo_sequence_forward(cfg, q.cuda(), k.cuda(), v.cuda(), o, cw.cuda(), cb.cuda(), cache, w.B, ws)
     assert lb.lococo_scan_status(cfg, ws) == 0           # the word is cleared by the next call
+
+
+@pytest.mark.parametrize("case", [
+    dict(M=128, P=256, n_dec=16),                          # 32-row tiles, T = 129 = 4 tiles + one position
+    dict(M=256, P=512, n_dec=12, n_q_heads=8, n_kv_heads=4),    # grouped query heads
+    dict(M=128, P=100, n_dec=40),                          # decode starts with a partly filled cache: 28 fills, 12 compress steps
+])
+def test_mfma_decode_after_prefill(case):
+    """Generation stage: prefill in blocks, then one token at a time (segment steps with B = 1,
+    T = M + 1), against the oracle run with the same two block sizes.  Every decode step rewrites
+    the whole cache in bf16, so the two free-running states drift apart by a rounding step per
+    token; the run is kept short enough for the contract tolerance and the per-step test below
+    covers long generations."""
+    from paper_2406_05317_amd import binding as lb
+    case = dict(case)
+    P, n_dec = case.pop("P"), case.pop("n_dec")
+    w = _w(L=P + n_dec, B=128, **case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    sl = lambda t, a, b: t[:, :, a:b]
+    o1, ck, cv, ln = oracle_forward(w, sl(q, 0, P), sl(k, 0, P), sl(v, 0, P), cw, cb, nthreads=16)
+    o2, ck, cv, ln = oracle_forward(w, sl(q, P, w.L), sl(k, P, w.L), sl(v, P, w.L), cw, cb, B=1,
+                                    cache=(ck, cv, ln), nthreads=16)
+    want = (np.concatenate([o1, o2], 2), ck, cv, ln)
+
+    cfg = lb.config_for(w, impl=MFMA)
+    qd, kd, vd, cwd, cbd = (t.cuda() for t in (q, k, v, cw, cb))
+    od = torch.full_like(qd, float("nan"))
+    cache = lb.Cache(cfg)
+    ws = lb.workspace(cfg, P, w.B, True)
+    lb.lococo_sequence_forward(cfg, sl(qd, 0, P), sl(kd, 0, P), sl(vd, 0, P), sl(od, 0, P), cwd, cbd, cache,
+                               w.B, ws)
+    ws1 = lb.workspace(cfg, 1, 1, False)
+    for t in range(P, w.L):
+        lb.lococo_segment_step(cfg, sl(qd, t, t + 1), sl(kd, t, t + 1), sl(vd, t, t + 1), sl(od, t, t + 1),
+                               cwd, cbd, cache, ws1)
+    torch.cuda.synchronize()
+    got = (od.cpu(), cache.k.cpu(), cache.v.cpu(), cache.len, cache.cur)
+    errs = compare_scan(w, got, want, what="decode")
+    print(case, {k_: (f"{e[0]:.2e}", f"{e[1]:.2e}") for k_, e in errs.items()})
+
+
+def test_mfma_decode_steps_from_the_oracle_state():
+    """A long generation checked step by step: before every token the GPU cache is set to the
+    oracle's current state, so each B = 1 step is compared on its own (no drift between the two
+    recursions) over 96 tokens."""
+    from paper_2406_05317_amd import binding as lb
+    w = _w(M=128, L=128 + 96, B=128)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    sl = lambda t, a, b: t[:, :, a:b]
+    _, ck, cv, ln = oracle_forward(w, sl(q, 0, 128), sl(k, 0, 128), sl(v, 0, 128), cw, cb, nthreads=16)
+    cfg = lb.config_for(w, impl=MFMA)
+    qd, kd, vd, cwd, cbd = (t.cuda() for t in (q, k, v, cw, cb))
+    ws1 = lb.workspace(cfg, 1, 1, False)
+    worst = 0.0
+    for t in range(128, w.L):
+        cache = lb.Cache(cfg)
+        cache.load(torch.as_tensor(ck).to("cuda", w.torch_dtype), torch.as_tensor(cv).to("cuda", w.torch_dtype), ln)
+        od = torch.full_like(sl(qd, t, t + 1), float("nan")).contiguous()
+        lb.lococo_segment_step(cfg, sl(qd, t, t + 1), sl(kd, t, t + 1), sl(vd, t, t + 1), od, cwd, cbd, cache, ws1)
+        o, ck, cv, ln = oracle_forward(w, sl(q, t, t + 1), sl(k, t, t + 1), sl(v, t, t + 1), cw, cb, B=1,
+                                       cache=(ck, cv, ln), nthreads=4)
+        errs = compare_scan(w, (od.cpu(), cache.k.cpu(), cache.v.cpu(), cache.len, cache.cur), (o, ck, cv, ln),
+                            what=f"decode step {t}")
+        worst = max(worst, max(e[0] for e in errs.values()))
+    print("worst per-step max-rel", f"{worst:.2e}")
+    assert worst < 1e-2
+
+
+def test_prepared_filters_give_the_same_steps():
+    """lococo_prepare_filters once + LOCOCO_FLAG_FILTERS_PREPARED on every step is bit-identical
+    to letting every step repack the filter bank itself."""
+    from paper_2406_05317_amd import binding as lb
+    w = _w(M=128, L=128 + 8, B=128)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    qd, kd, vd, cwd, cbd = (t.cuda() for t in (q, k, v, cw, cb))
+    sl = lambda t, a, b: t[:, :, a:b]
+    outs = []
+    for prepared in (False, True):
+        cfg = lb.config_for(w, impl=MFMA)
+        cache = lb.Cache(cfg)
+        od = torch.full_like(qd, float("nan"))
+        ws = lb.workspace(cfg, 128, 128, False)
+        lb.lococo_segment_step(cfg, sl(qd, 0, 128), sl(kd, 0, 128), sl(vd, 0, 128), sl(od, 0, 128), cwd, cbd, cache, ws)
+        if prepared:
+            ws.zero_()                                       # nothing left over from the step above
+            lb.lococo_prepare_filters(cfg, cwd, ws)
+            cfg.flags |= lb.LOCOCO_FLAG_FILTERS_PREPARED
+        for t in range(128, w.L):
+            lb.lococo_segment_step(cfg, sl(qd, t, t + 1), sl(kd, t, t + 1), sl(vd, t, t + 1), sl(od, t, t + 1),
+                                   cwd, cbd, cache, ws)
+        torch.cuda.synchronize()
+        outs.append((od.cpu(), cache.k.cpu(), cache.v.cpu(), cache.len, cache.cur))
+    for x, y in zip(outs[0][:3], outs[1][:3]):
+        assert torch.equal(x, y)
+    assert outs[0][3:] == outs[1][3:]
