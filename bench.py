@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-history", action="store_true",
                     help="step-by-step schedule instead of the batched-attention one")
+    ap.add_argument("--conv-width", type=int, default=0, help="override the workload's filter width (e.g. 21)")
+    ap.add_argument("--norm", type=int, default=-1, help="override the normalisation (0 softmax, 1 relu-sum)")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the prefill scan, time the generation stage: --steps segment steps "
                          "with B = 1 on a full cache, for this many sequences at once (0 = off)")
@@ -193,6 +195,10 @@ def main():
     from paper_2406_05317_amd import binding as lb
     from paper_2406_05317_amd import inputs
     w = inputs.CONFIGS[args.workload]
+    if args.conv_width:
+        w = w.replace(name=f"{w.name}-k{args.conv_width}", conv_width=args.conv_width)
+    if args.norm >= 0:
+        w = w.replace(name=f"{w.name}-norm{args.norm}", norm=args.norm)
     dev = "cuda"
     torch.cuda.set_device(0)
     if args.decode_batch:
@@ -240,7 +246,7 @@ def main():
     part_flops = sum(flops[p] for p in KERNEL_PARTS.get(name, ())) * args.steps
     achieved = part_flops / (total_ms * 1e-3) / 1e12 if total_ms > 0 else 0.0
     roofline = {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": measured_traffic(name, args.workload),
+                "frac": achieved / peak, "traffic": measured_traffic(name, args.workload) if w is inputs.CONFIGS[args.workload] else None,
                 "launches": launches,
                 "avg_launch_us": total_ms * 1e3 / max(launches, 1),
                 "flops_per_launch": part_flops / max(launches, 1),

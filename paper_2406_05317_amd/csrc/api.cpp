@@ -224,7 +224,7 @@ int spin_limit() {
 bool scan_in_one_launch(const lococo_config* c) {
   const char* e = getenv("LOCOCO_SCAN_LAUNCHES");
   if (e && !strcmp(e, "steps")) return false;
-  return compress_scan_fits(c->batch, c->n_kv_heads, c->M, cu_count());
+  return compress_scan_fits(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count());
 }
 
 View view_at(const lococo_tensor& t, int64_t tok, size_t es) {

@@ -33,8 +33,9 @@
 // inside that MFMA stream as well, so no barrier is waited for with the matrix
 // pipe idle.
 //
-// Shapes taken: head_dim = C = 128, bf16, conv_in = 0, norm = 0 (softmax),
-// M a multiple of BM; any T (tail positions are masked), any m.
+// Shapes taken: head_dim = C = 128, bf16, conv_in = 0, width 15 (64- or 32-slot
+// tiles) or 21 (32-slot tiles), either normalisation, M a multiple of BM; any T
+// (tail positions are masked), any m.
 #include <type_traits>
 
 #include "lococo_internal.h"
@@ -155,7 +156,9 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // wp: filters repacked in register order, [bank][M/32][wave][tap][half][lane] x 8 channels: lane l of
 // wave w holds slot (32-slot tile)*32 + l%32, channels 32w + 16*half + 8*(l/32) .. +7, so that every
 // load instruction of the prologue reads 1 KB of contiguous memory.
-template <int BM, int KW>
+// NORM = 0: softmax over the positions; NORM = 1: relu(W) / (sum of relu(W) + eps) (Eq. 6 as printed,
+// with the rectifier of the convolution head in front of it).
+template <int BM, int KW, int NORM>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // Ring of key operands of the logit MFMAs, fetched kRing-1 contraction steps ahead.  kRing
   // divides the number of steps, so the last steps of a stage fetch the first operands of the
   // next stage into the slots that stage expects and the matrix pipe never waits at a stage start.
-  constexpr int kRing = 5;
+  constexpr int kRing = G::NS % 5 == 0 ? 5 : (G::NS % 6 == 0 ? 6 : 7);
   static_assert(G::NS % kRing == 0, "operand ring must wrap exactly at a stage boundary");
   bf16x8 xv[kRing];
 
@@ -319,7 +322,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         sv[e4 * 4 + e] = (ww0 == 0 ? bias : sv[e4 * 4 + e]) + part[ww0][e4][e] + part[ww0 + 1][e4][e];
     };
     auto sm_exp = [&](int e) {
-      sv[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], kLog2e, -mc));
+      sv[e] = NORM == 0 ? __builtin_amdgcn_exp2f(fmaf(sv[e], kLog2e, -mc)) : fmaxf(sv[e], 0.f);
     };
     // mixing of tile i-1: operand fragments, fetched ahead of the MFMAs that follow the loop
     const int s16 = l & 15, g2 = (l >> 4) & 1;
@@ -379,14 +382,16 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
           if (j0 + BN > T) {                   // tail tile: positions past T carry no weight
 #pragma unroll
             for (int e = 0; e < G::EPL; ++e)
-              if (j0 + sp0 + e >= T) sv[e] = -INFINITY;
+              if (j0 + sp0 + e >= T) sv[e] = NORM == 0 ? -INFINITY : 0.f;
           }
-          mx = sv[0];
+          if (NORM == 0) {
+            mx = sv[0];
 #pragma unroll
-          for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
+            for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
+          }
         }
-        if (slot == 8 * S + 2 * E4 + 2) mx = group_max<G::LPR>(mx);
-        if (slot == 8 * S + 2 * E4 + 3) {
+        if (NORM == 0 && slot == 8 * S + 2 * E4 + 2) mx = group_max<G::LPR>(mx);
+        if (NORM == 0 && slot == 8 * S + 2 * E4 + 3) {
           // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref)
           // stays below e^kLazy and the accumulators are rescaled rarely.  Every tile has a
           // position < T, so mx is finite.
@@ -541,7 +546,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
 #pragma unroll
   for (int rt = 0; rt < G::RT; ++rt) {
     const int slot = rt * 32 + l31;
-    const float inv = 1.0f / lsum[slot];
+    const float inv = 1.0f / (NORM == 0 ? lsum[slot] : lsum[slot] + a.eps);
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -604,18 +609,18 @@ __global__ void zero_words_k(uint32_t* p, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-template <int BM, int KW>
+template <int BM, int KW, int NORM>
 hipError_t launch_one(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
   using G = Geo<BM, KW>;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid((a.st.M / BM) * a.st.batch * a.st.Hkv);
-  hipLaunchKernelGGL((compress_mfma_k<BM, KW>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
+  hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
   return hipGetLastError();
 }
 
@@ -626,8 +631,11 @@ bool compress_mfma_supports(int dtype, int d, int M, int conv_width, int conv_in
   if (dtype != LOCOCO_BF16) { *why = "the MFMA kernels take bf16 storage only"; return false; }
   if (d != kD) { *why = "the MFMA kernels take head_dim = 128 only"; return false; }
   if (conv_in != 0) { *why = "the MFMA compression kernel takes keys-only filters (conv_in = 0)"; return false; }
-  if (norm != 0) { *why = "the MFMA compression kernel implements the softmax normalisation only"; return false; }
-  if (conv_width != 15) { *why = "the MFMA compression kernel is built for conv_width = 15"; return false; }
+  if (norm != 0 && norm != 1) { *why = "unknown normalisation"; return false; }
+  if (conv_width != 15 && conv_width != 21) {
+    *why = "the MFMA compression kernel is built for conv_width = 15 and 21";
+    return false;
+  }
   if (M % 32) { *why = "the MFMA compression kernel needs M to be a multiple of 32"; return false; }
   return true;
 }
@@ -646,9 +654,21 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
 }
 
 namespace {
-// 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles
-bool use_big_tiles(int batch, int Hkv, int M, int n_cu) {
-  return (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
+// 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles; the
+// filter slice of a 64-slot tile fits the registers for width 15 only
+bool use_big_tiles(int batch, int Hkv, int M, int k_width, int n_cu) {
+  return k_width == 15 && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
+}
+hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
+  const StepArgs& t = a.st;
+  const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
+  if (t.k_width == 15 && t.norm == 0)
+    return big ? launch_one<64, 15, 0>(a, wp, wp_head_stride, s) : launch_one<32, 15, 0>(a, wp, wp_head_stride, s);
+  if (t.k_width == 15 && t.norm == 1)
+    return big ? launch_one<64, 15, 1>(a, wp, wp_head_stride, s) : launch_one<32, 15, 1>(a, wp, wp_head_stride, s);
+  if (t.k_width == 21 && t.norm == 0) return launch_one<32, 21, 0>(a, wp, wp_head_stride, s);
+  if (t.k_width == 21 && t.norm == 1) return launch_one<32, 21, 1>(a, wp, wp_head_stride, s);
+  return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
 }
 }  // namespace
 
@@ -666,13 +686,11 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.status = nullptr;
   sa.spin_limit = 0;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
-  if (use_big_tiles(a.batch, a.Hkv, a.M, n_cu))
-    return launch_one<64, 15>(sa, (const uint16_t*)wp, wp_head_stride, s);
-  return launch_one<32, 15>(sa, (const uint16_t*)wp, wp_head_stride, s);
+  return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
 
-bool compress_scan_fits(int batch, int Hkv, int M, int n_cu) {
-  const int bm = use_big_tiles(batch, Hkv, M, n_cu) ? 64 : 32;
+bool compress_scan_fits(int batch, int Hkv, int M, int k_width, int n_cu) {
+  const int bm = use_big_tiles(batch, Hkv, M, k_width, n_cu) ? 64 : 32;
   // one workgroup per compute unit (LDS): every workgroup of the launch is resident at once
   return (int64_t)batch * Hkv * (M / bm) <= n_cu;
 }
@@ -693,9 +711,7 @@ hipError_t launch_compress_scan(const ScanArgs& a_in, const void* wp, int banks,
   a.sync = (uint32_t*)sync_ws;
   a.status = (int32_t*)sync_ws + chains;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD : 0;
-  if (use_big_tiles(a.st.batch, a.st.Hkv, a.st.M, n_cu))
-    return launch_one<64, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
-  return launch_one<32, 15>(a, (const uint16_t*)wp, wp_head_stride, s);
+  return dispatch(a, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
 
 }  // namespace lococo

@@ -100,7 +100,7 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
                                 hipStream_t s);
 // true if all steps of a scan can run in one launch (every workgroup resident at once)
-bool compress_scan_fits(int batch, int Hkv, int M, int n_cu);
+bool compress_scan_fits(int batch, int Hkv, int M, int k_width, int n_cu);
 // bytes of the sync counters + status word the scan launch needs
 size_t compress_scan_sync_bytes(int batch, int Hkv);
 // zero them (a fill kernel, so the call may sit inside a captured graph)

@@ -119,7 +119,7 @@ def test_mfma_step_by_step_equals_sequence_call():
 
 def test_mfma_is_refused_for_shapes_it_does_not_take():
     from paper_2406_05317_amd import binding as lb
-    for kw in (dict(head_dim=64), dict(conv_width=7), dict(conv_in=1), dict(norm=1), dict(M=100),
+    for kw in (dict(head_dim=64), dict(conv_width=7), dict(conv_in=1), dict(conv_width=61), dict(M=100),
                dict(dtype="f32")):
         w = _w(**kw)
         cfg = lb.config_for(w, impl=MFMA)
@@ -262,3 +262,23 @@ def test_prepared_filters_give_the_same_steps():
     for x, y in zip(outs[0][:3], outs[1][:3]):
         assert torch.equal(x, y)
     assert outs[0][3:] == outs[1][3:]
+
+
+@pytest.mark.parametrize("case", [
+    dict(conv_width=21),                                            # the paper's default width
+    dict(conv_width=21, L=500),                                     # ragged last block
+    dict(conv_width=21, M=96, B=80, L=400),                         # T = 176 not a tile multiple, M % 64 != 0
+    dict(conv_width=21, M=256, B=256, L=1024, n_q_heads=8, n_kv_heads=2, per_head_filters=True),
+    dict(norm=1, bias_sigma=0.5),                                   # relu-sum normalisation (Eq. 6 as printed)
+    dict(norm=1, bias_sigma=0.5, L=500),
+    dict(norm=1, conv_width=21, bias_sigma=0.5, M=128, B=160, L=480),
+    dict(norm=1, bias_sigma=0.5, batch=2, n_q_heads=32, n_kv_heads=32, M=256, B=128, L=512),   # 64-row tiles
+    dict(norm=1, conv_gain=6.0, bias_sigma=1.0, L=640),             # peaked, many exactly-zero weights
+])
+def test_mfma_paper_literal_variants(case):
+    """Width 21 and the relu-sum normalisation on the MFMA kernels, with the history schedule (one-launch
+    scan where it fits) and without."""
+    w = _w(**case)
+    for history in (False, True):
+        errs = _run(w, history=history)
+    print(case, {k: (f"{e[0]:.2e}", f"{e[1]:.2e}") for k, e in errs.items()})
