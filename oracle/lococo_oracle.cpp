@@ -32,15 +32,24 @@
 //   * conv_in = 0 feeds the keys only (C = d); conv_in = 1 feeds keys stacked
 //     on values along channels (C = 2d, Eq. 5 as printed), K channels first;
 //   * when the cache is partly full and cache + block exceeds M, the entries
-//     present (m + B_n of them) are compressed to M.
+//     present (m + B_n of them) are compressed to M;
+//   * combination with an eviction policy (the ablation that adds attention
+//     sinks or heavy hitters): the paper only says that such tokens are stored
+//     in addition.  Read here as a per-slot "protected" mark: a live protected
+//     slot is kept as it is by every compression step and its position
+//     carries no weight in the mixing of the other slots; attention sees all
+//     slots as before.  Which slots to protect (the first few tokens, the
+//     tokens with the largest accumulated attention) is the caller's policy.
 //
 // Pins (tests/test_oracle_*.py): brute-force full causal attention when the
 // sequence fits, sliding-window attention under one-hot logits, closed-form
 // mean recursion under zero filters, library conv1d / matmul / SDPA, row sums,
 // convexity, shift invariance, chain independence, resumability, plan vs.
-// simulation.  Fidelity to the authors' trained heads (normalisation variant,
-// ReLU placement, padding convention) is parity unpinned: their code and
-// weights are not available.
+// simulation; for protected slots: a numpy recursion with given logits, rows
+// that never change, all-protected = frozen cache.  Fidelity to the authors'
+// trained heads (normalisation variant, ReLU placement, padding convention)
+// and to their way of combining with eviction policies is parity unpinned:
+// their code and weights are not available.
 
 #include <algorithm>
 #include <cmath>
@@ -191,7 +200,7 @@ void segment_step_chain(const Cfg& cf, const double* q, int64_t q_head_stride,
                         const double* kb, const double* vb, int Bn, double* o,
                         int64_t o_head_stride, double* ck, double* cv, int* len,
                         const double* conv_w, const double* conv_b,
-                        const double* logits_override, int nthreads) {
+                        const double* logits_override, const uint8_t* protect, int nthreads) {
   const int d = cf.head_dim, M = cf.M, m = *len;
   const double scale = cf.attn_scale > 0.0 ? cf.attn_scale : 1.0 / std::sqrt((double)d);
   for (int h = 0; h < cf.group; ++h) {
@@ -224,13 +233,23 @@ void segment_step_chain(const Cfg& cf, const double* q, int64_t q_head_stride,
     std::memcpy(W.data(), logits_override, sizeof(double) * (size_t)M * T);
   else
     conv_logits(X.data(), T, C, conv_w, conv_b, M, cf.conv_width, W.data(), nthreads);
+  // Protected slots (combination with an eviction policy that keeps some tokens as they are:
+  // attention sinks, heavy hitters): a live protected slot is no input of the mixing -- its
+  // position carries no weight in any row -- and is not rewritten (below).
+  if (protect)
+    for (int j = 0; j < m; ++j)
+      if (protect[j])
+        for (int i = 0; i < M; ++i) W[(size_t)i * T + j] = -INFINITY;
   normalise_rows(W.data(), M, T, cf.norm, cf.norm_eps, w.data());
   std::vector<double> nk((size_t)M * d), nv((size_t)M * d);
   mix(w.data(), YK.data(), M, T, d, nk.data());
   mix(w.data(), YV.data(), M, T, d, nv.data());
-  for (size_t e = 0; e < (size_t)M * d; ++e) {
-    ck[e] = round_store(nk[e], cf.state_round);
-    cv[e] = round_store(nv[e], cf.state_round);
+  for (int i = 0; i < M; ++i) {
+    if (protect && i < m && protect[i]) continue;        // kept as it is
+    for (int c = 0; c < d; ++c) {
+      ck[(size_t)i * d + c] = round_store(nk[(size_t)i * d + c], cf.state_round);
+      cv[(size_t)i * d + c] = round_store(nv[(size_t)i * d + c], cf.state_round);
+    }
   }
   *len = M;
 }
@@ -294,13 +313,15 @@ void lococo_oracle_mix(const double* w, const double* Y, int32_t M, int32_t T, i
 //   logits_override null, or [n_compress_steps, batch, Hkv, M, M+B] (row
 //   stride M+B even when T is smaller) replacing Eq. 5's output.
 // Returns 0, or 1 on bad arguments.
-int32_t lococo_oracle_sequence_forward(const lococo_oracle_cfg* cfg, int32_t batch, int32_t Hkv,
-                                       int64_t L, int32_t B, const double* q, const double* k,
-                                       const double* v, double* o, double* cache_k,
-                                       double* cache_v, int32_t* len, const double* conv_w,
-                                       int64_t w_head_stride, const double* conv_b,
-                                       int64_t b_head_stride, const double* logits_override,
-                                       int32_t nthreads) {
+//   protect null, or one byte per slot ([M], + protect_chain_stride bytes per chain, 0 = one
+//   mask for all chains): non-zero = the slot, once live, is kept as it is by every
+//   compression step and carries no weight in the mixing of the other slots.
+int32_t lococo_oracle_sequence_forward_protected(
+    const lococo_oracle_cfg* cfg, int32_t batch, int32_t Hkv, int64_t L, int32_t B, const double* q,
+    const double* k, const double* v, double* o, double* cache_k, double* cache_v, int32_t* len,
+    const double* conv_w, int64_t w_head_stride, const double* conv_b, int64_t b_head_stride,
+    const double* logits_override, const uint8_t* protect, int64_t protect_chain_stride,
+    int32_t nthreads) {
   const Cfg cf = *cfg;
   const int d = cf.head_dim, M = cf.M, g = cf.group;
   if (d <= 0 || M <= 0 || g <= 0 || B <= 0 || L < 0 || cf.conv_width < 1 ||
@@ -336,7 +357,8 @@ int32_t lococo_oracle_sequence_forward(const lococo_oracle_cfg* cfg, int32_t bat
         ov = packed.data();
       }
       segment_step_chain(cf, qc + s * d, L * d, kc + s * d, vc + s * d, Bn, oc + s * d, L * d,
-                         ck, cv, &m, cw, cb, ov, inner);
+                         ck, cv, &m, cw, cb, ov, protect ? protect + ch * protect_chain_stride : nullptr,
+                         inner);
       if (compress) ++step;
     }
   });
@@ -347,6 +369,18 @@ int32_t lococo_oracle_sequence_forward(const lococo_oracle_cfg* cfg, int32_t bat
   }
   *len = m;
   return 0;
+}
+
+int32_t lococo_oracle_sequence_forward(const lococo_oracle_cfg* cfg, int32_t batch, int32_t Hkv,
+                                       int64_t L, int32_t B, const double* q, const double* k,
+                                       const double* v, double* o, double* cache_k,
+                                       double* cache_v, int32_t* len, const double* conv_w,
+                                       int64_t w_head_stride, const double* conv_b,
+                                       int64_t b_head_stride, const double* logits_override,
+                                       int32_t nthreads) {
+  return lococo_oracle_sequence_forward_protected(cfg, batch, Hkv, L, B, q, k, v, o, cache_k, cache_v,
+                                                  len, conv_w, w_head_stride, conv_b, b_head_stride,
+                                                  logits_override, nullptr, 0, nthreads);
 }
 
 }  // extern "C"

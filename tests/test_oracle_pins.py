@@ -496,3 +496,78 @@ def test_scan_with_given_logits_matches_a_numpy_recursion():
         c_k, c_v = w @ np.concatenate([c_k, kk[0, 0, blk]]), w @ np.concatenate([c_v, v[0, 0, blk]])
     np.testing.assert_allclose(ck[0, 0], c_k, rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(cv[0, 0], c_v, rtol=1e-11, atol=1e-13)
+
+
+# ---- protected slots (combination with an eviction policy)
+
+def test_protected_slots_match_a_numpy_recursion_with_given_logits():
+    """With Eq. 5's output given, the protected-slot reading written out in numpy: the softmax of
+    an unprotected row runs over the unprotected cache positions and the block only, a protected
+    row is carried over."""
+    rng = np.random.default_rng(31)
+    L, B, M, d = 48, 8, 8, 4
+    q, kk, v = rand(rng, 1, 1, L, d), rand(rng, 1, 1, L, d), rand(rng, 1, 1, L, d)
+    lo = rand(rng, 5, 1, 1, M, M + B, scale=2.0)
+    prot = np.array([1, 0, 0, 1, 0, 0, 0, 1], dtype=bool)
+    o, ck, cv, _ = orc.sequence_forward(q, kk, v, None, B=B, M=M, logits_override=lo, protect=prot)
+    c_k, c_v = kk[0, 0, :M].copy(), v[0, 0, :M].copy()
+    keep = np.concatenate([~prot, np.ones(B, dtype=bool)])           # positions that may carry weight
+    for n in range(1, L // B):
+        blk = slice(n * B, (n + 1) * B)
+        want_o = orc.attention_block(q[0, 0, blk], kk[0, 0, blk], v[0, 0, blk], c_k, c_v)
+        np.testing.assert_allclose(o[0, 0, blk], want_o, rtol=1e-10, atol=1e-13)   # attention sees every slot
+        e = np.exp(lo[n - 1, 0, 0][:, keep] - lo[n - 1, 0, 0][:, keep].max(axis=1, keepdims=True))
+        w = e / e.sum(axis=1, keepdims=True)
+        new_k = w @ np.concatenate([c_k, kk[0, 0, blk]])[keep]
+        new_v = w @ np.concatenate([c_v, v[0, 0, blk]])[keep]
+        c_k, c_v = np.where(prot[:, None], c_k, new_k), np.where(prot[:, None], c_v, new_v)
+    np.testing.assert_allclose(ck[0, 0], c_k, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(cv[0, 0], c_v, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("norm", [0, 1])
+def test_protected_rows_never_change_and_an_empty_mask_changes_nothing(norm):
+    rng = np.random.default_rng(32)
+    b, H, L, B, M, d, kw = 2, 2, 40, 4, 8, 4, 3
+    q, kk, v = rand(rng, b, H, L, d), rand(rng, b, H, L, d), rand(rng, b, H, L, d)
+    cw, cb = rand(rng, M, d, kw), rand(rng, M)
+    base = orc.sequence_forward(q, kk, v, cw, cb, B=B, M=M, norm=norm)
+    none = orc.sequence_forward(q, kk, v, cw, cb, B=B, M=M, norm=norm, protect=np.zeros(M, bool))
+    for x, y in zip(base[:3], none[:3]):
+        np.testing.assert_array_equal(x, y)
+    # per-chain masks: sinks (the first two tokens) on some chains, arbitrary slots on others
+    prot = np.zeros((b, H, M), bool)
+    prot[0, 0, :2] = True
+    prot[1, 1, [3, 6]] = True
+    o, ck, cv, ln = orc.sequence_forward(q, kk, v, cw, cb, B=B, M=M, norm=norm, protect=prot)
+    assert ln == M
+    # a protected slot still holds the token that filled it (slot i was filled by token i)
+    np.testing.assert_array_equal(ck[0, 0, :2], kk[0, 0, :2])
+    np.testing.assert_array_equal(cv[0, 0, :2], v[0, 0, :2])
+    np.testing.assert_array_equal(ck[1, 1, [3, 6]], kk[1, 1, [3, 6]])
+    # chains without protected slots are the unprotected scan, the others are not
+    np.testing.assert_array_equal(ck[0, 1], base[1][0, 1])
+    np.testing.assert_array_equal(o[1, 0], base[0][1, 0])
+    assert np.abs(ck[0, 0, 2:] - base[1][0, 0, 2:]).max() > 1e-6
+    # the unprotected rows stay convex combinations: inside the hull of everything seen
+    assert ck.max() <= kk.max() + 1e-12 and ck.min() >= kk.min() - 1e-12
+
+
+def test_a_fully_protected_cache_is_frozen_and_attention_still_sees_it():
+    """Every slot protected: the cache stays what the first M tokens made it (sinks only), and each
+    later block attends over those M tokens and itself."""
+    rng = np.random.default_rng(33)
+    L, B, M, d, kw = 32, 4, 8, 4, 5
+    q, kk, v = rand(rng, 1, 1, L, d), rand(rng, 1, 1, L, d), rand(rng, 1, 1, L, d)
+    cw = rand(rng, M, d, kw)
+    o, ck, cv, _ = orc.sequence_forward(q, kk, v, cw, B=B, M=M, protect=np.ones(M, bool))
+    np.testing.assert_array_equal(ck[0, 0], kk[0, 0, :M])
+    np.testing.assert_array_equal(cv[0, 0], v[0, 0, :M])
+    for n in range(M // B, L // B):
+        blk = slice(n * B, (n + 1) * B)
+        keys = np.concatenate([kk[0, 0, :M], kk[0, 0, blk]])
+        vals = np.concatenate([v[0, 0, :M], v[0, 0, blk]])
+        s = q[0, 0, blk] @ keys.T / np.sqrt(d)
+        s[:, M:] += np.where(np.tril(np.ones((B, B), bool)), 0.0, -np.inf)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        np.testing.assert_allclose(o[0, 0, blk], (p / p.sum(axis=1, keepdims=True)) @ vals, rtol=1e-10, atol=1e-13)
