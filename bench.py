@@ -177,6 +177,8 @@ def main():
                     help="step-by-step schedule instead of the batched-attention one")
     ap.add_argument("--conv-width", type=int, default=0, help="override the workload's filter width (e.g. 21)")
     ap.add_argument("--norm", type=int, default=-1, help="override the normalisation (0 softmax, 1 relu-sum)")
+    ap.add_argument("--protect-sinks", type=int, default=0,
+                    help="protect the first N cache slots (attention sinks kept beside the compressed memory)")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the prefill scan, time the generation stage: --steps segment steps "
                          "with B = 1 on a full cache, for this many sequences at once (0 = off)")
@@ -209,6 +211,9 @@ def main():
     qd, kd, vd, cwd, cbd = (t.to(dev) for t in (q, k, v, cw, cb))
     od = torch.empty_like(qd)
     cache = lb.Cache(cfg, dev)
+    if args.protect_sinks:
+        import numpy as np
+        cache.set_protect(np.arange(w.M) < args.protect_sinks)
     ws = lb.workspace(cfg, w.L, w.B, not args.no_history, dev)
     plan = lb.lococo_plan(w.L, w.B, w.M)
     flops = scan_flops(w, plan)
@@ -246,7 +251,8 @@ def main():
     part_flops = sum(flops[p] for p in KERNEL_PARTS.get(name, ())) * args.steps
     achieved = part_flops / (total_ms * 1e-3) / 1e12 if total_ms > 0 else 0.0
     roofline = {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": measured_traffic(name, args.workload) if w is inputs.CONFIGS[args.workload] else None,
+                "frac": achieved / peak, "traffic": measured_traffic(name, args.workload)
+                if w is inputs.CONFIGS[args.workload] and not args.protect_sinks else None,
                 "launches": launches,
                 "avg_launch_us": total_ms * 1e3 / max(launches, 1),
                 "flops_per_launch": part_flops / max(launches, 1),
@@ -262,6 +268,7 @@ def main():
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.L, "B": w.B,
                    "M": w.M, "conv_width": w.conv_width, "conv_channels": w.C,
                    "schedule": "step-by-step" if args.no_history else "batched-attention",
+                   "protected_slots": args.protect_sinks,
                    "impl": args.impl},
         "segment_step_tokens_per_s": w.batch * w.B / (ms_per_step * 1e-3 / len(plan)),
         "mfma_util_whole_path": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,

@@ -100,6 +100,16 @@ typedef struct lococo_cache {
   void* v[2];
   int32_t cur;  /* which of the two buffers is live (0/1)                             */
   int32_t len;  /* live slots 0..M, the same for every chain                          */
+  /* Protected slots, for combining the method with an eviction policy that keeps some tokens as
+   * they are (the ablation on attention sinks / heavy hitters; the paper does not spell the
+   * mechanism out, this is this library's reading).  Device pointer or NULL.  Bit (i % 32) of
+   * word [chain * protect_chain_stride + i / 32] set = slot i is protected: once live it is
+   * copied unchanged by every compression step (Eq. 4a/4b are not applied to it) and its
+   * position gets no weight in the other slots' rows of Eq. 6.  Attention (step 3) is not
+   * affected.  ceil(M / 32) words per mask; protect_chain_stride = 0 shares one mask between
+   * all (batch, kv head) chains.  The words are read when the kernels run. */
+  const uint32_t* protect;
+  int64_t protect_chain_stride;
 } lococo_cache;
 
 /* A [batch, heads, tokens, head_dim] tensor view; head_dim contiguous. */
@@ -187,7 +197,8 @@ lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace
  * [batch, n_kv_heads, M, T] contiguous with T = cache->len + B.  Only blk->k
  * and blk->v are read.  Exists so that tests can drive the fusion with chosen
  * weights (e.g. one-hot rows: token selection, the paper's "token dropping"
- * special case).  Always compresses, whatever the occupancy. */
+ * special case).  Always compresses, whatever the occupancy.  Returns LOCOCO_EUNSUPPORTED when
+ * cache->protect is set. */
 lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                      const float* logits, lococo_cache* cache, void* stream);
 

@@ -37,7 +37,7 @@ class lococo_config(C.Structure):
 
 class lococo_cache(C.Structure):
     _fields_ = [("k", C.c_void_p * 2), ("v", C.c_void_p * 2), ("cur", C.c_int32),
-                ("len", C.c_int32)]
+                ("len", C.c_int32), ("protect", C.c_void_p), ("protect_chain_stride", C.c_int64)]
 
 
 class lococo_tensor(C.Structure):
@@ -152,7 +152,9 @@ class Cache:
         self.vbuf = [torch.zeros(shape, dtype=dt, device=device) for _ in range(2)]
         self.c = lococo_cache((C.c_void_p * 2)(self.kbuf[0].data_ptr(), self.kbuf[1].data_ptr()),
                               (C.c_void_p * 2)(self.vbuf[0].data_ptr(), self.vbuf[1].data_ptr()),
-                              0, 0)
+                              0, 0, None, 0)
+        self.M, self.device = cfg.M, device
+        self._protect = None
 
     @property
     def len(self) -> int:
@@ -169,6 +171,23 @@ class Cache:
     @property
     def v(self) -> torch.Tensor:
         return self.vbuf[self.c.cur]
+
+    def set_protect(self, mask):
+        """mask: None, or a bool array/tensor [M] (one mask for every chain) or [batch, n_kv_heads, M]:
+        True = the slot is protected (see lococo_cache.protect in lococo.h)."""
+        if mask is None:
+            self._protect, self.c.protect, self.c.protect_chain_stride = None, None, 0
+            return
+        m = torch.as_tensor(mask).to(torch.bool).cpu()
+        words = (self.M + 31) // 32
+        flat = m.reshape(-1, self.M)
+        bits = torch.zeros(flat.shape[0], words * 32, dtype=torch.int64)
+        bits[:, :self.M] = flat.to(torch.int64)
+        w = (bits.reshape(flat.shape[0], words, 32) << torch.arange(32, dtype=torch.int64)).sum(-1)
+        w = torch.where(w >= 2 ** 31, w - 2 ** 32, w).to(torch.int32)
+        self._protect = w.to(self.device).contiguous()
+        self.c.protect = self._protect.data_ptr()
+        self.c.protect_chain_stride = 0 if m.dim() == 1 else words
 
     def load(self, k: torch.Tensor, v: torch.Tensor, length: int):
         self.kbuf[self.c.cur].copy_(k)

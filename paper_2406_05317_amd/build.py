@@ -26,7 +26,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
 # Per-file extras.  The compression kernel pins its filter slice to the accumulation registers;
 # with the VGPR form of the MFMA (accumulators in ordinary registers) nothing is copied between
 # the two register halves inside the loop.
-EXTRA = {"compress_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA = {"compress_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form",
+                                # the pipeline stages must be unrolled completely (the slices are
+                                # selected by compile-time slot numbers); the default size limit of
+                                # "#pragma unroll" is too small for the width-21 instantiation
+                                "-mllvm", "-pragma-unroll-threshold=200000"]}
 
 
 def _compile(src: str) -> str:

@@ -134,6 +134,11 @@ lococo_status check_cache(const lococo_config* c, const lococo_cache* ca) {
   if (ca->cur != 0 && ca->cur != 1) return fail(LOCOCO_ESTATE, "cache.cur is %d", ca->cur);
   if (ca->len < 0 || ca->len > c->M)
     return fail(LOCOCO_ESTATE, "cache.len %d is outside [0, M=%d]", ca->len, c->M);
+  if (ca->protect) {
+    if ((uintptr_t)ca->protect & 3) return fail(LOCOCO_EINVAL, "cache.protect is not 4-byte aligned");
+    if (ca->protect_chain_stride != 0 && ca->protect_chain_stride < (c->M + 31) / 32)
+      return fail(LOCOCO_EINVAL, "cache.protect_chain_stride must be 0 or at least ceil(M / 32) words");
+  }
   return LOCOCO_OK;
 }
 
@@ -261,6 +266,8 @@ StepArgs make_args(const lococo_config* c, const lococo_qkvo* x, int64_t tok, in
   a.norm = c->norm;
   a.scale = c->attn_scale > 0.f ? c->attn_scale : 1.0f / std::sqrt((float)c->head_dim);
   a.eps = c->norm_eps > 0.f ? c->norm_eps : 1e-6f;
+  a.protect = ca->protect;
+  a.protect_stride = ca->protect_chain_stride;
   return a;
 }
 
@@ -342,6 +349,7 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
     KTimer t(K_CONV_GENERIC, s);
     HIP_TRY(launch_conv_logits_generic(c->dtype, a, logits, s), "conv launch");
   }
+  if (a.protect) HIP_TRY(launch_protect_logits_generic(a, logits, s), "protect launch");
   {
     KTimer t(K_NORM_GENERIC, s);
     HIP_TRY(launch_normalise_generic(a, logits, s), "normalise launch");
@@ -350,6 +358,7 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
     KTimer t(K_MIX_GENERIC, s);
     HIP_TRY(launch_mix_generic(c->dtype, a, logits, 0, s), "mix launch");
   }
+  if (a.protect) HIP_TRY(launch_protect_rows_generic(c->dtype, a, s), "protect launch");
   ca->cur ^= 1;
   ca->len = a.M;
   return LOCOCO_OK;
@@ -659,6 +668,8 @@ lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo
   if ((st = check_step_shape(cfg, B, cache->len))) return st;
   if ((st = check_qkvo(cfg, blk, B, false))) return st;
   if (!logits) return fail(LOCOCO_EINVAL, "logits is NULL");
+  if (cache->protect)
+    return fail(LOCOCO_EUNSUPPORTED, "lococo_mix_from_logits does not take protected slots");
   StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, false);
   a.new_k = cache->k[cache->cur ^ 1];
   a.new_v = cache->v[cache->cur ^ 1];

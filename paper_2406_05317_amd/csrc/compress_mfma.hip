@@ -158,7 +158,9 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // load instruction of the prologue reads 1 KB of contiguous memory.
 // NORM = 0: softmax over the positions; NORM = 1: relu(W) / (sum of relu(W) + eps) (Eq. 6 as printed,
 // with the rectifier of the convolution head in front of it).
-template <int BM, int KW, int NORM>
+// PROT = 1: the cache carries protected slots (lococo_cache.protect); a build of its own so that the
+// common case pays neither the registers nor the instructions.
+template <int BM, int KW, int NORM, int PROT>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
@@ -185,6 +187,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // per-step quantities, set at the top of the step loop
   int T = 0, m = 0, NT = 0;
   CatRows cat_k, cat_v;
+  const uint16_t *cat_k_rows = nullptr, *cat_v_rows = nullptr;   // the chain's source cache rows
+  // protected-slot bits of this chain (see lococo_cache.protect), or null
+  const uint32_t* pwords = PROT ? a.protect + (int64_t)ch * a.protect_stride : nullptr;
 
   // ---- this wave's slice of the filter bank, resident in registers for the whole kernel:
   // lane (slot l31 of tile rt, channels 32w + 16h + 8*lh ..) for every tap
@@ -304,6 +309,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       const int s2 = st < G::NS ? st : st - G::NS;
       xv[st % kRing] = *(const bf16x8*)(xb + (s2 >> 1) * G::XSTRIDE + (s2 & 1) * 32);
     };
+    // protected positions of tile i (bits of live protected slots; BN = 32 = one mask word)
+    uint32_t pmask = 0;
+    if (PROT && DoSoftmax && j0 < m) {
+      pmask = pwords[j0 >> 5];
+      if (j0 + BN > m) pmask &= (1u << (m - j0)) - 1u;
+    }
     // softmax of tile i
     constexpr int E4 = G::EPL / 4;
     f32x4 part[4][E4];
@@ -384,6 +395,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
             for (int e = 0; e < G::EPL; ++e)
               if (j0 + sp0 + e >= T) sv[e] = NORM == 0 ? -INFINITY : 0.f;
           }
+          if (PROT && pmask) {                 // neither do the positions of protected slots
+#pragma unroll
+            for (int e = 0; e < G::EPL; ++e)
+              if ((pmask >> (sp0 + e)) & 1u) sv[e] = NORM == 0 ? -INFINITY : 0.f;
+          }
           if (NORM == 0) {
             mx = sv[0];
 #pragma unroll
@@ -394,11 +410,13 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         if (NORM == 0 && slot == 8 * S + 2 * E4 + 3) {
           // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref)
           // stays below e^kLazy and the accumulators are rescaled rarely.  Every tile has a
-          // position < T, so mx is finite.
-          bump = mx > m_run + kLazy;
+          // position < T, so mx is finite -- unless all 32 positions of the tile are protected
+          // slots: such a tile adds nothing and leaves the reference alone.
+          const bool dead = PROT && mx == -INFINITY;
+          bump = !dead && mx > m_run + kLazy;
           m_new = bump ? mx : m_run;
           alpha = bump ? __expf(m_run - m_new) : 1.0f;
-          mc = m_new * kLog2e;
+          mc = dead ? 0.f : m_new * kLog2e;
         }
         constexpr int X0 = 8 * S + 2 * E4 + 4;   // one exponential per slot
         if (slot >= X0 && slot < X0 + G::EPL) sm_exp(slot - X0);
@@ -496,6 +514,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
                                       : (const uint16_t*)sa.out_k + (int64_t)(step - 1) * sa.out_stride;
     const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v
                                       : (const uint16_t*)sa.out_v + (int64_t)(step - 1) * sa.out_stride;
+    cat_k_rows = src_k + (int64_t)ch * a.M * kD;
+    cat_v_rows = src_v + (int64_t)ch * a.M * kD;
     cat_k = make_cat(src_k + (int64_t)ch * a.M * kD, m,
                      (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + tok * a.k.st, a.k.st, Bn);
     cat_v = make_cat(src_v + (int64_t)ch * a.M * kD, m,
@@ -546,6 +566,24 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
 #pragma unroll
   for (int rt = 0; rt < G::RT; ++rt) {
     const int slot = rt * 32 + l31;
+    // a live protected slot keeps its old row (copied below) instead of Eq. 4a / 4b
+    uint32_t keep = 0;
+    if (PROT && i0 + rt * 32 < m) {
+      keep = pwords[(i0 >> 5) + rt];
+      if (i0 + rt * 32 + 32 > m) keep &= (1u << (m - i0 - rt * 32)) - 1u;
+    }
+    if (keep) {
+      const uint16_t* sk = cat_k_rows + (int64_t)(i0 + rt * 32) * kD;
+      const uint16_t* sv_ = cat_v_rows + (int64_t)(i0 + rt * 32) * kD;
+      for (int e = tid; e < 32 * 16; e += kThreads) {        // (slot, 16-byte chunk)
+        const int r = e >> 4, c16 = e & 15;
+        if ((keep >> r) & 1u) {
+          *(u32x4*)(nk + (int64_t)(rt * 32 + r) * kD + c16 * 8) = *(const u32x4*)(sk + (int64_t)r * kD + c16 * 8);
+          *(u32x4*)(nv + (int64_t)(rt * 32 + r) * kD + c16 * 8) = *(const u32x4*)(sv_ + (int64_t)r * kD + c16 * 8);
+        }
+      }
+      if ((keep >> l31) & 1u) continue;
+    }
     const float inv = 1.0f / (NORM == 0 ? lsum[slot] : lsum[slot] + a.eps);
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
@@ -609,18 +647,18 @@ __global__ void zero_words_k(uint32_t* p, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-template <int BM, int KW, int NORM>
+template <int BM, int KW, int NORM, int PROT>
 hipError_t launch_one(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
   using G = Geo<BM, KW>;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid((a.st.M / BM) * a.st.batch * a.st.Hkv);
-  hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
+  hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
   return hipGetLastError();
 }
 
@@ -659,16 +697,21 @@ namespace {
 bool use_big_tiles(int batch, int Hkv, int M, int k_width, int n_cu) {
   return k_width == 15 && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
 }
-hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
+template <int PROT>
+hipError_t dispatch_shape(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
   const StepArgs& t = a.st;
   const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
   if (t.k_width == 15 && t.norm == 0)
-    return big ? launch_one<64, 15, 0>(a, wp, wp_head_stride, s) : launch_one<32, 15, 0>(a, wp, wp_head_stride, s);
+    return big ? launch_one<64, 15, 0, PROT>(a, wp, wp_head_stride, s) : launch_one<32, 15, 0, PROT>(a, wp, wp_head_stride, s);
   if (t.k_width == 15 && t.norm == 1)
-    return big ? launch_one<64, 15, 1>(a, wp, wp_head_stride, s) : launch_one<32, 15, 1>(a, wp, wp_head_stride, s);
-  if (t.k_width == 21 && t.norm == 0) return launch_one<32, 21, 0>(a, wp, wp_head_stride, s);
-  if (t.k_width == 21 && t.norm == 1) return launch_one<32, 21, 1>(a, wp, wp_head_stride, s);
+    return big ? launch_one<64, 15, 1, PROT>(a, wp, wp_head_stride, s) : launch_one<32, 15, 1, PROT>(a, wp, wp_head_stride, s);
+  if (t.k_width == 21 && t.norm == 0) return launch_one<32, 21, 0, PROT>(a, wp, wp_head_stride, s);
+  if (t.k_width == 21 && t.norm == 1) return launch_one<32, 21, 1, PROT>(a, wp, wp_head_stride, s);
   return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
+}
+hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
+  return a.st.protect ? dispatch_shape<1>(a, wp, wp_head_stride, n_cu, s)
+                      : dispatch_shape<0>(a, wp, wp_head_stride, n_cu, s);
 }
 }  // namespace
 

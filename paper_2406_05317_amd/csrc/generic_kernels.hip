@@ -3,6 +3,8 @@
 // They are the fp32 path of the library and the fallback for shapes the MFMA
 // kernels do not take.  One thread (or one workgroup) per output element,
 // straight from the definitions (Eq. 1, Eq. 4a/4b, Eq. 5, Eq. 6).
+#include <algorithm>
+
 #include "lococo_internal.h"
 
 namespace lococo {
@@ -215,6 +217,33 @@ __global__ __launch_bounds__(kThreads) void mix_generic_k(StepArgs a, const floa
   }
 }
 
+// Protected slots (see lococo_cache.protect): positions of live protected slots get no weight ...
+__device__ __forceinline__ bool slot_protected(const StepArgs& a, int ch, int i) {
+  return i < a.m && ((a.protect[(int64_t)ch * a.protect_stride + (i >> 5)] >> (i & 31)) & 1u);
+}
+__global__ __launch_bounds__(kThreads) void protect_logits_generic_k(StepArgs a, float* logits) {
+  const int Tn = a.m + a.Bn, ch = blockIdx.y;
+  float* rows = logits + (int64_t)ch * a.M * Tn;
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < (int64_t)a.M * a.m;
+       e += (int64_t)gridDim.x * kThreads) {
+    const int i = (int)(e / a.m), j = (int)(e % a.m);
+    if (slot_protected(a, ch, j)) rows[(int64_t)i * Tn + j] = -INFINITY;
+  }
+}
+// ... and the rows of live protected slots are carried over from the old cache.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void protect_rows_generic_k(StepArgs a) {
+  const int ch = blockIdx.y;
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < (int64_t)a.m * a.d;
+       e += (int64_t)gridDim.x * kThreads) {
+    const int i = (int)(e / a.d);
+    if (!slot_protected(a, ch, i)) continue;
+    const int64_t at = (int64_t)ch * a.M * a.d + e;
+    ((T*)a.new_k)[at] = ((const T*)a.cache_k)[at];
+    ((T*)a.new_v)[at] = ((const T*)a.cache_v)[at];
+  }
+}
+
 }  // namespace
 
 // scores (T floats) + query row (d <= 1024 floats) stay within 60 KB of LDS
@@ -254,6 +283,25 @@ hipError_t launch_conv_logits_generic(int dtype, const StepArgs& a, float* logit
 hipError_t launch_normalise_generic(const StepArgs& a, float* logits, hipStream_t s) {
   dim3 grid(a.M, a.batch * a.Hkv);
   hipLaunchKernelGGL(normalise_generic_k, grid, dim3(kThreads), 0, s, a, logits);
+  return hipGetLastError();
+}
+
+hipError_t launch_protect_logits_generic(const StepArgs& a, float* logits, hipStream_t s) {
+  if (a.m == 0) return hipSuccess;
+  const int64_t n = (int64_t)a.M * a.m;
+  dim3 grid((unsigned)std::min<int64_t>((n + kThreads - 1) / kThreads, 1024), a.batch * a.Hkv);
+  hipLaunchKernelGGL(protect_logits_generic_k, grid, dim3(kThreads), 0, s, a, logits);
+  return hipGetLastError();
+}
+
+hipError_t launch_protect_rows_generic(int dtype, const StepArgs& a, hipStream_t s) {
+  if (a.m == 0) return hipSuccess;
+  const int64_t n = (int64_t)a.m * a.d;
+  dim3 grid((unsigned)std::min<int64_t>((n + kThreads - 1) / kThreads, 1024), a.batch * a.Hkv);
+  if (dtype == LOCOCO_F32)
+    hipLaunchKernelGGL(protect_rows_generic_k<float>, grid, dim3(kThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(protect_rows_generic_k<bf16_t>, grid, dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

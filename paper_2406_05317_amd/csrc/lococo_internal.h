@@ -33,6 +33,8 @@ struct StepArgs {
   int32_t k_width;         // conv width
   int32_t conv_in, norm;
   float scale, eps;
+  const uint32_t* protect;     // protected-slot bits (see lococo_cache), or null
+  int64_t protect_stride;      // words between chains' masks, 0 = shared
 };
 
 // Arguments of the fused compression kernel: `n_steps` consecutive compress steps of the scan in
@@ -84,6 +86,10 @@ hipError_t launch_normalise_generic(const StepArgs& a, float* logits, hipStream_
 // raw != 0: w holds unnormalised logits, Eq. 6 is applied inside the kernel
 hipError_t launch_mix_generic(int dtype, const StepArgs& a, const float* w, int raw,
                               hipStream_t s);
+// protected slots on the generic path: logits of protected positions -> -inf (before the
+// normalisation); protected rows of the new cache <- the old rows (after the mix)
+hipError_t launch_protect_logits_generic(const StepArgs& a, float* logits, hipStream_t s);
+hipError_t launch_protect_rows_generic(int dtype, const StepArgs& a, hipStream_t s);
 // largest T = m + Bn the generic attention kernel can hold in LDS
 int generic_attn_max_T();
 

@@ -33,7 +33,7 @@ def to_np(t: torch.Tensor) -> np.ndarray:
 
 
 def oracle_forward(w: inputs.Workload, q, k, v, cw, cb, *, B=None, cache=None, nthreads=8,
-                   state_round=None):
+                   state_round=None, protect=None):
     """Oracle scan on CPU tensors in storage dtype; state rounded to the storage grid."""
     ck = cv = None
     ln = 0
@@ -41,11 +41,11 @@ def oracle_forward(w: inputs.Workload, q, k, v, cw, cb, *, B=None, cache=None, n
         ck, cv, ln = cache
     return orc.sequence_forward(q, k, v, cw, cb, B=B or w.B, M=w.M, conv_in=w.conv_in, norm=w.norm,
                                 state_round=state_round or w.dtype, cache_k=ck, cache_v=cv,
-                                cache_len=ln, nthreads=nthreads)
+                                cache_len=ln, protect=protect, nthreads=nthreads)
 
 
 def gpu_forward(w: inputs.Workload, q, k, v, cw, cb, *, B=None, impl=0, history=False,
-                cache_init=None, step_by_step=False):
+                cache_init=None, step_by_step=False, protect=None):
     """HIP path through the binding.  Returns (o, cache_k, cache_v, len, cur) as CPU tensors."""
     from paper_2406_05317_amd import binding as lb
     dev = "cuda"
@@ -56,6 +56,7 @@ def gpu_forward(w: inputs.Workload, q, k, v, cw, cb, *, B=None, impl=0, history=
     cbd = None if cb is None else cb.to(dev).contiguous()
     od = torch.full_like(qd, float("nan"))
     cache = lb.Cache(cfg, dev)
+    cache.set_protect(protect)
     if cache_init is not None:
         ck, cv, ln = cache_init
         cache.load(torch.as_tensor(ck).to(dev, w.torch_dtype), torch.as_tensor(cv).to(dev, w.torch_dtype), ln)

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     # sizes the C compiler gives for the header's structs (LP64, natural alignment)
     assert C.sizeof(lb.lococo_config) == 72
-    assert C.sizeof(lb.lococo_cache) == 40
+    assert C.sizeof(lb.lococo_cache) == 56
     assert C.sizeof(lb.lococo_tensor) == 32
     assert C.sizeof(lb.lococo_qkvo) == 128
     assert C.sizeof(lb.lococo_seg) == 32
@@ -114,6 +114,11 @@ def test_call_argument_errors_enqueue_nothing():
     cache.cur = 3
     assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_ESTATE
     cache.cur = 0
+    cache.protect = 0x70002                            # misaligned mask pointer
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    cache.protect, cache.protect_chain_stride = 0x70000, -1
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    cache.protect, cache.protect_chain_stride = None, 0
     assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 0, C.byref(cache), None) == lb.LOCOCO_EINVAL
     assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
     assert b"q pointer" in L.lococo_last_error()
