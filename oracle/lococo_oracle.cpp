@@ -7,7 +7,9 @@
 //   step 4  1-D convolution over [cache; block] -> logits,  (Eq. 5)
 //           normalised per slot over the positions          (Eq. 6)
 //   step 5  weighted fusion of K and V with shared weights  (Eq. 4a / 4b, Eq. 3)
-// and the scan of that step over a sequence (Alg. 2 loop).
+// and the scan of that step over a sequence (Alg. 2 loop), plus the backward
+// pass of one step (chain rule on the same definitions; the fine-tuning of the
+// convolution heads needs it).
 //
 // Only the tests, the smoke check and the benchmark's cpu_baseline leg may
 // call this file.  It shares no code, header, table or helper with the HIP
@@ -46,7 +48,9 @@
 // mean recursion under zero filters, library conv1d / matmul / SDPA, row sums,
 // convexity, shift invariance, chain independence, resumability, plan vs.
 // simulation; for protected slots: a numpy recursion with given logits, rows
-// that never change, all-protected = frozen cache.  Fidelity to the authors'
+// that never change, all-protected = frozen cache; for the backward pass:
+// central finite differences of the forward pass, every input, every branch
+// and variant.  Fidelity to the authors'
 // trained heads (normalisation variant, ReLU placement, padding convention)
 // and to their way of combining with eviction policies is parity unpinned:
 // their code and weights are not available.
@@ -254,6 +258,148 @@ void segment_step_chain(const Cfg& cf, const double* q, int64_t q_head_stride,
   *len = M;
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Backward of one pass of the Alg. 2 loop body for one chain (training the convolution heads
+// through the scan: the fine-tuning the paper runs on the heads).  Plain chain rule on the
+// definitions above, storage rounding treated as the identity.
+//   given   dO [g, Bn, d], dNewK, dNewV [M, d]   (gradients of a scalar loss)
+//   returns dq [g, Bn, d], dkb, dvb [Bn, d], dck, dcv [M, d] (rows >= m zero unless the step fills),
+//           and adds into dWc [M, C, k], db [M].
+void segment_step_backward_chain(const Cfg& cf, const double* q, int64_t q_head_stride,
+                                 const double* kb, const double* vb, int Bn, const double* ck,
+                                 const double* cv, int m, const double* conv_w, const double* conv_b,
+                                 const uint8_t* protect, const double* dO, int64_t do_head_stride,
+                                 const double* dNewK, const double* dNewV, double* dq,
+                                 int64_t dq_head_stride, double* dkb, double* dvb, double* dck,
+                                 double* dcv, double* dWc, double* db) {
+  const int d = cf.head_dim, M = cf.M, T = m + Bn;
+  const double scale = cf.attn_scale > 0.0 ? cf.attn_scale : 1.0 / std::sqrt((double)d);
+  std::vector<double> YK((size_t)T * d), YV((size_t)T * d), dYK((size_t)T * d, 0.0), dYV((size_t)T * d, 0.0);
+  std::memcpy(YK.data(), ck, sizeof(double) * (size_t)m * d);
+  std::memcpy(YV.data(), cv, sizeof(double) * (size_t)m * d);
+  std::memcpy(YK.data() + (size_t)m * d, kb, sizeof(double) * (size_t)Bn * d);
+  std::memcpy(YV.data() + (size_t)m * d, vb, sizeof(double) * (size_t)Bn * d);
+
+  // ---- attention (Alg. 2 step 3): O[r] = sum_j P[r, j] Yv[j], P = softmax over the visible j
+  std::vector<double> p(T), dp(T);
+  for (int h = 0; h < cf.group; ++h)
+    for (int r = 0; r < Bn; ++r) {
+      const double* qr = q + h * q_head_stride + (size_t)r * d;
+      const double* dor = dO + h * do_head_stride + (size_t)r * d;
+      double* dqr = dq + h * dq_head_stride + (size_t)r * d;
+      const int n_vis = m + r + 1;
+      double mx = -std::numeric_limits<double>::infinity(), z = 0.0;
+      for (int j = 0; j < n_vis; ++j) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += qr[c] * YK[(size_t)j * d + c];
+        p[j] = acc * scale;
+        mx = std::max(mx, p[j]);
+      }
+      for (int j = 0; j < n_vis; ++j) { p[j] = std::exp(p[j] - mx); z += p[j]; }
+      double dot = 0.0;                               // sum_j P_j dP_j
+      for (int j = 0; j < n_vis; ++j) {
+        p[j] /= z;
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += dor[c] * YV[(size_t)j * d + c];
+        dp[j] = acc;
+        dot += p[j] * acc;
+      }
+      for (int c = 0; c < d; ++c) dqr[c] = 0.0;
+      for (int j = 0; j < n_vis; ++j) {
+        const double ds = p[j] * (dp[j] - dot) * scale;     // d loss / d (q . k_j)
+        for (int c = 0; c < d; ++c) {
+          dqr[c] += ds * YK[(size_t)j * d + c];
+          dYK[(size_t)j * d + c] += ds * qr[c];
+          dYV[(size_t)j * d + c] += p[j] * dor[c];
+        }
+      }
+    }
+
+  if (m + Bn <= M) {
+    // ---- fill branch: the new cache is [cache ; block]
+    for (int j = 0; j < T; ++j)
+      for (int c = 0; c < d; ++c) {
+        dYK[(size_t)j * d + c] += dNewK[(size_t)j * d + c];
+        dYV[(size_t)j * d + c] += dNewV[(size_t)j * d + c];
+      }
+  } else {
+    // ---- steps 4-5: W = conv(X) (Eq. 5), w = normalise(W) (Eq. 6), new = w Y (Eq. 4a / 4b)
+    const int C = cf.conv_in ? 2 * d : d, k = cf.conv_width, pad = (k - 1) / 2;
+    std::vector<double> X((size_t)T * C), W((size_t)M * T), w((size_t)M * T), dW((size_t)M * T);
+    for (int j = 0; j < T; ++j) {
+      for (int c = 0; c < d; ++c) X[(size_t)j * C + c] = YK[(size_t)j * d + c];
+      if (cf.conv_in)
+        for (int c = 0; c < d; ++c) X[(size_t)j * C + d + c] = YV[(size_t)j * d + c];
+    }
+    conv_logits(X.data(), T, C, conv_w, conv_b, M, k, W.data(), 1);
+    if (protect)
+      for (int j = 0; j < m; ++j)
+        if (protect[j])
+          for (int i = 0; i < M; ++i) W[(size_t)i * T + j] = -INFINITY;
+    normalise_rows(W.data(), M, T, cf.norm, cf.norm_eps, w.data());
+    for (int i = 0; i < M; ++i) {
+      const double* gk = dNewK + (size_t)i * d;
+      const double* gv = dNewV + (size_t)i * d;
+      double* dWi = dW.data() + (size_t)i * T;
+      if (protect && i < m && protect[i]) {           // the row was carried over
+        for (int c = 0; c < d; ++c) {
+          dYK[(size_t)i * d + c] += gk[c];
+          dYV[(size_t)i * d + c] += gv[c];
+        }
+        for (int j = 0; j < T; ++j) dWi[j] = 0.0;
+        continue;
+      }
+      const double* wi = w.data() + (size_t)i * T;
+      double dot = 0.0, zsum = 0.0;
+      std::vector<double> dwv(T);
+      for (int j = 0; j < T; ++j) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c)
+          acc += gk[c] * YK[(size_t)j * d + c] + gv[c] * YV[(size_t)j * d + c];
+        dwv[j] = acc;                                 // d loss / d w[i, j]
+        dot += wi[j] * acc;
+        for (int c = 0; c < d; ++c) {
+          dYK[(size_t)j * d + c] += wi[j] * gk[c];
+          dYV[(size_t)j * d + c] += wi[j] * gv[c];
+        }
+      }
+      if (cf.norm == 0) {
+        for (int j = 0; j < T; ++j) dWi[j] = wi[j] * (dwv[j] - dot);
+      } else {
+        // w = r / (z + eps), r = relu(W), z = sum r
+        for (int j = 0; j < T; ++j) zsum += std::isfinite(W[(size_t)i * T + j]) && W[(size_t)i * T + j] > 0.0 ? W[(size_t)i * T + j] : 0.0;
+        for (int j = 0; j < T; ++j)
+          dWi[j] = W[(size_t)i * T + j] > 0.0 ? (dwv[j] - dot) / (zsum + cf.norm_eps) : 0.0;
+      }
+    }
+    // Eq. 5 backwards: bias, filters, input
+    for (int i = 0; i < M; ++i) {
+      const double* dWi = dW.data() + (size_t)i * T;
+      for (int j = 0; j < T; ++j) {
+        const double g = dWi[j];
+        if (g == 0.0) continue;
+        if (db) db[i] += g;
+        for (int t = 0; t < k; ++t) {
+          const int jj = j + t - pad;
+          if (jj < 0 || jj >= T) continue;
+          for (int c = 0; c < C; ++c) {
+            dWc[((size_t)i * C + c) * k + t] += g * X[(size_t)jj * C + c];
+            const double gx = g * conv_w[((size_t)i * C + c) * k + t];
+            if (c < d) dYK[(size_t)jj * d + c] += gx;
+            else dYV[(size_t)jj * d + (c - d)] += gx;
+          }
+        }
+      }
+    }
+  }
+  for (size_t e = 0; e < (size_t)M * d; ++e) dck[e] = dcv[e] = 0.0;
+  std::memcpy(dck, dYK.data(), sizeof(double) * (size_t)m * d);
+  std::memcpy(dcv, dYV.data(), sizeof(double) * (size_t)m * d);
+  std::memcpy(dkb, dYK.data() + (size_t)m * d, sizeof(double) * (size_t)Bn * d);
+  std::memcpy(dvb, dYV.data() + (size_t)m * d, sizeof(double) * (size_t)Bn * d);
+}
+
 }  // namespace
 
 extern "C" {
@@ -381,6 +527,38 @@ int32_t lococo_oracle_sequence_forward(const lococo_oracle_cfg* cfg, int32_t bat
   return lococo_oracle_sequence_forward_protected(cfg, batch, Hkv, L, B, q, k, v, o, cache_k, cache_v,
                                                   len, conv_w, w_head_stride, conv_b, b_head_stride,
                                                   logits_override, nullptr, 0, nthreads);
+}
+
+// Backward of ONE block step over all chains (the caller walks the scan in reverse with the cache
+// states it kept).  Layouts as in the forward; q, dO, dq [batch, Hkv*group, Bn, d]; kb, vb, dkb,
+// dvb [batch, Hkv, Bn, d]; cache_k/v (state BEFORE the step), d_new_k/v, d_cache_k/v
+// [batch, Hkv, M, d]; d_conv_w [M, C, k] (+ w_head_stride per kv head) and d_conv_b are ADDED to
+// (d_conv_b may be null).  len = live slots before the step.  Returns 0, or 1 on bad arguments.
+int32_t lococo_oracle_step_backward(const lococo_oracle_cfg* cfg, int32_t batch, int32_t Hkv, int32_t Bn,
+                                    const double* q, const double* kb, const double* vb,
+                                    const double* cache_k, const double* cache_v, int32_t len,
+                                    const double* conv_w, int64_t w_head_stride, const double* conv_b,
+                                    int64_t b_head_stride, const uint8_t* protect,
+                                    int64_t protect_chain_stride, const double* dO, const double* d_new_k,
+                                    const double* d_new_v, double* dq, double* dkb, double* dvb,
+                                    double* d_cache_k, double* d_cache_v, double* d_conv_w,
+                                    double* d_conv_b) {
+  const Cfg cf = *cfg;
+  const int d = cf.head_dim, M = cf.M, g = cf.group;
+  if (d <= 0 || M <= 0 || g <= 0 || Bn <= 0 || len < 0 || len > M) return 1;
+  if (len + Bn > M && !conv_w) return 1;
+  for (int64_t ch = 0; ch < (int64_t)batch * Hkv; ++ch) {     // serial: chains add into shared filter gradients
+    const int64_t h = ch % Hkv;
+    segment_step_backward_chain(
+        cf, q + ch * g * Bn * d, (int64_t)Bn * d, kb + ch * Bn * d, vb + ch * Bn * d, Bn,
+        cache_k + ch * (int64_t)M * d, cache_v + ch * (int64_t)M * d, len,
+        conv_w ? conv_w + h * w_head_stride : nullptr, conv_b ? conv_b + h * b_head_stride : nullptr,
+        protect ? protect + ch * protect_chain_stride : nullptr, dO + ch * g * Bn * d, (int64_t)Bn * d,
+        d_new_k + ch * (int64_t)M * d, d_new_v + ch * (int64_t)M * d, dq + ch * g * Bn * d, (int64_t)Bn * d,
+        dkb + ch * Bn * d, dvb + ch * Bn * d, d_cache_k + ch * (int64_t)M * d, d_cache_v + ch * (int64_t)M * d,
+        d_conv_w ? d_conv_w + h * w_head_stride : nullptr, d_conv_b ? d_conv_b + h * b_head_stride : nullptr);
+  }
+  return 0;
 }
 
 }  // extern "C"

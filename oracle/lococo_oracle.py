@@ -65,6 +65,10 @@ def lib():
             C.POINTER(Cfg), C.c_int32, C.c_int32, C.c_int64, C.c_int32, _DP, _DP, _DP, _DP, _DP,
             _DP, C.POINTER(C.c_int32), _DP, C.c_int64, _DP, C.c_int64, _DP,
             C.POINTER(C.c_uint8), C.c_int64, C.c_int32]
+        L.lococo_oracle_step_backward.restype = C.c_int32
+        L.lococo_oracle_step_backward.argtypes = (
+            [C.POINTER(Cfg), C.c_int32, C.c_int32, C.c_int32] + [_DP] * 5 + [C.c_int32, _DP, C.c_int64, _DP,
+             C.c_int64, C.POINTER(C.c_uint8), C.c_int64] + [_DP] * 10)
         _lib = L
     return _lib
 
@@ -197,3 +201,46 @@ def sequence_forward(q, k, v, conv_w, conv_b=None, *, B: int, M: int, conv_in: i
     if rc != 0:
         raise ValueError("oracle: bad arguments")
     return o, ck, cv, ln.value
+
+
+def step_backward(q, kb, vb, cache_k, cache_v, cache_len, conv_w, conv_b, d_o, d_new_k, d_new_v, *,
+                  M: int, conv_in: int = 0, norm: int = 0, attn_scale: float = 0.0,
+                  norm_eps: float = 1e-6, protect=None):
+    """Gradients of one pass of the Alg. 2 loop body (storage rounding ignored).
+
+    q, d_o [b,Hq,Bn,d]; kb, vb [b,Hkv,Bn,d]; cache_k, cache_v [b,Hkv,M,d] with cache_len live
+    rows BEFORE the step; d_new_k, d_new_v [b,Hkv,M,d] gradients w.r.t. the cache AFTER the step.
+    Returns dict(dq, dk, dv, d_cache_k, d_cache_v, d_conv_w, d_conv_b); the filter gradients are
+    sums over chains (per kv head if conv_w is [Hkv,M,C,k]).
+    """
+    q, kb, vb, ck, cv = _f64(q), _f64(kb), _f64(vb), _f64(cache_k), _f64(cache_v)
+    d_o, gk, gv = _f64(d_o), _f64(d_new_k), _f64(d_new_v)
+    b, Hq, Bn, d = q.shape
+    Hkv = kb.shape[1]
+    cw = None if conv_w is None else _f64(conv_w)
+    cb = None if conv_b is None else _f64(conv_b)
+    w_stride = b_stride = 0
+    kw = 1
+    if cw is not None:
+        kw = cw.shape[-1]
+        if cw.ndim == 4:
+            w_stride = cw.shape[1] * cw.shape[2] * cw.shape[3]
+    if cb is not None and cb.ndim == 2:
+        b_stride = M
+    cfg = Cfg(Hq // Hkv, d, M, kw, conv_in, norm, 0, 0, attn_scale, norm_eps)
+    pr, pr_stride = None, 0
+    if protect is not None:
+        pr = np.ascontiguousarray(np.asarray(protect) != 0, dtype=np.uint8)
+        pr_stride = M if pr.ndim == 3 else 0
+    out = dict(dq=np.zeros_like(q), dk=np.zeros_like(kb), dv=np.zeros_like(vb), d_cache_k=np.zeros_like(ck),
+               d_cache_v=np.zeros_like(cv),
+               d_conv_w=None if cw is None else np.zeros_like(cw),
+               d_conv_b=None if cb is None else np.zeros_like(cb))
+    rc = lib().lococo_oracle_step_backward(
+        C.byref(cfg), b, Hkv, Bn, _p(q), _p(kb), _p(vb), _p(ck), _p(cv), cache_len, _p(cw), w_stride, _p(cb),
+        b_stride, None if pr is None else pr.ctypes.data_as(C.POINTER(C.c_uint8)), pr_stride, _p(d_o), _p(gk),
+        _p(gv), _p(out["dq"]), _p(out["dk"]), _p(out["dv"]), _p(out["d_cache_k"]), _p(out["d_cache_v"]),
+        _p(out["d_conv_w"]), _p(out["d_conv_b"]))
+    if rc != 0:
+        raise ValueError("oracle: bad arguments")
+    return out
