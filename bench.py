@@ -165,6 +165,49 @@ def decode_bench(args, w, lb, inputs, torch):
     print(json.dumps(out))
 
 
+def backward_bench(args, w, lb, inputs, torch):
+    """Backward of one compress step (full cache, one block) on the shape-agnostic kernels."""
+    dev = "cuda"
+    w = w.replace(name=w.name + "-backward-step", L=w.B)
+    cfg = lb.config_for(w, impl=1)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    qd, kd, vd, cwd = (t.to(dev) for t in (q, k, v, cw))
+    cache = lb.Cache(cfg, dev)
+    shape = (w.batch, w.n_kv_heads, w.M, w.head_dim)
+    cache.load(torch.randn(shape, device=dev).to(w.torch_dtype), torch.randn(shape, device=dev).to(w.torch_dtype), w.M)
+    f = lambda *sh: torch.randn(*sh, device=dev, dtype=torch.float32)
+    d_o, gk, gv = f(*q.shape), f(*shape), f(*shape)
+    dq, dk, dv = torch.empty_like(d_o), f(*k.shape), f(*k.shape)
+    dck, dcv = torch.empty_like(gk), torch.empty_like(gv)
+    dW = torch.zeros(cw.shape, device=dev, dtype=torch.float32)
+    ws = torch.empty(lb.lococo_backward_workspace_bytes(cfg, w.B, w.M), dtype=torch.uint8, device=dev)
+
+    def step():
+        lb.lococo_segment_step_backward(cfg, qd, kd, vd, cwd, None, cache, d_o, gk, gv, dq, dk, dv, dck, dcv, dW,
+                                        None, ws)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fl = step_flops(w, w.M, w.B)
+    print(json.dumps({"metric": "backward of one compress step, tokens/sec per layer (shape-agnostic kernels)",
+                      "value": w.batch * w.B / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+                      "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads,
+                                 "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "B": w.B, "M": w.M,
+                                 "conv_width": w.conv_width},
+                      "roofline": {"bound": "alu", "achieved": 2.0 * sum(fl.values()) / (ms * 1e-3) / 1e12,
+                                   "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": 2.0 * sum(fl.values()) / (ms * 1e-3) / 1e12 / PEAK_FP32_VALU_TFLOPS,
+                                   "traffic": None}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,6 +222,9 @@ def main():
     ap.add_argument("--norm", type=int, default=-1, help="override the normalisation (0 softmax, 1 relu-sum)")
     ap.add_argument("--protect-sinks", type=int, default=0,
                     help="protect the first N cache slots (attention sinks kept beside the compressed memory)")
+    ap.add_argument("--backward", action="store_true",
+                    help="instead of the scan, time the backward pass of ONE compress step of the workload's shape "
+                         "(shape-agnostic kernels)")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the prefill scan, time the generation stage: --steps segment steps "
                          "with B = 1 on a full cache, for this many sequences at once (0 = off)")
@@ -205,6 +251,8 @@ def main():
     torch.cuda.set_device(0)
     if args.decode_batch:
         return decode_bench(args, w, lb, inputs, torch)
+    if args.backward:
+        return backward_bench(args, w, lb, inputs, torch)
     cfg = lb.config_for(w, impl=args.impl)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)

@@ -202,6 +202,33 @@ lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace
 lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                      const float* logits, lococo_cache* cache, void* stream);
 
+/* Backward pass of one block step (lococo_segment_step), for training the convolution heads
+ * through the scan: chain rule on Alg. 2 step 3, the fill branch and Eq. 5 / Eq. 6 / Eq. 4a-4b,
+ * storage rounding treated as the identity.  The caller walks the blocks in reverse with the
+ * cache states it kept from the forward pass.
+ *   blk: q, k, v of the block as in the forward (o is not read); cache_before: the state the
+ *   forward step started from (cur / len / protect as they were then).
+ *   Gradients are fp32 device arrays, contiguous:
+ *     in   d_o [batch, n_q_heads, B, d]; d_new_k, d_new_v [batch, n_kv_heads, M, d]: gradient
+ *          w.r.t. the cache AFTER the step (rows at and beyond its occupancy are ignored by a
+ *          fill step and must be zero for a compress step's unused slots: there are none);
+ *     out  d_q [batch, n_q_heads, B, d]; d_k, d_v [batch, n_kv_heads, B, d]; d_cache_k,
+ *          d_cache_v [batch, n_kv_heads, M, d]: gradient w.r.t. the cache BEFORE the step
+ *          (rows that were not live are zero); all five are overwritten;
+ *     acc  d_conv_w (laid out like conv_w, with w_head_stride) and d_conv_b (like conv_b, may be
+ *          NULL) are ADDED to, so one buffer collects the whole scan; untouched by a fill step.
+ *   workspace: lococo_backward_workspace_bytes(cfg, B, cache_before->len) bytes, 256-byte aligned.
+ * Runs on the shape-agnostic kernels whatever cfg->impl says (any shape, fp32 arithmetic; filter
+ * gradients are summed with floating-point atomics, so their last bits depend on the order). */
+lococo_status lococo_backward_workspace_bytes(const lococo_config* cfg, int32_t B, int32_t len, size_t* out);
+lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                           const void* conv_w, const void* conv_b,
+                                           const lococo_cache* cache_before, const float* d_o,
+                                           const float* d_new_k, const float* d_new_v, float* d_q,
+                                           float* d_k, float* d_v, float* d_cache_k, float* d_cache_v,
+                                           float* d_conv_w, float* d_conv_b, void* workspace,
+                                           size_t ws_bytes, void* stream);
+
 /* Optional per-kernel timing.  Between lococo_timing_begin() and
  * lococo_timing_end() every kernel the library launches (from any thread) is
  * bracketed by a pair of HIP events recorded on the stream it is launched on.

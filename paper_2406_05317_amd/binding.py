@@ -23,7 +23,7 @@ LOCOCO_FLAG_FILTERS_PREPARED = 1
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
            "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status",
-           "lococo_prepare_filters"]
+           "lococo_prepare_filters", "lococo_backward_workspace_bytes", "lococo_segment_step_backward"]
 
 
 class lococo_config(C.Structure):
@@ -90,6 +90,10 @@ def lib():
         L.lococo_mix_from_logits.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, cap, C.c_void_p]
         L.lococo_scan_status.argtypes = [cfgp, C.c_void_p, C.POINTER(C.c_int32)]
         L.lococo_prepare_filters.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        fp = C.c_void_p
+        L.lococo_backward_workspace_bytes.argtypes = [cfgp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        L.lococo_segment_step_backward.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, C.c_void_p, cap] + [fp] * 10 + [
+            C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_timing_begin.argtypes = []
         L.lococo_timing_end.argtypes = [C.POINTER(lococo_kernel_time), C.POINTER(C.c_int32)]
         for n in EXPORTS[:6] + EXPORTS[8:]:
@@ -250,6 +254,27 @@ def lococo_mix_from_logits(cfg, k, v, logits, cache: Cache):
 def lococo_prepare_filters(cfg, conv_w, workspace):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lococo_prepare_filters(C.byref(cfg), _ptr(conv_w), _ptr(workspace), ws_bytes, _stream()))
+
+
+def lococo_backward_workspace_bytes(cfg, B: int, length: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().lococo_backward_workspace_bytes(C.byref(cfg), B, length, C.byref(out)))
+    return out.value
+
+
+def lococo_segment_step_backward(cfg, q, k, v, conv_w, conv_b, cache: Cache, d_o, d_new_k, d_new_v, d_q, d_k,
+                                 d_v, d_cache_k, d_cache_v, d_conv_w, d_conv_b, workspace):
+    """Gradients of one block step; `cache` is the state BEFORE the step.  All gradient tensors are
+    fp32, contiguous, on the device; d_conv_w / d_conv_b are added to."""
+    for t in (d_o, d_new_k, d_new_v, d_q, d_k, d_v, d_cache_k, d_cache_v, d_conv_w, d_conv_b):
+        assert t is None or (t.dtype == torch.float32 and t.is_contiguous() and t.is_cuda)
+    B = q.shape[2]
+    x = _qkvo(q, k, v, None)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lococo_segment_step_backward(
+        C.byref(cfg), C.byref(x), B, _ptr(conv_w), _ptr(conv_b), C.byref(cache.c), _ptr(d_o), _ptr(d_new_k),
+        _ptr(d_new_v), _ptr(d_q), _ptr(d_k), _ptr(d_v), _ptr(d_cache_k), _ptr(d_cache_v), _ptr(d_conv_w),
+        _ptr(d_conv_b), _ptr(workspace), ws_bytes, _stream()))
 
 
 def lococo_scan_status(cfg, workspace) -> int:

@@ -660,6 +660,92 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   return LOCOCO_OK;
 }
 
+namespace {
+struct BwdLayout { size_t p, ds, w, n, total; };
+BwdLayout bwd_layout(const lococo_config* c, int32_t B, int32_t len) {
+  const size_t T = (size_t)len + B;
+  const size_t rows = (size_t)c->batch * c->n_q_heads * B * T * sizeof(float);
+  const bool compress = len + B > c->M;
+  const size_t mat = compress ? (size_t)c->batch * c->n_kv_heads * c->M * T * sizeof(float) : 0;
+  BwdLayout l;
+  l.p = 0;
+  l.ds = align_up(rows, 256);
+  l.w = l.ds + align_up(rows, 256);
+  l.n = l.w + align_up(mat, 256);
+  l.total = l.n + align_up(mat, 256);
+  return l;
+}
+}  // namespace
+
+lococo_status lococo_backward_workspace_bytes(const lococo_config* cfg, int32_t B, int32_t len, size_t* out) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (!out) return fail(LOCOCO_EINVAL, "out is NULL");
+  if (B <= 0 || len < 0 || len > cfg->M) return fail(LOCOCO_EINVAL, "B must be positive and len in [0, M]");
+  *out = bwd_layout(cfg, B, len).total;
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                           const void* conv_w, const void* conv_b,
+                                           const lococo_cache* cache_before, const float* d_o,
+                                           const float* d_new_k, const float* d_new_v, float* d_q,
+                                           float* d_k, float* d_v, float* d_cache_k, float* d_cache_v,
+                                           float* d_conv_w, float* d_conv_b, void* workspace,
+                                           size_t ws_bytes, void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache_before))) return st;
+  if ((st = check_step_shape(cfg, B, cache_before->len))) return st;
+  if (!blk) return fail(LOCOCO_EINVAL, "qkvo is NULL");
+  if ((st = check_tensor(cfg, blk->q, "q", B)) || (st = check_tensor(cfg, blk->k, "k", B)) ||
+      (st = check_tensor(cfg, blk->v, "v", B)))
+    return st;
+  if (!d_o || !d_new_k || !d_new_v || !d_q || !d_k || !d_v || !d_cache_k || !d_cache_v)
+    return fail(LOCOCO_EINVAL, "a gradient pointer is NULL");
+  const bool compress = cache_before->len + B > cfg->M;
+  if (compress && (!conv_w || !d_conv_w))
+    return fail(LOCOCO_EINVAL, "conv_w or d_conv_w is NULL but the step compresses");
+  if ((int64_t)cache_before->len + B + 2 * (int64_t)cfg->head_dim > 15360)
+    return fail(LOCOCO_EUNSUPPORTED, "cache.len + B + 2 head_dim = %lld exceeds the 15360 floats of LDS the "
+                "backward attention rows use", (long long)cache_before->len + B + 2 * cfg->head_dim);
+  const BwdLayout l = bwd_layout(cfg, B, cache_before->len);
+  if (!workspace || ws_bytes < l.total || ((uintptr_t)workspace & 255))
+    return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", l.total,
+                workspace ? ws_bytes : (size_t)0);
+  hipStream_t s = (hipStream_t)stream;
+  lococo_qkvo x = *blk;
+  x.o = x.q;                                  // not read; keeps make_args' view arithmetic defined
+  BwdArgs g;
+  g.st = make_args(cfg, &x, 0, B, cache_before, conv_w, conv_b, true);
+  g.d_o = d_o;
+  g.d_new_k = d_new_k;
+  g.d_new_v = d_new_v;
+  g.d_q = d_q;
+  g.d_k = d_k;
+  g.d_v = d_v;
+  g.d_cache_k = d_cache_k;
+  g.d_cache_v = d_cache_v;
+  g.d_conv_w = d_conv_w;
+  g.d_conv_b = d_conv_b;
+  char* ws = (char*)workspace;
+  g.ws_p = (float*)(ws + l.p);
+  g.ws_ds = (float*)(ws + l.ds);
+  g.ws_w = (float*)(ws + l.w);
+  g.ws_n = (float*)(ws + l.n);
+  if (compress) {
+    // recompute Eq. 5 and Eq. 6 of the forward step: raw logits and normalised rows
+    HIP_TRY(launch_conv_logits_generic(cfg->dtype, g.st, g.ws_w, s), "conv launch");
+    if (g.st.protect) HIP_TRY(launch_protect_logits_generic(g.st, g.ws_w, s), "protect launch");
+    const size_t mat = (size_t)cfg->batch * cfg->n_kv_heads * cfg->M * ((size_t)cache_before->len + B) *
+                       sizeof(float);
+    HIP_TRY(hipMemcpyAsync(g.ws_n, g.ws_w, mat, hipMemcpyDeviceToDevice, s), "copying the logits");
+    HIP_TRY(launch_normalise_generic(g.st, g.ws_n, s), "normalise launch");
+  }
+  HIP_TRY(launch_step_backward_generic(cfg->dtype, g, compress, s), "backward launches");
+  return LOCOCO_OK;
+}
+
 lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                      const float* logits, lococo_cache* cache, void* stream) {
   lococo_status st;

@@ -1,0 +1,334 @@
+// Backward pass of one block step (training the convolution heads through
+// the scan): chain rule on Alg. 2 step 3 (Eq. 1), the fill branch, and
+// Eq. 5 / Eq. 6 / Eq. 4a-4b.  Shape-agnostic, fp32 arithmetic, fp32 gradients;
+// inputs in the storage dtype (fp32 or bf16), storage rounding treated as the
+// identity.  One workgroup per output row, straight from the definitions, like
+// the forward kernels next door: correct first, not tuned.
+//
+// Notation (one chain): Y = [cache(0:m) ; block] (T = m + Bn rows) for K and V,
+// P the attention rows, w the mixing rows (Eq. 6), g_k / g_v the gradients of
+// the new cache.
+//   attention:  dS[r,j] = P[r,j] (dO[r].Yv[j] - sum_j' P[r,j'] dO[r].Yv[j']) * scale
+//               dq[r] = sum_j dS[r,j] Yk[j],  dYk[j] += sum_r dS[r,j] q[r],  dYv[j] += sum_r P[r,j] dO[r]
+//   fusion:     dw[i,j] = g_k[i].Yk[j] + g_v[i].Yv[j],  dYk[j] += sum_i w[i,j] g_k[i]  (same for V)
+//   Eq. 6:      softmax: dW[i,j] = w[i,j] (dw[i,j] - sum_j' w dw);
+//               relu-sum: dW[i,j] = [W[i,j] > 0] (dw[i,j] - sum_j' w dw) / (z_i + eps)
+//   Eq. 5:      db[i] += sum_j dW[i,j],  dWc[i,c,t] += sum_j dW[i,j] X[j+t-p, c],
+//               dX[j',c] += sum_i sum_t dW[i, j'-t+p] Wc[i,c,t]   (X = Yk, or [Yk | Yv])
+#include <algorithm>
+
+#include "lococo_internal.h"
+
+namespace lococo {
+namespace {
+
+struct bf16_t { uint16_t x; };
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(bf16_t v) { return __uint_as_float((uint32_t)v.x << 16); }
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r += red[w];
+  return r;
+}
+__device__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r = fmaxf(r, red[w]);
+  return r;
+}
+
+template <typename T>
+__device__ __forceinline__ const T* cat_row(const void* cache, const View& blk, int M, int d, int m, int b,
+                                            int hkv, int Hkv, int j) {
+  if (j < m) return (const T*)cache + ((int64_t)(b * Hkv + hkv) * M + j) * d;
+  return (const T*)blk.p + b * blk.sb + hkv * blk.sh + (int64_t)(j - m) * blk.st;
+}
+// where the gradient of row j of [cache ; block] lives
+__device__ __forceinline__ float* grad_row(float* d_cache, float* d_blk, int M, int d, int m, int Bn, int ch,
+                                           int j) {
+  if (j < m) return d_cache + ((int64_t)ch * M + j) * d;
+  return d_blk + ((int64_t)ch * Bn + (j - m)) * d;
+}
+__device__ __forceinline__ bool slot_protected(const StepArgs& a, int ch, int i) {
+  return a.protect && i < a.m && ((a.protect[(int64_t)ch * a.protect_stride + (i >> 5)] >> (i & 31)) & 1u);
+}
+
+// ---- attention, one workgroup per (query row r, query head, batch): P row, dS row, dq row
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_attn_rows_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  extern __shared__ float lds[];                 // [Tn] scores -> P, then [d] query, [d] dO
+  __shared__ float red[kWaves];
+  const int r = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, hkv = hq / a.group;
+  const int Tn = a.m + a.Bn, n_vis = a.m + r + 1, d = a.d;
+  float* prow = lds;
+  float* qs = lds + Tn;
+  float* dos = qs + d;
+  const T* qr = (const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)r * a.q.st;
+  const float* dor = g.d_o + (((int64_t)b * a.Hq + hq) * a.Bn + r) * d;
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    qs[c] = to_f(qr[c]);
+    dos[c] = dor[c];
+  }
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
+    const T* kj = cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j);
+    float acc = 0.f;
+    for (int c = 0; c < d; ++c) acc += qs[c] * to_f(kj[c]);
+    prow[j] = acc * a.scale;
+    mx = fmaxf(mx, prow[j]);
+  }
+  mx = block_max(mx, red);
+  float z = 0.f;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
+    prow[j] = expf(prow[j] - mx);
+    z += prow[j];
+  }
+  z = block_sum(z, red);
+  float* P = g.ws_p + (((int64_t)b * a.Hq + hq) * a.Bn + r) * Tn;
+  float* dS = g.ws_ds + (((int64_t)b * a.Hq + hq) * a.Bn + r) * Tn;
+  float dot = 0.f;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
+    const T* vj = cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j);
+    float acc = 0.f;
+    for (int c = 0; c < d; ++c) acc += dos[c] * to_f(vj[c]);
+    const float p = prow[j] / z;
+    prow[j] = p;
+    P[j] = p;
+    dS[j] = acc;                                  // dP for now
+    dot += p * acc;
+  }
+  dot = block_sum(dot, red);
+  for (int j = threadIdx.x; j < Tn; j += kThreads) {
+    if (j < n_vis) {
+      dS[j] = prow[j] * (dS[j] - dot) * a.scale;
+      prow[j] = dS[j];
+    } else {
+      P[j] = 0.f;
+      dS[j] = 0.f;
+    }
+  }
+  __syncthreads();
+  float* dq = g.d_q + (((int64_t)b * a.Hq + hq) * a.Bn + r) * d;
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    float acc = 0.f;
+    for (int j = 0; j < n_vis; ++j)
+      acc += prow[j] * to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j)[c]);
+    dq[c] = acc;
+  }
+}
+
+// ---- attention, one workgroup per (position j of [cache ; block], kv head, batch): dYk[j], dYv[j]
+// (assigned, not added: this is the first contribution to those rows)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_attn_cols_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  const int j = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z, ch = b * a.Hkv + hkv;
+  const int Tn = a.m + a.Bn, d = a.d;
+  float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
+  float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
+  const int r0 = j < a.m ? 0 : j - a.m;           // block key j' is visible to rows r >= j'
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    float ak = 0.f, av = 0.f;
+    for (int hh = 0; hh < a.group; ++hh) {
+      const int hq = hkv * a.group + hh;
+      const int64_t row0 = ((int64_t)b * a.Hq + hq) * a.Bn;
+      for (int r = r0; r < a.Bn; ++r) {
+        const float ds = g.ws_ds[(row0 + r) * Tn + j], p = g.ws_p[(row0 + r) * Tn + j];
+        ak += ds * to_f(((const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)r * a.q.st)[c]);
+        av += p * g.d_o[(row0 + r) * d + c];
+      }
+    }
+    dk[c] = ak;
+    dv[c] = av;
+  }
+}
+
+// rows of d_cache that are not live before the step carry no gradient
+__global__ __launch_bounds__(kThreads) void bwd_zero_dead_rows_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  const int64_t per = (int64_t)(a.M - a.m) * a.d;
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < per; e += (int64_t)gridDim.x * kThreads) {
+    const int64_t at = ((int64_t)blockIdx.y * a.M + a.m) * a.d + e;
+    g.d_cache_k[at] = 0.f;
+    g.d_cache_v[at] = 0.f;
+  }
+}
+
+// ---- fill branch: new cache = [cache ; block], so its gradient goes straight through
+__global__ __launch_bounds__(kThreads) void bwd_fill_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  const int ch = blockIdx.y, Tn = a.m + a.Bn;
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < (int64_t)Tn * a.d;
+       e += (int64_t)gridDim.x * kThreads) {
+    const int j = (int)(e / a.d), c = (int)(e % a.d);
+    const int64_t at = ((int64_t)ch * a.M + j) * a.d + c;
+    grad_row(g.d_cache_k, g.d_k, a.M, a.d, a.m, a.Bn, ch, j)[c] += g.d_new_k[at];
+    grad_row(g.d_cache_v, g.d_v, a.M, a.d, a.m, a.Bn, ch, j)[c] += g.d_new_v[at];
+  }
+}
+
+// ---- Eq. 4a/4b + Eq. 6, one workgroup per (slot i, chain): dW row into ws_w (over the raw logits),
+// bias gradient; a protected slot passes its gradient to the old row instead
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_mix_rows_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  extern __shared__ float lds[];                 // g_k[i], g_v[i]
+  __shared__ float red[kWaves];
+  const int i = blockIdx.x, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int Tn = a.m + a.Bn, d = a.d;
+  float* Wraw = g.ws_w + ((int64_t)ch * a.M + i) * Tn;       // raw logits in, dW out
+  const float* w = g.ws_n + ((int64_t)ch * a.M + i) * Tn;    // normalised rows
+  const float* gk = g.d_new_k + ((int64_t)ch * a.M + i) * d;
+  const float* gv = g.d_new_v + ((int64_t)ch * a.M + i) * d;
+  if (slot_protected(a, ch, i)) {
+    float* dk = g.d_cache_k + ((int64_t)ch * a.M + i) * d;
+    float* dv = g.d_cache_v + ((int64_t)ch * a.M + i) * d;
+    for (int c = threadIdx.x; c < d; c += kThreads) {
+      dk[c] += gk[c];
+      dv[c] += gv[c];
+    }
+    for (int j = threadIdx.x; j < Tn; j += kThreads) Wraw[j] = 0.f;
+    return;
+  }
+  float* gks = lds;
+  float* gvs = lds + d;
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    gks[c] = gk[c];
+    gvs[c] = gv[c];
+  }
+  __syncthreads();
+  // first pass: dw[j] kept in registers is not possible for any Tn, so it is recomputed in the second
+  float dot = 0.f, z = 0.f;
+  for (int j = threadIdx.x; j < Tn; j += kThreads) {
+    const T* yk = cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j);
+    const T* yv = cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j);
+    float acc = 0.f;
+    for (int c = 0; c < d; ++c) acc += gks[c] * to_f(yk[c]) + gvs[c] * to_f(yv[c]);
+    dot += w[j] * acc;
+    z += fmaxf(Wraw[j], 0.f);
+  }
+  dot = block_sum(dot, red);
+  z = block_sum(z, red) + a.eps;
+  float bsum = 0.f;
+  for (int j = threadIdx.x; j < Tn; j += kThreads) {
+    const T* yk = cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j);
+    const T* yv = cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j);
+    float acc = 0.f;
+    for (int c = 0; c < d; ++c) acc += gks[c] * to_f(yk[c]) + gvs[c] * to_f(yv[c]);
+    const float dW = a.norm == 0 ? w[j] * (acc - dot) : (Wraw[j] > 0.f ? (acc - dot) / z : 0.f);
+    Wraw[j] = dW;
+    bsum += dW;
+  }
+  bsum = block_sum(bsum, red);
+  if (threadIdx.x == 0 && g.d_conv_b) atomicAdd(g.d_conv_b + hkv * a.b_head_stride + i, bsum);
+}
+
+// ---- Eq. 4a/4b + Eq. 5 w.r.t. the inputs, one workgroup per (position j, chain):
+// dYk[j] += sum_i w[i,j] g_k[i] + (Eq. 5 through the key channels), same for V
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_mix_cols_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  const int j = blockIdx.x, ch = blockIdx.y, hkv = ch % a.Hkv;
+  const int Tn = a.m + a.Bn, d = a.d, C = a.conv_in ? 2 * d : d, k = a.k_width, pad = (k - 1) / 2;
+  float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
+  float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
+  const T* wc = (const T*)a.conv_w + hkv * a.w_head_stride;
+  for (int c = threadIdx.x; c < C; c += kThreads) {
+    // Eq. 5: X[j, c] feeds W[i, j - t + pad] through tap t
+    float ax = 0.f;
+    for (int i = 0; i < a.M; ++i) {
+      const float* dW = g.ws_w + ((int64_t)ch * a.M + i) * Tn;
+      const T* wi = wc + ((int64_t)i * C + c) * k;
+      for (int t = 0; t < k; ++t) {
+        const int jo = j - t + pad;
+        if (jo >= 0 && jo < Tn) ax += dW[jo] * to_f(wi[t]);
+      }
+    }
+    if (c < d) dk[c] += ax;
+    else dv[c - d] += ax;
+  }
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    float ak = 0.f, av = 0.f;
+    for (int i = 0; i < a.M; ++i) {
+      if (slot_protected(a, ch, i)) continue;
+      const float wij = g.ws_n[((int64_t)ch * a.M + i) * Tn + j];
+      ak += wij * g.d_new_k[((int64_t)ch * a.M + i) * d + c];
+      av += wij * g.d_new_v[((int64_t)ch * a.M + i) * d + c];
+    }
+    dk[c] += ak;
+    dv[c] += av;
+  }
+}
+
+// ---- Eq. 5 w.r.t. the filters, one workgroup per (slot i, chain): dWc[i, c, t] += sum_j dW[i,j] X[j+t-p, c]
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_conv_w_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  const int i = blockIdx.x, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int Tn = a.m + a.Bn, d = a.d, C = a.conv_in ? 2 * d : d, k = a.k_width, pad = (k - 1) / 2;
+  const float* dW = g.ws_w + ((int64_t)ch * a.M + i) * Tn;
+  float* out = g.d_conv_w + hkv * a.w_head_stride + (int64_t)i * C * k;
+  for (int e = threadIdx.x; e < C * k; e += kThreads) {
+    const int c = e / k, t = e % k;
+    float acc = 0.f;
+    for (int j = 0; j < Tn; ++j) {
+      const int jj = j + t - pad;
+      if (jj < 0 || jj >= Tn) continue;
+      const float x = c < d ? to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, jj)[c])
+                            : to_f(cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, jj)[c - d]);
+      acc += dW[j] * x;
+    }
+    atomicAdd(out + e, acc);
+  }
+}
+
+template <typename T>
+hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
+  const StepArgs& a = g.st;
+  const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv;
+  hipLaunchKernelGGL(bwd_attn_rows_k<T>, dim3(a.Bn, a.Hq, a.batch), dim3(kThreads),
+                     (size_t)(Tn + 2 * a.d) * sizeof(float), s, g);
+  hipLaunchKernelGGL(bwd_attn_cols_k<T>, dim3(Tn, a.Hkv, a.batch), dim3(kThreads), 0, s, g);
+  if (a.m < a.M) hipLaunchKernelGGL(bwd_zero_dead_rows_k, dim3(64, chains), dim3(kThreads), 0, s, g);
+  if (!compress) {
+    hipLaunchKernelGGL(bwd_fill_k, dim3(64, chains), dim3(kThreads), 0, s, g);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(bwd_mix_rows_k<T>, dim3(a.M, chains), dim3(kThreads), (size_t)2 * a.d * sizeof(float), s, g);
+  hipLaunchKernelGGL(bwd_mix_cols_k<T>, dim3(Tn, chains), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_conv_w_k<T>, dim3(a.M, chains), dim3(kThreads), 0, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_step_backward_generic(int dtype, const BwdArgs& g, bool compress, hipStream_t s) {
+  return dtype == LOCOCO_F32 ? run<float>(g, compress, s) : run<bf16_t>(g, compress, s);
+}
+
+}  // namespace lococo

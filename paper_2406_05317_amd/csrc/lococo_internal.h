@@ -77,6 +77,31 @@ struct AttnArgs {
   float scale;
 };
 
+// Arguments of the backward pass of one block step (backward_generic.hip).  `st` describes the
+// step as for the forward (cache = state before the step).  Gradients are fp32, contiguous:
+// d_o, d_q [batch, Hq, Bn, d]; d_k, d_v [batch, Hkv, Bn, d]; d_new_k/v, d_cache_k/v [chains, M, d];
+// d_conv_w / d_conv_b laid out like conv_w / conv_b (added to).  Workspace: ws_p, ws_ds
+// [batch, Hq, Bn, T] (attention rows and their gradient), ws_w [chains, M, T] (raw logits on entry,
+// their gradient on exit), ws_n [chains, M, T] (normalised rows).
+struct BwdArgs {
+  StepArgs st;
+  const float* d_o;
+  const float* d_new_k;
+  const float* d_new_v;
+  float* d_q;
+  float* d_k;
+  float* d_v;
+  float* d_cache_k;
+  float* d_cache_v;
+  float* d_conv_w;
+  float* d_conv_b;
+  float* ws_p;
+  float* ws_ds;
+  float* ws_w;
+  float* ws_n;
+};
+hipError_t launch_step_backward_generic(int dtype, const BwdArgs& g, bool compress, hipStream_t s);
+
 // ---- shape-agnostic kernels (generic_kernels.hip); dtype: LOCOCO_F32 / LOCOCO_BF16
 hipError_t launch_attn_generic(int dtype, const StepArgs& a, hipStream_t s);
 hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s);
