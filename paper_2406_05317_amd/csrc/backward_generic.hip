@@ -248,30 +248,14 @@ __global__ __launch_bounds__(kThreads) void bwd_mix_rows_k(BwdArgs g) {
   if (threadIdx.x == 0 && g.d_conv_b) atomicAdd(g.d_conv_b + hkv * a.b_head_stride + i, bsum);
 }
 
-// ---- Eq. 4a/4b + Eq. 5 w.r.t. the inputs, one workgroup per (position j, chain):
-// dYk[j] += sum_i w[i,j] g_k[i] + (Eq. 5 through the key channels), same for V
-template <typename T>
+// ---- Eq. 4a/4b w.r.t. the inputs, one workgroup per (position j, chain):
+// dYk[j] += sum_i w[i,j] g_k[i], same for V
 __global__ __launch_bounds__(kThreads) void bwd_mix_cols_k(BwdArgs g) {
   const StepArgs& a = g.st;
-  const int j = blockIdx.x, ch = blockIdx.y, hkv = ch % a.Hkv;
-  const int Tn = a.m + a.Bn, d = a.d, C = a.conv_in ? 2 * d : d, k = a.k_width, pad = (k - 1) / 2;
+  const int j = blockIdx.x, ch = blockIdx.y;
+  const int Tn = a.m + a.Bn, d = a.d;
   float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
   float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
-  const T* wc = (const T*)a.conv_w + hkv * a.w_head_stride;
-  for (int c = threadIdx.x; c < C; c += kThreads) {
-    // Eq. 5: X[j, c] feeds W[i, j - t + pad] through tap t
-    float ax = 0.f;
-    for (int i = 0; i < a.M; ++i) {
-      const float* dW = g.ws_w + ((int64_t)ch * a.M + i) * Tn;
-      const T* wi = wc + ((int64_t)i * C + c) * k;
-      for (int t = 0; t < k; ++t) {
-        const int jo = j - t + pad;
-        if (jo >= 0 && jo < Tn) ax += dW[jo] * to_f(wi[t]);
-      }
-    }
-    if (c < d) dk[c] += ax;
-    else dv[c - d] += ax;
-  }
   for (int c = threadIdx.x; c < d; c += kThreads) {
     float ak = 0.f, av = 0.f;
     for (int i = 0; i < a.M; ++i) {
@@ -285,25 +269,143 @@ __global__ __launch_bounds__(kThreads) void bwd_mix_cols_k(BwdArgs g) {
   }
 }
 
-// ---- Eq. 5 w.r.t. the filters, one workgroup per (slot i, chain): dWc[i, c, t] += sum_j dW[i,j] X[j+t-p, c]
+// The two Eq. 5 gradients are implicit GEMMs like the forward logits and are tiled the same way:
+// 64 x 64 outputs per workgroup, 4 x 4 per thread, operands through LDS, and along the Toeplitz
+// direction a thread slides a 4-value register window so that one new LDS value serves 16
+// multiply-adds.
+constexpr int kTI = 64, kTK = 16;
+
+// ---- Eq. 5 w.r.t. the filters: dWc[i, c, t] += sum_j dW[i, j] X[j + t - p, c].  Rows: 64 slots;
+// columns: 4 channels x 16 taps; contraction over the positions in chunks of 32.
+constexpr int kWC = 4, kJC = 32;
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bwd_conv_w_k(BwdArgs g) {
   const StepArgs& a = g.st;
-  const int i = blockIdx.x, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  __shared__ float dWs[kJC][kTI + 4];                 // [position][slot]
+  __shared__ float Xs[kWC][kJC + kTK + 4];            // [channel][row], rows jc + t0 - pad ..
   const int Tn = a.m + a.Bn, d = a.d, C = a.conv_in ? 2 * d : d, k = a.k_width, pad = (k - 1) / 2;
-  const float* dW = g.ws_w + ((int64_t)ch * a.M + i) * Tn;
-  float* out = g.d_conv_w + hkv * a.w_head_stride + (int64_t)i * C * k;
-  for (int e = threadIdx.x; e < C * k; e += kThreads) {
-    const int c = e / k, t = e % k;
-    float acc = 0.f;
-    for (int j = 0; j < Tn; ++j) {
-      const int jj = j + t - pad;
-      if (jj < 0 || jj >= Tn) continue;
-      const float x = c < d ? to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, jj)[c])
-                            : to_f(cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, jj)[c - d]);
-      acc += dW[j] * x;
+  const int ntk = (k + kTK - 1) / kTK;
+  const int c0 = (blockIdx.x / ntk) * kWC, t0 = (blockIdx.x % ntk) * kTK, i0 = blockIdx.y * kTI;
+  const int ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int ti = threadIdx.x / 16, tc = (threadIdx.x % 16) / 4, tt = (threadIdx.x % 4) * 4;
+  float acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[ii][q] = 0.f;
+  for (int jc = 0; jc < Tn; jc += kJC) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < kJC * kTI; e += kThreads) {
+      const int j = e % kJC, i = e / kJC;
+      dWs[j][i] = (i0 + i < a.M && jc + j < Tn) ? g.ws_w[((int64_t)ch * a.M + i0 + i) * Tn + jc + j] : 0.f;
     }
-    atomicAdd(out + e, acc);
+    for (int e = threadIdx.x; e < kWC * (kJC + kTK - 1); e += kThreads) {
+      const int c = e % kWC, r = e / kWC, jj = jc + t0 - pad + r, cc = c0 + c;
+      float v = 0.f;
+      if (jj >= 0 && jj < Tn && cc < C)
+        v = cc < d ? to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, jj)[cc])
+                   : to_f(cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, jj)[cc - d]);
+      Xs[c][r] = v;
+    }
+    __syncthreads();
+    // x[q] = X row (j + tt + q): slides by one row per position
+    float x0 = Xs[tc][tt], x1 = Xs[tc][tt + 1], x2 = Xs[tc][tt + 2], x3;
+#pragma unroll 8
+    for (int j = 0; j < kJC; ++j) {
+      x3 = Xs[tc][j + tt + 3];
+      const float4 wv = *(const float4*)&dWs[j][ti * 4];
+      const float wr[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii) {
+        acc[ii][0] = fmaf(wr[ii], x0, acc[ii][0]);
+        acc[ii][1] = fmaf(wr[ii], x1, acc[ii][1]);
+        acc[ii][2] = fmaf(wr[ii], x2, acc[ii][2]);
+        acc[ii][3] = fmaf(wr[ii], x3, acc[ii][3]);
+      }
+      x0 = x1; x1 = x2; x2 = x3;
+    }
+  }
+  const int c = c0 + tc;
+  if (c < C) {
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii) {
+      const int i = i0 + ti * 4 + ii;
+      if (i >= a.M) continue;
+      float* out = g.d_conv_w + hkv * a.w_head_stride + ((int64_t)i * C + c) * k;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (t0 + tt + q < k) atomicAdd(out + t0 + tt + q, acc[ii][q]);
+    }
+  }
+}
+
+// ---- Eq. 5 w.r.t. its input: dX[j, c] += sum_i sum_t dW[i, j - t + p] Wc[i, c, t].  Rows: 64
+// positions; columns: 64 channels; contraction over (slot, tap) in chunks of 8 slots x 16 taps.
+constexpr int kIC = 8;
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_conv_x_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  __shared__ float Ds[kIC][kTI + kTK + 4];            // [slot][position], positions j0 - t0 - (kTK-1) + pad ..
+  __shared__ float Ws[kIC][kTK][kTI + 4];             // [slot][tap][channel]
+  const int Tn = a.m + a.Bn, d = a.d, C = a.conv_in ? 2 * d : d, k = a.k_width, pad = (k - 1) / 2;
+  const int j0 = blockIdx.x * kTI, c0 = blockIdx.y * kTI, ch = blockIdx.z, hkv = ch % a.Hkv;
+  const int tj = threadIdx.x / 16, tc = threadIdx.x % 16;
+  const T* wbase = (const T*)a.conv_w + hkv * a.w_head_stride;
+  float acc[4][4];                                     // [position][channel]
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[jj][q] = 0.f;
+  for (int i0 = 0; i0 < a.M; i0 += kIC)
+    for (int t0 = 0; t0 < k; t0 += kTK) {
+      __syncthreads();
+      // Ds[i][r] = dW[i0 + i, base + r], base = j0 + pad - t0 - (kTK - 1): tap t0 + t of position
+      // j0 + p reads r = p + (kTK - 1) - t
+      const int base = j0 + pad - t0 - (kTK - 1);
+      for (int e = threadIdx.x; e < kIC * (kTI + kTK - 1); e += kThreads) {
+        const int r = e % (kTI + kTK - 1), i = e / (kTI + kTK - 1), jj = base + r;
+        Ds[i][r] = (i0 + i < a.M && jj >= 0 && jj < Tn) ? g.ws_w[((int64_t)ch * a.M + i0 + i) * Tn + jj] : 0.f;
+      }
+      for (int e = threadIdx.x; e < kIC * kTK * kTI; e += kThreads) {
+        const int t = e % kTK, c = (e / kTK) % kTI, i = e / (kTK * kTI);
+        float v = 0.f;
+        if (i0 + i < a.M && c0 + c < C && t0 + t < k) v = to_f(wbase[((int64_t)(i0 + i) * C + c0 + c) * k + t0 + t]);
+        Ws[i][t][c] = v;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < kIC; ++i) {
+        // window over r for positions tj*4 .. tj*4+3 at tap t: r = p + (kTK-1) - t; walk t downwards
+        // so that the window slides up by one per tap
+        float w0, w1 = Ds[i][tj * 4 + 0], w2 = Ds[i][tj * 4 + 1], w3 = Ds[i][tj * 4 + 2];
+#pragma unroll
+        for (int t = kTK - 1; t >= 0; --t) {
+          w0 = w1; w1 = w2; w2 = w3;
+          w3 = Ds[i][tj * 4 + 3 + (kTK - 1) - t];
+          const float4 fv = *(const float4*)&Ws[i][t][tc * 4];
+          const float fr[4] = {fv.x, fv.y, fv.z, fv.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acc[0][q] = fmaf(w0, fr[q], acc[0][q]);
+            acc[1][q] = fmaf(w1, fr[q], acc[1][q]);
+            acc[2][q] = fmaf(w2, fr[q], acc[2][q]);
+            acc[3][q] = fmaf(w3, fr[q], acc[3][q]);
+          }
+        }
+      }
+    }
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int j = j0 + tj * 4 + jj;
+    if (j >= Tn) continue;
+    float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
+    float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = c0 + tc * 4 + q;
+      if (c < d) dk[c] += acc[jj][q];
+      else if (c < C) dv[c - d] += acc[jj][q];
+    }
   }
 }
 
@@ -320,8 +422,12 @@ hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
     return hipGetLastError();
   }
   hipLaunchKernelGGL(bwd_mix_rows_k<T>, dim3(a.M, chains), dim3(kThreads), (size_t)2 * a.d * sizeof(float), s, g);
-  hipLaunchKernelGGL(bwd_mix_cols_k<T>, dim3(Tn, chains), dim3(kThreads), 0, s, g);
-  hipLaunchKernelGGL(bwd_conv_w_k<T>, dim3(a.M, chains), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_mix_cols_k, dim3(Tn, chains), dim3(kThreads), 0, s, g);
+  const int C = a.conv_in ? 2 * a.d : a.d;
+  hipLaunchKernelGGL(bwd_conv_x_k<T>, dim3((Tn + kTI - 1) / kTI, (C + kTI - 1) / kTI, chains), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_conv_w_k<T>,
+                     dim3(((C + kWC - 1) / kWC) * ((a.k_width + kTK - 1) / kTK), (a.M + kTI - 1) / kTI, chains),
+                     dim3(kThreads), 0, s, g);
   return hipGetLastError();
 }
 

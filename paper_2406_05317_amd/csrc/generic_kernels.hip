@@ -122,33 +122,77 @@ __global__ __launch_bounds__(kThreads) void fill_generic_k(StepArgs a) {
 }
 
 // Eq. 5: W[i, j] = bias[i] + sum_c sum_tau Wc[i, c, tau] X[j + tau - (k-1)/2, c],
-// zero outside [0, T).  One thread per (slot i, position j).
+// zero outside [0, T).  An implicit GEMM with inner dimension C*k, tiled through LDS: a workgroup
+// owns 64 slots x 64 positions, a thread 4 x 4 of them; the inner dimension is walked in chunks of
+// 8 channels x 16 taps.  For a fixed channel a thread keeps the 4 + 15 positions its taps touch
+// in registers, so each LDS value feeds several multiply-adds.
+constexpr int kTI = 64, kTJ = 64, kCC = 8, kTK = 16;
 template <typename T>
 __global__ __launch_bounds__(kThreads) void conv_logits_generic_k(StepArgs a, float* logits) {
+  __shared__ float Ws[kCC][kTK][kTI + 4];            // [channel][tap][slot]
+  __shared__ float Xs[kCC][kTJ + kTK + 4];           // [channel][row], rows j0 + t0 - pad ..
   const int Tn = a.m + a.Bn;
-  const int j = blockIdx.x * kThreads + threadIdx.x;
-  const int i = blockIdx.y, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
-  if (j >= Tn) return;
-  const int C = a.conv_in ? 2 * a.d : a.d;
-  const int pad = (a.k_width - 1) / 2;
-  const T* w = (const T*)a.conv_w + hkv * a.w_head_stride + (int64_t)i * C * a.k_width;
-  float acc = a.conv_b ? to_f(((const T*)a.conv_b)[hkv * a.b_head_stride + i]) : 0.f;
-  for (int t = 0; t < a.k_width; ++t) {
-    const int jj = j + t - pad;
-    if (jj < 0 || jj >= Tn) continue;
-    const T* xk = cat_row<T>(a.cache_k, a.k, a.M, a.d, a.m, b, hkv, a.Hkv, jj);
-    float s = 0.f;
-    for (int c = 0; c < a.d; ++c) s += to_f(w[c * a.k_width + t]) * to_f(xk[c]);
-    if (a.conv_in) {
-      const T* xv = cat_row<T>(a.cache_v, a.v, a.M, a.d, a.m, b, hkv, a.Hkv, jj);
-      for (int c = 0; c < a.d; ++c) s += to_f(w[(a.d + c) * a.k_width + t]) * to_f(xv[c]);
+  const int j0 = blockIdx.x * kTJ, i0 = blockIdx.y * kTI, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int C = a.conv_in ? 2 * a.d : a.d, k = a.k_width, pad = (k - 1) / 2;
+  const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
+  const T* wbase = (const T*)a.conv_w + hkv * a.w_head_stride;
+  float acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.f;
+  for (int c0 = 0; c0 < C; c0 += kCC)
+    for (int t0 = 0; t0 < k; t0 += kTK) {
+      __syncthreads();
+      for (int e = threadIdx.x; e < kCC * kTK * kTI; e += kThreads) {
+        const int t = e % kTK, c = (e / kTK) % kCC, i = e / (kTK * kCC);
+        float v = 0.f;
+        if (i0 + i < a.M && c0 + c < C && t0 + t < k)
+          v = to_f(wbase[((int64_t)(i0 + i) * C + c0 + c) * k + t0 + t]);
+        Ws[c][t][i] = v;
+      }
+      for (int e = threadIdx.x; e < kCC * (kTJ + kTK - 1); e += kThreads) {
+        const int c = e % kCC, r = e / kCC, jj = j0 + t0 - pad + r;
+        float v = 0.f;
+        if (jj >= 0 && jj < Tn && c0 + c < C) {
+          const int cc = c0 + c;
+          v = cc < a.d ? to_f(cat_row<T>(a.cache_k, a.k, a.M, a.d, a.m, b, hkv, a.Hkv, jj)[cc])
+                       : to_f(cat_row<T>(a.cache_v, a.v, a.M, a.d, a.m, b, hkv, a.Hkv, jj)[cc - a.d]);
+        }
+        Xs[c][r] = v;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int c = 0; c < kCC; ++c) {
+        float x[4 + kTK - 1];
+#pragma unroll
+        for (int r = 0; r < 4 + kTK - 1; ++r) x[r] = Xs[c][tj * 4 + r];
+#pragma unroll
+        for (int t = 0; t < kTK; ++t) {
+          const float4 wv = *(const float4*)&Ws[c][t][ti * 4];
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            acc[0][jj] = fmaf(wv.x, x[jj + t], acc[0][jj]);
+            acc[1][jj] = fmaf(wv.y, x[jj + t], acc[1][jj]);
+            acc[2][jj] = fmaf(wv.z, x[jj + t], acc[2][jj]);
+            acc[3][jj] = fmaf(wv.w, x[jj + t], acc[3][jj]);
+          }
+        }
+      }
     }
-    acc += s;
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) {
+    const int i = i0 + ti * 4 + ii;
+    if (i >= a.M) continue;
+    const float bias = a.conv_b ? to_f(((const T*)a.conv_b)[hkv * a.b_head_stride + i]) : 0.f;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + tj * 4 + jj;
+      if (j < Tn) logits[((int64_t)ch * a.M + i) * Tn + j] = acc[ii][jj] + bias;
+    }
   }
-  logits[((int64_t)ch * a.M + i) * Tn + j] = acc;
 }
 
-// Eq. 6, in place: one workgroup per (slot, chain) row of T logits.
 __global__ __launch_bounds__(kThreads) void normalise_generic_k(StepArgs a, float* logits) {
   __shared__ float red[kWaves];
   const int Tn = a.m + a.Bn;
@@ -272,7 +316,7 @@ hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s) {
 
 hipError_t launch_conv_logits_generic(int dtype, const StepArgs& a, float* logits, hipStream_t s) {
   const int Tn = a.m + a.Bn;
-  dim3 grid((Tn + kThreads - 1) / kThreads, a.M, a.batch * a.Hkv);
+  dim3 grid((Tn + kTJ - 1) / kTJ, (a.M + kTI - 1) / kTI, a.batch * a.Hkv);
   if (dtype == LOCOCO_F32)
     hipLaunchKernelGGL(conv_logits_generic_k<float>, grid, dim3(kThreads), 0, s, a, logits);
   else
