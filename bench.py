@@ -137,13 +137,31 @@ def decode_bench(args, w, lb, inputs, torch):
     for _ in range(args.warmup):
         token(t); t += 1
     torch.cuda.synchronize()
-    lb.lococo_timing_begin()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        token(t); t += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kt = lb.lococo_timing_end()
+    if args.decode_graph:
+        # two steps per graph: after two compressions the cache ping-pong is back at its first buffer
+        if (args.warmup % 2) or (args.steps % 2):
+            raise SystemExit("--decode-graph needs even --warmup and --steps")
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                token(t); token(t + 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps // 2):
+            graph.replay()                               # the same two tokens again: timing only
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kt = {"graph": (args.steps // 2, (t1 - t0) * 1e3)}
+    else:
+        lb.lococo_timing_begin()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            token(t); t += 1
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kt = lb.lococo_timing_end()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     flops = step_flops(w, w.M, 1)
     name = max(kt, key=lambda n: kt[n][1])
@@ -157,7 +175,7 @@ def decode_bench(args, w, lb, inputs, torch):
            "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
            "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                       "head_dim": w.head_dim, "B": 1, "M": w.M, "conv_width": w.conv_width,
-                      "conv_channels": w.C, "impl": args.impl},
+                      "conv_channels": w.C, "impl": args.impl, "hip_graph": bool(args.decode_graph)},
            "roofline": {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
                         "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
                         "launches": launches, "avg_launch_us": total_ms * 1e3 / max(launches, 1),
@@ -228,6 +246,8 @@ def main():
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the prefill scan, time the generation stage: --steps segment steps "
                          "with B = 1 on a full cache, for this many sequences at once (0 = off)")
+    ap.add_argument("--decode-graph", action="store_true",
+                    help="with --decode-batch: replay pairs of generation steps from a captured HIP graph")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the warm-up, so "
                          "that a rocprofv3 --pmc run has a kernel of known HBM traffic to scale "

@@ -282,3 +282,60 @@ def test_mfma_paper_literal_variants(case):
     for history in (False, True):
         errs = _run(w, history=history)
     print(case, {k: (f"{e[0]:.2e}", f"{e[1]:.2e}") for k, e in errs.items()})
+
+
+def test_decode_steps_replayed_from_a_hip_graph():
+    """Two generation steps (the cache ping-pong returns to its first buffer after two) captured in
+    a HIP graph and replayed several times with fresh tokens in the static input buffers, with
+    eager work and synchronisations between the replays: every replay equals the eager steps."""
+    from paper_2406_05317_amd import binding as lb
+    w = _w(M=128, L=128 + 12, B=128)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    qd, kd, vd, cwd, cbd = (t.cuda() for t in (q, k, v, cw, cb))
+    sl = lambda t, a, b: t[:, :, a:b]
+
+    def prefill(cfg):
+        cache = lb.Cache(cfg)
+        o = torch.empty_like(sl(qd, 0, 128))
+        lb.lococo_segment_step(cfg, sl(qd, 0, 128), sl(kd, 0, 128), sl(vd, 0, 128), o, cwd, cbd, cache,
+                               lb.workspace(cfg, 128, 128, False))
+        return cache
+
+    # eager reference
+    cfg = lb.config_for(w, impl=MFMA)
+    cache = prefill(cfg)
+    ws = lb.workspace(cfg, 1, 1, False)
+    lb.lococo_prepare_filters(cfg, cwd, ws)
+    cfg.flags |= lb.LOCOCO_FLAG_FILTERS_PREPARED
+    want = torch.empty_like(sl(qd, 128, w.L))
+    for t in range(128, w.L):
+        lb.lococo_segment_step(cfg, sl(qd, t, t + 1), sl(kd, t, t + 1), sl(vd, t, t + 1), sl(want, t - 128, t - 127),
+                               cwd, cbd, cache, ws)
+    torch.cuda.synchronize()
+    want_k, want_v = cache.k.clone(), cache.v.clone()
+
+    # graph: static two-token buffers
+    cache = prefill(cfg)
+    cur0 = cache.cur
+    sq, sk, sv = (torch.zeros_like(sl(x, 0, 2)).contiguous() for x in (qd, kd, vd))
+    so = torch.zeros_like(sq)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(2):
+                lb.lococo_segment_step(cfg, sl(sq, i, i + 1), sl(sk, i, i + 1), sl(sv, i, i + 1), sl(so, i, i + 1),
+                                       cwd, cbd, cache, ws)
+    assert cache.cur == cur0                      # two steps: the live buffer is the first one again
+    cache.c.len = w.M
+    got = torch.empty_like(want)
+    for t in range(128, w.L, 2):
+        sq.copy_(sl(qd, t, t + 2)); sk.copy_(sl(kd, t, t + 2)); sv.copy_(sl(vd, t, t + 2))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got[:, :, t - 128:t - 126] = so             # eager work between replays
+    assert torch.equal(got, want)
+    assert torch.equal(cache.k, want_k) and torch.equal(cache.v, want_v)
