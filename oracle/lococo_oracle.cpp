@@ -110,9 +110,11 @@ void parallel_for(int64_t n, int nthreads, F f) {
 
 // Alg. 2 step 3 with Eq. 1 for one query head: rows r < Bn of q against
 // the m cache slots (all visible) followed by block keys j' <= r.
+// colsum (or null): [m] accumulators; the probability each query row puts on cache slot j is added
+// to colsum[j] (the accumulated attention scores a heavy-hitter policy ranks slots by).
 void attention_block(const double* q, const double* kb, const double* vb,
                      const double* ck, const double* cv, int m, int Bn, int d,
-                     double scale, double* o) {
+                     double scale, double* o, double* colsum = nullptr) {
   std::vector<double> s((size_t)m + Bn);
   for (int r = 0; r < Bn; ++r) {
     const double* qr = q + (size_t)r * d;
@@ -132,6 +134,7 @@ void attention_block(const double* q, const double* kb, const double* vb,
     for (int j = 0; j < n_vis; ++j) {
       const double* vj = j < m ? cv + (size_t)j * d : vb + (size_t)(j - m) * d;
       double p = s[j] / z;
+      if (colsum && j < m) colsum[j] += p;
       for (int c = 0; c < d; ++c) orow[c] += p * vj[c];
     }
   }
@@ -204,12 +207,13 @@ void segment_step_chain(const Cfg& cf, const double* q, int64_t q_head_stride,
                         const double* kb, const double* vb, int Bn, double* o,
                         int64_t o_head_stride, double* ck, double* cv, int* len,
                         const double* conv_w, const double* conv_b,
-                        const double* logits_override, const uint8_t* protect, int nthreads) {
+                        const double* logits_override, const uint8_t* protect, double* colsum,
+                        int nthreads) {
   const int d = cf.head_dim, M = cf.M, m = *len;
   const double scale = cf.attn_scale > 0.0 ? cf.attn_scale : 1.0 / std::sqrt((double)d);
   for (int h = 0; h < cf.group; ++h) {
     double* oh = o + h * o_head_stride;
-    attention_block(q + h * q_head_stride, kb, vb, ck, cv, m, Bn, d, scale, oh);
+    attention_block(q + h * q_head_stride, kb, vb, ck, cv, m, Bn, d, scale, oh, colsum);
     for (size_t e = 0; e < (size_t)Bn * d; ++e) oh[e] = round_store(oh[e], cf.state_round);
   }
   if (m + Bn <= M) {                       // fill branch
@@ -462,12 +466,14 @@ void lococo_oracle_mix(const double* w, const double* Y, int32_t M, int32_t T, i
 //   protect null, or one byte per slot ([M], + protect_chain_stride bytes per chain, 0 = one
 //   mask for all chains): non-zero = the slot, once live, is kept as it is by every
 //   compression step and carries no weight in the mixing of the other slots.
+//   attn_colsum null, or [batch, Hkv, M] accumulators: every attention (step 3) adds, for each
+//   live cache slot, the probabilities the block's queries (all heads of the group) put on it.
 int32_t lococo_oracle_sequence_forward_protected(
     const lococo_oracle_cfg* cfg, int32_t batch, int32_t Hkv, int64_t L, int32_t B, const double* q,
     const double* k, const double* v, double* o, double* cache_k, double* cache_v, int32_t* len,
     const double* conv_w, int64_t w_head_stride, const double* conv_b, int64_t b_head_stride,
     const double* logits_override, const uint8_t* protect, int64_t protect_chain_stride,
-    int32_t nthreads) {
+    double* attn_colsum, int32_t nthreads) {
   const Cfg cf = *cfg;
   const int d = cf.head_dim, M = cf.M, g = cf.group;
   if (d <= 0 || M <= 0 || g <= 0 || B <= 0 || L < 0 || cf.conv_width < 1 ||
@@ -504,7 +510,7 @@ int32_t lococo_oracle_sequence_forward_protected(
       }
       segment_step_chain(cf, qc + s * d, L * d, kc + s * d, vc + s * d, Bn, oc + s * d, L * d,
                          ck, cv, &m, cw, cb, ov, protect ? protect + ch * protect_chain_stride : nullptr,
-                         inner);
+                         attn_colsum ? attn_colsum + ch * (int64_t)M : nullptr, inner);
       if (compress) ++step;
     }
   });
@@ -526,7 +532,7 @@ int32_t lococo_oracle_sequence_forward(const lococo_oracle_cfg* cfg, int32_t bat
                                        int32_t nthreads) {
   return lococo_oracle_sequence_forward_protected(cfg, batch, Hkv, L, B, q, k, v, o, cache_k, cache_v,
                                                   len, conv_w, w_head_stride, conv_b, b_head_stride,
-                                                  logits_override, nullptr, 0, nthreads);
+                                                  logits_override, nullptr, 0, nullptr, nthreads);
 }
 
 // Backward of ONE block step over all chains (the caller walks the scan in reverse with the cache

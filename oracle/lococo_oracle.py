@@ -64,7 +64,7 @@ def lib():
         L.lococo_oracle_sequence_forward_protected.argtypes = [
             C.POINTER(Cfg), C.c_int32, C.c_int32, C.c_int64, C.c_int32, _DP, _DP, _DP, _DP, _DP,
             _DP, C.POINTER(C.c_int32), _DP, C.c_int64, _DP, C.c_int64, _DP,
-            C.POINTER(C.c_uint8), C.c_int64, C.c_int32]
+            C.POINTER(C.c_uint8), C.c_int64, _DP, C.c_int32]
         L.lococo_oracle_step_backward.restype = C.c_int32
         L.lococo_oracle_step_backward.argtypes = (
             [C.POINTER(Cfg), C.c_int32, C.c_int32, C.c_int32] + [_DP] * 5 + [C.c_int32, _DP, C.c_int64, _DP,
@@ -147,7 +147,7 @@ _ROUND = {None: 0, "none": 0, "f64": 0, "f32": 1, "bf16": 2}
 def sequence_forward(q, k, v, conv_w, conv_b=None, *, B: int, M: int, conv_in: int = 0,
                      norm: int = 0, state_round="none", attn_scale: float = 0.0,
                      norm_eps: float = 1e-6, cache_k=None, cache_v=None, cache_len: int = 0,
-                     logits_override=None, protect=None, nthreads: int = 1):
+                     logits_override=None, protect=None, attn_colsum=None, nthreads: int = 1):
     """Alg. 2 over q [b,Hq,L,d], k, v [b,Hkv,L,d].
 
     conv_w is [M,C,k] (shared) or [Hkv,M,C,k]; conv_b [M], [Hkv,M] or None.
@@ -155,6 +155,9 @@ def sequence_forward(q, k, v, conv_w, conv_b=None, *, B: int, M: int, conv_in: i
     protected slot, once live, is kept as it is by every compression step and carries no weight
     in the mixing of the other slots (combination with an eviction policy, ablation on combining
     with StreamingLLM / H2O).
+    attn_colsum: None, or a float64 C-contiguous array [b,Hkv,M] that is ADDED to: for every block,
+    the attention probabilities its queries (all heads of the group) put on each live cache slot
+    (the accumulated scores a heavy-hitter policy ranks slots by).
     Returns (o [b,Hq,L,d], cache_k [b,Hkv,M,d], cache_v, cache_len); rows of the
     caches at and beyond cache_len are zero / untouched input.
     """
@@ -194,10 +197,13 @@ def sequence_forward(q, k, v, conv_w, conv_b=None, *, B: int, M: int, conv_in: i
         pr = np.ascontiguousarray(np.asarray(protect) != 0, dtype=np.uint8)
         assert pr.shape in ((M,), (b, Hkv, M)), pr.shape
         pr_stride = M if pr.ndim == 3 else 0
+    if attn_colsum is not None:
+        assert (isinstance(attn_colsum, np.ndarray) and attn_colsum.dtype == np.float64 and
+                attn_colsum.flags.c_contiguous and attn_colsum.shape == (b, Hkv, M)), "attn_colsum: float64 [b,Hkv,M]"
     rc = lib().lococo_oracle_sequence_forward_protected(
         C.byref(cfg), b, Hkv, L, B, _p(q), _p(k), _p(v), _p(o), _p(ck), _p(cv), C.byref(ln), _p(cw),
         w_stride, _p(cb), b_stride, _p(lo),
-        None if pr is None else pr.ctypes.data_as(C.POINTER(C.c_uint8)), pr_stride, nthreads)
+        None if pr is None else pr.ctypes.data_as(C.POINTER(C.c_uint8)), pr_stride, _p(attn_colsum), nthreads)
     if rc != 0:
         raise ValueError("oracle: bad arguments")
     return o, ck, cv, ln.value

@@ -571,3 +571,35 @@ def test_a_fully_protected_cache_is_frozen_and_attention_still_sees_it():
         s[:, M:] += np.where(np.tril(np.ones((B, B), bool)), 0.0, -np.inf)
         p = np.exp(s - s.max(axis=1, keepdims=True))
         np.testing.assert_allclose(o[0, 0, blk], (p / p.sum(axis=1, keepdims=True)) @ vals, rtol=1e-10, atol=1e-13)
+
+
+def test_attention_column_sums_match_a_numpy_softmax():
+    """The accumulated attention scores per cache slot (what a heavy-hitter policy ranks slots by):
+    for every block, the softmax rows of all heads of the group, summed over the rows, cache
+    columns only -- written out in numpy for a scan that only fills and then attends."""
+    rng = np.random.default_rng(41)
+    b, Hq, Hkv, L, B, M, d = 1, 4, 2, 24, 4, 8, 4
+    q, kk, v = rand(rng, b, Hq, L, d), rand(rng, b, Hkv, L, d), rand(rng, b, Hkv, L, d)
+    col = np.zeros((b, Hkv, M))
+    prot = np.ones(M, bool)                                # frozen cache: the slots keep their meaning
+    cw = rand(rng, M, d, 3)
+    orc.sequence_forward(q, kk, v, cw, B=B, M=M, protect=prot, attn_colsum=col)
+    want = np.zeros((b, Hkv, M))
+    g = Hq // Hkv
+    for n in range(L // B):
+        m = min(n * B, M)                                  # live slots before block n
+        blk = slice(n * B, (n + 1) * B)
+        for h in range(Hq):
+            keys = np.concatenate([kk[0, h // g, :m], kk[0, h // g, blk]])
+            s = q[0, h, blk] @ keys.T / np.sqrt(d)
+            s[:, m:] += np.where(np.tril(np.ones((B, B), bool)), 0.0, -np.inf)
+            p = np.exp(s - s.max(axis=1, keepdims=True))
+            p /= p.sum(axis=1, keepdims=True)
+            want[0, h // g, :m] += p[:, :m].sum(axis=0)
+    np.testing.assert_allclose(col, want, rtol=1e-11, atol=1e-13)
+    # every query row spends at most its whole probability on the cache
+    assert col.sum() <= Hq * L + 1e-9 and col.min() >= 0.0
+    # accumulation: a second call adds to what is there
+    before = col.copy()
+    orc.sequence_forward(q, kk, v, cw, B=B, M=M, protect=prot, attn_colsum=col)
+    np.testing.assert_allclose(col, 2 * before, rtol=1e-12)
