@@ -110,6 +110,16 @@ typedef struct lococo_cache {
    * all (batch, kv head) chains.  The words are read when the kernels run. */
   const uint32_t* protect;
   int64_t protect_chain_stride;
+  /* Accumulated attention scores, for policies that pick the slots to protect by them (heavy
+   * hitters).  Device pointer or NULL; fp32 [batch, n_kv_heads, M], ADDED to: every attention
+   * (step 3) adds, for each live cache slot, the probabilities that the block's queries (all
+   * query heads of the group) put on it.  The library never clears or remaps it: after a
+   * compression step an unprotected slot holds a different mixture, what its old score means is
+   * the caller's business.  With this pointer set, blocks of more than one token are attended by
+   * the shape-agnostic kernel and lococo_sequence_forward uses its step-by-step schedule (the
+   * MFMA attention kernel keeps no normalised probabilities to sum); one-token blocks (the
+   * generation stage) keep their kernel. */
+  float* attn_colsum;
 } lococo_cache;
 
 /* A [batch, heads, tokens, head_dim] tensor view; head_dim contiguous. */

@@ -37,7 +37,8 @@ class lococo_config(C.Structure):
 
 class lococo_cache(C.Structure):
     _fields_ = [("k", C.c_void_p * 2), ("v", C.c_void_p * 2), ("cur", C.c_int32),
-                ("len", C.c_int32), ("protect", C.c_void_p), ("protect_chain_stride", C.c_int64)]
+                ("len", C.c_int32), ("protect", C.c_void_p), ("protect_chain_stride", C.c_int64),
+                ("attn_colsum", C.c_void_p)]
 
 
 class lococo_tensor(C.Structure):
@@ -156,9 +157,11 @@ class Cache:
         self.vbuf = [torch.zeros(shape, dtype=dt, device=device) for _ in range(2)]
         self.c = lococo_cache((C.c_void_p * 2)(self.kbuf[0].data_ptr(), self.kbuf[1].data_ptr()),
                               (C.c_void_p * 2)(self.vbuf[0].data_ptr(), self.vbuf[1].data_ptr()),
-                              0, 0, None, 0)
+                              0, 0, None, 0, None)
         self.M, self.device = cfg.M, device
         self._protect = None
+        self.attn_colsum = None
+        self._chains = (cfg.batch, cfg.n_kv_heads, cfg.M)
 
     @property
     def len(self) -> int:
@@ -192,6 +195,12 @@ class Cache:
         self._protect = w.to(self.device).contiguous()
         self.c.protect = self._protect.data_ptr()
         self.c.protect_chain_stride = 0 if m.dim() == 1 else words
+
+    def track_attention(self, on: bool = True):
+        """Allocate (zeroed) or drop the fp32 [batch, n_kv_heads, M] accumulator of attention scores
+        per cache slot (see lococo_cache.attn_colsum in lococo.h); read it as `self.attn_colsum`."""
+        self.attn_colsum = torch.zeros(self._chains, dtype=torch.float32, device=self.device) if on else None
+        self.c.attn_colsum = _ptr(self.attn_colsum)
 
     def load(self, k: torch.Tensor, v: torch.Tensor, length: int):
         self.kbuf[self.c.cur].copy_(k)

@@ -139,6 +139,7 @@ lococo_status check_cache(const lococo_config* c, const lococo_cache* ca) {
     if (ca->protect_chain_stride != 0 && ca->protect_chain_stride < (c->M + 31) / 32)
       return fail(LOCOCO_EINVAL, "cache.protect_chain_stride must be 0 or at least ceil(M / 32) words");
   }
+  if ((uintptr_t)ca->attn_colsum & 3) return fail(LOCOCO_EINVAL, "cache.attn_colsum is not 4-byte aligned");
   return LOCOCO_OK;
 }
 
@@ -268,6 +269,7 @@ StepArgs make_args(const lococo_config* c, const lococo_qkvo* x, int64_t tok, in
   a.eps = c->norm_eps > 0.f ? c->norm_eps : 1e-6f;
   a.protect = ca->protect;
   a.protect_stride = ca->protect_chain_stride;
+  a.colsum = ca->attn_colsum;
   return a;
 }
 
@@ -300,12 +302,12 @@ AttnArgs attn_args_one_block(const StepArgs& a) {
 
 // Enqueue the attention of one block.
 lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, hipStream_t s) {
-  if (path == PATH_MFMA && attn_decode_supports(c->dtype, c->head_dim, a.Bn)) {
+  if (path == PATH_MFMA && attn_decode_supports(c->dtype, c->head_dim, a.Bn, c->M, a.colsum != nullptr)) {
     KTimer t(K_ATTN_DECODE, s);          // one query row per head: a matrix-vector product
     HIP_TRY(launch_attn_decode(a, s), "attention launch");
     return LOCOCO_OK;
   }
-  if (path == PATH_MFMA) {
+  if (path == PATH_MFMA && !a.colsum) {
     KTimer t(K_ATTN_MFMA, s);
     HIP_TRY(launch_attn_mfma(attn_args_one_block(a), s), "attention launch");
     return LOCOCO_OK;
@@ -570,7 +572,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   int64_t n_compress = 0, n_fill = 0;
   for (const auto& sg : plan) n_compress += sg.branch;
   while (n_fill < n && plan[(size_t)n_fill].branch == 0) ++n_fill;
-  if (path == PATH_MFMA && any_compress && workspace &&
+  if (path == PATH_MFMA && any_compress && workspace && !cache->attn_colsum &&
       ws_bytes >= history_ws_bytes(cfg, path, B, n_compress)) {
     // Batched-attention schedule: run the fill / compress recurrence first, keeping every
     // cache state, then one attention launch over all blocks, then publish the last state.

@@ -12,6 +12,10 @@
 // waves take groups of 4 keys round-robin.  Each 16-lane group keeps its own
 // online softmax state (reference, row sum, 8 output columns per lane); the 64
 // states of a workgroup are merged through LDS at the end.
+//
+// With accumulated attention scores asked for (StepArgs::colsum), the raw
+// scores of the cache slots are also kept in LDS, and once the row's reference
+// and sum are known every slot's probability is added to its accumulator.
 #include "lococo_internal.h"
 
 namespace lococo {
@@ -44,9 +48,12 @@ __device__ __forceinline__ void unpack8(const u32x4& r, float* f) {
   }
 }
 
+template <bool COLSUM>
 __global__ __launch_bounds__(kThreads) void attn_decode_k(StepArgs a) {
+  extern __shared__ float sc[];            // COLSUM: a.m raw scores (log2 units)
   __shared__ float part_o[kParts][kD + 4];
   __shared__ float part_m[kParts], part_l[kParts];
+  __shared__ float fin[2];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, grp = l >> 4, c16 = l & 15;
   const int hq = blockIdx.x % a.Hq, b = blockIdx.x / a.Hq, hkv = hq / a.group;
   const int ch = b * a.Hkv + hkv;
@@ -84,6 +91,10 @@ __global__ __launch_bounds__(kThreads) void attn_decode_k(StepArgs a) {
     for (int i = 0; i < 8; ++i) s1 = fmaf(q[i], kf[i], s1);
     s0 = row16_sum(s0);                            // scores in log2 units
     s1 = has1 ? row16_sum(s1) : -INFINITY;
+    if (COLSUM && c16 == 0) {
+      if (j0 < a.m) sc[j0] = s0;
+      if (j1 < a.m) sc[j1] = s1;
+    }
     const float m_new = fmaxf(m_run, fmaxf(s0, s1));
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     const float p0 = __builtin_amdgcn_exp2f(s0 - m_new), p1 = __builtin_amdgcn_exp2f(s1 - m_new);
@@ -119,22 +130,39 @@ __global__ __launch_bounds__(kThreads) void attn_decode_k(StepArgs a) {
       num = fmaf(wgt, part_o[p][tid], num);
       den = fmaf(wgt, part_l[p], den);
     }
+    if (COLSUM && tid == 0) {
+      fin[0] = mx;
+      fin[1] = den;
+    }
     const float r = num / den;
     // round to nearest even bf16
     uint32_t u = __float_as_uint(r);
     u += 0x7fffu + ((u >> 16) & 1u);
     ((uint16_t*)a.o.p)[b * a.o.sb + hq * a.o.sh + tid] = (uint16_t)(u >> 16);
   }
+  if (COLSUM) {
+    __syncthreads();
+    const float mx = fin[0], inv = 1.f / fin[1];
+    float* cs = a.colsum + (int64_t)ch * a.M;
+    for (int j = tid; j < a.m; j += kThreads) atomicAdd(cs + j, __builtin_amdgcn_exp2f(sc[j] - mx) * inv);
+  }
 }
+
+// LDS the kernel holds besides the scores: the partial states.
+constexpr size_t kStaticLds = sizeof(float) * (kParts * (kD + 4) + 2 * kParts + 2);
 
 }  // namespace
 
-bool attn_decode_supports(int dtype, int d, int Bn) {
+bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum) {
+  if (colsum && kStaticLds + sizeof(float) * (size_t)M > 64 * 1024) return false;   // scores must fit LDS
   return dtype == LOCOCO_BF16 && d == kD && Bn == 1;
 }
 
 hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(attn_decode_k, dim3(a.batch * a.Hq), dim3(kThreads), 0, s, a);
+  if (a.colsum)
+    hipLaunchKernelGGL(attn_decode_k<true>, dim3(a.batch * a.Hq), dim3(kThreads), sizeof(float) * (size_t)a.M, s, a);
+  else
+    hipLaunchKernelGGL(attn_decode_k<false>, dim3(a.batch * a.Hq), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -97,6 +97,10 @@ __global__ __launch_bounds__(kThreads) void attn_generic_k(StepArgs a) {
   }
   z = block_sum(z, red);
   __syncthreads();
+  if (a.colsum) {                 // accumulated attention per live cache slot
+    float* cs = a.colsum + (int64_t)(b * a.Hkv + hkv) * a.M;
+    for (int j = threadIdx.x; j < a.m; j += kThreads) atomicAdd(cs + j, sc[j] / z);
+  }
   T* o = (T*)a.o.p + b * a.o.sb + hq * a.o.sh + (int64_t)r * a.o.st;
   for (int c = threadIdx.x; c < a.d; c += kThreads) {
     float acc = 0.f;

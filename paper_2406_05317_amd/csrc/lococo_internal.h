@@ -35,6 +35,7 @@ struct StepArgs {
   float scale, eps;
   const uint32_t* protect;     // protected-slot bits (see lococo_cache), or null
   int64_t protect_stride;      // words between chains' masks, 0 = shared
+  float* colsum;               // accumulated attention per slot [chains, M] (see lococo_cache), or null
 };
 
 // Arguments of the fused compression kernel: `n_steps` consecutive compress steps of the scan in
@@ -147,7 +148,7 @@ bool attn_mfma_supports(int dtype, int d, const char** why);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 
 // ---- attention of one new token per sequence (attn_decode.hip): bf16, head_dim 128, Bn = 1
-bool attn_decode_supports(int dtype, int d, int Bn);
+bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum);
 hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s);
 
 }  // namespace lococo

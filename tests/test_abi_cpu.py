@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     # sizes the C compiler gives for the header's structs (LP64, natural alignment)
     assert C.sizeof(lb.lococo_config) == 72
-    assert C.sizeof(lb.lococo_cache) == 56
+    assert C.sizeof(lb.lococo_cache) == 64
     assert C.sizeof(lb.lococo_tensor) == 32
     assert C.sizeof(lb.lococo_qkvo) == 128
     assert C.sizeof(lb.lococo_seg) == 32
@@ -119,6 +119,10 @@ def test_call_argument_errors_enqueue_nothing():
     cache.protect, cache.protect_chain_stride = 0x70000, -1
     assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
     cache.protect, cache.protect_chain_stride = None, 0
+    cache.attn_colsum = 0x80002                        # misaligned score accumulator
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
+    assert b"attn_colsum" in L.lococo_last_error()
+    cache.attn_colsum = None
     assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 0, C.byref(cache), None) == lb.LOCOCO_EINVAL
     assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 4, C.byref(cache), None) == lb.LOCOCO_EINVAL
     assert b"q pointer" in L.lococo_last_error()
