@@ -31,7 +31,9 @@ EXTRA = {"compress_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form",
                                 # the pipeline stages must be unrolled completely (the slices are
                                 # selected by compile-time slot numbers); the default size limit of
                                 # "#pragma unroll" is too small for the width-21 instantiation
-                                "-mllvm", "-pragma-unroll-threshold=200000"]}
+                                "-mllvm", "-pragma-unroll-threshold=200000"],
+         # accumulators in ordinary registers: the softmax reads the scores where the MFMA left them
+         "attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:

@@ -32,7 +32,6 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kD = 128;
 constexpr int kThreads = 256;
-constexpr int BQ = 128;                       // query rows per workgroup
 constexpr int BK = 64;                        // keys per tile
 constexpr int KSTRIDE = kD * 2 + 16;          // bytes per key-tile row (conflict-free 16-byte reads)
 constexpr int VSTRIDE = kD * 2 + 64;          // bytes per value-tile row (conflict-free transposing reads)
@@ -57,26 +56,28 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
-// [cache ; block] rows through two raw buffer resources: an index outside a resource's range reads
-// as zero without touching memory, so OR-ing the two loads gives row j of the concatenation for
-// 0 <= j < T and zeros elsewhere (only tiles that straddle the seam need both).
-struct CatRows {
-  __amdgpu_buffer_rsrc_t cache, blk;
-  int m, blk_stride;
+// The keys of a block's attention are [cache ; block].  The walk over them is split at the seam:
+// tiles of 64 cache slots first (the last one ragged when m is no multiple of 64), then tiles of
+// 64 block keys, so that every tile comes from one array.  Rows are fetched through raw buffer
+// resources sized to the array: a row past its end reads as zero without touching memory.
+struct Rows {
+  __amdgpu_buffer_rsrc_t rsrc;
+  int stride;                                 // bytes between rows
 };
-__device__ __forceinline__ CatRows make_cat(const uint16_t* cache_rows, int m, const uint16_t* blk_rows,
-                                            int64_t blk_st, int Bn) {
-  CatRows c;
-  c.cache = __builtin_amdgcn_make_buffer_rsrc((void*)cache_rows, 0, m * kD * 2, 0x00020000);
-  c.blk = __builtin_amdgcn_make_buffer_rsrc((void*)blk_rows, 0, (int)((Bn - 1) * blk_st + kD) * 2,
-                                            0x00020000);
-  c.m = m;
-  c.blk_stride = (int)blk_st * 2;
-  return c;
+__device__ __forceinline__ Rows make_rows(const uint16_t* p, int n, int64_t st) {
+  Rows r;
+  r.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, n > 0 ? (int)((n - 1) * st + kD) * 2 : 0, 0x00020000);
+  r.stride = (int)st * 2;
+  return r;
 }
-struct Cat16 { u32x4 from_cache, from_blk; };
 
-__global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
+// QB = 32-query column blocks per wave: 1 (128 queries per workgroup, two workgroups per compute
+// unit) or 2 (256 queries, one workgroup: every key and value fragment read from LDS feeds two
+// MFMAs, which halves the LDS traffic per flop).
+template <int QB>
+__global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArgs a) {
+  constexpr int BQ = 128 * QB;                // query rows per workgroup
+  constexpr int WQ = 32 * QB;                 // query rows per wave
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Ks0 = smem;
   unsigned char* Vs0 = smem + 2 * KBYTES;
@@ -99,7 +100,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
   if (q0 >= Bn) return;
   const int hkv = hq / a.group;
   const int chain = b * a.Hkv + hkv;
-  const int T = m + Bn;
 
   const uint16_t* cache_k;
   const uint16_t* cache_v;
@@ -111,75 +111,87 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
     cache_k = (const uint16_t*)a.hist_k + slot;
     cache_v = (const uint16_t*)a.hist_v + slot;
   }
-  const CatRows cat_k =
-      make_cat(cache_k, m, (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + start * a.k.st, a.k.st, Bn);
-  const CatRows cat_v =
-      make_cat(cache_v, m, (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + start * a.v.st, a.v.st, Bn);
-  const uint16_t* qb = (const uint16_t*)a.q.p + b * a.q.sb + hq * a.q.sh + start * a.q.st;
+  const Rows ck = make_rows(cache_k, m, kD), cv = make_rows(cache_v, m, kD);
+  const Rows bk = make_rows((const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + start * a.k.st, Bn, a.k.st);
+  const Rows bv = make_rows((const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + start * a.v.st, Bn, a.v.st);
+  const uint16_t* qb_ptr = (const uint16_t*)a.q.p + b * a.q.sb + hq * a.q.sh + start * a.q.st;
   uint16_t* ob = (uint16_t*)a.o.p + b * a.o.sb + hq * a.o.sh + start * a.o.st;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
-  const int wq0 = q0 + 32 * w;          // first query row of this wave
-  const int qrow = wq0 + l31;           // this lane's query (block-relative)
+  const int wq0 = q0 + WQ * w;          // first query row of this wave
+  // this lane's queries (block-relative): wq0 + 32*qb + l31
 
-  // ---- this lane's query row as the B operand of S^T = K Q^T
-  bf16x8 qreg[8];
+  // ---- this lane's query rows as the B operand of S^T = K Q^T.  The rows are fetched whole
+  // (16 lanes x 16 bytes = one row per quarter wave, 1 KB contiguous per instruction), parked in a
+  // wave-private piece of the key-tile area and read back as operand fragments; rows past the
+  // block read as zero.
+  bf16x8 qreg[QB][8];
+  {
+    const Rows qr = make_rows(qb_ptr, Bn, a.q.st);
+    unsigned char* Qs = smem + w * (WQ * KSTRIDE);
+    u32x4 qrow_regs[WQ / 4];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (qrow < Bn) v = *(const u32x4*)(qb + (int64_t)qrow * a.q.st + ks * 16 + lh * 8);
-    qreg[ks] = __builtin_bit_cast(bf16x8, v);
+    for (int i = 0; i < WQ / 4; ++i)
+      qrow_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(qr.rsrc, (wq0 + i * 4 + (l >> 4)) * qr.stride + (l & 15) * 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < WQ / 4; ++i) *(u32x4*)(Qs + (i * 4 + (l >> 4)) * KSTRIDE + (l & 15) * 16) = qrow_regs[i];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        qreg[qb][ks] = *(const bf16x8*)(Qs + (32 * qb + l31) * KSTRIDE + ks * 32 + lh * 16);
   }
 
-  f32x16 oacc[4];
+  f32x16 oacc[QB][4];
 #pragma unroll
-  for (int ct = 0; ct < 4; ++ct)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[ct][i] = 0.f;
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[qb][ct][i] = 0.f;
   // running softmax reference (in raw score units) and row sum; exp(x * scale) = exp2(x * c)
   const float c = a.scale * kLog2e;
   const float lazy_raw = kLazy / a.scale;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
-  // keys this workgroup needs: the cache and the block up to its last query row
-  const int kend = min(T, m + q0 + BQ);
-  const int NT = (kend + BK - 1) / BK;
+  // tiles: NTc over the cache, then over the block up to this workgroup's last query row
+  const int NTc = (m + BK - 1) / BK;
+  const int NT = NTc + (min(Bn, q0 + BQ) + BK - 1) / BK;
 
-  // A tile that lies wholly in the cache or wholly in the block needs one load per chunk; only a
-  // tile straddling the seam issues both and ORs them.  (src: 1 = cache, 2 = block, 3 = both.)
-  Cat16 kreg[PER], vreg[PER];
-  auto tile_src = [&](int key0) { return (key0 < m ? 1 : 0) | (key0 + BK > m ? 2 : 0); };
-  auto stage_load = [&](int key0, int src) {
+  // Two sets of staging registers: the loads of tile t + 2 are issued at the top of iteration t
+  // and land in LDS at the end of iteration t + 1, so a load has two iterations to arrive.
+  u32x4 kreg0[PER], vreg0[PER], kreg1[PER], vreg1[PER];
+  auto stage_load = [&](int t, u32x4* kreg, u32x4* vreg) {
+    if (t >= NT) return;
+    const bool blk = t >= NTc;
+    const int row0 = (blk ? t - NTc : t) * BK;
+    const __amdgpu_buffer_rsrc_t rk = blk ? bk.rsrc : ck.rsrc, rv = blk ? bv.rsrc : cv.rsrc;
+    const int sk = blk ? bk.stride : ck.stride, sv = blk ? bv.stride : cv.stride;
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      const int j = key0 + (idx >> 4), chunk = idx & 15;
-      if (src & 1) {
-        kreg[it].from_cache = __builtin_amdgcn_raw_buffer_load_b128(cat_k.cache, j * (kD * 2) + chunk * 16, 0, 0);
-        vreg[it].from_cache = __builtin_amdgcn_raw_buffer_load_b128(cat_v.cache, j * (kD * 2) + chunk * 16, 0, 0);
-      }
-      if (src & 2) {
-        kreg[it].from_blk = __builtin_amdgcn_raw_buffer_load_b128(cat_k.blk, (j - m) * cat_k.blk_stride + chunk * 16, 0, 0);
-        vreg[it].from_blk = __builtin_amdgcn_raw_buffer_load_b128(cat_v.blk, (j - m) * cat_v.blk_stride + chunk * 16, 0, 0);
-      }
+      const int j = row0 + (idx >> 4), chunk = idx & 15;
+      kreg[it] = __builtin_amdgcn_raw_buffer_load_b128(rk, j * sk + chunk * 16, 0, 0);
+      vreg[it] = __builtin_amdgcn_raw_buffer_load_b128(rv, j * sv + chunk * 16, 0, 0);
     }
   };
-  auto stage_store = [&](int buf, int src) {
+  auto stage_store = [&](int buf, const u32x4* kreg, const u32x4* vreg) {
     unsigned char* Ks = Ks0 + buf * KBYTES;
     unsigned char* Vs = Vs0 + buf * VBYTES;
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
-      u32x4* kd = (u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16);
-      u32x4* vd = (u32x4*)(Vs + (idx >> 4) * VSTRIDE + (idx & 15) * 16);
-      if (src == 1) { *kd = kreg[it].from_cache; *vd = vreg[it].from_cache; }
-      else if (src == 2) { *kd = kreg[it].from_blk; *vd = vreg[it].from_blk; }
-      else { *kd = kreg[it].from_cache | kreg[it].from_blk; *vd = vreg[it].from_cache | vreg[it].from_blk; }
+      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = kreg[it];
+      *(u32x4*)(Vs + (idx >> 4) * VSTRIDE + (idx & 15) * 16) = vreg[it];
     }
   };
 
-  stage_load(0, tile_src(0));
-  stage_store(0, tile_src(0));
+  stage_load(0, kreg0, vreg0);
+  __syncthreads();                     // every wave has its query fragments: the area is free for tile 0
+  stage_store(0, kreg0, vreg0);
+  stage_load(1, kreg1, vreg1);
   __syncthreads();
 
   // value fragments: lane (head-dim column ct*32 + l31) x 8 keys.  The key order inside a
@@ -188,105 +200,154 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_k(AttnArgs a) {
   const int s16 = l & 15, g2 = (l >> 4) & 1;
   const int v_lane_off = (lh * 4 + (s16 >> 2)) * VSTRIDE + (16 * g2 + 4 * (s16 & 3)) * 2;
 
-  for (int t = 0; t < NT; ++t) {
+  auto iteration = [&](int t, u32x4* kld, u32x4* vld, const u32x4* kst, const u32x4* vst) {
     const int buf = t & 1;
-    const int key0 = t * BK;
+    const bool blk = t >= NTc;
+    const int row0 = (blk ? t - NTc : t) * BK;     // first key of the tile, within its array
     const unsigned char* Ks = Ks0 + buf * KBYTES;
     const unsigned char* Vs = Vs0 + buf * VBYTES;
-    // past the last tile the loads are out of range of their resource: zeros, no memory traffic
-    const int src_next = tile_src(key0 + BK);
-    stage_load(key0 + BK, src_next);
+    stage_load(t + 2, kld, vld);
 
-    if (key0 < m + wq0 + 32) {           // some key of the tile is visible to some query of this wave
+    if (!blk || row0 < wq0 + WQ) {       // some key of the tile is visible to some query of this wave
       // ---- S^T tile: keys x queries
-      f32x16 sacc[BK / 32];
+      f32x16 sacc[QB][BK / 32];
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt) {
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           const bf16x8 kv = *(const bf16x8*)(Ks + (kt * 32 + l31) * KSTRIDE + (ks * 16 + lh * 8) * 2);
-          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[ks], ks == 0 ? zero : sacc[kt], 0, 0, 0);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[qb][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[qb][ks], ks == 0 ? zero : sacc[qb][kt], 0, 0, 0);
         }
       }
-      // ---- mask, online softmax with a lazy reference (everything of one query sits in one lane pair)
-      if (key0 + BK > m + wq0 || key0 + BK > T) {
+      // ---- mask: cache rows at and beyond m; block keys after the query
+      if (blk ? row0 + BK - 1 > wq0 : row0 + BK > m) {
+        const int lim0 = blk ? wq0 + l31 : m - 1;    // last visible row for qb = 0 (block: the query itself)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          const int lim = blk ? lim0 + 32 * qb : lim0;
+#pragma unroll
+          for (int kt = 0; kt < BK / 32; ++kt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = row0 + kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+              if (key > lim) sacc[qb][kt][i] = -INFINITY;
+            }
+        }
+      }
+      // ---- online softmax with a lazy reference (everything of one query sits in one lane pair)
+      float psum[QB];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float mx = sacc[qb][0][0];
 #pragma unroll
         for (int kt = 0; kt < BK / 32; ++kt)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = key0 + kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-            if (key >= T || key - m > qrow) sacc[kt][i] = -INFINITY;
-          }
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[qb][kt][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // The reference only moves when the row maximum outgrows it by kLazy (in exponent units),
+        // so exp(..) stays below e^kLazy and the accumulator is rescaled rarely.
+        const bool bump = mx > m_run[qb] + lazy_raw;
+        const float m_new = bump ? mx : m_run[qb];
+        if (__any(bump)) {
+          const float alpha = bump ? __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c) : 1.0f;
+          l_run[qb] *= alpha;
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[qb][ct][i] *= alpha;
+        }
+        m_run[qb] = m_new;
+        const float mc = m_new * c;
+#pragma unroll
+        for (int kt = 0; kt < BK / 32; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[qb][kt][i] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kt][i], c, -mc));
+        psum[qb] = 0.f;
       }
-      float mx = sacc[0][0];
-#pragma unroll
-      for (int kt = 0; kt < BK / 32; ++kt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kt][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      // The reference only moves when the row maximum outgrows it by kLazy (in exponent units),
-      // so exp(..) stays below e^kLazy and the accumulator is rescaled rarely.
-      const bool bump = mx > m_run + lazy_raw;
-      const float m_new = bump ? mx : m_run;
-      if (__any(bump)) {
-        const float alpha = bump ? __builtin_amdgcn_exp2f((m_run - m_new) * c) : 1.0f;
-        l_run *= alpha;
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
-      }
-      m_run = m_new;
-      const float mc = m_new * c;
-#pragma unroll
-      for (int kt = 0; kt < BK / 32; ++kt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[kt][i] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][i], c, -mc));
-      float psum = 0.f;
       // ---- O^T += V^T P^T; contraction slot j of step u holds key (u*16 + (j/4)*8 + lh*4 + j%4)
 #pragma unroll
       for (int kt = 0; kt < BK / 32; ++kt)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          u32x4 pp;
+          bf16x8 pv[QB];
 #pragma unroll
-          for (int j2 = 0; j2 < 4; ++j2) {
-            pp[j2] = pack_bf16(sacc[kt][u * 8 + 2 * j2], sacc[kt][u * 8 + 2 * j2 + 1]);
-            psum += sacc[kt][u * 8 + 2 * j2] + sacc[kt][u * 8 + 2 * j2 + 1];
+          for (int qb = 0; qb < QB; ++qb) {
+            u32x4 pp;
+#pragma unroll
+            for (int j2 = 0; j2 < 4; ++j2) {
+              pp[j2] = pack_bf16(sacc[qb][kt][u * 8 + 2 * j2], sacc[qb][kt][u * 8 + 2 * j2 + 1]);
+              psum[qb] += sacc[qb][kt][u * 8 + 2 * j2] + sacc[qb][kt][u * 8 + 2 * j2 + 1];
+            }
+            pv[qb] = __builtin_bit_cast(bf16x8, pp);
           }
-          const bf16x8 pv = __builtin_bit_cast(bf16x8, pp);
 #pragma unroll
           for (int ct = 0; ct < 4; ++ct) {
             const unsigned char* vp = Vs + (kt * 32 + u * 16) * VSTRIDE + (ct * 32) * 2 + v_lane_off;
             const s16x4 y0 = lds_read_tr(vp);
             const s16x4 y1 = lds_read_tr(vp + 8 * VSTRIDE);
             const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
-            oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, yy), pv,
-                                                               oacc[ct], 0, 0, 0);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+              oacc[qb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, yy), pv[qb],
+                                                                     oacc[qb][ct], 0, 0, 0);
           }
         }
-      psum += __shfl_xor(psum, 32, 64);
-      l_run += psum;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb] + __shfl_xor(psum[qb], 32, 64);
     }
-    stage_store(buf ^ 1, src_next);
+    stage_store(buf ^ 1, kst, vst);
     __syncthreads();
+  };
+  for (int t = 0; t < NT; t += 2) {
+    iteration(t, kreg0, vreg0, kreg1, vreg1);
+    if (t + 1 < NT) iteration(t + 1, kreg1, vreg1, kreg0, vreg0);
   }
 
-  // ---- O = O^T / l: lane holds query qrow, head-dim columns ct*32 + (i/4)*8 + lh*4 + i%4
-  if (qrow < Bn) {
-    const float inv = 1.0f / l_run;
-    uint16_t* orow = ob + (int64_t)qrow * a.o.st;
+  // ---- O = O^T / l: lane holds its queries, head-dim columns ct*32 + (i/4)*8 + lh*4 + i%4.
+  // The rows are put together in a wave-private piece of LDS (the loop's last barrier has been
+  // passed, nobody reads tiles any more) and leave as whole rows, 1 KB contiguous per instruction.
+  unsigned char* Os = smem + w * (WQ * KSTRIDE);
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float inv = 1.0f / l_run[qb];
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x2 pk;
-        pk[0] = pack_bf16(oacc[ct][g * 4 + 0] * inv, oacc[ct][g * 4 + 1] * inv);
-        pk[1] = pack_bf16(oacc[ct][g * 4 + 2] * inv, oacc[ct][g * 4 + 3] * inv);
-        *(u32x2*)(orow + ct * 32 + g * 8 + lh * 4) = pk;
+        pk[0] = pack_bf16(oacc[qb][ct][g * 4 + 0] * inv, oacc[qb][ct][g * 4 + 1] * inv);
+        pk[1] = pack_bf16(oacc[qb][ct][g * 4 + 2] * inv, oacc[qb][ct][g * 4 + 3] * inv);
+        *(u32x2*)(Os + (32 * qb + l31) * KSTRIDE + (ct * 32 + g * 8 + lh * 4) * 2) = pk;
       }
   }
+#pragma unroll
+  for (int i = 0; i < WQ / 4; ++i) {
+    const int row = i * 4 + (l >> 4);
+    const u32x4 v = *(const u32x4*)(Os + row * KSTRIDE + (l & 15) * 16);
+    if (wq0 + row < Bn) *(u32x4*)(ob + (int64_t)(wq0 + row) * a.o.st + (l & 15) * 8) = v;
+  }
+}
+
+template <int QB>
+hipError_t launch_qb(const AttnArgs& a_in, hipStream_t s) {
+  AttnArgs a = a_in;
+  constexpr int BQ = 128 * QB;
+  a.qtiles = (a.B + BQ - 1) / BQ;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_k<QB>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int64_t total = (int64_t)a.qtiles * a.Hq * a.batch * a.n_seg;
+  if (total <= 0) return hipSuccess;
+  if (total > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attn_mfma_k<QB>, dim3((unsigned)total), dim3(kThreads), LDS_BYTES, s, a);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -297,21 +358,8 @@ bool attn_mfma_supports(int dtype, int d, const char** why) {
   return true;
 }
 
-hipError_t launch_attn_mfma(const AttnArgs& a_in, hipStream_t s) {
-  AttnArgs a = a_in;
-  a.qtiles = (a.B + BQ - 1) / BQ;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_k,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  const int64_t total = (int64_t)a.qtiles * a.Hq * a.batch * a.n_seg;
-  if (total <= 0) return hipSuccess;
-  if (total > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attn_mfma_k, dim3((unsigned)total), dim3(kThreads), LDS_BYTES, s, a);
-  return hipGetLastError();
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
+  return launch_qb<1>(a, s);
 }
 
 }  // namespace lococo
