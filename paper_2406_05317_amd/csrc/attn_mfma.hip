@@ -18,6 +18,8 @@
 // diagonal are skipped.  Shapes taken: head_dim = 128, bf16.
 #include "lococo_internal.h"
 
+#include <type_traits>
+
 namespace lococo {
 namespace {
 
@@ -31,14 +33,12 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kD = 128;
-constexpr int kThreads = 256;
 constexpr int BK = 64;                        // keys per tile
 constexpr int KSTRIDE = kD * 2 + 16;          // bytes per key-tile row (conflict-free 16-byte reads)
 constexpr int VSTRIDE = kD * 2 + 64;          // bytes per value-tile row (conflict-free transposing reads)
 constexpr int KBYTES = BK * KSTRIDE;
 constexpr int VBYTES = BK * VSTRIDE;
 constexpr int LDS_BYTES = 2 * (KBYTES + VBYTES);
-constexpr int PER = BK * 16 / kThreads;       // 16-byte chunks of a key (or value) tile per thread
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.0f;                 // the softmax reference lags the row maximum by at most this much
 
@@ -61,22 +61,40 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char* p) {
 // 64 block keys, so that every tile comes from one array.  Rows are fetched through raw buffer
 // resources sized to the array: a row past its end reads as zero without touching memory.
 struct Rows {
-  __amdgpu_buffer_rsrc_t rsrc;
+  u32x4 rsrc;                                 // raw buffer resource: base, 0 stride, bytes, 32-bit format
   int stride;                                 // bytes between rows
 };
 __device__ __forceinline__ Rows make_rows(const uint16_t* p, int n, int64_t st) {
   Rows r;
-  r.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, n > 0 ? (int)((n - 1) * st + kD) * 2 : 0, 0x00020000);
+  const uint64_t base = (uint64_t)p;
+  r.rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+  r.rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+  r.rsrc[2] = __builtin_amdgcn_readfirstlane(n > 0 ? (uint32_t)((n - 1) * st + kD) * 2u : 0u);
+  r.rsrc[3] = 0x00020000u;
   r.stride = (int)st * 2;
   return r;
 }
+// A 16-byte load the compiler does not wait for: the caller counts the loads in flight and puts
+// `wait_loads<N>()` (at most N of the newest still pending; they complete in order) before the
+// first use of the register.  An offset beyond the resource reads zero and moves no data.
+__device__ __forceinline__ void load16_async(u32x4& dst, const u32x4& rsrc, int voff) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(voff), "s"(rsrc) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
 
-// QB = 32-query column blocks per wave: 1 (128 queries per workgroup, two workgroups per compute
-// unit) or 2 (256 queries, one workgroup: every key and value fragment read from LDS feeds two
-// MFMAs, which halves the LDS traffic per flop).
-template <int QB>
-__global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArgs a) {
-  constexpr int BQ = 128 * QB;                // query rows per workgroup
+// QB = 32-query column blocks per wave, NW = waves per workgroup.  Launched with QB = 1, NW = 4:
+// 128 queries per workgroup, two workgroups per compute unit.  (QB = 2 halves the LDS reads per
+// flop but needs the whole register file for one wave per SIMD, which then has to issue every
+// vector, LDS and matrix instruction itself; NW = 8 halves the staging per query but loses the
+// second, independent workgroup.  Both measured slower on the 32 K-token workload.)
+template <int QB, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_mfma_k(AttnArgs a) {
+  constexpr int kThreads = 64 * NW;           // NW waves, 32 * QB query rows each
+  constexpr int BQ = 32 * QB * NW;            // query rows per workgroup
+  constexpr int PER = BK * 16 / kThreads;     // 16-byte chunks of a key (or value) tile per thread
   constexpr int WQ = 32 * QB;                 // query rows per wave
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Ks0 = smem;
@@ -132,7 +150,10 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArg
     u32x4 qrow_regs[WQ / 4];
 #pragma unroll
     for (int i = 0; i < WQ / 4; ++i)
-      qrow_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(qr.rsrc, (wq0 + i * 4 + (l >> 4)) * qr.stride + (l & 15) * 16, 0, 0);
+      load16_async(qrow_regs[i], qr.rsrc, (wq0 + i * 4 + (l >> 4)) * qr.stride + (l & 15) * 16);
+    wait_loads<0>();
+#pragma unroll
+    for (int i = 0; i < WQ / 4; ++i) asm volatile("" : "+v"(qrow_regs[i]));
 #pragma unroll
     for (int i = 0; i < WQ / 4; ++i) *(u32x4*)(Qs + (i * 4 + (l >> 4)) * KSTRIDE + (l & 15) * 16) = qrow_regs[i];
 #pragma unroll
@@ -161,25 +182,32 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArg
   const int NT = NTc + (min(Bn, q0 + BQ) + BK - 1) / BK;
 
   // Two sets of staging registers: the loads of tile t + 2 are issued at the top of iteration t
-  // and land in LDS at the end of iteration t + 1, so a load has two iterations to arrive.
+  // and land in LDS at the end of iteration t + 1, so a load has two iterations to arrive (the
+  // loaded latency of this access pattern is about one iteration).  Every call issues exactly
+  // 2 * PER loads per lane, also past the last tile (offsets out of range: zeros, no traffic), so
+  // that "at most 2 * PER pending" always means "the older set has arrived".
   u32x4 kreg0[PER], vreg0[PER], kreg1[PER], vreg1[PER];
   auto stage_load = [&](int t, u32x4* kreg, u32x4* vreg) {
-    if (t >= NT) return;
     const bool blk = t >= NTc;
     const int row0 = (blk ? t - NTc : t) * BK;
-    const __amdgpu_buffer_rsrc_t rk = blk ? bk.rsrc : ck.rsrc, rv = blk ? bv.rsrc : cv.rsrc;
+    const u32x4 rk = blk ? bk.rsrc : ck.rsrc, rv = blk ? bv.rsrc : cv.rsrc;
     const int sk = blk ? bk.stride : ck.stride, sv = blk ? bv.stride : cv.stride;
+    const int beyond = t >= NT ? 0x7fff0000 : 0;
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
       const int j = row0 + (idx >> 4), chunk = idx & 15;
-      kreg[it] = __builtin_amdgcn_raw_buffer_load_b128(rk, j * sk + chunk * 16, 0, 0);
-      vreg[it] = __builtin_amdgcn_raw_buffer_load_b128(rv, j * sv + chunk * 16, 0, 0);
+      load16_async(kreg[it], rk, (j * sk + chunk * 16) | beyond);
+      load16_async(vreg[it], rv, (j * sv + chunk * 16) | beyond);
     }
   };
-  auto stage_store = [&](int buf, const u32x4* kreg, const u32x4* vreg) {
+  // `pending`: loads issued after the set being stored (0 or 2 * PER)
+  auto stage_store = [&](int buf, u32x4* kreg, u32x4* vreg, auto pending) {
     unsigned char* Ks = Ks0 + buf * KBYTES;
     unsigned char* Vs = Vs0 + buf * VBYTES;
+    wait_loads<decltype(pending)::value>();
+#pragma unroll
+    for (int it = 0; it < PER; ++it) asm volatile("" : "+v"(kreg[it]), "+v"(vreg[it]));
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const int idx = tid + it * kThreads;
@@ -190,7 +218,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArg
 
   stage_load(0, kreg0, vreg0);
   __syncthreads();                     // every wave has its query fragments: the area is free for tile 0
-  stage_store(0, kreg0, vreg0);
+  stage_store(0, kreg0, vreg0, std::integral_constant<int, 0>());
   stage_load(1, kreg1, vreg1);
   __syncthreads();
 
@@ -200,7 +228,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArg
   const int s16 = l & 15, g2 = (l >> 4) & 1;
   const int v_lane_off = (lh * 4 + (s16 >> 2)) * VSTRIDE + (16 * g2 + 4 * (s16 & 3)) * 2;
 
-  auto iteration = [&](int t, u32x4* kld, u32x4* vld, const u32x4* kst, const u32x4* vst) {
+  auto iteration = [&](int t, u32x4* kld, u32x4* vld, u32x4* kst, u32x4* vst) {
     const int buf = t & 1;
     const bool blk = t >= NTc;
     const int row0 = (blk ? t - NTc : t) * BK;     // first key of the tile, within its array
@@ -298,7 +326,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArg
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb] + __shfl_xor(psum[qb], 32, 64);
     }
-    stage_store(buf ^ 1, kst, vst);
+    stage_store(buf ^ 1, kst, vst, std::integral_constant<int, 2 * PER>());
     __syncthreads();
   };
   for (int t = 0; t < NT; t += 2) {
@@ -331,14 +359,15 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 2 : 1) void attn_mfma_k(AttnArg
   }
 }
 
-template <int QB>
+template <int QB, int NW>
 hipError_t launch_qb(const AttnArgs& a_in, hipStream_t s) {
+  constexpr int kThreads = 64 * NW;
   AttnArgs a = a_in;
-  constexpr int BQ = 128 * QB;
+  constexpr int BQ = 32 * QB * NW;
   a.qtiles = (a.B + BQ - 1) / BQ;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_k<QB>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_k<QB, NW>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -346,7 +375,7 @@ hipError_t launch_qb(const AttnArgs& a_in, hipStream_t s) {
   const int64_t total = (int64_t)a.qtiles * a.Hq * a.batch * a.n_seg;
   if (total <= 0) return hipSuccess;
   if (total > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attn_mfma_k<QB>, dim3((unsigned)total), dim3(kThreads), LDS_BYTES, s, a);
+  hipLaunchKernelGGL((attn_mfma_k<QB, NW>), dim3((unsigned)total), dim3(kThreads), LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
@@ -359,7 +388,12 @@ bool attn_mfma_supports(int dtype, int d, const char** why) {
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
-  return launch_qb<1>(a, s);
+  // rows are addressed with 32-bit byte offsets inside resources of less than 2 GiB
+  const int64_t lim = 0x7fff0000;
+  for (const View* v : {&a.q, &a.k, &a.v})
+    if (((int64_t)a.B * v->st + kD) * 2 >= lim) return hipErrorInvalidValue;
+  if ((int64_t)a.M * kD * 2 >= lim) return hipErrorInvalidValue;
+  return launch_qb<1, 4>(a, s);
 }
 
 }  // namespace lococo
