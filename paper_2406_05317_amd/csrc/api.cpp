@@ -225,6 +225,13 @@ int spin_limit() {
   const char* e = getenv("LOCOCO_SPIN_LIMIT");
   return e ? atoi(e) : (1 << 24);
 }
+// LOCOCO_CHAIN_SYNC=device makes the slot tiles of a chain always meet with device-scope release and
+// acquire between the steps of the one-launch scan; by default they skip the L2 write-back when
+// they find themselves on one XCD (see compress_mfma.hip).
+bool chain_sync_through_l2() {
+  const char* e = getenv("LOCOCO_CHAIN_SYNC");
+  return !(e && !strcmp(e, "device"));
+}
 // LOCOCO_SCAN_LAUNCHES=steps forces one launch per compress step (the default is one launch for
 // the whole scan whenever every workgroup can be resident at once).
 bool scan_in_one_launch(const lococo_config* c) {
@@ -604,6 +611,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         sa.sync = nullptr;
         sa.status = nullptr;
         sa.spin_limit = spin_limit();
+        sa.same_l2_allowed = chain_sync_through_l2() ? 1 : 0;
         KTimer t(K_COMPRESS_MFMA, s);
         HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
                 "compress scan launch");

@@ -146,9 +146,13 @@ __device__ __forceinline__ CatRows make_cat(const uint16_t* cache_rows, int m, c
 }
 // The two halves are OR-ed only when the data is stored to LDS, many steps after the loads were issued.
 struct Cat16 { u32x4 from_cache, from_blk; };
+// Cache rows are read at device scope (sc1: served by the L2, never by this CU's L1): in the
+// one-launch scan they were written by other workgroups a step ago, and every row is read once per
+// workgroup anyway.
+constexpr int kDeviceScope = 1 << 4;
 __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) {
   Cat16 r;
-  r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, 0);
+  r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, kDeviceScope);
   r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
   return r;
 }
@@ -187,7 +191,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // per-step quantities, set at the top of the step loop
   int T = 0, m = 0, NT = 0;
   CatRows cat_k, cat_v;
-  const uint16_t *cat_k_rows = nullptr, *cat_v_rows = nullptr;   // the chain's source cache rows
   // protected-slot bits of this chain (see lococo_cache.protect), or null
   const uint32_t* pwords = PROT ? a.protect + (int64_t)ch * a.protect_stride : nullptr;
 
@@ -499,8 +502,59 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     __builtin_amdgcn_sched_barrier(0);
   };
 
+  // ---- meeting point of the slot tiles of a chain between two steps of the one-launch scan.
+  // Round r is complete when the chain's counter has reached tiles * (r + 1).
+  //
+  // General form: workgroup barrier, thread 0 does a device-scope release increment (which writes
+  // the L2 back: every dirty line of the XCD, about 3 us per step on the 32 K-token workload) and
+  // polls, device-scope acquire, workgroup barrier.  One wave pays for the cache maintenance.
+  //
+  // When all tiles of the chain run on one XCD they share one L2, and nothing has to be written
+  // back or invalidated there: stores go through the CU's L1 to the L2 and have arrived when the
+  // wave's store counter reaches zero, and the cache rows are read at device scope (see
+  // load_cat16).  So each wave waits for its stores, the workgroup meets, thread 0 increments and
+  // polls with relaxed device-scope atomics, the workgroup meets again.  Whether the tiles share
+  // an XCD is not assumed from the workgroup numbering: round 0, before the first step, is a
+  // general-form meeting in which every tile reports the XCD it runs on.
   __shared__ int bail;                       // a chain wait timed out: leave
-  if (tid == 0) bail = 0;
+  __shared__ int same_l2;
+  if (tid == 0) { bail = 0; same_l2 = 0; }
+  __syncthreads();
+  auto chain_sync = [&](int round) -> bool {
+    const bool fast = same_l2 != 0;          // LDS word written before the previous workgroup barrier
+    if (fast) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) {
+      if (fast) __hip_atomic_fetch_add(sa.sync + ch, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else __hip_atomic_fetch_add(sa.sync + ch, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t target = (uint32_t)tiles * (uint32_t)(round + 1);
+      int polls = 0;
+      while (__hip_atomic_load(sa.sync + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        __builtin_amdgcn_s_sleep(2);
+        if (++polls > sa.spin_limit) {         // bounded: never spin forever on a workgroup that is not there
+          __hip_atomic_store(sa.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          bail = 1;
+          break;
+        }
+      }
+      if (!fast) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    __syncthreads();
+    return bail == 0;
+  };
+  if (sa.n_steps > 1) {
+    uint32_t* xcd_mask = sa.sync + (int64_t)a.batch * a.Hkv + 1 + ch;
+    if (tid == 0) {
+      const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | ((4 - 1) << 11));   // XCC_ID, bits [3:0]
+      __hip_atomic_fetch_or(xcd_mask, 1u << xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (!chain_sync(0)) return;
+    if (tid == 0) {
+      const uint32_t mask = __hip_atomic_load(xcd_mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      same_l2 = (mask & (mask - 1)) == 0 && sa.same_l2_allowed;
+    }
+    __syncthreads();
+  }
 
   for (int step = 0; step < sa.n_steps; ++step) {
   // ---- this step's inputs: source state, occupancy, block
@@ -514,8 +568,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
                                       : (const uint16_t*)sa.out_k + (int64_t)(step - 1) * sa.out_stride;
     const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v
                                       : (const uint16_t*)sa.out_v + (int64_t)(step - 1) * sa.out_stride;
-    cat_k_rows = src_k + (int64_t)ch * a.M * kD;
-    cat_v_rows = src_v + (int64_t)ch * a.M * kD;
     cat_k = make_cat(src_k + (int64_t)ch * a.M * kD, m,
                      (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + tok * a.k.st, a.k.st, Bn);
     cat_v = make_cat(src_v + (int64_t)ch * a.M * kD, m,
@@ -573,13 +625,14 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       if (i0 + rt * 32 + 32 > m) keep &= (1u << (m - i0 - rt * 32)) - 1u;
     }
     if (keep) {
-      const uint16_t* sk = cat_k_rows + (int64_t)(i0 + rt * 32) * kD;
-      const uint16_t* sv_ = cat_v_rows + (int64_t)(i0 + rt * 32) * kD;
       for (int e = tid; e < 32 * 16; e += kThreads) {        // (slot, 16-byte chunk)
         const int r = e >> 4, c16 = e & 15;
-        if ((keep >> r) & 1u) {
-          *(u32x4*)(nk + (int64_t)(rt * 32 + r) * kD + c16 * 8) = *(const u32x4*)(sk + (int64_t)r * kD + c16 * 8);
-          *(u32x4*)(nv + (int64_t)(rt * 32 + r) * kD + c16 * 8) = *(const u32x4*)(sv_ + (int64_t)r * kD + c16 * 8);
+        if ((keep >> r) & 1u) {                              // live slot: inside the cache resources
+          const int off = (i0 + rt * 32 + r) * (kD * 2) + c16 * 16;
+          *(u32x4*)(nk + (int64_t)(rt * 32 + r) * kD + c16 * 8) =
+              __builtin_amdgcn_raw_buffer_load_b128(cat_k.cache, off, 0, kDeviceScope);
+          *(u32x4*)(nv + (int64_t)(rt * 32 + r) * kD + c16 * 8) =
+              __builtin_amdgcn_raw_buffer_load_b128(cat_v.cache, off, 0, kDeviceScope);
         }
       }
       if ((keep >> l31) & 1u) continue;
@@ -596,29 +649,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       }
   }
 
-  // ---- the next step reads what every slot tile of this chain has just written.
-  // The barrier orders every wave's stores before thread 0's device-scope release (the counter
-  // increment); thread 0's device-scope acquire after the wait, followed by the second barrier,
-  // orders every wave's loads of the next step after the other tiles' stores.  One wave per
-  // workgroup pays for the cache write-back and invalidate instead of all four.
+  // ---- the next step reads what every slot tile of this chain has just written
   if (step + 1 < sa.n_steps) {
-    __syncthreads();
-    if (tid == 0) {
-      __hip_atomic_fetch_add(sa.sync + ch, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-      const uint32_t target = (uint32_t)tiles * (uint32_t)(step + 1);
-      int polls = 0;
-      while (__hip_atomic_load(sa.sync + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-        __builtin_amdgcn_s_sleep(2);
-        if (++polls > sa.spin_limit) {         // bounded: never spin forever on a workgroup that is not there
-          __hip_atomic_store(sa.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          bail = 1;
-          break;
-        }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    }
-    __syncthreads();
-    if (bail) break;
+    if (!chain_sync(step + 1)) break;
   }
   }  // step loop
 }
@@ -728,6 +761,7 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.sync = nullptr;
   sa.status = nullptr;
   sa.spin_limit = 0;
+  sa.same_l2_allowed = 0;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
   return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
@@ -738,12 +772,13 @@ bool compress_scan_fits(int batch, int Hkv, int M, int k_width, int n_cu) {
   return (int64_t)batch * Hkv * (M / bm) <= n_cu;
 }
 
+// [chain counters][status word][per chain: bit mask of the XCDs its slot tiles run on]
 size_t compress_scan_sync_bytes(int batch, int Hkv) {
-  return ((size_t)batch * Hkv + 1) * sizeof(uint32_t);
+  return (2 * (size_t)batch * Hkv + 1) * sizeof(uint32_t);
 }
 
 hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, hipStream_t s) {
-  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws, batch * Hkv + 1);
+  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws, 2 * batch * Hkv + 1);
   return hipGetLastError();
 }
 

@@ -56,6 +56,7 @@ struct ScanArgs {
   uint32_t* sync;
   int32_t* status;
   int32_t spin_limit;
+  int32_t same_l2_allowed;   // 0: always meet with device-scope release / acquire (see compress_mfma.hip)
 };
 
 // Arguments of the MFMA attention kernel: one block, or every block of a scan

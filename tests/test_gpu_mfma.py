@@ -146,6 +146,31 @@ def test_one_launch_scan_equals_one_launch_per_step(monkeypatch):
     compare_scan(w, a, want, what="one-launch scan")
 
 
+@pytest.mark.parametrize("case", [
+    dict(M=256, B=128, L=1536, n_q_heads=8, n_kv_heads=8),            # 4 slot tiles per chain
+    dict(M=512, B=512, L=4096, n_q_heads=16, n_kv_heads=16),          # 128 workgroups, 8 tiles per chain
+    dict(M=128, B=96, L=1000, n_q_heads=4, n_kv_heads=2, batch=2),    # ragged blocks, grouped heads
+])
+def test_chain_meeting_through_the_shared_l2_equals_the_device_scope_one(case, monkeypatch):
+    """Between the steps of the one-launch scan the slot tiles of a chain meet without writing the
+    L2 back when they find themselves on one XCD; with LOCOCO_CHAIN_SYNC=device they always use
+    device-scope release / acquire.  Same kernel arithmetic either way: bit-identical results,
+    several runs each (a stale read would show as a difference)."""
+    w = _w(**case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    monkeypatch.setenv("LOCOCO_CHAIN_SYNC", "device")
+    ref = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    monkeypatch.delenv("LOCOCO_CHAIN_SYNC")
+    for _ in range(4):
+        got = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+        for x, y in zip(got[:3], ref[:3]):
+            assert torch.equal(x, y)
+        assert got[3:] == ref[3:]
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    compare_scan(w, ref, want, what="device-scope chain meeting")
+
+
 def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
     """Forced from the host: with no polls allowed, the first slot tile to finish a step cannot wait
     for its chain, leaves the kernel, and the status word says so.  Every workgroup still exits."""
