@@ -582,18 +582,31 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   m_run = -INFINITY;
   l_run = 0.f;
 
-  // ---- prologue: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way
+  // ---- prologue: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way.  All
+  // loads are issued before the first store (the accumulators' registers are free here), so the
+  // step starts after one memory latency, not three.
+  {
+    Cat16 xpro[3][G::XPER];
 #pragma unroll
-  for (int t = 0; t < 3; ++t) {
+    for (int t = 0; t < 3; ++t)
 #pragma unroll
-    for (int it = 0; it < G::XPER; ++it) load_x(it, t * BN);
+      for (int it = 0; it < G::XPER; ++it) {
+        const int item = tid + it * kThreads;
+        xpro[t][it] = load_cat16(cat_k, t * BN - G::PAD + (item >> 4), item & 15);
+      }
 #pragma unroll
-    for (int it = 0; it < G::XPER; ++it) store_x(it, t * BN, Xs0 + t * G::XBYTES);
+    for (int it = 0; it < G::XPER; ++it) load_x(it, 3 * BN);
+#pragma unroll
+    for (int it = 0; it < G::VPER; ++it) load_v(it, 0);
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int it = 0; it < G::XPER; ++it) {
+        const int item = tid + it * kThreads;
+        *(u32x4*)(Xs0 + t * G::XBYTES + (item >> 4) * G::XSTRIDE + (item & 15) * 16) =
+            xpro[t][it].from_cache | xpro[t][it].from_blk;
+      }
   }
-#pragma unroll
-  for (int it = 0; it < G::XPER; ++it) load_x(it, 3 * BN);
-#pragma unroll
-  for (int it = 0; it < G::VPER; ++it) load_v(it, 0);
   __syncthreads();
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
@@ -609,35 +622,27 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   }
   stage(NT, no, no, yes);
 
-  // ---- normalise by the row sums and store the new cache rows, 4 columns (8 bytes) per store
+  // ---- normalise by the row sums and store the new cache rows.  A lane holds 4 columns of a
+  // slot at a time; the rows are put together in the key-tile area of LDS (free after the last
+  // stage) and leave as whole rows, 1 KB of contiguous memory per wave instruction.
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
   __syncthreads();
   uint16_t* nk = (uint16_t*)sa.out_k + (int64_t)step * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
   uint16_t* nv = (uint16_t*)sa.out_v + (int64_t)step * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
-  uint16_t* obase = (w < 2 ? nk : nv) + 64 * (w & 1);
+  unsigned char* Orows = Xs0;                // [K rows of the tile ; V rows of the tile][XSTRIDE]
+  static_assert(2 * BM * G::XSTRIDE <= G::NXBUF * G::XBYTES, "the output rows fit the key-tile area");
+  uint32_t keep[G::RT];
 #pragma unroll
   for (int rt = 0; rt < G::RT; ++rt) {
-    const int slot = rt * 32 + l31;
     // a live protected slot keeps its old row (copied below) instead of Eq. 4a / 4b
-    uint32_t keep = 0;
+    keep[rt] = 0;
     if (PROT && i0 + rt * 32 < m) {
-      keep = pwords[(i0 >> 5) + rt];
-      if (i0 + rt * 32 + 32 > m) keep &= (1u << (m - i0 - rt * 32)) - 1u;
+      keep[rt] = pwords[(i0 >> 5) + rt];
+      if (i0 + rt * 32 + 32 > m) keep[rt] &= (1u << (m - i0 - rt * 32)) - 1u;
     }
-    if (keep) {
-      for (int e = tid; e < 32 * 16; e += kThreads) {        // (slot, 16-byte chunk)
-        const int r = e >> 4, c16 = e & 15;
-        if ((keep >> r) & 1u) {                              // live slot: inside the cache resources
-          const int off = (i0 + rt * 32 + r) * (kD * 2) + c16 * 16;
-          *(u32x4*)(nk + (int64_t)(rt * 32 + r) * kD + c16 * 8) =
-              __builtin_amdgcn_raw_buffer_load_b128(cat_k.cache, off, 0, kDeviceScope);
-          *(u32x4*)(nv + (int64_t)(rt * 32 + r) * kD + c16 * 8) =
-              __builtin_amdgcn_raw_buffer_load_b128(cat_v.cache, off, 0, kDeviceScope);
-        }
-      }
-      if ((keep >> l31) & 1u) continue;
-    }
+    const int slot = rt * 32 + l31;
     const float inv = 1.0f / (NORM == 0 ? lsum[slot] : lsum[slot] + a.eps);
+    unsigned char* orow = Orows + ((w >> 1) * BM + slot) * G::XSTRIDE + (64 * (w & 1)) * 2;
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -645,8 +650,21 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         u32x2 pk;
         pk[0] = pack_bf16(oacc[ct][rt][g * 4 + 0] * inv, oacc[ct][rt][g * 4 + 1] * inv);
         pk[1] = pack_bf16(oacc[ct][rt][g * 4 + 2] * inv, oacc[ct][rt][g * 4 + 3] * inv);
-        *(u32x2*)(obase + (int64_t)slot * kD + ct * 32 + g * 8 + lh * 4) = pk;
+        *(u32x2*)(orow + (ct * 32 + g * 8 + lh * 4) * 2) = pk;
       }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 2 * BM * 16 / kThreads; ++it) {      // (K or V, slot, 16-byte chunk)
+    const int e = tid + it * kThreads;
+    const int kv = e / (BM * 16), r = (e >> 4) % BM, c16 = e & 15;
+    uint16_t* dst = (kv ? nv : nk) + (int64_t)r * kD + c16 * 8;
+    if (PROT && ((keep[r >> 5] >> (r & 31)) & 1u)) {         // live protected slot: inside the cache resources
+      const int off = (i0 + r) * (kD * 2) + c16 * 16;
+      *(u32x4*)dst = __builtin_amdgcn_raw_buffer_load_b128(kv ? cat_v.cache : cat_k.cache, off, 0, kDeviceScope);
+    } else {
+      *(u32x4*)dst = *(const u32x4*)(Orows + (kv * BM + r) * G::XSTRIDE + c16 * 16);
+    }
   }
 
   // ---- the next step reads what every slot tile of this chain has just written
