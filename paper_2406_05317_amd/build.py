@@ -33,7 +33,7 @@ EXTRA = {"compress_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form",
                                 # "#pragma unroll" is too small for the width-21 instantiation
                                 "-mllvm", "-pragma-unroll-threshold=200000"],
          # accumulators in ordinary registers: the softmax reads the scores where the MFMA left them
-         "attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+         "attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"]}
 
 
 def _compile(src: str) -> str:

@@ -1,21 +1,22 @@
 // Block-vs-(cache+block) causal attention for gfx950 (Alg. 2 step 3, Eq. 1):
-// bf16 MFMA, fp32 accumulation and softmax, K/V tiles staged through LDS,
-// online softmax.  One launch covers one block or, for a whole sequence whose
-// intermediate caches were kept, every block at once.
+// bf16 MFMA, fp32 accumulation and softmax, K/V tiles in LDS, online softmax.
+// One launch covers one block or, for a whole sequence whose intermediate
+// caches were kept, every block at once.
 //
 // Each workgroup takes 128 query rows of one (batch, query head, block); each
-// of its four waves owns 32 of them.  The kernel works on the TRANSPOSED
-// score tile S^T = K Q^T (keys are MFMA rows, queries are MFMA columns), so
-// that one lane holds scores of a single query: row maxima and sums need one
-// cross-lane exchange, the rescale factor is a per-lane scalar, and the
-// probabilities feed the second MFMA (O^T = V^T P^T) straight from registers.
-// The key order inside the second contraction is permuted the same way on
-// both operands so no shuffle is needed; the value operand is read with the
-// transposing LDS load straight from the row-major value tile.
+// of its four waves owns 32 of them; two workgroups share a compute unit.  The
+// kernel works on the TRANSPOSED score tile S^T = K Q^T (keys are MFMA rows,
+// queries are MFMA columns), so that one lane holds scores of a single query:
+// row maxima and sums need one cross-lane exchange, the rescale factor is a
+// per-lane scalar, and the probabilities feed the second MFMA (O^T = V^T P^T)
+// straight from registers.  The key order inside the second contraction is
+// permuted the same way on both operands so no shuffle is needed; the value
+// operand is read with the transposing LDS load straight from the row-major
+// value tile.
 //
 // Keys are indexed over [cache ; block]: all m cache slots are visible, block
-// key j' is visible to block query j iff j' <= j; key tiles past a wave's
-// diagonal are skipped.  Shapes taken: head_dim = 128, bf16.
+// key j' is visible to block query j iff j' <= j; a wave past its diagonal
+// only helps to bring tiles in.  Shapes taken: head_dim = 128, bf16.
 #include "lococo_internal.h"
 
 #include <type_traits>
@@ -34,11 +35,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 constexpr int kD = 128;
 constexpr int BK = 64;                        // keys per tile
-constexpr int KSTRIDE = kD * 2 + 16;          // bytes per key-tile row (conflict-free 16-byte reads)
-constexpr int VSTRIDE = kD * 2 + 64;          // bytes per value-tile row (conflict-free transposing reads)
-constexpr int KBYTES = BK * KSTRIDE;
-constexpr int VBYTES = BK * VSTRIDE;
-constexpr int LDS_BYTES = 2 * (KBYTES + VBYTES);
+constexpr int KSTRIDE = kD * 2 + 16;          // bytes per row of the padded output staging rows
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.0f;                 // the softmax reference lags the row maximum by at most this much
 
@@ -85,22 +82,39 @@ __device__ __forceinline__ void wait_loads() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-// QB = 32-query column blocks per wave, NW = waves per workgroup.  Launched with QB = 1, NW = 4:
-// 128 queries per workgroup, two workgroups per compute unit.  (QB = 2 halves the LDS reads per
-// flop but needs the whole register file for one wave per SIMD, which then has to issue every
-// vector, LDS and matrix instruction itself; NW = 8 halves the staging per query but loses the
-// second, independent workgroup.  Both measured slower on the 32 K-token workload.)
-template <int QB, int NW>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_mfma_k(AttnArgs a) {
-  constexpr int kThreads = 64 * NW;           // NW waves, 32 * QB query rows each
-  constexpr int BQ = 32 * QB * NW;            // query rows per workgroup
-  constexpr int PER = BK * 16 / kThreads;     // 16-byte chunks of a key (or value) tile per thread
-  constexpr int WQ = 32 * QB;                 // query rows per wave
-  extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* Ks0 = smem;
-  unsigned char* Vs0 = smem + 2 * KBYTES;
+// The parts of a tile are interleaved inside each wave by hand, and the tiles are brought in by
+// loads that write LDS directly:
+//   phase A of iteration t:  S(t+1) = K(t+1) Q^T on the matrix pipe  ||  exponentials of S(t) on the VALU
+//   phase B of iteration t:  O += V(t) P(t)     on the matrix pipe
+// so the matrix pipe has work from this wave while it does its softmax, whatever phase the other
+// wave of the SIMD is in.  The slices are pinned with sched_barrier.  Key tiles run one tile ahead
+// of value tiles.  K(t+2) and V(t+1) are requested at the top of iteration t into the buffers the
+// previous iteration has finished with, and must have landed at the barrier that ends it: a whole
+// iteration of cover, no staging registers, no LDS store instructions.
+//
+// Tiles are unpadded (256 bytes per row) and XOR-swizzled in units of 16 bytes so that both kinds
+// of operand read stay free of bank conflicts: chunk c of key row r sits in cell c ^ (r % 16), chunk
+// c of value row r in cell c ^ (4 * (r % 4)).  A load instruction fills 64 consecutive cells (four
+// rows); each lane fetches whatever chunk belongs in its cell.
+#define LOCOCO_SB() __builtin_amdgcn_sched_barrier(0)
+constexpr int TBYTES = BK * kD * 2;            // one unpadded tile
+constexpr int LDS_BYTES = 4 * TBYTES;           // K(2) + V(2)
 
-  // ---- work item: consecutive items share K/V; spread so that they land on one XCD
+// 64 lanes x 16 bytes from a buffer resource straight into the 1 KB of LDS at lds_addr (lane l
+// writes cell l).  Counted by vmcnt; the compiler does not know that LDS is written, so the wait
+// and the barrier that publish the tile are written by hand.
+__device__ __forceinline__ void load_to_lds(const u32x4& rsrc, uint32_t lds_addr, int voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+}
+
+__global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
+  constexpr int BQ = 128;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* Ks0 = smem;                   // key tiles t % 2
+  unsigned char* Vs0 = smem + 2 * TBYTES;      // value tiles t % 2
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)smem);
+
   int item = blockIdx.x;
   {
     const int total = gridDim.x, per = total / 8;
@@ -136,238 +150,253 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_mfma_k(AttnArgs a) {
   uint16_t* ob = (uint16_t*)a.o.p + b * a.o.sb + hq * a.o.sh + start * a.o.st;
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
-  const int wq0 = q0 + WQ * w;          // first query row of this wave
-  // this lane's queries (block-relative): wq0 + 32*qb + l31
+  const int wq0 = q0 + 32 * w;          // first query row of this wave
+  const int qrow = wq0 + l31;           // this lane's query (block-relative)
 
-  // ---- this lane's query rows as the B operand of S^T = K Q^T.  The rows are fetched whole
-  // (16 lanes x 16 bytes = one row per quarter wave, 1 KB contiguous per instruction), parked in a
-  // wave-private piece of the key-tile area and read back as operand fragments; rows past the
-  // block read as zero.
-  bf16x8 qreg[QB][8];
-  {
-    const Rows qr = make_rows(qb_ptr, Bn, a.q.st);
-    unsigned char* Qs = smem + w * (WQ * KSTRIDE);
-    u32x4 qrow_regs[WQ / 4];
+  f32x16 oacc[4];
 #pragma unroll
-    for (int i = 0; i < WQ / 4; ++i)
-      load16_async(qrow_regs[i], qr.rsrc, (wq0 + i * 4 + (l >> 4)) * qr.stride + (l & 15) * 16);
-    wait_loads<0>();
+  for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-    for (int i = 0; i < WQ / 4; ++i) asm volatile("" : "+v"(qrow_regs[i]));
-#pragma unroll
-    for (int i = 0; i < WQ / 4; ++i) *(u32x4*)(Qs + (i * 4 + (l >> 4)) * KSTRIDE + (l & 15) * 16) = qrow_regs[i];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        qreg[qb][ks] = *(const bf16x8*)(Qs + (32 * qb + l31) * KSTRIDE + ks * 32 + lh * 16);
-  }
-
-  f32x16 oacc[QB][4];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[qb][ct][i] = 0.f;
-  // running softmax reference (in raw score units) and row sum; exp(x * scale) = exp2(x * c)
+    for (int i = 0; i < 16; ++i) oacc[ct][i] = 0.f;
   const float c = a.scale * kLog2e;
   const float lazy_raw = kLazy / a.scale;
-  float m_run[QB], l_run[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+  float m_run = -INFINITY, l_run = 0.f;
 
-  // tiles: NTc over the cache, then over the block up to this workgroup's last query row
   const int NTc = (m + BK - 1) / BK;
   const int NT = NTc + (min(Bn, q0 + BQ) + BK - 1) / BK;
 
-  // Two sets of staging registers: the loads of tile t + 2 are issued at the top of iteration t
-  // and land in LDS at the end of iteration t + 1, so a load has two iterations to arrive (the
-  // loaded latency of this access pattern is about one iteration).  Every call issues exactly
-  // 2 * PER loads per lane, also past the last tile (offsets out of range: zeros, no traffic), so
-  // that "at most 2 * PER pending" always means "the older set has arrived".
-  u32x4 kreg0[PER], vreg0[PER], kreg1[PER], vreg1[PER];
-  auto stage_load = [&](int t, u32x4* kreg, u32x4* vreg) {
+  // ---- tile requests.  Instruction `it` of wave w fills the cells of tile rows 16w + 4it .. + 3;
+  // lane l: row 16w + 4it + l/16, cell l%16.  Past the last tile the offset is out of range: zeros.
+  const int w_uniform = __builtin_amdgcn_readfirstlane(w);     // the wave index as a scalar: M0 takes no vector register
+  auto request_one = [&](int t, int it, const Rows& fc, const Rows& fb, uint32_t lds_tile, bool keys) {
     const bool blk = t >= NTc;
     const int row0 = (blk ? t - NTc : t) * BK;
-    const u32x4 rk = blk ? bk.rsrc : ck.rsrc, rv = blk ? bv.rsrc : cv.rsrc;
-    const int sk = blk ? bk.stride : ck.stride, sv = blk ? bv.stride : cv.stride;
+    u32x4 r = blk ? fb.rsrc : fc.rsrc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_readfirstlane(r[i]);   // the instruction takes scalars only
+    const int st = blk ? fb.stride : fc.stride;
     const int beyond = t >= NT ? 0x7fff0000 : 0;
-#pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int idx = tid + it * kThreads;
-      const int j = row0 + (idx >> 4), chunk = idx & 15;
-      load16_async(kreg[it], rk, (j * sk + chunk * 16) | beyond);
-      load16_async(vreg[it], rv, (j * sv + chunk * 16) | beyond);
-    }
+    const int row = 16 * w + 4 * it + (l >> 4), cell = l & 15;
+    const int chunk = keys ? cell ^ (row & 15) : cell ^ ((row & 3) << 2);
+    load_to_lds(r, lds_tile + (uint32_t)((16 * w_uniform + 4 * it) * (kD * 2)), ((row0 + row) * st + chunk * 16) | beyond);
   };
-  // `pending`: loads issued after the set being stored (0 or 2 * PER)
-  auto stage_store = [&](int buf, u32x4* kreg, u32x4* vreg, auto pending) {
-    unsigned char* Ks = Ks0 + buf * KBYTES;
-    unsigned char* Vs = Vs0 + buf * VBYTES;
-    wait_loads<decltype(pending)::value>();
+  auto request = [&](int t, const Rows& fc, const Rows& fb, uint32_t lds_tile, bool keys) {
 #pragma unroll
-    for (int it = 0; it < PER; ++it) asm volatile("" : "+v"(kreg[it]), "+v"(vreg[it]));
-#pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int idx = tid + it * kThreads;
-      *(u32x4*)(Ks + (idx >> 4) * KSTRIDE + (idx & 15) * 16) = kreg[it];
-      *(u32x4*)(Vs + (idx >> 4) * VSTRIDE + (idx & 15) * 16) = vreg[it];
-    }
+    for (int it = 0; it < 4; ++it) request_one(t, it, fc, fb, lds_tile, keys);
   };
-
-  stage_load(0, kreg0, vreg0);
-  __syncthreads();                     // every wave has its query fragments: the area is free for tile 0
-  stage_store(0, kreg0, vreg0, std::integral_constant<int, 0>());
-  stage_load(1, kreg1, vreg1);
-  __syncthreads();
-
-  // value fragments: lane (head-dim column ct*32 + l31) x 8 keys.  The key order inside a
-  // contraction step follows the layout the probabilities already have in the score accumulator:
-  // slot j of step u is key u*16 + (j/4)*8 + lh*4 + j%4 (see below), so nothing is shuffled.
-  const int s16 = l & 15, g2 = (l >> 4) & 1;
-  const int v_lane_off = (lh * 4 + (s16 >> 2)) * VSTRIDE + (16 * g2 + 4 * (s16 & 3)) * 2;
-
-  auto iteration = [&](int t, u32x4* kld, u32x4* vld, u32x4* kst, u32x4* vst) {
-    const int buf = t & 1;
-    const bool blk = t >= NTc;
-    const int row0 = (blk ? t - NTc : t) * BK;     // first key of the tile, within its array
-    const unsigned char* Ks = Ks0 + buf * KBYTES;
-    const unsigned char* Vs = Vs0 + buf * VBYTES;
-    stage_load(t + 2, kld, vld);
-
-    if (!blk || row0 < wq0 + WQ) {       // some key of the tile is visible to some query of this wave
-      // ---- S^T tile: keys x queries
-      f32x16 sacc[QB][BK / 32];
-#pragma unroll
-      for (int kt = 0; kt < BK / 32; ++kt) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 kv = *(const bf16x8*)(Ks + (kt * 32 + l31) * KSTRIDE + (ks * 16 + lh * 8) * 2);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            sacc[qb][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[qb][ks], ks == 0 ? zero : sacc[qb][kt], 0, 0, 0);
-        }
-      }
-      // ---- mask: cache rows at and beyond m; block keys after the query
-      if (blk ? row0 + BK - 1 > wq0 : row0 + BK > m) {
-        const int lim0 = blk ? wq0 + l31 : m - 1;    // last visible row for qb = 0 (block: the query itself)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          const int lim = blk ? lim0 + 32 * qb : lim0;
-#pragma unroll
-          for (int kt = 0; kt < BK / 32; ++kt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int key = row0 + kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-              if (key > lim) sacc[qb][kt][i] = -INFINITY;
-            }
-        }
-      }
-      // ---- online softmax with a lazy reference (everything of one query sits in one lane pair)
-      float psum[QB];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float mx = sacc[qb][0][0];
-#pragma unroll
-        for (int kt = 0; kt < BK / 32; ++kt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[qb][kt][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // The reference only moves when the row maximum outgrows it by kLazy (in exponent units),
-        // so exp(..) stays below e^kLazy and the accumulator is rescaled rarely.
-        const bool bump = mx > m_run[qb] + lazy_raw;
-        const float m_new = bump ? mx : m_run[qb];
-        if (__any(bump)) {
-          const float alpha = bump ? __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c) : 1.0f;
-          l_run[qb] *= alpha;
-#pragma unroll
-          for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[qb][ct][i] *= alpha;
-        }
-        m_run[qb] = m_new;
-        const float mc = m_new * c;
-#pragma unroll
-        for (int kt = 0; kt < BK / 32; ++kt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[qb][kt][i] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kt][i], c, -mc));
-        psum[qb] = 0.f;
-      }
-      // ---- O^T += V^T P^T; contraction slot j of step u holds key (u*16 + (j/4)*8 + lh*4 + j%4)
-#pragma unroll
-      for (int kt = 0; kt < BK / 32; ++kt)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          bf16x8 pv[QB];
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) {
-            u32x4 pp;
-#pragma unroll
-            for (int j2 = 0; j2 < 4; ++j2) {
-              pp[j2] = pack_bf16(sacc[qb][kt][u * 8 + 2 * j2], sacc[qb][kt][u * 8 + 2 * j2 + 1]);
-              psum[qb] += sacc[qb][kt][u * 8 + 2 * j2] + sacc[qb][kt][u * 8 + 2 * j2 + 1];
-            }
-            pv[qb] = __builtin_bit_cast(bf16x8, pp);
-          }
-#pragma unroll
-          for (int ct = 0; ct < 4; ++ct) {
-            const unsigned char* vp = Vs + (kt * 32 + u * 16) * VSTRIDE + (ct * 32) * 2 + v_lane_off;
-            const s16x4 y0 = lds_read_tr(vp);
-            const s16x4 y1 = lds_read_tr(vp + 8 * VSTRIDE);
-            const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-              oacc[qb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, yy), pv[qb],
-                                                                     oacc[qb][ct], 0, 0, 0);
-          }
-        }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb] + __shfl_xor(psum[qb], 32, 64);
-    }
-    stage_store(buf ^ 1, kst, vst, std::integral_constant<int, 2 * PER>());
+  auto tiles_landed = [&]() {            // this wave's requests are in LDS; then everybody's
+    wait_loads<0>();
     __syncthreads();
   };
+
+  // ---- operand addresses inside a swizzled tile
+  // keys: lane (row l31 of a 32-row half, chunks 2 ks + lh): cell (2 ks + lh) ^ (l31 % 16)
+  int kaddr[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = l31 * (kD * 2) + (((2 * ks + lh) ^ (l31 & 15)) << 4);
+  // values (transposing read): lane s16 of a 16-lane group covers row (lh*4 + s16/4) of an 8-row
+  // group and 8 bytes at column 32 ct + 16 g2 + 4 (s16 % 4): chunk 4 ct + 2 g2 + (s16 % 4) / 2
+  const int s16 = l & 15, g2 = (l >> 4) & 1;
+  int vaddr[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) {
+    const int vrow = lh * 4 + (s16 >> 2), chunk = 4 * ct + 2 * g2 + ((s16 & 3) >> 1);
+    vaddr[ct] = vrow * (kD * 2) + ((chunk ^ ((vrow & 3) << 2)) << 4) + (s16 & 1) * 8;
+  }
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // ---- prologue.  K(0) and V(0) are requested first; the query rows come in behind them as whole
+  // rows, are parked (swizzled like a key tile) in the two tile buffers nothing has been requested
+  // into yet -- waves 0, 1 in key buffer 1, waves 2, 3 in value buffer 1 -- and read back as
+  // operand fragments; then K(1) is requested and S(0) computed while it is on its way.
+  request(0, ck, bk, lds0, true);
+  request(0, cv, bv, lds0 + 2 * TBYTES, false);
+  bf16x8 qreg[8];
+  {
+    const Rows qr = make_rows(qb_ptr, Bn, a.q.st);
+    unsigned char* Qs = smem + (w < 2 ? TBYTES : 3 * TBYTES) + (w & 1) * (32 * kD * 2);
+    u32x4 qrow_regs[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      load16_async(qrow_regs[i], qr.rsrc, (wq0 + i * 4 + (l >> 4)) * qr.stride + (l & 15) * 16);
+    wait_loads<0>();                   // loads complete in order: K(0) and V(0) of this wave are in LDS too
+#pragma unroll
+    for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(qrow_regs[i]));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = i * 4 + (l >> 4);
+      *(u32x4*)(Qs + row * (kD * 2) + (((l & 15) ^ (row & 15)) << 4)) = qrow_regs[i];
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *(const bf16x8*)(Qs + kaddr[ks]);
+  }
+  __syncthreads();                     // every wave has its query fragments, and K(0), V(0) are complete
+  request(1, ck, bk, lds0 + TBYTES, true);
+  f32x16 s_a[2], s_b[2];
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 kv = *(const bf16x8*)(Ks0 + kt * 32 * (kD * 2) + kaddr[ks]);
+      s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[ks], ks == 0 ? zero : s_a[kt], 0, 0, 0);
+    }
+  // Mask a score tile (cache rows at and beyond m; block keys after the query) and take this
+  // lane pair's maximum.  Done for tile t + 1 under the P V MFMAs of iteration t.
+  auto mask_tile = [&](int t, f32x16* sx) {
+    const bool blk = t >= NTc;
+    const int row0 = (blk ? t - NTc : t) * BK;
+    if (blk ? row0 + BK - 1 > wq0 : row0 + BK > m) {
+      const int lim = blk ? qrow : m - 1;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = row0 + kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+          if (key > lim) sx[kt][i] = -INFINITY;
+        }
+    }
+  };
+  float mx_tile;                         // row maximum of the tile the next iteration consumes
+  {
+    mask_tile(0, s_a);
+    float mx = s_a[0][0];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_a[kt][i]);
+    mx_tile = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  }
+  tiles_landed();                      // K(1) is in; key buffer 0 is refilled in the first iteration
+
+  // sc: scores of tile t (input), sn: scores of tile t + 1 (output); PAR = t % 2
+  auto iteration = [&](int t, auto par, f32x16* sc, f32x16* sn) {
+    constexpr int PAR = decltype(par)::value;
+    const bool blk = t >= NTc;
+    const int row0 = (blk ? t - NTc : t) * BK;
+    const unsigned char* Kn = Ks0 + (PAR ^ 1) * TBYTES;     // K(t+1)
+    const unsigned char* Vs = Vs0 + PAR * TBYTES;           // V(t)
+    const uint32_t k_dst = lds0 + PAR * TBYTES;                       // K(t+2) goes where K(t) was
+    const uint32_t v_dst = lds0 + 2 * TBYTES + (PAR ^ 1) * TBYTES;    // V(t+1) goes where V(t-1) was
+
+    if (!blk || row0 < wq0 + 32) {       // some key of the tile is visible to some query of this wave
+      // ---- the lazy reference (the tile was masked and its maximum taken an iteration ago)
+      const float mx = mx_tile;
+      const bool bump = mx > m_run + lazy_raw;
+      const float m_new = bump ? mx : m_run;
+      if (__any(bump)) {
+        const float alpha = bump ? __builtin_amdgcn_exp2f((m_run - m_new) * c) : 1.0f;
+        l_run *= alpha;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
+      }
+      m_run = m_new;
+      const float mc = m_new * c;
+
+      // ---- phase A: 16 MFMAs of S(t+1), two exponentials of S(t) behind each
+      LOCOCO_SB();
+      bf16x8 kf[4];
+#pragma unroll
+      for (int pf = 0; pf < 3; ++pf) kf[pf] = *(const bf16x8*)(Kn + (pf >> 3) * 32 * (kD * 2) + kaddr[pf & 7]);
+      float psum = 0.f;
+#pragma unroll
+      for (int sl = 0; sl < 16; ++sl) {
+        const int kt = sl >> 3, ks = sl & 7;
+        if (sl + 3 < 16)
+          kf[(sl + 3) & 3] = *(const bf16x8*)(Kn + ((sl + 3) >> 3) * 32 * (kD * 2) + kaddr[(sl + 3) & 7]);
+        sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sl & 3], qreg[ks], ks == 0 ? zero : sn[kt], 0, 0, 0);
+        if (sl < 4) request_one(t + 2, sl, ck, bk, k_dst, true);          // the tile requests ride in the first slices
+        else if (sl < 8) request_one(t + 1, sl - 4, cv, bv, v_dst, false);
+#pragma unroll
+        for (int e = sl * 2; e < sl * 2 + 2; ++e) {
+          float pval = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][e & 15], c, -mc));
+          asm volatile("" : "+v"(pval));   // a use here: otherwise the exponentials sink to where P is consumed
+          sc[e >> 4][e & 15] = pval;
+          psum += pval;
+        }
+        LOCOCO_SB();
+      }
+
+      // ---- phase B: 16 MFMAs of O^T += V(t)^T P^T; tile t + 1 is masked and its maximum taken behind them
+      mask_tile(t + 1, sn);
+      float mxn = sn[0][0];
+      s16x4 vf[4][2];
+#pragma unroll
+      for (int pf = 0; pf < 3; ++pf) {
+        const unsigned char* vp = Vs + ((pf >> 2) * 16) * (kD * 2) + vaddr[pf & 3];
+        vf[pf][0] = lds_read_tr(vp);
+        vf[pf][1] = lds_read_tr(vp + 8 * (kD * 2));
+      }
+      bf16x8 pv;
+#pragma unroll
+      for (int g = 0; g < 16; ++g) {
+        const int ku = g >> 2, ct = g & 3;      // ku = kt*2 + u: 16 keys per contraction step
+        if (g + 3 < 16) {
+          const unsigned char* vp = Vs + (((g + 3) >> 2) * 16) * (kD * 2) + vaddr[(g + 3) & 3];
+          vf[(g + 3) & 3][0] = lds_read_tr(vp);
+          vf[(g + 3) & 3][1] = lds_read_tr(vp + 8 * (kD * 2));
+        }
+        if (ct == 0) {
+          const int kt = ku >> 1, u = ku & 1;
+          u32x4 pp;
+#pragma unroll
+          for (int j2 = 0; j2 < 4; ++j2) pp[j2] = pack_bf16(sc[kt][u * 8 + 2 * j2], sc[kt][u * 8 + 2 * j2 + 1]);
+          pv = __builtin_bit_cast(bf16x8, pp);
+        }
+        const s16x4 y0 = vf[g & 3][0], y1 = vf[g & 3][1];
+        const s16x8 yy = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, yy), pv, oacc[ct], 0, 0, 0);
+        if (g >= 4 && g < 12) {
+#pragma unroll
+          for (int e = (g - 4) * 4; e < (g - 4) * 4 + 4; ++e) mxn = fmaxf(mxn, sn[e >> 4][e & 15]);
+        }
+        if (g == 13) mx_tile = fmaxf(mxn, __shfl_xor(mxn, 32, 64));
+        LOCOCO_SB();
+      }
+      l_run += psum + __shfl_xor(psum, 32, 64);
+    } else {
+      request(t + 2, ck, bk, k_dst, true);
+      request(t + 1, cv, bv, v_dst, false);
+    }
+    tiles_landed();
+  };
   for (int t = 0; t < NT; t += 2) {
-    iteration(t, kreg0, vreg0, kreg1, vreg1);
-    if (t + 1 < NT) iteration(t + 1, kreg1, vreg1, kreg0, vreg0);
+    iteration(t, std::integral_constant<int, 0>(), s_a, s_b);
+    if (t + 1 < NT) iteration(t + 1, std::integral_constant<int, 1>(), s_b, s_a);
   }
 
-  // ---- O = O^T / l: lane holds its queries, head-dim columns ct*32 + (i/4)*8 + lh*4 + i%4.
-  // The rows are put together in a wave-private piece of LDS (the loop's last barrier has been
-  // passed, nobody reads tiles any more) and leave as whole rows, 1 KB contiguous per instruction.
-  unsigned char* Os = smem + w * (WQ * KSTRIDE);
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float inv = 1.0f / l_run[qb];
+  // ---- O = O^T / l: lane holds its query, head-dim columns ct*32 + (i/4)*8 + lh*4 + i%4.  The rows
+  // are put together in a wave-private piece of LDS (the loop's last barrier has been passed, every
+  // request has landed) and leave as whole rows, 1 KB contiguous per wave instruction.
+  static_assert(4 * 32 * KSTRIDE <= LDS_BYTES, "the output staging rows fit the tile area");
+  unsigned char* Os = smem + w * (32 * KSTRIDE);
+  {
+    const float inv = 1.0f / l_run;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x2 pk;
-        pk[0] = pack_bf16(oacc[qb][ct][g * 4 + 0] * inv, oacc[qb][ct][g * 4 + 1] * inv);
-        pk[1] = pack_bf16(oacc[qb][ct][g * 4 + 2] * inv, oacc[qb][ct][g * 4 + 3] * inv);
-        *(u32x2*)(Os + (32 * qb + l31) * KSTRIDE + (ct * 32 + g * 8 + lh * 4) * 2) = pk;
+        pk[0] = pack_bf16(oacc[ct][g * 4 + 0] * inv, oacc[ct][g * 4 + 1] * inv);
+        pk[1] = pack_bf16(oacc[ct][g * 4 + 2] * inv, oacc[ct][g * 4 + 3] * inv);
+        *(u32x2*)(Os + l31 * KSTRIDE + (ct * 32 + g * 8 + lh * 4) * 2) = pk;
       }
   }
 #pragma unroll
-  for (int i = 0; i < WQ / 4; ++i) {
+  for (int i = 0; i < 8; ++i) {
     const int row = i * 4 + (l >> 4);
     const u32x4 v = *(const u32x4*)(Os + row * KSTRIDE + (l & 15) * 16);
     if (wq0 + row < Bn) *(u32x4*)(ob + (int64_t)(wq0 + row) * a.o.st + (l & 15) * 8) = v;
   }
 }
 
-template <int QB, int NW>
-hipError_t launch_qb(const AttnArgs& a_in, hipStream_t s) {
-  constexpr int kThreads = 64 * NW;
+hipError_t launch_tiles(const AttnArgs& a_in, hipStream_t s) {
   AttnArgs a = a_in;
-  constexpr int BQ = 32 * QB * NW;
-  a.qtiles = (a.B + BQ - 1) / BQ;
+  a.qtiles = (a.B + 127) / 128;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_k<QB, NW>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_k,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -375,7 +404,7 @@ hipError_t launch_qb(const AttnArgs& a_in, hipStream_t s) {
   const int64_t total = (int64_t)a.qtiles * a.Hq * a.batch * a.n_seg;
   if (total <= 0) return hipSuccess;
   if (total > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((attn_mfma_k<QB, NW>), dim3((unsigned)total), dim3(kThreads), LDS_BYTES, s, a);
+  hipLaunchKernelGGL(attn_mfma_k, dim3((unsigned)total), dim3(256), LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
@@ -393,7 +422,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
   for (const View* v : {&a.q, &a.k, &a.v})
     if (((int64_t)a.B * v->st + kD) * 2 >= lim) return hipErrorInvalidValue;
   if ((int64_t)a.M * kD * 2 >= lim) return hipErrorInvalidValue;
-  return launch_qb<1, 4>(a, s);
+  return launch_tiles(a, s);
 }
 
 }  // namespace lococo
