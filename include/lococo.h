@@ -199,7 +199,15 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
  * gave up.  `workspace` is the one passed to lococo_sequence_forward (at least
  * lococo_workspace_bytes(history = 0) bytes); the word is cleared at the start of every such call
  * and means nothing before the first one.  Configurations the MFMA kernels do not serve never
- * wait: *out is 0. */
+ * wait: *out is 0.
+ *
+ * Environment variables read by lococo_sequence_forward (for tests and measurements; results are
+ * the same bit for bit whatever they say):
+ *   LOCOCO_SPIN_LIMIT=n          polls a waiting workgroup makes before it gives up (default 2^24)
+ *   LOCOCO_SCAN_LAUNCHES=steps   one launch per compression step instead of one per scan
+ *   LOCOCO_CHAIN_SYNC=device     workgroups of a chain always meet with device-scope release and
+ *                                acquire (default: without the L2 write-back when they find themselves
+ *                                on one XCD) */
 lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out);
 
 /* Steps 4-5 with Eq. 5's output supplied by the caller: the cache becomes
