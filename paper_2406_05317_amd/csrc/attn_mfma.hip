@@ -168,6 +168,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
   // ---- tile requests.  Instruction `it` of wave w fills the cells of tile rows 16w + 4it .. + 3;
   // lane l: row 16w + 4it + l/16, cell l%16.  Past the last tile the offset is out of range: zeros.
   const int w_uniform = __builtin_amdgcn_readfirstlane(w);     // the wave index as a scalar: M0 takes no vector register
+  const uint32_t req_row = (uint32_t)(16 * w + (l >> 4));
+  const uint32_t req_cell_k = (uint32_t)(((l & 15) ^ (l >> 4)) << 4);          // it = 0; instruction it flips bits 6, 7
+  const uint32_t req_cell_v = (uint32_t)(((l & 15) ^ (((l >> 4) & 3) << 2)) << 4);
   auto request_one = [&](int t, int it, const Rows& fc, const Rows& fb, uint32_t lds_tile, bool keys) {
     const bool blk = t >= NTc;
     const int row0 = (blk ? t - NTc : t) * BK;
@@ -175,10 +178,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_readfirstlane(r[i]);   // the instruction takes scalars only
     const int st = blk ? fb.stride : fc.stride;
-    const int beyond = t >= NT ? 0x7fff0000 : 0;
-    const int row = 16 * w + 4 * it + (l >> 4), cell = l & 15;
-    const int chunk = keys ? cell ^ (row & 15) : cell ^ ((row & 3) << 2);
-    load_to_lds(r, lds_tile + (uint32_t)((16 * w_uniform + 4 * it) * (kD * 2)), ((row0 + row) * st + chunk * 16) | beyond);
+    // byte offset = (row0 + 16 w + 4 it + l/16) * st + 16 * chunk, split into a part per lane (a 24-bit
+    // multiply-add on two values computed once) and a scalar part; rows of the tile: 16 w + 4 it + l/16
+    const uint32_t chunk16 = keys ? req_cell_k ^ (uint32_t)(it << 6) : req_cell_v;   // cell ^ (row % 16), cell ^ 4 (row % 4)
+    const uint32_t lane_part = __umul24(req_row, (uint32_t)st) + chunk16;
+    const uint32_t tile_part = t >= NT ? 0x7fff0000u : (uint32_t)((row0 + 4 * it) * st);
+    load_to_lds(r, lds_tile + (uint32_t)((16 * w_uniform + 4 * it) * (kD * 2)), (int)(lane_part + tile_part));
   };
   auto request = [&](int t, const Rows& fc, const Rows& fb, uint32_t lds_tile, bool keys) {
 #pragma unroll
