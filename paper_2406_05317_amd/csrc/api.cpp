@@ -671,7 +671,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
 }
 
 namespace {
-struct BwdLayout { size_t p, ds, w, n, total; };
+struct BwdLayout { size_t p, ds, w, n, dw, total; };
 BwdLayout bwd_layout(const lococo_config* c, int32_t B, int32_t len) {
   const size_t T = (size_t)len + B;
   const size_t rows = (size_t)c->batch * c->n_q_heads * B * T * sizeof(float);
@@ -682,7 +682,8 @@ BwdLayout bwd_layout(const lococo_config* c, int32_t B, int32_t len) {
   l.ds = align_up(rows, 256);
   l.w = l.ds + align_up(rows, 256);
   l.n = l.w + align_up(mat, 256);
-  l.total = l.n + align_up(mat, 256);
+  l.dw = l.n + align_up(mat, 256);
+  l.total = l.dw + align_up(mat, 256);
   return l;
 }
 }  // namespace
@@ -743,6 +744,7 @@ lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococ
   g.ws_ds = (float*)(ws + l.ds);
   g.ws_w = (float*)(ws + l.w);
   g.ws_n = (float*)(ws + l.n);
+  g.ws_dw = (float*)(ws + l.dw);
   if (compress) {
     // recompute Eq. 5 and Eq. 6 of the forward step: raw logits and normalised rows
     HIP_TRY(launch_conv_logits_generic(cfg->dtype, g.st, g.ws_w, s), "conv launch");

@@ -192,20 +192,78 @@ __global__ __launch_bounds__(kThreads) void bwd_fill_k(BwdArgs g) {
   }
 }
 
-// ---- Eq. 4a/4b + Eq. 6, one workgroup per (slot i, chain): dW row into ws_w (over the raw logits),
-// bias gradient; a protected slot passes its gradient to the old row instead
+// ---- Eq. 4a/4b and Eq. 6.  The two contractions of the fusion are plain GEMMs and are tiled like
+// the Eq. 5 ones below (64 x 64 outputs per workgroup, 4 x 4 per thread, operands through LDS in
+// chunks of 16 along the contraction); the row reductions of Eq. 6 stay one workgroup per slot.
+constexpr int kMT = 64, kMK = 16;
+
+// dw[i, j] = g_k[i] . Yk[j] + g_v[i] . Yv[j]   (slots x positions, contraction over the 2 d columns)
 template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_mix_dw_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  __shared__ float Gs[kMK][kMT + 4];               // [column][slot]
+  __shared__ float Ys[kMK][kMT + 4];               // [column][position]
+  const int Tn = a.m + a.Bn, d = a.d;
+  const int j0 = blockIdx.x * kMT, i0 = blockIdx.y * kMT, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
+  float acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.f;
+  for (int c0 = 0; c0 < 2 * d; c0 += kMK) {        // columns of [K | V]; d is a multiple of 16 or the tail is zero-filled
+    __syncthreads();
+    for (int e = threadIdx.x; e < kMK * kMT; e += kThreads) {
+      const int c = e % kMK, r = e / kMK, cc = c0 + c;
+      float gv = 0.f, yv = 0.f;
+      if (cc < 2 * d) {
+        const bool val = cc >= d;
+        const int col = val ? cc - d : cc;
+        if (i0 + r < a.M) gv = (val ? g.d_new_v : g.d_new_k)[((int64_t)ch * a.M + i0 + r) * d + col];
+        if (j0 + r < Tn)
+          yv = val ? to_f(cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j0 + r)[col])
+                   : to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j0 + r)[col]);
+      }
+      Gs[c][r] = gv;
+      Ys[c][r] = yv;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kMK; ++c) {
+      const float4 gq = *(const float4*)&Gs[c][ti * 4];
+      const float4 yq = *(const float4*)&Ys[c][tj * 4];
+      const float gr[4] = {gq.x, gq.y, gq.z, gq.w}, yr[4] = {yq.x, yq.y, yq.z, yq.w};
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = fmaf(gr[ii], yr[jj], acc[ii][jj]);
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) {
+    const int i = i0 + ti * 4 + ii;
+    if (i >= a.M) continue;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + tj * 4 + jj;
+      if (j < Tn) g.ws_dw[((int64_t)ch * a.M + i) * Tn + j] = acc[ii][jj];
+    }
+  }
+}
+
+// Eq. 6 w.r.t. the logits, one workgroup per (slot i, chain): dW[i,:] from dw[i,:] and the
+// normalised row, and the bias gradient; a protected slot passes its gradient to the old row instead
 __global__ __launch_bounds__(kThreads) void bwd_mix_rows_k(BwdArgs g) {
   const StepArgs& a = g.st;
-  extern __shared__ float lds[];                 // g_k[i], g_v[i]
   __shared__ float red[kWaves];
-  const int i = blockIdx.x, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int i = blockIdx.x, ch = blockIdx.y, hkv = ch % a.Hkv;
   const int Tn = a.m + a.Bn, d = a.d;
   float* Wraw = g.ws_w + ((int64_t)ch * a.M + i) * Tn;       // raw logits in, dW out
   const float* w = g.ws_n + ((int64_t)ch * a.M + i) * Tn;    // normalised rows
-  const float* gk = g.d_new_k + ((int64_t)ch * a.M + i) * d;
-  const float* gv = g.d_new_v + ((int64_t)ch * a.M + i) * d;
+  const float* dw = g.ws_dw + ((int64_t)ch * a.M + i) * Tn;
   if (slot_protected(a, ch, i)) {
+    const float* gk = g.d_new_k + ((int64_t)ch * a.M + i) * d;
+    const float* gv = g.d_new_v + ((int64_t)ch * a.M + i) * d;
     float* dk = g.d_cache_k + ((int64_t)ch * a.M + i) * d;
     float* dv = g.d_cache_v + ((int64_t)ch * a.M + i) * d;
     for (int c = threadIdx.x; c < d; c += kThreads) {
@@ -215,32 +273,16 @@ __global__ __launch_bounds__(kThreads) void bwd_mix_rows_k(BwdArgs g) {
     for (int j = threadIdx.x; j < Tn; j += kThreads) Wraw[j] = 0.f;
     return;
   }
-  float* gks = lds;
-  float* gvs = lds + d;
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    gks[c] = gk[c];
-    gvs[c] = gv[c];
-  }
-  __syncthreads();
-  // first pass: dw[j] kept in registers is not possible for any Tn, so it is recomputed in the second
   float dot = 0.f, z = 0.f;
   for (int j = threadIdx.x; j < Tn; j += kThreads) {
-    const T* yk = cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j);
-    const T* yv = cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j);
-    float acc = 0.f;
-    for (int c = 0; c < d; ++c) acc += gks[c] * to_f(yk[c]) + gvs[c] * to_f(yv[c]);
-    dot += w[j] * acc;
+    dot += w[j] * dw[j];
     z += fmaxf(Wraw[j], 0.f);
   }
   dot = block_sum(dot, red);
   z = block_sum(z, red) + a.eps;
   float bsum = 0.f;
   for (int j = threadIdx.x; j < Tn; j += kThreads) {
-    const T* yk = cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j);
-    const T* yv = cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j);
-    float acc = 0.f;
-    for (int c = 0; c < d; ++c) acc += gks[c] * to_f(yk[c]) + gvs[c] * to_f(yv[c]);
-    const float dW = a.norm == 0 ? w[j] * (acc - dot) : (Wraw[j] > 0.f ? (acc - dot) / z : 0.f);
+    const float dW = a.norm == 0 ? w[j] * (dw[j] - dot) : (Wraw[j] > 0.f ? (dw[j] - dot) / z : 0.f);
     Wraw[j] = dW;
     bsum += dW;
   }
@@ -248,24 +290,56 @@ __global__ __launch_bounds__(kThreads) void bwd_mix_rows_k(BwdArgs g) {
   if (threadIdx.x == 0 && g.d_conv_b) atomicAdd(g.d_conv_b + hkv * a.b_head_stride + i, bsum);
 }
 
-// ---- Eq. 4a/4b w.r.t. the inputs, one workgroup per (position j, chain):
-// dYk[j] += sum_i w[i,j] g_k[i], same for V
+// ---- Eq. 4a/4b w.r.t. the inputs: dYk[j] += sum_i w[i,j] g_k[i], same for V
+// (positions x columns of [K | V], contraction over the unprotected slots)
 __global__ __launch_bounds__(kThreads) void bwd_mix_cols_k(BwdArgs g) {
   const StepArgs& a = g.st;
-  const int j = blockIdx.x, ch = blockIdx.y;
+  __shared__ float Ws[kMK][kMT + 4];               // [slot][position]
+  __shared__ float Gs[kMK][kMT + 4];               // [slot][column]
   const int Tn = a.m + a.Bn, d = a.d;
-  float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
-  float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    float ak = 0.f, av = 0.f;
-    for (int i = 0; i < a.M; ++i) {
-      if (slot_protected(a, ch, i)) continue;
-      const float wij = g.ws_n[((int64_t)ch * a.M + i) * Tn + j];
-      ak += wij * g.d_new_k[((int64_t)ch * a.M + i) * d + c];
-      av += wij * g.d_new_v[((int64_t)ch * a.M + i) * d + c];
+  const int c0 = blockIdx.x * kMT, j0 = blockIdx.y * kMT, ch = blockIdx.z;
+  const int tj = threadIdx.x / 16, tc = threadIdx.x % 16;
+  float acc[4][4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[jj][q] = 0.f;
+  for (int s0 = 0; s0 < a.M; s0 += kMK) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < kMK * kMT; e += kThreads) {
+      const int x = e % kMT, r = e / kMT, i = s0 + r;
+      const bool live = i < a.M && !slot_protected(a, ch, i);
+      Ws[r][x] = live && j0 + x < Tn ? g.ws_n[((int64_t)ch * a.M + i) * Tn + j0 + x] : 0.f;
+      const int cc = c0 + x;
+      float gv = 0.f;
+      if (live && cc < 2 * d)
+        gv = cc < d ? g.d_new_k[((int64_t)ch * a.M + i) * d + cc] : g.d_new_v[((int64_t)ch * a.M + i) * d + cc - d];
+      Gs[r][x] = gv;
     }
-    dk[c] += ak;
-    dv[c] += av;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kMK; ++r) {
+      const float4 wq = *(const float4*)&Ws[r][tj * 4];
+      const float4 gq = *(const float4*)&Gs[r][tc * 4];
+      const float wr[4] = {wq.x, wq.y, wq.z, wq.w}, gr[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[jj][q] = fmaf(wr[jj], gr[q], acc[jj][q]);
+    }
+  }
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int j = j0 + tj * 4 + jj;
+    if (j >= Tn) continue;
+    float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
+    float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = c0 + tc * 4 + q;
+      if (c < d) dk[c] += acc[jj][q];
+      else if (c < 2 * d) dv[c - d] += acc[jj][q];
+    }
   }
 }
 
@@ -421,8 +495,9 @@ hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
     hipLaunchKernelGGL(bwd_fill_k, dim3(64, chains), dim3(kThreads), 0, s, g);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(bwd_mix_rows_k<T>, dim3(a.M, chains), dim3(kThreads), (size_t)2 * a.d * sizeof(float), s, g);
-  hipLaunchKernelGGL(bwd_mix_cols_k, dim3(Tn, chains), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_mix_dw_k<T>, dim3((Tn + kMT - 1) / kMT, (a.M + kMT - 1) / kMT, chains), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_mix_rows_k, dim3(a.M, chains), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_mix_cols_k, dim3((2 * a.d + kMT - 1) / kMT, (Tn + kMT - 1) / kMT, chains), dim3(kThreads), 0, s, g);
   const int C = a.conv_in ? 2 * a.d : a.d;
   hipLaunchKernelGGL(bwd_conv_x_k<T>, dim3((Tn + kTI - 1) / kTI, (C + kTI - 1) / kTI, chains), dim3(kThreads), 0, s, g);
   hipLaunchKernelGGL(bwd_conv_w_k<T>,

@@ -84,7 +84,8 @@ struct AttnArgs {
 // d_o, d_q [batch, Hq, Bn, d]; d_k, d_v [batch, Hkv, Bn, d]; d_new_k/v, d_cache_k/v [chains, M, d];
 // d_conv_w / d_conv_b laid out like conv_w / conv_b (added to).  Workspace: ws_p, ws_ds
 // [batch, Hq, Bn, T] (attention rows and their gradient), ws_w [chains, M, T] (raw logits on entry,
-// their gradient on exit), ws_n [chains, M, T] (normalised rows).
+// their gradient on exit), ws_n [chains, M, T] (normalised rows), ws_dw [chains, M, T] (gradient of the
+// normalised rows).
 struct BwdArgs {
   StepArgs st;
   const float* d_o;
@@ -101,6 +102,7 @@ struct BwdArgs {
   float* ws_ds;
   float* ws_w;
   float* ws_n;
+  float* ws_dw;
 };
 hipError_t launch_step_backward_generic(int dtype, const BwdArgs& g, bool compress, hipStream_t s);
 
