@@ -717,9 +717,6 @@ lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococ
   const bool compress = cache_before->len + B > cfg->M;
   if (compress && (!conv_w || !d_conv_w))
     return fail(LOCOCO_EINVAL, "conv_w or d_conv_w is NULL but the step compresses");
-  if ((int64_t)cache_before->len + B + 2 * (int64_t)cfg->head_dim > 15360)
-    return fail(LOCOCO_EUNSUPPORTED, "cache.len + B + 2 head_dim = %lld exceeds the 15360 floats of LDS the "
-                "backward attention rows use", (long long)cache_before->len + B + 2 * cfg->head_dim);
   const BwdLayout l = bwd_layout(cfg, B, cache_before->len);
   if (!workspace || ws_bytes < l.total || ((uintptr_t)workspace & 255))
     return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", l.total,

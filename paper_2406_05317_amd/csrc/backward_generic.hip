@@ -2,8 +2,8 @@
 // the scan): chain rule on Alg. 2 step 3 (Eq. 1), the fill branch, and
 // Eq. 5 / Eq. 6 / Eq. 4a-4b.  Shape-agnostic, fp32 arithmetic, fp32 gradients;
 // inputs in the storage dtype (fp32 or bf16), storage rounding treated as the
-// identity.  One workgroup per output row, straight from the definitions, like
-// the forward kernels next door: correct first, not tuned.
+// identity.  The contractions are tiled through LDS (64 x 64 outputs per
+// workgroup); the row reductions between them are one workgroup per row.
 //
 // Notation (one chain): Y = [cache(0:m) ; block] (T = m + Bn rows) for K and V,
 // P the attention rows, w the mixing rows (Eq. 6), g_k / g_v the gradients of
@@ -76,95 +76,220 @@ __device__ __forceinline__ bool slot_protected(const StepArgs& a, int ch, int i)
   return a.protect && i < a.m && ((a.protect[(int64_t)ch * a.protect_stride + (i >> 5)] >> (i & 31)) & 1u);
 }
 
-// ---- attention, one workgroup per (query row r, query head, batch): P row, dS row, dq row
+// ---- attention.  Its five contractions are GEMMs, tiled through LDS in fp32: 64 x 64 outputs per
+// workgroup, 4 x 4 per thread, operands in chunks of 16 along the contraction; the softmax and its
+// backward are row reductions between them, one workgroup per query row.
+constexpr int kAT = 64, kAK = 16;
+
+// scores S[r, j] = scale q[r] . Yk[j] and dP[r, j] = dO[r] . Yv[j]  (query rows x positions, over d);
+// entries a query does not see are left to the row kernel
 template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_attn_scores_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  __shared__ float Qs[kAK][kAT + 4], Os[kAK][kAT + 4];     // [column][query row]
+  __shared__ float Ks[kAK][kAT + 4], Vs[kAK][kAT + 4];     // [column][position]
+  const int Tn = a.m + a.Bn, d = a.d;
+  const int j0 = blockIdx.x * kAT, r0 = blockIdx.y * kAT;
+  const int hq = blockIdx.z % a.Hq, b = blockIdx.z / a.Hq, hkv = hq / a.group;
+  if (j0 > a.m + r0 + kAT - 1) return;             // the whole tile lies after its queries
+  const int tr = threadIdx.x / 16, tj = threadIdx.x % 16;
+  const int64_t row0 = ((int64_t)b * a.Hq + hq) * a.Bn;
+  float accs[4][4], accp[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) accs[ii][jj] = accp[ii][jj] = 0.f;
+  for (int c0 = 0; c0 < d; c0 += kAK) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < kAK * kAT; e += kThreads) {
+      const int c = e % kAK, x = e / kAK, cc = c0 + c;
+      float qv = 0.f, ov = 0.f, kv = 0.f, vv = 0.f;
+      if (cc < d) {
+        if (r0 + x < a.Bn) {
+          qv = to_f(((const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)(r0 + x) * a.q.st)[cc]);
+          ov = g.d_o[(row0 + r0 + x) * d + cc];
+        }
+        if (j0 + x < Tn) {
+          kv = to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j0 + x)[cc]);
+          vv = to_f(cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j0 + x)[cc]);
+        }
+      }
+      Qs[c][x] = qv; Os[c][x] = ov; Ks[c][x] = kv; Vs[c][x] = vv;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kAK; ++c) {
+      const float4 q4 = *(const float4*)&Qs[c][tr * 4], o4 = *(const float4*)&Os[c][tr * 4];
+      const float4 k4 = *(const float4*)&Ks[c][tj * 4], v4 = *(const float4*)&Vs[c][tj * 4];
+      const float qr[4] = {q4.x, q4.y, q4.z, q4.w}, orr[4] = {o4.x, o4.y, o4.z, o4.w};
+      const float kr[4] = {k4.x, k4.y, k4.z, k4.w}, vr[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          accs[ii][jj] = fmaf(qr[ii], kr[jj], accs[ii][jj]);
+          accp[ii][jj] = fmaf(orr[ii], vr[jj], accp[ii][jj]);
+        }
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) {
+    const int r = r0 + tr * 4 + ii;
+    if (r >= a.Bn) continue;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + tj * 4 + jj;
+      if (j < Tn) {
+        g.ws_p[(row0 + r) * Tn + j] = accs[ii][jj] * a.scale;
+        g.ws_ds[(row0 + r) * Tn + j] = accp[ii][jj];
+      }
+    }
+  }
+}
+
+// one workgroup per (query row r, query head, batch): P[r, :] from the scores, dS[r, :] from dP
 __global__ __launch_bounds__(kThreads) void bwd_attn_rows_k(BwdArgs g) {
   const StepArgs& a = g.st;
-  extern __shared__ float lds[];                 // [Tn] scores -> P, then [d] query, [d] dO
   __shared__ float red[kWaves];
-  const int r = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, hkv = hq / a.group;
-  const int Tn = a.m + a.Bn, n_vis = a.m + r + 1, d = a.d;
-  float* prow = lds;
-  float* qs = lds + Tn;
-  float* dos = qs + d;
-  const T* qr = (const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)r * a.q.st;
-  const float* dor = g.d_o + (((int64_t)b * a.Hq + hq) * a.Bn + r) * d;
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    qs[c] = to_f(qr[c]);
-    dos[c] = dor[c];
-  }
-  __syncthreads();
-  float mx = -INFINITY;
-  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
-    const T* kj = cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j);
-    float acc = 0.f;
-    for (int c = 0; c < d; ++c) acc += qs[c] * to_f(kj[c]);
-    prow[j] = acc * a.scale;
-    mx = fmaxf(mx, prow[j]);
-  }
-  mx = block_max(mx, red);
-  float z = 0.f;
-  for (int j = threadIdx.x; j < n_vis; j += kThreads) {
-    prow[j] = expf(prow[j] - mx);
-    z += prow[j];
-  }
-  z = block_sum(z, red);
+  const int r = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  const int Tn = a.m + a.Bn, n_vis = a.m + r + 1;
   float* P = g.ws_p + (((int64_t)b * a.Hq + hq) * a.Bn + r) * Tn;
   float* dS = g.ws_ds + (((int64_t)b * a.Hq + hq) * a.Bn + r) * Tn;
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) mx = fmaxf(mx, P[j]);
+  mx = block_max(mx, red);
+  float z = 0.f;
+  for (int j = threadIdx.x; j < n_vis; j += kThreads) z += expf(P[j] - mx);
+  z = block_sum(z, red);
   float dot = 0.f;
   for (int j = threadIdx.x; j < n_vis; j += kThreads) {
-    const T* vj = cat_row<T>(a.cache_v, a.v, a.M, d, a.m, b, hkv, a.Hkv, j);
-    float acc = 0.f;
-    for (int c = 0; c < d; ++c) acc += dos[c] * to_f(vj[c]);
-    const float p = prow[j] / z;
-    prow[j] = p;
+    const float p = expf(P[j] - mx) / z;
     P[j] = p;
-    dS[j] = acc;                                  // dP for now
-    dot += p * acc;
+    dot += p * dS[j];
   }
   dot = block_sum(dot, red);
   for (int j = threadIdx.x; j < Tn; j += kThreads) {
     if (j < n_vis) {
-      dS[j] = prow[j] * (dS[j] - dot) * a.scale;
-      prow[j] = dS[j];
+      dS[j] = P[j] * (dS[j] - dot) * a.scale;
     } else {
       P[j] = 0.f;
       dS[j] = 0.f;
     }
   }
-  __syncthreads();
-  float* dq = g.d_q + (((int64_t)b * a.Hq + hq) * a.Bn + r) * d;
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    float acc = 0.f;
-    for (int j = 0; j < n_vis; ++j)
-      acc += prow[j] * to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, j)[c]);
-    dq[c] = acc;
+}
+
+// dq[r, c] = sum_j dS[r, j] Yk[j, c]  (query rows x columns, over the positions)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_attn_dq_k(BwdArgs g) {
+  const StepArgs& a = g.st;
+  __shared__ float Ss[kAK][kAT + 4];               // [position][query row]
+  __shared__ float Ys[kAK][kAT + 4];               // [position][column]
+  const int Tn = a.m + a.Bn, d = a.d;
+  const int c0 = blockIdx.x * kAT, r0 = blockIdx.y * kAT;
+  const int hq = blockIdx.z % a.Hq, b = blockIdx.z / a.Hq, hkv = hq / a.group;
+  const int tr = threadIdx.x / 16, tc = threadIdx.x % 16;
+  const int64_t row0 = ((int64_t)b * a.Hq + hq) * a.Bn;
+  const int jend = min(Tn, a.m + r0 + kAT);        // nothing to add after the tile's last query
+  float acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[ii][q] = 0.f;
+  for (int jc = 0; jc < jend; jc += kAK) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < kAK * kAT; e += kThreads) {
+      const int jj = e % kAK, x = e / kAK;         // dS rows are contiguous along the positions
+      Ss[jj][x] = (r0 + x < a.Bn && jc + jj < Tn) ? g.ws_ds[(row0 + r0 + x) * Tn + jc + jj] : 0.f;
+    }
+    for (int e = threadIdx.x; e < kAK * kAT; e += kThreads) {
+      const int x = e % kAT, jj = e / kAT;
+      Ys[jj][x] = (jc + jj < Tn && c0 + x < d)
+                      ? to_f(cat_row<T>(a.cache_k, a.k, a.M, d, a.m, b, hkv, a.Hkv, jc + jj)[c0 + x]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jj = 0; jj < kAK; ++jj) {
+      const float4 s4 = *(const float4*)&Ss[jj][tr * 4], y4 = *(const float4*)&Ys[jj][tc * 4];
+      const float sr[4] = {s4.x, s4.y, s4.z, s4.w}, yr[4] = {y4.x, y4.y, y4.z, y4.w};
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[ii][q] = fmaf(sr[ii], yr[q], acc[ii][q]);
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) {
+    const int r = r0 + tr * 4 + ii;
+    if (r >= a.Bn) continue;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = c0 + tc * 4 + q;
+      if (c < d) g.d_q[(row0 + r) * d + c] = acc[ii][q];
+    }
   }
 }
 
-// ---- attention, one workgroup per (position j of [cache ; block], kv head, batch): dYk[j], dYv[j]
-// (assigned, not added: this is the first contribution to those rows)
+// dYk[j, c] = sum over the group's heads and rows of dS[r, j] q[r, c], dYv[j, c] = sum of P[r, j] dO[r, c]
+// (positions x columns, over the query rows; assigned, not added: the first contribution to those rows)
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bwd_attn_cols_k(BwdArgs g) {
   const StepArgs& a = g.st;
-  const int j = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z, ch = b * a.Hkv + hkv;
+  __shared__ float Ss[kAK][kAT + 4], Ps[kAK][kAT + 4];     // [query row][position]
+  __shared__ float Qs[kAK][kAT + 4], Os[kAK][kAT + 4];     // [query row][column]
   const int Tn = a.m + a.Bn, d = a.d;
-  float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
-  float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
-  const int r0 = j < a.m ? 0 : j - a.m;           // block key j' is visible to rows r >= j'
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    float ak = 0.f, av = 0.f;
-    for (int hh = 0; hh < a.group; ++hh) {
-      const int hq = hkv * a.group + hh;
-      const int64_t row0 = ((int64_t)b * a.Hq + hq) * a.Bn;
-      for (int r = r0; r < a.Bn; ++r) {
-        const float ds = g.ws_ds[(row0 + r) * Tn + j], p = g.ws_p[(row0 + r) * Tn + j];
-        ak += ds * to_f(((const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)r * a.q.st)[c]);
-        av += p * g.d_o[(row0 + r) * d + c];
+  const int c0 = blockIdx.x * kAT, j0 = blockIdx.y * kAT, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int tj = threadIdx.x / 16, tc = threadIdx.x % 16;
+  const int rbeg = j0 < a.m ? 0 : (j0 - a.m) / kAK * kAK;   // block key j' is visible to rows r >= j'
+  float acck[4][4], accv[4][4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acck[jj][q] = accv[jj][q] = 0.f;
+  for (int hh = 0; hh < a.group; ++hh) {
+    const int hq = hkv * a.group + hh;
+    const int64_t row0 = ((int64_t)b * a.Hq + hq) * a.Bn;
+    for (int rc = rbeg; rc < a.Bn; rc += kAK) {
+      __syncthreads();
+      for (int e = threadIdx.x; e < kAK * kAT; e += kThreads) {
+        const int x = e % kAT, rr = e / kAT, r = rc + rr;
+        const bool in = r < a.Bn && j0 + x < Tn;
+        Ss[rr][x] = in ? g.ws_ds[(row0 + r) * Tn + j0 + x] : 0.f;
+        Ps[rr][x] = in ? g.ws_p[(row0 + r) * Tn + j0 + x] : 0.f;
+        const bool inc = r < a.Bn && c0 + x < d;
+        Qs[rr][x] = inc ? to_f(((const T*)a.q.p + b * a.q.sb + hq * a.q.sh + (int64_t)r * a.q.st)[c0 + x]) : 0.f;
+        Os[rr][x] = inc ? g.d_o[(row0 + r) * d + c0 + x] : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int rr = 0; rr < kAK; ++rr) {
+        const float4 s4 = *(const float4*)&Ss[rr][tj * 4], p4 = *(const float4*)&Ps[rr][tj * 4];
+        const float4 q4 = *(const float4*)&Qs[rr][tc * 4], o4 = *(const float4*)&Os[rr][tc * 4];
+        const float sr[4] = {s4.x, s4.y, s4.z, s4.w}, pr[4] = {p4.x, p4.y, p4.z, p4.w};
+        const float qr[4] = {q4.x, q4.y, q4.z, q4.w}, orr[4] = {o4.x, o4.y, o4.z, o4.w};
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acck[jj][q] = fmaf(sr[jj], qr[q], acck[jj][q]);
+            accv[jj][q] = fmaf(pr[jj], orr[q], accv[jj][q]);
+          }
       }
     }
-    dk[c] = ak;
-    dv[c] = av;
+  }
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int j = j0 + tj * 4 + jj;
+    if (j >= Tn) continue;
+    float* dk = grad_row(g.d_cache_k, g.d_k, a.M, d, a.m, a.Bn, ch, j);
+    float* dv = grad_row(g.d_cache_v, g.d_v, a.M, d, a.m, a.Bn, ch, j);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = c0 + tc * 4 + q;
+      if (c < d) {
+        dk[c] = acck[jj][q];
+        dv[c] = accv[jj][q];
+      }
+    }
   }
 }
 
@@ -487,9 +612,13 @@ template <typename T>
 hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
   const StepArgs& a = g.st;
   const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv;
-  hipLaunchKernelGGL(bwd_attn_rows_k<T>, dim3(a.Bn, a.Hq, a.batch), dim3(kThreads),
-                     (size_t)(Tn + 2 * a.d) * sizeof(float), s, g);
-  hipLaunchKernelGGL(bwd_attn_cols_k<T>, dim3(Tn, a.Hkv, a.batch), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_attn_scores_k<T>, dim3((Tn + kAT - 1) / kAT, (a.Bn + kAT - 1) / kAT, a.batch * a.Hq),
+                     dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_attn_rows_k, dim3(a.Bn, a.Hq, a.batch), dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_attn_dq_k<T>, dim3((a.d + kAT - 1) / kAT, (a.Bn + kAT - 1) / kAT, a.batch * a.Hq),
+                     dim3(kThreads), 0, s, g);
+  hipLaunchKernelGGL(bwd_attn_cols_k<T>, dim3((a.d + kAT - 1) / kAT, (Tn + kAT - 1) / kAT, chains), dim3(kThreads),
+                     0, s, g);
   if (a.m < a.M) hipLaunchKernelGGL(bwd_zero_dead_rows_k, dim3(64, chains), dim3(kThreads), 0, s, g);
   if (!compress) {
     hipLaunchKernelGGL(bwd_fill_k, dim3(64, chains), dim3(kThreads), 0, s, g);
