@@ -237,7 +237,8 @@ bool chain_sync_through_l2() {
 bool scan_in_one_launch(const lococo_config* c) {
   const char* e = getenv("LOCOCO_SCAN_LAUNCHES");
   if (e && !strcmp(e, "steps")) return false;
-  return compress_scan_fits(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count());
+  return compress_scan_groups(c->batch, c->n_kv_heads, c->M, c->conv_width,
+                              c->w_head_stride != 0 || c->b_head_stride != 0, cu_count()) > 0;
 }
 
 View view_at(const lococo_tensor& t, int64_t tok, size_t es) {

@@ -164,7 +164,9 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // with the rectifier of the convolution head in front of it).
 // PROT = 1: the cache carries protected slots (lococo_cache.protect); a build of its own so that the
 // common case pays neither the registers nor the instructions.
-template <int BM, int KW, int NORM, int PROT>
+// MULTI = 1: a workgroup may own several chains (see below); also a build of its own, because the
+// register allocation of the one-chain build is tight and the 32 K-token workload runs on it.
+template <int BM, int KW, int NORM, int PROT, int MULTI>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
@@ -186,19 +188,23 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     if (item < per * 8) item = (item % 8) * per + item / 8;
   }
   const int tiles = a.M / BM;
-  const int ch = item / tiles, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  // A workgroup owns one slot tile of the chains grp, grp + groups, grp + 2 groups, ...  (one chain
+  // when the launch has a workgroup per chain and tile).  Where filters or biases differ between
+  // kv heads the host picks `groups` as a multiple of Hkv, so all of them belong to head hkv0.
+  const int grp = item / tiles, groups = gridDim.x / tiles, n_chains = a.batch * a.Hkv;
+  const int hkv0 = grp % a.Hkv;
   const int i0 = (item % tiles) * BM;
-  // per-step quantities, set at the top of the step loop
+  // per-step and per-chain quantities, set at the top of the loops
   int T = 0, m = 0, NT = 0;
   CatRows cat_k, cat_v;
-  // protected-slot bits of this chain (see lococo_cache.protect), or null
-  const uint32_t* pwords = PROT ? a.protect + (int64_t)ch * a.protect_stride : nullptr;
+  // protected-slot bits of the chain at hand (see lococo_cache.protect), or null
+  const uint32_t* pwords = nullptr;
 
   // ---- this wave's slice of the filter bank, resident in registers for the whole kernel:
   // lane (slot l31 of tile rt, channels 32w + 16h + 8*lh ..) for every tap
   bf16x8 wreg[G::RT][KW][2];
   {
-    const uint16_t* wb = wp + hkv * wp_head_stride;
+    const uint16_t* wb = wp + hkv0 * wp_head_stride;
 #pragma unroll
     for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
@@ -225,7 +231,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   const int sp0 = (l % G::LPR) * G::EPL;
   float m_run = 0.f, l_run = 0.f;
   const float bias =
-      a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv * a.b_head_stride + i0 + srow] << 16)
+      a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv0 * a.b_head_stride + i0 + srow] << 16)
                : 0.f;
 
   // ---- staging: global -> registers -> LDS (key tile with halo, value tile; both row-major)
@@ -502,34 +508,44 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // ---- meeting point of the slot tiles of a chain between two steps of the one-launch scan.
-  // Round r is complete when the chain's counter has reached tiles * (r + 1).
+  // ---- meeting point of the slot tiles of a chain between two steps of the one-launch scan:
+  // a counter per chain.  A tile signals when its rows of the new cache are written and waits,
+  // before it reads the chain's cache for the next step, until the counter says that every tile
+  // has signalled: round r is complete at tiles * (r + 1).  A workgroup with several chains goes
+  // through them in the same order as the other tiles of its group, so by the time it comes back to a
+  // chain the others have long signalled and the wait costs one load; with one chain per
+  // workgroup the wait follows the signal directly.
   //
   // General form: workgroup barrier, thread 0 does a device-scope release increment (which writes
-  // the L2 back: every dirty line of the XCD, about 3 us per step on the 32 K-token workload) and
-  // polls, device-scope acquire, workgroup barrier.  One wave pays for the cache maintenance.
+  // the L2 back: every dirty line of the XCD, about 3 us per step on the 32 K-token workload);
+  // the wait polls, then a device-scope acquire, then a workgroup barrier.  One wave pays for the
+  // cache maintenance.
   //
   // When all tiles of the chain run on one XCD they share one L2, and nothing has to be written
   // back or invalidated there: stores go through the CU's L1 to the L2 and have arrived when the
   // wave's store counter reaches zero, and the cache rows are read at device scope (see
-  // load_cat16).  So each wave waits for its stores, the workgroup meets, thread 0 increments and
-  // polls with relaxed device-scope atomics, the workgroup meets again.  Whether the tiles share
-  // an XCD is not assumed from the workgroup numbering: round 0, before the first step, is a
-  // general-form meeting in which every tile reports the XCD it runs on.
+  // load_cat16).  So each wave waits for its stores, the workgroup meets, thread 0 increments with
+  // a relaxed device-scope atomic and polls with relaxed loads.  Whether the tiles share an XCD is
+  // not assumed from the workgroup numbering: round 0, before the first step, is a general-form
+  // meeting in which every tile reports the XCD it runs on.
   __shared__ int bail;                       // a chain wait timed out: leave
   __shared__ int same_l2;
   if (tid == 0) { bail = 0; same_l2 = 0; }
   __syncthreads();
-  auto chain_sync = [&](int round) -> bool {
+  auto chain_signal = [&](int c) {
     const bool fast = same_l2 != 0;          // LDS word written before the previous workgroup barrier
     if (fast) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-      if (fast) __hip_atomic_fetch_add(sa.sync + ch, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      else __hip_atomic_fetch_add(sa.sync + ch, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      if (fast) __hip_atomic_fetch_add(sa.sync + c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else __hip_atomic_fetch_add(sa.sync + c, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  };
+  auto chain_wait = [&](int c, int round) -> bool {
+    if (tid == 0) {
       const uint32_t target = (uint32_t)tiles * (uint32_t)(round + 1);
       int polls = 0;
-      while (__hip_atomic_load(sa.sync + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      while (__hip_atomic_load(sa.sync + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
         __builtin_amdgcn_s_sleep(2);
         if (++polls > sa.spin_limit) {         // bounded: never spin forever on a workgroup that is not there
           __hip_atomic_store(sa.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -537,28 +553,41 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
           break;
         }
       }
-      if (!fast) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      if (same_l2 == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
     return bail == 0;
   };
   if (sa.n_steps > 1) {
-    uint32_t* xcd_mask = sa.sync + (int64_t)a.batch * a.Hkv + 1 + ch;
+    uint32_t* xcd_mask = sa.sync + n_chains + 1;
     if (tid == 0) {
       const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | ((4 - 1) << 11));   // XCC_ID, bits [3:0]
-      __hip_atomic_fetch_or(xcd_mask, 1u << xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int c = grp; c < n_chains; c += groups)
+        __hip_atomic_fetch_or(xcd_mask + c, 1u << xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (!chain_sync(0)) return;
-    if (tid == 0) {
-      const uint32_t mask = __hip_atomic_load(xcd_mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      same_l2 = (mask & (mask - 1)) == 0 && sa.same_l2_allowed;
+    for (int c = grp; c < n_chains; c += groups) chain_signal(c);
+    bool one_xcd = true;
+    for (int c = grp; c < n_chains; c += groups) {
+      if (!chain_wait(c, 0)) return;
+      if (tid == 0) {
+        const uint32_t mask = __hip_atomic_load(xcd_mask + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        one_xcd = one_xcd && (mask & (mask - 1)) == 0;
+      }
     }
+    if (tid == 0) same_l2 = one_xcd && sa.same_l2_allowed;
     __syncthreads();
   }
 
-  for (int step = 0; step < sa.n_steps; ++step) {
+  const int n_mine = MULTI ? (n_chains - grp + groups - 1) / groups : 1;
+  for (int step = 0; step < sa.n_steps; ++step)
+  for (int ci = 0; ci < n_mine; ++ci) {
+  const int ch = grp + ci * groups;
+  // ---- the step reads what every slot tile of this chain wrote in the step before
+  if (step > 0 && !chain_wait(ch, step)) return;
   // ---- this step's inputs: source state, occupancy, block
   {
+    const int b = ch / a.Hkv, hkv = ch % a.Hkv;
+    if (PROT) pwords = a.protect + (int64_t)ch * a.protect_stride;
     const int64_t tok = (int64_t)step * sa.B;
     const int Bn = step == 0 ? a.Bn : (int)(sa.tokens_left - tok < sa.B ? sa.tokens_left - tok : sa.B);
     m = step == 0 ? a.m : a.M;
@@ -667,11 +696,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     }
   }
 
-  // ---- the next step reads what every slot tile of this chain has just written
-  if (step + 1 < sa.n_steps) {
-    if (!chain_sync(step + 1)) break;
-  }
-  }  // step loop
+  // ---- the rows are on their way: tell the other tiles of the chain.  (The barrier also keeps
+  // the next prologue's LDS stores behind the copy-out above.)
+  if (step + 1 < sa.n_steps) chain_signal(ch);
+  else __syncthreads();
+  }  // step and chain loops
 }
 
 // [M][C][k] per bank -> register order (see compress_mfma_k); one thread per 16-byte chunk.
@@ -698,19 +727,25 @@ __global__ void zero_words_k(uint32_t* p, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-template <int BM, int KW, int NORM, int PROT>
-hipError_t launch_one(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
+template <int BM, int KW, int NORM, int PROT, int MULTI>
+hipError_t launch_kernel(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
   using G = Geo<BM, KW>;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((a.st.M / BM) * a.st.batch * a.st.Hkv);
-  hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT>), grid, dim3(kThreads), G::LDS, s, a, wp, wp_head_stride);
+  dim3 grid((a.st.M / BM) * a.groups);
+  hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI>), grid, dim3(kThreads), G::LDS, s, a, wp,
+                     wp_head_stride);
   return hipGetLastError();
+}
+template <int BM, int KW, int NORM, int PROT>
+hipError_t launch_one(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
+  return a.groups < a.st.batch * a.st.Hkv ? launch_kernel<BM, KW, NORM, PROT, 1>(a, wp, wp_head_stride, s)
+                                          : launch_kernel<BM, KW, NORM, PROT, 0>(a, wp, wp_head_stride, s);
 }
 
 }  // namespace
@@ -780,14 +815,24 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.status = nullptr;
   sa.spin_limit = 0;
   sa.same_l2_allowed = 0;
+  sa.groups = a.batch * a.Hkv;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
   return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
 
-bool compress_scan_fits(int batch, int Hkv, int M, int k_width, int n_cu) {
+int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, int n_cu) {
   const int bm = use_big_tiles(batch, Hkv, M, k_width, n_cu) ? 64 : 32;
-  // one workgroup per compute unit (LDS): every workgroup of the launch is resident at once
-  return (int64_t)batch * Hkv * (M / bm) <= n_cu;
+  const int tiles = M / bm, chains = batch * Hkv;
+  // one workgroup per compute unit (LDS): every workgroup of the launch must be resident at once
+  int g = n_cu / tiles;
+  if (g >= chains) return chains;
+  // Fewer workgroups than (chain, tile) pairs: each takes several chains.  They must share its
+  // resident filter slice, and the tiles of a group should share an XCD (ids are dealt round-robin
+  // over 8 XCDs: a multiple of 8 groups does that).
+  const int unit = per_head ? (Hkv % 8 == 0 ? Hkv : (8 % Hkv == 0 ? 8 : 8 * Hkv)) : 8;
+  if (g >= unit) g -= g % unit;
+  else if (per_head) g -= g % Hkv;
+  return g;
 }
 
 // [chain counters][status word][per chain: bit mask of the XCDs its slot tiles run on]
@@ -806,6 +851,9 @@ hipError_t launch_compress_scan(const ScanArgs& a_in, const void* wp, int banks,
   const int chains = a.st.batch * a.st.Hkv;
   a.sync = (uint32_t*)sync_ws;
   a.status = (int32_t*)sync_ws + chains;
+  a.groups = compress_scan_groups(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width,
+                                  a.st.w_head_stride != 0 || a.st.b_head_stride != 0, n_cu);
+  if (a.groups <= 0) return hipErrorInvalidValue;   // scan_in_one_launch() keeps such shapes away
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD : 0;
   return dispatch(a, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }

@@ -57,6 +57,7 @@ struct ScanArgs {
   int32_t* status;
   int32_t spin_limit;
   int32_t same_l2_allowed;   // 0: always meet with device-scope release / acquire (see compress_mfma.hip)
+  int32_t groups;            // workgroups per slot tile; group g runs chains g, g + groups, ... (filled in by the launcher)
 };
 
 // Arguments of the MFMA attention kernel: one block, or every block of a scan
@@ -134,8 +135,10 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
 // Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
                                 hipStream_t s);
-// true if all steps of a scan can run in one launch (every workgroup resident at once)
-bool compress_scan_fits(int batch, int Hkv, int M, int k_width, int n_cu);
+// Workgroups per slot tile with which all steps of a scan run in one launch, every workgroup
+// resident at once (each takes every groups-th chain); 0 if there is no such number.  per_head:
+// filters or biases differ between kv heads.
+int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, int n_cu);
 // bytes of the sync counters + status word the scan launch needs
 size_t compress_scan_sync_bytes(int batch, int Hkv);
 // zero them (a fill kernel, so the call may sit inside a captured graph)

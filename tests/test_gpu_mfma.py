@@ -171,6 +171,35 @@ def test_chain_meeting_through_the_shared_l2_equals_the_device_scope_one(case, m
     compare_scan(w, ref, want, what="device-scope chain meeting")
 
 
+@pytest.mark.parametrize("case", [
+    # 96 chains x 4 slot tiles of 32 for 256 compute units: 64 workgroups per tile, one or two chains each
+    dict(batch=12, n_q_heads=8, n_kv_heads=8, M=128, B=64, L=448),
+    # 320 chains x 2 slot tiles of 64, filters per head: 128 workgroups per tile, two or three chains each
+    dict(batch=5, n_q_heads=64, n_kv_heads=64, M=128, B=64, L=384, per_head_filters=True, bias_sigma=0.5),
+    # grouped query heads, ragged last block, partly filled cache at the first compress step
+    dict(batch=40, n_q_heads=8, n_kv_heads=4, M=64, B=48, L=300, tok_lognormal_sigma=0.5),
+])
+def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
+    """More (chain, slot tile) pairs than compute units: the one-launch scan gives every workgroup
+    several chains of one slot tile.  Bit-identical to one launch per step, with either form of the
+    chain meeting, and equal to the oracle."""
+    w = _w(**case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    monkeypatch.setenv("LOCOCO_CHAIN_SYNC", "device")
+    c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    monkeypatch.delenv("LOCOCO_CHAIN_SYNC")
+    monkeypatch.setenv("LOCOCO_SCAN_LAUNCHES", "steps")
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    for other in (b, c):
+        for x, y in zip(a[:3], other[:3]):
+            assert torch.equal(x, y)
+        assert a[3:] == other[3:]
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    compare_scan(w, a, want, what="several chains per workgroup")
+
+
 def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
     """Forced from the host: with no polls allowed, the first slot tile to finish a step cannot wait
     for its chain, leaves the kernel, and the status word says so.  Every workgroup still exits."""
