@@ -263,6 +263,20 @@ typedef struct lococo_kernel_time {
 lococo_status lococo_timing_begin(void);
 lococo_status lococo_timing_end(lococo_kernel_time* out, int32_t* n_inout);
 
+/* Measurement aid for benchmarks (no step of the method): what the current
+ * GPU sustains on a bare bf16 MFMA loop (32x32x16, no memory traffic; the
+ * better of one and two waves per SIMD) and on a plain copy inside `scratch`
+ * (bytes read + bytes written per second), so that a kernel's rate can be
+ * quoted against the measured ceilings next to the published ones.
+ *   scratch: device, 16-byte aligned, bytes >= 32 MiB (use >= 1 GiB for a
+ *            figure that is not a cache's); contents overwritten.
+ *   mfma_tflops, copy_gbs: host, written on success.
+ * Runs for about 0.2 s (long enough for the clock to settle under matrix load)
+ * and waits for the stream.
+ * LOCOCO_EINVAL for null / misaligned / too small arguments. */
+lococo_status lococo_measure_peaks(void* scratch, size_t bytes, void* stream, double* mfma_tflops,
+                                   double* copy_gbs);
+
 /* Message for the last non-OK status returned on the calling thread
  * (static thread-local storage; never NULL). */
 const char* lococo_last_error(void);

@@ -23,7 +23,8 @@ LOCOCO_FLAG_FILTERS_PREPARED = 1
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
            "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status",
-           "lococo_prepare_filters", "lococo_backward_workspace_bytes", "lococo_segment_step_backward"]
+           "lococo_prepare_filters", "lococo_backward_workspace_bytes", "lococo_segment_step_backward",
+           "lococo_measure_peaks"]
 
 
 class lococo_config(C.Structure):
@@ -95,6 +96,8 @@ def lib():
         L.lococo_backward_workspace_bytes.argtypes = [cfgp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         L.lococo_segment_step_backward.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, C.c_void_p, cap] + [fp] * 10 + [
             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.lococo_measure_peaks.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double),
+                                           C.POINTER(C.c_double)]
         L.lococo_timing_begin.argtypes = []
         L.lococo_timing_end.argtypes = [C.POINTER(lococo_kernel_time), C.POINTER(C.c_int32)]
         for n in EXPORTS[:6] + EXPORTS[8:]:
@@ -291,6 +294,14 @@ def lococo_scan_status(cfg, workspace) -> int:
     out = C.c_int32(0)
     _check(lib().lococo_scan_status(C.byref(cfg), _ptr(workspace), C.byref(out)))
     return out.value
+
+
+def lococo_measure_peaks(scratch: torch.Tensor) -> tuple:
+    """(bf16 MFMA TFLOP/s of a bare loop, GB/s of a plain copy inside `scratch`) on the current GPU."""
+    tf, gbs = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().lococo_measure_peaks(_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(),
+                                      C.byref(tf), C.byref(gbs)))
+    return tf.value, gbs.value
 
 
 def lococo_timing_begin():

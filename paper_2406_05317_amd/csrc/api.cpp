@@ -397,6 +397,16 @@ lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace
   return LOCOCO_OK;
 }
 
+lococo_status lococo_measure_peaks(void* scratch, size_t bytes, void* stream, double* mfma_tflops,
+                                   double* copy_gbs) {
+  if (!scratch || !mfma_tflops || !copy_gbs) return fail(LOCOCO_EINVAL, "null argument");
+  if ((uintptr_t)scratch & 15) return fail(LOCOCO_EINVAL, "scratch must be 16-byte aligned");
+  if (bytes < ((size_t)32 << 20)) return fail(LOCOCO_EINVAL, "scratch must hold at least 32 MiB (got %zu bytes)", bytes);
+  HIP_TRY(measure_peaks(scratch, bytes, cu_count(), (hipStream_t)stream, mfma_tflops, copy_gbs),
+          "peak measurement");
+  return LOCOCO_OK;
+}
+
 lococo_status lococo_timing_begin(void) {
   std::lock_guard<std::mutex> lk(g_timing_mu);
   for (auto& t : g_timed) {

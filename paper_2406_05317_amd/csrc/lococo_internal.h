@@ -157,4 +157,9 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum);
 hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s);
 
+// ---- measurement aid (peaks.hip): sustained bf16 MFMA rate of a bare loop and bandwidth of a plain
+// copy inside `scratch` (device, overwritten); synchronises the stream
+hipError_t measure_peaks(void* scratch, size_t bytes, int n_cu, hipStream_t s, double* mfma_tflops,
+                         double* copy_gbs);
+
 }  // namespace lococo
