@@ -815,7 +815,10 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.status = nullptr;
   sa.spin_limit = 0;
   sa.same_l2_allowed = 0;
-  sa.groups = a.batch * a.Hkv;
+  // more (chain, tile) pairs than compute units: one resident workgroup per compute unit, each
+  // taking several chains on one load of its filter slice (nothing to wait for within one step)
+  sa.groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
+  if (sa.groups <= 0) sa.groups = a.batch * a.Hkv;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
   return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
