@@ -184,10 +184,12 @@ def decode_bench(args, w, lb, inputs, torch):
 
 
 def backward_bench(args, w, lb, inputs, torch):
-    """Backward of one compress step (full cache, one block) on the shape-agnostic kernels."""
+    """Backward of one compress step (full cache, one block).  --impl 1: every kernel shape-agnostic,
+    fp32 vector arithmetic; default: the three Eq. 5 contractions on the matrix cores."""
     dev = "cuda"
     w = w.replace(name=w.name + "-backward-step", L=w.B)
-    cfg = lb.config_for(w, impl=1)
+    cfg = lb.config_for(w, impl=args.impl)
+    generic = args.impl == 1
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
     qd, kd, vd, cwd = (t.to(dev) for t in (q, k, v, cw))
@@ -213,17 +215,18 @@ def backward_bench(args, w, lb, inputs, torch):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     fl = step_flops(w, w.M, w.B)
-    print(json.dumps({"metric": "backward of one compress step, tokens/sec per layer (shape-agnostic kernels)",
+    tf = 2.0 * sum(fl.values()) / (ms * 1e-3) / 1e12
+    peak = PEAK_FP32_VALU_TFLOPS if generic else PEAK_BF16_MFMA_TFLOPS
+    print(json.dumps({"metric": "backward of one compress step, tokens/sec per layer (%s)" %
+                                ("shape-agnostic kernels" if generic else "Eq. 5 contractions on MFMA, the rest fp32 vector"),
                       "value": w.batch * w.B / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
                       "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
                       "vs_baseline": None, "dtype": "f32", "data": "synthetic",
                       "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads,
                                  "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "B": w.B, "M": w.M,
                                  "conv_width": w.conv_width},
-                      "roofline": {"bound": "alu", "achieved": 2.0 * sum(fl.values()) / (ms * 1e-3) / 1e12,
-                                   "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": 2.0 * sum(fl.values()) / (ms * 1e-3) / 1e12 / PEAK_FP32_VALU_TFLOPS,
-                                   "traffic": None}}))
+                      "roofline": {"bound": "alu" if generic else "mfma", "achieved": tf, "peak": peak,
+                                   "unit": "TFLOP/s", "frac": tf / peak, "traffic": None}}))
 
 
 def main():

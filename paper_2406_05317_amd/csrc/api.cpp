@@ -682,7 +682,11 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
 }
 
 namespace {
-struct BwdLayout { size_t p, ds, w, n, dw, total; };
+// the Eq. 5 contractions of the backward pass run on MFMA unless the shape-agnostic kernels are asked for
+bool bwd_on_mfma(const lococo_config* c) {
+  return c->impl != LOCOCO_IMPL_GENERIC && bwd_mfma_supports(c->dtype, c->head_dim, c->conv_in, c->conv_width);
+}
+struct BwdLayout { size_t p, ds, w, n, dw, mf, total; };
 BwdLayout bwd_layout(const lococo_config* c, int32_t B, int32_t len) {
   const size_t T = (size_t)len + B;
   const size_t rows = (size_t)c->batch * c->n_q_heads * B * T * sizeof(float);
@@ -694,7 +698,10 @@ BwdLayout bwd_layout(const lococo_config* c, int32_t B, int32_t len) {
   l.w = l.ds + align_up(rows, 256);
   l.n = l.w + align_up(mat, 256);
   l.dw = l.n + align_up(mat, 256);
-  l.total = l.dw + align_up(mat, 256);
+  l.mf = l.dw + align_up(mat, 256);
+  l.total = l.mf;
+  if (compress && bwd_on_mfma(c))
+    l.total += bwd_mfma_layout(c->batch, c->n_kv_heads, c->M, (int)T, c->conv_width, filter_banks(c)).total;
   return l;
 }
 }  // namespace
@@ -753,9 +760,16 @@ lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococ
   g.ws_w = (float*)(ws + l.w);
   g.ws_n = (float*)(ws + l.n);
   g.ws_dw = (float*)(ws + l.dw);
+  g.ws_mfma = compress && bwd_on_mfma(cfg) ? ws + l.mf : nullptr;
+  g.banks = filter_banks(cfg);
   if (compress) {
     // recompute Eq. 5 and Eq. 6 of the forward step: raw logits and normalised rows
-    HIP_TRY(launch_conv_logits_generic(cfg->dtype, g.st, g.ws_w, s), "conv launch");
+    if (g.ws_mfma) {
+      HIP_TRY(launch_bwd_pack_filters(g.st, g.banks, g.ws_mfma, s), "filter packing launch");
+      HIP_TRY(launch_bwd_logits_mfma(g.st, g.ws_mfma, g.ws_w, s), "conv launch");
+    } else {
+      HIP_TRY(launch_conv_logits_generic(cfg->dtype, g.st, g.ws_w, s), "conv launch");
+    }
     if (g.st.protect) HIP_TRY(launch_protect_logits_generic(g.st, g.ws_w, s), "protect launch");
     const size_t mat = (size_t)cfg->batch * cfg->n_kv_heads * cfg->M * ((size_t)cache_before->len + B) *
                        sizeof(float);

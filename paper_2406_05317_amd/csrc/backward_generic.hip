@@ -627,6 +627,10 @@ hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
   hipLaunchKernelGGL(bwd_mix_dw_k<T>, dim3((Tn + kMT - 1) / kMT, (a.M + kMT - 1) / kMT, chains), dim3(kThreads), 0, s, g);
   hipLaunchKernelGGL(bwd_mix_rows_k, dim3(a.M, chains), dim3(kThreads), 0, s, g);
   hipLaunchKernelGGL(bwd_mix_cols_k, dim3((2 * a.d + kMT - 1) / kMT, (Tn + kMT - 1) / kMT, chains), dim3(kThreads), 0, s, g);
+  if (g.ws_mfma) {                      // the two Eq. 5 gradients on the matrix cores
+    hipError_t e = hipGetLastError();
+    return e != hipSuccess ? e : launch_bwd_conv_mfma(g, g.banks, g.ws_mfma, s);
+  }
   const int C = a.conv_in ? 2 * a.d : a.d;
   hipLaunchKernelGGL(bwd_conv_x_k<T>, dim3((Tn + kTI - 1) / kTI, (C + kTI - 1) / kTI, chains), dim3(kThreads), 0, s, g);
   hipLaunchKernelGGL(bwd_conv_w_k<T>,

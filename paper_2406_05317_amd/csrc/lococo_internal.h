@@ -104,6 +104,8 @@ struct BwdArgs {
   float* ws_w;
   float* ws_n;
   float* ws_dw;
+  void* ws_mfma;           // workspace of the MFMA form of the Eq. 5 contractions (see BwdMfmaLayout), or null
+  int32_t banks;           // filter banks (1 = shared by the kv heads)
 };
 hipError_t launch_step_backward_generic(int dtype, const BwdArgs& g, bool compress, hipStream_t s);
 
@@ -156,6 +158,19 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 // ---- attention of one new token per sequence (attn_decode.hip): bf16, head_dim 128, Bn = 1
 bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum);
 hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s);
+
+// ---- Eq. 5 of the backward pass on MFMA (backward_mfma.hip): bf16, head_dim 128, keys-only filters
+bool bwd_mfma_supports(int dtype, int d, int conv_in, int conv_width);
+// byte offsets inside its workspace: filters per tap, dW split into two bf16 halves (transposed, then as it is),
+// filter gradient per tap
+struct BwdMfmaLayout { size_t wt, dhi, dlo, dhi_s, dlo_s, dwt, total; };
+BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int banks);
+// conv_w -> [bank][tap][slot][channel] at the layout's wt
+hipError_t launch_bwd_pack_filters(const StepArgs& a, int banks, void* wt, hipStream_t s);
+// raw logits fp32 [chains, M, T] (bias added), from the packed filters
+hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s);
+// dX into d_k / d_cache_k (added) and dWc into d_conv_w (added), from the logit gradient in g.ws_w
+hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream_t s);
 
 // ---- measurement aid (peaks.hip): sustained bf16 MFMA rate of a bare loop and bandwidth of a plain
 // copy inside `scratch` (device, overwritten); synchronises the stream

@@ -48,6 +48,17 @@ CASES = [
          m=12, conv_width=3, conv_in=1, per_head_filters=True, bias_sigma=0.3),
     dict(name="bf16 protected", dtype="bf16", batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128, B=40, M=64, m=64,
          conv_width=15, protect=True),
+    # the Eq. 5 contractions on the matrix cores (bf16, head_dim 128, keys-only filters; impl = AUTO)
+    dict(name="mfma protected", dtype="bf16", batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128, B=40, M=64, m=64,
+         conv_width=15, protect=True, impl=0),
+    dict(name="mfma ragged per-head", dtype="bf16", batch=2, n_q_heads=2, n_kv_heads=2, head_dim=128, B=100, M=160,
+         m=160, conv_width=15, per_head_filters=True, bias_sigma=0.4, impl=0),     # T = 260, slots padded to 192
+    dict(name="mfma partial cache relu-sum width 21", dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=2, head_dim=128,
+         B=70, M=128, m=90, conv_width=21, norm=1, bias_sigma=0.5, impl=0),
+    dict(name="mfma several tiles grouped heads", dtype="bf16", batch=3, n_q_heads=2, n_kv_heads=1, head_dim=128,
+         B=256, M=256, m=256, conv_width=15, impl=0),                              # 4 position x 2 slot tiles
+    dict(name="mfma width 3", dtype="bf16", batch=1, n_q_heads=1, n_kv_heads=1, head_dim=128, B=33, M=32, m=20,
+         conv_width=3, impl=0),
 ]
 
 
@@ -55,7 +66,7 @@ CASES = [
 def test_step_backward_matches_the_oracle(case):
     c = dict(case)
     c.pop("name")
-    m, use_protect = c.pop("m"), c.pop("protect", False)
+    m, use_protect, impl = c.pop("m"), c.pop("protect", False), c.pop("impl", 1)
     w = inputs.Workload(name="bwd", L=c["B"], seed=11, conv_gain=3.0, **c)
     rng = np.random.default_rng(3)
     q, k, v = inputs.qkv(w)
@@ -71,7 +82,7 @@ def test_step_backward_matches_the_oracle(case):
     protect = (rng.random((w.batch, w.n_kv_heads, w.M)) < 0.2) if use_protect else None
     want = orc.step_backward(q, k, v, ck, cv, m, cw, cb, d_o, gk, gv, M=w.M, conv_in=w.conv_in, norm=w.norm,
                              protect=protect)
-    cfg = lb.config_for(w, impl=1)
+    cfg = lb.config_for(w, impl=impl)
     dW = torch.zeros(cw.shape, dtype=torch.float32, device="cuda")
     dB = None if cb is None else torch.zeros(cb.shape, dtype=torch.float32, device="cuda")
     got = _gpu_step_backward(w, cfg, q, k, v, cw, cb, ck, cv, m, d_o, gk, gv, dW, dB, protect)
