@@ -115,10 +115,12 @@ typedef struct lococo_cache {
    * (step 3) adds, for each live cache slot, the probabilities that the block's queries (all
    * query heads of the group) put on it.  The library never clears or remaps it: after a
    * compression step an unprotected slot holds a different mixture, what its old score means is
-   * the caller's business.  With this pointer set, blocks of more than one token are attended by
-   * the shape-agnostic kernel and lococo_sequence_forward uses its step-by-step schedule (the
-   * MFMA attention kernel keeps no normalised probabilities to sum); one-token blocks (the
-   * generation stage) keep their kernel. */
+   * the caller's business.  On the MFMA path the attention kernel then also writes its row
+   * statistics into the workspace and a second pass over the cache keys sums the normalised
+   * probabilities per slot (lococo_sequence_forward does it for all blocks at once: the sums
+   * commute); a call without workspace (lococo_attn_only, or a fill step given none) attends
+   * such a block with the shape-agnostic kernel instead.  One-token blocks (the generation stage)
+   * have the sums inside their kernel. */
   float* attn_colsum;
 } lococo_cache;
 

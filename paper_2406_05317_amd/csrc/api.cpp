@@ -38,10 +38,10 @@ lococo_status hip_fail(hipError_t e, const char* what) {
 
 // ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
 enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC,
-                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_ATTN_DECODE, K_COUNT };
+                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_ATTN_DECODE, K_ATTN_COLSUM, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
                                            "normalise_generic", "mix_generic", "repack_filters",
-                                           "compress_mfma", "attn_mfma", "attn_decode"};
+                                           "compress_mfma", "attn_mfma", "attn_decode", "attn_colsum"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
@@ -201,9 +201,14 @@ size_t filter_ws_bytes(const lococo_config* c) {
 size_t scan_sync_bytes(const lococo_config* c) {
   return align_up(compress_scan_sync_bytes(c->batch, c->n_kv_heads), 256);
 }
-// MFMA path: [repacked filters][chain sync counters + status word]; generic path: the logits.
+// softmax statistics of `rows` query rows per head (what the column sums of the MFMA attention need)
+size_t stats_bytes(const lococo_config* c, int64_t rows) {
+  return align_up((size_t)c->batch * c->n_q_heads * (size_t)rows * 2 * sizeof(float), 256);
+}
+// MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block];
+// generic path: the logits.
 size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
-  if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c);
+  if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B);
   return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
 }
 
@@ -214,9 +219,9 @@ size_t state_bytes(const lococo_config* c) {
 
 // Workspace of the batched-attention schedule: the step workspace followed by
 // K and V history slots for n_compress cache states.
-// Layout: [step workspace][K history][V history].
-size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_compress) {
-  return step_ws_bytes(c, path, B) + 2 * (size_t)n_compress * align_up(state_bytes(c), 256);
+// Layout: [step workspace][row statistics of the sequence][K history][V history].
+size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_compress, int64_t L) {
+  return step_ws_bytes(c, path, B) + stats_bytes(c, L) + 2 * (size_t)n_compress * align_up(state_bytes(c), 256);
 }
 
 // Polls a waiting workgroup makes before it gives up on its chain (each poll sleeps ~256 cycles);
@@ -308,21 +313,38 @@ AttnArgs attn_args_one_block(const StepArgs& a) {
   return t;
 }
 
-// Enqueue the attention of one block.
-lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, hipStream_t s) {
+// Enqueue the attention of one block.  `stats`: room for the block's row statistics (see
+// stats_bytes), or null; without it a block whose attention is to be accumulated per slot goes
+// to the shape-agnostic kernel.
+lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, float* stats, hipStream_t s) {
   if (path == PATH_MFMA && attn_decode_supports(c->dtype, c->head_dim, a.Bn, c->M, a.colsum != nullptr)) {
     KTimer t(K_ATTN_DECODE, s);          // one query row per head: a matrix-vector product
     HIP_TRY(launch_attn_decode(a, s), "attention launch");
     return LOCOCO_OK;
   }
-  if (path == PATH_MFMA && !a.colsum) {
-    KTimer t(K_ATTN_MFMA, s);
-    HIP_TRY(launch_attn_mfma(attn_args_one_block(a), s), "attention launch");
+  if (path == PATH_MFMA && (!a.colsum || stats)) {
+    AttnArgs t = attn_args_one_block(a);
+    t.stats = a.colsum ? stats : nullptr;
+    {
+      KTimer kt(K_ATTN_MFMA, s);
+      HIP_TRY(launch_attn_mfma(t, s), "attention launch");
+    }
+    if (a.colsum && a.m > 0) {
+      KTimer kt(K_ATTN_COLSUM, s);
+      HIP_TRY(launch_attn_colsum_mfma(t, a.colsum, s), "attention column-sum launch");
+    }
     return LOCOCO_OK;
   }
   KTimer t(K_ATTN_GENERIC, s);
   HIP_TRY(launch_attn_generic(c->dtype, a, s), "attention launch");
   return LOCOCO_OK;
+}
+
+// The statistics area of a step workspace, if the caller passed one that holds it.
+float* step_stats(const lococo_config* c, Path path, int32_t B, void* workspace, size_t ws_bytes) {
+  if (path != PATH_MFMA || !workspace || ((uintptr_t)workspace & 255) || ws_bytes < step_ws_bytes(c, path, B))
+    return nullptr;
+  return (float*)((char*)workspace + filter_ws_bytes(c) + scan_sync_bytes(c));
 }
 
 // Repack the filter bank into the workspace (MFMA path; once per call unless the caller says
@@ -479,7 +501,7 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
   if (history && path == PATH_MFMA)
-    *out = history_ws_bytes(cfg, path, B, (L + B - 1) / B);   // every block may compress
+    *out = history_ws_bytes(cfg, path, B, (L + B - 1) / B, L);   // every block may compress
   else
     *out = step_ws_bytes(cfg, path, B);
   return LOCOCO_OK;
@@ -495,7 +517,7 @@ lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk,
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
   StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, true);
-  return enqueue_attn(cfg, path, a, (hipStream_t)stream);
+  return enqueue_attn(cfg, path, a, nullptr, (hipStream_t)stream);
 }
 
 lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_w, void* workspace,
@@ -543,7 +565,8 @@ lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* b
   if (compress && path == PATH_MFMA &&
       (st = enqueue_repack(cfg, a, workspace, (hipStream_t)stream)))
     return st;
-  if ((st = enqueue_attn(cfg, path, a, (hipStream_t)stream))) return st;
+  if ((st = enqueue_attn(cfg, path, a, step_stats(cfg, path, B, workspace, ws_bytes), (hipStream_t)stream)))
+    return st;
   if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
   *cache = tmp;
   return LOCOCO_OK;
@@ -590,14 +613,15 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   int64_t n_compress = 0, n_fill = 0;
   for (const auto& sg : plan) n_compress += sg.branch;
   while (n_fill < n && plan[(size_t)n_fill].branch == 0) ++n_fill;
-  if (path == PATH_MFMA && any_compress && workspace && !cache->attn_colsum &&
-      ws_bytes >= history_ws_bytes(cfg, path, B, n_compress)) {
+  if (path == PATH_MFMA && any_compress && workspace &&
+      ws_bytes >= history_ws_bytes(cfg, path, B, n_compress, L)) {
     // Batched-attention schedule: run the fill / compress recurrence first, keeping every
     // cache state, then one attention launch over all blocks, then publish the last state.
     hipStream_t s = (hipStream_t)stream;
     const size_t slot = align_up(state_bytes(cfg), 256);
     char* sync_ws = (char*)workspace + filter_ws_bytes(cfg);
-    char* hist_k = (char*)workspace + step_ws_bytes(cfg, path, B);
+    float* seq_stats = (float*)((char*)workspace + step_ws_bytes(cfg, path, B));
+    char* hist_k = (char*)seq_stats + stats_bytes(cfg, L);
     char* hist_v = hist_k + (size_t)n_compress * slot;
     const void* src_k = tmp.k[tmp.cur];
     const void* src_v = tmp.v[tmp.cur];
@@ -659,8 +683,15 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
       t.len0 = cache->len;
       t.n_fill = (int32_t)n_fill;
       t.n_seg = (int32_t)n;
-      KTimer kt(K_ATTN_MFMA, s);
-      HIP_TRY(launch_attn_mfma(t, s), "attention launch");
+      t.stats = cache->attn_colsum ? seq_stats : nullptr;
+      {
+        KTimer kt(K_ATTN_MFMA, s);
+        HIP_TRY(launch_attn_mfma(t, s), "attention launch");
+      }
+      if (cache->attn_colsum) {             // sums over blocks commute: one launch for all of them
+        KTimer kt(K_ATTN_COLSUM, s);
+        HIP_TRY(launch_attn_colsum_mfma(t, cache->attn_colsum, s), "attention column-sum launch");
+      }
     }
     const lococo_seg& last = plan.back();
     HIP_TRY(hipMemcpyAsync(tmp.k[last.buf_after], src_k, state_bytes(cfg), hipMemcpyDeviceToDevice, s),
@@ -674,7 +705,8 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   }
   for (const auto& sg : plan) {
     StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
-    if ((st = enqueue_attn(cfg, path, a, (hipStream_t)stream))) return st;
+    if ((st = enqueue_attn(cfg, path, a, step_stats(cfg, path, B, workspace, ws_bytes), (hipStream_t)stream)))
+      return st;
     if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
   }
   *cache = tmp;

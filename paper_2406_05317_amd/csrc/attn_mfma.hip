@@ -378,6 +378,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
   unsigned char* Os = smem + w * (32 * KSTRIDE);
   {
     const float inv = 1.0f / l_run;
+    if (a.stats && lh == 0 && qrow < Bn) {     // for the column sums (see attn_colsum_k)
+      float* st = a.stats + (((int64_t)b * a.Hq + hq) * a.L + start + qrow) * 2;
+      st[0] = m_run * c;
+      st[1] = inv;
+    }
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -394,6 +399,78 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
     const u32x4 v = *(const u32x4*)(Os + row * KSTRIDE + (l & 15) * 16);
     if (wq0 + row < Bn) *(u32x4*)(ob + (int64_t)(wq0 + row) * a.o.st + (l & 15) * 8) = v;
   }
+}
+
+// ---- accumulated attention per cache slot.  One workgroup per (block, chain, 64 cache slots): the
+// slots' keys stay in registers as MFMA operands, the waves share out the block's query rows (all
+// heads of the group) in chunks of 32, recompute S^T = K Q^T, turn it into probabilities with the
+// row statistics the attention kernel left, and sum over the queries.  Cache slots precede every
+// token of the block, so there is no mask.
+__global__ __launch_bounds__(256) void attn_colsum_k(AttnArgs a, float* colsum) {
+  __shared__ float sums[64];
+  const int j0 = blockIdx.x * 64;
+  const int chain = blockIdx.y, b = chain / a.Hkv, hkv = chain % a.Hkv;
+  const int n = a.seg_first + blockIdx.z;
+  const int64_t start = (int64_t)n * a.B;
+  const int Bn = (int)(a.L - start < a.B ? a.L - start : a.B);
+  const int m = n <= a.n_fill ? a.len0 + n * a.B : a.M;
+  if (j0 >= m) return;
+  const uint16_t* cache_k =
+      n <= a.n_fill ? (const uint16_t*)a.cache_k + (int64_t)chain * a.M * kD
+                    : (const uint16_t*)a.hist_k + (int64_t)(n - a.n_fill - 1) * a.hist_stride + (int64_t)chain * a.M * kD;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
+  if (tid < 64) sums[tid] = 0.f;
+  __syncthreads();
+
+  // keys j0 + 32 kt + l31, channels 16 ks + 8 lh ..: rows of S^T
+  bf16x8 kf[2][8];
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const int j = j0 + kt * 32 + l31;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      const u32x4 v = j < m ? *(const u32x4*)(cache_k + (int64_t)j * kD + ks * 16 + lh * 8) : z;
+      kf[kt][ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  const float c = a.scale * kLog2e;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 part[2] = {zero, zero};          // per lane: sums over its queries, keys as in the accumulator rows
+  const int R = a.group * Bn;             // query rows of the group, head-major
+  for (int r0 = w * 32; r0 < R; r0 += 4 * 32) {
+    const int rr = r0 + l31;
+    const bool live = rr < R;
+    const int gi = live ? rr / Bn : 0, r = live ? rr % Bn : 0, hq = hkv * a.group + gi;
+    const uint16_t* qrow = (const uint16_t*)a.q.p + b * a.q.sb + hq * a.q.sh + (start + r) * a.q.st;
+    const float* st = a.stats + (((int64_t)b * a.Hq + hq) * a.L + start + r) * 2;
+    const float mc = live ? st[0] : 0.f, inv = live ? st[1] : 0.f;
+    f32x16 sacc[2];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      const u32x4 qv = live ? *(const u32x4*)(qrow + ks * 16 + lh * 8) : z;
+      const bf16x8 qf = __builtin_bit_cast(bf16x8, qv);
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ks], qf, ks == 0 ? zero : sacc[kt], 0, 0, 0);
+    }
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) part[kt][i] += __builtin_amdgcn_exp2f(fmaf(sacc[kt][i], c, -mc)) * inv;
+  }
+  // sum over the 32 queries held by the lanes of a half wave, then over the waves
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float v = part[kt][i];
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+      if (l31 == 0) atomicAdd(&sums[kt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)], v);
+    }
+  __syncthreads();
+  if (tid < 64 && j0 + tid < m) atomicAdd(colsum + (int64_t)chain * a.M + j0 + tid, sums[tid]);
 }
 
 hipError_t launch_tiles(const AttnArgs& a_in, hipStream_t s) {
@@ -419,6 +496,13 @@ bool attn_mfma_supports(int dtype, int d, const char** why) {
   if (dtype != LOCOCO_BF16) { *why = "the MFMA kernels take bf16 storage only"; return false; }
   if (d != kD) { *why = "the MFMA kernels take head_dim = 128 only"; return false; }
   return true;
+}
+
+hipError_t launch_attn_colsum_mfma(const AttnArgs& a, float* colsum, hipStream_t s) {
+  if (!a.stats || !colsum) return hipErrorInvalidValue;
+  if (a.n_seg <= 0) return hipSuccess;
+  hipLaunchKernelGGL(attn_colsum_k, dim3((a.M + 63) / 64, a.batch * a.Hkv, a.n_seg), dim3(256), 0, s, a, colsum);
+  return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {

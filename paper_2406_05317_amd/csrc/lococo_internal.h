@@ -78,6 +78,10 @@ struct AttnArgs {
   int32_t batch, Hq, Hkv, group;
   int32_t qtiles;          // filled in by the launcher
   float scale;
+  // Row statistics of the softmax, written when not null: pairs (m, 1 / l) per query row,
+  // [batch, Hq, L] with the row index counted like the token index of the q view, such that the
+  // probability of a key with raw score s is exp2(s * scale * log2(e) - m) / l.
+  float* stats;
 };
 
 // Arguments of the backward pass of one block step (backward_generic.hip).  `st` describes the
@@ -154,6 +158,10 @@ hipError_t launch_compress_scan(const ScanArgs& a, const void* wp, int banks, in
 // ---- attention on MFMA (attn_mfma.hip)
 bool attn_mfma_supports(int dtype, int d, const char** why);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
+// Adds to colsum [chains, M], for every block of `a` and every live cache slot, the probabilities
+// the block's queries (all heads of the group) put on it; reads the statistics the attention
+// launch with the same arguments left in a.stats.
+hipError_t launch_attn_colsum_mfma(const AttnArgs& a, float* colsum, hipStream_t s);
 
 // ---- attention of one new token per sequence (attn_decode.hip): bf16, head_dim 128, Bn = 1
 bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum);

@@ -1,6 +1,7 @@
 """GPU parity of the accumulated attention scores per cache slot (what a heavy-hitter policy ranks
-slots by) against the CPU oracle: prefill blocks on the shape-agnostic attention kernel, single
-tokens on the generation-stage kernel, and the scan's outputs unchanged by asking for them."""
+slots by) against the CPU oracle: prefill blocks on the shape-agnostic attention kernel and on the
+MFMA one (row statistics + a column-sum pass), single tokens on the generation-stage kernel, and
+the scan's outputs unchanged by asking for them."""
 import numpy as np
 import pytest
 import torch
@@ -42,6 +43,10 @@ def _gpu_scan(w, q, k, v, cw, cb, impl, track=True):
     dict(dtype="f32", batch=2, n_q_heads=4, n_kv_heads=2, head_dim=32, L=100, B=16, M=40, conv_width=5),
     dict(dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=2, head_dim=64, L=160, B=32, M=64, conv_width=7),
     dict(dtype="bf16", batch=1, n_q_heads=8, n_kv_heads=4, head_dim=128, L=500, B=96, M=128, conv_width=15, impl=MFMA),
+    # several 64-slot tiles, the last one ragged (M = 160); four query heads per kv head; ragged last block
+    dict(dtype="bf16", batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, L=700, B=200, M=160, conv_width=15, impl=MFMA),
+    # blocks shorter than a 32-row chunk
+    dict(dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=2, head_dim=128, L=150, B=20, M=64, conv_width=15, impl=MFMA),
 ])
 def test_scan_accumulates_attention_per_slot(case):
     case = dict(case)
@@ -60,9 +65,37 @@ def test_scan_accumulates_attention_per_slot(case):
     assert float(cache.attn_colsum.sum()) < (w.L - w.B) * w.n_q_heads * w.batch
 
 
+def test_tracked_steps_one_by_one_on_the_mfma_kernels():
+    """lococo_segment_step block by block with a step workspace (no history): the MFMA attention
+    leaves its row statistics there and the column-sum pass follows; same sums as the oracle."""
+    from paper_2406_05317_amd import binding as lb
+    w = inputs.Workload(name="colsum", seed=15, dtype="bf16", batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128,
+                        L=600, B=128, M=192, conv_width=15)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    want_cs = np.zeros((w.batch, w.n_kv_heads, w.M))
+    want = _oracle(w, q, k, v, cw, cb, w.B, None, want_cs)
+    cfg = lb.config_for(w, impl=MFMA)
+    qd, kd, vd, cwd = (t.cuda() for t in (q, k, v, cw))
+    cbd = None if cb is None else cb.cuda()
+    od = torch.full_like(qd, float("nan"))
+    cache = lb.Cache(cfg)
+    cache.track_attention()
+    ws = lb.workspace(cfg, w.B, w.B, False)
+    lb.lococo_timing_begin()
+    for s0 in range(0, w.L, w.B):
+        e = min(w.L, s0 + w.B)
+        lb.lococo_segment_step(cfg, qd[:, :, s0:e], kd[:, :, s0:e], vd[:, :, s0:e], od[:, :, s0:e], cwd, cbd, cache, ws)
+    torch.cuda.synchronize()
+    ran = lb.lococo_timing_end()
+    assert "attn_colsum" in ran and "attn_generic" not in ran, ran
+    compare_scan(w, (od.cpu(), cache.k.cpu(), cache.v.cpu(), cache.len, cache.cur), want, what="tracked steps")
+    assert_close(cache.attn_colsum.cpu().double().numpy(), want_cs, 2e-2, "attention column sums")
+
+
 def test_tracking_leaves_the_scan_outputs_as_they_were():
-    """The MFMA scan without tracking (batched attention schedule) and with it (attention on the
-    shape-agnostic kernel, step by step) agree to the contract tolerance."""
+    """The MFMA scan without tracking and with it (the attention kernel also writes its row
+    statistics, a column-sum pass follows) give the same outputs."""
     w = inputs.Workload(name="colsum", seed=12, dtype="bf16", batch=1, n_q_heads=4, n_kv_heads=4, head_dim=128,
                         L=512, B=128, M=128, conv_width=15)
     q, k, v = inputs.qkv(w)
