@@ -238,10 +238,11 @@ lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo
  *     acc  d_conv_w (laid out like conv_w, with w_head_stride) and d_conv_b (like conv_b, may be
  *          NULL) are ADDED to, so one buffer collects the whole scan; untouched by a fill step.
  *   workspace: lococo_backward_workspace_bytes(cfg, B, cache_before->len) bytes, 256-byte aligned.
- * Any shape; fp32 vector arithmetic, except that with bf16 storage, head_dim 128, keys-only
- * filters and cfg->impl != LOCOCO_IMPL_GENERIC the three convolution contractions (Eq. 5 and its
- * two gradients) run on the matrix cores, the fp32 logit gradient entering as the sum of two
- * bf16 numbers (about 16 bits kept; the workspace is larger then).  Filter gradients are summed
+ * Any shape; fp32 vector arithmetic, except that with bf16 storage and cfg->impl !=
+ * LOCOCO_IMPL_GENERIC the contractions run on the matrix cores, every fp32 operand entering as
+ * the sum of two bf16 numbers (about 16 bits kept): the plain ones when block length + live
+ * slots is a multiple of 4, the three convolution ones (Eq. 5 and its two gradients) with
+ * head_dim 128 and keys-only filters (the workspace is larger then).  Filter gradients are summed
  * with floating-point atomics, so their last bits depend on the order. */
 lococo_status lococo_backward_workspace_bytes(const lococo_config* cfg, int32_t B, int32_t len, size_t* out);
 lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,

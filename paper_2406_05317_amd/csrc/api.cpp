@@ -794,6 +794,7 @@ lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococ
   g.ws_dw = (float*)(ws + l.dw);
   g.ws_mfma = compress && bwd_on_mfma(cfg) ? ws + l.mf : nullptr;
   g.banks = filter_banks(cfg);
+  g.gemms_mfma = cfg->impl != LOCOCO_IMPL_GENERIC && cfg->dtype == LOCOCO_BF16 ? 1 : 0;
   if (compress) {
     // recompute Eq. 5 and Eq. 6 of the forward step: raw logits and normalised rows
     if (g.ws_mfma) {

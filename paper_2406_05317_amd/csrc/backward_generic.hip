@@ -612,25 +612,41 @@ template <typename T>
 hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
   const StepArgs& a = g.st;
   const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv;
-  hipLaunchKernelGGL(bwd_attn_scores_k<T>, dim3((Tn + kAT - 1) / kAT, (a.Bn + kAT - 1) / kAT, a.batch * a.Hq),
-                     dim3(kThreads), 0, s, g);
+  // with g.ws_mfma set every contraction below has a matrix-core form (backward_mfma.hip)
+  const bool conv_mfma = g.ws_mfma != nullptr;
+  const bool mfma = g.gemms_mfma && bwd_gemms_mfma_fit(g);
+  hipError_t e = hipSuccess;
+  if (mfma) e = launch_bwd_attn_scores_mfma(g, s);
+  else
+    hipLaunchKernelGGL(bwd_attn_scores_k<T>, dim3((Tn + kAT - 1) / kAT, (a.Bn + kAT - 1) / kAT, a.batch * a.Hq),
+                       dim3(kThreads), 0, s, g);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bwd_attn_rows_k, dim3(a.Bn, a.Hq, a.batch), dim3(kThreads), 0, s, g);
-  hipLaunchKernelGGL(bwd_attn_dq_k<T>, dim3((a.d + kAT - 1) / kAT, (a.Bn + kAT - 1) / kAT, a.batch * a.Hq),
-                     dim3(kThreads), 0, s, g);
-  hipLaunchKernelGGL(bwd_attn_cols_k<T>, dim3((a.d + kAT - 1) / kAT, (Tn + kAT - 1) / kAT, chains), dim3(kThreads),
-                     0, s, g);
+  if (mfma) {
+    if ((e = launch_bwd_attn_grads_mfma(g, s)) != hipSuccess) return e;
+  } else {
+    hipLaunchKernelGGL(bwd_attn_dq_k<T>, dim3((a.d + kAT - 1) / kAT, (a.Bn + kAT - 1) / kAT, a.batch * a.Hq),
+                       dim3(kThreads), 0, s, g);
+    hipLaunchKernelGGL(bwd_attn_cols_k<T>, dim3((a.d + kAT - 1) / kAT, (Tn + kAT - 1) / kAT, chains),
+                       dim3(kThreads), 0, s, g);
+  }
   if (a.m < a.M) hipLaunchKernelGGL(bwd_zero_dead_rows_k, dim3(64, chains), dim3(kThreads), 0, s, g);
   if (!compress) {
     hipLaunchKernelGGL(bwd_fill_k, dim3(64, chains), dim3(kThreads), 0, s, g);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(bwd_mix_dw_k<T>, dim3((Tn + kMT - 1) / kMT, (a.M + kMT - 1) / kMT, chains), dim3(kThreads), 0, s, g);
+  if (mfma) e = launch_bwd_mix_dw_mfma(g, s);
+  else
+    hipLaunchKernelGGL(bwd_mix_dw_k<T>, dim3((Tn + kMT - 1) / kMT, (a.M + kMT - 1) / kMT, chains), dim3(kThreads), 0,
+                       s, g);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bwd_mix_rows_k, dim3(a.M, chains), dim3(kThreads), 0, s, g);
-  hipLaunchKernelGGL(bwd_mix_cols_k, dim3((2 * a.d + kMT - 1) / kMT, (Tn + kMT - 1) / kMT, chains), dim3(kThreads), 0, s, g);
-  if (g.ws_mfma) {                      // the two Eq. 5 gradients on the matrix cores
-    hipError_t e = hipGetLastError();
-    return e != hipSuccess ? e : launch_bwd_conv_mfma(g, g.banks, g.ws_mfma, s);
-  }
+  if (mfma) e = launch_bwd_mix_cols_mfma(g, s);
+  else
+    hipLaunchKernelGGL(bwd_mix_cols_k, dim3((2 * a.d + kMT - 1) / kMT, (Tn + kMT - 1) / kMT, chains), dim3(kThreads), 0,
+                       s, g);
+  if (e != hipSuccess) return e;
+  if (conv_mfma) return launch_bwd_conv_mfma(g, g.banks, g.ws_mfma, s);   // the two Eq. 5 gradients
   const int C = a.conv_in ? 2 * a.d : a.d;
   hipLaunchKernelGGL(bwd_conv_x_k<T>, dim3((Tn + kTI - 1) / kTI, (C + kTI - 1) / kTI, chains), dim3(kThreads), 0, s, g);
   hipLaunchKernelGGL(bwd_conv_w_k<T>,

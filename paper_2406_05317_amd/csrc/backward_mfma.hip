@@ -32,6 +32,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int kThreads = 256;
 constexpr int kD = 128;          // channels
@@ -382,6 +384,265 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_k(BwdArgs g, const ui
     }
 }
 
+
+// ---- the seven plain contractions of the pass (attention: scores, dP, dq, dYk, dYv; Eq. 4: dw and
+// the gradient of [K | V]) as one batched GEMM kernel, C[i, j] = sum_k A(i, k) B(j, k).
+//
+// An operand is a functor over a tensor in memory:
+//   load4(v, z, r, c): four consecutive elements (memory row r, offsets c .. c + 3) of batch entry
+//                      z as floats, zero outside the tensor;
+//   kMajor:  false = memory rows are operand rows and the contraction runs along them (staged as
+//            128 rows x 64 k, fragments by 16-byte reads); true = memory rows are contraction
+//            steps (staged as 64 k x 128 rows, fragments by transposing reads);
+//   kParts:  1 = the values are bf16 numbers; 2 = fp32 values, staged as hi + lo (the product of
+//            two such operands takes three MFMAs: hi hi, hi lo, lo hi).
+// The output functor decides where C[i, j] goes (store) and may skip whole tiles.
+constexpr int kPartBytes = kTile * kRow64;       // 18 432 >= kChunk * kRow
+static_assert(kChunk * kRow <= kPartBytes, "a staged operand part fits its LDS area either way round");
+
+template <class OpA, class OpB, class Out>
+__global__ __launch_bounds__(kThreads, 2) void bwd_gemm_k(OpA A, OpB B, Out out, int I, int J, int K) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* As = smem;
+  unsigned char* Bs = smem + OpA::kParts * kPartBytes;
+  const int j0 = blockIdx.x * kTile, i0 = blockIdx.y * kTile, z = blockIdx.z;
+  if (out.skip(z, i0, j0)) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
+
+  float ra[8][4], rb[8][4];
+  auto load = [&](int k0) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int gidx = tid + n * kThreads;
+      if (OpA::kMajor) A.load4(ra[n], z, k0 + (gidx >> 5), i0 + (gidx & 31) * 4);
+      else A.load4(ra[n], z, i0 + (gidx >> 4), k0 + (gidx & 15) * 4);
+      if (OpB::kMajor) B.load4(rb[n], z, k0 + (gidx >> 5), j0 + (gidx & 31) * 4);
+      else B.load4(rb[n], z, j0 + (gidx >> 4), k0 + (gidx & 15) * 4);
+    }
+  };
+  // four values -> 8 bytes of bf16 (round to nearest even), and the rounding errors likewise
+  auto put = [&](unsigned char* base, int parts, bool kmajor, int gidx, const float (&v)[4]) {
+    unsigned char* at = kmajor ? base + (gidx >> 5) * kRow + (gidx & 31) * 8 : base + (gidx >> 4) * kRow64 + (gidx & 15) * 8;
+    const f32x2 x0 = {v[0], v[1]}, x1 = {v[2], v[3]};
+    const bf16x2 h0 = __builtin_convertvector(x0, bf16x2), h1 = __builtin_convertvector(x1, bf16x2);
+    const u32x2 vh = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1)};
+    *(u32x2*)at = vh;
+    if (parts == 2) {
+      const f32x2 e0 = x0 - __builtin_convertvector(h0, f32x2), e1 = x1 - __builtin_convertvector(h1, f32x2);
+      const bf16x2 l0 = __builtin_convertvector(e0, bf16x2), l1 = __builtin_convertvector(e1, bf16x2);
+      const u32x2 vl = {__builtin_bit_cast(uint32_t, l0), __builtin_bit_cast(uint32_t, l1)};
+      *(u32x2*)(at + kPartBytes) = vl;
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      put(As, OpA::kParts, OpA::kMajor, tid + n * kThreads, ra[n]);
+      put(Bs, OpB::kParts, OpB::kMajor, tid + n * kThreads, rb[n]);
+    }
+  };
+  f32x16 acc[2][2];
+  zero_acc(acc);
+  const int tro = tr_lane_offset(l, kRow);
+  load(0);
+  for (int k0 = 0; k0 < K; k0 += kChunk) {
+    __syncthreads();
+    stage();
+    if (k0 + kChunk < K) load(k0 + kChunk);
+    __syncthreads();
+#pragma unroll
+    for (int kc = 0; kc < kChunk / 16; ++kc) {
+      bf16x8 fa[OpA::kParts][2], fb[OpB::kParts][2];
+#pragma unroll
+      for (int p = 0; p < OpA::kParts; ++p)
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+          fa[p][x] = OpA::kMajor
+                         ? frag_tr(As + p * kPartBytes + tro + kc * 16 * kRow + (wy * 64 + x * 32) * 2, kRow)
+                         : frag(As + p * kPartBytes + (wy * 64 + x * 32 + l31) * kRow64 + (kc * 16 + lh * 8) * 2);
+#pragma unroll
+      for (int p = 0; p < OpB::kParts; ++p)
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+          fb[p][x] = OpB::kMajor
+                         ? frag_tr(Bs + p * kPartBytes + tro + kc * 16 * kRow + (wx * 64 + x * 32) * 2, kRow)
+                         : frag(Bs + p * kPartBytes + (wx * 64 + x * 32 + l31) * kRow64 + (kc * 16 + lh * 8) * 2);
+#pragma unroll
+      for (int pa = 0; pa < OpA::kParts; ++pa)
+#pragma unroll
+        for (int pb = 0; pb < OpB::kParts; ++pb) {
+          if (pa + pb == 2) continue;     // lo x lo: below the 16 bits kept
+#pragma unroll
+          for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int y = 0; y < 2; ++y)
+              acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[pa][x], fb[pb][y], acc[x][y], 0, 0, 0);
+        }
+    }
+  }
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int i16 = 0; i16 < 16; ++i16) {
+      const int i = i0 + wy * 64 + x * 32 + (i16 >> 2) * 8 + lh * 4 + (i16 & 3);
+      if (i >= I) continue;
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        const int j = j0 + wx * 64 + y * 32 + l31;
+        if (j < J) out.store(z, i, j, acc[x][y][i16]);
+      }
+    }
+}
+
+// -- operands.  `grouped`: z is a chain and the memory row runs over the rows of all query heads
+// of its group, head-major; otherwise z is (batch entry, query head).  Every width is a multiple
+// of 4 and every base 16-byte aligned (the launcher checks), so a group of four is inside or
+// outside as a whole; the loads are branch-free: an outside group reads element 0 and is zeroed.
+struct Dims { int Bn, Tn, d, M, m, Hq, Hkv, group; };
+__device__ __forceinline__ void head_row(const Dims& s, bool grouped, int z, int r, int& b, int& hq, int& rr) {
+  if (grouped) {
+    b = z / s.Hkv;
+    hq = (z % s.Hkv) * s.group + r / s.Bn;
+    rr = r % s.Bn;
+  } else {
+    b = z / s.Hq;
+    hq = z % s.Hq;
+    rr = r;
+  }
+}
+__device__ __forceinline__ void from_bf16x4(float (&v)[4], const uint16_t* p, bool ok) {
+  u32x2 u = *(const u32x2*)p;
+  if (!ok) u = u32x2{0u, 0u};
+  v[0] = __uint_as_float(u[0] << 16);
+  v[1] = __uint_as_float(u[0] & 0xffff0000u);
+  v[2] = __uint_as_float(u[1] << 16);
+  v[3] = __uint_as_float(u[1] & 0xffff0000u);
+}
+__device__ __forceinline__ void from_f32x4(float (&v)[4], const float* p, bool ok) {
+  const float4 q = *(const float4*)p;
+  v[0] = ok ? q.x : 0.f; v[1] = ok ? q.y : 0.f; v[2] = ok ? q.z : 0.f; v[3] = ok ? q.w : 0.f;
+}
+__device__ __forceinline__ bool is_protected(const uint32_t* protect, int64_t stride, int z, int r, int m) {
+  if (!protect) return false;           // uniform
+  const int rc = r < m ? r : 0;
+  return r < m && ((protect[(int64_t)z * stride + (rc >> 5)] >> (rc & 31)) & 1u);
+}
+
+template <bool KMAJOR>
+struct OpQ {               // query rows, bf16
+  static constexpr bool kMajor = KMAJOR;
+  static constexpr int kParts = 1;
+  Dims s; View q; bool grouped;
+  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+    const bool ok = r < (grouped ? s.group * s.Bn : s.Bn) && c < s.d;
+    int b, hq, rr;
+    head_row(s, grouped, z, ok ? r : 0, b, hq, rr);
+    from_bf16x4(v, (const uint16_t*)q.p + b * q.sb + hq * q.sh + (int64_t)rr * q.st + (ok ? c : 0), ok);
+  }
+};
+template <bool KMAJOR>
+struct OpRowsF32 {         // fp32 [batch, Hq, Bn, width] rows: d_o (width d), ws_p / ws_ds (width Tn)
+  static constexpr bool kMajor = KMAJOR;
+  static constexpr int kParts = 2;
+  Dims s; const float* p; int width; bool grouped;
+  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+    const bool ok = r < (grouped ? s.group * s.Bn : s.Bn) && c < width;
+    int b, hq, rr;
+    head_row(s, grouped, z, ok ? r : 0, b, hq, rr);
+    from_f32x4(v, p + (((int64_t)b * s.Hq + hq) * s.Bn + rr) * width + (ok ? c : 0), ok);
+  }
+};
+template <bool KMAJOR, int WHICH>     // WHICH: 0 keys, 1 values, 2 [keys | values] (width 2 d)
+struct OpY {               // rows of [cache(0:m) ; block], bf16
+  static constexpr bool kMajor = KMAJOR;
+  static constexpr int kParts = 1;
+  Dims s; const void* cache_k; const void* cache_v; View k, v; bool per_qhead;
+  __device__ void load4(float (&out)[4], int z, int r, int c) const {
+    const bool ok = r < s.Tn && c < (WHICH == 2 ? 2 * s.d : s.d);
+    const int r2 = ok ? r : 0, c2 = ok ? c : 0;
+    int b, hkv;
+    if (per_qhead) { b = z / s.Hq; hkv = (z % s.Hq) / s.group; }
+    else { b = z / s.Hkv; hkv = z % s.Hkv; }
+    const bool val = WHICH == 1 || (WHICH == 2 && c2 >= s.d);
+    const int col = WHICH == 2 && c2 >= s.d ? c2 - s.d : c2;
+    const View& blk = val ? v : k;
+    const bool in_cache = r2 < s.m;
+    const uint16_t* crow =
+        (const uint16_t*)(val ? cache_v : cache_k) + ((int64_t)(b * s.Hkv + hkv) * s.M + (in_cache ? r2 : 0)) * s.d;
+    const uint16_t* brow =
+        (const uint16_t*)blk.p + b * blk.sb + hkv * blk.sh + (int64_t)(in_cache ? 0 : r2 - s.m) * blk.st;
+    from_bf16x4(out, (in_cache ? crow : brow) + col, ok);
+  }
+};
+template <bool KMAJOR>
+struct OpG {               // gradient of the new cache, fp32 rows [g_k | g_v] of width 2 d
+  static constexpr bool kMajor = KMAJOR;
+  static constexpr int kParts = 2;
+  Dims s; const float* gk; const float* gv; const uint32_t* protect; int64_t protect_stride; bool mask;
+  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+    const bool in = r < s.M && c < 2 * s.d;
+    const int r2 = in ? r : 0, c2 = in ? c : 0;
+    const bool ok = in && !(mask && is_protected(protect, protect_stride, z, r2, s.m));
+    const float* row = (c2 < s.d ? gk : gv) + ((int64_t)z * s.M + r2) * s.d + (c2 < s.d ? c2 : c2 - s.d);
+    from_f32x4(v, row, ok);
+  }
+};
+struct OpWn {              // normalised mixing rows, fp32 [chain, M, Tn]; protected slots mix nothing
+  static constexpr bool kMajor = true;
+  static constexpr int kParts = 2;
+  Dims s; const float* w; const uint32_t* protect; int64_t protect_stride;
+  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+    const bool in = r < s.M && c < s.Tn;
+    const int r2 = in ? r : 0, c2 = in ? c : 0;
+    const bool ok = in && !is_protected(protect, protect_stride, z, r2, s.m);
+    from_f32x4(v, w + ((int64_t)z * s.M + r2) * s.Tn + c2, ok);
+  }
+};
+
+// -- outputs
+struct OutRows {           // fp32 [batch, Hq, Bn, Tn] rows, scaled; tiles wholly after their queries are skipped
+  Dims s; float* p; float scale;
+  __device__ bool skip(int, int i0, int j0) const { return j0 > s.m + i0 + kTile - 1; }
+  __device__ void store(int z, int i, int j, float v) const { p[((int64_t)z * s.Bn + i) * s.Tn + j] = v * scale; }
+};
+struct OutPlain {          // fp32 [z, rows, width]
+  float* p; int rows, width;
+  __device__ bool skip(int, int, int) const { return false; }
+  __device__ void store(int z, int i, int j, float v) const { p[((int64_t)z * rows + i) * width + j] = v; }
+};
+template <bool ADD>
+struct OutGrad {           // gradient rows of [cache ; block]: i = position, j = column of K (or of [K | V])
+  Dims s; float* d_cache_k; float* d_blk_k; float* d_cache_v; float* d_blk_v; int which;   // 0 K, 1 V, 2 [K | V]
+  __device__ bool skip(int, int, int) const { return false; }
+  __device__ void store(int z, int i, int j, float v) const {
+    const bool val = which == 1 || (which == 2 && j >= s.d);
+    const int col = which == 2 && j >= s.d ? j - s.d : j;
+    float* dc = val ? d_cache_v : d_cache_k;
+    float* db = val ? d_blk_v : d_blk_k;
+    float* at = (i < s.m ? dc + ((int64_t)z * s.M + i) * s.d : db + ((int64_t)z * s.Bn + (i - s.m)) * s.d) + col;
+    if (ADD) *at += v;
+    else *at = v;
+  }
+};
+
+template <class OpA, class OpB, class Out>
+hipError_t launch_gemm(const OpA& A, const OpB& B, const Out& out, int I, int J, int K, int Z, hipStream_t s) {
+  const int lds = (OpA::kParts + OpB::kParts) * kPartBytes;
+  static bool attr_set = false;   // per instantiation; benign race
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_gemm_k<OpA, OpB, Out>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (I <= 0 || J <= 0 || Z <= 0) return hipSuccess;
+  hipLaunchKernelGGL((bwd_gemm_k<OpA, OpB, Out>), dim3((J + kTile - 1) / kTile, (I + kTile - 1) / kTile, Z),
+                     dim3(kThreads), lds, s, A, B, out, I, J, K);
+  return hipGetLastError();
+}
+
+Dims dims_of(const StepArgs& a) { return Dims{a.Bn, a.m + a.Bn, a.d, a.M, a.m, a.Hq, a.Hkv, a.group}; }
+
 __global__ void bwd_zero_k(float* p, int64_t n) {
   for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
     p[e] = 0.f;
@@ -444,6 +705,65 @@ hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logi
   hipLaunchKernelGGL(bwd_logits_mfma_k, dim3((Tn + kTile - 1) / kTile, (a.M + kTile - 1) / kTile, a.batch * a.Hkv),
                      dim3(kThreads), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
+}
+
+
+// The plain contractions take whole groups of four: every row width (d, 2 d, T) a multiple of 4
+// and every fp32 array 16-byte aligned.  Otherwise the caller keeps the fp32 vector kernels.
+bool bwd_gemms_mfma_fit(const BwdArgs& g) {
+  const StepArgs& a = g.st;
+  if ((a.m + a.Bn) % 4 || a.d % 4) return false;
+  for (const void* p : {(const void*)g.d_o, (const void*)g.d_new_k, (const void*)g.d_new_v, (const void*)g.ws_p,
+                        (const void*)g.ws_ds, (const void*)g.ws_n})
+    if ((uintptr_t)p & 15) return false;
+  return true;
+}
+
+// S = scale q Yk^T into ws_p and dP = dO Yv^T into ws_ds (the row kernel turns them into P and dS)
+hipError_t launch_bwd_attn_scores_mfma(const BwdArgs& g, hipStream_t s) {
+  const StepArgs& a = g.st;
+  const Dims dm = dims_of(a);
+  const int Z = a.batch * a.Hq;
+  hipError_t e = launch_gemm(OpQ<false>{dm, a.q, false}, OpY<false, 0>{dm, a.cache_k, a.cache_v, a.k, a.v, true},
+                             OutRows{dm, g.ws_p, a.scale}, a.Bn, dm.Tn, a.d, Z, s);
+  if (e != hipSuccess) return e;
+  return launch_gemm(OpRowsF32<false>{dm, g.d_o, a.d, false}, OpY<false, 1>{dm, a.cache_k, a.cache_v, a.k, a.v, true},
+                     OutRows{dm, g.ws_ds, 1.0f}, a.Bn, dm.Tn, a.d, Z, s);
+}
+
+// dq = dS Yk; dYk = dS^T q and dYv = P^T dO over the heads of a group (assigned: first contributions)
+hipError_t launch_bwd_attn_grads_mfma(const BwdArgs& g, hipStream_t s) {
+  const StepArgs& a = g.st;
+  const Dims dm = dims_of(a);
+  const int chains = a.batch * a.Hkv;
+  hipError_t e = launch_gemm(OpRowsF32<false>{dm, g.ws_ds, dm.Tn, false},
+                             OpY<true, 0>{dm, a.cache_k, a.cache_v, a.k, a.v, true},
+                             OutPlain{g.d_q, a.Bn, a.d}, a.Bn, a.d, dm.Tn, a.batch * a.Hq, s);
+  if (e != hipSuccess) return e;
+  e = launch_gemm(OpRowsF32<true>{dm, g.ws_ds, dm.Tn, true}, OpQ<true>{dm, a.q, true},
+                  OutGrad<false>{dm, g.d_cache_k, g.d_k, g.d_cache_v, g.d_v, 0}, dm.Tn, a.d, a.group * a.Bn, chains, s);
+  if (e != hipSuccess) return e;
+  return launch_gemm(OpRowsF32<true>{dm, g.ws_p, dm.Tn, true}, OpRowsF32<true>{dm, g.d_o, a.d, true},
+                     OutGrad<false>{dm, g.d_cache_k, g.d_k, g.d_cache_v, g.d_v, 1}, dm.Tn, a.d, a.group * a.Bn, chains, s);
+}
+
+// dw[i, j] = g_k[i] . Yk[j] + g_v[i] . Yv[j] into ws_dw
+hipError_t launch_bwd_mix_dw_mfma(const BwdArgs& g, hipStream_t s) {
+  const StepArgs& a = g.st;
+  const Dims dm = dims_of(a);
+  return launch_gemm(OpG<false>{dm, g.d_new_k, g.d_new_v, a.protect, a.protect_stride, false},
+                     OpY<false, 2>{dm, a.cache_k, a.cache_v, a.k, a.v, false}, OutPlain{g.ws_dw, a.M, dm.Tn}, a.M,
+                     dm.Tn, 2 * a.d, a.batch * a.Hkv, s);
+}
+
+// d[Yk | Yv][j] += sum over the unprotected slots of w[i, j] [g_k | g_v][i]
+hipError_t launch_bwd_mix_cols_mfma(const BwdArgs& g, hipStream_t s) {
+  const StepArgs& a = g.st;
+  const Dims dm = dims_of(a);
+  return launch_gemm(OpWn{dm, g.ws_n, a.protect, a.protect_stride},
+                     OpG<true>{dm, g.d_new_k, g.d_new_v, a.protect, a.protect_stride, true},
+                     OutGrad<true>{dm, g.d_cache_k, g.d_k, g.d_cache_v, g.d_v, 2}, dm.Tn, 2 * a.d, a.M,
+                     a.batch * a.Hkv, s);
 }
 
 hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream_t s) {

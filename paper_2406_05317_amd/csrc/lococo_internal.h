@@ -110,6 +110,7 @@ struct BwdArgs {
   float* ws_dw;
   void* ws_mfma;           // workspace of the MFMA form of the Eq. 5 contractions (see BwdMfmaLayout), or null
   int32_t banks;           // filter banks (1 = shared by the kv heads)
+  int32_t gemms_mfma;      // the plain contractions may take their MFMA form (bf16 storage; see bwd_gemms_mfma_fit)
 };
 hipError_t launch_step_backward_generic(int dtype, const BwdArgs& g, bool compress, hipStream_t s);
 
@@ -179,6 +180,13 @@ hipError_t launch_bwd_pack_filters(const StepArgs& a, int banks, void* wt, hipSt
 hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s);
 // dX into d_k / d_cache_k (added) and dWc into d_conv_w (added), from the logit gradient in g.ws_w
 hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream_t s);
+// the plain contractions of the pass (fp32 operands enter as two bf16 halves): same inputs,
+// outputs and workspace arrays as the fp32 kernels of backward_generic.hip they stand in for
+bool bwd_gemms_mfma_fit(const BwdArgs& g);                                 // widths multiples of 4, arrays 16-byte aligned
+hipError_t launch_bwd_attn_scores_mfma(const BwdArgs& g, hipStream_t s);   // ws_p = scale q Yk^T, ws_ds = dO Yv^T
+hipError_t launch_bwd_attn_grads_mfma(const BwdArgs& g, hipStream_t s);    // d_q; first contributions to dYk, dYv
+hipError_t launch_bwd_mix_dw_mfma(const BwdArgs& g, hipStream_t s);        // ws_dw
+hipError_t launch_bwd_mix_cols_mfma(const BwdArgs& g, hipStream_t s);      // Eq. 4 w.r.t. [K | V], added
 
 // ---- measurement aid (peaks.hip): sustained bf16 MFMA rate of a bare loop and bandwidth of a plain
 // copy inside `scratch` (device, overwritten); synchronises the stream

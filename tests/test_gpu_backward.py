@@ -57,6 +57,10 @@ CASES = [
          B=70, M=128, m=90, conv_width=21, norm=1, bias_sigma=0.5, impl=0),
     dict(name="mfma several tiles grouped heads", dtype="bf16", batch=3, n_q_heads=2, n_kv_heads=1, head_dim=128,
          B=256, M=256, m=256, conv_width=15, impl=0),                              # 4 position x 2 slot tiles
+    dict(name="mfma fill step", dtype="bf16", batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, B=24, M=96, m=40,
+         conv_width=15, impl=0),
+    dict(name="mfma head_dim 64 (plain contractions only)", dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=2,
+         head_dim=64, B=40, M=64, m=64, conv_width=7, bias_sigma=0.3, impl=0),
     dict(name="mfma width 3", dtype="bf16", batch=1, n_q_heads=1, n_kv_heads=1, head_dim=128, B=33, M=32, m=20,
          conv_width=3, impl=0),
 ]
