@@ -243,9 +243,11 @@ def main():
     ap.add_argument("--norm", type=int, default=-1, help="override the normalisation (0 softmax, 1 relu-sum)")
     ap.add_argument("--protect-sinks", type=int, default=0,
                     help="protect the first N cache slots (attention sinks kept beside the compressed memory)")
+    ap.add_argument("--track-attention", action="store_true",
+                    help="accumulate the attention each cache slot receives (lococo_cache.attn_colsum) during the scan")
     ap.add_argument("--backward", action="store_true",
                     help="instead of the scan, time the backward pass of ONE compress step of the workload's shape "
-                         "(shape-agnostic kernels)")
+                         "(--impl 1: shape-agnostic fp32 kernels only)")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the prefill scan, time the generation stage: --steps segment steps "
                          "with B = 1 on a full cache, for this many sequences at once (0 = off)")
@@ -285,6 +287,8 @@ def main():
     if args.protect_sinks:
         import numpy as np
         cache.set_protect(np.arange(w.M) < args.protect_sinks)
+    if args.track_attention:
+        cache.track_attention()
     ws = lb.workspace(cfg, w.L, w.B, not args.no_history, dev)
     plan = lb.lococo_plan(w.L, w.B, w.M)
     flops = scan_flops(w, plan)
@@ -339,7 +343,7 @@ def main():
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.L, "B": w.B,
                    "M": w.M, "conv_width": w.conv_width, "conv_channels": w.C,
                    "schedule": "step-by-step" if args.no_history else "batched-attention",
-                   "protected_slots": args.protect_sinks,
+                   "protected_slots": args.protect_sinks, "track_attention": bool(args.track_attention),
                    "impl": args.impl},
         "segment_step_tokens_per_s": w.batch * w.B / (ms_per_step * 1e-3 / len(plan)),
         "mfma_util_whole_path": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,

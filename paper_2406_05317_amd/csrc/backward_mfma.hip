@@ -16,6 +16,9 @@
 // row-shifted view of a staged tile.  Where the contraction runs down the rows of a row-major
 // tile the fragments come from transposing LDS reads.  The next tile is fetched into registers
 // while the current one is multiplied.
+//
+// The seven plain contractions of the pass (attention and Eq. 4) are instances of one batched GEMM
+// kernel of the same shape further down (bwd_gemm_k), their fp32 operands split the same way.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
