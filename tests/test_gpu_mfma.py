@@ -178,25 +178,32 @@ def test_chain_meeting_through_the_shared_l2_equals_the_device_scope_one(case, m
     dict(batch=5, n_q_heads=64, n_kv_heads=64, M=128, B=64, L=384, per_head_filters=True, bias_sigma=0.5),
     # grouped query heads, ragged last block, partly filled cache at the first compress step
     dict(batch=40, n_q_heads=8, n_kv_heads=4, M=64, B=48, L=300, tok_lognormal_sigma=0.5),
+    # width 21 and relu-sum (32-slot tiles only): 40 chains x 8 tiles on 256 compute units
+    dict(batch=5, n_q_heads=8, n_kv_heads=8, M=256, B=96, L=640, conv_width=21, norm=1, bias_sigma=0.5),
+    # protected slots, different ones in every chain, with several chains per workgroup, 64-slot tiles
+    dict(batch=24, n_q_heads=8, n_kv_heads=8, M=128, B=64, L=384, protect_share=0.1),
 ])
 def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
     """More (chain, slot tile) pairs than compute units: the one-launch scan gives every workgroup
     several chains of one slot tile.  Bit-identical to one launch per step, with either form of the
     chain meeting, and equal to the oracle."""
+    case = dict(case)
+    share = case.pop("protect_share", 0.0)
     w = _w(**case)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
-    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    protect = (np.random.default_rng(5).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
     monkeypatch.setenv("LOCOCO_CHAIN_SYNC", "device")
-    c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
     monkeypatch.delenv("LOCOCO_CHAIN_SYNC")
     monkeypatch.setenv("LOCOCO_SCAN_LAUNCHES", "steps")
-    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
     for other in (b, c):
         for x, y in zip(a[:3], other[:3]):
             assert torch.equal(x, y)
         assert a[3:] == other[3:]
-    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
     compare_scan(w, a, want, what="several chains per workgroup")
 
 
