@@ -437,19 +437,29 @@ __global__ __launch_bounds__(256) void attn_colsum_k(AttnArgs a, float* colsum) 
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 part[2] = {zero, zero};          // per lane: sums over its queries, keys as in the accumulator rows
   const int R = a.group * Bn;             // query rows of the group, head-major
-  for (int r0 = w * 32; r0 < R; r0 += 4 * 32) {
+  // The query fragments go from memory straight into MFMA operands; the next chunk's are fetched
+  // while the current chunk is multiplied and exponentiated.
+  u32x4 qv[8], qn[8];
+  float mc = 0.f, inv = 0.f, mcn = 0.f, invn = 0.f;
+  auto fetch = [&](int r0, u32x4 (&dst)[8], float& m_out, float& i_out) {
     const int rr = r0 + l31;
     const bool live = rr < R;
     const int gi = live ? rr / Bn : 0, r = live ? rr % Bn : 0, hq = hkv * a.group + gi;
     const uint16_t* qrow = (const uint16_t*)a.q.p + b * a.q.sb + hq * a.q.sh + (start + r) * a.q.st;
     const float* st = a.stats + (((int64_t)b * a.Hq + hq) * a.L + start + r) * 2;
-    const float mc = live ? st[0] : 0.f, inv = live ? st[1] : 0.f;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) dst[ks] = live ? *(const u32x4*)(qrow + ks * 16 + lh * 8) : z;
+    m_out = live ? st[0] : 0.f;
+    i_out = live ? st[1] : 0.f;             // a row past the end adds nothing
+  };
+  if (w * 32 < R) fetch(w * 32, qv, mc, inv);
+  for (int r0 = w * 32; r0 < R; r0 += 4 * 32) {
+    if (r0 + 4 * 32 < R) fetch(r0 + 4 * 32, qn, mcn, invn);
     f32x16 sacc[2];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      const u32x4 qv = live ? *(const u32x4*)(qrow + ks * 16 + lh * 8) : z;
-      const bf16x8 qf = __builtin_bit_cast(bf16x8, qv);
+      const bf16x8 qf = __builtin_bit_cast(bf16x8, qv[ks]);
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
         sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ks], qf, ks == 0 ? zero : sacc[kt], 0, 0, 0);
@@ -458,6 +468,10 @@ __global__ __launch_bounds__(256) void attn_colsum_k(AttnArgs a, float* colsum) 
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) part[kt][i] += __builtin_amdgcn_exp2f(fmaf(sacc[kt][i], c, -mc)) * inv;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qv[ks] = qn[ks];
+    mc = mcn;
+    inv = invn;
   }
   // sum over the 32 queries held by the lanes of a half wave, then over the waves
 #pragma unroll
