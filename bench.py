@@ -52,6 +52,7 @@ def scan_flops(w, plan):
 KERNEL_PARTS = {
     "attn_generic": ("attn",), "attn_mfma": ("attn",),
     "conv_logits_generic": ("conv",), "mix_generic": ("mix",),
+    "conv_logits_mfma": ("conv",), "mix_mfma": ("mix",),
     "compress_mfma": ("conv", "mix"),
 }
 KERNEL_BOUND = {  # roofline that bounds each kernel, peak, unit
@@ -241,6 +242,7 @@ def main():
                     help="step-by-step schedule instead of the batched-attention one")
     ap.add_argument("--conv-width", type=int, default=0, help="override the workload's filter width (e.g. 21)")
     ap.add_argument("--norm", type=int, default=-1, help="override the normalisation (0 softmax, 1 relu-sum)")
+    ap.add_argument("--conv-in", type=int, default=0, help="1: the filters read [K | V] (2 d channels) instead of the keys")
     ap.add_argument("--protect-sinks", type=int, default=0,
                     help="protect the first N cache slots (attention sinks kept beside the compressed memory)")
     ap.add_argument("--track-attention", action="store_true",
@@ -272,6 +274,8 @@ def main():
         w = w.replace(name=f"{w.name}-k{args.conv_width}", conv_width=args.conv_width)
     if args.norm >= 0:
         w = w.replace(name=f"{w.name}-norm{args.norm}", norm=args.norm)
+    if args.conv_in:
+        w = w.replace(name=f"{w.name}-kv", conv_in=1)
     dev = "cuda"
     torch.cuda.set_device(0)
     if args.decode_batch:

@@ -84,9 +84,13 @@ typedef struct lococo_config {
   int32_t conv_in;        /* 0: filters read keys only, C = d; 1: keys stacked on values along
                              channels, C = 2d (Eq. 5 as printed), K channels first               */
   int32_t norm;           /* 0: softmax over the positions; 1: relu(W)/(sum relu(W)+norm_eps)     */
-  int32_t impl;           /* LOCOCO_IMPL_*: AUTO picks the MFMA kernels when the shape allows,
-                             GENERIC forces the shape-agnostic kernels, MFMA fails with
-                             LOCOCO_EUNSUPPORTED when the shape does not allow them               */
+  int32_t impl;           /* LOCOCO_IMPL_*: AUTO picks the fused MFMA kernels when the shape allows
+                             (bf16, head_dim 128, keys-only filters of width 15 or 21, M a multiple
+                             of 32), separate MFMA kernels for Eq. 5 and Eq. 4 for other bf16 /
+                             head_dim 128 compressors (odd width <= 31, [K|V] filters, any M), else
+                             the shape-agnostic kernels; GENERIC forces the shape-agnostic kernels;
+                             MFMA asks for the fused kernels and fails with LOCOCO_EUNSUPPORTED
+                             when the shape does not allow them                                   */
   int32_t flags;          /* LOCOCO_FLAG_* bits, 0 by default                                     */
   int64_t w_head_stride;  /* elements between per-kv-head filter banks; 0 = one shared bank       */
   int64_t b_head_stride;  /* same for the bias                                                    */

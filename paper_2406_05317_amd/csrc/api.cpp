@@ -38,10 +38,12 @@ lococo_status hip_fail(hipError_t e, const char* what) {
 
 // ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
 enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC,
-                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_ATTN_DECODE, K_ATTN_COLSUM, K_COUNT };
+                K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_ATTN_DECODE, K_ATTN_COLSUM, K_CONV_MFMA, K_MIX_MFMA,
+                K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
                                            "normalise_generic", "mix_generic", "repack_filters",
-                                           "compress_mfma", "attn_mfma", "attn_decode", "attn_colsum"};
+                                           "compress_mfma", "attn_mfma", "attn_decode", "attn_colsum",
+                                           "conv_logits_mfma", "mix_mfma"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
@@ -158,15 +160,21 @@ lococo_status check_qkvo(const lococo_config* c, const lococo_qkvo* x, int64_t t
   return LOCOCO_OK;
 }
 
-enum Path { PATH_GENERIC = 0, PATH_MFMA = 1 };
+// PATH_MFMA: the fused compression kernel.  PATH_MFMA_UNFUSED: shapes it does not take (other filter
+// widths, [K | V] filters, M not a multiple of 32) with bf16 storage and head_dim 128: attention on
+// MFMA, Eq. 5 and Eq. 4 as two MFMA kernels around the shape-agnostic normalisation, the logits
+// passing through the workspace in fp32.
+enum Path { PATH_GENERIC = 0, PATH_MFMA = 1, PATH_MFMA_UNFUSED = 2 };
 
-// Which kernels take this shape.  *why is set when MFMA is refused.
+// Which kernels take this shape.  *why is set when the fused kernel is refused.
 Path choose_path(const lococo_config* c, int32_t B, const char** why) {
   (void)B;
-  if (!compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why))
-    return PATH_GENERIC;
+  const char* ignore = "";
   if (!attn_mfma_supports(c->dtype, c->head_dim, why)) return PATH_GENERIC;
-  return PATH_MFMA;
+  if (compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why)) return PATH_MFMA;
+  if (conv_logits_mfma_supports(c->dtype, c->head_dim, c->conv_width) && attn_mfma_supports(c->dtype, c->head_dim, &ignore))
+    return PATH_MFMA_UNFUSED;
+  return PATH_GENERIC;
 }
 
 int filter_banks(const lococo_config* c) { return c->w_head_stride ? c->n_kv_heads : 1; }
@@ -186,7 +194,7 @@ int cu_count() {
 lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
   const char* why = "";
   Path p = c->impl == LOCOCO_IMPL_GENERIC ? PATH_GENERIC : choose_path(c, B, &why);
-  if (c->impl == LOCOCO_IMPL_MFMA && p != PATH_MFMA)
+  if (c->impl == LOCOCO_IMPL_MFMA && p != PATH_MFMA)     // MFMA means the fused kernel, nothing less
     return fail(LOCOCO_EUNSUPPORTED, "impl = MFMA requested but %s", why);
   *out = p;
   return LOCOCO_OK;
@@ -205,11 +213,19 @@ size_t scan_sync_bytes(const lococo_config* c) {
 size_t stats_bytes(const lococo_config* c, int64_t rows) {
   return align_up((size_t)c->batch * c->n_q_heads * (size_t)rows * 2 * sizeof(float), 256);
 }
+// filters packed per tap for the unfused MFMA path
+size_t packed_ws_bytes(const lococo_config* c) {
+  return align_up(packed_filter_bytes(c->M, c->conv_width, c->conv_in, filter_banks(c)), 256);
+}
+size_t logits_bytes(const lococo_config* c, int32_t B) {
+  return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
+}
 // MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block];
-// generic path: the logits.
+// unfused MFMA path: [filters packed per tap][row statistics of one block][logits]; generic path: the logits.
 size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
   if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B);
-  return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
+  if (path == PATH_MFMA_UNFUSED) return packed_ws_bytes(c) + stats_bytes(c, B) + logits_bytes(c, B);
+  return logits_bytes(c, B);
 }
 
 // Bytes of one history slot pair member: one cache state [chains, M, d].
@@ -317,12 +333,12 @@ AttnArgs attn_args_one_block(const StepArgs& a) {
 // stats_bytes), or null; without it a block whose attention is to be accumulated per slot goes
 // to the shape-agnostic kernel.
 lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a, float* stats, hipStream_t s) {
-  if (path == PATH_MFMA && attn_decode_supports(c->dtype, c->head_dim, a.Bn, c->M, a.colsum != nullptr)) {
+  if (path != PATH_GENERIC && attn_decode_supports(c->dtype, c->head_dim, a.Bn, c->M, a.colsum != nullptr)) {
     KTimer t(K_ATTN_DECODE, s);          // one query row per head: a matrix-vector product
     HIP_TRY(launch_attn_decode(a, s), "attention launch");
     return LOCOCO_OK;
   }
-  if (path == PATH_MFMA && (!a.colsum || stats)) {
+  if (path != PATH_GENERIC && (!a.colsum || stats)) {
     AttnArgs t = attn_args_one_block(a);
     t.stats = a.colsum ? stats : nullptr;
     {
@@ -342,23 +358,25 @@ lococo_status enqueue_attn(const lococo_config* c, Path path, const StepArgs& a,
 
 // The statistics area of a step workspace, if the caller passed one that holds it.
 float* step_stats(const lococo_config* c, Path path, int32_t B, void* workspace, size_t ws_bytes) {
-  if (path != PATH_MFMA || !workspace || ((uintptr_t)workspace & 255) || ws_bytes < step_ws_bytes(c, path, B))
+  if (path == PATH_GENERIC || !workspace || ((uintptr_t)workspace & 255) || ws_bytes < step_ws_bytes(c, path, B))
     return nullptr;
-  return (float*)((char*)workspace + filter_ws_bytes(c) + scan_sync_bytes(c));
+  return (float*)((char*)workspace + (path == PATH_MFMA ? filter_ws_bytes(c) + scan_sync_bytes(c) : packed_ws_bytes(c)));
 }
 
 // Repack the filter bank into the workspace (MFMA path; once per call unless the caller says
 // the workspace already holds it).
-lococo_status enqueue_repack(const lococo_config* c, const StepArgs& a, void* ws, hipStream_t s) {
+lococo_status enqueue_repack(const lococo_config* c, Path path, const StepArgs& a, void* ws, hipStream_t s) {
   if (c->flags & LOCOCO_FLAG_FILTERS_PREPARED) return LOCOCO_OK;
   KTimer t(K_REPACK, s);
-  HIP_TRY(launch_repack_filters(a, ws, filter_banks(c), s), "filter repack launch");
+  if (path == PATH_MFMA) HIP_TRY(launch_repack_filters(a, ws, filter_banks(c), s), "filter repack launch");
+  else HIP_TRY(launch_bwd_pack_filters(a, filter_banks(c), ws, s), "filter packing launch");
   return LOCOCO_OK;
 }
 
 // Enqueue fill or compress of one block and update the host-side state.
+// `B`: the block length the workspace was laid out for (a.Bn may be a shorter last block).
 lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, lococo_cache* ca,
-                             void* ws, hipStream_t s) {
+                             void* ws, int32_t B, hipStream_t s) {
   if (a.m + a.Bn <= a.M) {
     a.new_k = ca->k[ca->cur];
     a.new_v = ca->v[ca->cur];
@@ -376,8 +394,12 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
     ca->len = a.M;
     return LOCOCO_OK;
   }
-  float* logits = (float*)ws;
-  {
+  const bool unfused = path == PATH_MFMA_UNFUSED;
+  float* logits = unfused ? (float*)((char*)ws + packed_ws_bytes(c) + stats_bytes(c, B)) : (float*)ws;
+  if (unfused) {
+    KTimer t(K_CONV_MFMA, s);
+    HIP_TRY(launch_bwd_logits_mfma(a, ws, logits, s), "conv launch");
+  } else {
     KTimer t(K_CONV_GENERIC, s);
     HIP_TRY(launch_conv_logits_generic(c->dtype, a, logits, s), "conv launch");
   }
@@ -386,7 +408,10 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
     KTimer t(K_NORM_GENERIC, s);
     HIP_TRY(launch_normalise_generic(a, logits, s), "normalise launch");
   }
-  {
+  if (unfused && mix_mfma_fits(a, logits)) {
+    KTimer t(K_MIX_MFMA, s);
+    HIP_TRY(launch_mix_mfma(a, logits, s), "mix launch");
+  } else {
     KTimer t(K_MIX_GENERIC, s);
     HIP_TRY(launch_mix_generic(c->dtype, a, logits, 0, s), "mix launch");
   }
@@ -527,8 +552,8 @@ lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_
   if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL");
   Path path;
   if ((st = resolve_path(cfg, 1, &path))) return st;
-  if (path != PATH_MFMA) return LOCOCO_OK;       // the shape-agnostic kernels read [M, C, k] as given
-  const size_t need = filter_ws_bytes(cfg);
+  if (path == PATH_GENERIC) return LOCOCO_OK;    // the shape-agnostic kernels read [M, C, k] as given
+  const size_t need = path == PATH_MFMA ? filter_ws_bytes(cfg) : packed_ws_bytes(cfg);
   if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))
     return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
                 workspace ? ws_bytes : (size_t)0);
@@ -537,9 +562,10 @@ lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_
   a.w_head_stride = cfg->w_head_stride;
   a.M = cfg->M;
   a.k_width = cfg->conv_width;
+  a.conv_in = cfg->conv_in;
   lococo_config once = *cfg;
   once.flags &= ~LOCOCO_FLAG_FILTERS_PREPARED;
-  return enqueue_repack(&once, a, workspace, (hipStream_t)stream);
+  return enqueue_repack(&once, path, a, workspace, (hipStream_t)stream);
 }
 
 lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
@@ -562,12 +588,12 @@ lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* b
   }
   StepArgs a = make_args(cfg, blk, 0, B, cache, conv_w, conv_b, true);
   lococo_cache tmp = *cache;
-  if (compress && path == PATH_MFMA &&
-      (st = enqueue_repack(cfg, a, workspace, (hipStream_t)stream)))
+  if (compress && path != PATH_GENERIC &&
+      (st = enqueue_repack(cfg, path, a, workspace, (hipStream_t)stream)))
     return st;
   if ((st = enqueue_attn(cfg, path, a, step_stats(cfg, path, B, workspace, ws_bytes), (hipStream_t)stream)))
     return st;
-  if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
+  if ((st = enqueue_update(cfg, path, a, &tmp, workspace, B, (hipStream_t)stream))) return st;
   *cache = tmp;
   return LOCOCO_OK;
 }
@@ -601,9 +627,9 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
                   workspace ? ws_bytes : (size_t)0);
   }
   lococo_cache tmp = *cache;
-  if (any_compress && path == PATH_MFMA) {
+  if (any_compress && path != PATH_GENERIC) {
     StepArgs a0 = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
-    if ((st = enqueue_repack(cfg, a0, workspace, (hipStream_t)stream))) return st;
+    if ((st = enqueue_repack(cfg, path, a0, workspace, (hipStream_t)stream))) return st;
   }
   if (path == PATH_MFMA && workspace && ws_bytes >= step_ws_bytes(cfg, path, B)) {
     // the scan status of this call starts at "no wait gave up", whichever schedule runs
@@ -707,7 +733,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
     StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
     if ((st = enqueue_attn(cfg, path, a, step_stats(cfg, path, B, workspace, ws_bytes), (hipStream_t)stream)))
       return st;
-    if ((st = enqueue_update(cfg, path, a, &tmp, workspace, (hipStream_t)stream))) return st;
+    if ((st = enqueue_update(cfg, path, a, &tmp, workspace, B, (hipStream_t)stream))) return st;
   }
   *cache = tmp;
   return LOCOCO_OK;

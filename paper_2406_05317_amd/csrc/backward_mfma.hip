@@ -76,6 +76,11 @@ __device__ __forceinline__ const uint16_t* x_row(const StepArgs& a, int b, int h
   return (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + (int64_t)(j - a.m) * a.k.st;
 }
 
+__device__ __forceinline__ const uint16_t* v_row(const StepArgs& a, int b, int hkv, int j) {   // same for the values
+  if (j < a.m) return (const uint16_t*)a.cache_v + ((int64_t)(b * a.Hkv + hkv) * a.M + j) * kD;
+  return (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + (int64_t)(j - a.m) * a.v.st;
+}
+
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
 #pragma unroll
   for (int x = 0; x < 2; ++x)
@@ -87,15 +92,15 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
 
 // ---- filters [bank][slot][channel][tap] -> [bank][tap][slot][channel]: every tap a row-major
 // (slot x channel) matrix, which the logits read along the channels and dX down the slots
-__global__ void bwd_pack_filters_k(const uint16_t* w, uint16_t* wt, int M, int KW, int banks,
+__global__ void bwd_pack_filters_k(const uint16_t* w, uint16_t* wt, int M, int C, int KW, int banks,
                                    int64_t w_head_stride) {
-  const int64_t n = (int64_t)banks * KW * M * kD;
+  const int64_t n = (int64_t)banks * KW * M * C;
   for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
-    const int c = (int)(e % kD);
-    const int s = (int)((e / kD) % M);
-    const int t = (int)((e / ((int64_t)kD * M)) % KW);
-    const int bank = (int)(e / ((int64_t)kD * M * KW));
-    wt[e] = w[bank * w_head_stride + ((int64_t)s * kD + c) * KW + t];
+    const int c = (int)(e % C);
+    const int s = (int)((e / C) % M);
+    const int t = (int)((e / ((int64_t)C * M)) % KW);
+    const int bank = (int)(e / ((int64_t)C * M * KW));
+    wt[e] = w[bank * w_head_stride + ((int64_t)s * C + c) * KW + t];
   }
 }
 
@@ -134,37 +139,41 @@ __global__ __launch_bounds__(kThreads) void bwd_split_dl_k(const float* dl, uint
 // ---- logits[i, j] (slots x positions, contraction over channels and taps)
 // LDS: X rows p0 - pad .. p0 + 127 + (KW - 1 - pad) once; per tap the (slot x channel) matrix of
 // 128 slots.  A = filters (rows: slots), B = keys (lane: position): a lane stores 32 consecutive
-// positions of one slot per instruction.
-__global__ __launch_bounds__(kThreads, 2) void bwd_logits_mfma_k(StepArgs a, const uint16_t* wt, float* out) {
+// positions of one slot per instruction.  KV = 1: the convolution reads [K | V], 256 channels.
+template <int KV>
+__global__ __launch_bounds__(kThreads, KV ? 1 : 2) void conv_logits_mfma_k(StepArgs a, const uint16_t* wt, float* out) {
   extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int C = KV ? 2 * kD : kD, ROW = C * 2 + 16, CH16 = C / 8;   // channels, LDS row bytes, 16-byte chunks per row
   const int KW = a.k_width, pad = (KW - 1) / 2, Tn = a.m + a.Bn;
   const int xrows = kTile + KW - 1;
   unsigned char* Xs = smem;
-  unsigned char* Ws = smem + xrows * kRow;
+  unsigned char* Ws = smem + xrows * ROW;
   const int p0 = blockIdx.x * kTile, s0 = blockIdx.y * kTile, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
-  const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * kD : 0);
+  const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * C : 0);
 
-  for (int item = tid; item < xrows * 16; item += kThreads) {
-    const int row = item >> 4, c16 = item & 15, p = p0 - pad + row;
+  for (int item = tid; item < xrows * CH16; item += kThreads) {
+    const int row = item / CH16, c16 = item % CH16, p = p0 - pad + row;
     u32x4 v = {0u, 0u, 0u, 0u};
-    if (p >= 0 && p < Tn) v = *(const u32x4*)(x_row(a, b, hkv, p) + c16 * 8);
-    *(u32x4*)(Xs + row * kRow + c16 * 16) = v;
+    if (p >= 0 && p < Tn)
+      v = *(const u32x4*)((c16 < 16 ? x_row(a, b, hkv, p) : v_row(a, b, hkv, p)) + (c16 & 15) * 8);
+    *(u32x4*)(Xs + row * ROW + c16 * 16) = v;
   }
-  u32x4 wreg[8];
+  constexpr int WPER = kTile * CH16 / kThreads;
+  u32x4 wreg[WPER];
   auto load_w = [&](int t) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int item = tid + i * kThreads, row = item >> 4, c16 = item & 15, s = s0 + row;
+    for (int i = 0; i < WPER; ++i) {
+      const int item = tid + i * kThreads, row = item / CH16, c16 = item % CH16, s = s0 + row;
       const u32x4 z = {0u, 0u, 0u, 0u};
-      wreg[i] = s < a.M ? *(const u32x4*)(wtb + ((int64_t)t * a.M + s) * kD + c16 * 8) : z;
+      wreg[i] = s < a.M ? *(const u32x4*)(wtb + ((int64_t)t * a.M + s) * C + c16 * 8) : z;
     }
   };
   auto store_w = [&]() {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int item = tid + i * kThreads, row = item >> 4, c16 = item & 15;
-      *(u32x4*)(Ws + row * kRow + c16 * 16) = wreg[i];
+    for (int i = 0; i < WPER; ++i) {
+      const int item = tid + i * kThreads, row = item / CH16, c16 = item % CH16;
+      *(u32x4*)(Ws + row * ROW + c16 * 16) = wreg[i];
     }
   };
   f32x16 acc[2][2];                       // [slot block][position block]
@@ -175,12 +184,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_logits_mfma_k(StepArgs a, con
     store_w();
     if (t + 1 < KW) load_w(t + 1);
     __syncthreads();
-    const unsigned char* wl = Ws + (wy * 64 + l31) * kRow + lh * 16;
-    const unsigned char* xl = Xs + (wx * 64 + l31 + t) * kRow + lh * 16;
+    const unsigned char* wl = Ws + (wy * 64 + l31) * ROW + lh * 16;
+    const unsigned char* xl = Xs + (wx * 64 + l31 + t) * ROW + lh * 16;
 #pragma unroll
-    for (int kc = 0; kc < kD / 16; ++kc) {
-      const bf16x8 a0 = frag(wl + kc * 32), a1 = frag(wl + 32 * kRow + kc * 32);
-      const bf16x8 b0 = frag(xl + kc * 32), b1 = frag(xl + 32 * kRow + kc * 32);
+    for (int kc = 0; kc < C / 16; ++kc) {
+      const bf16x8 a0 = frag(wl + kc * 32), a1 = frag(wl + 32 * ROW + kc * 32);
+      const bf16x8 b0 = frag(xl + kc * 32), b1 = frag(xl + 32 * ROW + kc * 32);
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
@@ -602,7 +611,25 @@ struct OpWn {              // normalised mixing rows, fp32 [chain, M, Tn]; prote
   }
 };
 
+struct OpWrows {           // normalised mixing rows fp32 [chain, M, Tn], as rows (contraction along them);
+  static constexpr bool kMajor = false;      // rounded to bf16 like the probabilities of the fused kernel
+  static constexpr int kParts = 1;
+  Dims s; const float* w;
+  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+    const bool ok = r < s.M && c < s.Tn;
+    from_f32x4(v, w + ((int64_t)z * s.M + (ok ? r : 0)) * s.Tn + (ok ? c : 0), ok);
+  }
+};
+
 // -- outputs
+struct OutNewCache {       // bf16 rows of the next cache [chain, M, d]: j < d keys, else values
+  Dims s; uint16_t* nk; uint16_t* nv;
+  __device__ bool skip(int, int, int) const { return false; }
+  __device__ void store(int z, int i, int j, float v) const {
+    uint16_t* row = (j < s.d ? nk : nv) + ((int64_t)z * s.M + i) * s.d;
+    row[j < s.d ? j : j - s.d] = (uint16_t)bf16_rne(v);
+  }
+};
 struct OutRows {           // fp32 [batch, Hq, Bn, Tn] rows, scaled; tiles wholly after their queries are skipped
   Dims s; float* p; float scale;
   __device__ bool skip(int, int i0, int j0) const { return j0 > s.m + i0 + kTile - 1; }
@@ -670,6 +697,12 @@ int grid_for(int64_t n) { return (int)std::min<int64_t>((n + 255) / 256, 4096); 
 bool bwd_mfma_supports(int dtype, int d, int conv_in, int conv_width) {
   return dtype == LOCOCO_BF16 && d == kD && conv_in == 0 && conv_width % 2 == 1 && conv_width <= 31;
 }
+bool conv_logits_mfma_supports(int dtype, int d, int conv_width) {    // keys-only or [K | V] filters
+  return dtype == LOCOCO_BF16 && d == kD && conv_width % 2 == 1 && conv_width <= 31;
+}
+size_t packed_filter_bytes(int M, int conv_width, int conv_in, int banks) {
+  return (size_t)banks * conv_width * M * (conv_in ? 2 * kD : kD) * 2;
+}
 
 static int padded_slots(int n) { return (n + kChunk - 1) / kChunk * kChunk; }   // also for positions
 
@@ -689,27 +722,32 @@ BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width,
 }
 
 hipError_t launch_bwd_pack_filters(const StepArgs& a, int banks, void* wt, hipStream_t s) {
-  const int64_t n = (int64_t)banks * a.k_width * a.M * kD;
+  const int C = a.conv_in ? 2 * kD : kD;
+  const int64_t n = (int64_t)banks * a.k_width * a.M * C;
   hipLaunchKernelGGL(bwd_pack_filters_k, dim3(grid_for(n)), dim3(256), 0, s, (const uint16_t*)a.conv_w,
-                     (uint16_t*)wt, a.M, a.k_width, banks, a.w_head_stride);
+                     (uint16_t*)wt, a.M, C, a.k_width, banks, a.w_head_stride);
   return hipGetLastError();
 }
 
-hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
+template <int KV>
+static hipError_t launch_logits(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
+  constexpr int ROW = (KV ? 2 * kD : kD) * 2 + 16;
   const int Tn = a.m + a.Bn;
-  const int lds = (kTile + a.k_width - 1) * kRow + kTile * kRow;
+  const int lds = (kTile + a.k_width - 1) * ROW + kTile * ROW;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_logits_mfma_k, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (kTile + 30) * kRow + kTile * kRow);
+    hipError_t e = hipFuncSetAttribute((const void*)conv_logits_mfma_k<KV>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (kTile + 30) * ROW + kTile * ROW);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(bwd_logits_mfma_k, dim3((Tn + kTile - 1) / kTile, (a.M + kTile - 1) / kTile, a.batch * a.Hkv),
+  hipLaunchKernelGGL(conv_logits_mfma_k<KV>, dim3((Tn + kTile - 1) / kTile, (a.M + kTile - 1) / kTile, a.batch * a.Hkv),
                      dim3(kThreads), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
-
+hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
+  return a.conv_in ? launch_logits<1>(a, wt, logits, s) : launch_logits<0>(a, wt, logits, s);
+}
 
 // The plain contractions take whole groups of four: every row width (d, 2 d, T) a multiple of 4
 // and every fp32 array 16-byte aligned.  Otherwise the caller keeps the fp32 vector kernels.
@@ -757,6 +795,17 @@ hipError_t launch_bwd_mix_dw_mfma(const BwdArgs& g, hipStream_t s) {
   return launch_gemm(OpG<false>{dm, g.d_new_k, g.d_new_v, a.protect, a.protect_stride, false},
                      OpY<false, 2>{dm, a.cache_k, a.cache_v, a.k, a.v, false}, OutPlain{g.ws_dw, a.M, dm.Tn}, a.M,
                      dm.Tn, 2 * a.d, a.batch * a.Hkv, s);
+}
+
+// Eq. 4a / 4b of the forward step from normalised rows: [new_K | new_V][i] = sum_j w[i, j] [Yk | Yv][j]
+bool mix_mfma_fits(const StepArgs& a, const float* w) {
+  return a.d == kD && (a.m + a.Bn) % 4 == 0 && ((uintptr_t)w & 15) == 0;
+}
+hipError_t launch_mix_mfma(const StepArgs& a, const float* w, hipStream_t s) {
+  const Dims dm = dims_of(a);
+  return launch_gemm(OpWrows{dm, w}, OpY<true, 2>{dm, a.cache_k, a.cache_v, a.k, a.v, false},
+                     OutNewCache{dm, (uint16_t*)a.new_k, (uint16_t*)a.new_v}, a.M, 2 * a.d, dm.Tn,
+                     a.batch * a.Hkv, s);
 }
 
 // d[Yk | Yv][j] += sum over the unprotected slots of w[i, j] [g_k | g_v][i]

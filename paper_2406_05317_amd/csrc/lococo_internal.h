@@ -176,8 +176,14 @@ struct BwdMfmaLayout { size_t wt, dhi, dlo, dhi_s, dlo_s, dwt, total; };
 BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int banks);
 // conv_w -> [bank][tap][slot][channel] at the layout's wt
 hipError_t launch_bwd_pack_filters(const StepArgs& a, int banks, void* wt, hipStream_t s);
-// raw logits fp32 [chains, M, T] (bias added), from the packed filters
+// raw logits fp32 [chains, M, T] (bias added), from the packed filters; keys-only or [K | V] input (a.conv_in)
 hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s);
+bool conv_logits_mfma_supports(int dtype, int d, int conv_width);
+// bytes of the filters packed per tap [bank][tap][slot][channel]
+size_t packed_filter_bytes(int M, int conv_width, int conv_in, int banks);
+// Eq. 4a / 4b from normalised rows w [chains, M, T] into a.new_k / a.new_v (bf16); needs mix_mfma_fits
+bool mix_mfma_fits(const StepArgs& a, const float* w);
+hipError_t launch_mix_mfma(const StepArgs& a, const float* w, hipStream_t s);
 // dX into d_k / d_cache_k (added) and dWc into d_conv_w (added), from the logit gradient in g.ws_w
 hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream_t s);
 // the plain contractions of the pass (fp32 operands enter as two bf16 halves): same inputs,

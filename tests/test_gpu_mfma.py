@@ -207,6 +207,39 @@ def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
     compare_scan(w, a, want, what="several chains per workgroup")
 
 
+@pytest.mark.parametrize("case", [
+    dict(conv_in=1, conv_width=21, norm=1, bias_sigma=0.5, L=640),              # the compressor as the paper prints it
+    dict(conv_in=1, conv_width=15, M=256, B=128, L=1024, n_q_heads=8, n_kv_heads=2, per_head_filters=True),
+    dict(conv_width=7, L=500),                                                   # a width the fused kernel is not built for; ragged last block
+    dict(conv_width=31, M=100, B=60, L=400),                                     # M not a multiple of 32, widest filter
+    dict(conv_in=1, conv_width=3, M=64, B=48, L=300, batch=3, n_q_heads=4, n_kv_heads=2, tok_lognormal_sigma=0.5),
+    dict(conv_in=1, conv_width=21, conv_gain=6.0, qk_gain=6.0, L=640),           # peaked rows
+    dict(conv_in=1, conv_width=21, L=512, protect_share=0.15),                   # protected slots
+])
+def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case):
+    """impl = AUTO with bf16 / head_dim 128 and a compressor the fused kernel is not built for
+    ([K | V] input, other widths, odd M): MFMA attention, MFMA logits and MFMA fusion around the
+    shape-agnostic normalisation.  Equal to the oracle; the timing rows say which kernels ran."""
+    from paper_2406_05317_amd import binding as lb
+    case = dict(case)
+    share = case.pop("protect_share", 0.0)
+    w = _w(**case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    protect = (np.random.default_rng(6).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    lb.lococo_timing_begin()
+    got = gpu_forward(w, q, k, v, cw, cb, impl=0, history=True, protect=protect)
+    ran = lb.lococo_timing_end()
+    assert "conv_logits_mfma" in ran and "attn_mfma" in ran and "mix_mfma" in ran, ran
+    assert "conv_logits_generic" not in ran and "attn_generic" not in ran, ran
+    compare_scan(w, got, want, what="unfused MFMA path")
+    # block by block through lococo_segment_step: the same kernels, the same bits
+    again = gpu_forward(w, q, k, v, cw, cb, impl=0, step_by_step=True, protect=protect)
+    for x, y in zip(got[:3], again[:3]):
+        assert torch.equal(x, y)
+
+
 def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
     """Forced from the host: with no polls allowed, the first slot tile to finish a step cannot wait
     for its chain, leaves the kernel, and the status word says so.  Every workgroup still exits."""
