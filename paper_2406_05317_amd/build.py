@@ -16,7 +16,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblococo.so")
 
 SOURCES = ["api.cpp", "generic_kernels.hip", "compress_mfma.hip", "attn_mfma.hip", "attn_decode.hip",
-           "backward_generic.hip", "backward_mfma.hip", "peaks.hip"]
+           "backward_generic.hip", "tiled_mfma.hip", "peaks.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

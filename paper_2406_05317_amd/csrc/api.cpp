@@ -369,7 +369,7 @@ lococo_status enqueue_repack(const lococo_config* c, Path path, const StepArgs& 
   if (c->flags & LOCOCO_FLAG_FILTERS_PREPARED) return LOCOCO_OK;
   KTimer t(K_REPACK, s);
   if (path == PATH_MFMA) HIP_TRY(launch_repack_filters(a, ws, filter_banks(c), s), "filter repack launch");
-  else HIP_TRY(launch_bwd_pack_filters(a, filter_banks(c), ws, s), "filter packing launch");
+  else HIP_TRY(launch_pack_filters_per_tap(a, filter_banks(c), ws, s), "filter packing launch");
   return LOCOCO_OK;
 }
 
@@ -398,7 +398,7 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
   float* logits = unfused ? (float*)((char*)ws + packed_ws_bytes(c) + stats_bytes(c, B)) : (float*)ws;
   if (unfused) {
     KTimer t(K_CONV_MFMA, s);
-    HIP_TRY(launch_bwd_logits_mfma(a, ws, logits, s), "conv launch");
+    HIP_TRY(launch_conv_logits_mfma(a, ws, logits, s), "conv launch");
   } else {
     KTimer t(K_CONV_GENERIC, s);
     HIP_TRY(launch_conv_logits_generic(c->dtype, a, logits, s), "conv launch");
@@ -824,8 +824,8 @@ lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococ
   if (compress) {
     // recompute Eq. 5 and Eq. 6 of the forward step: raw logits and normalised rows
     if (g.ws_mfma) {
-      HIP_TRY(launch_bwd_pack_filters(g.st, g.banks, g.ws_mfma, s), "filter packing launch");
-      HIP_TRY(launch_bwd_logits_mfma(g.st, g.ws_mfma, g.ws_w, s), "conv launch");
+      HIP_TRY(launch_pack_filters_per_tap(g.st, g.banks, g.ws_mfma, s), "filter packing launch");
+      HIP_TRY(launch_conv_logits_mfma(g.st, g.ws_mfma, g.ws_w, s), "conv launch");
     } else {
       HIP_TRY(launch_conv_logits_generic(cfg->dtype, g.st, g.ws_w, s), "conv launch");
     }

@@ -612,7 +612,7 @@ template <typename T>
 hipError_t run(const BwdArgs& g, bool compress, hipStream_t s) {
   const StepArgs& a = g.st;
   const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv;
-  // with g.ws_mfma set every contraction below has a matrix-core form (backward_mfma.hip)
+  // with g.ws_mfma set every contraction below has a matrix-core form (tiled_mfma.hip)
   const bool conv_mfma = g.ws_mfma != nullptr;
   const bool mfma = g.gemms_mfma && bwd_gemms_mfma_fit(g);
   hipError_t e = hipSuccess;

@@ -168,16 +168,16 @@ hipError_t launch_attn_colsum_mfma(const AttnArgs& a, float* colsum, hipStream_t
 bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum);
 hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s);
 
-// ---- Eq. 5 of the backward pass on MFMA (backward_mfma.hip): bf16, head_dim 128, keys-only filters
+// ---- Eq. 5 of the backward pass on MFMA (tiled_mfma.hip): bf16, head_dim 128, keys-only filters
 bool bwd_mfma_supports(int dtype, int d, int conv_in, int conv_width);
 // byte offsets inside its workspace: filters per tap, dW split into two bf16 halves (transposed, then as it is),
 // filter gradient per tap
 struct BwdMfmaLayout { size_t wt, dhi, dlo, dhi_s, dlo_s, dwt, total; };
 BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int banks);
 // conv_w -> [bank][tap][slot][channel] at the layout's wt
-hipError_t launch_bwd_pack_filters(const StepArgs& a, int banks, void* wt, hipStream_t s);
+hipError_t launch_pack_filters_per_tap(const StepArgs& a, int banks, void* wt, hipStream_t s);
 // raw logits fp32 [chains, M, T] (bias added), from the packed filters; keys-only or [K | V] input (a.conv_in)
-hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s);
+hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s);
 bool conv_logits_mfma_supports(int dtype, int d, int conv_width);
 // bytes of the filters packed per tap [bank][tap][slot][channel]
 size_t packed_filter_bytes(int M, int conv_width, int conv_in, int banks);

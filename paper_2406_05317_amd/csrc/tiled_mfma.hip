@@ -1,6 +1,10 @@
-// Eq. 5 in the backward pass of a compress step on the matrix cores (bf16 storage, head_dim =
-// channels = 128, keys-only filters): the recomputed logits, their gradient w.r.t. the keys and
-// w.r.t. the filters are the three large contractions of that pass (2 M T C k flops each).
+// LDS-tiled bf16 MFMA kernels for the contractions outside the two fused forward kernels:
+//  * Eq. 5 as a kernel of its own (keys-only or [K | V] filters, any odd width up to 31), used by the
+//    forward path for compressors the fused kernel is not built for and by the backward pass to
+//    recompute the logits;
+//  * the two gradients of Eq. 5 in the backward pass (head_dim = channels = 128, keys-only filters);
+//  * one batched GEMM kernel (bwd_gemm_k) whose instances are the seven plain contractions of the
+//    backward pass (attention and Eq. 4) and Eq. 4 of the unfused forward path.
 //
 //   logits[i, j]  = b[i] + sum_t sum_c Wc[i, c, t] X[j + t - p, c]
 //   dX[j, c]     += sum_t sum_i dW[i, j - t + p] Wc[i, c, t]
@@ -11,14 +15,11 @@
 // bf16 numbers (dW = hi + lo, lo = the rounding error of hi), two MFMAs per operand pair, which
 // keeps about 16 bits of it: the results agree with the fp32 kernels to the usual 1e-4.
 //
-// All three kernels: 256 threads, 128 x 128 outputs per workgroup (64 x 64 per wave, 2 x 2 MFMA
+// The Eq. 5 kernels: 256 threads, 128 x 128 outputs per workgroup (64 x 64 per wave, 2 x 2 MFMA
 // tiles of 32 x 32 x 16), operands staged through LDS in rows padded by 16 bytes; a tap is a
 // row-shifted view of a staged tile.  Where the contraction runs down the rows of a row-major
 // tile the fragments come from transposing LDS reads.  The next tile is fetched into registers
 // while the current one is multiplied.
-//
-// The seven plain contractions of the pass (attention and Eq. 4) are instances of one batched GEMM
-// kernel of the same shape further down (bwd_gemm_k), their fp32 operands split the same way.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -92,7 +93,7 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
 
 // ---- filters [bank][slot][channel][tap] -> [bank][tap][slot][channel]: every tap a row-major
 // (slot x channel) matrix, which the logits read along the channels and dX down the slots
-__global__ void bwd_pack_filters_k(const uint16_t* w, uint16_t* wt, int M, int C, int KW, int banks,
+__global__ void pack_filters_per_tap_k(const uint16_t* w, uint16_t* wt, int M, int C, int KW, int banks,
                                    int64_t w_head_stride) {
   const int64_t n = (int64_t)banks * KW * M * C;
   for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
@@ -721,10 +722,10 @@ BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width,
   return l;
 }
 
-hipError_t launch_bwd_pack_filters(const StepArgs& a, int banks, void* wt, hipStream_t s) {
+hipError_t launch_pack_filters_per_tap(const StepArgs& a, int banks, void* wt, hipStream_t s) {
   const int C = a.conv_in ? 2 * kD : kD;
   const int64_t n = (int64_t)banks * a.k_width * a.M * C;
-  hipLaunchKernelGGL(bwd_pack_filters_k, dim3(grid_for(n)), dim3(256), 0, s, (const uint16_t*)a.conv_w,
+  hipLaunchKernelGGL(pack_filters_per_tap_k, dim3(grid_for(n)), dim3(256), 0, s, (const uint16_t*)a.conv_w,
                      (uint16_t*)wt, a.M, C, a.k_width, banks, a.w_head_stride);
   return hipGetLastError();
 }
@@ -745,7 +746,7 @@ static hipError_t launch_logits(const StepArgs& a, const void* wt, float* logits
                      dim3(kThreads), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
-hipError_t launch_bwd_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
+hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
   return a.conv_in ? launch_logits<1>(a, wt, logits, s) : launch_logits<0>(a, wt, logits, s);
 }
 
