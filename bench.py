@@ -219,13 +219,14 @@ def backward_bench(args, w, lb, inputs, torch):
     tf = 2.0 * sum(fl.values()) / (ms * 1e-3) / 1e12
     peak = PEAK_FP32_VALU_TFLOPS if generic else PEAK_BF16_MFMA_TFLOPS
     print(json.dumps({"metric": "backward of one compress step, tokens/sec per layer (%s)" %
-                                ("shape-agnostic kernels" if generic else "Eq. 5 contractions on MFMA, the rest fp32 vector"),
+                                ("shape-agnostic fp32 kernels" if generic else
+                                 "contractions on bf16 MFMA with fp32 operands as two bf16 halves, row reductions fp32 vector"),
                       "value": w.batch * w.B / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
                       "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-                      "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                      "vs_baseline": None, "dtype": "f32" if generic else "bf16", "data": "synthetic",
                       "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads,
                                  "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "B": w.B, "M": w.M,
-                                 "conv_width": w.conv_width},
+                                 "conv_width": w.conv_width, "conv_channels": w.C, "norm": w.norm},
                       "roofline": {"bound": "alu" if generic else "mfma", "achieved": tf, "peak": peak,
                                    "unit": "TFLOP/s", "frac": tf / peak, "traffic": None}}))
 

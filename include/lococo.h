@@ -246,7 +246,7 @@ lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo
  * LOCOCO_IMPL_GENERIC the contractions run on the matrix cores, every fp32 operand entering as
  * the sum of two bf16 numbers (about 16 bits kept): the plain ones when block length + live
  * slots is a multiple of 4, the three convolution ones (Eq. 5 and its two gradients) with
- * head_dim 128 and keys-only filters (the workspace is larger then).  Filter gradients are summed
+ * head_dim 128 and a filter width up to 31 (the workspace is larger then).  Filter gradients are summed
  * with floating-point atomics, so their last bits depend on the order. */
 lococo_status lococo_backward_workspace_bytes(const lococo_config* cfg, int32_t B, int32_t len, size_t* out);
 lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,

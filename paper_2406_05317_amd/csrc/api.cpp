@@ -759,7 +759,7 @@ BwdLayout bwd_layout(const lococo_config* c, int32_t B, int32_t len) {
   l.mf = l.dw + align_up(mat, 256);
   l.total = l.mf;
   if (compress && bwd_on_mfma(c))
-    l.total += bwd_mfma_layout(c->batch, c->n_kv_heads, c->M, (int)T, c->conv_width, filter_banks(c)).total;
+    l.total += bwd_mfma_layout(c->batch, c->n_kv_heads, c->M, (int)T, c->conv_width, c->conv_in, filter_banks(c)).total;
   return l;
 }
 }  // namespace

@@ -168,12 +168,12 @@ hipError_t launch_attn_colsum_mfma(const AttnArgs& a, float* colsum, hipStream_t
 bool attn_decode_supports(int dtype, int d, int Bn, int M, bool colsum);
 hipError_t launch_attn_decode(const StepArgs& a, hipStream_t s);
 
-// ---- Eq. 5 of the backward pass on MFMA (tiled_mfma.hip): bf16, head_dim 128, keys-only filters
+// ---- Eq. 5 of the backward pass on MFMA (tiled_mfma.hip): bf16, head_dim 128, keys-only or [K | V] filters
 bool bwd_mfma_supports(int dtype, int d, int conv_in, int conv_width);
 // byte offsets inside its workspace: filters per tap, dW split into two bf16 halves (transposed, then as it is),
 // filter gradient per tap
 struct BwdMfmaLayout { size_t wt, dhi, dlo, dhi_s, dlo_s, dwt, total; };
-BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int banks);
+BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int conv_in, int banks);
 // conv_w -> [bank][tap][slot][channel] at the layout's wt
 hipError_t launch_pack_filters_per_tap(const StepArgs& a, int banks, void* wt, hipStream_t s);
 // raw logits fp32 [chains, M, T] (bias added), from the packed filters; keys-only or [K | V] input (a.conv_in)

@@ -226,8 +226,11 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_k(BwdArgs g, const ui
   unsigned char* Dl = Dh + drows * kRow64;
   unsigned char* Ws = Dl + drows * kRow64;
   const int p0 = blockIdx.x * kTile, ch = blockIdx.y, hkv = ch % a.Hkv;
+  // channel tile: 0 = the key channels; 1 = the value channels of [K | V] filters, whose gradient
+  // belongs to the value rows
+  const int c0 = blockIdx.z * kTile, C = a.conv_in ? 2 * kD : kD;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
-  const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * kD : 0);
+  const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * C : 0) + c0;
   const int nsc = Mp / kChunk, nsteps = nsc * KW;
 
   u32x4 wreg[4];
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_k(BwdArgs g, const ui
     for (int i = 0; i < 4; ++i) {
       const int item = tid + i * kThreads, row = item >> 4, c16 = item & 15, s = sc * kChunk + row;
       const u32x4 z = {0u, 0u, 0u, 0u};
-      wreg[i] = s < a.M ? *(const u32x4*)(wtb + ((int64_t)t * a.M + s) * kD + c16 * 8) : z;
+      wreg[i] = s < a.M ? *(const u32x4*)(wtb + ((int64_t)t * a.M + s) * C + c16 * 8) : z;
     }
   };
   auto store_w = [&]() {
@@ -295,8 +298,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_k(BwdArgs g, const ui
     for (int i = 0; i < 16; ++i) {
       const int p = p0 + wy * 64 + pb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
       if (p >= Tn) continue;
-      float* row = p < a.m ? g.d_cache_k + ((int64_t)ch * a.M + p) * kD
-                           : g.d_k + ((int64_t)ch * a.Bn + (p - a.m)) * kD;
+      float* row = p < a.m ? (c0 ? g.d_cache_v : g.d_cache_k) + ((int64_t)ch * a.M + p) * kD
+                           : (c0 ? g.d_v : g.d_k) + ((int64_t)ch * a.Bn + (p - a.m)) * kD;
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) row[wx * 64 + cb * 32 + l31] += acc[pb][cb][i];
     }
@@ -314,7 +317,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_k(BwdArgs g, const ui
   __shared__ __align__(16) unsigned char Dl[kTile * kRow64];
   const StepArgs& a = g.st;
   const int KW = a.k_width, pad = (KW - 1) / 2, Tn = a.m + a.Bn;
-  const int t = blockIdx.x, s0 = blockIdx.y * kTile;
+  const int C = a.conv_in ? 2 * kD : kD, ctiles = C / kTile;
+  const int t = blockIdx.x, s0 = (blockIdx.y / ctiles) * kTile, c0 = (blockIdx.y % ctiles) * kTile;   // c0 = 128: value channels
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
   const bool per_head = a.w_head_stride != 0;
   // the chains of this workgroup share a filter bank: consecutive chains when the bank is shared,
@@ -336,7 +340,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_k(BwdArgs g, const ui
     for (int i = 0; i < 4; ++i) {
       const int item = tid + i * kThreads, row = item >> 4, c16 = item & 15, q = pc + row + t - pad;
       const u32x4 z = {0u, 0u, 0u, 0u};
-      xreg[i] = (q >= 0 && q < Tn) ? *(const u32x4*)(x_row(a, b, hkv, q) + c16 * 8) : z;
+      xreg[i] = (q >= 0 && q < Tn) ? *(const u32x4*)((c0 ? v_row(a, b, hkv, q) : x_row(a, b, hkv, q)) + c16 * 8) : z;
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -385,7 +389,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_k(BwdArgs g, const ui
       }
     }
   }
-  float* o = dwt + ((int64_t)(per_head ? hkv_fixed : 0) * KW + t) * a.M * kD;
+  float* o = dwt + ((int64_t)(per_head ? hkv_fixed : 0) * KW + t) * a.M * C + c0;
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -393,7 +397,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_k(BwdArgs g, const ui
       const int s = s0 + wy * 64 + sb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
       if (s >= a.M) continue;
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) atomicAdd(o + (int64_t)s * kD + wx * 64 + cb * 32 + l31, acc[sb][cb][i]);
+      for (int cb = 0; cb < 2; ++cb) atomicAdd(o + (int64_t)s * C + wx * 64 + cb * 32 + l31, acc[sb][cb][i]);
     }
 }
 
@@ -679,15 +683,16 @@ __global__ void bwd_zero_k(float* p, int64_t n) {
     p[e] = 0.f;
 }
 // d_conv_w[bank][slot][channel][tap] += dwt[bank][tap][slot][channel]
-__global__ void bwd_add_dw_k(const float* dwt, float* d_conv_w, int M, int KW, int banks, int64_t w_head_stride) {
-  const int64_t n = (int64_t)banks * M * kD * KW;
+__global__ void bwd_add_dw_k(const float* dwt, float* d_conv_w, int M, int C, int KW, int banks,
+                             int64_t w_head_stride) {
+  const int64_t n = (int64_t)banks * M * C * KW;
   for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
     const int t = (int)(e % KW);
-    const int c = (int)((e / KW) % kD);
-    const int s = (int)((e / ((int64_t)KW * kD)) % M);
-    const int bank = (int)(e / ((int64_t)KW * kD * M));
-    d_conv_w[bank * w_head_stride + ((int64_t)s * kD + c) * KW + t] +=
-        dwt[(((int64_t)bank * KW + t) * M + s) * kD + c];
+    const int c = (int)((e / KW) % C);
+    const int s = (int)((e / ((int64_t)KW * C)) % M);
+    const int bank = (int)(e / ((int64_t)KW * C * M));
+    d_conv_w[bank * w_head_stride + ((int64_t)s * C + c) * KW + t] +=
+        dwt[(((int64_t)bank * KW + t) * M + s) * C + c];
   }
 }
 
@@ -696,7 +701,8 @@ int grid_for(int64_t n) { return (int)std::min<int64_t>((n + 255) / 256, 4096); 
 }  // namespace
 
 bool bwd_mfma_supports(int dtype, int d, int conv_in, int conv_width) {
-  return dtype == LOCOCO_BF16 && d == kD && conv_in == 0 && conv_width % 2 == 1 && conv_width <= 31;
+  (void)conv_in;                          // keys-only and [K | V] filters alike
+  return dtype == LOCOCO_BF16 && d == kD && conv_width % 2 == 1 && conv_width <= 31;
 }
 bool conv_logits_mfma_supports(int dtype, int d, int conv_width) {    // keys-only or [K | V] filters
   return dtype == LOCOCO_BF16 && d == kD && conv_width % 2 == 1 && conv_width <= 31;
@@ -707,18 +713,19 @@ size_t packed_filter_bytes(int M, int conv_width, int conv_in, int banks) {
 
 static int padded_slots(int n) { return (n + kChunk - 1) / kChunk * kChunk; }   // also for positions
 
-BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int banks) {
+BwdMfmaLayout bwd_mfma_layout(int batch, int Hkv, int M, int Tn, int conv_width, int conv_in, int banks) {
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const int C = conv_in ? 2 * kD : kD;
   BwdMfmaLayout l;
   l.wt = 0;
-  l.dhi = up((size_t)banks * conv_width * M * kD * 2);
+  l.dhi = up((size_t)banks * conv_width * M * C * 2);
   const size_t half = up((size_t)batch * Hkv * Tn * padded_slots(M) * 2);
   l.dlo = l.dhi + half;
   const size_t half_s = up((size_t)batch * Hkv * M * padded_slots(Tn) * 2);
   l.dhi_s = l.dlo + half;
   l.dlo_s = l.dhi_s + half_s;
   l.dwt = l.dlo_s + half_s;
-  l.total = l.dwt + up((size_t)banks * conv_width * M * kD * 4);
+  l.total = l.dwt + up((size_t)banks * conv_width * M * C * 4);
   return l;
 }
 
@@ -822,7 +829,8 @@ hipError_t launch_bwd_mix_cols_mfma(const BwdArgs& g, hipStream_t s) {
 hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream_t s) {
   const StepArgs& a = g.st;
   const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv, Mp = padded_slots(a.M);
-  const BwdMfmaLayout l = bwd_mfma_layout(a.batch, a.Hkv, a.M, Tn, a.k_width, banks);
+  const BwdMfmaLayout l = bwd_mfma_layout(a.batch, a.Hkv, a.M, Tn, a.k_width, a.conv_in, banks);
+  const int C = a.conv_in ? 2 * kD : kD, ctiles = C / kTile;
   const uint16_t* wt = (const uint16_t*)((char*)ws + l.wt);
   uint16_t* dhi = (uint16_t*)((char*)ws + l.dhi);
   uint16_t* dlo = (uint16_t*)((char*)ws + l.dlo);
@@ -842,21 +850,22 @@ hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    hipLaunchKernelGGL(bwd_dx_mfma_k, dim3((Tn + kTile - 1) / kTile, chains), dim3(kThreads), lds, s, g, wt, dhi, dlo,
-                       Mp);
+    hipLaunchKernelGGL(bwd_dx_mfma_k, dim3((Tn + kTile - 1) / kTile, chains, ctiles), dim3(kThreads), lds, s, g, wt,
+                       dhi, dlo, Mp);
   }
-  const int64_t nw = (int64_t)banks * a.k_width * a.M * kD;
+  const int64_t nw = (int64_t)banks * a.k_width * a.M * C;
   hipLaunchKernelGGL(bwd_zero_k, dim3(grid_for(nw)), dim3(256), 0, s, dwt, nw);
   {
     // chains per workgroup: enough workgroups to fill the chip several times over, as few atomics as that allows
     const int entries = banks > 1 ? a.batch : chains;
-    const int tiles = a.k_width * ((a.M + kTile - 1) / kTile) * (banks > 1 ? a.Hkv : 1);
+    const int tiles = a.k_width * ((a.M + kTile - 1) / kTile) * ctiles * (banks > 1 ? a.Hkv : 1);
     int per_group = (int)std::min<int64_t>(8, std::max<int64_t>(1, (int64_t)tiles * entries / 1024));
     const int groups = (entries + per_group - 1) / per_group;
-    hipLaunchKernelGGL(bwd_dw_mfma_k, dim3(a.k_width, (a.M + kTile - 1) / kTile, groups * (banks > 1 ? a.Hkv : 1)),
+    hipLaunchKernelGGL(bwd_dw_mfma_k,
+                       dim3(a.k_width, ((a.M + kTile - 1) / kTile) * ctiles, groups * (banks > 1 ? a.Hkv : 1)),
                        dim3(kThreads), 0, s, g, dhi_s, dlo_s, Tp, dwt, per_group);
   }
-  hipLaunchKernelGGL(bwd_add_dw_k, dim3(grid_for(nw)), dim3(256), 0, s, dwt, g.d_conv_w, a.M, a.k_width, banks,
+  hipLaunchKernelGGL(bwd_add_dw_k, dim3(grid_for(nw)), dim3(256), 0, s, dwt, g.d_conv_w, a.M, C, a.k_width, banks,
                      a.w_head_stride);
   return hipGetLastError();
 }

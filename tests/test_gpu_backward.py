@@ -61,6 +61,11 @@ CASES = [
          conv_width=15, impl=0),
     dict(name="mfma head_dim 64 (plain contractions only)", dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=2,
          head_dim=64, B=40, M=64, m=64, conv_width=7, bias_sigma=0.3, impl=0),
+    dict(name="mfma [K|V] filters width 21 relu-sum per-head", dtype="bf16", batch=2, n_q_heads=4, n_kv_heads=2,
+         head_dim=128, B=72, M=160, m=160, conv_width=21, conv_in=1, norm=1, per_head_filters=True, bias_sigma=0.4,
+         impl=0),                                                                  # the compressor as the paper prints it
+    dict(name="mfma [K|V] filters partial cache", dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=1, head_dim=128,
+         B=100, M=128, m=60, conv_width=15, conv_in=1, impl=0),
     dict(name="mfma width 3", dtype="bf16", batch=1, n_q_heads=1, n_kv_heads=1, head_dim=128, B=33, M=32, m=20,
          conv_width=3, impl=0),
 ]
