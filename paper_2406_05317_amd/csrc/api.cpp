@@ -217,8 +217,8 @@ size_t stats_bytes(const lococo_config* c, int64_t rows) {
 size_t packed_ws_bytes(const lococo_config* c) {
   return align_up(packed_filter_bytes(c->M, c->conv_width, c->conv_in, filter_banks(c)), 256);
 }
-size_t logits_bytes(const lococo_config* c, int32_t B) {
-  return align_up((size_t)c->batch * c->n_kv_heads * c->M * ((size_t)c->M + B) * sizeof(float), 256);
+size_t logits_bytes(const lococo_config* c, int32_t B) {     // rows of up to M + B logits, padded to a multiple of 4
+  return align_up((size_t)c->batch * c->n_kv_heads * c->M * (((size_t)c->M + B + 3) / 4 * 4) * sizeof(float), 256);
 }
 // MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block];
 // unfused MFMA path: [filters packed per tap][row statistics of one block][logits]; generic path: the logits.
@@ -396,6 +396,7 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
   }
   const bool unfused = path == PATH_MFMA_UNFUSED;
   float* logits = unfused ? (float*)((char*)ws + packed_ws_bytes(c) + stats_bytes(c, B)) : (float*)ws;
+  if (unfused) a.ldw = (a.m + a.Bn + 3) / 4 * 4;      // whole groups of four for the MFMA form of Eq. 4
   if (unfused) {
     KTimer t(K_CONV_MFMA, s);
     HIP_TRY(launch_conv_logits_mfma(a, ws, logits, s), "conv launch");

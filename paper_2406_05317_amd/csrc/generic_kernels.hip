@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void conv_logits_generic_k(StepArgs a, fl
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       const int j = j0 + tj * 4 + jj;
-      if (j < Tn) logits[((int64_t)ch * a.M + i) * Tn + j] = acc[ii][jj] + bias;
+      if (j < Tn) logits[((int64_t)ch * a.M + i) * (a.ldw ? a.ldw : Tn) + j] = acc[ii][jj] + bias;
     }
   }
 }
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void conv_logits_generic_k(StepArgs a, fl
 __global__ __launch_bounds__(kThreads) void normalise_generic_k(StepArgs a, float* logits) {
   __shared__ float red[kWaves];
   const int Tn = a.m + a.Bn;
-  float* row = logits + ((int64_t)blockIdx.y * a.M + blockIdx.x) * Tn;
+  float* row = logits + ((int64_t)blockIdx.y * a.M + blockIdx.x) * (a.ldw ? a.ldw : Tn);
   if (a.norm == 0) {
     float mx = -INFINITY;
     for (int j = threadIdx.x; j < Tn; j += kThreads) mx = fmaxf(mx, row[j]);
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void mix_generic_k(StepArgs a, const floa
   __shared__ float red[kWaves];
   const int Tn = a.m + a.Bn;
   const int i = blockIdx.x, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
-  const float* wr = w + ((int64_t)ch * a.M + i) * Tn;
+  const float* wr = w + ((int64_t)ch * a.M + i) * (a.ldw ? a.ldw : Tn);
   float mx = 0.f, z = 1.f;
   if (raw) {
     if (a.norm == 0) {
@@ -271,11 +271,12 @@ __device__ __forceinline__ bool slot_protected(const StepArgs& a, int ch, int i)
 }
 __global__ __launch_bounds__(kThreads) void protect_logits_generic_k(StepArgs a, float* logits) {
   const int Tn = a.m + a.Bn, ch = blockIdx.y;
-  float* rows = logits + (int64_t)ch * a.M * Tn;
+  const int ld = a.ldw ? a.ldw : Tn;
+  float* rows = logits + (int64_t)ch * a.M * ld;
   for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < (int64_t)a.M * a.m;
        e += (int64_t)gridDim.x * kThreads) {
     const int i = (int)(e / a.m), j = (int)(e % a.m);
-    if (slot_protected(a, ch, j)) rows[(int64_t)i * Tn + j] = -INFINITY;
+    if (slot_protected(a, ch, j)) rows[(int64_t)i * ld + j] = -INFINITY;
   }
 }
 // ... and the rows of live protected slots are carried over from the old cache.

@@ -36,6 +36,7 @@ struct StepArgs {
   const uint32_t* protect;     // protected-slot bits (see lococo_cache), or null
   int64_t protect_stride;      // words between chains' masks, 0 = shared
   float* colsum;               // accumulated attention per slot [chains, M] (see lococo_cache), or null
+  int32_t ldw;                 // elements between the rows of a logits / weights array [chains, M, .]; 0 = m + Bn
 };
 
 // Arguments of the fused compression kernel: `n_steps` consecutive compress steps of the scan in

@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kThreads, KV ? 1 : 2) void conv_logits_mfma_k(StepA
       for (int i = 0; i < 16; ++i) {
         const int s = s0 + wy * 64 + sb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
         if (s < a.M && p < Tn)
-          out[((int64_t)ch * a.M + s) * Tn + p] = acc[sb][pb][i] + (bias ? bf16_val(bias[s]) : 0.f);
+          out[((int64_t)ch * a.M + s) * (a.ldw ? a.ldw : Tn) + p] = acc[sb][pb][i] + (bias ? bf16_val(bias[s]) : 0.f);
       }
     }
 }
@@ -619,10 +619,13 @@ struct OpWn {              // normalised mixing rows, fp32 [chain, M, Tn]; prote
 struct OpWrows {           // normalised mixing rows fp32 [chain, M, Tn], as rows (contraction along them);
   static constexpr bool kMajor = false;      // rounded to bf16 like the probabilities of the fused kernel
   static constexpr int kParts = 1;
-  Dims s; const float* w;
+  Dims s; const float* w; int ld;            // ld: row stride, a multiple of 4 (the columns T .. ld hold nothing)
   __device__ void load4(float (&v)[4], int z, int r, int c) const {
     const bool ok = r < s.M && c < s.Tn;
-    from_f32x4(v, w + ((int64_t)z * s.M + (ok ? r : 0)) * s.Tn + (ok ? c : 0), ok);
+    from_f32x4(v, w + ((int64_t)z * s.M + (ok ? r : 0)) * ld + (ok ? c : 0), ok);
+#pragma unroll
+    for (int e = 1; e < 4; ++e)
+      if (c + e >= s.Tn) v[e] = 0.f;
   }
 };
 
@@ -807,11 +810,11 @@ hipError_t launch_bwd_mix_dw_mfma(const BwdArgs& g, hipStream_t s) {
 
 // Eq. 4a / 4b of the forward step from normalised rows: [new_K | new_V][i] = sum_j w[i, j] [Yk | Yv][j]
 bool mix_mfma_fits(const StepArgs& a, const float* w) {
-  return a.d == kD && (a.m + a.Bn) % 4 == 0 && ((uintptr_t)w & 15) == 0;
+  return a.d == kD && (a.ldw ? a.ldw : a.m + a.Bn) % 4 == 0 && ((uintptr_t)w & 15) == 0;
 }
 hipError_t launch_mix_mfma(const StepArgs& a, const float* w, hipStream_t s) {
   const Dims dm = dims_of(a);
-  return launch_gemm(OpWrows{dm, w}, OpY<true, 2>{dm, a.cache_k, a.cache_v, a.k, a.v, false},
+  return launch_gemm(OpWrows{dm, w, a.ldw ? a.ldw : dm.Tn}, OpY<true, 2>{dm, a.cache_k, a.cache_v, a.k, a.v, false},
                      OutNewCache{dm, (uint16_t*)a.new_k, (uint16_t*)a.new_v}, a.M, 2 * a.d, dm.Tn,
                      a.batch * a.Hkv, s);
 }

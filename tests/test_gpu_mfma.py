@@ -264,6 +264,9 @@ def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
     dict(M=128, P=256, n_dec=16),                          # 32-row tiles, T = 129 = 4 tiles + one position
     dict(M=256, P=512, n_dec=12, n_q_heads=8, n_kv_heads=4),    # grouped query heads
     dict(M=128, P=100, n_dec=40),                          # decode starts with a partly filled cache: 28 fills, 12 compress steps
+    # the unfused MFMA path: T = M + 1 is odd, so the logits rows are padded to a multiple of 4
+    dict(M=128, P=256, n_dec=14, conv_in=1, conv_width=21, norm=1, bias_sigma=0.5, impl=0),
+    dict(M=96, P=200, n_dec=10, conv_width=9, n_q_heads=8, n_kv_heads=2, impl=0),
 ])
 def test_mfma_decode_after_prefill(case):
     """Generation stage: prefill in blocks, then one token at a time (segment steps with B = 1,
@@ -273,7 +276,7 @@ def test_mfma_decode_after_prefill(case):
     covers long generations."""
     from paper_2406_05317_amd import binding as lb
     case = dict(case)
-    P, n_dec = case.pop("P"), case.pop("n_dec")
+    P, n_dec, impl = case.pop("P"), case.pop("n_dec"), case.pop("impl", MFMA)
     w = _w(L=P + n_dec, B=128, **case)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
@@ -283,8 +286,9 @@ def test_mfma_decode_after_prefill(case):
                                     cache=(ck, cv, ln), nthreads=16)
     want = (np.concatenate([o1, o2], 2), ck, cv, ln)
 
-    cfg = lb.config_for(w, impl=MFMA)
-    qd, kd, vd, cwd, cbd = (t.cuda() for t in (q, k, v, cw, cb))
+    cfg = lb.config_for(w, impl=impl)
+    qd, kd, vd, cwd = (t.cuda() for t in (q, k, v, cw))
+    cbd = None if cb is None else cb.cuda()
     od = torch.full_like(qd, float("nan"))
     cache = lb.Cache(cfg)
     ws = lb.workspace(cfg, P, w.B, True)
