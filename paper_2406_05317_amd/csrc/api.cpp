@@ -373,25 +373,13 @@ lococo_status enqueue_repack(const lococo_config* c, Path path, const StepArgs& 
   return LOCOCO_OK;
 }
 
-// Enqueue fill or compress of one block and update the host-side state.
-// `B`: the block length the workspace was laid out for (a.Bn may be a shorter last block).
-lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, lococo_cache* ca,
-                             void* ws, int32_t B, hipStream_t s) {
-  if (a.m + a.Bn <= a.M) {
-    a.new_k = ca->k[ca->cur];
-    a.new_v = ca->v[ca->cur];
-    KTimer t(K_FILL, s);
-    HIP_TRY(launch_fill_generic(c->dtype, a, s), "fill launch");
-    ca->len = a.m + a.Bn;
-    return LOCOCO_OK;
-  }
-  a.new_k = ca->k[ca->cur ^ 1];
-  a.new_v = ca->v[ca->cur ^ 1];
+// Enqueue Eq. 5, Eq. 6 and Eq. 4 of one block: from a.cache_k / a.cache_v (a.m live slots) and the block
+// into a.new_k / a.new_v.  `B`: the block length the workspace was laid out for (a.Bn may be a shorter
+// last block).
+lococo_status enqueue_compress(const lococo_config* c, Path path, StepArgs a, void* ws, int32_t B, hipStream_t s) {
   if (path == PATH_MFMA) {
     KTimer t(K_COMPRESS_MFMA, s);
     HIP_TRY(launch_compress_mfma(a, ws, filter_banks(c), cu_count(), s), "compress launch");
-    ca->cur ^= 1;
-    ca->len = a.M;
     return LOCOCO_OK;
   }
   const bool unfused = path == PATH_MFMA_UNFUSED;
@@ -417,6 +405,24 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
     HIP_TRY(launch_mix_generic(c->dtype, a, logits, 0, s), "mix launch");
   }
   if (a.protect) HIP_TRY(launch_protect_rows_generic(c->dtype, a, s), "protect launch");
+  return LOCOCO_OK;
+}
+
+// Enqueue fill or compress of one block and update the host-side state.
+lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, lococo_cache* ca,
+                             void* ws, int32_t B, hipStream_t s) {
+  if (a.m + a.Bn <= a.M) {
+    a.new_k = ca->k[ca->cur];
+    a.new_v = ca->v[ca->cur];
+    KTimer t(K_FILL, s);
+    HIP_TRY(launch_fill_generic(c->dtype, a, s), "fill launch");
+    ca->len = a.m + a.Bn;
+    return LOCOCO_OK;
+  }
+  a.new_k = ca->k[ca->cur ^ 1];
+  a.new_v = ca->v[ca->cur ^ 1];
+  lococo_status st = enqueue_compress(c, path, a, ws, B, s);
+  if (st) return st;
   ca->cur ^= 1;
   ca->len = a.M;
   return LOCOCO_OK;
@@ -526,7 +532,7 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
   if (L < 0 || B <= 0) return fail(LOCOCO_EINVAL, "need L >= 0 and B > 0");
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
-  if (history && path == PATH_MFMA)
+  if (history && path != PATH_GENERIC)
     *out = history_ws_bytes(cfg, path, B, (L + B - 1) / B, L);   // every block may compress
   else
     *out = step_ws_bytes(cfg, path, B);
@@ -640,19 +646,19 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   int64_t n_compress = 0, n_fill = 0;
   for (const auto& sg : plan) n_compress += sg.branch;
   while (n_fill < n && plan[(size_t)n_fill].branch == 0) ++n_fill;
-  if (path == PATH_MFMA && any_compress && workspace &&
+  if (path != PATH_GENERIC && any_compress && workspace &&
       ws_bytes >= history_ws_bytes(cfg, path, B, n_compress, L)) {
     // Batched-attention schedule: run the fill / compress recurrence first, keeping every
     // cache state, then one attention launch over all blocks, then publish the last state.
     hipStream_t s = (hipStream_t)stream;
     const size_t slot = align_up(state_bytes(cfg), 256);
-    char* sync_ws = (char*)workspace + filter_ws_bytes(cfg);
+    char* sync_ws = (char*)workspace + filter_ws_bytes(cfg);      // fused path only
     float* seq_stats = (float*)((char*)workspace + step_ws_bytes(cfg, path, B));
     char* hist_k = (char*)seq_stats + stats_bytes(cfg, L);
     char* hist_v = hist_k + (size_t)n_compress * slot;
     const void* src_k = tmp.k[tmp.cur];
     const void* src_v = tmp.v[tmp.cur];
-    const bool one_launch = scan_in_one_launch(cfg);
+    const bool one_launch = path == PATH_MFMA && scan_in_one_launch(cfg);
     int64_t step = 0;
     for (const auto& sg : plan) {
       StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
@@ -691,9 +697,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         a.cache_v = src_v;
         a.new_k = hist_k + (size_t)step * slot;
         a.new_v = hist_v + (size_t)step * slot;
-        KTimer t(K_COMPRESS_MFMA, s);
-        HIP_TRY(launch_compress_mfma(a, workspace, filter_banks(cfg), cu_count(), s),
-                "compress launch");
+        if ((st = enqueue_compress(cfg, path, a, workspace, B, s))) return st;
         src_k = a.new_k;
         src_v = a.new_v;
         ++step;
