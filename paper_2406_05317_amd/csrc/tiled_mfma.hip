@@ -142,67 +142,99 @@ __global__ __launch_bounds__(kThreads) void bwd_split_dl_k(const float* dl, uint
 // 128 slots.  A = filters (rows: slots), B = keys (lane: position): a lane stores 32 consecutive
 // positions of one slot per instruction.  KV = 1: the convolution reads [K | V], 256 channels.
 template <int KV>
-__global__ __launch_bounds__(kThreads, KV ? 1 : 2) void conv_logits_mfma_k(StepArgs a, const uint16_t* wt, float* out) {
+__global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k(StepArgs a, const uint16_t* wt,
+                                                                                 float* out) {
   extern __shared__ __align__(16) unsigned char smem[];
+  // 8 waves per compute unit either way: two workgroups of 4 (each wave 64 slots x 64 positions), or,
+  // where the tiles of 256 channels leave LDS for one workgroup only, one of 8 (64 slots x 32 positions
+  // per wave), so that every SIMD has a second wave to run while one waits for its fragments
+  constexpr int NT = KV ? 512 : 256, PB = KV ? 1 : 2;
   constexpr int C = KV ? 2 * kD : kD, ROW = C * 2 + 16, CH16 = C / 8;   // channels, LDS row bytes, 16-byte chunks per row
   const int KW = a.k_width, pad = (KW - 1) / 2, Tn = a.m + a.Bn;
   const int xrows = kTile + KW - 1;
   unsigned char* Xs = smem;
   unsigned char* Ws = smem + xrows * ROW;
   const int p0 = blockIdx.x * kTile, s0 = blockIdx.y * kTile, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
+  const int wy = w / (NT / 128), wx = w % (NT / 128);     // wave: slots 64 wy .., positions 32 PB wx ..
   const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * C : 0);
 
-  for (int item = tid; item < xrows * CH16; item += kThreads) {
-    const int row = item / CH16, c16 = item % CH16, p = p0 - pad + row;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (p >= 0 && p < Tn)
-      v = *(const u32x4*)((c16 < 16 ? x_row(a, b, hkv, p) : v_row(a, b, hkv, p)) + (c16 & 15) * 8);
-    *(u32x4*)(Xs + row * ROW + c16 * 16) = v;
-  }
-  constexpr int WPER = kTile * CH16 / kThreads;
-  u32x4 wreg[WPER];
-  auto load_w = [&](int t) {
+  {
+    // every load is issued before the first store: one memory latency for the whole tile, not one per chunk
+    constexpr int XPER = ((kTile + 30) * CH16 + NT - 1) / NT;
+    u32x4 xr[XPER];
 #pragma unroll
-    for (int i = 0; i < WPER; ++i) {
-      const int item = tid + i * kThreads, row = item / CH16, c16 = item % CH16, s = s0 + row;
+    for (int i = 0; i < XPER; ++i) {
+      const int item = tid + i * NT, row = item / CH16, c16 = item % CH16, p = p0 - pad + row;
       const u32x4 z = {0u, 0u, 0u, 0u};
-      wreg[i] = s < a.M ? *(const u32x4*)(wtb + ((int64_t)t * a.M + s) * C + c16 * 8) : z;
+      xr[i] = (item < xrows * CH16 && p >= 0 && p < Tn)
+                  ? *(const u32x4*)((c16 < 16 ? x_row(a, b, hkv, p) : v_row(a, b, hkv, p)) + (c16 & 15) * 8)
+                  : z;
     }
+#pragma unroll
+    for (int i = 0; i < XPER; ++i) {
+      const int item = tid + i * NT, row = item / CH16, c16 = item % CH16;
+      if (item < xrows * CH16) *(u32x4*)(Xs + row * ROW + c16 * 16) = xr[i];
+    }
+  }
+  constexpr int WPER = kTile * CH16 / NT;
+  u32x4 wreg[WPER];
+  // element offsets of this thread's chunks inside a tap's matrix, computed once; a tap adds a uniform
+  // base.  A slot past M reads the last slot instead: its outputs are never stored, and nothing
+  // touches the loaded values before they go to LDS, so the loads stay in flight under the MFMAs.
+  uint32_t woff[WPER];
+#pragma unroll
+  for (int i = 0; i < WPER; ++i) {
+    const int item = tid + i * NT, row = item / CH16, c16 = item % CH16, s = s0 + row;
+    woff[i] = (uint32_t)((s < a.M ? s : a.M - 1) * C + c16 * 8);
+  }
+  auto load_w = [&](int t) {
+    const uint16_t* wtap = wtb + (int64_t)t * a.M * C;
+#pragma unroll
+    for (int i = 0; i < WPER; ++i) wreg[i] = *(const u32x4*)(wtap + woff[i]);
   };
   auto store_w = [&]() {
 #pragma unroll
     for (int i = 0; i < WPER; ++i) {
-      const int item = tid + i * kThreads, row = item / CH16, c16 = item % CH16;
+      const int item = tid + i * NT, row = item / CH16, c16 = item % CH16;
       *(u32x4*)(Ws + row * ROW + c16 * 16) = wreg[i];
     }
   };
-  f32x16 acc[2][2];                       // [slot block][position block]
-  zero_acc(acc);
+  f32x16 acc[2][PB];                      // [slot block][position block]
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[sb][pb][i] = 0.f;
   load_w(0);
   for (int t = 0; t < KW; ++t) {
     __syncthreads();                      // the previous tap's reads are done (first time: X is staged)
     store_w();
-    if (t + 1 < KW) load_w(t + 1);
     __syncthreads();
+    if (t + 1 < KW) load_w(t + 1);        // in flight under this tap's MFMAs
     const unsigned char* wl = Ws + (wy * 64 + l31) * ROW + lh * 16;
-    const unsigned char* xl = Xs + (wx * 64 + l31 + t) * ROW + lh * 16;
+    const unsigned char* xl = Xs + (wx * 32 * PB + l31 + t) * ROW + lh * 16;
 #pragma unroll
     for (int kc = 0; kc < C / 16; ++kc) {
-      const bf16x8 a0 = frag(wl + kc * 32), a1 = frag(wl + 32 * ROW + kc * 32);
-      const bf16x8 b0 = frag(xl + kc * 32), b1 = frag(xl + 32 * ROW + kc * 32);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+      bf16x8 fa[2], fb[PB];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) fa[sb] = frag(wl + sb * 32 * ROW + kc * 32);
+#pragma unroll
+      for (int pb = 0; pb < PB; ++pb) fb[pb] = frag(xl + pb * 32 * ROW + kc * 32);
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+          acc[sb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[sb], fb[pb], acc[sb][pb], 0, 0, 0);
     }
   }
   const uint16_t* bias = a.conv_b ? (const uint16_t*)a.conv_b + hkv * a.b_head_stride : nullptr;
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-    for (int pb = 0; pb < 2; ++pb) {
-      const int p = p0 + wx * 64 + pb * 32 + l31;
+    for (int pb = 0; pb < PB; ++pb) {
+      const int p = p0 + wx * 32 * PB + pb * 32 + l31;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int s = s0 + wy * 64 + sb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
@@ -250,17 +282,25 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_k(BwdArgs g, const ui
       *(u32x4*)(Ws + row * kRow + c16 * 16) = wreg[i];
     }
   };
-  auto stage_d = [&](int sc) {
-    for (int item = tid; item < drows * 8; item += kThreads) {
-      const int row = item >> 3, c16 = item & 7, q = p0 + row - (KW - 1) + pad;
-      u32x4 vh = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
-      if (q >= 0 && q < Tn) {
-        const int64_t o = ((int64_t)ch * Tn + q) * Mp + sc * kChunk + c16 * 8;
-        vh = *(const u32x4*)(dhi + o);
-        vl = *(const u32x4*)(dlo + o);
+  auto stage_d = [&](int sc) {            // all loads before the first store: one memory latency per tile
+    constexpr int DPER = ((kTile + 30) * 8 + kThreads - 1) / kThreads;
+    u32x4 vh[DPER], vl[DPER];
+#pragma unroll
+    for (int i = 0; i < DPER; ++i) {
+      const int item = tid + i * kThreads, row = item >> 3, c16 = item & 7, q = p0 + row - (KW - 1) + pad;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      const bool in = item < drows * 8 && q >= 0 && q < Tn;
+      const int64_t o = ((int64_t)ch * Tn + (in ? q : 0)) * Mp + sc * kChunk + c16 * 8;
+      vh[i] = in ? *(const u32x4*)(dhi + o) : z;
+      vl[i] = in ? *(const u32x4*)(dlo + o) : z;
+    }
+#pragma unroll
+    for (int i = 0; i < DPER; ++i) {
+      const int item = tid + i * kThreads, row = item >> 3, c16 = item & 7;
+      if (item < drows * 8) {
+        *(u32x4*)(Dh + row * kRow64 + c16 * 16) = vh[i];
+        *(u32x4*)(Dl + row * kRow64 + c16 * 16) = vl[i];
       }
-      *(u32x4*)(Dh + row * kRow64 + c16 * 16) = vh;
-      *(u32x4*)(Dl + row * kRow64 + c16 * 16) = vl;
     }
   };
   f32x16 acc[2][2];                       // [position block][channel block]
@@ -753,7 +793,7 @@ static hipError_t launch_logits(const StepArgs& a, const void* wt, float* logits
     attr_set = true;
   }
   hipLaunchKernelGGL(conv_logits_mfma_k<KV>, dim3((Tn + kTile - 1) / kTile, (a.M + kTile - 1) / kTile, a.batch * a.Hkv),
-                     dim3(kThreads), lds, s, a, (const uint16_t*)wt, logits);
+                     dim3(KV ? 512 : 256), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
 hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
