@@ -466,21 +466,31 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_gemm_k(OpA A, OpB B, Out out,
   if (out.skip(z, i0, j0)) return;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
 
-  float ra[8][4], rb[8][4];
+  // A chunk is fetched as raw bits (bf16 sources: 8 bytes per group of four, fp32 sources: 16) with the
+  // number of valid elements beside them; nothing reads the registers before the chunk is staged, so
+  // the loads stay in flight under the MFMAs of the chunk before.
+  u32x4 ra[8], rb[8];
+  int na[8], nb[8];
   auto load = [&](int k0) {
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int gidx = tid + n * kThreads;
-      if (OpA::kMajor) A.load4(ra[n], z, k0 + (gidx >> 5), i0 + (gidx & 31) * 4);
-      else A.load4(ra[n], z, i0 + (gidx >> 4), k0 + (gidx & 15) * 4);
-      if (OpB::kMajor) B.load4(rb[n], z, k0 + (gidx >> 5), j0 + (gidx & 31) * 4);
-      else B.load4(rb[n], z, j0 + (gidx >> 4), k0 + (gidx & 15) * 4);
+      na[n] = OpA::kMajor ? A.load4(ra[n], z, k0 + (gidx >> 5), i0 + (gidx & 31) * 4)
+                          : A.load4(ra[n], z, i0 + (gidx >> 4), k0 + (gidx & 15) * 4);
+      nb[n] = OpB::kMajor ? B.load4(rb[n], z, k0 + (gidx >> 5), j0 + (gidx & 31) * 4)
+                          : B.load4(rb[n], z, j0 + (gidx >> 4), k0 + (gidx & 15) * 4);
     }
   };
   // four values -> 8 bytes of bf16 (round to nearest even), and the rounding errors likewise
-  auto put = [&](unsigned char* base, int parts, bool kmajor, int gidx, const float (&v)[4]) {
+  auto put = [&](unsigned char* base, int parts, bool kmajor, bool bf16_source, int gidx, const u32x4& raw, int nv) {
     unsigned char* at = kmajor ? base + (gidx >> 5) * kRow + (gidx & 31) * 8 : base + (gidx >> 4) * kRow64 + (gidx & 15) * 8;
-    const f32x2 x0 = {v[0], v[1]}, x1 = {v[2], v[3]};
+    if (bf16_source) {                    // already bf16: as it is, or nothing
+      const u32x2 v = {nv ? raw[0] : 0u, nv ? raw[1] : 0u};
+      *(u32x2*)at = v;
+      return;
+    }
+    const f32x2 x0 = {nv > 0 ? __uint_as_float(raw[0]) : 0.f, nv > 1 ? __uint_as_float(raw[1]) : 0.f};
+    const f32x2 x1 = {nv > 2 ? __uint_as_float(raw[2]) : 0.f, nv > 3 ? __uint_as_float(raw[3]) : 0.f};
     const bf16x2 h0 = __builtin_convertvector(x0, bf16x2), h1 = __builtin_convertvector(x1, bf16x2);
     const u32x2 vh = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1)};
     *(u32x2*)at = vh;
@@ -494,8 +504,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_gemm_k(OpA A, OpB B, Out out,
   auto stage = [&]() {
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      put(As, OpA::kParts, OpA::kMajor, tid + n * kThreads, ra[n]);
-      put(Bs, OpB::kParts, OpB::kMajor, tid + n * kThreads, rb[n]);
+      put(As, OpA::kParts, OpA::kMajor, OpA::kBf16, tid + n * kThreads, ra[n], na[n]);
+      put(Bs, OpB::kParts, OpB::kMajor, OpB::kBf16, tid + n * kThreads, rb[n], nb[n]);
     }
   };
   f32x16 acc[2][2];
@@ -505,8 +515,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_gemm_k(OpA A, OpB B, Out out,
   for (int k0 = 0; k0 < K; k0 += kChunk) {
     __syncthreads();
     stage();
-    if (k0 + kChunk < K) load(k0 + kChunk);
     __syncthreads();
+    if (k0 + kChunk < K) load(k0 + kChunk);
 #pragma unroll
     for (int kc = 0; kc < kChunk / 16; ++kc) {
       bf16x8 fa[OpA::kParts][2], fb[OpB::kParts][2];
@@ -551,10 +561,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_gemm_k(OpA A, OpB B, Out out,
     }
 }
 
-// -- operands.  `grouped`: z is a chain and the memory row runs over the rows of all query heads
-// of its group, head-major; otherwise z is (batch entry, query head).  Every width is a multiple
-// of 4 and every base 16-byte aligned (the launcher checks), so a group of four is inside or
-// outside as a whole; the loads are branch-free: an outside group reads element 0 and is zeroed.
+// -- operands.  load4(raw, z, r, c) fetches the raw bits of the four elements (memory row r, offsets
+// c .. c + 3) of batch entry z -- 8 bytes in raw[0], raw[1] from a bf16 tensor (kBf16), 16 bytes from
+// an fp32 one -- and returns how many of them count (0: the group lies outside the tensor; it is
+// then read at element 0 of a valid row, never out of bounds).  It does not touch what it loaded.
+// `grouped`: z is a chain and the memory row runs over the rows of all query heads of its group,
+// head-major; otherwise z is (batch entry, query head).  Every width is a multiple of 4 and every base
+// 16-byte aligned (the launcher checks), so a group of four is inside or outside as a whole.
 struct Dims { int Bn, Tn, d, M, m, Hq, Hkv, group; };
 __device__ __forceinline__ void head_row(const Dims& s, bool grouped, int z, int r, int& b, int& hq, int& rr) {
   if (grouped) {
@@ -567,18 +580,12 @@ __device__ __forceinline__ void head_row(const Dims& s, bool grouped, int z, int
     rr = r;
   }
 }
-__device__ __forceinline__ void from_bf16x4(float (&v)[4], const uint16_t* p, bool ok) {
-  u32x2 u = *(const u32x2*)p;
-  if (!ok) u = u32x2{0u, 0u};
-  v[0] = __uint_as_float(u[0] << 16);
-  v[1] = __uint_as_float(u[0] & 0xffff0000u);
-  v[2] = __uint_as_float(u[1] << 16);
-  v[3] = __uint_as_float(u[1] & 0xffff0000u);
+__device__ __forceinline__ void raw_bf16x4(u32x4& raw, const uint16_t* p) {
+  const u32x2 u = *(const u32x2*)p;
+  raw[0] = u[0];
+  raw[1] = u[1];
 }
-__device__ __forceinline__ void from_f32x4(float (&v)[4], const float* p, bool ok) {
-  const float4 q = *(const float4*)p;
-  v[0] = ok ? q.x : 0.f; v[1] = ok ? q.y : 0.f; v[2] = ok ? q.z : 0.f; v[3] = ok ? q.w : 0.f;
-}
+__device__ __forceinline__ void raw_f32x4(u32x4& raw, const float* p) { raw = *(const u32x4*)p; }
 __device__ __forceinline__ bool is_protected(const uint32_t* protect, int64_t stride, int z, int r, int m) {
   if (!protect) return false;           // uniform
   const int rc = r < m ? r : 0;
@@ -587,34 +594,36 @@ __device__ __forceinline__ bool is_protected(const uint32_t* protect, int64_t st
 
 template <bool KMAJOR>
 struct OpQ {               // query rows, bf16
-  static constexpr bool kMajor = KMAJOR;
+  static constexpr bool kMajor = KMAJOR, kBf16 = true;
   static constexpr int kParts = 1;
   Dims s; View q; bool grouped;
-  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+  __device__ int load4(u32x4& raw, int z, int r, int c) const {
     const bool ok = r < (grouped ? s.group * s.Bn : s.Bn) && c < s.d;
     int b, hq, rr;
     head_row(s, grouped, z, ok ? r : 0, b, hq, rr);
-    from_bf16x4(v, (const uint16_t*)q.p + b * q.sb + hq * q.sh + (int64_t)rr * q.st + (ok ? c : 0), ok);
+    raw_bf16x4(raw, (const uint16_t*)q.p + b * q.sb + hq * q.sh + (int64_t)rr * q.st + (ok ? c : 0));
+    return ok ? 4 : 0;
   }
 };
 template <bool KMAJOR>
 struct OpRowsF32 {         // fp32 [batch, Hq, Bn, width] rows: d_o (width d), ws_p / ws_ds (width Tn)
-  static constexpr bool kMajor = KMAJOR;
+  static constexpr bool kMajor = KMAJOR, kBf16 = false;
   static constexpr int kParts = 2;
   Dims s; const float* p; int width; bool grouped;
-  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+  __device__ int load4(u32x4& raw, int z, int r, int c) const {
     const bool ok = r < (grouped ? s.group * s.Bn : s.Bn) && c < width;
     int b, hq, rr;
     head_row(s, grouped, z, ok ? r : 0, b, hq, rr);
-    from_f32x4(v, p + (((int64_t)b * s.Hq + hq) * s.Bn + rr) * width + (ok ? c : 0), ok);
+    raw_f32x4(raw, p + (((int64_t)b * s.Hq + hq) * s.Bn + rr) * width + (ok ? c : 0));
+    return ok ? 4 : 0;
   }
 };
 template <bool KMAJOR, int WHICH>     // WHICH: 0 keys, 1 values, 2 [keys | values] (width 2 d)
 struct OpY {               // rows of [cache(0:m) ; block], bf16
-  static constexpr bool kMajor = KMAJOR;
+  static constexpr bool kMajor = KMAJOR, kBf16 = true;
   static constexpr int kParts = 1;
   Dims s; const void* cache_k; const void* cache_v; View k, v; bool per_qhead;
-  __device__ void load4(float (&out)[4], int z, int r, int c) const {
+  __device__ int load4(u32x4& raw, int z, int r, int c) const {
     const bool ok = r < s.Tn && c < (WHICH == 2 ? 2 * s.d : s.d);
     const int r2 = ok ? r : 0, c2 = ok ? c : 0;
     int b, hkv;
@@ -628,44 +637,43 @@ struct OpY {               // rows of [cache(0:m) ; block], bf16
         (const uint16_t*)(val ? cache_v : cache_k) + ((int64_t)(b * s.Hkv + hkv) * s.M + (in_cache ? r2 : 0)) * s.d;
     const uint16_t* brow =
         (const uint16_t*)blk.p + b * blk.sb + hkv * blk.sh + (int64_t)(in_cache ? 0 : r2 - s.m) * blk.st;
-    from_bf16x4(out, (in_cache ? crow : brow) + col, ok);
+    raw_bf16x4(raw, (in_cache ? crow : brow) + col);
+    return ok ? 4 : 0;
   }
 };
 template <bool KMAJOR>
 struct OpG {               // gradient of the new cache, fp32 rows [g_k | g_v] of width 2 d
-  static constexpr bool kMajor = KMAJOR;
+  static constexpr bool kMajor = KMAJOR, kBf16 = false;
   static constexpr int kParts = 2;
   Dims s; const float* gk; const float* gv; const uint32_t* protect; int64_t protect_stride; bool mask;
-  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+  __device__ int load4(u32x4& raw, int z, int r, int c) const {
     const bool in = r < s.M && c < 2 * s.d;
     const int r2 = in ? r : 0, c2 = in ? c : 0;
     const bool ok = in && !(mask && is_protected(protect, protect_stride, z, r2, s.m));
-    const float* row = (c2 < s.d ? gk : gv) + ((int64_t)z * s.M + r2) * s.d + (c2 < s.d ? c2 : c2 - s.d);
-    from_f32x4(v, row, ok);
+    raw_f32x4(raw, (c2 < s.d ? gk : gv) + ((int64_t)z * s.M + r2) * s.d + (c2 < s.d ? c2 : c2 - s.d));
+    return ok ? 4 : 0;
   }
 };
 struct OpWn {              // normalised mixing rows, fp32 [chain, M, Tn]; protected slots mix nothing
-  static constexpr bool kMajor = true;
+  static constexpr bool kMajor = true, kBf16 = false;
   static constexpr int kParts = 2;
   Dims s; const float* w; const uint32_t* protect; int64_t protect_stride;
-  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+  __device__ int load4(u32x4& raw, int z, int r, int c) const {
     const bool in = r < s.M && c < s.Tn;
     const int r2 = in ? r : 0, c2 = in ? c : 0;
     const bool ok = in && !is_protected(protect, protect_stride, z, r2, s.m);
-    from_f32x4(v, w + ((int64_t)z * s.M + r2) * s.Tn + c2, ok);
+    raw_f32x4(raw, w + ((int64_t)z * s.M + r2) * s.Tn + c2);
+    return ok ? 4 : 0;
   }
 };
-
 struct OpWrows {           // normalised mixing rows fp32 [chain, M, Tn], as rows (contraction along them);
-  static constexpr bool kMajor = false;      // rounded to bf16 like the probabilities of the fused kernel
+  static constexpr bool kMajor = false, kBf16 = false;   // rounded to bf16 like the probabilities of the fused kernel
   static constexpr int kParts = 1;
   Dims s; const float* w; int ld;            // ld: row stride, a multiple of 4 (the columns T .. ld hold nothing)
-  __device__ void load4(float (&v)[4], int z, int r, int c) const {
+  __device__ int load4(u32x4& raw, int z, int r, int c) const {
     const bool ok = r < s.M && c < s.Tn;
-    from_f32x4(v, w + ((int64_t)z * s.M + (ok ? r : 0)) * ld + (ok ? c : 0), ok);
-#pragma unroll
-    for (int e = 1; e < 4; ++e)
-      if (c + e >= s.Tn) v[e] = 0.f;
+    raw_f32x4(raw, w + ((int64_t)z * s.M + (ok ? r : 0)) * ld + (ok ? c : 0));
+    return ok ? (s.Tn - c < 4 ? s.Tn - c : 4) : 0;
   }
 };
 
