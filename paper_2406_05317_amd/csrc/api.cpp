@@ -393,6 +393,14 @@ lococo_status enqueue_compress(const lococo_config* c, Path path, StepArgs a, vo
     HIP_TRY(launch_conv_logits_generic(c->dtype, a, logits, s), "conv launch");
   }
   if (a.protect) HIP_TRY(launch_protect_logits_generic(a, logits, s), "protect launch");
+  if (unfused && mixnorm_mfma_fits(a, logits)) {       // Eq. 6 inside the mixing kernel: the logits are read once
+    {
+      KTimer t(K_MIX_MFMA, s);
+      HIP_TRY(launch_mixnorm_mfma(a, logits, s), "mix launch");
+    }
+    if (a.protect) HIP_TRY(launch_protect_rows_generic(c->dtype, a, s), "protect launch");
+    return LOCOCO_OK;
+  }
   {
     KTimer t(K_NORM_GENERIC, s);
     HIP_TRY(launch_normalise_generic(a, logits, s), "normalise launch");

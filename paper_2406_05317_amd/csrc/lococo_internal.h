@@ -185,6 +185,9 @@ size_t packed_filter_bytes(int M, int conv_width, int conv_in, int banks);
 // Eq. 4a / 4b from normalised rows w [chains, M, T] into a.new_k / a.new_v (bf16); needs mix_mfma_fits
 bool mix_mfma_fits(const StepArgs& a, const float* w);
 hipError_t launch_mix_mfma(const StepArgs& a, const float* w, hipStream_t s);
+// Eq. 6 and Eq. 4a / 4b in one kernel, from raw logits [chains, M, ldw] into a.new_k / a.new_v (bf16)
+bool mixnorm_mfma_fits(const StepArgs& a, const float* logits);
+hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream_t s);
 // dX into d_k / d_cache_k (added) and dWc into d_conv_w (added), from the logit gradient in g.ws_w
 hipError_t launch_bwd_conv_mfma(const BwdArgs& g, int banks, void* ws, hipStream_t s);
 // the plain contractions of the pass (fp32 operands enter as two bf16 halves): same inputs,

@@ -442,6 +442,167 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_k(BwdArgs g, const ui
 }
 
 
+// ---- Eq. 6 and Eq. 4a / 4b of the unfused forward path in one kernel: from raw logits fp32
+// [chain, M, ld] to the bf16 rows of the next cache, [new_K | new_V][i] = sum_j w[i, j] [Yk | Yv][j]
+// with w the normalised row i.  One workgroup owns 128 slots x all 256 columns of a chain and walks
+// the positions in chunks of 64: a thread holds four positions of eight rows, sixteen threads share
+// a row and keep its running reference and sum (softmax: the reference moves only when the row
+// maximum outgrows it by 8, so the accumulators are rescaled almost never; relu-sum: a plain sum),
+// the weights go to LDS as bf16 (what the fused kernel does with its probabilities), [K | V] rows are
+// read down their rows through transposing reads.  The division by the row sum comes last.
+// NORM: 0 softmax, 1 relu / (sum + eps).
+constexpr float kLog2e = 1.4426950408889634f;
+// Reductions over the 16 lanes that share a row, on the VALU (DPP), no LDS round trip: inside quads,
+// then lane i <-> 7 - i of each 8, then lane i <-> 15 - i of each 16; every lane ends with the result.
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float max16(float v) {
+  v = fmaxf(v, dpp<0xB1>(v));           // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp<0x4E>(v));           // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp<0x141>(v));          // row_half_mirror
+  return fmaxf(v, dpp<0x140>(v));       // row_mirror
+}
+__device__ __forceinline__ float sum16(float v) {
+  v += dpp<0xB1>(v);
+  v += dpp<0x4E>(v);
+  v += dpp<0x141>(v);
+  return v + dpp<0x140>(v);
+}
+constexpr int kYRow = 2 * kD * 2 + 16;             // bytes of a staged [K | V] row
+template <int NORM>
+__global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const float* logits, int ld) {
+  __shared__ __align__(16) unsigned char Ps[kTile * kRow64];      // weights of the chunk [slot][position], bf16
+  __shared__ __align__(16) unsigned char Ys[kChunk * kYRow];      // [position][K | V columns]
+  __shared__ __align__(16) float alpha_s[kTile];                  // rescale factor per slot for this chunk
+  __shared__ __align__(16) float sum_s[kTile];                    // final row sums
+  __shared__ int any_rescale[2];                                  // by chunk parity: reset two barriers after its last read
+  const int Tn = a.m + a.Bn;
+  const int s0 = blockIdx.x * kTile, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
+  const int c4 = tid & 15;                           // this thread's four positions inside a chunk: 4 c4 ..
+  const float* lrow[8];
+#pragma unroll
+  for (int n = 0; n < 8; ++n) {
+    const int srow = s0 + (tid >> 4) + 16 * n;       // a slot past M reads the last one; it is never stored
+    lrow[n] = logits + ((int64_t)ch * a.M + (srow < a.M ? srow : a.M - 1)) * ld;
+  }
+  float m_run[8], l_part[8];
+#pragma unroll
+  for (int n = 0; n < 8; ++n) { m_run[n] = -1e30f; l_part[n] = 0.f; }
+
+  f32x16 acc[2][4];                                  // [slot block][column block]
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 4; ++y)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[x][y][i] = 0.f;
+
+  u32x4 lreg[8], yreg[8];
+  auto load = [&](int j0) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n)             // a group past T reads the row's first group (ld >= 4) and counts for nothing
+      lreg[n] = *(const u32x4*)(lrow[n] + (j0 + c4 * 4 < Tn ? j0 + c4 * 4 : 0));
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int item = tid + n * kThreads, row = item >> 5, c16 = item & 31, j = j0 + row;
+      const int jc = j < Tn ? j : 0;
+      yreg[n] = *(const u32x4*)((c16 < 16 ? x_row(a, b, hkv, jc) : v_row(a, b, hkv, jc)) + (c16 & 15) * 8);
+    }
+  };
+  const int tro = tr_lane_offset(l, kYRow);
+  load(0);
+  for (int j0 = 0; j0 < Tn; j0 += kChunk) {
+    const int par = (j0 / kChunk) & 1;
+    if (tid == 0) any_rescale[par] = 0;
+    __syncthreads();                                 // the previous chunk's fragments have been read
+    // ---- this chunk's weights
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x = __uint_as_float(lreg[n][e]);
+        v[e] = j0 + c4 * 4 + e < Tn ? x : -INFINITY;
+      }
+      float al = 1.f;
+      if (NORM == 0) {
+        const float mx = max16(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+        if (mx > m_run[n] + 8.f) {                   // same for the sixteen threads of the row
+          al = __builtin_amdgcn_exp2f((m_run[n] - mx) * kLog2e);
+          m_run[n] = mx;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_exp2f((v[e] - m_run[n]) * kLog2e);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+      }
+      l_part[n] = l_part[n] * al + (v[0] + v[1]) + (v[2] + v[3]);
+      const f32x2 x0 = {v[0], v[1]}, x1 = {v[2], v[3]};
+      const bf16x2 h0 = __builtin_convertvector(x0, bf16x2), h1 = __builtin_convertvector(x1, bf16x2);
+      const u32x2 pk = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1)};
+      const int row = (tid >> 4) + 16 * n;
+      *(u32x2*)(Ps + row * kRow64 + c4 * 8) = pk;
+      if (NORM == 0 && c4 == 0) {
+        alpha_s[row] = al;
+        if (al != 1.f) any_rescale[par] = 1;
+      }
+    }
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int item = tid + n * kThreads, row = item >> 5, c16 = item & 31;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      *(u32x4*)(Ys + row * kYRow + c16 * 16) = j0 + row < Tn ? yreg[n] : z;
+    }
+    __syncthreads();
+    if (j0 + kChunk < Tn) load(j0 + kChunk);         // in flight under the MFMAs
+    if (NORM == 0 && any_rescale[par]) {             // rare: a reference moved
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float al = alpha_s[wy * 64 + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
+#pragma unroll
+          for (int y = 0; y < 4; ++y) acc[x][y][i] *= al;
+        }
+    }
+#pragma unroll
+    for (int kc = 0; kc < kChunk / 16; ++kc) {
+      bf16x8 fp[2], fy[4];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) fp[x] = frag(Ps + (wy * 64 + x * 32 + l31) * kRow64 + (kc * 16 + lh * 8) * 2);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) fy[y] = frag_tr(Ys + tro + kc * 16 * kYRow + (wx * 128 + y * 32) * 2, kYRow);
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp[x], fy[y], acc[x][y], 0, 0, 0);
+    }
+  }
+  // ---- row sums: over the sixteen threads of a row, then to everybody
+#pragma unroll
+  for (int n = 0; n < 8; ++n) {
+    const float t = sum16(l_part[n]);
+    if (c4 == 0) sum_s[(tid >> 4) + 16 * n] = t;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = wy * 64 + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), slot = s0 + row;
+      if (slot >= a.M) continue;
+      const float inv = 1.0f / (NORM == 0 ? sum_s[row] : sum_s[row] + a.eps);
+      uint16_t* dst = (uint16_t*)(wx ? a.new_v : a.new_k) + ((int64_t)ch * a.M + slot) * kD;
+#pragma unroll
+      for (int y = 0; y < 4; ++y) dst[y * 32 + l31] = (uint16_t)bf16_rne(acc[x][y][i] * inv);
+    }
+}
+
 // ---- the seven plain contractions of the pass (attention: scores, dP, dq, dYk, dYv; Eq. 4: dw and
 // the gradient of [K | V]) as one batched GEMM kernel, C[i, j] = sum_k A(i, k) B(j, k).
 //
@@ -865,6 +1026,20 @@ hipError_t launch_mix_mfma(const StepArgs& a, const float* w, hipStream_t s) {
   return launch_gemm(OpWrows{dm, w, a.ldw ? a.ldw : dm.Tn}, OpY<true, 2>{dm, a.cache_k, a.cache_v, a.k, a.v, false},
                      OutNewCache{dm, (uint16_t*)a.new_k, (uint16_t*)a.new_v}, a.M, 2 * a.d, dm.Tn,
                      a.batch * a.Hkv, s);
+}
+
+
+// Eq. 6 + Eq. 4a / 4b of the forward step from raw logits (rows ld floats apart); needs mixnorm_mfma_fits
+bool mixnorm_mfma_fits(const StepArgs& a, const float* logits) {
+  const int ld = a.ldw ? a.ldw : a.m + a.Bn;
+  return a.d == kD && ld % 4 == 0 && ((uintptr_t)logits & 15) == 0 && (a.norm == 0 || a.norm == 1);
+}
+hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream_t s) {
+  const int ld = a.ldw ? a.ldw : a.m + a.Bn;
+  const dim3 grid((a.M + kTile - 1) / kTile, a.batch * a.Hkv);
+  if (a.norm == 0) hipLaunchKernelGGL(mixnorm_mfma_k<0>, grid, dim3(kThreads), 0, s, a, logits, ld);
+  else hipLaunchKernelGGL(mixnorm_mfma_k<1>, grid, dim3(kThreads), 0, s, a, logits, ld);
+  return hipGetLastError();
 }
 
 // d[Yk | Yv][j] += sum over the unprotected slots of w[i, j] [g_k | g_v][i]
