@@ -471,39 +471,41 @@ __device__ __forceinline__ float sum16(float v) {
   return v + dpp<0x140>(v);
 }
 constexpr int kYRow = 2 * kD * 2 + 16;             // bytes of a staged [K | V] row
-template <int NORM>
+// SLOTS: 128 slots per workgroup, or 64 where that is what it takes to give every compute unit one.
+template <int NORM, int SLOTS>
 __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const float* logits, int ld) {
-  __shared__ __align__(16) unsigned char Ps[kTile * kRow64];      // weights of the chunk [slot][position], bf16
+  constexpr int RPT = SLOTS / 16, SB = SLOTS / 64;      // rows of logits per thread; 32-slot blocks per wave
+  __shared__ __align__(16) unsigned char Ps[SLOTS * kRow64];      // weights of the chunk [slot][position], bf16
   __shared__ __align__(16) unsigned char Ys[kChunk * kYRow];      // [position][K | V columns]
-  __shared__ __align__(16) float alpha_s[kTile];                  // rescale factor per slot for this chunk
-  __shared__ __align__(16) float sum_s[kTile];                    // final row sums
+  __shared__ __align__(16) float alpha_s[SLOTS];                  // rescale factor per slot for this chunk
+  __shared__ __align__(16) float sum_s[SLOTS];                    // final row sums
   __shared__ int any_rescale[2];                                  // by chunk parity: reset two barriers after its last read
   const int Tn = a.m + a.Bn;
-  const int s0 = blockIdx.x * kTile, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int s0 = blockIdx.x * SLOTS, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
   const int c4 = tid & 15;                           // this thread's four positions inside a chunk: 4 c4 ..
-  const float* lrow[8];
+  const float* lrow[RPT];
 #pragma unroll
-  for (int n = 0; n < 8; ++n) {
+  for (int n = 0; n < RPT; ++n) {
     const int srow = s0 + (tid >> 4) + 16 * n;       // a slot past M reads the last one; it is never stored
     lrow[n] = logits + ((int64_t)ch * a.M + (srow < a.M ? srow : a.M - 1)) * ld;
   }
-  float m_run[8], l_part[8];
+  float m_run[RPT], l_part[RPT];
 #pragma unroll
-  for (int n = 0; n < 8; ++n) { m_run[n] = -1e30f; l_part[n] = 0.f; }
+  for (int n = 0; n < RPT; ++n) { m_run[n] = -1e30f; l_part[n] = 0.f; }
 
-  f32x16 acc[2][4];                                  // [slot block][column block]
+  f32x16 acc[SB][4];                                 // [slot block][column block]
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < SB; ++x)
 #pragma unroll
     for (int y = 0; y < 4; ++y)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[x][y][i] = 0.f;
 
-  u32x4 lreg[8], yreg[8];
+  u32x4 lreg[RPT], yreg[8];
   auto load = [&](int j0) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n)             // a group past T reads the row's first group (ld >= 4) and counts for nothing
+    for (int n = 0; n < RPT; ++n)           // a group past T reads the row's first group (ld >= 4) and counts for nothing
       lreg[n] = *(const u32x4*)(lrow[n] + (j0 + c4 * 4 < Tn ? j0 + c4 * 4 : 0));
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
@@ -520,7 +522,7 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
     __syncthreads();                                 // the previous chunk's fragments have been read
     // ---- this chunk's weights
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
+    for (int n = 0; n < RPT; ++n) {
       float v[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -561,23 +563,23 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
     if (j0 + kChunk < Tn) load(j0 + kChunk);         // in flight under the MFMAs
     if (NORM == 0 && any_rescale[par]) {             // rare: a reference moved
 #pragma unroll
-      for (int x = 0; x < 2; ++x)
+      for (int x = 0; x < SB; ++x)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float al = alpha_s[wy * 64 + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
+          const float al = alpha_s[wy * 32 * SB + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
 #pragma unroll
           for (int y = 0; y < 4; ++y) acc[x][y][i] *= al;
         }
     }
 #pragma unroll
     for (int kc = 0; kc < kChunk / 16; ++kc) {
-      bf16x8 fp[2], fy[4];
+      bf16x8 fp[SB], fy[4];
 #pragma unroll
-      for (int x = 0; x < 2; ++x) fp[x] = frag(Ps + (wy * 64 + x * 32 + l31) * kRow64 + (kc * 16 + lh * 8) * 2);
+      for (int x = 0; x < SB; ++x) fp[x] = frag(Ps + (wy * 32 * SB + x * 32 + l31) * kRow64 + (kc * 16 + lh * 8) * 2);
 #pragma unroll
       for (int y = 0; y < 4; ++y) fy[y] = frag_tr(Ys + tro + kc * 16 * kYRow + (wx * 128 + y * 32) * 2, kYRow);
 #pragma unroll
-      for (int x = 0; x < 2; ++x)
+      for (int x = 0; x < SB; ++x)
 #pragma unroll
         for (int y = 0; y < 4; ++y)
           acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp[x], fy[y], acc[x][y], 0, 0, 0);
@@ -585,16 +587,16 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
   }
   // ---- row sums: over the sixteen threads of a row, then to everybody
 #pragma unroll
-  for (int n = 0; n < 8; ++n) {
+  for (int n = 0; n < RPT; ++n) {
     const float t = sum16(l_part[n]);
     if (c4 == 0) sum_s[(tid >> 4) + 16 * n] = t;
   }
   __syncthreads();
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < SB; ++x)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int row = wy * 64 + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), slot = s0 + row;
+      const int row = wy * 32 * SB + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), slot = s0 + row;
       if (slot >= a.M) continue;
       const float inv = 1.0f / (NORM == 0 ? sum_s[row] : sum_s[row] + a.eps);
       uint16_t* dst = (uint16_t*)(wx ? a.new_v : a.new_k) + ((int64_t)ch * a.M + slot) * kD;
@@ -1036,9 +1038,16 @@ bool mixnorm_mfma_fits(const StepArgs& a, const float* logits) {
 }
 hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream_t s) {
   const int ld = a.ldw ? a.ldw : a.m + a.Bn;
-  const dim3 grid((a.M + kTile - 1) / kTile, a.batch * a.Hkv);
-  if (a.norm == 0) hipLaunchKernelGGL(mixnorm_mfma_k<0>, grid, dim3(kThreads), 0, s, a, logits, ld);
-  else hipLaunchKernelGGL(mixnorm_mfma_k<1>, grid, dim3(kThreads), 0, s, a, logits, ld);
+  const int chains = a.batch * a.Hkv;
+  if ((int64_t)((a.M + 127) / 128) * chains >= 256) {       // enough 128-slot tiles for every compute unit
+    const dim3 grid((a.M + 127) / 128, chains);
+    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 128>), grid, dim3(kThreads), 0, s, a, logits, ld);
+    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 128>), grid, dim3(kThreads), 0, s, a, logits, ld);
+  } else {
+    const dim3 grid((a.M + 63) / 64, chains);
+    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 64>), grid, dim3(kThreads), 0, s, a, logits, ld);
+    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 64>), grid, dim3(kThreads), 0, s, a, logits, ld);
+  }
   return hipGetLastError();
 }
 
