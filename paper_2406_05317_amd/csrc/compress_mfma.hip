@@ -502,9 +502,38 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     }
     // Mixing MFMAs of tile i-1 run while the last logit MFMAs drain; the partial logits are
     // published in between.  The next stage's B1 makes them visible.
-    if (DoMix) { mix_mfma(0, 0); mix_mfma(0, 1); }
-    if (DoConv) write_partials();
-    if (DoMix) { mix_mfma(1, 0); mix_mfma(1, 1); }
+    if (DoMix && DoConv) {
+      // one partial-logit store behind each mixing MFMA: the stores issue in the shadow of the matrix
+      // pipe instead of as one burst
+      int nw = 0;
+      auto one_write = [&]() {
+        const int rt = nw / 4, g = nw % 4;
+        if (rt < G::RT) {
+          const f32x4 v = {sacc[rt][g * 4 + 0], sacc[rt][g * 4 + 1], sacc[rt][g * 4 + 2], sacc[rt][g * 4 + 3]};
+          *(f32x4*)(Sred + (w * BM + rt * 32 + l31) * G::SSTRIDE + g * 8 + lh * 4) = v;
+        }
+        ++nw;
+      };
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          const s16x4 a0 = y0[ks][ct], a1 = y1[ks][ct];
+          const s16x8 yy = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+          const bf16x8 yv = __builtin_bit_cast(bf16x8, yy);
+#pragma unroll
+          for (int rt = 0; rt < G::RT; ++rt) {
+            oacc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yv, pv[ks][rt], oacc[ct][rt], 0, 0, 0);
+            one_write();
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      while (nw < 4 * G::RT) one_write();
+    } else {
+      if (DoMix) { mix_mfma(0, 0); mix_mfma(0, 1); }
+      if (DoConv) write_partials();
+      if (DoMix) { mix_mfma(1, 0); mix_mfma(1, 1); }
+    }
     __builtin_amdgcn_sched_barrier(0);
   };
 
