@@ -245,6 +245,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     const int item = tid + it * kThreads;
     vreg[it] = load_cat16(cat_v, j0 + (item >> 4), item & 15);
   };
+  // the two halves of a chunk's fetch on their own, for stages that give each a slot of its own
+  auto load_half = [&](Cat16& r, const CatRows& c, int p, int chunk, bool blk) {
+    if (blk) r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
+    else r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, kDeviceScope);
+  };
   auto store_x = [&](int it, int j0, unsigned char* Xs) {
     const int item = tid + it * kThreads;
     (void)j0;
@@ -387,13 +392,34 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         // staging: the chunks loaded during the previous stage (key tile i+3, value tile i) go to
         // LDS, then the same registers receive key tile i+4 and value tile i+1: a whole stage
         // of latency cover, enough for a first touch that has to come from HBM
-        if (slot >= 5 * S && slot < 5 * S + G::XPER) {
-          store_x(slot - 5 * S, j0 + 3 * BN, Xstage);
-          load_x(slot - 5 * S, j0 + 4 * BN);
-        }
-        if (slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) {
-          store_v(slot - 5 * S - G::XPER, j0, Vstage);
-          load_v(slot - 5 * S - G::XPER, j0 + BN);
+        // With 60 slots in a stage the 15 pieces (LDS store, cache-side fetch, block-side fetch of each
+        // chunk) get a slot each, in the slots the softmax leaves free at the end of the stage: one LDS
+        // store or one load fits the shadow of an MFMA, a store and two loads together do not.
+        constexpr int kPieces = 3 * (G::XPER + G::VPER);
+        constexpr bool kSpread = kSlots - kPieces - 1 >= kSlots * 3 / 5 + 8;   // behind the softmax and the mixing fetches
+        if (kSpread) {
+          constexpr int Z0 = kSlots - kPieces - 1;
+          if (slot >= Z0 && slot < Z0 + kPieces) {
+            const int piece = slot - Z0, it = piece / 3, what = piece % 3;
+            if (it < G::XPER) {
+              const int item = tid + it * kThreads, jn = j0 + 4 * BN;
+              if (what == 0) store_x(it, j0 + 3 * BN, Xstage);
+              else load_half(xreg[it], cat_k, jn - G::PAD + (item >> 4), item & 15, what == 2);
+            } else {
+              const int iv = it - G::XPER, item = tid + iv * kThreads;
+              if (what == 0) store_v(iv, j0, Vstage);
+              else load_half(vreg[iv], cat_v, j0 + BN + (item >> 4), item & 15, what == 2);
+            }
+          }
+        } else {
+          if (slot >= 5 * S && slot < 5 * S + G::XPER) {
+            store_x(slot - 5 * S, j0 + 3 * BN, Xstage);
+            load_x(slot - 5 * S, j0 + 4 * BN);
+          }
+          if (slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) {
+            store_v(slot - 5 * S - G::XPER, j0, Vstage);
+            load_v(slot - 5 * S - G::XPER, j0 + BN);
+          }
         }
         if (slot >= 8 * S && slot < 8 * S + E4) sm_add(0, slot - 8 * S);
         if (slot >= 8 * S + E4 && slot < 8 * S + 2 * E4) sm_add(2, slot - 8 * S - E4);
