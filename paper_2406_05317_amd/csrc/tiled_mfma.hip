@@ -244,6 +244,156 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
     }
 }
 
+// ---- the same logits for filters over [K | V] and more than 128 slots: 256 slots x 256 positions per
+// workgroup, 8 waves of 64 x 128 (three fragment reads per four MFMAs instead of six).  The
+// contraction walks the four quarters of the 256 channels and, inside a quarter, the taps: the
+// keys or values of a quarter (all positions of the tile, 64 channels) are staged once, and the
+// filter tile of a stage (256 slots x 64 channels of one tap) arrives by loads that write LDS
+// directly, two stages ahead in a ring of three buffers: no staging registers, no LDS store
+// instructions, one barrier per stage.  Such a load fills 64 consecutive 16-byte cells (8 rows of
+// 128 bytes), so the filter tiles are unpadded and XOR-swizzled: chunk c of row r sits in cell
+// c ^ (r % 8); each lane requests whatever chunk belongs in its cell.
+__device__ __forceinline__ void load_to_lds_at(const u32x4& rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+// A 16-byte load the compiler does not wait for; the caller counts the loads in flight (they
+// complete in order, those into LDS included) and waits by hand before the first use.
+__device__ __forceinline__ void load16_unwaited(u32x4& dst, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+__global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const uint16_t* wt, float* out) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NT = 512, C = 2 * kD, SL = 256, PT = 256, WBUF = SL * 128;
+  const int KW = a.k_width, pad = (KW - 1) / 2, Tn = a.m + a.Bn, xrows = PT + KW - 1;
+  unsigned char* Xs = smem + 3 * WBUF;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)smem);
+  const int p0 = blockIdx.x * PT, s0 = blockIdx.y * SL, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
+  const int wy = w >> 1, wx = w & 1;                       // wave: slots 64 wy .., positions 128 wx ..
+  const int w_uniform = __builtin_amdgcn_readfirstlane(w);
+  const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * C : 0);
+
+  // ---- filter tiles.  Instruction i of wave w fills rows 8 (4 w + i) .. + 7 of the tile; lane l:
+  // row + l / 8, cell l % 8.  A slot past M reads the last slot instead: its outputs are never stored.
+  u32x4 rs;
+  {
+    const uint64_t base = (uint64_t)wtb;
+    rs[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+    rs[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+    rs[2] = __builtin_amdgcn_readfirstlane((uint32_t)((int64_t)KW * a.M * C * 2));
+    rs[3] = 0x00020000u;
+  }
+  uint32_t wvoff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int sl = s0 + (w * 4 + i) * 8 + (l >> 3);
+    wvoff[i] = (uint32_t)((sl < a.M ? sl : a.M - 1) * (C * 2) + (((l & 7) ^ (l >> 3)) << 4));
+  }
+  auto request_w = [&](int t, int q, int buf) {            // tap t, channels 64 q .., into ring buffer buf
+    const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)t * a.M * C + q * 64) * 2));
+    const uint32_t dst = lds0 + (uint32_t)(buf * WBUF + w_uniform * 4096);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_to_lds_at(rs, dst + i * 1024, wvoff[i], soff);
+  };
+  // ---- keys (quarters 0, 1) or values (2, 3): rows p0 - pad .. of 64 channels, padded rows in LDS.
+  // Rows outside the sequence are fetched from its nearest row and zeroed when they are stored.
+  constexpr int XPER = ((PT + 30) * 8 + NT - 1) / NT;
+  u32x4 xr[XPER];
+  auto request_x = [&](int q) {
+#pragma unroll
+    for (int i = 0; i < XPER; ++i) {
+      const int item = tid + i * NT, p = p0 - pad + (item >> 3);
+      const int pc = p < 0 ? 0 : (p < Tn ? p : Tn - 1);
+      load16_unwaited(xr[i], (q < 2 ? x_row(a, b, hkv, pc) : v_row(a, b, hkv, pc)) + (q & 1) * 64 + (item & 7) * 8);
+    }
+  };
+  auto store_x = [&]() {
+#pragma unroll
+    for (int i = 0; i < XPER; ++i) asm volatile("" : "+v"(xr[i]));
+#pragma unroll
+    for (int i = 0; i < XPER; ++i) {
+      const int item = tid + i * NT, row = item >> 3, p = p0 - pad + row;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      if (row < xrows) *(u32x4*)(Xs + row * kRow64 + (item & 7) * 16) = (p >= 0 && p < Tn) ? xr[i] : z;
+    }
+  };
+  int wcell[4];
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) wcell[kc] = ((2 * kc + lh) ^ (l31 & 7)) << 4;
+
+  f32x16 acc[2][4];                       // [slot block][position block]
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[sb][pb][i] = 0.f;
+
+  const int N = 4 * KW;                   // stage n = (quarter n / KW, tap n % KW)
+  request_x(0);
+  request_w(0, 0, 0);
+  request_w(1 % KW, 1 / KW, 1);
+  wait_loads_but<0>();
+  store_x();
+  __syncthreads();
+  int buf = 0;
+  for (int q = 0; q < 4; ++q)
+    for (int t = 0; t < KW; ++t) {
+      const int n = q * KW + t;
+      const bool next_quarter = t == KW - 1 && q < 3;
+      if (next_quarter) request_x(q + 1);
+      const bool more = n + 2 < N;
+      if (more) {
+        int t2 = t + 2, q2 = q;
+        while (t2 >= KW) t2 -= KW, ++q2;
+        request_w(t2, q2, buf == 0 ? 2 : buf - 1);         // (n + 2) % 3: the buffer stage n - 1 has finished with
+      }
+      const unsigned char* wl = smem + buf * WBUF + (wy * 64 + l31) * 128;
+      const unsigned char* xl = Xs + (wx * 128 + l31 + t) * kRow64 + lh * 16;
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc) {
+        bf16x8 fa[2], fb[4];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) fa[sb] = frag(wl + sb * 32 * 128 + wcell[kc]);
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb) fb[pb] = frag(xl + pb * 32 * kRow64 + kc * 32);
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int pb = 0; pb < 4; ++pb)
+            acc[sb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[sb], fb[pb], acc[sb][pb], 0, 0, 0);
+      }
+      // the next stage's filter tile (and the next quarter's rows, requested before it) have landed;
+      // only this stage's own four requests may still be on their way
+      if (more) wait_loads_but<4>(); else wait_loads_but<0>();
+      __syncthreads();
+      if (next_quarter) {                 // every wave has finished with the old rows
+        store_x();
+        __syncthreads();
+      }
+      buf = buf == 2 ? 0 : buf + 1;
+    }
+  const uint16_t* bias = a.conv_b ? (const uint16_t*)a.conv_b + hkv * a.b_head_stride : nullptr;
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+      const int p = p0 + wx * 128 + pb * 32 + l31;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int sl = s0 + wy * 64 + sb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+        if (sl < a.M && p < Tn)
+          out[((int64_t)ch * a.M + sl) * (a.ldw ? a.ldw : Tn) + p] = acc[sb][pb][i] + (bias ? bf16_val(bias[sl]) : 0.f);
+      }
+    }
+}
+
 // ---- dX[j, c] (positions x channels, contraction over slots and taps)
 // LDS: per chunk of 64 slots the rows j0 + pad - (KW - 1) .. of dW^T (hi and lo), read row-shifted
 // per tap; per (chunk, tap) the 64 x 128 (slot x channel) filter matrix, read down its rows.
@@ -967,8 +1117,23 @@ static hipError_t launch_logits(const StepArgs& a, const void* wt, float* logits
                      dim3(KV ? 512 : 256), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
+static hipError_t launch_logits_wide(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
+  constexpr int WBUFS = 3 * 256 * 128;    // the ring of filter tiles; behind it the rows of one channel quarter
+  const int Tn = a.m + a.Bn;
+  static bool attr_set = false;   // benign race: setting it twice is harmless
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv_logits_wide_k, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       WBUFS + (256 + 30) * kRow64);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(conv_logits_wide_k, dim3((Tn + 255) / 256, (a.M + 255) / 256, a.batch * a.Hkv), dim3(512),
+                     WBUFS + (256 + a.k_width - 1) * kRow64, s, a, (const uint16_t*)wt, logits);
+  return hipGetLastError();
+}
 hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
-  return a.conv_in ? launch_logits<1>(a, wt, logits, s) : launch_logits<0>(a, wt, logits, s);
+  if (a.conv_in) return a.M > kTile ? launch_logits_wide(a, wt, logits, s) : launch_logits<1>(a, wt, logits, s);
+  return launch_logits<0>(a, wt, logits, s);
 }
 
 // The plain contractions take whole groups of four: every row width (d, 2 d, T) a multiple of 4
