@@ -631,7 +631,15 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
   __shared__ __align__(16) float sum_s[SLOTS];                    // final row sums
   __shared__ int any_rescale[2];                                  // by chunk parity: reset two barriers after its last read
   const int Tn = a.m + a.Bn;
-  const int s0 = blockIdx.x * SLOTS, ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  // the slot tiles of a chain read the same [K | V] rows: workgroup ids are dealt round-robin to the
+  // 8 XCDs, so consecutive work items go to one XCD and a chain's rows come in through one L2
+  int item = blockIdx.x;
+  {
+    const int per = gridDim.x / 8;
+    if (item < per * 8) item = (item % 8) * per + item / 8;
+  }
+  const int tiles = (a.M + SLOTS - 1) / SLOTS;
+  const int s0 = (item % tiles) * SLOTS, ch = item / tiles, b = ch / a.Hkv, hkv = ch % a.Hkv;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
   const int c4 = tid & 15;                           // this thread's four positions inside a chunk: 4 c4 ..
   const float* lrow[RPT];
@@ -1205,11 +1213,11 @@ hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream
   const int ld = a.ldw ? a.ldw : a.m + a.Bn;
   const int chains = a.batch * a.Hkv;
   if ((int64_t)((a.M + 127) / 128) * chains >= 256) {       // enough 128-slot tiles for every compute unit
-    const dim3 grid((a.M + 127) / 128, chains);
+    const dim3 grid((a.M + 127) / 128 * chains);
     if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 128>), grid, dim3(kThreads), 0, s, a, logits, ld);
     else hipLaunchKernelGGL((mixnorm_mfma_k<1, 128>), grid, dim3(kThreads), 0, s, a, logits, ld);
   } else {
-    const dim3 grid((a.M + 63) / 64, chains);
+    const dim3 grid((a.M + 63) / 64 * chains);
     if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 64>), grid, dim3(kThreads), 0, s, a, logits, ld);
     else hipLaunchKernelGGL((mixnorm_mfma_k<1, 64>), grid, dim3(kThreads), 0, s, a, logits, ld);
   }
