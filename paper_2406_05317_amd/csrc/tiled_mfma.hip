@@ -244,9 +244,9 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
     }
 }
 
-// ---- the same logits for filters over [K | V] and more than 128 slots: 256 slots x 256 positions per
-// workgroup, 8 waves of 64 x 128 (three fragment reads per four MFMAs instead of six).  The
-// contraction walks the four quarters of the 256 channels and, inside a quarter, the taps: the
+// ---- the same logits for more than 128 slots (NQ = 2: filters over the keys, 128 channels; NQ = 4:
+// over [K | V], 256 channels): 256 slots x 256 positions per workgroup, 8 waves of 64 x 128 (three fragment reads per four MFMAs instead of six).  The
+// contraction walks the channels in NQ quarters of 64 and, inside a quarter, the taps: the
 // keys or values of a quarter (all positions of the tile, 64 channels) are staged once, and the
 // filter tile of a stage (256 slots x 64 channels of one tap) arrives by loads that write LDS
 // directly, two stages ahead in a ring of three buffers: no staging registers, no LDS store
@@ -267,9 +267,10 @@ __device__ __forceinline__ void wait_loads_but() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
+template <int NQ>
 __global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const uint16_t* wt, float* out) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int NT = 512, C = 2 * kD, SL = 256, PT = 256, WBUF = SL * 128;
+  constexpr int NT = 512, C = NQ * 64, SL = 256, PT = 256, WBUF = SL * 128;
   const int KW = a.k_width, pad = (KW - 1) / 2, Tn = a.m + a.Bn, xrows = PT + KW - 1;
   unsigned char* Xs = smem + 3 * WBUF;
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)smem);
@@ -335,7 +336,7 @@ __global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const u
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[sb][pb][i] = 0.f;
 
-  const int N = 4 * KW;                   // stage n = (quarter n / KW, tap n % KW)
+  const int N = NQ * KW;                  // stage n = (quarter n / KW, tap n % KW)
   request_x(0);
   request_w(0, 0, 0);
   request_w(1 % KW, 1 / KW, 1);
@@ -343,10 +344,10 @@ __global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const u
   store_x();
   __syncthreads();
   int buf = 0;
-  for (int q = 0; q < 4; ++q)
+  for (int q = 0; q < NQ; ++q)
     for (int t = 0; t < KW; ++t) {
       const int n = q * KW + t;
-      const bool next_quarter = t == KW - 1 && q < 3;
+      const bool next_quarter = t == KW - 1 && q < NQ - 1;
       if (next_quarter) request_x(q + 1);
       const bool more = n + 2 < N;
       if (more) {
@@ -1125,23 +1126,24 @@ static hipError_t launch_logits(const StepArgs& a, const void* wt, float* logits
                      dim3(KV ? 512 : 256), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
+template <int NQ>
 static hipError_t launch_logits_wide(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
   constexpr int WBUFS = 3 * 256 * 128;    // the ring of filter tiles; behind it the rows of one channel quarter
   const int Tn = a.m + a.Bn;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv_logits_wide_k, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)conv_logits_wide_k<NQ>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        WBUFS + (256 + 30) * kRow64);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(conv_logits_wide_k, dim3((Tn + 255) / 256, (a.M + 255) / 256, a.batch * a.Hkv), dim3(512),
+  hipLaunchKernelGGL(conv_logits_wide_k<NQ>, dim3((Tn + 255) / 256, (a.M + 255) / 256, a.batch * a.Hkv), dim3(512),
                      WBUFS + (256 + a.k_width - 1) * kRow64, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
 hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
-  if (a.conv_in) return a.M > kTile ? launch_logits_wide(a, wt, logits, s) : launch_logits<1>(a, wt, logits, s);
-  return launch_logits<0>(a, wt, logits, s);
+  if (a.M > kTile) return a.conv_in ? launch_logits_wide<4>(a, wt, logits, s) : launch_logits_wide<2>(a, wt, logits, s);
+  return a.conv_in ? launch_logits<1>(a, wt, logits, s) : launch_logits<0>(a, wt, logits, s);
 }
 
 // The plain contractions take whole groups of four: every row width (d, 2 d, T) a multiple of 4

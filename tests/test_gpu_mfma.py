@@ -217,6 +217,7 @@ def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
     dict(conv_in=1, conv_width=21, L=512, protect_share=0.15),                   # protected slots
     dict(conv_in=1, conv_width=31, M=384, B=200, L=1000, n_q_heads=2, n_kv_heads=2, bias_sigma=0.5),   # 256-slot tiles, the second half empty
     dict(conv_in=1, conv_width=21, norm=1, M=512, B=256, L=1536, n_q_heads=2, n_kv_heads=1),      # two full 256-slot tiles
+    dict(conv_width=9, M=320, B=128, L=900, n_q_heads=2, n_kv_heads=2),                          # keys-only filters on the 256-slot tiles
 ])
 def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case):
     """impl = AUTO with bf16 / head_dim 128 and a compressor the fused kernel is not built for
