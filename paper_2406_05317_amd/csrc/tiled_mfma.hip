@@ -623,9 +623,12 @@ __device__ __forceinline__ float sum16(float v) {
 }
 constexpr int kYRow = 2 * kD * 2 + 16;             // bytes of a staged [K | V] row
 // SLOTS: 128 slots per workgroup, or 64 where that is what it takes to give every compute unit one.
-template <int NORM, int SLOTS>
-__global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const float* logits, int ld) {
-  constexpr int RPT = SLOTS / 16, SB = SLOTS / 64;      // rows of logits per thread; 32-slot blocks per wave
+// NT: 256 threads (waves 2 x 2: half the slots x the K or the V columns each), or 512 (waves 2 x 4:
+// half the slots x 64 columns) so that every SIMD has a second wave to run while one waits.
+template <int NORM, int SLOTS, int NT>
+__global__ __launch_bounds__(NT) void mixnorm_mfma_k(StepArgs a, const float* logits, int ld) {
+  constexpr int RPT = SLOTS * 16 / NT, SB = SLOTS / 64;   // rows of logits per thread; 32-slot blocks per wave
+  constexpr int WX = NT / 128, YB = 8 / WX, YPER = kChunk * 32 / NT;   // waves across the columns; 32-column blocks per wave; staged chunks per thread
   __shared__ __align__(16) unsigned char Ps[SLOTS * kRow64];      // weights of the chunk [slot][position], bf16
   __shared__ __align__(16) unsigned char Ys[kChunk * kYRow];      // [position][K | V columns]
   __shared__ __align__(16) float alpha_s[SLOTS];                  // rescale factor per slot for this chunk
@@ -641,34 +644,34 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
   }
   const int tiles = (a.M + SLOTS - 1) / SLOTS;
   const int s0 = (item % tiles) * SLOTS, ch = item / tiles, b = ch / a.Hkv, hkv = ch % a.Hkv;
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w >> 1, wx = w & 1;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5, wy = w / WX, wx = w % WX;
   const int c4 = tid & 15;                           // this thread's four positions inside a chunk: 4 c4 ..
   const float* lrow[RPT];
 #pragma unroll
   for (int n = 0; n < RPT; ++n) {
-    const int srow = s0 + (tid >> 4) + 16 * n;       // a slot past M reads the last one; it is never stored
+    const int srow = s0 + (tid >> 4) + (NT / 16) * n;       // a slot past M reads the last one; it is never stored
     lrow[n] = logits + ((int64_t)ch * a.M + (srow < a.M ? srow : a.M - 1)) * ld;
   }
   float m_run[RPT], l_part[RPT];
 #pragma unroll
   for (int n = 0; n < RPT; ++n) { m_run[n] = -1e30f; l_part[n] = 0.f; }
 
-  f32x16 acc[SB][4];                                 // [slot block][column block]
+  f32x16 acc[SB][YB];                                // [slot block][column block]
 #pragma unroll
   for (int x = 0; x < SB; ++x)
 #pragma unroll
-    for (int y = 0; y < 4; ++y)
+    for (int y = 0; y < YB; ++y)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[x][y][i] = 0.f;
 
-  u32x4 lreg[RPT], yreg[8];
+  u32x4 lreg[RPT], yreg[YPER];
   auto load = [&](int j0) {
 #pragma unroll
     for (int n = 0; n < RPT; ++n)           // a group past T reads the row's first group (ld >= 4) and counts for nothing
       lreg[n] = *(const u32x4*)(lrow[n] + (j0 + c4 * 4 < Tn ? j0 + c4 * 4 : 0));
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      const int item = tid + n * kThreads, row = item >> 5, c16 = item & 31, j = j0 + row;
+    for (int n = 0; n < YPER; ++n) {
+      const int item = tid + n * NT, row = item >> 5, c16 = item & 31, j = j0 + row;
       const int jc = j < Tn ? j : 0;
       yreg[n] = *(const u32x4*)((c16 < 16 ? x_row(a, b, hkv, jc) : v_row(a, b, hkv, jc)) + (c16 & 15) * 8);
     }
@@ -705,7 +708,7 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
       const f32x2 x0 = {v[0], v[1]}, x1 = {v[2], v[3]};
       const bf16x2 h0 = __builtin_convertvector(x0, bf16x2), h1 = __builtin_convertvector(x1, bf16x2);
       const u32x2 pk = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1)};
-      const int row = (tid >> 4) + 16 * n;
+      const int row = (tid >> 4) + (NT / 16) * n;
       *(u32x2*)(Ps + row * kRow64 + c4 * 8) = pk;
       if (NORM == 0 && c4 == 0) {
         alpha_s[row] = al;
@@ -713,8 +716,8 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
       }
     }
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      const int item = tid + n * kThreads, row = item >> 5, c16 = item & 31;
+    for (int n = 0; n < YPER; ++n) {
+      const int item = tid + n * NT, row = item >> 5, c16 = item & 31;
       const u32x4 z = {0u, 0u, 0u, 0u};
       *(u32x4*)(Ys + row * kYRow + c16 * 16) = j0 + row < Tn ? yreg[n] : z;
     }
@@ -727,20 +730,20 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
         for (int i = 0; i < 16; ++i) {
           const float al = alpha_s[wy * 32 * SB + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)];
 #pragma unroll
-          for (int y = 0; y < 4; ++y) acc[x][y][i] *= al;
+          for (int y = 0; y < YB; ++y) acc[x][y][i] *= al;
         }
     }
 #pragma unroll
     for (int kc = 0; kc < kChunk / 16; ++kc) {
-      bf16x8 fp[SB], fy[4];
+      bf16x8 fp[SB], fy[YB];
 #pragma unroll
       for (int x = 0; x < SB; ++x) fp[x] = frag(Ps + (wy * 32 * SB + x * 32 + l31) * kRow64 + (kc * 16 + lh * 8) * 2);
 #pragma unroll
-      for (int y = 0; y < 4; ++y) fy[y] = frag_tr(Ys + tro + kc * 16 * kYRow + (wx * 128 + y * 32) * 2, kYRow);
+      for (int y = 0; y < YB; ++y) fy[y] = frag_tr(Ys + tro + kc * 16 * kYRow + (wx * YB + y) * 32 * 2, kYRow);
 #pragma unroll
       for (int x = 0; x < SB; ++x)
 #pragma unroll
-        for (int y = 0; y < 4; ++y)
+        for (int y = 0; y < YB; ++y)
           acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp[x], fy[y], acc[x][y], 0, 0, 0);
     }
   }
@@ -748,7 +751,7 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
 #pragma unroll
   for (int n = 0; n < RPT; ++n) {
     const float t = sum16(l_part[n]);
-    if (c4 == 0) sum_s[(tid >> 4) + 16 * n] = t;
+    if (c4 == 0) sum_s[(tid >> 4) + (NT / 16) * n] = t;
   }
   __syncthreads();
 #pragma unroll
@@ -758,9 +761,10 @@ __global__ __launch_bounds__(kThreads) void mixnorm_mfma_k(StepArgs a, const flo
       const int row = wy * 32 * SB + x * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), slot = s0 + row;
       if (slot >= a.M) continue;
       const float inv = 1.0f / (NORM == 0 ? sum_s[row] : sum_s[row] + a.eps);
-      uint16_t* dst = (uint16_t*)(wx ? a.new_v : a.new_k) + ((int64_t)ch * a.M + slot) * kD;
+      const int col0 = wx * YB * 32;                   // of [new_K | new_V]
+      uint16_t* dst = (uint16_t*)(col0 >= kD ? a.new_v : a.new_k) + ((int64_t)ch * a.M + slot) * kD + (col0 & (kD - 1));
 #pragma unroll
-      for (int y = 0; y < 4; ++y) dst[y * 32 + l31] = (uint16_t)bf16_rne(acc[x][y][i] * inv);
+      for (int y = 0; y < YB; ++y) dst[y * 32 + l31] = (uint16_t)bf16_rne(acc[x][y][i] * inv);
     }
 }
 
@@ -1216,12 +1220,12 @@ hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream
   const int chains = a.batch * a.Hkv;
   if ((int64_t)((a.M + 127) / 128) * chains >= 256) {       // enough 128-slot tiles for every compute unit
     const dim3 grid((a.M + 127) / 128 * chains);
-    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 128>), grid, dim3(kThreads), 0, s, a, logits, ld);
-    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 128>), grid, dim3(kThreads), 0, s, a, logits, ld);
-  } else {
+    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 128, 512>), grid, dim3(512), 0, s, a, logits, ld);
+    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 128, 512>), grid, dim3(512), 0, s, a, logits, ld);
+  } else {                                                  // (32 slots per workgroup, twice as many of them: slower)
     const dim3 grid((a.M + 63) / 64 * chains);
-    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 64>), grid, dim3(kThreads), 0, s, a, logits, ld);
-    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 64>), grid, dim3(kThreads), 0, s, a, logits, ld);
+    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 64, 512>), grid, dim3(512), 0, s, a, logits, ld);
+    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 64, 512>), grid, dim3(512), 0, s, a, logits, ld);
   }
   return hipGetLastError();
 }
