@@ -213,7 +213,11 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
  *   LOCOCO_SCAN_LAUNCHES=steps   one launch per compression step instead of one per scan
  *   LOCOCO_CHAIN_SYNC=device     workgroups of a chain always meet with device-scope release and
  *                                acquire (default: without the L2 write-back when they find themselves
- *                                on one XCD) */
+ *                                on one XCD)
+ *   LOCOCO_LOGITS_TILES=64|128|256  slots per workgroup of the Eq. 5 kernel of the unfused MFMA path
+ *                                (default: chosen from the grid size; 256 needs more than 128 slots
+ *                                and adds up Eq. 5's fp32 sum in another order: the one knob that can
+ *                                move results, by rounding) */
 lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out);
 
 /* Steps 4-5 with Eq. 5's output supplied by the caller: the cache becomes

@@ -26,6 +26,7 @@
 #include <cstdint>
 
 #include "lococo_internal.h"
+#include <cstdlib>
 
 namespace lococo {
 namespace {
@@ -141,22 +142,24 @@ __global__ __launch_bounds__(kThreads) void bwd_split_dl_k(const float* dl, uint
 // LDS: X rows p0 - pad .. p0 + 127 + (KW - 1 - pad) once; per tap the (slot x channel) matrix of
 // 128 slots.  A = filters (rows: slots), B = keys (lane: position): a lane stores 32 consecutive
 // positions of one slot per instruction.  KV = 1: the convolution reads [K | V], 256 channels.
-template <int KV>
+// ST: 128 slots per workgroup, or 64 (a wave then has one block of 32 slots instead of two) where
+// 128 would leave compute units without a workgroup.
+template <int KV, int ST>
 __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k(StepArgs a, const uint16_t* wt,
                                                                                  float* out) {
   extern __shared__ __align__(16) unsigned char smem[];
   // 8 waves per compute unit either way: two workgroups of 4 (each wave 64 slots x 64 positions), or,
   // where the tiles of 256 channels leave LDS for one workgroup only, one of 8 (64 slots x 32 positions
   // per wave), so that every SIMD has a second wave to run while one waits for its fragments
-  constexpr int NT = KV ? 512 : 256, PB = KV ? 1 : 2;
+  constexpr int NT = KV ? 512 : 256, PB = KV ? 1 : 2, SBW = ST / 64;
   constexpr int C = KV ? 2 * kD : kD, ROW = C * 2 + 16, CH16 = C / 8;   // channels, LDS row bytes, 16-byte chunks per row
   const int KW = a.k_width, pad = (KW - 1) / 2, Tn = a.m + a.Bn;
   const int xrows = kTile + KW - 1;
   unsigned char* Xs = smem;
   unsigned char* Ws = smem + xrows * ROW;
-  const int p0 = blockIdx.x * kTile, s0 = blockIdx.y * kTile, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
+  const int p0 = blockIdx.x * kTile, s0 = blockIdx.y * ST, ch = blockIdx.z, b = ch / a.Hkv, hkv = ch % a.Hkv;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
-  const int wy = w / (NT / 128), wx = w % (NT / 128);     // wave: slots 64 wy .., positions 32 PB wx ..
+  const int wy = w / (NT / 128), wx = w % (NT / 128);     // wave: slots 32 SBW wy .., positions 32 PB wx ..
   const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * C : 0);
 
   {
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
       if (item < xrows * CH16) *(u32x4*)(Xs + row * ROW + c16 * 16) = xr[i];
     }
   }
-  constexpr int WPER = kTile * CH16 / NT;
+  constexpr int WPER = ST * CH16 / NT;
   u32x4 wreg[WPER];
   // element offsets of this thread's chunks inside a tap's matrix, computed once; a tap adds a uniform
   // base.  A slot past M reads the last slot instead: its outputs are never stored, and nothing
@@ -200,9 +203,9 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
       *(u32x4*)(Ws + row * ROW + c16 * 16) = wreg[i];
     }
   };
-  f32x16 acc[2][PB];                      // [slot block][position block]
+  f32x16 acc[SBW][PB];                    // [slot block][position block]
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb)
+  for (int sb = 0; sb < SBW; ++sb)
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb)
 #pragma unroll
@@ -213,17 +216,17 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
     store_w();
     __syncthreads();
     if (t + 1 < KW) load_w(t + 1);        // in flight under this tap's MFMAs
-    const unsigned char* wl = Ws + (wy * 64 + l31) * ROW + lh * 16;
+    const unsigned char* wl = Ws + (wy * 32 * SBW + l31) * ROW + lh * 16;
     const unsigned char* xl = Xs + (wx * 32 * PB + l31 + t) * ROW + lh * 16;
 #pragma unroll
     for (int kc = 0; kc < C / 16; ++kc) {
-      bf16x8 fa[2], fb[PB];
+      bf16x8 fa[SBW], fb[PB];
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb) fa[sb] = frag(wl + sb * 32 * ROW + kc * 32);
+      for (int sb = 0; sb < SBW; ++sb) fa[sb] = frag(wl + sb * 32 * ROW + kc * 32);
 #pragma unroll
       for (int pb = 0; pb < PB; ++pb) fb[pb] = frag(xl + pb * 32 * ROW + kc * 32);
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
+      for (int sb = 0; sb < SBW; ++sb)
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb)
           acc[sb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[sb], fb[pb], acc[sb][pb], 0, 0, 0);
@@ -231,13 +234,13 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
   }
   const uint16_t* bias = a.conv_b ? (const uint16_t*)a.conv_b + hkv * a.b_head_stride : nullptr;
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb)
+  for (int sb = 0; sb < SBW; ++sb)
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
       const int p = p0 + wx * 32 * PB + pb * 32 + l31;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int s = s0 + wy * 64 + sb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+        const int s = s0 + wy * 32 * SBW + sb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
         if (s < a.M && p < Tn)
           out[((int64_t)ch * a.M + s) * (a.ldw ? a.ldw : Tn) + p] = acc[sb][pb][i] + (bias ? bf16_val(bias[s]) : 0.f);
       }
@@ -1114,19 +1117,19 @@ hipError_t launch_pack_filters_per_tap(const StepArgs& a, int banks, void* wt, h
   return hipGetLastError();
 }
 
-template <int KV>
+template <int KV, int ST>
 static hipError_t launch_logits(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
   constexpr int ROW = (KV ? 2 * kD : kD) * 2 + 16;
   const int Tn = a.m + a.Bn;
-  const int lds = (kTile + a.k_width - 1) * ROW + kTile * ROW;
+  const int lds = (kTile + a.k_width - 1) * ROW + ST * ROW;
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv_logits_mfma_k<KV>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (kTile + 30) * ROW + kTile * ROW);
+    hipError_t e = hipFuncSetAttribute((const void*)conv_logits_mfma_k<KV, ST>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (kTile + 30) * ROW + ST * ROW);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(conv_logits_mfma_k<KV>, dim3((Tn + kTile - 1) / kTile, (a.M + kTile - 1) / kTile, a.batch * a.Hkv),
+  hipLaunchKernelGGL((conv_logits_mfma_k<KV, ST>), dim3((Tn + kTile - 1) / kTile, (a.M + ST - 1) / ST, a.batch * a.Hkv),
                      dim3(KV ? 512 : 256), lds, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
@@ -1145,9 +1148,24 @@ static hipError_t launch_logits_wide(const StepArgs& a, const void* wt, float* l
                      WBUFS + (256 + a.k_width - 1) * kRow64, s, a, (const uint16_t*)wt, logits);
   return hipGetLastError();
 }
+// Three tile shapes.  64 and 128 slots give the same bits (every output element is the same sum in
+// the same order: taps outermost); the 256 x 256 kernel walks the channel quarters outermost, so its
+// fp32 sums differ from theirs in rounding.  LOCOCO_LOGITS_TILES = 64 | 128 | 256 overrides the
+// choice by grid size, for tests and measurements; 256 is ignored where there are at most 128 slots.
 hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
-  if (a.M > kTile) return a.conv_in ? launch_logits_wide<4>(a, wt, logits, s) : launch_logits_wide<2>(a, wt, logits, s);
-  return a.conv_in ? launch_logits<1>(a, wt, logits, s) : launch_logits<0>(a, wt, logits, s);
+  const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv;
+  const int64_t tiles256 = (int64_t)((Tn + 255) / 256) * ((a.M + 255) / 256) * chains;
+  const int64_t tiles128 = (int64_t)((Tn + kTile - 1) / kTile) * ((a.M + kTile - 1) / kTile) * chains;
+  // 256 x 256 where there are enough of those tiles for three quarters of the compute units;
+  // 64-slot tiles where 128-slot ones would be fewer than the compute units
+  int shape = a.M > kTile && tiles256 >= 192 ? 256 : tiles128 < 256 ? 64 : 128;
+  if (const char* e = getenv("LOCOCO_LOGITS_TILES")) {
+    const int v = atoi(e);
+    if (v == 64 || v == 128 || (v == 256 && a.M > kTile)) shape = v;
+  }
+  if (shape == 256) return a.conv_in ? launch_logits_wide<4>(a, wt, logits, s) : launch_logits_wide<2>(a, wt, logits, s);
+  if (shape == 64) return a.conv_in ? launch_logits<1, 64>(a, wt, logits, s) : launch_logits<0, 64>(a, wt, logits, s);
+  return a.conv_in ? launch_logits<1, 128>(a, wt, logits, s) : launch_logits<0, 128>(a, wt, logits, s);
 }
 
 // The plain contractions take whole groups of four: every row width (d, 2 d, T) a multiple of 4

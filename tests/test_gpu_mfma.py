@@ -218,11 +218,15 @@ def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
     dict(conv_in=1, conv_width=31, M=384, B=200, L=1000, n_q_heads=2, n_kv_heads=2, bias_sigma=0.5),   # 256-slot tiles, the second half empty
     dict(conv_in=1, conv_width=21, norm=1, M=512, B=256, L=1536, n_q_heads=2, n_kv_heads=1),      # two full 256-slot tiles
     dict(conv_width=9, M=320, B=128, L=900, n_q_heads=2, n_kv_heads=2),                          # keys-only filters on the 256-slot tiles
+    dict(conv_in=1, conv_width=21, norm=1, batch=4, n_q_heads=32, n_kv_heads=32, L=384),          # enough chains for 128-slot tiles, [K | V]
+    dict(conv_width=7, batch=4, n_q_heads=32, n_kv_heads=32, L=384),                             # the same, keys only
 ])
-def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case):
+def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case, monkeypatch):
     """impl = AUTO with bf16 / head_dim 128 and a compressor the fused kernel is not built for
     ([K | V] input, other widths, odd M): MFMA attention, MFMA logits and MFMA fusion around the
-    shape-agnostic normalisation.  Equal to the oracle; the timing rows say which kernels ran."""
+    shape-agnostic normalisation.  Equal to the oracle; the timing rows say which kernels ran.
+    Then every tile shape of the logits kernel, forced from the host: each equal to the oracle,
+    the 64- and 128-slot tiles equal to each other bit for bit."""
     from paper_2406_05317_amd import binding as lb
     case = dict(case)
     share = case.pop("protect_share", 0.0)
@@ -240,6 +244,14 @@ def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case):
     # block by block through lococo_segment_step: the same kernels, the same bits
     again = gpu_forward(w, q, k, v, cw, cb, impl=0, step_by_step=True, protect=protect)
     for x, y in zip(got[:3], again[:3]):
+        assert torch.equal(x, y)
+    by_shape = {}
+    for shape in ("64", "128", "256"):
+        monkeypatch.setenv("LOCOCO_LOGITS_TILES", shape)
+        by_shape[shape] = gpu_forward(w, q, k, v, cw, cb, impl=0, history=True, protect=protect)
+        compare_scan(w, by_shape[shape], want, what="logits tiles of %s slots" % shape)
+    monkeypatch.delenv("LOCOCO_LOGITS_TILES")
+    for x, y in zip(by_shape["64"][:3], by_shape["128"][:3]):
         assert torch.equal(x, y)
 
 
