@@ -625,13 +625,14 @@ __device__ __forceinline__ float sum16(float v) {
   return v + dpp<0x140>(v);
 }
 constexpr int kYRow = 2 * kD * 2 + 16;             // bytes of a staged [K | V] row
-// SLOTS: 128 slots per workgroup, or 64 where that is what it takes to give every compute unit one.
+// SLOTS: 128 slots per workgroup, or 64 or 32 where that is what it takes to give the compute units one each.
 // NT: 256 threads (waves 2 x 2: half the slots x the K or the V columns each), or 512 (waves 2 x 4:
 // half the slots x 64 columns) so that every SIMD has a second wave to run while one waits.
 template <int NORM, int SLOTS, int NT>
 __global__ __launch_bounds__(NT) void mixnorm_mfma_k(StepArgs a, const float* logits, int ld) {
-  constexpr int RPT = SLOTS * 16 / NT, SB = SLOTS / 64;   // rows of logits per thread; 32-slot blocks per wave
-  constexpr int WX = NT / 128, YB = 8 / WX, YPER = kChunk * 32 / NT;   // waves across the columns; 32-column blocks per wave; staged chunks per thread
+  constexpr int RPT = SLOTS * 16 / NT, SB = SLOTS >= 64 ? SLOTS / 64 : 1;   // rows of logits per thread; 32-slot blocks per wave
+  constexpr int WY = SLOTS / (32 * SB), WX = NT / 64 / WY;   // waves down the slots and across the columns
+  constexpr int YB = 8 / WX, YPER = kChunk * 32 / NT;        // 32-column blocks per wave; staged chunks per thread
   __shared__ __align__(16) unsigned char Ps[SLOTS * kRow64];      // weights of the chunk [slot][position], bf16
   __shared__ __align__(16) unsigned char Ys[kChunk * kYRow];      // [position][K | V columns]
   __shared__ __align__(16) float alpha_s[SLOTS];                  // rescale factor per slot for this chunk
@@ -1240,10 +1241,14 @@ hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream
     const dim3 grid((a.M + 127) / 128 * chains);
     if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 128, 512>), grid, dim3(512), 0, s, a, logits, ld);
     else hipLaunchKernelGGL((mixnorm_mfma_k<1, 128, 512>), grid, dim3(512), 0, s, a, logits, ld);
-  } else {                                                  // (32 slots per workgroup, twice as many of them: slower)
+  } else if ((int64_t)((a.M + 63) / 64) * chains >= 128) {  // (with 256 of these, 512 tiles of 32 slots are slower)
     const dim3 grid((a.M + 63) / 64 * chains);
     if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 64, 512>), grid, dim3(512), 0, s, a, logits, ld);
     else hipLaunchKernelGGL((mixnorm_mfma_k<1, 64, 512>), grid, dim3(512), 0, s, a, logits, ld);
+  } else {                                                  // few chains: 32 slots per workgroup, eight waves of 32 columns
+    const dim3 grid((a.M + 31) / 32 * chains);
+    if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 32, 512>), grid, dim3(512), 0, s, a, logits, ld);
+    else hipLaunchKernelGGL((mixnorm_mfma_k<1, 32, 512>), grid, dim3(512), 0, s, a, logits, ld);
   }
   return hipGetLastError();
 }
