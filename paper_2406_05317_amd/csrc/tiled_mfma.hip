@@ -255,7 +255,8 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
 // directly, two stages ahead in a ring of three buffers: no staging registers, no LDS store
 // instructions, one barrier per stage.  Such a load fills 64 consecutive 16-byte cells (8 rows of
 // 128 bytes), so the filter tiles are unpadded and XOR-swizzled: chunk c of row r sits in cell
-// c ^ (r % 8); each lane requests whatever chunk belongs in its cell.
+// c ^ ((r / 2) % 8), which spreads 16 consecutive rows over the 16 cells of 256 bytes; each lane
+// requests whatever chunk belongs in its cell.
 __device__ __forceinline__ void load_to_lds_at(const u32x4& rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const u
   const uint16_t* wtb = wt + (a.w_head_stride ? (int64_t)hkv * KW * a.M * C : 0);
 
   // ---- filter tiles.  Instruction i of wave w fills rows 8 (4 w + i) .. + 7 of the tile; lane l:
-  // row + l / 8, cell l % 8.  A slot past M reads the last slot instead: its outputs are never stored.
+  // row r = 8 (4 w + i) + l / 8, cell l % 8, so (r / 2) % 8 = 4 (i % 2) + l / 16.  A slot past M reads the last slot instead: its outputs are never stored.
   u32x4 rs;
   {
     const uint64_t base = (uint64_t)wtb;
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const u
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int sl = s0 + (w * 4 + i) * 8 + (l >> 3);
-    wvoff[i] = (uint32_t)((sl < a.M ? sl : a.M - 1) * (C * 2) + (((l & 7) ^ (l >> 3)) << 4));
+    wvoff[i] = (uint32_t)((sl < a.M ? sl : a.M - 1) * (C * 2) + (((l & 7) ^ (4 * (i & 1) + (l >> 4))) << 4));
   }
   auto request_w = [&](int t, int q, int buf) {            // tap t, channels 64 q .., into ring buffer buf
     const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)t * a.M * C + q * 64) * 2));
@@ -329,7 +330,7 @@ __global__ __launch_bounds__(512, 1) void conv_logits_wide_k(StepArgs a, const u
   };
   int wcell[4];
 #pragma unroll
-  for (int kc = 0; kc < 4; ++kc) wcell[kc] = ((2 * kc + lh) ^ (l31 & 7)) << 4;
+  for (int kc = 0; kc < 4; ++kc) wcell[kc] = ((2 * kc + lh) ^ ((l31 >> 1) & 7)) << 4;
 
   f32x16 acc[2][4];                       // [slot block][position block]
 #pragma unroll
@@ -624,7 +625,7 @@ __device__ __forceinline__ float sum16(float v) {
   v += dpp<0x141>(v);
   return v + dpp<0x140>(v);
 }
-constexpr int kYRow = 2 * kD * 2 + 16;             // bytes of a staged [K | V] row
+constexpr int kYRow = 2 * kD * 2 + 64;             // bytes of a staged [K | V] row (64 past a multiple of 256: conflict-free transposing reads)
 // SLOTS: 128 slots per workgroup, or 64 or 32 where that is what it takes to give the compute units one each.
 // NT: 256 threads (waves 2 x 2: half the slots x the K or the V columns each), or 512 (waves 2 x 4:
 // half the slots x 64 columns) so that every SIMD has a second wave to run while one waits.
