@@ -42,7 +42,8 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int kThreads = 256;
 constexpr int kD = 128;          // channels
-constexpr int kRow = 272;        // bytes of a 128-element row in LDS (256 + 16: conflict-free 16-byte column reads)
+constexpr int kRow = 320;        // bytes of a 128-element row in LDS read by transposing reads: 64 past a multiple of 256, so
+                                 // that the four rows x 64 bytes half a wave touches fall on different banks
 constexpr int kRow64 = 144;      // bytes of a 64-element row in LDS
 constexpr int kTile = 128;       // outputs per workgroup, both ways
 constexpr int kChunk = 64;       // contraction chunk of the two gradient kernels
@@ -785,8 +786,8 @@ __global__ __launch_bounds__(NT) void mixnorm_mfma_k(StepArgs a, const float* lo
 //   kParts:  1 = the values are bf16 numbers; 2 = fp32 values, staged as hi + lo (the product of
 //            two such operands takes three MFMAs: hi hi, hi lo, lo hi).
 // The output functor decides where C[i, j] goes (store) and may skip whole tiles.
-constexpr int kPartBytes = kTile * kRow64;       // 18 432 >= kChunk * kRow
-static_assert(kChunk * kRow <= kPartBytes, "a staged operand part fits its LDS area either way round");
+constexpr int kPartBytes = kChunk * kRow;        // 20 480 >= kTile * kRow64
+static_assert(kTile * kRow64 <= kPartBytes, "a staged operand part fits its LDS area either way round");
 
 template <class OpA, class OpB, class Out>
 __global__ __launch_bounds__(kThreads, 2) void bwd_gemm_k(OpA A, OpB B, Out out, int I, int J, int K) {
