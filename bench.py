@@ -64,6 +64,48 @@ KERNEL_BOUND = {  # roofline that bounds each kernel, peak, unit
 }
 
 
+def scan_bytes(w, plan):
+    """Algorithmic HBM bytes of the stand-alone passes of the unfused path, summed over the scan: the
+    fp32 logits written by Eq. 5 and read (once) by Eq. 6 + Eq. 4, which also reads [K | V] and writes the
+    new cache rows."""
+    chains = w.batch * w.n_kv_heads
+    e = 2 if w.dtype == "bf16" else 4
+    tot = {"logits_write": 0.0, "mixnorm": 0.0, "normalise": 0.0}
+    for (_, ln, branch, before, _, _) in plan:
+        if not branch:
+            continue
+        T = before + ln
+        tot["logits_write"] += 4.0 * w.M * T * chains
+        tot["mixnorm"] += (4.0 * w.M * T + 2.0 * T * w.head_dim * e + 2.0 * w.M * w.head_dim * e) * chains
+        tot["normalise"] += 8.0 * w.M * T * chains
+    return tot
+
+
+def kernel_rooflines(w, plan, flops, kt, steps):
+    """One roofline entry per kernel that ran: the matrix-core fraction of the contractions, the HBM
+    fraction of the passes whose arithmetic intensity is left of the ridge (Eq. 6 alone; Eq. 6 + Eq. 4
+    from fp32 logits: 4 M T d flops over 4 M T bytes = d flop/B)."""
+    by = scan_bytes(w, plan)
+    out = {}
+    for name, (launches, total_ms) in kt.items():
+        if total_ms <= 0:
+            continue
+        sec = total_ms * 1e-3 / steps
+        if name in ("mix_mfma", "normalise_generic"):
+            b = by["mixnorm" if name == "mix_mfma" else "normalise"]
+            out[name] = {"bound": "hbm", "achieved": b / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": b / sec / 1e9 / PEAK_HBM_GBS, "ms_per_step": sec * 1e3}
+        elif name in KERNEL_PARTS:
+            f = sum(flops[p_] for p_ in KERNEL_PARTS[name])
+            out[name] = {"bound": "mfma", "achieved": f / sec / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
+                         "unit": "TFLOP/s", "frac": f / sec / 1e12 / PEAK_BF16_MFMA_TFLOPS, "ms_per_step": sec * 1e3}
+            if name == "conv_logits_mfma":       # its fp32 logits cross HBM: the achieved write rate beside it
+                out[name]["hbm_write_gbs"] = by["logits_write"] / sec / 1e9
+        else:
+            out[name] = {"ms_per_step": sec * 1e3}
+    return out
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and
     workload (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or None."""
@@ -256,6 +298,9 @@ def main():
                          "with B = 1 on a full cache, for this many sequences at once (0 = off)")
     ap.add_argument("--decode-graph", action="store_true",
                     help="with --decode-batch: replay pairs of generation steps from a captured HIP graph")
+    ap.add_argument("--sustain-seconds", type=float, default=2.0,
+                    help="after the timed steps, run sequences back to back for at least this long and report the "
+                         "steady-state rate (the chip is power-limited under matrix load; 0 = skip)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the warm-up, so "
                          "that a rocprofv3 --pmc run has a kernel of known HBM traffic to scale "
@@ -320,6 +365,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kt = lb.lococo_timing_end()
+    # a wait inside the one-launch scan that gave up would end the launch early and look fast
+    if ws is not None and lb.lococo_scan_status(cfg, ws) != 0:
+        print("bench.py: a chain wait inside the one-launch scan gave up; the run is invalid", file=sys.stderr)
+        sys.exit(3)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens = w.batch * w.L
     value = tokens / (ms_per_step * 1e-3)
@@ -337,6 +386,7 @@ def main():
                 "avg_launch_us": total_ms * 1e3 / max(launches, 1),
                 "flops_per_launch": part_flops / max(launches, 1),
                 "kernel_ms_per_step": {n: kt[n][1] / args.steps for n in kt}}
+    path_info = lb.lococo_describe_path(cfg, w.B)
     total_flops = sum(flops.values())
     out = {
         "metric": "segment-step tokens/sec per layer (whole Alg. 2 scan incl. attention, conv "
@@ -349,11 +399,29 @@ def main():
                    "M": w.M, "conv_width": w.conv_width, "conv_channels": w.C,
                    "schedule": "step-by-step" if args.no_history else "batched-attention",
                    "protected_slots": args.protect_sinks, "track_attention": bool(args.track_attention),
-                   "impl": args.impl},
+                   "impl": args.impl, "kernels": path_info},
         "segment_step_tokens_per_s": w.batch * w.B / (ms_per_step * 1e-3 / len(plan)),
         "mfma_util_whole_path": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
         "roofline": roofline,
+        "kernel_rooflines": kernel_rooflines(w, plan, flops, kt, args.steps),
     }
+    if args.sustain_seconds > 0:
+        # steady state: sequences back to back for a couple of seconds, timed as a whole
+        n_seq = max(args.steps, int(args.sustain_seconds / (ms_per_step * 1e-3)) + 1)
+        lb.lococo_timing_begin()
+        t0 = time.perf_counter()
+        for _ in range(n_seq):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kts = lb.lococo_timing_end()
+        if ws is not None and lb.lococo_scan_status(cfg, ws) != 0:
+            print("bench.py: a chain wait inside the one-launch scan gave up; the run is invalid", file=sys.stderr)
+            sys.exit(3)
+        dom_ms = kts[name][1] / n_seq
+        out["sustained"] = {"seconds": t1 - t0, "sequences": n_seq, "value": tokens * n_seq / (t1 - t0), "unit": "tokens/s",
+                            "kernel": name, "avg_launch_us": kts[name][1] * 1e3 / max(kts[name][0], 1),
+                            "frac": part_flops / args.steps / (dom_ms * 1e-3) / 1e12 / peak if dom_ms > 0 else 0.0}
     # what this machine sustains on a bare MFMA loop and a plain copy, after the timed region, so that the
     # fraction can also be read against the measured ceiling (`peak` stays the published figure)
     scratch = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")

@@ -19,8 +19,12 @@
  *    `workspace` argument (see lococo_workspace_bytes).
  *  - Struct pointers (config, cache, qkvo, plan rows) are HOST pointers.
  *  - Layouts are row-major with head_dim contiguous.  Strides are in ELEMENTS.
- *  - Arguments are validated synchronously; on any status other than
- *    LOCOCO_OK nothing was enqueued and `cache` is unchanged.
+ *  - Arguments are validated synchronously; on a validation status (LOCOCO_EINVAL,
+ *    LOCOCO_EUNSUPPORTED, LOCOCO_ESTATE, LOCOCO_EWORKSPACE) nothing was enqueued and
+ *    nothing the caller owns has changed.  LOCOCO_EHIP means that a HIP call failed
+ *    after some kernels of the call may already have been enqueued: the `cache`
+ *    struct (cur / len) is still unchanged, but the cache buffers, the outputs and
+ *    the workspace hold undefined contents.
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *    default stream) and the call returns without synchronising.
  *    `cache->cur` / `cache->len` are updated on the host at enqueue time.
@@ -53,6 +57,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The library is built with hidden visibility; only the functions below are exported. */
+#define LOCOCO_API __attribute__((visibility("default")))
 
 typedef enum lococo_status {
   LOCOCO_OK = 0,
@@ -154,7 +161,7 @@ typedef struct lococo_seg {
 /* Alg. 2 loop bounds and IF, as integers.  *n_inout holds the capacity of
  * `out` on entry (out may be NULL with capacity 0) and the number of blocks
  * on return; at most the capacity is written.  Host pointers. */
-lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_t cur0,
+LOCOCO_API lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_t cur0,
                           lococo_seg* out, int64_t* n_inout);
 
 /* Bytes of device workspace lococo_segment_step (L = B) or
@@ -162,7 +169,7 @@ lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_t
  * `history` != 0 asks for the larger size with which lococo_sequence_forward
  * keeps every intermediate cache and runs all blocks' attention as one
  * batched launch after the compression scan.  May return 0. */
-lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
+LOCOCO_API lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
                                      int32_t history, size_t* out);
 
 /* The filter bank in the form the kernels read (for the MFMA path: Eq. 5's [M, C, k] weights
@@ -170,20 +177,20 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
  * lococo_segment_step / lococo_sequence_forward does this itself unless the configuration
  * carries LOCOCO_FLAG_FILTERS_PREPARED, in which case the caller must have called this function
  * on the same workspace with the same conv_w since either last changed.  Enqueued on `stream`. */
-lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_w, void* workspace,
+LOCOCO_API lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_w, void* workspace,
                                      size_t ws_bytes, void* stream);
 
 /* Alg. 2 step 3 alone: o = Attn([Kc, K_blk], Q_blk, [Vc, V_blk]) for one block
  * of B tokens against the live cache (cache->len slots).  Does not modify the
  * cache.  With an empty cache this is plain causal attention (Eq. 1). */
-lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+LOCOCO_API lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                const lococo_cache* cache, void* stream);
 
 /* One pass of the Alg. 2 loop body: step 3, then either the fill branch or
  * steps 4-5 (Eq. 5, Eq. 6, Eq. 4a/4b) into the other cache buffer.
  * conv_w: [M, C, k] (device, storage dtype); conv_b: [M] or NULL.
  * workspace: device, 256-byte aligned, ws_bytes >= lococo_workspace_bytes(cfg, B, B, 0). */
-lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+LOCOCO_API lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                   const void* conv_w, const void* conv_b, lococo_cache* cache,
                                   void* workspace, size_t ws_bytes, void* stream);
 
@@ -192,42 +199,73 @@ lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* b
  * it.  seq.q/o: [batch, n_q_heads, L, d]; seq.k/v: [batch, n_kv_heads, L, d].
  * If ws_bytes >= lococo_workspace_bytes(cfg, L, B, 1) the batched-attention
  * schedule is used, otherwise the step-by-step one; results are the same. */
-lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
+LOCOCO_API lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
                                       int32_t B, const void* conv_w, const void* conv_b,
                                       lococo_cache* cache, void* workspace, size_t ws_bytes,
                                       void* stream);
 
 /* When lococo_sequence_forward runs a whole scan's compression steps in one launch, the
  * workgroups that share a chain wait for each other between steps with a bounded number of
- * polls.  If a wait ever ran out (it cannot while the launch has the GPU to itself), the kernel
- * leaves early, the outputs of that call are invalid and a status word in the workspace is set.
+ * polls (a few seconds).  That form is chosen only when the whole grid can be resident at once
+ * (the runtime's occupancy figure for the kernel) and no other such launch of this process is
+ * still running on another stream of the device; otherwise every step gets a launch of its own.
+ * Work from elsewhere that keeps compute units busy for longer than the bound (another process, a
+ * long kernel on another stream) can still make a wait run out: the kernel then leaves early, a
+ * status word in the workspace is set, and THE OUTPUTS AND THE CACHE OF THAT CALL ARE INVALID
+ * although it returned LOCOCO_OK at enqueue time.  A caller that shares the GPU must therefore
+ * check lococo_scan_status() == 0 before it uses the results of a lococo_sequence_forward call
+ * made with the larger (history) workspace; a caller that has the GPU to itself need not.
+ *
  * This call SYNCHRONISES with the device and returns that word in *out: 0 = fine, 1 = a wait
  * gave up.  `workspace` is the one passed to lococo_sequence_forward (at least
  * lococo_workspace_bytes(history = 0) bytes); the word is cleared at the start of every such call
  * and means nothing before the first one.  Configurations the MFMA kernels do not serve never
- * wait: *out is 0.
- *
- * Environment variables read by lococo_sequence_forward (for tests and measurements; results are
- * the same bit for bit whatever they say):
- *   LOCOCO_SPIN_LIMIT=n          polls a waiting workgroup makes before it gives up (default 2^24)
- *   LOCOCO_SCAN_LAUNCHES=steps   one launch per compression step instead of one per scan
- *   LOCOCO_CHAIN_SYNC=device     workgroups of a chain always meet with device-scope release and
- *                                acquire (default: without the L2 write-back when they find themselves
- *                                on one XCD)
- *   LOCOCO_LOGITS_TILES=64|128|256  slots per workgroup of the Eq. 5 kernel of the unfused MFMA path
- *                                (default: chosen from the grid size; 256 needs more than 128 slots
- *                                and adds up Eq. 5's fp32 sum in another order: the one knob that can
- *                                move results, by rounding) */
-lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out);
+ * wait: *out is 0.  Under stream capture the in-flight check is skipped: replays of graphs that
+ * hold such a scan must not overlap each other on one device. */
+LOCOCO_API lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out);
+
+/* Test and measurement hooks, process-wide, not thread safe against running calls; none changes
+ * what is computed except LOCOCO_OPT_LOGITS_TILES = 256, which adds up Eq. 5's fp32 sum in another
+ * order.  (Nothing in the library reads environment variables.) */
+enum {
+  LOCOCO_OPT_RESET = 0,             /* every option back to its default; value ignored                         */
+  LOCOCO_OPT_SPIN_LIMIT = 1,        /* polls a waiting workgroup of the one-launch scan makes before it gives
+                                       up (0 = default, 2^21); negative: give up at once                       */
+  LOCOCO_OPT_SCAN_PER_STEP = 2,     /* 1: one launch per compression step even where one per scan fits         */
+  LOCOCO_OPT_CHAIN_SYNC_DEVICE = 3, /* 1: workgroups of a chain always meet with device-scope release and
+                                       acquire (default: without the L2 write-back when they find themselves
+                                       on one XCD)                                                             */
+  LOCOCO_OPT_LOGITS_TILES = 4,      /* 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused
+                                       MFMA path (0 = chosen from the grid size; 256 needs more than 128 slots) */
+  LOCOCO_OPT_MAX_RESIDENT = 5       /* > 0: pretend the device holds only this many workgroups of the scan
+                                       kernel at once (exercises the fall-back to one launch per step)         */
+};
+LOCOCO_API lococo_status lococo_debug_option(int32_t option, int64_t value);
+
+/* Which kernels a configuration runs on, on the current device (for tests and benchmark reports). */
+typedef struct lococo_path_info {
+  int32_t path;                 /* 0: shape-agnostic kernels; 1: fused MFMA compression kernel + MFMA attention;
+                                   2: MFMA attention with separate MFMA kernels for Eq. 5 and Eq. 6 / Eq. 4    */
+  int32_t compute_units;        /* of the current device                                                       */
+  int32_t tile_slots;           /* path 1: cache slots per workgroup of the compression kernel (64 or 32)      */
+  int32_t scan_groups;          /* path 1: workgroups per slot tile when lococo_sequence_forward runs all
+                                   compression steps in one launch (each takes every scan_groups-th chain);
+                                   0 when it would launch every step separately                                */
+  int32_t scan_resident_limit;  /* path 1: workgroups of that kernel the device holds at once                  */
+  int32_t reserved[3];
+} lococo_path_info;
+LOCOCO_API lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_path_info* out);
 
 /* Steps 4-5 with Eq. 5's output supplied by the caller: the cache becomes
  * normalise(logits) . [cache ; block] (Eq. 6, Eq. 4a/4b).  logits: device fp32
  * [batch, n_kv_heads, M, T] contiguous with T = cache->len + B.  Only blk->k
  * and blk->v are read.  Exists so that tests can drive the fusion with chosen
  * weights (e.g. one-hot rows: token selection, the paper's "token dropping"
- * special case).  Always compresses, whatever the occupancy.  Returns LOCOCO_EUNSUPPORTED when
- * cache->protect is set. */
-lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+ * special case).  Always compresses, whatever the occupancy.  With bf16 storage, head_dim 128,
+ * impl != LOCOCO_IMPL_GENERIC and T a multiple of 4 the kernel is the MFMA one of the unfused path
+ * (Eq. 6 and Eq. 4 together), otherwise the shape-agnostic one; a one-hot row selects its entry bit
+ * for bit on either.  Returns LOCOCO_EUNSUPPORTED when cache->protect is set. */
+LOCOCO_API lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                      const float* logits, lococo_cache* cache, void* stream);
 
 /* Backward pass of one block step (lococo_segment_step), for training the convolution heads
@@ -252,8 +290,8 @@ lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo
  * slots is a multiple of 4, the three convolution ones (Eq. 5 and its two gradients) with
  * head_dim 128 and a filter width up to 31 (the workspace is larger then).  Filter gradients are summed
  * with floating-point atomics, so their last bits depend on the order. */
-lococo_status lococo_backward_workspace_bytes(const lococo_config* cfg, int32_t B, int32_t len, size_t* out);
-lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+LOCOCO_API lococo_status lococo_backward_workspace_bytes(const lococo_config* cfg, int32_t B, int32_t len, size_t* out);
+LOCOCO_API lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                            const void* conv_w, const void* conv_b,
                                            const lococo_cache* cache_before, const float* d_o,
                                            const float* d_new_k, const float* d_new_v, float* d_q,
@@ -274,8 +312,8 @@ typedef struct lococo_kernel_time {
   int64_t launches;
   double total_ms;
 } lococo_kernel_time;
-lococo_status lococo_timing_begin(void);
-lococo_status lococo_timing_end(lococo_kernel_time* out, int32_t* n_inout);
+LOCOCO_API lococo_status lococo_timing_begin(void);
+LOCOCO_API lococo_status lococo_timing_end(lococo_kernel_time* out, int32_t* n_inout);
 
 /* Measurement aid for benchmarks (no step of the method): what the current
  * GPU sustains on a bare bf16 MFMA loop (32x32x16, no memory traffic; the
@@ -288,15 +326,15 @@ lococo_status lococo_timing_end(lococo_kernel_time* out, int32_t* n_inout);
  * Runs for about 0.2 s (long enough for the clock to settle under matrix load)
  * and waits for the stream.
  * LOCOCO_EINVAL for null / misaligned / too small arguments. */
-lococo_status lococo_measure_peaks(void* scratch, size_t bytes, void* stream, double* mfma_tflops,
+LOCOCO_API lococo_status lococo_measure_peaks(void* scratch, size_t bytes, void* stream, double* mfma_tflops,
                                    double* copy_gbs);
 
 /* Message for the last non-OK status returned on the calling thread
  * (static thread-local storage; never NULL). */
-const char* lococo_last_error(void);
+LOCOCO_API const char* lococo_last_error(void);
 
 /* Library version, "major.minor.patch". */
-const char* lococo_version(void);
+LOCOCO_API const char* lococo_version(void);
 
 #ifdef __cplusplus
 }

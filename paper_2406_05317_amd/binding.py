@@ -19,12 +19,14 @@ LOCOCO_OK, LOCOCO_EINVAL, LOCOCO_EUNSUPPORTED, LOCOCO_ESTATE, LOCOCO_EHIP, LOCOC
 LOCOCO_F32, LOCOCO_BF16 = 0, 1
 LOCOCO_IMPL_AUTO, LOCOCO_IMPL_GENERIC, LOCOCO_IMPL_MFMA = 0, 1, 2
 LOCOCO_FLAG_FILTERS_PREPARED = 1
+(LOCOCO_OPT_RESET, LOCOCO_OPT_SPIN_LIMIT, LOCOCO_OPT_SCAN_PER_STEP, LOCOCO_OPT_CHAIN_SYNC_DEVICE,
+ LOCOCO_OPT_LOGITS_TILES, LOCOCO_OPT_MAX_RESIDENT) = range(6)
 
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
            "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status",
            "lococo_prepare_filters", "lococo_backward_workspace_bytes", "lococo_segment_step_backward",
-           "lococo_measure_peaks"]
+           "lococo_measure_peaks", "lococo_debug_option", "lococo_describe_path"]
 
 
 class lococo_config(C.Structure):
@@ -60,6 +62,11 @@ class lococo_seg(C.Structure):
 
 class lococo_kernel_time(C.Structure):
     _fields_ = [("name", C.c_char_p), ("launches", C.c_int64), ("total_ms", C.c_double)]
+
+
+class lococo_path_info(C.Structure):
+    _fields_ = [("path", C.c_int32), ("compute_units", C.c_int32), ("tile_slots", C.c_int32),
+                ("scan_groups", C.c_int32), ("scan_resident_limit", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 class LococoError(RuntimeError):
@@ -98,6 +105,8 @@ def lib():
             C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_measure_peaks.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double),
                                            C.POINTER(C.c_double)]
+        L.lococo_debug_option.argtypes = [C.c_int32, C.c_int64]
+        L.lococo_describe_path.argtypes = [cfgp, C.c_int32, C.POINTER(lococo_path_info)]
         L.lococo_timing_begin.argtypes = []
         L.lococo_timing_end.argtypes = [C.POINTER(lococo_kernel_time), C.POINTER(C.c_int32)]
         for n in EXPORTS[:6] + EXPORTS[8:]:
@@ -302,6 +311,19 @@ def lococo_measure_peaks(scratch: torch.Tensor) -> tuple:
     _check(lib().lococo_measure_peaks(_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(),
                                       C.byref(tf), C.byref(gbs)))
     return tf.value, gbs.value
+
+
+def lococo_debug_option(option: int, value: int = 0):
+    """Process-wide test / measurement hook (see LOCOCO_OPT_* in lococo.h)."""
+    _check(lib().lococo_debug_option(option, value))
+
+
+def lococo_describe_path(cfg, B: int) -> dict:
+    """Which kernels the configuration runs on, on the current device."""
+    out = lococo_path_info()
+    _check(lib().lococo_describe_path(C.byref(cfg), B, C.byref(out)))
+    return {"path": out.path, "compute_units": out.compute_units, "tile_slots": out.tile_slots,
+            "scan_groups": out.scan_groups, "scan_resident_limit": out.scan_resident_limit}
 
 
 def lococo_timing_begin():

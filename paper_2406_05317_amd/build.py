@@ -20,7 +20,7 @@ SOURCES = ["api.cpp", "generic_kernels.hip", "compress_mfma.hip", "attn_mfma.hip
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument",
+         "-fvisibility=hidden", "-Wall", "-Wno-unused-command-line-argument",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
@@ -33,7 +33,7 @@ EXTRA = {"compress_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form",
                                 # "#pragma unroll" is too small for the width-21 instantiation
                                 "-mllvm", "-pragma-unroll-threshold=200000"],
          # accumulators in ordinary registers: the softmax reads the scores where the MFMA left them
-         "attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"]}
+         "attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:

@@ -15,6 +15,24 @@
 using namespace lococo;
 
 namespace {
+DebugOptions g_debug = {0, 0, 0, 0, 0};
+}
+namespace lococo {
+const DebugOptions& debug_options() { return g_debug; }
+int cu_count() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n = prop.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
+}
+}  // namespace lococo
+
+namespace {
 
 thread_local char g_err[512] = "";
 
@@ -179,18 +197,6 @@ Path choose_path(const lococo_config* c, int32_t B, const char** why) {
 
 int filter_banks(const lococo_config* c) { return c->w_head_stride ? c->n_kv_heads : 1; }
 
-int cu_count() {
-  static int n = 0;
-  if (!n) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      n = prop.multiProcessorCount;
-    if (n <= 0) n = 256;
-  }
-  return n;
-}
-
 lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
   const char* why = "";
   Path p = c->impl == LOCOCO_IMPL_GENERIC ? PATH_GENERIC : choose_path(c, B, &why);
@@ -240,26 +246,64 @@ size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_
   return step_ws_bytes(c, path, B) + stats_bytes(c, L) + 2 * (size_t)n_compress * align_up(state_bytes(c), 256);
 }
 
-// Polls a waiting workgroup makes before it gives up on its chain (each poll sleeps ~256 cycles);
-// LOCOCO_SPIN_LIMIT overrides it, which is how the tests force the give-up path from the host.
+// Polls a waiting workgroup makes before it gives up on its chain (each poll sleeps ~128 cycles and
+// reads the counter from the L2: roughly a microsecond, so the default bounds a wait to a few
+// seconds).  The tests force the give-up path from the host with a limit of -1.
 int spin_limit() {
-  const char* e = getenv("LOCOCO_SPIN_LIMIT");
-  return e ? atoi(e) : (1 << 24);
+  return g_debug.spin_limit ? (int)g_debug.spin_limit : (1 << 21);
 }
-// LOCOCO_CHAIN_SYNC=device makes the slot tiles of a chain always meet with device-scope release and
-// acquire between the steps of the one-launch scan; by default they skip the L2 write-back when
-// they find themselves on one XCD (see compress_mfma.hip).
-bool chain_sync_through_l2() {
-  const char* e = getenv("LOCOCO_CHAIN_SYNC");
-  return !(e && !strcmp(e, "device"));
+// By default the slot tiles of a chain skip the L2 write-back between the steps of the one-launch
+// scan when they find themselves on one XCD (see compress_mfma.hip).
+bool chain_sync_through_l2() { return g_debug.chain_sync_device == 0; }
+
+// One launch for all compression steps of a scan needs every workgroup of it resident at once: the
+// grid must fit the occupancy the runtime reports for the kernel, and no other such launch of this
+// process may still be running on another stream of the device (two of them could each hold part of
+// the compute units and wait for workgroups that never become resident).
+constexpr int kMaxDevices = 64;
+struct ScanInFlight { hipEvent_t done = nullptr; hipStream_t stream = nullptr; bool valid = false; };
+ScanInFlight g_scan[kMaxDevices];
+std::mutex g_scan_mu;
+
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return st != hipStreamCaptureStatusNone;
 }
-// LOCOCO_SCAN_LAUNCHES=steps forces one launch per compress step (the default is one launch for
-// the whole scan whenever every workgroup can be resident at once).
-bool scan_in_one_launch(const lococo_config* c) {
-  const char* e = getenv("LOCOCO_SCAN_LAUNCHES");
-  if (e && !strcmp(e, "steps")) return false;
-  return compress_scan_groups(c->batch, c->n_kv_heads, c->M, c->conv_width,
-                              c->w_head_stride != 0 || c->b_head_stride != 0, cu_count()) > 0;
+
+// call with g_scan_mu held
+bool another_scan_in_flight(hipStream_t s) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return true;
+  ScanInFlight& g = g_scan[dev];
+  if (!g.valid || g.stream == s) return false;        // same stream: ordered behind it
+  const hipError_t e = hipEventQuery(g.done);
+  if (e == hipSuccess) { g.valid = false; return false; }
+  (void)hipGetLastError();
+  return true;                                        // not ready (or unknown): assume it still runs
+}
+void note_scan_launched(hipStream_t s) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return;
+  ScanInFlight& g = g_scan[dev];
+  if (!g.done && hipEventCreateWithFlags(&g.done, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    g.done = nullptr;
+    return;
+  }
+  if (hipEventRecord(g.done, s) == hipSuccess) { g.stream = s; g.valid = true; }
+  else (void)hipGetLastError();
+}
+
+// Whether the shape allows the one-launch form at all (grid rule and occupancy); the in-flight check
+// is made under the lock right before the launch.
+bool scan_fits_one_launch(const lococo_config* c, const StepArgs& a) {
+  if (g_debug.scan_per_step) return false;
+  const int groups = compress_scan_groups(c->batch, c->n_kv_heads, c->M, c->conv_width,
+                                          c->w_head_stride != 0 || c->b_head_stride != 0, cu_count());
+  if (groups <= 0) return false;
+  const int64_t grid = (int64_t)groups * (c->M / compress_tile_slots(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count()));
+  return grid <= compress_scan_max_resident(a, cu_count());
 }
 
 View view_at(const lococo_tensor& t, int64_t tok, size_t es) {
@@ -308,6 +352,23 @@ lococo_status check_step_shape(const lococo_config* c, int32_t B, int32_t len) {
   if ((int64_t)len + B > generic_attn_max_T())
     return fail(LOCOCO_EUNSUPPORTED, "cache.len + B = %lld exceeds the supported %d",
                 (long long)len + B, generic_attn_max_T());
+  return LOCOCO_OK;
+}
+
+// The MFMA kernels address the rows of a block with 32-bit byte offsets inside buffer resources of
+// less than 2 GiB (out-of-range rows must read as zero): a block's rows have to span less than that.
+lococo_status check_mfma_strides(const lococo_config* c, Path path, const lococo_qkvo* x, int32_t B, bool with_q) {
+  if (path == PATH_GENERIC) return LOCOCO_OK;
+  const int64_t lim = 0x7fff0000;
+  const lococo_tensor* t[4] = {&x->k, &x->v, &x->q, &x->o};
+  const char* names[4] = {"k", "v", "q", "o"};
+  for (int i = 0; i < (with_q ? 4 : 2); ++i)
+    if (((int64_t)B * t[i]->stride_t + c->head_dim) * (int64_t)esize(c->dtype) >= lim)
+      return fail(LOCOCO_EUNSUPPORTED, "%s: a block of %d tokens with stride_t %lld spans 2 GiB or more; the MFMA "
+                  "kernels address a block's rows with 32-bit offsets (use impl = GENERIC)", names[i], B,
+                  (long long)t[i]->stride_t);
+  if ((int64_t)c->M * c->head_dim * (int64_t)esize(c->dtype) >= lim)
+    return fail(LOCOCO_EUNSUPPORTED, "a chain's cache spans 2 GiB or more");
   return LOCOCO_OK;
 }
 
@@ -436,12 +497,86 @@ lococo_status enqueue_update(const lococo_config* c, Path path, StepArgs a, loco
   return LOCOCO_OK;
 }
 
+lococo_status segment_step_impl(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                const void* conv_w, const void* conv_b, lococo_cache* cache,
+                                void* workspace, size_t ws_bytes, void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache))) return st;
+  if ((st = check_step_shape(cfg, B, cache->len))) return st;
+  if ((st = check_qkvo(cfg, blk, B, true))) return st;
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  if ((st = check_mfma_strides(cfg, path, blk, B, true))) return st;
+  const bool compress = cache->len + B > cfg->M;
+  if (compress) {
+    if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL but this step compresses");
+    const size_t need = step_ws_bytes(cfg, path, B);
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)))
+      return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
+                  workspace ? ws_bytes : (size_t)0);
+  }
+  StepArgs a = make_args(cfg, blk, 0, B, cache, conv_w, conv_b, true);
+  lococo_cache tmp = *cache;
+  if (compress && path != PATH_GENERIC &&
+      (st = enqueue_repack(cfg, path, a, workspace, (hipStream_t)stream)))
+    return st;
+  if ((st = enqueue_attn(cfg, path, a, step_stats(cfg, path, B, workspace, ws_bytes), (hipStream_t)stream)))
+    return st;
+  if ((st = enqueue_update(cfg, path, a, &tmp, workspace, B, (hipStream_t)stream))) return st;
+  *cache = tmp;
+  return LOCOCO_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
 const char* lococo_last_error(void) { return g_err; }
 const char* lococo_version(void) { return "0.2.0"; }
+
+lococo_status lococo_debug_option(int32_t option, int64_t value) {
+  switch (option) {
+    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0}; return LOCOCO_OK;
+    case LOCOCO_OPT_SPIN_LIMIT: g_debug.spin_limit = value; return LOCOCO_OK;
+    case LOCOCO_OPT_SCAN_PER_STEP: g_debug.scan_per_step = value != 0; return LOCOCO_OK;
+    case LOCOCO_OPT_CHAIN_SYNC_DEVICE: g_debug.chain_sync_device = value != 0; return LOCOCO_OK;
+    case LOCOCO_OPT_LOGITS_TILES:
+      if (value != 0 && value != 64 && value != 128 && value != 256)
+        return fail(LOCOCO_EINVAL, "LOCOCO_OPT_LOGITS_TILES takes 0, 64, 128 or 256");
+      g_debug.logits_tiles = value;
+      return LOCOCO_OK;
+    case LOCOCO_OPT_MAX_RESIDENT:
+      if (value < 0) return fail(LOCOCO_EINVAL, "LOCOCO_OPT_MAX_RESIDENT takes a count >= 0");
+      g_debug.max_resident = value;
+      return LOCOCO_OK;
+    default: return fail(LOCOCO_EINVAL, "unknown debug option %d", option);
+  }
+}
+
+lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_path_info* out) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (!out) return fail(LOCOCO_EINVAL, "out is NULL");
+  if (B <= 0) return fail(LOCOCO_EINVAL, "block length B must be positive");
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  std::memset(out, 0, sizeof(*out));
+  out->path = (int32_t)path;
+  out->compute_units = cu_count();
+  if (path == PATH_MFMA) {
+    out->tile_slots = compress_tile_slots(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cu_count());
+    StepArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.batch = cfg->batch; a.Hkv = cfg->n_kv_heads; a.M = cfg->M; a.k_width = cfg->conv_width; a.norm = cfg->norm;
+    a.w_head_stride = cfg->w_head_stride; a.b_head_stride = cfg->b_head_stride;
+    out->scan_resident_limit = compress_scan_max_resident(a, cu_count());
+    if (scan_fits_one_launch(cfg, a))
+      out->scan_groups = compress_scan_groups(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width,
+                                              cfg->w_head_stride != 0 || cfg->b_head_stride != 0, cu_count());
+  }
+  return LOCOCO_OK;
+}
 
 lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out) {
   lococo_status st;
@@ -556,6 +691,7 @@ lococo_status lococo_attn_only(const lococo_config* cfg, const lococo_qkvo* blk,
   if ((st = check_qkvo(cfg, blk, B, true))) return st;
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
+  if ((st = check_mfma_strides(cfg, path, blk, B, true))) return st;
   StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, true);
   return enqueue_attn(cfg, path, a, nullptr, (hipStream_t)stream);
 }
@@ -586,31 +722,7 @@ lococo_status lococo_prepare_filters(const lococo_config* cfg, const void* conv_
 lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                   const void* conv_w, const void* conv_b, lococo_cache* cache,
                                   void* workspace, size_t ws_bytes, void* stream) {
-  lococo_status st;
-  if ((st = check_config(cfg))) return st;
-  if ((st = check_cache(cfg, cache))) return st;
-  if ((st = check_step_shape(cfg, B, cache->len))) return st;
-  if ((st = check_qkvo(cfg, blk, B, true))) return st;
-  Path path;
-  if ((st = resolve_path(cfg, B, &path))) return st;
-  const bool compress = cache->len + B > cfg->M;
-  if (compress) {
-    if (!conv_w) return fail(LOCOCO_EINVAL, "conv_w is NULL but this step compresses");
-    const size_t need = step_ws_bytes(cfg, path, B);
-    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)))
-      return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", need,
-                  workspace ? ws_bytes : (size_t)0);
-  }
-  StepArgs a = make_args(cfg, blk, 0, B, cache, conv_w, conv_b, true);
-  lococo_cache tmp = *cache;
-  if (compress && path != PATH_GENERIC &&
-      (st = enqueue_repack(cfg, path, a, workspace, (hipStream_t)stream)))
-    return st;
-  if ((st = enqueue_attn(cfg, path, a, step_stats(cfg, path, B, workspace, ws_bytes), (hipStream_t)stream)))
-    return st;
-  if ((st = enqueue_update(cfg, path, a, &tmp, workspace, B, (hipStream_t)stream))) return st;
-  *cache = tmp;
-  return LOCOCO_OK;
+  return segment_step_impl(cfg, blk, B, conv_w, conv_b, cache, workspace, ws_bytes, stream);
 }
 
 lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
@@ -666,7 +778,11 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
     char* hist_v = hist_k + (size_t)n_compress * slot;
     const void* src_k = tmp.k[tmp.cur];
     const void* src_v = tmp.v[tmp.cur];
-    const bool one_launch = path == PATH_MFMA && scan_in_one_launch(cfg);
+    bool one_launch = false;
+    if (path == PATH_MFMA) {
+      StepArgs probe = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
+      one_launch = scan_fits_one_launch(cfg, probe);
+    }
     int64_t step = 0;
     for (const auto& sg : plan) {
       StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
@@ -674,26 +790,35 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
       if (sg.branch == 1 && one_launch) {
         // every later block compresses too (the cache stays full): one launch runs them all,
         // the slot tiles of a chain handing the new cache to each other through the history
-        a.cache_k = src_k;
-        a.cache_v = src_v;
-        ScanArgs sa;
-        sa.st = a;
-        sa.n_steps = (int32_t)n_compress;
-        sa.B = B;
-        sa.tokens_left = L - sg.start;
-        sa.out_k = hist_k;
-        sa.out_v = hist_v;
-        sa.out_stride = (int64_t)(slot / esize(cfg->dtype));
-        sa.sync = nullptr;
-        sa.status = nullptr;
-        sa.spin_limit = spin_limit();
-        sa.same_l2_allowed = chain_sync_through_l2() ? 1 : 0;
-        KTimer t(K_COMPRESS_MFMA, s);
-        HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
-                "compress scan launch");
-        src_k = hist_k + (size_t)(n_compress - 1) * slot;
-        src_v = hist_v + (size_t)(n_compress - 1) * slot;
-        break;
+        const bool capturing = stream_is_capturing(s);
+        std::unique_lock<std::mutex> lk(g_scan_mu);
+        if (!capturing && another_scan_in_flight(s)) {
+          one_launch = false;            // another persistent scan holds compute units: one launch per step
+        } else {
+          a.cache_k = src_k;
+          a.cache_v = src_v;
+          ScanArgs sa;
+          sa.st = a;
+          sa.n_steps = (int32_t)n_compress;
+          sa.B = B;
+          sa.tokens_left = L - sg.start;
+          sa.out_k = hist_k;
+          sa.out_v = hist_v;
+          sa.out_stride = (int64_t)(slot / esize(cfg->dtype));
+          sa.sync = nullptr;
+          sa.status = nullptr;
+          sa.spin_limit = spin_limit();
+          sa.same_l2_allowed = chain_sync_through_l2() ? 1 : 0;
+          {
+            KTimer t(K_COMPRESS_MFMA, s);
+            HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
+                    "compress scan launch");
+          }
+          if (!capturing) note_scan_launched(s);
+          src_k = hist_k + (size_t)(n_compress - 1) * slot;
+          src_v = hist_v + (size_t)(n_compress - 1) * slot;
+          break;
+        }
       }
       if (sg.branch == 0) {
         a.new_k = tmp.k[tmp.cur];
@@ -862,10 +987,21 @@ lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo
   if (!logits) return fail(LOCOCO_EINVAL, "logits is NULL");
   if (cache->protect)
     return fail(LOCOCO_EUNSUPPORTED, "lococo_mix_from_logits does not take protected slots");
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  if ((st = check_mfma_strides(cfg, path, blk, B, false))) return st;
   StepArgs a = make_args(cfg, blk, 0, B, cache, nullptr, nullptr, false);
   a.new_k = cache->k[cache->cur ^ 1];
   a.new_v = cache->v[cache->cur ^ 1];
-  HIP_TRY(launch_mix_generic(cfg->dtype, a, logits, 1, (hipStream_t)stream), "mix launch");
+  // bf16 / head_dim 128 unless the shape-agnostic kernels are asked for: Eq. 6 and Eq. 4 on the matrix
+  // cores (the kernel of the unfused MFMA path), which needs rows of logits that start 16-byte aligned
+  if (path != PATH_GENERIC && mixnorm_mfma_fits(a, logits)) {
+    KTimer t(K_MIX_MFMA, (hipStream_t)stream);
+    HIP_TRY(launch_mixnorm_mfma(a, logits, (hipStream_t)stream), "mix launch");
+  } else {
+    KTimer t(K_MIX_GENERIC, (hipStream_t)stream);
+    HIP_TRY(launch_mix_generic(cfg->dtype, a, logits, 1, (hipStream_t)stream), "mix launch");
+  }
   cache->cur ^= 1;
   cache->len = cfg->M;
   return LOCOCO_OK;

@@ -104,8 +104,10 @@ constexpr int LDS_BYTES = 4 * TBYTES;           // K(2) + V(2)
 // writes cell l).  Counted by vmcnt; the compiler does not know that LDS is written, so the wait
 // and the barrier that publish the tile are written by hand.
 __device__ __forceinline__ void load_to_lds(const u32x4& rsrc, uint32_t lds_addr, int voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+  // M0 (the LDS address) is an operand the compiler sets itself; the wait state the hardware wants
+  // between a write of M0 and such a load is the s_nop
+  asm volatile("s_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "{m0}"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
 }
 
 __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {

@@ -782,25 +782,55 @@ __global__ void zero_words_k(uint32_t* p, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
 }
 
+// The instantiation a shape runs on, handed to `f` as compile-time constants (BM, KW, NORM, PROT, MULTI).
+// 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles; the filter
+// slice of a 64-slot tile fits the registers for width 15 only.
+bool use_big_tiles(int batch, int Hkv, int M, int k_width, int n_cu) {
+  return k_width == 15 && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
+}
+template <int V> using ic = std::integral_constant<int, V>;
+template <class F>
+hipError_t with_instantiation(const StepArgs& t, bool multi, int n_cu, F&& f) {
+  const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
+  auto pick_multi = [&](auto bm, auto kw, auto norm, auto prot) {
+    return multi ? f(bm, kw, norm, prot, ic<1>{}) : f(bm, kw, norm, prot, ic<0>{});
+  };
+  auto pick_prot = [&](auto bm, auto kw, auto norm) {
+    return t.protect ? pick_multi(bm, kw, norm, ic<1>{}) : pick_multi(bm, kw, norm, ic<0>{});
+  };
+  auto pick_norm = [&](auto bm, auto kw) {
+    return t.norm == 1 ? pick_prot(bm, kw, ic<1>{}) : pick_prot(bm, kw, ic<0>{});
+  };
+  if (t.k_width == 15) return big ? pick_norm(ic<64>{}, ic<15>{}) : pick_norm(ic<32>{}, ic<15>{});
+  if (t.k_width == 21) return pick_norm(ic<32>{}, ic<21>{});
+  return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
+}
+
 template <int BM, int KW, int NORM, int PROT, int MULTI>
-hipError_t launch_kernel(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
-  using G = Geo<BM, KW>;
+hipError_t prepare_kernel() {
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Geo<BM, KW>::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((a.st.M / BM) * a.groups);
-  hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI>), grid, dim3(kThreads), G::LDS, s, a, wp,
-                     wp_head_stride);
-  return hipGetLastError();
+  return hipSuccess;
 }
-template <int BM, int KW, int NORM, int PROT>
-hipError_t launch_one(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, hipStream_t s) {
-  return a.groups < a.st.batch * a.st.Hkv ? launch_kernel<BM, KW, NORM, PROT, 1>(a, wp, wp_head_stride, s)
-                                          : launch_kernel<BM, KW, NORM, PROT, 0>(a, wp, wp_head_stride, s);
+
+hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
+  const bool multi = a.groups < a.st.batch * a.st.Hkv;
+  return with_instantiation(a.st, multi, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu) {
+    constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
+    constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value;
+    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI>();
+    if (e != hipSuccess) return e;
+    dim3 grid((a.st.M / BM) * a.groups);
+    constexpr int kLds = Geo<BM, KW>::LDS;
+    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI>), grid, dim3(kThreads), kLds, s, a, wp,
+                       wp_head_stride);
+    return hipGetLastError();
+  });
 }
 
 }  // namespace
@@ -832,30 +862,6 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
   return hipGetLastError();
 }
 
-namespace {
-// 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles; the
-// filter slice of a 64-slot tile fits the registers for width 15 only
-bool use_big_tiles(int batch, int Hkv, int M, int k_width, int n_cu) {
-  return k_width == 15 && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
-}
-template <int PROT>
-hipError_t dispatch_shape(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
-  const StepArgs& t = a.st;
-  const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
-  if (t.k_width == 15 && t.norm == 0)
-    return big ? launch_one<64, 15, 0, PROT>(a, wp, wp_head_stride, s) : launch_one<32, 15, 0, PROT>(a, wp, wp_head_stride, s);
-  if (t.k_width == 15 && t.norm == 1)
-    return big ? launch_one<64, 15, 1, PROT>(a, wp, wp_head_stride, s) : launch_one<32, 15, 1, PROT>(a, wp, wp_head_stride, s);
-  if (t.k_width == 21 && t.norm == 0) return launch_one<32, 21, 0, PROT>(a, wp, wp_head_stride, s);
-  if (t.k_width == 21 && t.norm == 1) return launch_one<32, 21, 1, PROT>(a, wp, wp_head_stride, s);
-  return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
-}
-hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
-  return a.st.protect ? dispatch_shape<1>(a, wp, wp_head_stride, n_cu, s)
-                      : dispatch_shape<0>(a, wp, wp_head_stride, n_cu, s);
-}
-}  // namespace
-
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
                                 hipStream_t s) {
   ScanArgs sa;
@@ -876,6 +882,27 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   if (sa.groups <= 0) sa.groups = a.batch * a.Hkv;
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
   return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
+}
+
+int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu) {
+  return use_big_tiles(batch, Hkv, M, k_width, n_cu) ? 64 : 32;
+}
+
+int compress_scan_max_resident(const StepArgs& a, int n_cu) {
+  if (debug_options().max_resident > 0) return (int)debug_options().max_resident;
+  const int groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
+  int per_cu = 0;
+  hipError_t e = with_instantiation(a, groups < a.batch * a.Hkv, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu) {
+    constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
+    constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value;
+    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI>();
+    if (e2 != hipSuccess) return e2;
+    constexpr int kLds = Geo<BM, KW>::LDS;
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI>,
+                                                        kThreads, kLds);
+  });
+  if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
+  return per_cu * n_cu;
 }
 
 int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, int n_cu) {

@@ -9,6 +9,18 @@
 
 namespace lococo {
 
+// Process-wide test and measurement hooks (lococo_debug_option); every field 0 by default.
+struct DebugOptions {
+  int64_t spin_limit;         // polls a waiting workgroup makes before it gives up (0: the default)
+  int64_t scan_per_step;      // 1: one launch per compression step even where one launch per scan fits
+  int64_t chain_sync_device;  // 1: the slot tiles of a chain always meet with device-scope release / acquire
+  int64_t logits_tiles;       // 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused MFMA path
+  int64_t max_resident;       // > 0: pretend that only this many workgroups of the scan kernel fit the GPU at once
+};
+const DebugOptions& debug_options();
+// compute units of the current device
+int cu_count();
+
 // View of a [batch, heads, tokens, d] tensor, strides in elements.
 struct View {
   const void* p;
@@ -147,6 +159,12 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
 // resident at once (each takes every groups-th chain); 0 if there is no such number.  per_head:
 // filters or biases differ between kv heads.
 int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, int n_cu);
+// Workgroups of the scan kernel (the instantiation this shape runs on) the current device can hold at
+// once, from the runtime's occupancy query; <= 0 if the query failed.  The one-launch scan needs its
+// whole grid resident.
+int compress_scan_max_resident(const StepArgs& a, int n_cu);
+// cache slots per workgroup of the fused kernel for this shape on a device with n_cu compute units
+int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu);
 // bytes of the sync counters + status word the scan launch needs
 size_t compress_scan_sync_bytes(int batch, int Hkv);
 // zero them (a fill kernel, so the call may sit inside a captured graph)

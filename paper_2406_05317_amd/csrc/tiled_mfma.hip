@@ -259,8 +259,10 @@ __global__ __launch_bounds__(KV ? 512 : 256, KV ? 1 : 2) void conv_logits_mfma_k
 // c ^ ((r / 2) % 8), which spreads 16 consecutive rows over the 16 cells of 256 bytes; each lane
 // requests whatever chunk belongs in its cell.
 __device__ __forceinline__ void load_to_lds_at(const u32x4& rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+  // M0 (the LDS address) is an operand the compiler sets itself; the wait state the hardware wants
+  // between a write of M0 and such a load is the s_nop
+  asm volatile("s_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "{m0}"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 // A 16-byte load the compiler does not wait for; the caller counts the loads in flight (they
 // complete in order, those into LDS included) and waits by hand before the first use.
@@ -1153,17 +1155,19 @@ static hipError_t launch_logits_wide(const StepArgs& a, const void* wt, float* l
 }
 // Three tile shapes.  64 and 128 slots give the same bits (every output element is the same sum in
 // the same order: taps outermost); the 256 x 256 kernel walks the channel quarters outermost, so its
-// fp32 sums differ from theirs in rounding.  LOCOCO_LOGITS_TILES = 64 | 128 | 256 overrides the
-// choice by grid size, for tests and measurements; 256 is ignored where there are at most 128 slots.
+// fp32 sums differ from theirs in rounding.  The debug option LOCOCO_OPT_LOGITS_TILES (64 | 128 | 256)
+// overrides the choice by grid size, for tests and measurements; 256 is ignored where there are at most
+// 128 slots.
 hipError_t launch_conv_logits_mfma(const StepArgs& a, const void* wt, float* logits, hipStream_t s) {
   const int Tn = a.m + a.Bn, chains = a.batch * a.Hkv;
   const int64_t tiles256 = (int64_t)((Tn + 255) / 256) * ((a.M + 255) / 256) * chains;
   const int64_t tiles128 = (int64_t)((Tn + kTile - 1) / kTile) * ((a.M + kTile - 1) / kTile) * chains;
   // 256 x 256 where there are enough of those tiles for three quarters of the compute units;
   // 64-slot tiles where 128-slot ones would be fewer than the compute units
-  int shape = a.M > kTile && tiles256 >= 192 ? 256 : tiles128 < 256 ? 64 : 128;
-  if (const char* e = getenv("LOCOCO_LOGITS_TILES")) {
-    const int v = atoi(e);
+  const int n_cu = cu_count();
+  int shape = a.M > kTile && tiles256 >= n_cu * 3 / 4 ? 256 : tiles128 < n_cu ? 64 : 128;
+  {
+    const int v = (int)debug_options().logits_tiles;
     if (v == 64 || v == 128 || (v == 256 && a.M > kTile)) shape = v;
   }
   if (shape == 256) return a.conv_in ? launch_logits_wide<4>(a, wt, logits, s) : launch_logits_wide<2>(a, wt, logits, s);
@@ -1239,11 +1243,12 @@ bool mixnorm_mfma_fits(const StepArgs& a, const float* logits) {
 hipError_t launch_mixnorm_mfma(const StepArgs& a, const float* logits, hipStream_t s) {
   const int ld = a.ldw ? a.ldw : a.m + a.Bn;
   const int chains = a.batch * a.Hkv;
-  if ((int64_t)((a.M + 127) / 128) * chains >= 256) {       // enough 128-slot tiles for every compute unit
+  const int n_cu = cu_count();
+  if ((int64_t)((a.M + 127) / 128) * chains >= n_cu) {      // enough 128-slot tiles for every compute unit
     const dim3 grid((a.M + 127) / 128 * chains);
     if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 128, 512>), grid, dim3(512), 0, s, a, logits, ld);
     else hipLaunchKernelGGL((mixnorm_mfma_k<1, 128, 512>), grid, dim3(512), 0, s, a, logits, ld);
-  } else if ((int64_t)((a.M + 63) / 64) * chains >= 128) {  // (with 256 of these, 512 tiles of 32 slots are slower)
+  } else if ((int64_t)((a.M + 63) / 64) * chains >= n_cu / 2) {  // (with one per compute unit of these, twice as many of 32 slots are slower)
     const dim3 grid((a.M + 63) / 64 * chains);
     if (a.norm == 0) hipLaunchKernelGGL((mixnorm_mfma_k<0, 64, 512>), grid, dim3(512), 0, s, a, logits, ld);
     else hipLaunchKernelGGL((mixnorm_mfma_k<1, 64, 512>), grid, dim3(512), 0, s, a, logits, ld);

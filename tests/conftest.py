@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture
+def options():
+    """Setter for the library's process-wide test hooks (lococo_debug_option); all of them are back
+    at their defaults when the test ends."""
+    from paper_2406_05317_amd import binding as lb
+    lb.lococo_debug_option(lb.LOCOCO_OPT_RESET)
+    yield lb.lococo_debug_option
+    lb.lococo_debug_option(lb.LOCOCO_OPT_RESET)

@@ -162,3 +162,47 @@ def test_prepare_filters_rejects_bad_arguments_before_touching_the_gpu():
     with pytest.raises(lb.LococoError) as e:
         lb.lococo_workspace_bytes(cfg, 128, 128)
     assert e.value.status == lb.LOCOCO_EINVAL
+
+
+def test_blocks_that_span_2_gib_are_refused_on_the_mfma_paths():
+    """The MFMA kernels address the rows of a block with 32-bit offsets inside buffer resources; a
+    token stride that makes a block span 2 GiB or more is refused at validation, and the
+    shape-agnostic kernels (64-bit addressing) still take it."""
+    L = lb.lib()
+    cfg = lb.make_config(dtype=torch.bfloat16, batch=1, n_q_heads=4, n_kv_heads=4, head_dim=128, M=128,
+                         conv_width=15)
+    fake = [0x100000, 0x200000, 0x300000, 0x400000]    # never dereferenced: validation fails first
+    cache = lb.lococo_cache((C.c_void_p * 2)(fake[0], fake[1]), (C.c_void_p * 2)(fake[2], fake[3]), 0, 0)
+    huge = 1 << 24                                     # elements between tokens: 128 tokens * 32 MiB = 4 GiB
+    t = lambda p: lb.lococo_tensor(p, 0, 128, huge)
+    x = lb.lococo_qkvo(t(0x500000), t(0x600000), t(0x700000), t(0x800000))
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 128, C.byref(cache), None) == lb.LOCOCO_EUNSUPPORTED
+    assert b"2 GiB" in L.lococo_last_error()
+    assert L.lococo_segment_step(C.byref(cfg), C.byref(x), 128, 0x900000, None, C.byref(cache), 0xa00000,
+                                 1 << 30, None) == lb.LOCOCO_EUNSUPPORTED
+    assert cache.len == 0 and cache.cur == 0
+    cache.len = 128
+    assert L.lococo_mix_from_logits(C.byref(cfg), C.byref(x), 128, 0xb00000, C.byref(cache),
+                                    None) == lb.LOCOCO_EUNSUPPORTED
+    assert cache.len == 128 and cache.cur == 0
+
+
+def test_debug_options_are_validated_and_path_description_needs_no_gpu_for_generic_shapes():
+    assert C.sizeof(lb.lococo_path_info) == 32
+    L = lb.lib()
+    assert L.lococo_debug_option(99, 0) == lb.LOCOCO_EINVAL
+    assert L.lococo_debug_option(lb.LOCOCO_OPT_LOGITS_TILES, 100) == lb.LOCOCO_EINVAL
+    assert L.lococo_debug_option(lb.LOCOCO_OPT_MAX_RESIDENT, -3) == lb.LOCOCO_EINVAL
+    assert L.lococo_debug_option(lb.LOCOCO_OPT_LOGITS_TILES, 128) == lb.LOCOCO_OK
+    assert L.lococo_debug_option(lb.LOCOCO_OPT_RESET, 0) == lb.LOCOCO_OK
+    info = lb.lococo_describe_path(_cfg(), 4)          # fp32, head_dim 8: the shape-agnostic kernels
+    assert info["path"] == 0 and info["tile_slots"] == 0 and info["scan_groups"] == 0
+    assert L.lococo_describe_path(C.byref(_cfg()), 0, C.byref(lb.lococo_path_info())) == lb.LOCOCO_EINVAL
+    assert L.lococo_describe_path(C.byref(_cfg()), 4, None) == lb.LOCOCO_EINVAL
+
+
+def test_the_library_reads_no_environment_variable():
+    """Behaviour switches are explicit calls (lococo_debug_option), not ambient state."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--undefined-only", lb.LIB_PATH], capture_output=True, text=True).stdout
+    assert "getenv" not in out

@@ -6,6 +6,7 @@ import pytest
 import torch
 
 from oracle import lococo_oracle as orc
+from paper_2406_05317_amd import binding as lb
 from paper_2406_05317_amd import inputs
 from parity_util import compare_scan, gpu_forward, oracle_forward
 
@@ -130,14 +131,14 @@ def test_mfma_is_refused_for_shapes_it_does_not_take():
         assert lb.lococo_workspace_bytes(lb.config_for(w, impl=0), w.L, w.B) > 0
 
 
-def test_one_launch_scan_equals_one_launch_per_step(monkeypatch):
+def test_one_launch_scan_equals_one_launch_per_step(options):
     """All compress steps of a scan in one launch (slot tiles of a chain handing the cache to each
     other inside the kernel) against one launch per step: bit-identical."""
     w = _w(M=256, B=128, L=1536, n_q_heads=8, n_kv_heads=8)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
     a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
-    monkeypatch.setenv("LOCOCO_SCAN_LAUNCHES", "steps")
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 1)
     b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
     for x, y in zip(a[:3], b[:3]):
         assert torch.equal(x, y)
@@ -151,17 +152,17 @@ def test_one_launch_scan_equals_one_launch_per_step(monkeypatch):
     dict(M=512, B=512, L=4096, n_q_heads=16, n_kv_heads=16),          # 128 workgroups, 8 tiles per chain
     dict(M=128, B=96, L=1000, n_q_heads=4, n_kv_heads=2, batch=2),    # ragged blocks, grouped heads
 ])
-def test_chain_meeting_through_the_shared_l2_equals_the_device_scope_one(case, monkeypatch):
+def test_chain_meeting_through_the_shared_l2_equals_the_device_scope_one(case, options):
     """Between the steps of the one-launch scan the slot tiles of a chain meet without writing the
-    L2 back when they find themselves on one XCD; with LOCOCO_CHAIN_SYNC=device they always use
+    L2 back when they find themselves on one XCD; with the debug option LOCOCO_OPT_CHAIN_SYNC_DEVICE they always use
     device-scope release / acquire.  Same kernel arithmetic either way: bit-identical results,
     several runs each (a stale read would show as a difference)."""
     w = _w(**case)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
-    monkeypatch.setenv("LOCOCO_CHAIN_SYNC", "device")
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 1)
     ref = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
-    monkeypatch.delenv("LOCOCO_CHAIN_SYNC")
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 0)
     for _ in range(4):
         got = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True)
         for x, y in zip(got[:3], ref[:3]):
@@ -183,7 +184,7 @@ def test_chain_meeting_through_the_shared_l2_equals_the_device_scope_one(case, m
     # protected slots, different ones in every chain, with several chains per workgroup, 64-slot tiles
     dict(batch=24, n_q_heads=8, n_kv_heads=8, M=128, B=64, L=384, protect_share=0.1),
 ])
-def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
+def test_one_launch_scan_with_several_chains_per_workgroup(case, options):
     """More (chain, slot tile) pairs than compute units: the one-launch scan gives every workgroup
     several chains of one slot tile.  Bit-identical to one launch per step, with either form of the
     chain meeting, and equal to the oracle."""
@@ -194,10 +195,10 @@ def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
     cw, cb = inputs.conv_filters(w)
     protect = (np.random.default_rng(5).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
     a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
-    monkeypatch.setenv("LOCOCO_CHAIN_SYNC", "device")
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 1)
     c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
-    monkeypatch.delenv("LOCOCO_CHAIN_SYNC")
-    monkeypatch.setenv("LOCOCO_SCAN_LAUNCHES", "steps")
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 0)
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 1)
     b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
     for other in (b, c):
         for x, y in zip(a[:3], other[:3]):
@@ -221,7 +222,7 @@ def test_one_launch_scan_with_several_chains_per_workgroup(case, monkeypatch):
     dict(conv_in=1, conv_width=21, norm=1, batch=4, n_q_heads=32, n_kv_heads=32, L=384),          # enough chains for 128-slot tiles, [K | V]
     dict(conv_width=7, batch=4, n_q_heads=32, n_kv_heads=32, L=384),                             # the same, keys only
 ])
-def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case, monkeypatch):
+def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case, options):
     """impl = AUTO with bf16 / head_dim 128 and a compressor the fused kernel is not built for
     ([K | V] input, other widths, odd M): MFMA attention, MFMA logits and MFMA fusion around the
     shape-agnostic normalisation.  Equal to the oracle; the timing rows say which kernels ran.
@@ -247,15 +248,15 @@ def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case, monke
         assert torch.equal(x, y)
     by_shape = {}
     for shape in ("64", "128", "256"):
-        monkeypatch.setenv("LOCOCO_LOGITS_TILES", shape)
+        options(lb.LOCOCO_OPT_LOGITS_TILES, int(shape))
         by_shape[shape] = gpu_forward(w, q, k, v, cw, cb, impl=0, history=True, protect=protect)
         compare_scan(w, by_shape[shape], want, what="logits tiles of %s slots" % shape)
-    monkeypatch.delenv("LOCOCO_LOGITS_TILES")
+    options(lb.LOCOCO_OPT_LOGITS_TILES, 0)
     for x, y in zip(by_shape["64"][:3], by_shape["128"][:3]):
         assert torch.equal(x, y)
 
 
-def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
+def test_a_chain_wait_that_gives_up_is_reported(options):
     """Forced from the host: with no polls allowed, the first slot tile to finish a step cannot wait
     for its chain, leaves the kernel, and the status word says so.  Every workgroup still exits."""
     from paper_2406_05317_amd import binding as lb
@@ -266,10 +267,10 @@ def test_a_chain_wait_that_gives_up_is_reported(monkeypatch):
     ws = lb.workspace(cfg, w.L, w.B, True)
     cache = lb.Cache(cfg)
     o = torch.empty_like(q, device="cuda")
-    monkeypatch.setenv("LOCOCO_SPIN_LIMIT", "-1")
+    options(lb.LOCOCO_OPT_SPIN_LIMIT, -1)
     lb.lococo_sequence_forward(cfg, q.cuda(), k.cuda(), v.cuda(), o, cw.cuda(), cb.cuda(), cache, w.B, ws)
     assert lb.lococo_scan_status(cfg, ws) == 1
-    monkeypatch.delenv("LOCOCO_SPIN_LIMIT")
+    options(lb.LOCOCO_OPT_SPIN_LIMIT, 0)
     cache = lb.Cache(cfg)
     lb.lococo_sequence_forward(cfg, q.cuda(), k.cuda(), v.cuda(), o, cw.cuda(), cb.cuda(), cache, w.B, ws)
     assert lb.lococo_scan_status(cfg, ws) == 0           # the word is cleared by the next call
