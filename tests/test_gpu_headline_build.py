@@ -113,12 +113,13 @@ def test_a_second_scan_on_another_stream_does_not_start_a_second_persistent_laun
     for _ in range(2):
         runs.append(dict(o=torch.full_like(qd, float("nan")), cache=lb.Cache(cfg, dev),
                          ws=lb.workspace(cfg, w.L, w.B, True, dev), stream=torch.cuda.Stream()))
+    torch.cuda._sleep(1000)                               # (its first use loads the kernel and waits for it)
     torch.cuda.synchronize()
     lb.lococo_timing_begin()                              # (reading the timing waits for the device: once, at the end)
     for i, r in enumerate(runs):
         with torch.cuda.stream(r["stream"]):
             if i == 0:
-                torch.cuda._sleep(20_000_000)             # the first scan sits behind some milliseconds of other work
+                torch.cuda._sleep(200_000_000)            # the first scan sits behind ~80 ms of other work
             lb.lococo_sequence_forward(cfg, qd, kd, vd, r["o"], cwd, cbd, r["cache"], w.B, r["ws"])
     launches = lb.lococo_timing_end()["compress_mfma"][0]
     torch.cuda.synchronize()
