@@ -194,6 +194,27 @@ LOCOCO_API lococo_status lococo_segment_step(const lococo_config* cfg, const loc
                                   const void* conv_w, const void* conv_b, lococo_cache* cache,
                                   void* workspace, size_t ws_bytes, void* stream);
 
+/* lococo_segment_step for callers that cannot allocate device memory or keep a workspace of their
+ * own: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments, same kernels and the same results as lococo_segment_step, but the scratch the step
+ * needs (the repacked filter bank, the row statistics of the attention, on the other paths the
+ * logits) lives in an array of LOCOCO_NOALLOC_SCRATCH_BYTES that is part of the library's device
+ * code: each GPU the library runs on holds one copy from the moment the library is loaded until the
+ * process ends, and the call itself allocates and frees nothing (no hipMalloc, no hipFree, no stream
+ * or event creation; the optional kernel timing of lococo_timing_begin, which creates events, must
+ * be off).
+ *   - A step whose lococo_workspace_bytes(cfg, B, B, 0) exceeds the array is refused with
+ *     LOCOCO_EWORKSPACE (enough for the benchmark shapes on the fused path: 32 heads, M = 512, width 15
+ *     needs 2.1 MB; not for the logits of large shapes on the other paths).
+ *   - LOCOCO_FLAG_FILTERS_PREPARED is refused (LOCOCO_EINVAL): the array is shared by every caller on
+ *     the device and keeps whatever the last call left in it, so each call repacks the filters itself.
+ *   - Calls that overlap on one GPU (two streams, two threads) race on the array: the caller must
+ *     order them, as for any shared workspace.  Nothing in it has to start at zero. */
+#define LOCOCO_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+LOCOCO_API lococo_status lococo_segment_step_noalloc(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                                     const void* conv_w, const void* conv_b, lococo_cache* cache,
+                                                     void* stream);
+
 /* The whole Alg. 2 loop over a sequence of L tokens in blocks of B, starting
  * from `cache` (len = 0 for a fresh sequence) and leaving the final cache in
  * it.  seq.q/o: [batch, n_q_heads, L, d]; seq.k/v: [batch, n_kv_heads, L, d].

@@ -26,7 +26,8 @@ EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
            "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status",
            "lococo_prepare_filters", "lococo_backward_workspace_bytes", "lococo_segment_step_backward",
-           "lococo_measure_peaks", "lococo_debug_option", "lococo_describe_path"]
+           "lococo_measure_peaks", "lococo_debug_option", "lococo_describe_path",
+           "lococo_segment_step_noalloc"]
 
 
 class lococo_config(C.Structure):
@@ -94,6 +95,7 @@ def lib():
         L.lococo_attn_only.argtypes = [cfgp, qp, C.c_int32, cap, C.c_void_p]
         L.lococo_segment_step.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, C.c_void_p, cap,
                                           C.c_void_p, C.c_size_t, C.c_void_p]
+        L.lococo_segment_step_noalloc.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, C.c_void_p, cap, C.c_void_p]
         L.lococo_sequence_forward.argtypes = [cfgp, qp, C.c_int64, C.c_int32, C.c_void_p,
                                               C.c_void_p, cap, C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_mix_from_logits.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, cap, C.c_void_p]
@@ -253,6 +255,14 @@ def lococo_segment_step(cfg, q, k, v, o, conv_w, conv_b, cache: Cache, workspace
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lococo_segment_step(C.byref(cfg), C.byref(x), B, _ptr(conv_w), _ptr(conv_b),
                                      C.byref(cache.c), _ptr(workspace), ws_bytes, _stream()))
+
+
+def lococo_segment_step_noalloc(cfg, q, k, v, o, conv_w, conv_b, cache: Cache):
+    """lococo_segment_step on the library's own scratch array (allocates nothing)."""
+    B = q.shape[2]
+    x = _qkvo(q, k, v, o)
+    _check(lib().lococo_segment_step_noalloc(C.byref(cfg), C.byref(x), B, _ptr(conv_w), _ptr(conv_b),
+                                             C.byref(cache.c), _stream()))
 
 
 def lococo_sequence_forward(cfg, q, k, v, o, conv_w, conv_b, cache: Cache, B: int, workspace=None):

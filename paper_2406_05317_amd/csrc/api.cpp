@@ -14,6 +14,11 @@
 
 using namespace lococo;
 
+// The library's own scratch array (see lococo_segment_step_noalloc): device memory that exists from
+// the moment the code object is loaded.  On the host this name is only a handle for
+// hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[LOCOCO_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 DebugOptions g_debug = {0, 0, 0, 0, 0};
 }
@@ -528,6 +533,28 @@ lococo_status segment_step_impl(const lococo_config* cfg, const lococo_qkvo* blk
   return LOCOCO_OK;
 }
 
+// ---- device address of the library's own scratch array on the current device, looked up once per
+// device (every device the library runs on holds its own copy at its own address) and used from then
+// on wherever host code needs the array's memory
+constexpr size_t kScratchBytes = LOCOCO_NOALLOC_SCRATCH_BYTES;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mu;
+
+lococo_status scratch_on_this_device(void** out) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(LOCOCO_EUNSUPPORTED, "device index %d above %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "address of the library's scratch array");
+    if (!p || ((uintptr_t)p & 255)) return fail(LOCOCO_EHIP, "the library's scratch array has no usable device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LOCOCO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -723,6 +750,26 @@ lococo_status lococo_segment_step(const lococo_config* cfg, const lococo_qkvo* b
                                   const void* conv_w, const void* conv_b, lococo_cache* cache,
                                   void* workspace, size_t ws_bytes, void* stream) {
   return segment_step_impl(cfg, blk, B, conv_w, conv_b, cache, workspace, ws_bytes, stream);
+}
+
+lococo_status lococo_segment_step_noalloc(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
+                                          const void* conv_w, const void* conv_b, lococo_cache* cache,
+                                          void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (cfg->flags & LOCOCO_FLAG_FILTERS_PREPARED)
+    return fail(LOCOCO_EINVAL, "LOCOCO_FLAG_FILTERS_PREPARED cannot be used with the library's own scratch "
+                "array: every caller on the device shares it, so nothing prepared can be assumed to be there");
+  if (B <= 0) return fail(LOCOCO_EINVAL, "block length B must be positive");
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  const size_t need = step_ws_bytes(cfg, path, B);
+  if (need > kScratchBytes)
+    return fail(LOCOCO_EWORKSPACE, "this step needs %zu bytes of scratch, the library's own array holds %zu: "
+                "use lococo_segment_step with a workspace of the caller's", need, kScratchBytes);
+  void* ws = nullptr;
+  if ((st = scratch_on_this_device(&ws))) return st;
+  return segment_step_impl(cfg, blk, B, conv_w, conv_b, cache, ws, kScratchBytes, stream);
 }
 
 lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
