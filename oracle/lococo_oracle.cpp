@@ -29,8 +29,14 @@
 //   * the convolution is a cross-correlation with zero "same" padding of
 //     (k-1)/2 on both sides, stride 1, odd width (output length = input length);
 //   * Eq. 6 is read as a softmax over the positions (norm = 0).  The literal
-//     form relu(W) / (sum relu(W) + eps) is norm = 1 ("prepended ReLU" read as
-//     acting on the convolution output so that weights are convex);
+//     form relu(W) / (sum relu(W) + eps) is norm = 1 (the rectifier of the
+//     convolution head read as acting on the convolution OUTPUT, so that the
+//     weights are convex).  norm = 2 is the other reading of "a ReLU is
+//     prepended": the rectifier acts on the convolution's INPUT (the stacked
+//     keys / values that Eq. 5 convolves; the entries that Eq. 4 fuses stay as
+//     they are) and Eq. 6 is taken exactly as printed, W / sum(W); a row sum
+//     of magnitude below eps is replaced by +-eps (such a sum is signed and can
+//     vanish: the reason the other two forms exist).  Forward only;
 //   * conv_in = 0 feeds the keys only (C = d); conv_in = 1 feeds keys stacked
 //     on values along channels (C = 2d, Eq. 5 as printed), K channels first;
 //   * when the cache is partly full and cache + block exceeds M, the entries
@@ -71,7 +77,7 @@ struct Cfg {
   int32_t M;            // cache slots
   int32_t conv_width;   // k, odd
   int32_t conv_in;      // 0: keys only; 1: [K;V] stacked on channels
-  int32_t norm;         // 0: softmax over positions; 1: relu + sum
+  int32_t norm;         // 0: softmax over positions; 1: relu(W) / (sum + eps); 2: relu on the conv input, W / sum(W)
   int32_t state_round;  // 0: keep double; 1: fp32; 2: bf16 (on every cache write and on O)
   int32_t reserved;
   double attn_scale;    // <= 0 means 1/sqrt(d)
@@ -142,9 +148,17 @@ void attention_block(const double* q, const double* kb, const double* vb,
 
 // Eq. 5: W[i, j] = bias[i] + sum_c sum_tau Wc[i, c, tau] * X[j + tau - (k-1)/2, c],
 // X zero outside [0, T).  X is [T, C], Wc is [M, C, k], W is [M, T].
+// relu_input: the input entries pass through max(., 0) first (the rectifier in front of the
+// convolution layer, norm = 2).
 void conv_logits(const double* X, int T, int C, const double* Wc, const double* bias,
-                 int M, int k, double* W, int nthreads) {
+                 int M, int k, double* W, int nthreads, bool relu_input = false) {
   const int pad = (k - 1) / 2;
+  std::vector<double> Xr;
+  if (relu_input) {
+    Xr.assign(X, X + (size_t)T * C);
+    for (double& x : Xr) x = x > 0.0 ? x : 0.0;
+    X = Xr.data();
+  }
   // layout-only copy: Wt[i][tau][c] = Wc[i][c][tau]
   std::vector<double> Wt((size_t)M * k * C);
   for (int i = 0; i < M; ++i)
@@ -179,10 +193,17 @@ void normalise_rows(const double* W, int M, int T, int norm, double eps, double*
       double z = 0.0;
       for (int j = 0; j < T; ++j) { out[j] = std::exp(r[j] - mx); z += out[j]; }
       for (int j = 0; j < T; ++j) out[j] /= z;
-    } else {
+    } else if (norm == 1) {
       double z = 0.0;
       for (int j = 0; j < T; ++j) { out[j] = r[j] > 0.0 ? r[j] : 0.0; z += out[j]; }
       for (int j = 0; j < T; ++j) out[j] /= (z + eps);
+    } else {
+      // Eq. 6 as printed: W[i, j] / sum_k W[i, k].  Positions excluded from the mixing (-inf:
+      // protected slots) carry no weight and do not enter the sum.
+      double z = 0.0;
+      for (int j = 0; j < T; ++j) { out[j] = std::isfinite(r[j]) ? r[j] : 0.0; z += out[j]; }
+      if (std::fabs(z) < eps) z = z < 0.0 ? -eps : eps;
+      for (int j = 0; j < T; ++j) out[j] /= z;
     }
   }
 }
@@ -240,7 +261,7 @@ void segment_step_chain(const Cfg& cf, const double* q, int64_t q_head_stride,
   if (logits_override)
     std::memcpy(W.data(), logits_override, sizeof(double) * (size_t)M * T);
   else
-    conv_logits(X.data(), T, C, conv_w, conv_b, M, cf.conv_width, W.data(), nthreads);
+    conv_logits(X.data(), T, C, conv_w, conv_b, M, cf.conv_width, W.data(), nthreads, cf.norm == 2);
   // Protected slots (combination with an eviction policy that keeps some tokens as they are:
   // attention sinks, heavy hitters): a live protected slot is no input of the mixing -- its
   // position carries no weight in any row -- and is not rewritten (below).
@@ -434,25 +455,34 @@ int64_t lococo_oracle_plan(int64_t L, int32_t B, int32_t M, int32_t len0, int32_
 
 double lococo_oracle_round(double x, int32_t mode) { return round_store(x, mode); }
 
-void lococo_oracle_attention_block(const double* q, const double* kb, const double* vb,
-                                   const double* ck, const double* cv, int32_t m, int32_t Bn,
-                                   int32_t d, double scale, double* o) {
+// The single operations, for the pins.  Each returns 0, or 1 on null pointers / sizes that make no sense.
+int32_t lococo_oracle_attention_block(const double* q, const double* kb, const double* vb,
+                                      const double* ck, const double* cv, int32_t m, int32_t Bn,
+                                      int32_t d, double scale, double* o) {
+  if (!q || !kb || !vb || !o || m < 0 || Bn <= 0 || d <= 0 || (m > 0 && (!ck || !cv))) return 1;
   attention_block(q, kb, vb, ck, cv, m, Bn, d, scale, o);
+  return 0;
 }
 
-void lococo_oracle_conv_logits(const double* X, int32_t T, int32_t C, const double* Wc,
-                               const double* bias, int32_t M, int32_t k, double* W) {
-  conv_logits(X, T, C, Wc, bias, M, k, W, 1);
+int32_t lococo_oracle_conv_logits(const double* X, int32_t T, int32_t C, const double* Wc,
+                                  const double* bias, int32_t M, int32_t k, int32_t relu_input, double* W) {
+  if (!X || !Wc || !W || T <= 0 || C <= 0 || M <= 0 || k < 1 || k % 2 == 0) return 1;
+  conv_logits(X, T, C, Wc, bias, M, k, W, 1, relu_input != 0);
+  return 0;
 }
 
-void lococo_oracle_normalise(const double* W, int32_t M, int32_t T, int32_t norm, double eps,
-                             double* w) {
+int32_t lococo_oracle_normalise(const double* W, int32_t M, int32_t T, int32_t norm, double eps,
+                                double* w) {
+  if (!W || !w || M <= 0 || T <= 0 || norm < 0 || norm > 2 || !(eps >= 0.0)) return 1;
   normalise_rows(W, M, T, norm, eps, w);
+  return 0;
 }
 
-void lococo_oracle_mix(const double* w, const double* Y, int32_t M, int32_t T, int32_t d,
-                       double* out) {
+int32_t lococo_oracle_mix(const double* w, const double* Y, int32_t M, int32_t T, int32_t d,
+                          double* out) {
+  if (!w || !Y || !out || M <= 0 || T <= 0 || d <= 0) return 1;
   mix(w, Y, M, T, d, out);
+  return 0;
 }
 
 // Whole scan (Alg. 2) over all chains.  Contiguous layouts:
@@ -476,9 +506,23 @@ int32_t lococo_oracle_sequence_forward_protected(
     double* attn_colsum, int32_t nthreads) {
   const Cfg cf = *cfg;
   const int d = cf.head_dim, M = cf.M, g = cf.group;
-  if (d <= 0 || M <= 0 || g <= 0 || B <= 0 || L < 0 || cf.conv_width < 1 ||
-      cf.conv_width % 2 == 0 || *len < 0 || *len > M)
+  if (!cfg || !len) return 1;
+  if (d <= 0 || M <= 0 || g <= 0 || B <= 0 || L < 0 || batch <= 0 || Hkv <= 0 || cf.conv_width < 1 ||
+      cf.conv_width % 2 == 0 || *len < 0 || *len > M || cf.norm < 0 || cf.norm > 2 ||
+      cf.conv_in < 0 || cf.conv_in > 1 || cf.state_round < 0 || cf.state_round > 2 ||
+      !(cf.norm_eps >= 0.0) || nthreads < 1 || w_head_stride < 0 || b_head_stride < 0 || protect_chain_stride < 0)
     return 1;
+  if (L > 0 && (!q || !k || !v || !o || !cache_k || !cache_v)) return 1;
+  {
+    // a step that compresses needs filters (or given logits): decided by the same test the scan applies
+    int m = *len;
+    for (int64_t s = 0; s < L; s += B) {
+      const int Bn = (int)std::min<int64_t>(B, L - s);
+      if (m + Bn <= M) { m += Bn; continue; }
+      if (!conv_w && !logits_override) return 1;
+      m = M;
+    }
+  }
   const int64_t chains = (int64_t)batch * Hkv;
   const int len0 = *len;
   const int inner = chains >= nthreads ? 1 : nthreads;  // few chains: thread the conv rows instead
@@ -549,10 +593,15 @@ int32_t lococo_oracle_step_backward(const lococo_oracle_cfg* cfg, int32_t batch,
                                     const double* d_new_v, double* dq, double* dkb, double* dvb,
                                     double* d_cache_k, double* d_cache_v, double* d_conv_w,
                                     double* d_conv_b) {
+  if (!cfg) return 1;
   const Cfg cf = *cfg;
   const int d = cf.head_dim, M = cf.M, g = cf.group;
-  if (d <= 0 || M <= 0 || g <= 0 || Bn <= 0 || len < 0 || len > M) return 1;
-  if (len + Bn > M && !conv_w) return 1;
+  if (d <= 0 || M <= 0 || g <= 0 || Bn <= 0 || len < 0 || len > M || batch <= 0 || Hkv <= 0) return 1;
+  if (cf.norm != 0 && cf.norm != 1) return 1;            // the input-side rectifier (norm = 2) is forward only
+  if (!q || !kb || !vb || !cache_k || !cache_v || !dO || !d_new_k || !d_new_v || !dq || !dkb || !dvb ||
+      !d_cache_k || !d_cache_v)
+    return 1;
+  if (len + Bn > M && (!conv_w || !d_conv_w || cf.conv_width < 1 || cf.conv_width % 2 == 0)) return 1;
   for (int64_t ch = 0; ch < (int64_t)batch * Hkv; ++ch) {     // serial: chains add into shared filter gradients
     const int64_t h = ch % Hkv;
     segment_step_backward_chain(

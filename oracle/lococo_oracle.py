@@ -14,16 +14,28 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lococo_oracle.cpp")
-_LIB = os.path.join(_HERE, "liblococo_oracle.so")
+# LOCOCO_ORACLE_LIB: another build of the same source to load instead (the sanitizer job of the tests)
+_LIB = os.environ.get("LOCOCO_ORACLE_LIB") or os.path.join(_HERE, "liblococo_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with g++ (generic x86-64 code: built here, run elsewhere)."""
+    if os.environ.get("LOCOCO_ORACLE_LIB"):
+        return _LIB                          # somebody else's build: load it as it is
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["g++", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
                                "-Wall", "-Wextra", "-o", _LIB, _SRC])
     return _LIB
+
+
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only), any
+    finding fatal; loaded through LOCOCO_ORACLE_LIB with libasan preloaded."""
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-pthread",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+                           "-o", out_path, _SRC])
+    return out_path
 
 
 class Cfg(C.Structure):
@@ -47,14 +59,14 @@ def lib():
                                          C.POINTER(C.c_int64), C.c_int64]
         L.lococo_oracle_round.restype = C.c_double
         L.lococo_oracle_round.argtypes = [C.c_double, C.c_int32]
-        L.lococo_oracle_attention_block.restype = None
+        L.lococo_oracle_attention_block.restype = C.c_int32
         L.lococo_oracle_attention_block.argtypes = [_DP] * 5 + [C.c_int32] * 3 + [C.c_double, _DP]
-        L.lococo_oracle_conv_logits.restype = None
+        L.lococo_oracle_conv_logits.restype = C.c_int32
         L.lococo_oracle_conv_logits.argtypes = [_DP, C.c_int32, C.c_int32, _DP, _DP, C.c_int32,
-                                                C.c_int32, _DP]
-        L.lococo_oracle_normalise.restype = None
+                                                C.c_int32, C.c_int32, _DP]
+        L.lococo_oracle_normalise.restype = C.c_int32
         L.lococo_oracle_normalise.argtypes = [_DP, C.c_int32, C.c_int32, C.c_int32, C.c_double, _DP]
-        L.lococo_oracle_mix.restype = None
+        L.lococo_oracle_mix.restype = C.c_int32
         L.lococo_oracle_mix.argtypes = [_DP, _DP, C.c_int32, C.c_int32, C.c_int32, _DP]
         L.lococo_oracle_sequence_forward.restype = C.c_int32
         L.lococo_oracle_sequence_forward.argtypes = [
@@ -85,6 +97,11 @@ def _p(a):
     return None if a is None else a.ctypes.data_as(_DP)
 
 
+def _ok(rc):
+    if rc != 0:
+        raise ValueError("oracle: bad arguments")
+
+
 def plan(L: int, B: int, M: int, len0: int = 0, cur0: int = 0) -> np.ndarray:
     """[n_segments, 6] int64: start, len, branch, len_before, len_after, buf_after."""
     n = lib().lococo_oracle_plan(L, B, M, len0, cur0, None, 0)
@@ -106,20 +123,21 @@ def attention_block(q, kb, vb, ck, cv, scale=None) -> np.ndarray:
     m = ck.shape[0]
     assert kb.shape == vb.shape == (Bn, d) and cv.shape == (m, d)
     o = np.empty((Bn, d))
-    lib().lococo_oracle_attention_block(_p(q), _p(kb), _p(vb), _p(ck), _p(cv), m, Bn, d,
-                                        float(scale if scale is not None else d ** -0.5), _p(o))
+    _ok(lib().lococo_oracle_attention_block(_p(q), _p(kb), _p(vb), _p(ck), _p(cv), m, Bn, d,
+                                            float(scale if scale is not None else d ** -0.5), _p(o)))
     return o
 
 
-def conv_logits(X, Wc, bias=None) -> np.ndarray:
-    """X [T, C], Wc [M, C, k], bias [M] or None -> W [M, T]."""
+def conv_logits(X, Wc, bias=None, relu_input: bool = False) -> np.ndarray:
+    """X [T, C], Wc [M, C, k], bias [M] or None -> W [M, T].  relu_input: the entries of X pass
+    through max(., 0) first (the rectifier in front of the convolution, norm = 2)."""
     X, Wc = _f64(X), _f64(Wc)
     T, Cc = X.shape
     M, C2, k = Wc.shape
     assert C2 == Cc and k % 2 == 1
     b = None if bias is None else _f64(bias)
     W = np.empty((M, T))
-    lib().lococo_oracle_conv_logits(_p(X), T, Cc, _p(Wc), _p(b), M, k, _p(W))
+    _ok(lib().lococo_oracle_conv_logits(_p(X), T, Cc, _p(Wc), _p(b), M, k, int(relu_input), _p(W)))
     return W
 
 
@@ -127,7 +145,7 @@ def normalise(W, norm: int = 0, eps: float = 1e-6) -> np.ndarray:
     W = _f64(W)
     M, T = W.shape
     w = np.empty((M, T))
-    lib().lococo_oracle_normalise(_p(W), M, T, norm, eps, _p(w))
+    _ok(lib().lococo_oracle_normalise(_p(W), M, T, norm, eps, _p(w)))
     return w
 
 
@@ -137,7 +155,7 @@ def mix(w, Y) -> np.ndarray:
     M, T = w.shape
     assert Y.shape[0] == T
     out = np.empty((M, Y.shape[1]))
-    lib().lococo_oracle_mix(_p(w), _p(Y), M, T, Y.shape[1], _p(out))
+    _ok(lib().lococo_oracle_mix(_p(w), _p(Y), M, T, Y.shape[1], _p(out)))
     return out
 
 

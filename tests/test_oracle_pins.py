@@ -603,3 +603,105 @@ def test_attention_column_sums_match_a_numpy_softmax():
     before = col.copy()
     orc.sequence_forward(q, kk, v, cw, B=B, M=M, protect=prot, attn_colsum=col)
     np.testing.assert_allclose(col, 2 * before, rtol=1e-12)
+
+
+# ----------------------------------------------------------------- the other reading of "a ReLU is prepended"
+def test_input_side_rectifier_with_eq6_as_printed():
+    """norm = 2: the rectifier acts on the convolution's input and Eq. 6 is the plain division by the
+    row sum.  Pinned by the library conv1d on a rectified input, a hand-computed case, the agreement
+    of the two placements where they must agree, and the guard of a vanishing row sum."""
+    rng = np.random.default_rng(31)
+    T, C, M, k = 23, 6, 5, 7
+    X, Wc, bias = rand(rng, T, C), rand(rng, M, C, k), rand(rng, M)
+    got = orc.conv_logits(X, Wc, bias, relu_input=True)
+    want = torch.nn.functional.conv1d(torch.relu(torch.from_numpy(X.T.copy()))[None], torch.from_numpy(Wc),
+                                      torch.from_numpy(bias), padding=(k - 1) // 2)[0].numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    assert np.abs(got - orc.conv_logits(X, Wc, bias)).max() > 0.1          # the rectifier matters
+    # Eq. 6 as printed, signed entries and signed sums included
+    W = rand(rng, 4, 9, scale=2.0)
+    w = orc.normalise(W, norm=2)
+    np.testing.assert_allclose(w, W / W.sum(1, keepdims=True), rtol=1e-13)
+    np.testing.assert_allclose(w.sum(1), 1.0, rtol=0, atol=1e-12)
+    # by hand: taps (1, 10, 100) on x = (1, -2, 3, -4) rectified to (1, 0, 3, 0):
+    # W = (10 + 0, 1 + 300, 0 + 30, 3) = (10, 301, 30, 3), sum 344
+    Wh = orc.conv_logits(np.array([[1.0], [-2.0], [3.0], [-4.0]]), np.array([[[1.0, 10.0, 100.0]]]), relu_input=True)
+    assert np.array_equal(Wh, np.array([[10.0, 301.0, 30.0, 3.0]]))
+    np.testing.assert_allclose(orc.normalise(Wh, norm=2), Wh / 344.0, rtol=1e-15)
+    # non-negative filters and bias: the logits of a rectified input are non-negative, so rectifying
+    # them again changes nothing and the two placements give the same weights (up to eps in the sum)
+    Wp, bp = np.abs(Wc), np.abs(bias)
+    a = orc.normalise(orc.conv_logits(X, Wp, bp, relu_input=True), norm=2)
+    b = orc.normalise(orc.conv_logits(np.maximum(X, 0.0), Wp, bp), norm=1, eps=1e-12)
+    np.testing.assert_allclose(a, b, rtol=1e-10)
+    # a vanishing (signed) row sum is replaced by +-eps
+    Wz = np.array([[1.0, -1.0, 0.0], [2.0, -2.0 - 1e-9, 0.0]])
+    wz = orc.normalise(Wz, norm=2, eps=1e-6)
+    np.testing.assert_allclose(wz[0], Wz[0] / 1e-6, rtol=1e-12)
+    np.testing.assert_allclose(wz[1], Wz[1] / -1e-6, rtol=1e-12)
+
+
+def test_one_compress_step_with_the_input_side_rectifier_composed_from_library_routines():
+    """Full step with norm = 2: only the convolution's input is rectified; the entries that Eq. 4a / 4b
+    fuse are the stored keys and values as they are.  Protected positions get no weight."""
+    rng = np.random.default_rng(32)
+    for conv_in in (0, 1):
+        B, M, d, k = 6, 10, 4, 5
+        q, kk, v = rand(rng, 1, 1, B, d), rand(rng, 1, 1, B, d), rand(rng, 1, 1, B, d)
+        ck0, cv0 = rand(rng, 1, 1, M, d), rand(rng, 1, 1, M, d)
+        C = d * (2 if conv_in else 1)
+        cw, cb = np.abs(rand(rng, M, C, k)) + 0.1, np.abs(rand(rng, M))      # positive: row sums far from zero
+        YK = np.concatenate([ck0[0, 0], kk[0, 0]])
+        YV = np.concatenate([cv0[0, 0], v[0, 0]])
+        X = np.concatenate([YK, YV], axis=1) if conv_in else YK
+        W = torch.nn.functional.conv1d(torch.relu(torch.from_numpy(X.T.copy()))[None], torch.from_numpy(cw),
+                                       torch.from_numpy(cb), padding=(k - 1) // 2)[0].numpy()
+        for protect in (None, np.arange(M) % 4 == 1):
+            _, ck, cv, ln = orc.sequence_forward(q, kk, v, cw, cb, B=B, M=M, conv_in=conv_in, norm=2,
+                                                 cache_k=ck0, cache_v=cv0, cache_len=M, protect=protect)
+            Wm = W.copy()
+            if protect is not None:
+                Wm[:, :M][:, protect] = 0.0
+            w = Wm / Wm.sum(1, keepdims=True)
+            nk, nv = w @ YK, w @ YV
+            if protect is not None:
+                nk[protect], nv[protect] = ck0[0, 0][protect], cv0[0, 0][protect]
+            assert ln == M
+            np.testing.assert_allclose(ck[0, 0], nk, rtol=1e-11, atol=1e-13)
+            np.testing.assert_allclose(cv[0, 0], nv, rtol=1e-11, atol=1e-13)
+    # forward only: the backward entry point refuses it
+    with pytest.raises(ValueError):
+        orc.step_backward(q, kk, v, ck0, cv0, M, cw, cb, np.zeros_like(q), np.zeros_like(ck0), np.zeros_like(cv0),
+                          M=M, conv_in=conv_in, norm=2)
+
+
+def test_bad_arguments_come_back_as_an_error_not_as_a_crash():
+    rng = np.random.default_rng(33)
+    q, kk, v = rand(rng, 1, 1, 12, 4), rand(rng, 1, 1, 12, 4), rand(rng, 1, 1, 12, 4)
+    L = orc.lib()
+    cfg = orc.Cfg(1, 4, 8, 3, 0, 0, 0, 0, 0.0, 1e-6)
+    ln = orc.C.c_int32(0)
+    dp = lambda a: a.ctypes.data_as(orc._DP)
+    o, ck, cv = np.zeros_like(q), np.zeros((1, 1, 8, 4)), np.zeros((1, 1, 8, 4))
+    call = lambda **kw: L.lococo_oracle_sequence_forward_protected(
+        orc.C.byref(kw.get("cfg", cfg)), 1, 1, 12, kw.get("B", 4), dp(q), dp(kk), dp(v), kw.get("o", dp(o)), dp(ck),
+        dp(cv), orc.C.byref(ln), kw.get("cw", None), 0, None, 0, None, None, 0, None, kw.get("nthreads", 1))
+    assert call() == 1                                       # the third block compresses: filters missing
+    cw = rand(rng, 8, 4, 3)
+    assert call(cw=dp(cw)) == 0
+    ln.value = 0
+    assert call(cw=dp(cw), o=None) == 1
+    assert call(cw=dp(cw), B=0) == 1
+    assert call(cw=dp(cw), nthreads=0) == 1
+    for bad in (dict(norm=3), dict(conv_width=4), dict(state_round=5), dict(conv_in=2), dict(norm_eps=-1.0)):
+        c2 = orc.Cfg(1, 4, 8, 3, 0, 0, 0, 0, 0.0, 1e-6)
+        for k_, val in bad.items():
+            setattr(c2, k_, val)
+        assert call(cw=dp(cw), cfg=c2) == 1, bad
+    ln.value = 9
+    assert call(cw=dp(cw)) == 1                              # occupancy beyond M
+    with pytest.raises(ValueError):
+        orc.normalise(np.zeros((2, 3)), norm=7)
+    assert L.lococo_oracle_conv_logits(None, 3, 2, None, None, 2, 3, 0, None) == 1
+    assert L.lococo_oracle_mix(None, None, 1, 1, 1, None) == 1
+    assert L.lococo_oracle_attention_block(dp(q), dp(kk), dp(v), None, None, 2, 4, 4, 0.5, dp(o)) == 1
