@@ -283,6 +283,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-history", action="store_true",
                     help="step-by-step schedule instead of the batched-attention one")
+    ap.add_argument("--history-window", type=int, default=0,
+                    help="workspace for a window of this many blocks (>= 2) instead of the whole sequence: the "
+                         "batched-attention schedule window by window, memory independent of the sequence length")
     ap.add_argument("--conv-width", type=int, default=0, help="override the workload's filter width (e.g. 21)")
     ap.add_argument("--norm", type=int, default=-1, help="override the normalisation (0 softmax, 1 relu-sum)")
     ap.add_argument("--conv-in", type=int, default=0, help="1: the filters read [K | V] (2 d channels) instead of the keys")
@@ -339,7 +342,7 @@ def main():
         cache.set_protect(np.arange(w.M) < args.protect_sinks)
     if args.track_attention:
         cache.track_attention()
-    ws = lb.workspace(cfg, w.L, w.B, not args.no_history, dev)
+    ws = lb.workspace(cfg, w.L, w.B, 0 if args.no_history else (args.history_window or 1), dev)
     plan = lb.lococo_plan(w.L, w.B, w.M)
     flops = scan_flops(w, plan)
 
@@ -397,7 +400,10 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.L, "B": w.B,
                    "M": w.M, "conv_width": w.conv_width, "conv_channels": w.C,
-                   "schedule": "step-by-step" if args.no_history else "batched-attention",
+                   "schedule": "step-by-step" if args.no_history else
+                               (f"batched-attention, windows of {args.history_window} blocks" if args.history_window
+                                else "batched-attention"),
+                   "workspace_bytes": 0 if ws is None else ws.numel(),
                    "protected_slots": args.protect_sinks, "track_attention": bool(args.track_attention),
                    "impl": args.impl, "kernels": path_info},
         "segment_step_tokens_per_s": w.batch * w.B / (ms_per_step * 1e-3 / len(plan)),

@@ -44,7 +44,8 @@
  *  - Convolution: cross-correlation, zero padding (k-1)/2 on both sides,
  *    stride 1, odd width only.
  *  - Eq. 6 as a softmax over the positions (norm = 0) or, literally,
- *    relu(W) / (sum relu(W) + eps) (norm = 1).
+ *    relu(W) / (sum relu(W) + eps) (norm = 1), or W / sum(W) behind a rectifier
+ *    on the convolution's input (norm = 2).
  *  - A compress step with a partly filled cache (m < M, m + B > M) mixes the
  *    m + B entries present.
  */
@@ -90,7 +91,11 @@ typedef struct lococo_config {
   int32_t conv_width;     /* k, odd, >= 1 (Eq. 5; the paper's default is 21)                      */
   int32_t conv_in;        /* 0: filters read keys only, C = d; 1: keys stacked on values along
                              channels, C = 2d (Eq. 5 as printed), K channels first               */
-  int32_t norm;           /* 0: softmax over the positions; 1: relu(W)/(sum relu(W)+norm_eps)     */
+  int32_t norm;           /* 0: softmax over the positions; 1: relu(W)/(sum relu(W)+norm_eps);
+                             2: the other reading of the rectifier the paper puts in the head: on the
+                             convolution's INPUT (Eq. 4 still fuses the stored entries), and Eq. 6 as
+                             printed, W / sum(W), a row sum below norm_eps in magnitude replaced by
+                             +-norm_eps (shape-agnostic kernels and forward only)                    */
   int32_t impl;           /* LOCOCO_IMPL_*: AUTO picks the fused MFMA kernels when the shape allows
                              (bf16, head_dim 128, keys-only filters of width 15 or 21, M a multiple
                              of 32), separate MFMA kernels for Eq. 5 and Eq. 4 for other bf16 /
@@ -165,10 +170,14 @@ LOCOCO_API lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t le
                           lococo_seg* out, int64_t* n_inout);
 
 /* Bytes of device workspace lococo_segment_step (L = B) or
- * lococo_sequence_forward (L = sequence length) need for this shape.  Passing
- * `history` != 0 asks for the larger size with which lococo_sequence_forward
- * keeps every intermediate cache and runs all blocks' attention as one
- * batched launch after the compression scan.  May return 0. */
+ * lococo_sequence_forward (L = sequence length) need for this shape.
+ *   history = 0: the step-by-step schedule (one block's scratch);
+ *   history = 1: room for the cache state after every block, with which
+ *                lococo_sequence_forward runs the whole compression scan first and then
+ *                all blocks' attention as one batched launch;
+ *   history = G >= 2: room for a window of G blocks (G + 1 cache states): the same
+ *                schedule window by window, memory independent of L.
+ * May return 0. */
 LOCOCO_API lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
                                      int32_t history, size_t* out);
 
@@ -218,8 +227,10 @@ LOCOCO_API lococo_status lococo_segment_step_noalloc(const lococo_config* cfg, c
 /* The whole Alg. 2 loop over a sequence of L tokens in blocks of B, starting
  * from `cache` (len = 0 for a fresh sequence) and leaving the final cache in
  * it.  seq.q/o: [batch, n_q_heads, L, d]; seq.k/v: [batch, n_kv_heads, L, d].
- * If ws_bytes >= lococo_workspace_bytes(cfg, L, B, 1) the batched-attention
- * schedule is used, otherwise the step-by-step one; results are the same. */
+ * The schedule follows from ws_bytes: with lococo_workspace_bytes(cfg, L, B, 1) or more the
+ * batched-attention schedule over the whole sequence; with less, the same schedule over
+ * windows of as many blocks as the workspace holds states for (at least two); below that
+ * the step-by-step schedule.  Results are the same bit for bit. */
 LOCOCO_API lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
                                       int32_t B, const void* conv_w, const void* conv_b,
                                       lococo_cache* cache, void* workspace, size_t ws_bytes,

@@ -113,7 +113,7 @@ lococo_status check_config(const lococo_config* c) {
     return fail(LOCOCO_EUNSUPPORTED, "conv_width %d is even; only odd widths have a centred "
                 "same-length convolution", c->conv_width);
   if (c->conv_in != 0 && c->conv_in != 1) return fail(LOCOCO_EINVAL, "conv_in must be 0 or 1");
-  if (c->norm != 0 && c->norm != 1) return fail(LOCOCO_EINVAL, "norm must be 0 or 1");
+  if (c->norm < 0 || c->norm > 2) return fail(LOCOCO_EINVAL, "norm must be 0, 1 or 2");
   if (c->impl < LOCOCO_IMPL_AUTO || c->impl > LOCOCO_IMPL_MFMA)
     return fail(LOCOCO_EINVAL, "impl must be one of LOCOCO_IMPL_*");
   if (c->flags & ~LOCOCO_FLAG_FILTERS_PREPARED) return fail(LOCOCO_EINVAL, "config.flags has unknown bits set");
@@ -195,7 +195,8 @@ Path choose_path(const lococo_config* c, int32_t B, const char** why) {
   const char* ignore = "";
   if (!attn_mfma_supports(c->dtype, c->head_dim, why)) return PATH_GENERIC;
   if (compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why)) return PATH_MFMA;
-  if (conv_logits_mfma_supports(c->dtype, c->head_dim, c->conv_width) && attn_mfma_supports(c->dtype, c->head_dim, &ignore))
+  if (c->norm != 2 &&                 // the input-side rectifier exists in the shape-agnostic kernels only
+      conv_logits_mfma_supports(c->dtype, c->head_dim, c->conv_width) && attn_mfma_supports(c->dtype, c->head_dim, &ignore))
     return PATH_MFMA_UNFUSED;
   return PATH_GENERIC;
 }
@@ -388,6 +389,7 @@ AttnArgs attn_args_one_block(const StepArgs& a) {
   t.M = a.M;
   t.len0 = a.m;
   t.n_fill = 0;            // block 0 sees the base cache with len0 slots
+  t.hist_ring = 1;
   t.seg_first = 0;
   t.n_seg = 1;
   t.batch = a.batch; t.Hq = a.Hq; t.Hkv = a.Hkv; t.group = a.group;
@@ -702,10 +704,16 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
   if (L < 0 || B <= 0) return fail(LOCOCO_EINVAL, "need L >= 0 and B > 0");
   Path path;
   if ((st = resolve_path(cfg, B, &path))) return st;
-  if (history && path != PATH_GENERIC)
-    *out = history_ws_bytes(cfg, path, B, (L + B - 1) / B, L);   // every block may compress
-  else
+  const int64_t n_blocks = (L + B - 1) / B;
+  if (history < 0) return fail(LOCOCO_EINVAL, "history must be >= 0");
+  if (history == 0 || path == PATH_GENERIC || n_blocks == 0)
     *out = step_ws_bytes(cfg, path, B);
+  else if (history == 1 || history >= n_blocks)
+    *out = history_ws_bytes(cfg, path, B, n_blocks, L);             // every block may compress
+  else {
+    const int64_t g = std::max<int64_t>(history, 2);
+    *out = history_ws_bytes(cfg, path, B, g + 1, g * (int64_t)B);   // a window of g blocks: g + 1 states
+  }
   return LOCOCO_OK;
 }
 
@@ -807,108 +815,138 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   }
   if (path == PATH_MFMA && workspace && ws_bytes >= step_ws_bytes(cfg, path, B)) {
     // the scan status of this call starts at "no wait gave up", whichever schedule runs
-    HIP_TRY(launch_scan_sync_clear((char*)workspace + filter_ws_bytes(cfg), cfg->batch, cfg->n_kv_heads,
+    HIP_TRY(launch_scan_sync_clear((char*)workspace + filter_ws_bytes(cfg), cfg->batch, cfg->n_kv_heads, false,
                                    (hipStream_t)stream), "clearing the scan counters");
   }
-  int64_t n_compress = 0, n_fill = 0;
+  int64_t n_compress = 0;
   for (const auto& sg : plan) n_compress += sg.branch;
-  while (n_fill < n && plan[(size_t)n_fill].branch == 0) ++n_fill;
-  if (path != PATH_GENERIC && any_compress && workspace &&
-      ws_bytes >= history_ws_bytes(cfg, path, B, n_compress, L)) {
-    // Batched-attention schedule: run the fill / compress recurrence first, keeping every
-    // cache state, then one attention launch over all blocks, then publish the last state.
+  // Batched-attention schedules: run the fill / compress recurrence of a window of blocks first,
+  // keeping the cache state after each of them in a ring of history slots, then one attention
+  // launch over the window's blocks.  The window is the whole sequence when the workspace holds
+  // every state, otherwise as many blocks as it holds (at least two: a ring of G + 1 slots serves a
+  // window of G blocks, the extra one being the state the window starts from); memory then stays
+  // independent of the sequence length, as in the step-by-step schedule.
+  int64_t window = 0, ring = 0;
+  if (path != PATH_GENERIC && any_compress && workspace) {
+    if (ws_bytes >= history_ws_bytes(cfg, path, B, n_compress, L)) {
+      window = n;
+      ring = n_compress;
+    } else {
+      for (int64_t g = std::min<int64_t>(n, 4096); g >= 2; --g)
+        if (ws_bytes >= history_ws_bytes(cfg, path, B, g + 1, g * (int64_t)B)) { window = g; ring = g + 1; break; }
+    }
+  }
+  if (window > 0) {
     hipStream_t s = (hipStream_t)stream;
     const size_t slot = align_up(state_bytes(cfg), 256);
+    const int64_t window_rows = std::min<int64_t>(L, window * (int64_t)B);
     char* sync_ws = (char*)workspace + filter_ws_bytes(cfg);      // fused path only
-    float* seq_stats = (float*)((char*)workspace + step_ws_bytes(cfg, path, B));
-    char* hist_k = (char*)seq_stats + stats_bytes(cfg, L);
-    char* hist_v = hist_k + (size_t)n_compress * slot;
-    const void* src_k = tmp.k[tmp.cur];
-    const void* src_v = tmp.v[tmp.cur];
+    float* win_stats = (float*)((char*)workspace + step_ws_bytes(cfg, path, B));
+    char* hist_k = (char*)win_stats + stats_bytes(cfg, window_rows);
+    char* hist_v = hist_k + (size_t)ring * slot;
+    const int64_t hist_stride = (int64_t)(slot / esize(cfg->dtype));
+    auto slot_k = [&](int64_t c) { return hist_k + (size_t)(c % ring) * slot; };
+    auto slot_v = [&](int64_t c) { return hist_v + (size_t)(c % ring) * slot; };
     bool one_launch = false;
     if (path == PATH_MFMA) {
       StepArgs probe = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
       one_launch = scan_fits_one_launch(cfg, probe);
     }
-    int64_t step = 0;
-    for (const auto& sg : plan) {
-      StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
-      a.m = sg.len_before;
-      if (sg.branch == 1 && one_launch) {
-        // every later block compresses too (the cache stays full): one launch runs them all,
-        // the slot tiles of a chain handing the new cache to each other through the history
-        const bool capturing = stream_is_capturing(s);
-        std::unique_lock<std::mutex> lk(g_scan_mu);
-        if (!capturing && another_scan_in_flight(s)) {
-          one_launch = false;            // another persistent scan holds compute units: one launch per step
-        } else {
-          a.cache_k = src_k;
-          a.cache_v = src_v;
-          ScanArgs sa;
-          sa.st = a;
-          sa.n_steps = (int32_t)n_compress;
-          sa.B = B;
-          sa.tokens_left = L - sg.start;
-          sa.out_k = hist_k;
-          sa.out_v = hist_v;
-          sa.out_stride = (int64_t)(slot / esize(cfg->dtype));
-          sa.sync = nullptr;
-          sa.status = nullptr;
-          sa.spin_limit = spin_limit();
-          sa.same_l2_allowed = chain_sync_through_l2() ? 1 : 0;
-          {
-            KTimer t(K_COMPRESS_MFMA, s);
-            HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
-                    "compress scan launch");
-          }
-          if (!capturing) note_scan_launched(s);
-          src_k = hist_k + (size_t)(n_compress - 1) * slot;
-          src_v = hist_v + (size_t)(n_compress - 1) * slot;
-          break;
+    int64_t c_done = 0;                       // compress steps enqueued so far: state c_done - 1 is the newest
+    for (int64_t w0 = 0; w0 < n; w0 += window) {
+      const int64_t w1 = std::min<int64_t>(n, w0 + window);
+      // the state the window starts from: the caller's live buffer until the first compression
+      const int64_t c0 = c_done;
+      const void* base_k = c0 == 0 ? tmp.k[tmp.cur] : slot_k(c0 - 1);
+      const void* base_v = c0 == 0 ? tmp.v[tmp.cur] : slot_v(c0 - 1);
+      int64_t fills = 0;                      // fill blocks at the head of the window
+      while (w0 + fills < w1 && plan[(size_t)(w0 + fills)].branch == 0) ++fills;
+      for (int64_t bi = w0; bi < w1; ++bi) {
+        const lococo_seg& sg = plan[(size_t)bi];
+        StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
+        a.m = sg.len_before;
+        if (sg.branch == 0) {
+          a.new_k = tmp.k[tmp.cur];
+          a.new_v = tmp.v[tmp.cur];
+          KTimer t(K_FILL, s);
+          HIP_TRY(launch_fill_generic(cfg->dtype, a, s), "fill launch");
+          continue;
         }
-      }
-      if (sg.branch == 0) {
-        a.new_k = tmp.k[tmp.cur];
-        a.new_v = tmp.v[tmp.cur];
-        KTimer t(K_FILL, s);
-        HIP_TRY(launch_fill_generic(cfg->dtype, a, s), "fill launch");
-      } else {
-        a.cache_k = src_k;
-        a.cache_v = src_v;
-        a.new_k = hist_k + (size_t)step * slot;
-        a.new_v = hist_v + (size_t)step * slot;
+        a.cache_k = c_done == 0 ? tmp.k[tmp.cur] : slot_k(c_done - 1);
+        a.cache_v = c_done == 0 ? tmp.v[tmp.cur] : slot_v(c_done - 1);
+        if (one_launch) {
+          // every later block of the window compresses too (the cache stays full): one launch runs
+          // them all, the slot tiles of a chain handing the new cache to each other through the ring
+          const bool capturing = stream_is_capturing(s);
+          std::unique_lock<std::mutex> lk(g_scan_mu);
+          if (!capturing && another_scan_in_flight(s)) {
+            one_launch = false;          // another persistent scan holds compute units: one launch per step
+          } else {
+            if (c_done > 0)              // the counters start every launch at zero; the status word is kept
+              HIP_TRY(launch_scan_sync_clear(sync_ws, cfg->batch, cfg->n_kv_heads, true, s), "clearing the scan counters");
+            ScanArgs sa;
+            sa.st = a;
+            sa.n_steps = (int32_t)(w1 - bi);
+            sa.B = B;
+            sa.tokens_left = L - sg.start;
+            sa.out_k = hist_k;
+            sa.out_v = hist_v;
+            sa.out_stride = hist_stride;
+            sa.slot0 = (int32_t)(c_done % ring);
+            sa.ring = (int32_t)ring;
+            sa.sync = nullptr;
+            sa.status = nullptr;
+            sa.spin_limit = spin_limit();
+            sa.same_l2_allowed = chain_sync_through_l2() ? 1 : 0;
+            {
+              KTimer t(K_COMPRESS_MFMA, s);
+              HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
+                      "compress scan launch");
+            }
+            if (!capturing) note_scan_launched(s);
+            c_done += w1 - bi;
+            break;
+          }
+        }
+        a.new_k = slot_k(c_done);
+        a.new_v = slot_v(c_done);
         if ((st = enqueue_compress(cfg, path, a, workspace, B, s))) return st;
-        src_k = a.new_k;
-        src_v = a.new_v;
-        ++step;
+        ++c_done;
       }
-    }
-    {
-      StepArgs a0 = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
-      AttnArgs t = attn_args_one_block(a0);
-      t.hist_k = hist_k;
-      t.hist_v = hist_v;
-      t.hist_stride = (int64_t)(slot / esize(cfg->dtype));
-      t.L = L;
-      t.B = B;
-      t.len0 = cache->len;
-      t.n_fill = (int32_t)n_fill;
-      t.n_seg = (int32_t)n;
-      t.stats = cache->attn_colsum ? seq_stats : nullptr;
       {
-        KTimer kt(K_ATTN_MFMA, s);
-        HIP_TRY(launch_attn_mfma(t, s), "attention launch");
-      }
-      if (cache->attn_colsum) {             // sums over blocks commute: one launch for all of them
-        KTimer kt(K_ATTN_COLSUM, s);
-        HIP_TRY(launch_attn_colsum_mfma(t, cache->attn_colsum, s), "attention column-sum launch");
+        const lococo_seg& first = plan[(size_t)w0];
+        StepArgs a0 = make_args(cfg, seq, first.start, B, &tmp, conv_w, conv_b, true);
+        AttnArgs t = attn_args_one_block(a0);
+        t.cache_k = base_k;
+        t.cache_v = base_v;
+        t.hist_k = hist_k;
+        t.hist_v = hist_v;
+        t.hist_stride = hist_stride;
+        t.hist_first = (int32_t)(c0 % ring);
+        t.hist_ring = (int32_t)ring;
+        t.L = std::min<int64_t>(L - first.start, (w1 - w0) * (int64_t)B);
+        t.B = B;
+        t.len0 = first.len_before;
+        t.n_fill = (int32_t)fills;
+        t.n_seg = (int32_t)(w1 - w0);
+        t.stats = cache->attn_colsum ? win_stats : nullptr;
+        {
+          KTimer kt(K_ATTN_MFMA, s);
+          HIP_TRY(launch_attn_mfma(t, s), "attention launch");
+        }
+        if (cache->attn_colsum) {           // sums over blocks commute: one launch for all of the window's
+          KTimer kt(K_ATTN_COLSUM, s);
+          HIP_TRY(launch_attn_colsum_mfma(t, cache->attn_colsum, s), "attention column-sum launch");
+        }
       }
     }
     const lococo_seg& last = plan.back();
-    HIP_TRY(hipMemcpyAsync(tmp.k[last.buf_after], src_k, state_bytes(cfg), hipMemcpyDeviceToDevice, s),
-            "publishing the final cache");
-    HIP_TRY(hipMemcpyAsync(tmp.v[last.buf_after], src_v, state_bytes(cfg), hipMemcpyDeviceToDevice, s),
-            "publishing the final cache");
+    if (c_done > 0) {
+      HIP_TRY(hipMemcpyAsync(tmp.k[last.buf_after], slot_k(c_done - 1), state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+              "publishing the final cache");
+      HIP_TRY(hipMemcpyAsync(tmp.v[last.buf_after], slot_v(c_done - 1), state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+              "publishing the final cache");
+    }
     tmp.cur = last.buf_after;
     tmp.len = last.len_after;
     *cache = tmp;
@@ -975,6 +1013,7 @@ lococo_status lococo_segment_step_backward(const lococo_config* cfg, const lococ
     return st;
   if (!d_o || !d_new_k || !d_new_v || !d_q || !d_k || !d_v || !d_cache_k || !d_cache_v)
     return fail(LOCOCO_EINVAL, "a gradient pointer is NULL");
+  if (cfg->norm == 2) return fail(LOCOCO_EUNSUPPORTED, "norm = 2 (rectifier on the convolution input) is forward only");
   const bool compress = cache_before->len + B > cfg->M;
   if (compress && (!conv_w || !d_conv_w))
     return fail(LOCOCO_EINVAL, "conv_w or d_conv_w is NULL but the step compresses");

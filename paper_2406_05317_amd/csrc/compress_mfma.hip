@@ -648,10 +648,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     m = step == 0 ? a.m : a.M;
     T = m + Bn;
     NT = (T + BN - 1) / BN;
-    const uint16_t* src_k = step == 0 ? (const uint16_t*)a.cache_k
-                                      : (const uint16_t*)sa.out_k + (int64_t)(step - 1) * sa.out_stride;
-    const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v
-                                      : (const uint16_t*)sa.out_v + (int64_t)(step - 1) * sa.out_stride;
+    const int64_t prev = (int64_t)((sa.slot0 + step - 1) % sa.ring) * sa.out_stride;   // (unused for step 0)
+    const uint16_t* src_k = step == 0 ? (const uint16_t*)a.cache_k : (const uint16_t*)sa.out_k + prev;
+    const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v : (const uint16_t*)sa.out_v + prev;
     cat_k = make_cat(src_k + (int64_t)ch * a.M * kD, m,
                      (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + tok * a.k.st, a.k.st, Bn);
     cat_v = make_cat(src_v + (int64_t)ch * a.M * kD, m,
@@ -711,8 +710,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // stage) and leave as whole rows, 1 KB of contiguous memory per wave instruction.
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
   __syncthreads();
-  uint16_t* nk = (uint16_t*)sa.out_k + (int64_t)step * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
-  uint16_t* nv = (uint16_t*)sa.out_v + (int64_t)step * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
+  const int64_t out_at = (int64_t)((sa.slot0 + step) % sa.ring) * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
+  uint16_t* nk = (uint16_t*)sa.out_k + out_at;
+  uint16_t* nv = (uint16_t*)sa.out_v + out_at;
   unsigned char* Orows = Xs0;                // [K rows of the tile ; V rows of the tile][XSTRIDE]
   static_assert(2 * BM * G::XSTRIDE <= G::NXBUF * G::XBYTES, "the output rows fit the key-tile area");
   uint32_t keep[G::RT];
@@ -872,6 +872,8 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.out_k = a.new_k;
   sa.out_v = a.new_v;
   sa.out_stride = 0;
+  sa.slot0 = 0;
+  sa.ring = 1;
   sa.sync = nullptr;
   sa.status = nullptr;
   sa.spin_limit = 0;
@@ -925,8 +927,9 @@ size_t compress_scan_sync_bytes(int batch, int Hkv) {
   return (2 * (size_t)batch * Hkv + 1) * sizeof(uint32_t);
 }
 
-hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, hipStream_t s) {
-  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws, 2 * batch * Hkv + 1);
+hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, bool keep_status, hipStream_t s) {
+  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws,
+                     keep_status ? batch * Hkv : 2 * batch * Hkv + 1);
   return hipGetLastError();
 }
 

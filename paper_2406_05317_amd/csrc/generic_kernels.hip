@@ -162,6 +162,7 @@ __global__ __launch_bounds__(kThreads) void conv_logits_generic_k(StepArgs a, fl
           const int cc = c0 + c;
           v = cc < a.d ? to_f(cat_row<T>(a.cache_k, a.k, a.M, a.d, a.m, b, hkv, a.Hkv, jj)[cc])
                        : to_f(cat_row<T>(a.cache_v, a.v, a.M, a.d, a.m, b, hkv, a.Hkv, jj)[cc - a.d]);
+          if (a.norm == 2) v = fmaxf(v, 0.f);          // the rectifier in front of the convolution layer
         }
         Xs[c][r] = v;
       }
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void normalise_generic_k(StepArgs a, floa
     }
     z = block_sum(z, red);
     for (int j = threadIdx.x; j < Tn; j += kThreads) row[j] /= z;
-  } else {
+  } else if (a.norm == 1) {
     float z = 0.f;
     for (int j = threadIdx.x; j < Tn; j += kThreads) {
       float e = fmaxf(row[j], 0.f);
@@ -221,6 +222,18 @@ __global__ __launch_bounds__(kThreads) void normalise_generic_k(StepArgs a, floa
       z += e;
     }
     z = block_sum(z, red) + a.eps;
+    for (int j = threadIdx.x; j < Tn; j += kThreads) row[j] /= z;
+  } else {
+    // Eq. 6 as printed: W / sum(W); excluded positions (-inf) carry no weight; a vanishing signed
+    // sum is replaced by +-eps
+    float z = 0.f;
+    for (int j = threadIdx.x; j < Tn; j += kThreads) {
+      const float e = isfinite(row[j]) ? row[j] : 0.f;
+      row[j] = e;
+      z += e;
+    }
+    z = block_sum(z, red);
+    if (fabsf(z) < a.eps) z = z < 0.f ? -a.eps : a.eps;
     for (int j = threadIdx.x; j < Tn; j += kThreads) row[j] /= z;
   }
 }
@@ -243,10 +256,15 @@ __global__ __launch_bounds__(kThreads) void mix_generic_k(StepArgs a, const floa
       z = 0.f;
       for (int j = threadIdx.x; j < Tn; j += kThreads) z += expf(wr[j] - mx);
       z = block_sum(z, red);
-    } else {
+    } else if (a.norm == 1) {
       z = 0.f;
       for (int j = threadIdx.x; j < Tn; j += kThreads) z += fmaxf(wr[j], 0.f);
       z = block_sum(z, red) + a.eps;
+    } else {
+      z = 0.f;
+      for (int j = threadIdx.x; j < Tn; j += kThreads) z += isfinite(wr[j]) ? wr[j] : 0.f;
+      z = block_sum(z, red);
+      if (fabsf(z) < a.eps) z = z < 0.f ? -a.eps : a.eps;
     }
   }
   for (int e = threadIdx.x; e < 2 * a.d; e += kThreads) {
@@ -257,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void mix_generic_k(StepArgs a, const floa
       const T* y = cat_row<T>(isv ? a.cache_v : a.cache_k, isv ? a.v : a.k, a.M, a.d, a.m, b, hkv,
                               a.Hkv, j);
       float wj = wr[j];
-      if (raw) wj = (a.norm == 0 ? expf(wj - mx) : fmaxf(wj, 0.f)) / z;
+      if (raw) wj = (a.norm == 0 ? expf(wj - mx) : a.norm == 1 ? fmaxf(wj, 0.f) : isfinite(wj) ? wj : 0.f) / z;
       acc += wj * to_f(y[c]);
     }
     T* dst = (T*)(isv ? a.new_v : a.new_k) + ((int64_t)ch * a.M + i) * a.d + c;

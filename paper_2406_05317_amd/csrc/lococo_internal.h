@@ -55,7 +55,8 @@ struct StepArgs {
 // one launch.  Step 0 is described by `st` (source cache, occupancy st.m, block at the k/v views,
 // st.Bn tokens).  Step s > 0 reads the state step s-1 wrote, has a full cache (M slots) and takes
 // the block s*B tokens further on (B tokens, fewer if tokens_left runs out).  Step s writes its
-// new cache to out_k/out_v + s*out_stride elements.  Between steps the slot tiles of a chain wait
+// new cache to slot (slot0 + s) % ring of out_k/out_v, slots out_stride elements apart (a ring of
+// states: the whole history of a sequence, or a window of it).  Between steps the slot tiles of a chain wait
 // for each other on sync[chain] (zeroed by the caller); a wait that exceeds spin_limit polls sets
 // *status to 1 and makes the workgroup leave the kernel.
 struct ScanArgs {
@@ -66,6 +67,7 @@ struct ScanArgs {
   void* out_k;
   void* out_v;
   int64_t out_stride;
+  int32_t slot0, ring;       // ring >= 1
   uint32_t* sync;
   int32_t* status;
   int32_t spin_limit;
@@ -77,7 +79,8 @@ struct ScanArgs {
 // whose intermediate caches were kept.  Block n = seg_first + (launch index)
 // covers tokens [n*B, min((n+1)*B, L)) of the q/k/v/o views.  Blocks n <= n_fill
 // see the base cache with len0 + n*B live slots (the fill phase appends in
-// place); block n > n_fill sees history slot n - n_fill - 1 with M live slots.
+// place; with n_fill = 0 the base is simply the state before block 0); block
+// n > n_fill sees history slot (hist_first + n - n_fill - 1) % hist_ring with M live slots.
 struct AttnArgs {
   View q, k, v;
   View o;
@@ -86,6 +89,7 @@ struct AttnArgs {
   const void* hist_k;      // history slots, hist_stride elements apart (may be null if unused)
   const void* hist_v;
   int64_t hist_stride;
+  int32_t hist_first, hist_ring;   // hist_ring >= 1 whenever hist_k is used
   int64_t L;
   int32_t B, M, len0, n_fill, seg_first, n_seg;
   int32_t batch, Hq, Hkv, group;
@@ -167,8 +171,9 @@ int compress_scan_max_resident(const StepArgs& a, int n_cu);
 int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu);
 // bytes of the sync counters + status word the scan launch needs
 size_t compress_scan_sync_bytes(int batch, int Hkv);
-// zero them (a fill kernel, so the call may sit inside a captured graph)
-hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, hipStream_t s);
+// zero them (a fill kernel, so the call may sit inside a captured graph); keep_status: only the chain
+// counters, not the status word (between the launches of one call)
+hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, bool keep_status, hipStream_t s);
 // the same kernel over n_steps consecutive compress steps (see ScanArgs); `sync_ws` is
 // compress_scan_sync_bytes() of device memory, cleared beforehand
 hipError_t launch_compress_scan(const ScanArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,

@@ -42,12 +42,13 @@ class Workload:
     M: int                  # cache slots
     conv_width: int         # odd
     conv_in: int = 0        # 0: keys only (C = d); 1: [K;V] stacked (C = 2d)
-    norm: int = 0           # 0: softmax over positions; 1: relu + sum
+    norm: int = 0           # 0: softmax over positions; 1: relu + sum; 2: relu on the conv input, plain sum
     per_head_filters: bool = False
     qk_gain: float = 1.0    # multiplies Q and K ("sharpened" variants use > 1)
     conv_gain: float = 1.0  # multiplies the conv weights
     tok_lognormal_sigma: float = 0.0  # per-token norm scale ~ LogNormal(0, sigma)
     bias_sigma: float = 0.0
+    filter_abs: bool = False          # |weights|, |bias|: keeps the signed row sums of norm = 2 away from zero
     seed: int = 0
 
     @property
@@ -139,11 +140,13 @@ def conv_filters(w: Workload):
     g = _stream(w.seed, "conv_w")
     x = g.standard_normal(shape, dtype=np.float32)
     x *= np.float32(w.conv_gain / math.sqrt(w.C * w.conv_width))
+    if w.filter_abs:
+        x = np.abs(x)
     cw = _store(x if w.per_head_filters else x[0], w.torch_dtype)
     bshape = (banks, w.M) if w.per_head_filters else (w.M,)
     if w.bias_sigma > 0.0:
         bz = _stream(w.seed, "conv_b").standard_normal(bshape, dtype=np.float32)
-        cb = _store(bz * np.float32(w.bias_sigma), w.torch_dtype)
+        cb = _store((np.abs(bz) if w.filter_abs else bz) * np.float32(w.bias_sigma), w.torch_dtype)
     else:
         cb = torch.zeros(bshape, dtype=w.torch_dtype)
     return cw, cb

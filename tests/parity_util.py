@@ -46,7 +46,8 @@ def oracle_forward(w: inputs.Workload, q, k, v, cw, cb, *, B=None, cache=None, n
 
 def gpu_forward(w: inputs.Workload, q, k, v, cw, cb, *, B=None, impl=0, history=False,
                 cache_init=None, step_by_step=False, protect=None):
-    """HIP path through the binding.  Returns (o, cache_k, cache_v, len, cur) as CPU tensors."""
+    """HIP path through the binding.  Returns (o, cache_k, cache_v, len, cur) as CPU tensors.
+    history: False / True, or an int G >= 2 for a workspace that holds a window of G blocks."""
     from paper_2406_05317_amd import binding as lb
     dev = "cuda"
     B = B or w.B

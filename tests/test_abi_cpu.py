@@ -82,7 +82,7 @@ def test_plan_and_config_errors_are_status_codes():
     for kw, status in [(dict(conv_width=4), lb.LOCOCO_EUNSUPPORTED),
                        (dict(conv_width=0), lb.LOCOCO_EINVAL),
                        (dict(n_q_heads=3, n_kv_heads=2), lb.LOCOCO_EINVAL),
-                       (dict(M=0), lb.LOCOCO_EINVAL), (dict(norm=2), lb.LOCOCO_EINVAL),
+                       (dict(M=0), lb.LOCOCO_EINVAL), (dict(norm=3), lb.LOCOCO_EINVAL),
                        (dict(conv_in=3), lb.LOCOCO_EINVAL), (dict(impl=7), lb.LOCOCO_EINVAL),
                        (dict(head_dim=4096), lb.LOCOCO_EUNSUPPORTED)]:
         cfg = _cfg(**kw)

@@ -74,6 +74,64 @@ def test_mfma_batched_attention_schedule(case):
     assert a[3:] == b[3:]
 
 
+@pytest.mark.parametrize("case", [
+    dict(M=128, B=64, L=1024, window=3),                               # two fills; windows of 3: fills + one compress, then compress only
+    dict(M=128, B=128, L=1500, window=2),                              # ragged last block in a window of its own
+    dict(M=256, B=64, L=1024, window=2, n_q_heads=8, n_kv_heads=2),    # four fills: the fill phase spans two windows
+    dict(M=128, B=96, L=960, window=4, batch=2, n_q_heads=6, n_kv_heads=3),   # partly filled cache at the first compress
+    dict(M=512, B=512, L=4096, window=3, n_q_heads=16, n_kv_heads=16),        # 128 workgroups of 64 slots, 8 per chain
+    dict(M=128, B=64, L=640, window=4, batch=12, n_q_heads=8, n_kv_heads=8),  # several chains per workgroup
+    dict(M=128, B=128, L=900, window=3, conv_in=1, conv_width=21, norm=1, bias_sigma=0.5, impl=0),   # unfused MFMA path
+    dict(M=128, B=128, L=896, window=5, protect_share=0.1, track=True),       # protected slots, attention per slot tracked
+])
+def test_windowed_history_equals_full_history_and_step_by_step(case, options):
+    """A workspace that holds the states of a window of G blocks: the compression scan and the batched
+    attention run window by window on a ring of G + 1 states.  Bit-identical to the whole-sequence
+    history and to the step-by-step schedule; equal to the oracle."""
+    case = dict(case)
+    G, impl = case.pop("window"), case.pop("impl", MFMA)
+    share, track = case.pop("protect_share", 0.0), case.pop("track", False)
+    w = _w(**case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    protect = (np.random.default_rng(5).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
+    cfg = lb.config_for(w, impl=impl)
+    full_bytes = lb.lococo_workspace_bytes(cfg, w.L, w.B, 1)
+    win_bytes = lb.lococo_workspace_bytes(cfg, w.L, w.B, G)
+    assert lb.lococo_workspace_bytes(cfg, w.L, w.B, 0) < win_bytes < full_bytes
+    assert win_bytes == lb.lococo_workspace_bytes(cfg, 100 * w.L, w.B, G)      # independent of the sequence length
+    lb.lococo_timing_begin()
+    a = gpu_forward(w, q, k, v, cw, cb, impl=impl, history=G, protect=protect)
+    ran = lb.lococo_timing_end()
+    n_blocks = -(-w.L // w.B)
+    assert ran["attn_mfma"][0] == -(-n_blocks // G), ran             # one attention launch per window
+    b = gpu_forward(w, q, k, v, cw, cb, impl=impl, history=True, protect=protect)
+    c = gpu_forward(w, q, k, v, cw, cb, impl=impl, history=False, protect=protect)
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 1)
+    d = gpu_forward(w, q, k, v, cw, cb, impl=impl, history=G, protect=protect)
+    for other in (b, c, d):
+        for x, y in zip(a[:3], other[:3]):
+            assert torch.equal(x, y)
+        assert a[3:] == other[3:]
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    compare_scan(w, a, want, what="windowed history")
+    if track:
+        # attention per slot, accumulated window by window (the row statistics of one window at a time)
+        want_cs = np.zeros((w.batch, w.n_kv_heads, w.M))
+        orc.sequence_forward(q, k, v, cw, cb, B=w.B, M=w.M, conv_in=w.conv_in, norm=w.norm, state_round=w.dtype,
+                             protect=protect, attn_colsum=want_cs, nthreads=16)
+        cache = lb.Cache(cfg)
+        cache.set_protect(protect)
+        cache.track_attention()
+        od = torch.empty_like(q, device="cuda")
+        lb.lococo_sequence_forward(cfg, q.cuda(), k.cuda(), v.cuda(), od, cw.cuda(), cb.cuda(), cache, w.B,
+                                   lb.workspace(cfg, w.L, w.B, G))
+        torch.cuda.synchronize()
+        assert torch.equal(od.cpu(), a[0])
+        from parity_util import assert_close
+        assert_close(cache.attn_colsum.cpu().double().numpy(), want_cs, 2e-2, "attention column sums, windowed")
+
+
 def test_mfma_resume_with_history_from_a_full_cache():
     """A scan continued from a full cache (no fill phase) under the batched schedule."""
     w = _w(L=768)

@@ -69,6 +69,8 @@ def test_cfg1_sharpened_inputs():
     dict(n_q_heads=6, n_kv_heads=2, head_dim=24, conv_width=1),
     dict(conv_in=1, conv_width=7),
     dict(norm=1, conv_gain=4.0),
+    dict(norm=2, filter_abs=True, bias_sigma=0.3),       # rectifier on the conv input, Eq. 6 as printed
+    dict(norm=2, filter_abs=True, conv_in=1, conv_width=7, L=120, B=50),
     dict(per_head_filters=True, bias_sigma=0.5),
     dict(batch=1, n_q_heads=1, n_kv_heads=1, head_dim=64, L=96, B=16, M=16, conv_width=21),
 ])
