@@ -213,13 +213,14 @@ LOCOCO_API lococo_status lococo_segment_step(const lococo_config* cfg, const loc
  * or event creation; the optional kernel timing of lococo_timing_begin, which creates events, must
  * be off).
  *   - A step whose lococo_workspace_bytes(cfg, B, B, 0) exceeds the array is refused with
- *     LOCOCO_EWORKSPACE (enough for the benchmark shapes on the fused path: 32 heads, M = 512, width 15
- *     needs 2.1 MB; not for the logits of large shapes on the other paths).
+ *     LOCOCO_EWORKSPACE (enough for every shape of the fused path: 32 heads, M = 512, width 15 needs
+ *     2.1 MB, 32 heads with M = 128, whose steps are split over two workgroups per slot tile, 9 MB; not
+ *     for the logits of large shapes on the other paths).
  *   - LOCOCO_FLAG_FILTERS_PREPARED is refused (LOCOCO_EINVAL): the array is shared by every caller on
  *     the device and keeps whatever the last call left in it, so each call repacks the filters itself.
  *   - Calls that overlap on one GPU (two streams, two threads) race on the array: the caller must
  *     order them, as for any shared workspace.  Nothing in it has to start at zero. */
-#define LOCOCO_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+#define LOCOCO_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
 LOCOCO_API lococo_status lococo_segment_step_noalloc(const lococo_config* cfg, const lococo_qkvo* blk, int32_t B,
                                                      const void* conv_w, const void* conv_b, lococo_cache* cache,
                                                      void* stream);
@@ -284,7 +285,10 @@ typedef struct lococo_path_info {
                                    compression steps in one launch (each takes every scan_groups-th chain);
                                    0 when it would launch every step separately                                */
   int32_t scan_resident_limit;  /* path 1: workgroups of that kernel the device holds at once                  */
-  int32_t reserved[3];
+  int32_t position_split;       /* path 1: workgroups that share out the positions of a step of one (chain,
+                                   slot tile) where one each would leave compute units idle; 1 = no split
+                                   (several chains per workgroup never split)                                  */
+  int32_t reserved[2];
 } lococo_path_info;
 LOCOCO_API lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_path_info* out);
 

@@ -67,7 +67,8 @@ class lococo_kernel_time(C.Structure):
 
 class lococo_path_info(C.Structure):
     _fields_ = [("path", C.c_int32), ("compute_units", C.c_int32), ("tile_slots", C.c_int32),
-                ("scan_groups", C.c_int32), ("scan_resident_limit", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("scan_groups", C.c_int32), ("scan_resident_limit", C.c_int32), ("position_split", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class LococoError(RuntimeError):
@@ -333,7 +334,8 @@ def lococo_describe_path(cfg, B: int) -> dict:
     out = lococo_path_info()
     _check(lib().lococo_describe_path(C.byref(cfg), B, C.byref(out)))
     return {"path": out.path, "compute_units": out.compute_units, "tile_slots": out.tile_slots,
-            "scan_groups": out.scan_groups, "scan_resident_limit": out.scan_resident_limit}
+            "scan_groups": out.scan_groups, "scan_resident_limit": out.scan_resident_limit,
+            "position_split": out.position_split}
 
 
 def lococo_timing_begin():

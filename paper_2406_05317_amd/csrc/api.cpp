@@ -219,7 +219,7 @@ size_t filter_ws_bytes(const lococo_config* c) {
 }
 // chain sync counters + status word of the one-launch scan
 size_t scan_sync_bytes(const lococo_config* c) {
-  return align_up(compress_scan_sync_bytes(c->batch, c->n_kv_heads), 256);
+  return align_up(compress_scan_sync_bytes(c->batch, c->n_kv_heads, c->M), 256);
 }
 // softmax statistics of `rows` query rows per head (what the column sums of the MFMA attention need)
 size_t stats_bytes(const lococo_config* c, int64_t rows) {
@@ -232,12 +232,20 @@ size_t packed_ws_bytes(const lococo_config* c) {
 size_t logits_bytes(const lococo_config* c, int32_t B) {     // rows of up to M + B logits, padded to a multiple of 4
   return align_up((size_t)c->batch * c->n_kv_heads * c->M * (((size_t)c->M + B + 3) / 4 * 4) * sizeof(float), 256);
 }
-// MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block];
-// unfused MFMA path: [filters packed per tap][row statistics of one block][logits]; generic path: the logits.
+// results of the parts of a split step (see compress_mfma.hip), 0 where the shape is not split
+size_t partials_ws_bytes(const lococo_config* c) {
+  return align_up(compress_partials_bytes(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count()), 256);
+}
+// MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block][results of
+// the parts of a split step]; unfused MFMA path: [filters packed per tap][row statistics of one block][logits];
+// generic path: the logits.
 size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
-  if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B);
+  if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B) + partials_ws_bytes(c);
   if (path == PATH_MFMA_UNFUSED) return packed_ws_bytes(c) + stats_bytes(c, B) + logits_bytes(c, B);
   return logits_bytes(c, B);
+}
+void* partials_of(const lococo_config* c, void* ws, int32_t B) {
+  return (char*)ws + filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B);
 }
 
 // Bytes of one history slot pair member: one cache state [chains, M, d].
@@ -308,7 +316,10 @@ bool scan_fits_one_launch(const lococo_config* c, const StepArgs& a) {
   const int groups = compress_scan_groups(c->batch, c->n_kv_heads, c->M, c->conv_width,
                                           c->w_head_stride != 0 || c->b_head_stride != 0, cu_count());
   if (groups <= 0) return false;
-  const int64_t grid = (int64_t)groups * (c->M / compress_tile_slots(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count()));
+  const int split = groups < c->batch * c->n_kv_heads
+                        ? 1 : compress_position_split(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count());
+  const int64_t grid = (int64_t)groups * split *
+                       (c->M / compress_tile_slots(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count()));
   return grid <= compress_scan_max_resident(a, cu_count());
 }
 
@@ -447,7 +458,8 @@ lococo_status enqueue_repack(const lococo_config* c, Path path, const StepArgs& 
 lococo_status enqueue_compress(const lococo_config* c, Path path, StepArgs a, void* ws, int32_t B, hipStream_t s) {
   if (path == PATH_MFMA) {
     KTimer t(K_COMPRESS_MFMA, s);
-    HIP_TRY(launch_compress_mfma(a, ws, filter_banks(c), cu_count(), s), "compress launch");
+    HIP_TRY(launch_compress_mfma(a, ws, filter_banks(c), cu_count(), (char*)ws + filter_ws_bytes(c), partials_of(c, ws, B), s),
+            "compress launch");
     return LOCOCO_OK;
   }
   const bool unfused = path == PATH_MFMA_UNFUSED;
@@ -595,6 +607,7 @@ lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_p
   out->compute_units = cu_count();
   if (path == PATH_MFMA) {
     out->tile_slots = compress_tile_slots(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cu_count());
+    out->position_split = compress_position_split(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cu_count());
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.batch = cfg->batch; a.Hkv = cfg->n_kv_heads; a.M = cfg->M; a.k_width = cfg->conv_width; a.norm = cfg->norm;
@@ -815,7 +828,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   }
   if (path == PATH_MFMA && workspace && ws_bytes >= step_ws_bytes(cfg, path, B)) {
     // the scan status of this call starts at "no wait gave up", whichever schedule runs
-    HIP_TRY(launch_scan_sync_clear((char*)workspace + filter_ws_bytes(cfg), cfg->batch, cfg->n_kv_heads, false,
+    HIP_TRY(launch_scan_sync_clear((char*)workspace + filter_ws_bytes(cfg), cfg->batch, cfg->n_kv_heads, cfg->M, false,
                                    (hipStream_t)stream), "clearing the scan counters");
   }
   int64_t n_compress = 0;
@@ -883,7 +896,7 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
             one_launch = false;          // another persistent scan holds compute units: one launch per step
           } else {
             if (c_done > 0)              // the counters start every launch at zero; the status word is kept
-              HIP_TRY(launch_scan_sync_clear(sync_ws, cfg->batch, cfg->n_kv_heads, true, s), "clearing the scan counters");
+              HIP_TRY(launch_scan_sync_clear(sync_ws, cfg->batch, cfg->n_kv_heads, cfg->M, true, s), "clearing the scan counters");
             ScanArgs sa;
             sa.st = a;
             sa.n_steps = (int32_t)(w1 - bi);
@@ -900,8 +913,8 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
             sa.same_l2_allowed = chain_sync_through_l2() ? 1 : 0;
             {
               KTimer t(K_COMPRESS_MFMA, s);
-              HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws, s),
-                      "compress scan launch");
+              HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws,
+                                           partials_of(cfg, workspace, B), s), "compress scan launch");
             }
             if (!capturing) note_scan_launched(s);
             c_done += w1 - bi;

@@ -81,6 +81,7 @@ struct Geo {
   static constexpr int LPR = 64 / RPW;               // lanes per slot there
   static constexpr int EPL = BN / LPR;               // positions per lane there
   static_assert(BM == 32 || BM == 64, "BM");
+  static constexpr int PART_FLOATS = BM * 2 * kD + 2 * BM;   // a part's accumulators [slot][2 d], references, row sums
   static_assert(EPL % 4 == 0, "softmax lanes read whole float4s");
   static_assert(NS >= 26, "the slices of the pipelined loop are laid out over 26 contraction steps");
   static_assert(LDS <= 160 * 1024, "LDS budget");
@@ -166,10 +167,16 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // common case pays neither the registers nor the instructions.
 // MULTI = 1: a workgroup may own several chains (see below); also a build of its own, because the
 // register allocation of the one-chain build is tight and the 32 K-token workload runs on it.
-template <int BM, int KW, int NORM, int PROT, int MULTI>
+// SPLIT = 1: the positions of a step are shared out between sa.psplit workgroups per (chain, slot
+// tile) -- for shapes whose (chain, tile) pairs would leave compute units idle.  Each part walks its
+// range of position tiles with the same pipeline and leaves its running reference, row sum and
+// unnormalised accumulators in the workspace; the part that arrives last merges them in a fixed
+// order (so the result does not depend on who is last) and writes the rows.
+template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
+  static_assert(!SPLIT || (BM == 32 && !MULTI), "the position split is built for 32-slot tiles, one chain per workgroup");
   const StepArgs& a = sa.st;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Xs0 = smem;                                    // NXBUF key tiles (with halo)
@@ -188,14 +195,19 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     if (item < per * 8) item = (item % 8) * per + item / 8;
   }
   const int tiles = a.M / BM;
+  // position split: consecutive work items are the parts of one (chain, slot tile), so they land on one XCD
+  const int P = SPLIT ? sa.psplit : 1;
+  const int part = SPLIT ? item % P : 0;
+  if (SPLIT) item /= P;
   // A workgroup owns one slot tile of the chains grp, grp + groups, grp + 2 groups, ...  (one chain
   // when the launch has a workgroup per chain and tile).  Where filters or biases differ between
   // kv heads the host picks `groups` as a multiple of Hkv, so all of them belong to head hkv0.
-  const int grp = item / tiles, groups = gridDim.x / tiles, n_chains = a.batch * a.Hkv;
+  const int grp = item / tiles, groups = gridDim.x / (tiles * P), n_chains = a.batch * a.Hkv;
   const int hkv0 = grp % a.Hkv;
   const int i0 = (item % tiles) * BM;
   // per-step and per-chain quantities, set at the top of the loops
   int T = 0, m = 0, NT = 0;
+  int jbase = 0;            // first position of this workgroup's range (0 unless the positions are split)
   CatRows cat_k, cat_v;
   // protected-slot bits of the chain at hand (see lococo_cache.protect), or null
   const uint32_t* pwords = nullptr;
@@ -303,7 +315,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t) {
     constexpr bool DoConv = decltype(do_conv)::value, DoSoftmax = decltype(do_softmax)::value;
     constexpr bool DoMix = decltype(do_mix_t)::value;
-    const int j0 = i * BN;
+    const int j0 = (SPLIT ? jbase : 0) + i * BN;
     const unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
     const unsigned char* Xnext2 = Xs0 + ((i + 2) % G::NXBUF) * G::XBYTES;
     const unsigned char* Xprev = Xs0 + ((i + G::NXBUF - 1) % G::NXBUF) * G::XBYTES;
@@ -598,7 +610,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   };
   auto chain_wait = [&](int c, int round) -> bool {
     if (tid == 0) {
-      const uint32_t target = (uint32_t)tiles * (uint32_t)(round + 1);
+      // round 0 (the census) is signalled by every workgroup of the chain, later rounds by the one
+      // workgroup per slot tile that writes the rows
+      const uint32_t target = (uint32_t)(tiles * P) + (uint32_t)tiles * (uint32_t)round;
       int polls = 0;
       while (__hip_atomic_load(sa.sync + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
         __builtin_amdgcn_s_sleep(2);
@@ -613,6 +627,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     __syncthreads();
     return bail == 0;
   };
+  if (SPLIT && tid == 0) {
+    // every part registers the XCD it runs on in the census word of its (chain, tile); read at the hand-off
+    const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | ((4 - 1) << 11)) & 7u;
+    __hip_atomic_fetch_add(sa.psync + 2 * (grp * tiles + i0 / BM) + 1, 1u << (3u * xcd), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+  }
   if (sa.n_steps > 1) {
     uint32_t* xcd_mask = sa.sync + n_chains + 1;
     if (tid == 0) {
@@ -648,6 +668,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     m = step == 0 ? a.m : a.M;
     T = m + Bn;
     NT = (T + BN - 1) / BN;
+    if (SPLIT) {                       // this part's range of position tiles (possibly empty)
+      const int per = (NT + P - 1) / P, lo = part * per;
+      const int hi = lo + per < NT ? lo + per : NT;
+      jbase = lo * BN;
+      NT = hi > lo ? hi - lo : 0;
+    }
     const int64_t prev = (int64_t)((sa.slot0 + step - 1) % sa.ring) * sa.out_stride;   // (unused for step 0)
     const uint16_t* src_k = step == 0 ? (const uint16_t*)a.cache_k : (const uint16_t*)sa.out_k + prev;
     const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v : (const uint16_t*)sa.out_v + prev;
@@ -668,19 +694,21 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // ---- prologue: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way.  All
   // loads are issued before the first store (the accumulators' registers are free here), so the
   // step starts after one memory latency, not three.
+  if (!SPLIT || NT > 0) {
   {
+    const int jb = SPLIT ? jbase : 0;
     Cat16 xpro[3][G::XPER];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
       for (int it = 0; it < G::XPER; ++it) {
         const int item = tid + it * kThreads;
-        xpro[t][it] = load_cat16(cat_k, t * BN - G::PAD + (item >> 4), item & 15);
+        xpro[t][it] = load_cat16(cat_k, jb + t * BN - G::PAD + (item >> 4), item & 15);
       }
 #pragma unroll
-    for (int it = 0; it < G::XPER; ++it) load_x(it, 3 * BN);
+    for (int it = 0; it < G::XPER; ++it) load_x(it, jb + 3 * BN);
 #pragma unroll
-    for (int it = 0; it < G::VPER; ++it) load_v(it, 0);
+    for (int it = 0; it < G::VPER; ++it) load_v(it, jb);
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
@@ -704,15 +732,136 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     stage(0, no, yes, no);
   }
   stage(NT, no, no, yes);
+  }  // a part with positions
 
+  uint16_t* nk;
+  uint16_t* nv;
+  {
+    const int64_t out_at = (int64_t)((sa.slot0 + step) % sa.ring) * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
+    nk = (uint16_t*)sa.out_k + out_at;
+    nv = (uint16_t*)sa.out_v + out_at;
+  }
+  if constexpr (SPLIT) {
+    // ---- this part's result goes to the workspace: accumulators [slot][2 d] as they are
+    // (unnormalised, relative to this part's reference), then the references, then the row sums
+    float* mine = sa.partials + ((int64_t)(ch * tiles + i0 / BM) * P + part) * G::PART_FLOATS;
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 v = {oacc[ct][0][g * 4 + 0], oacc[ct][0][g * 4 + 1], oacc[ct][0][g * 4 + 2], oacc[ct][0][g * 4 + 3]};
+        *(f32x4*)(mine + l31 * (2 * kD) + 64 * w + ct * 32 + g * 8 + lh * 4) = v;
+      }
+    if ((l % G::LPR) == 0) {
+      mine[BM * 2 * kD + srow] = m_run;
+      mine[BM * 2 * kD + BM + srow] = l_run;
+    }
+    // ---- hand-off.  The parts of a (chain, tile) count themselves in; the one that completes the
+    // count merges.  Two forms, as for the meeting of a chain: when all parts run on one XCD they
+    // share its L2, so a part's stores have arrived once its store counter is at zero and the merging
+    // part reads them at device scope (from the L2); otherwise device-scope release / acquire.  Which
+    // form applies is read from the census word of the (chain, tile), where every part registered
+    // its XCD when the kernel started: P registrations, all in this workgroup's field.  (A part that
+    // looks before everybody has registered takes the general form, which is always safe.)
+    __shared__ int i_merge;
+    __shared__ int split_fast;
+    uint32_t* cnt = sa.psync + 2 * (ch * tiles + i0 / BM);
+    if (tid == 0) {
+      const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | ((4 - 1) << 11)) & 7u;   // XCC_ID
+      split_fast = sa.same_l2_allowed &&
+                   __hip_atomic_load(cnt + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ((uint32_t)P << (3u * xcd));
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const bool fast = split_fast != 0;
+    if (tid == 0) {
+      const uint32_t old = fast ? __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                : __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      i_merge = (old + 1u) % (uint32_t)P == 0u;
+    }
+    __syncthreads();
+    if (!i_merge) continue;              // the merging part signals the chain; this one goes on to the next step
+    // ---- merge: reference = the largest of the parts' references; every part's sums and
+    // accumulators are scaled to it and added in the order of the parts.  All loads are issued
+    // before the first is used: one trip to the L2 for the lot.
+    float* scale_s = Sred;               // [part][slot]
+    float* inv_s = Sred + 4 * BM;        // 1 / row sum
+    const __amdgpu_buffer_rsrc_t parts = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(sa.partials + (int64_t)(ch * tiles + i0 / BM) * P * G::PART_FLOATS), 0, P * G::PART_FLOATS * 4, 0x00020000);
+    constexpr int kIters = BM * (2 * kD / 4) / kThreads;      // (slot, four columns of [K | V]) chunks per thread
+    u32x4 raw[kIters][4];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      const int e = tid + it * kThreads, slot = e / (2 * kD / 4), c4 = e % (2 * kD / 4);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p < P)
+          raw[it][p] = __builtin_amdgcn_raw_buffer_load_b128(parts, (p * G::PART_FLOATS + slot * (2 * kD) + c4 * 4) * 4, 0, kDeviceScope);
+    }
+    if (tid < BM) {
+      float mp[4], lp[4], mstar = -INFINITY;
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p < P) {
+          mp[p] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(parts, (p * G::PART_FLOATS + BM * 2 * kD + tid) * 4, 0, kDeviceScope));
+          lp[p] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(parts, (p * G::PART_FLOATS + BM * 2 * kD + BM + tid) * 4, 0, kDeviceScope));
+        }
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p < P) mstar = fmaxf(mstar, mp[p]);
+      float lsum_all = 0.f;
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p < P) {
+          const float sc = (NORM == 0) ? (mp[p] == -INFINITY ? 0.f : __expf(mp[p] - mstar)) : 1.0f;
+          scale_s[p * BM + tid] = sc;
+          lsum_all += sc * lp[p];
+        }
+      inv_s[tid] = 1.0f / (NORM == 0 ? lsum_all : lsum_all + a.eps);
+    }
+    __syncthreads();
+    uint32_t keep = 0;                     // live protected slots keep their old rows (BM = 32: one mask word)
+    if (PROT && i0 < m) {
+      keep = pwords[i0 >> 5];
+      if (i0 + 32 > m) keep &= (1u << (m - i0)) - 1u;
+    }
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      const int e = tid + it * kThreads, slot = e / (2 * kD / 4), c4 = e % (2 * kD / 4);
+      if (PROT && ((keep >> slot) & 1u)) continue;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p < P) {
+          const float sc = scale_s[p * BM + slot];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[q] = fmaf(sc, __uint_as_float(raw[it][p][q]), acc[q]);
+        }
+      const float inv = inv_s[slot];
+      u32x2 pk;
+      pk[0] = pack_bf16(acc[0] * inv, acc[1] * inv);
+      pk[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
+      uint16_t* dst = (c4 < kD / 4 ? nk : nv) + (int64_t)slot * kD + (c4 % (kD / 4)) * 4;
+      *(u32x2*)dst = pk;
+    }
+    if (PROT && keep) {
+#pragma unroll
+      for (int it = 0; it < 2 * BM * 16 / kThreads; ++it) {
+        const int e = tid + it * kThreads;
+        const int kv = e / (BM * 16), r = (e >> 4) % BM, c16 = e & 15;
+        if ((keep >> r) & 1u) {
+          const int off = (i0 + r) * (kD * 2) + c16 * 16;
+          *(u32x4*)((kv ? nv : nk) + (int64_t)r * kD + c16 * 8) =
+              __builtin_amdgcn_raw_buffer_load_b128(kv ? cat_v.cache : cat_k.cache, off, 0, kDeviceScope);
+        }
+      }
+    }
+  } else {
   // ---- normalise by the row sums and store the new cache rows.  A lane holds 4 columns of a
   // slot at a time; the rows are put together in the key-tile area of LDS (free after the last
   // stage) and leave as whole rows, 1 KB of contiguous memory per wave instruction.
   if ((l % G::LPR) == 0) lsum[srow] = l_run;
   __syncthreads();
-  const int64_t out_at = (int64_t)((sa.slot0 + step) % sa.ring) * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
-  uint16_t* nk = (uint16_t*)sa.out_k + out_at;
-  uint16_t* nv = (uint16_t*)sa.out_v + out_at;
   unsigned char* Orows = Xs0;                // [K rows of the tile ; V rows of the tile][XSTRIDE]
   static_assert(2 * BM * G::XSTRIDE <= G::NXBUF * G::XBYTES, "the output rows fit the key-tile area");
   uint32_t keep[G::RT];
@@ -750,6 +899,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       *(u32x4*)dst = *(const u32x4*)(Orows + (kv * BM + r) * G::XSTRIDE + c16 * 16);
     }
   }
+  }  // not split
 
   // ---- the rows are on their way: tell the other tiles of the chain.  (The barrier also keeps
   // the next prologue's LDS stores behind the copy-out above.)
@@ -778,8 +928,9 @@ __global__ void repack_filters_k(const uint16_t* w, uint16_t* wp, int M, int C, 
   }
 }
 
-__global__ void zero_words_k(uint32_t* p, int n) {
+__global__ void zero_words_k(uint32_t* p, int n, uint32_t* p2, int n2) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += gridDim.x * blockDim.x) p2[i] = 0u;
 }
 
 // The instantiation a shape runs on, handed to `f` as compile-time constants (BM, KW, NORM, PROT, MULTI).
@@ -789,11 +940,26 @@ bool use_big_tiles(int batch, int Hkv, int M, int k_width, int n_cu) {
   return k_width == 15 && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
 }
 template <int V> using ic = std::integral_constant<int, V>;
+// Parts the positions of a step are shared out between (1: no split).  Only with 32-slot tiles and
+// one chain per workgroup, as long as the grid still fits the compute units and the cache part of
+// a step alone gives every part four position tiles (with fewer, handing the partial results over
+// costs more than the shorter walk saves: measured on the 3.5 K-token shape, M = 128).  A function of the shape and the device only:
+// every schedule and every block of a scan use the same number, so results do not depend on them.
+int position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
+  if (use_big_tiles(batch, Hkv, M, k_width, n_cu)) return 1;
+  const int64_t grid = (int64_t)batch * Hkv * (M / 32);
+  int p = 1;
+  while (p < 4 && grid * (2 * p) <= n_cu && M / 32 >= 4 * (2 * p)) p *= 2;
+  return p;
+}
 template <class F>
-hipError_t with_instantiation(const StepArgs& t, bool multi, int n_cu, F&& f) {
+hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, int n_cu, F&& f) {
   const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
   auto pick_multi = [&](auto bm, auto kw, auto norm, auto prot) {
-    return multi ? f(bm, kw, norm, prot, ic<1>{}) : f(bm, kw, norm, prot, ic<0>{});
+    if constexpr (decltype(bm)::value == 32) {
+      if (split && !multi) return f(bm, kw, norm, prot, ic<0>{}, ic<1>{});
+    }
+    return multi ? f(bm, kw, norm, prot, ic<1>{}, ic<0>{}) : f(bm, kw, norm, prot, ic<0>{}, ic<0>{});
   };
   auto pick_prot = [&](auto bm, auto kw, auto norm) {
     return t.protect ? pick_multi(bm, kw, norm, ic<1>{}) : pick_multi(bm, kw, norm, ic<0>{});
@@ -806,11 +972,11 @@ hipError_t with_instantiation(const StepArgs& t, bool multi, int n_cu, F&& f) {
   return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
 }
 
-template <int BM, int KW, int NORM, int PROT, int MULTI>
+template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT>
 hipError_t prepare_kernel() {
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<BM, KW>::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -820,14 +986,14 @@ hipError_t prepare_kernel() {
 
 hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
   const bool multi = a.groups < a.st.batch * a.st.Hkv;
-  return with_instantiation(a.st, multi, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu) {
+  return with_instantiation(a.st, multi, a.psplit > 1, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
-    constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value;
-    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI>();
+    constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
+    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT>();
     if (e != hipSuccess) return e;
-    dim3 grid((a.st.M / BM) * a.groups);
+    dim3 grid((a.st.M / BM) * a.groups * (SPLIT ? a.psplit : 1));
     constexpr int kLds = Geo<BM, KW>::LDS;
-    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI>), grid, dim3(kThreads), kLds, s, a, wp,
+    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>), grid, dim3(kThreads), kLds, s, a, wp,
                        wp_head_stride);
     return hipGetLastError();
   });
@@ -862,8 +1028,33 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
-                                hipStream_t s) {
+// [chain counters][status word][per chain: bit mask of the XCDs its workgroups run on][per (chain,
+// 32-slot tile): count of the parts of a split step that have handed in their result, census of the
+// XCDs the parts run on (3 bits per XCD)]
+size_t compress_scan_sync_bytes(int batch, int Hkv, int M) {
+  return ((size_t)batch * Hkv * (2 + 2 * (M / 32)) + 1) * sizeof(uint32_t);
+}
+static uint32_t* psync_of(void* sync_ws, int batch, int Hkv) { return (uint32_t*)sync_ws + 2 * batch * Hkv + 1; }
+
+int compress_position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
+  return position_split(batch, Hkv, M, k_width, n_cu);
+}
+// room for every part's result of one step: [chain][tile][part] x (32 x 2 d accumulators + 32 references + 32 sums)
+size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int n_cu) {
+  const int p = position_split(batch, Hkv, M, k_width, n_cu);
+  return p > 1 ? (size_t)batch * Hkv * (M / 32) * p * Geo<32, 15>::PART_FLOATS * sizeof(float) : 0;
+}
+
+hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, int M, bool keep_status, hipStream_t s) {
+  const int chains = batch * Hkv;
+  // everything, or the chain counters and the part counters only
+  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws, keep_status ? chains : 2 * chains + 1,
+                     psync_of(sync_ws, batch, Hkv), 2 * chains * (M / 32));
+  return hipGetLastError();
+}
+
+hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
+                                void* partials, hipStream_t s) {
   ScanArgs sa;
   sa.st = a;
   sa.n_steps = 1;
@@ -877,11 +1068,21 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.sync = nullptr;
   sa.status = nullptr;
   sa.spin_limit = 0;
-  sa.same_l2_allowed = 0;
+  sa.same_l2_allowed = debug_options().chain_sync_device ? 0 : 1;   // (only the hand-off of a split step looks at it here)
   // more (chain, tile) pairs than compute units: one resident workgroup per compute unit, each
   // taking several chains on one load of its filter slice (nothing to wait for within one step)
   sa.groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
   if (sa.groups <= 0) sa.groups = a.batch * a.Hkv;
+  // fewer than half as many: the positions of the step are shared out between several workgroups,
+  // whose count per (chain, tile) starts at zero
+  sa.psplit = sa.groups < a.batch * a.Hkv ? 1 : position_split(a.batch, a.Hkv, a.M, a.k_width, n_cu);
+  sa.partials = (float*)partials;
+  sa.psync = psync_of(sync_ws, a.batch, a.Hkv);
+  if (sa.psplit > 1) {
+    hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, sa.psync, 2 * a.batch * a.Hkv * (a.M / 32), sa.psync, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
   return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
@@ -893,14 +1094,16 @@ int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu) {
 int compress_scan_max_resident(const StepArgs& a, int n_cu) {
   if (debug_options().max_resident > 0) return (int)debug_options().max_resident;
   const int groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
+  const bool multi = groups < a.batch * a.Hkv;
+  const bool split = !multi && position_split(a.batch, a.Hkv, a.M, a.k_width, n_cu) > 1;
   int per_cu = 0;
-  hipError_t e = with_instantiation(a, groups < a.batch * a.Hkv, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu) {
+  hipError_t e = with_instantiation(a, multi, split, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
-    constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value;
-    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI>();
+    constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
+    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT>();
     if (e2 != hipSuccess) return e2;
     constexpr int kLds = Geo<BM, KW>::LDS;
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI>,
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>,
                                                         kThreads, kLds);
   });
   if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
@@ -922,26 +1125,18 @@ int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, 
   return g;
 }
 
-// [chain counters][status word][per chain: bit mask of the XCDs its slot tiles run on]
-size_t compress_scan_sync_bytes(int batch, int Hkv) {
-  return (2 * (size_t)batch * Hkv + 1) * sizeof(uint32_t);
-}
-
-hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, bool keep_status, hipStream_t s) {
-  hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, (uint32_t*)sync_ws,
-                     keep_status ? batch * Hkv : 2 * batch * Hkv + 1);
-  return hipGetLastError();
-}
-
 hipError_t launch_compress_scan(const ScanArgs& a_in, const void* wp, int banks, int n_cu,
-                                void* sync_ws, hipStream_t s) {
+                                void* sync_ws, void* partials, hipStream_t s) {
   ScanArgs a = a_in;
   const int chains = a.st.batch * a.st.Hkv;
   a.sync = (uint32_t*)sync_ws;
   a.status = (int32_t*)sync_ws + chains;
   a.groups = compress_scan_groups(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width,
                                   a.st.w_head_stride != 0 || a.st.b_head_stride != 0, n_cu);
-  if (a.groups <= 0) return hipErrorInvalidValue;   // scan_in_one_launch() keeps such shapes away
+  if (a.groups <= 0) return hipErrorInvalidValue;   // the caller keeps such shapes away
+  a.psplit = a.groups < chains ? 1 : position_split(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width, n_cu);
+  a.partials = (float*)partials;
+  a.psync = psync_of(sync_ws, a.st.batch, a.st.Hkv);
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD : 0;
   return dispatch(a, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }

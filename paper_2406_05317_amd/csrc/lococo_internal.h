@@ -73,6 +73,9 @@ struct ScanArgs {
   int32_t spin_limit;
   int32_t same_l2_allowed;   // 0: always meet with device-scope release / acquire (see compress_mfma.hip)
   int32_t groups;            // workgroups per slot tile; group g runs chains g, g + groups, ... (filled in by the launcher)
+  int32_t psplit;            // workgroups that share out the positions of a step of one (chain, slot tile); 1 = no split (launcher)
+  float* partials;           // where the parts of a split step leave their results (launcher)
+  uint32_t* psync;           // per (chain, 32-slot tile): parts that have handed in (launcher)
 };
 
 // Arguments of the MFMA attention kernel: one block, or every block of a scan
@@ -157,8 +160,12 @@ size_t compress_mfma_filter_bytes(int M, int conv_width, int banks);
 // conv_w [M][C][k] (+ w_head_stride per bank) -> wp [bank][M][k][C]
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s);
 // Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
-hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu,
-                                hipStream_t s);
+// sync_ws / partials: compress_scan_sync_bytes() / compress_partials_bytes() of device memory
+hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
+                                void* partials, hipStream_t s);
+// workgroups per (chain, slot tile) that share out the positions of a step (1: no split)
+int compress_position_split(int batch, int Hkv, int M, int k_width, int n_cu);
+size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int n_cu);
 // Workgroups per slot tile with which all steps of a scan run in one launch, every workgroup
 // resident at once (each takes every groups-th chain); 0 if there is no such number.  per_head:
 // filters or biases differ between kv heads.
@@ -170,14 +177,14 @@ int compress_scan_max_resident(const StepArgs& a, int n_cu);
 // cache slots per workgroup of the fused kernel for this shape on a device with n_cu compute units
 int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu);
 // bytes of the sync counters + status word the scan launch needs
-size_t compress_scan_sync_bytes(int batch, int Hkv);
+size_t compress_scan_sync_bytes(int batch, int Hkv, int M);
 // zero them (a fill kernel, so the call may sit inside a captured graph); keep_status: only the chain
 // counters, not the status word (between the launches of one call)
-hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, bool keep_status, hipStream_t s);
+hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, int M, bool keep_status, hipStream_t s);
 // the same kernel over n_steps consecutive compress steps (see ScanArgs); `sync_ws` is
 // compress_scan_sync_bytes() of device memory, cleared beforehand
 hipError_t launch_compress_scan(const ScanArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
-                                hipStream_t s);
+                                void* partials, hipStream_t s);
 
 
 // ---- attention on MFMA (attn_mfma.hip)

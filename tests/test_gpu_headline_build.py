@@ -39,7 +39,7 @@ def test_64_slot_build_under_peaked_rows(gains, history):
     w = _w(batch=2, n_q_heads=32, n_kv_heads=32, M=256, B=128, L=640, qk_gain=qk, conv_gain=cg)
     cfg = lb.config_for(w, impl=MFMA)
     info = lb.lococo_describe_path(cfg, w.B)
-    assert info["path"] == 1 and info["tile_slots"] == 64, info
+    assert info["path"] == 1 and info["tile_slots"] == 64 and info["position_split"] == 1, info
     if history:
         assert info["scan_groups"] == w.batch * w.n_kv_heads, info      # one launch, one chain per workgroup
     q, k, v = inputs.qkv(w)
@@ -195,3 +195,82 @@ def test_one_hot_logits_select_tokens_bit_exactly_on_the_mfma_kernel(shape):
     torch.cuda.synchronize()
     cat_k, cat_v = torch.cat([before_k, blk_k], 2), torch.cat([before_v, blk_v], 2)
     assert torch.equal(cache.k, cat_k[:, :, perm]) and torch.equal(cache.v, cat_v[:, :, perm])
+
+
+@pytest.mark.parametrize("name,split", [("cfg2", 1), ("cfg5", 2), ("cfg3", 1), ("cfg4", 1)])
+def test_which_shapes_split_the_positions_of_a_step(name, split):
+    """The GQA workload (16 chains x 8 slot tiles) leaves half of the compute units without a (chain,
+    slot tile) pair: two workgroups share out the positions of every step.  The 3.5 K-token shape
+    (M = 128: four position tiles of cache) is too short for the hand-over to pay."""
+    w = inputs.CONFIGS[name]
+    info = lb.lococo_describe_path(lb.config_for(w), w.B)
+    assert info["position_split"] == split, info
+    if info["compute_units"] == 256:
+        assert info["scan_groups"] > 0, info
+
+
+@pytest.mark.parametrize("case", [
+    dict(M=256, B=256, L=1280, n_q_heads=8, n_kv_heads=4, batch=2),                      # cfg5-shaped, cut down: two parts
+    dict(M=512, B=512, L=2048, n_q_heads=2, n_kv_heads=2),                               # four parts
+    dict(M=256, B=200, L=1100, n_q_heads=4, n_kv_heads=4, qk_gain=6.0, conv_gain=4.0),   # peaked rows, ragged blocks, T = 456
+    dict(M=256, B=96, L=800, n_q_heads=4, n_kv_heads=2),                                 # partly filled cache at the first compress
+    dict(M=256, B=40, L=600, n_q_heads=4, n_kv_heads=2),                                 # short blocks: the last part nearly empty
+    dict(M=256, B=128, L=896, norm=1, bias_sigma=0.5),                                   # relu-sum
+    dict(M=256, B=128, L=896, conv_width=21, per_head_filters=True, bias_sigma=0.5),     # width 21, per-head banks
+    dict(M=256, B=128, L=896, protect_share=0.15),                                       # protected slots
+    dict(M=512, B=300, L=1500, norm=1, conv_width=21, protect_share=0.1, bias_sigma=0.3, n_q_heads=2, n_kv_heads=2),
+])
+def test_split_steps_match_the_oracle_and_every_schedule(case, options):
+    """Shapes whose (chain, slot tile) pairs leave compute units idle share out the positions of a step
+    between several workgroups, which leave partial results in the workspace for the last of them to
+    merge.  Equal to the oracle; bit-identical between one launch per scan, one launch per step, block
+    by block through lococo_segment_step, and either form of the hand-off."""
+    case = dict(case)
+    share = case.pop("protect_share", 0.0)
+    w = _w(**case)
+    cfg = lb.config_for(w, impl=MFMA)
+    info = lb.lococo_describe_path(cfg, w.B)
+    assert info["position_split"] > 1 and info["tile_slots"] == 32, info
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    protect = (np.random.default_rng(5).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=False, protect=protect)
+    c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, step_by_step=True, protect=protect)
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 1)
+    d = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    e = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=False, protect=protect)
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 0)
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 1)
+    f = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=3, protect=protect)
+    for other in (b, c, d, e, f):
+        for x, y in zip(a[:3], other[:3]):
+            assert torch.equal(x, y)
+        assert a[3:] == other[3:]
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    errs = compare_scan(w, a, want, what="split steps")
+    print(case, info["position_split"], {k_: (f"{e_[0]:.2e}", f"{e_[1]:.2e}") for k_, e_ in errs.items()})
+
+
+def test_split_generation_steps():
+    """B = 1 on a shape that splits: T = M + 1, the last part holds the new token's tile."""
+    w = _w(M=512, B=128, L=512 + 10, n_q_heads=4, n_kv_heads=2)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    cfg = lb.config_for(w, impl=MFMA)
+    assert lb.lococo_describe_path(cfg, 1)["position_split"] > 1
+    sl = lambda t, a_, b_: t[:, :, a_:b_]
+    P = 512
+    o1, ck, cv, ln = oracle_forward(w, sl(q, 0, P), sl(k, 0, P), sl(v, 0, P), cw, cb, nthreads=16)
+    o2, ck, cv, ln = oracle_forward(w, sl(q, P, w.L), sl(k, P, w.L), sl(v, P, w.L), cw, cb, B=1, cache=(ck, cv, ln), nthreads=16)
+    want = (np.concatenate([o1, o2], 2), ck, cv, ln)
+    qd, kd, vd, cwd, cbd = (t.cuda() for t in (q, k, v, cw, cb))
+    od = torch.full_like(qd, float("nan"))
+    cache = lb.Cache(cfg)
+    lb.lococo_sequence_forward(cfg, sl(qd, 0, P), sl(kd, 0, P), sl(vd, 0, P), sl(od, 0, P), cwd, cbd, cache, w.B,
+                               lb.workspace(cfg, P, w.B, True))
+    ws1 = lb.workspace(cfg, 1, 1, False)
+    for t in range(P, w.L):
+        lb.lococo_segment_step(cfg, sl(qd, t, t + 1), sl(kd, t, t + 1), sl(vd, t, t + 1), sl(od, t, t + 1), cwd, cbd, cache, ws1)
+    torch.cuda.synchronize()
+    compare_scan(w, (od.cpu(), cache.k.cpu(), cache.v.cpu(), cache.len, cache.cur), want, what="split decode")
