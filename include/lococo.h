@@ -270,10 +270,8 @@ enum {
                                        on one XCD)                                                             */
   LOCOCO_OPT_LOGITS_TILES = 4,      /* 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused
                                        MFMA path (0 = chosen from the grid size; 256 needs more than 128 slots) */
-  LOCOCO_OPT_MAX_RESIDENT = 5,      /* > 0: pretend the device holds only this many workgroups of the scan
+  LOCOCO_OPT_MAX_RESIDENT = 5       /* > 0: pretend the device holds only this many workgroups of the scan
                                        kernel at once (exercises the fall-back to one launch per step)         */
-  LOCOCO_OPT_TWO_ARRAYS = 6         /* 1: the one-launch scan reads the cache rows and the block rows of a step
-                                       as two arrays even where it would keep them as one                      */
 };
 LOCOCO_API lococo_status lococo_debug_option(int32_t option, int64_t value);
 

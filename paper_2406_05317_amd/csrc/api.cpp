@@ -20,7 +20,7 @@ using namespace lococo;
 static __device__ __align__(256) unsigned char scratch[LOCOCO_NOALLOC_SCRATCH_BYTES];
 
 namespace {
-DebugOptions g_debug = {0, 0, 0, 0, 0, 0};
+DebugOptions g_debug = {0, 0, 0, 0, 0};
 }
 namespace lococo {
 const DebugOptions& debug_options() { return g_debug; }
@@ -62,11 +62,11 @@ lococo_status hip_fail(hipError_t e, const char* what) {
 // ---- optional per-kernel timing with HIP events (lococo_timing_begin / _end)
 enum KernelId { K_ATTN_GENERIC, K_FILL, K_CONV_GENERIC, K_NORM_GENERIC, K_MIX_GENERIC,
                 K_REPACK, K_COMPRESS_MFMA, K_ATTN_MFMA, K_ATTN_DECODE, K_ATTN_COLSUM, K_CONV_MFMA, K_MIX_MFMA,
-                K_GATHER, K_COUNT };
+                K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"attn_generic", "fill", "conv_logits_generic",
                                            "normalise_generic", "mix_generic", "repack_filters",
                                            "compress_mfma", "attn_mfma", "attn_decode", "attn_colsum",
-                                           "conv_logits_mfma", "mix_mfma", "gather_rows"};
+                                           "conv_logits_mfma", "mix_mfma"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
@@ -248,23 +248,17 @@ void* partials_of(const lococo_config* c, void* ws, int32_t B) {
   return (char*)ws + filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B);
 }
 
-// A history slot holds one cache state per chain; on the fused path each chain has room for B more rows
-// behind its M slots, where the scan kernel puts the keys / values of the block the NEXT step adds, so that
-// step reads [cache ; block] as one array.
-int64_t slot_rows(const lococo_config* c, Path path, int32_t B) { return path == PATH_MFMA ? (int64_t)c->M + B : c->M; }
-size_t slot_bytes(const lococo_config* c, Path path, int32_t B) {
-  return align_up((size_t)c->batch * c->n_kv_heads * (size_t)slot_rows(c, path, B) * c->head_dim * esize(c->dtype), 256);
+// Bytes of one history slot pair member: one cache state [chains, M, d].
+size_t state_bytes(const lococo_config* c) {
+  return (size_t)c->batch * c->n_kv_heads * c->M * c->head_dim * esize(c->dtype);
 }
 
-// Workspace of the batched-attention schedule: the step workspace followed by the row statistics of
-// `rows` query rows and K and V history slots for n_slots cache states.
-// Layout: [step workspace][row statistics][K history][V history].
-size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_slots, int64_t rows) {
-  return step_ws_bytes(c, path, B) + stats_bytes(c, rows) + 2 * (size_t)n_slots * slot_bytes(c, path, B);
+// Workspace of the batched-attention schedule: the step workspace followed by
+// K and V history slots for n_compress cache states.
+// Layout: [step workspace][row statistics of the sequence][K history][V history].
+size_t history_ws_bytes(const lococo_config* c, Path path, int32_t B, int64_t n_compress, int64_t L) {
+  return step_ws_bytes(c, path, B) + stats_bytes(c, L) + 2 * (size_t)n_compress * align_up(state_bytes(c), 256);
 }
-// slots that hold every state of a scan with n_compress compression steps (the fused path keeps the
-// state the scan starts from in a slot of its own)
-int64_t full_history_slots(Path path, int64_t n_compress) { return n_compress + (path == PATH_MFMA ? 1 : 0); }
 
 // Polls a waiting workgroup makes before it gives up on its chain (each poll sleeps ~128 cycles and
 // reads the counter from the L2: roughly a microsecond, so the default bounds a wait to a few
@@ -584,7 +578,7 @@ const char* lococo_version(void) { return "0.2.0"; }
 
 lococo_status lococo_debug_option(int32_t option, int64_t value) {
   switch (option) {
-    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0, 0}; return LOCOCO_OK;
+    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0}; return LOCOCO_OK;
     case LOCOCO_OPT_SPIN_LIMIT: g_debug.spin_limit = value; return LOCOCO_OK;
     case LOCOCO_OPT_SCAN_PER_STEP: g_debug.scan_per_step = value != 0; return LOCOCO_OK;
     case LOCOCO_OPT_CHAIN_SYNC_DEVICE: g_debug.chain_sync_device = value != 0; return LOCOCO_OK;
@@ -597,7 +591,6 @@ lococo_status lococo_debug_option(int32_t option, int64_t value) {
       if (value < 0) return fail(LOCOCO_EINVAL, "LOCOCO_OPT_MAX_RESIDENT takes a count >= 0");
       g_debug.max_resident = value;
       return LOCOCO_OK;
-    case LOCOCO_OPT_TWO_ARRAYS: g_debug.two_arrays = value != 0; return LOCOCO_OK;
     default: return fail(LOCOCO_EINVAL, "unknown debug option %d", option);
   }
 }
@@ -729,7 +722,7 @@ lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_
   if (history == 0 || path == PATH_GENERIC || n_blocks == 0)
     *out = step_ws_bytes(cfg, path, B);
   else if (history == 1 || history >= n_blocks)
-    *out = history_ws_bytes(cfg, path, B, full_history_slots(path, n_blocks), L);   // every block may compress
+    *out = history_ws_bytes(cfg, path, B, n_blocks, L);             // every block may compress
   else {
     const int64_t g = std::max<int64_t>(history, 2);
     *out = history_ws_bytes(cfg, path, B, g + 1, g * (int64_t)B);   // a window of g blocks: g + 1 states
@@ -848,9 +841,9 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   // independent of the sequence length, as in the step-by-step schedule.
   int64_t window = 0, ring = 0;
   if (path != PATH_GENERIC && any_compress && workspace) {
-    if (ws_bytes >= history_ws_bytes(cfg, path, B, full_history_slots(path, n_compress), L)) {
+    if (ws_bytes >= history_ws_bytes(cfg, path, B, n_compress, L)) {
       window = n;
-      ring = full_history_slots(path, n_compress);
+      ring = n_compress;
     } else {
       for (int64_t g = std::min<int64_t>(n, 4096); g >= 2; --g)
         if (ws_bytes >= history_ws_bytes(cfg, path, B, g + 1, g * (int64_t)B)) { window = g; ring = g + 1; break; }
@@ -858,24 +851,21 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
   }
   if (window > 0) {
     hipStream_t s = (hipStream_t)stream;
-    const size_t slot = slot_bytes(cfg, path, B);
-    const int64_t slot_cs = slot_rows(cfg, path, B) * cfg->head_dim;       // elements between the chains of a slot
+    const size_t slot = align_up(state_bytes(cfg), 256);
     const int64_t window_rows = std::min<int64_t>(L, window * (int64_t)B);
     char* sync_ws = (char*)workspace + filter_ws_bytes(cfg);      // fused path only
     float* win_stats = (float*)((char*)workspace + step_ws_bytes(cfg, path, B));
     char* hist_k = (char*)win_stats + stats_bytes(cfg, window_rows);
     char* hist_v = hist_k + (size_t)ring * slot;
     const int64_t hist_stride = (int64_t)(slot / esize(cfg->dtype));
-    auto slot_k = [&](int64_t c) { return hist_k + (size_t)(((c % ring) + ring) % ring) * slot; };   // state c; -1: the one the scan starts from
-    auto slot_v = [&](int64_t c) { return hist_v + (size_t)(((c % ring) + ring) % ring) * slot; };
-    bool one_launch = false, contig = false;
+    auto slot_k = [&](int64_t c) { return hist_k + (size_t)(c % ring) * slot; };
+    auto slot_v = [&](int64_t c) { return hist_v + (size_t)(c % ring) * slot; };
+    bool one_launch = false;
     if (path == PATH_MFMA) {
       StepArgs probe = make_args(cfg, seq, 0, B, &tmp, conv_w, conv_b, true);
       one_launch = scan_fits_one_launch(cfg, probe);
-      contig = !g_debug.two_arrays && compress_contig_supported(probe, cu_count());
     }
     int64_t c_done = 0;                       // compress steps enqueued so far: state c_done - 1 is the newest
-    bool block_appended = false;              // state c_done - 1 has the next block's rows behind its cache rows
     for (int64_t w0 = 0; w0 < n; w0 += window) {
       const int64_t w1 = std::min<int64_t>(n, w0 + window);
       // the state the window starts from: the caller's live buffer until the first compression
@@ -897,7 +887,6 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         }
         a.cache_k = c_done == 0 ? tmp.k[tmp.cur] : slot_k(c_done - 1);
         a.cache_v = c_done == 0 ? tmp.v[tmp.cur] : slot_v(c_done - 1);
-        a.cache_cs = c_done == 0 ? 0 : slot_cs;
         if (one_launch) {
           // every later block of the window compresses too (the cache stays full): one launch runs
           // them all, the slot tiles of a chain handing the new cache to each other through the ring
@@ -908,18 +897,6 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
           } else {
             if (c_done > 0)              // the counters start every launch at zero; the status word is kept
               HIP_TRY(launch_scan_sync_clear(sync_ws, cfg->batch, cfg->n_kv_heads, cfg->M, true, s), "clearing the scan counters");
-            if (contig) {
-              // [cache ; block] as one array: the launch's first step finds its block behind the cache
-              // rows of the state it starts from -- put there by the previous launch's last step, or here
-              if (c_done == 0 || !block_appended) {
-                KTimer t(K_GATHER, s);
-                HIP_TRY(launch_gather_rows(a, slot_k(c_done - 1), slot_v(c_done - 1), slot_cs, c_done == 0, s),
-                        "putting a block behind the cache rows");
-              }
-              a.cache_k = slot_k(c_done - 1);
-              a.cache_v = slot_v(c_done - 1);
-              a.cache_cs = slot_cs;
-            }
             ScanArgs sa;
             sa.st = a;
             sa.n_steps = (int32_t)(w1 - bi);
@@ -928,10 +905,8 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
             sa.out_k = hist_k;
             sa.out_v = hist_v;
             sa.out_stride = hist_stride;
-            sa.out_cs = slot_cs;
             sa.slot0 = (int32_t)(c_done % ring);
             sa.ring = (int32_t)ring;
-            sa.contig = contig ? 1 : 0;
             sa.sync = nullptr;
             sa.status = nullptr;
             sa.spin_limit = spin_limit();
@@ -943,16 +918,13 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
             }
             if (!capturing) note_scan_launched(s);
             c_done += w1 - bi;
-            block_appended = contig && w1 < n;   // its last step appended the block of the next window's first step
             break;
           }
         }
         a.new_k = slot_k(c_done);
         a.new_v = slot_v(c_done);
-        a.new_cs = path == PATH_MFMA ? slot_cs : 0;
         if ((st = enqueue_compress(cfg, path, a, workspace, B, s))) return st;
         ++c_done;
-        block_appended = false;
       }
       {
         const lococo_seg& first = plan[(size_t)w0];
@@ -960,11 +932,9 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         AttnArgs t = attn_args_one_block(a0);
         t.cache_k = base_k;
         t.cache_v = base_v;
-        t.cache_cs = c0 == 0 ? 0 : slot_cs;
         t.hist_k = hist_k;
         t.hist_v = hist_v;
         t.hist_stride = hist_stride;
-        t.hist_cs = slot_cs;
         t.hist_first = (int32_t)(c0 % ring);
         t.hist_ring = (int32_t)ring;
         t.L = std::min<int64_t>(L - first.start, (w1 - w0) * (int64_t)B);
@@ -985,13 +955,10 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
     }
     const lococo_seg& last = plan.back();
     if (c_done > 0) {
-      // the newest state's cache rows (the first M rows of every chain of its slot) become the caller's cache
-      const size_t row_bytes = (size_t)cfg->M * cfg->head_dim * esize(cfg->dtype);
-      const size_t chains = (size_t)cfg->batch * cfg->n_kv_heads;
-      HIP_TRY(hipMemcpy2DAsync(tmp.k[last.buf_after], row_bytes, slot_k(c_done - 1), (size_t)slot_cs * esize(cfg->dtype),
-                               row_bytes, chains, hipMemcpyDeviceToDevice, s), "publishing the final cache");
-      HIP_TRY(hipMemcpy2DAsync(tmp.v[last.buf_after], row_bytes, slot_v(c_done - 1), (size_t)slot_cs * esize(cfg->dtype),
-                               row_bytes, chains, hipMemcpyDeviceToDevice, s), "publishing the final cache");
+      HIP_TRY(hipMemcpyAsync(tmp.k[last.buf_after], slot_k(c_done - 1), state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+              "publishing the final cache");
+      HIP_TRY(hipMemcpyAsync(tmp.v[last.buf_after], slot_v(c_done - 1), state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+              "publishing the final cache");
     }
     tmp.cur = last.buf_after;
     tmp.len = last.len_after;

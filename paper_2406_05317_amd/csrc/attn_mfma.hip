@@ -138,12 +138,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
   const uint16_t* cache_k;
   const uint16_t* cache_v;
   if (n <= a.n_fill) {
-    const int64_t cs = a.cache_cs ? a.cache_cs : (int64_t)a.M * kD;
-    cache_k = (const uint16_t*)a.cache_k + chain * cs;
-    cache_v = (const uint16_t*)a.cache_v + chain * cs;
+    cache_k = (const uint16_t*)a.cache_k + (int64_t)chain * a.M * kD;
+    cache_v = (const uint16_t*)a.cache_v + (int64_t)chain * a.M * kD;
   } else {
     const int64_t slot = (int64_t)((a.hist_first + n - a.n_fill - 1) % a.hist_ring) * a.hist_stride +
-                         chain * (a.hist_cs ? a.hist_cs : (int64_t)a.M * kD);
+                         (int64_t)chain * a.M * kD;
     cache_k = (const uint16_t*)a.hist_k + slot;
     cache_v = (const uint16_t*)a.hist_v + slot;
   }
@@ -420,9 +419,9 @@ __global__ __launch_bounds__(256) void attn_colsum_k(AttnArgs a, float* colsum) 
   const int m = n <= a.n_fill ? a.len0 + n * a.B : a.M;
   if (j0 >= m) return;
   const uint16_t* cache_k =
-      n <= a.n_fill ? (const uint16_t*)a.cache_k + chain * (a.cache_cs ? a.cache_cs : (int64_t)a.M * kD)
+      n <= a.n_fill ? (const uint16_t*)a.cache_k + (int64_t)chain * a.M * kD
                     : (const uint16_t*)a.hist_k + (int64_t)((a.hist_first + n - a.n_fill - 1) % a.hist_ring) * a.hist_stride +
-                          chain * (a.hist_cs ? a.hist_cs : (int64_t)a.M * kD);
+                          (int64_t)chain * a.M * kD;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
   if (tid < 64) sums[tid] = 0.f;
   __syncthreads();

@@ -151,6 +151,12 @@ struct Cat16 { u32x4 from_cache, from_blk; };
 // one-launch scan they were written by other workgroups a step ago, and every row is read once per
 // workgroup anyway.
 constexpr int kDeviceScope = 1 << 4;
+__device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) {
+  Cat16 r;
+  r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, kDeviceScope);
+  r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
+  return r;
+}
 
 // wp: filters repacked in register order, [bank][M/32][wave][tap][half][lane] x 8 channels: lane l of
 // wave w holds slot (32-slot tile)*32 + l%32, channels 32w + 16*half + 8*(l/32) .. +7, so that every
@@ -166,16 +172,11 @@ constexpr int kDeviceScope = 1 << 4;
 // range of position tiles with the same pipeline and leaves its running reference, row sum and
 // unnormalised accumulators in the workspace; the part that arrives last merges them in a fixed
 // order (so the result does not depend on who is last) and writes the rows.
-// CONTIG = 1: [cache ; block] of every step is ONE array -- the block's rows lie behind the cache rows
-// of the state the step starts from -- so a row is one load instead of two loads and an OR (the
-// stage loop is bound by instruction issue: measured 6 - 7 % of the launch).  A step keeps it that
-// way by appending the next block's rows behind the rows it writes.
-template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT, int CONTIG>
+template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
   static_assert(!SPLIT || (BM == 32 && !MULTI), "the position split is built for 32-slot tiles, one chain per workgroup");
-  static_assert(!CONTIG || (!PROT && !SPLIT), "the one-array form is built without protected slots and without the position split");
   const StepArgs& a = sa.st;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Xs0 = smem;                                    // NXBUF key tiles (with halo)
@@ -185,9 +186,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   float* alphas0 = (float*)(Ps0 + 2 * G::PBYTES);               // 2 x rescale factor per slot
   float* lsum = alphas0 + 2 * BM;                               // final row sums
 
-  // (the wave index as a scalar: everything derived from it stays on the scalar unit, and the
-  // choices between the key and the value side of the mixing are uniform branches)
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l31 = l & 31, lh = l >> 5;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
   // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  The slot tiles of one chain
   // all read the same keys and values, so they are given ids that land on one XCD (one L2).
   int item = blockIdx.x;
@@ -243,7 +242,6 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   const int srow = w * G::RPW + l / G::LPR;
   const int sp0 = (l % G::LPR) * G::EPL;
   float m_run = 0.f, l_run = 0.f;
-  // (a softmax over the positions does not see a per-slot constant: the bias only enters the relu-sum form)
   const float bias =
       a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv0 * a.b_head_stride + i0 + srow] << 16)
                : 0.f;
@@ -251,21 +249,13 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // ---- staging: global -> registers -> LDS (key tile with halo, value tile; both row-major)
   Cat16 xreg[G::XPER];
   Cat16 vreg[G::VPER];
-  // (one array: the `cache` resource spans the cache rows and the block rows behind them, the other half is never touched)
-  auto load_rows = [&](const CatRows& c, int p, int chunk) {
-    Cat16 r;
-    r.from_cache = __builtin_amdgcn_raw_buffer_load_b128(c.cache, p * (kD * 2) + chunk * 16, 0, kDeviceScope);
-    if (!CONTIG) r.from_blk = __builtin_amdgcn_raw_buffer_load_b128(c.blk, (p - c.m) * c.blk_stride + chunk * 16, 0, 0);
-    return r;
-  };
-  auto whole = [&](const Cat16& r) { return CONTIG ? r.from_cache : (r.from_cache | r.from_blk); };
   auto load_x = [&](int it, int j0) {
     const int item = tid + it * kThreads;
-    xreg[it] = load_rows(cat_k, j0 - G::PAD + (item >> 4), item & 15);
+    xreg[it] = load_cat16(cat_k, j0 - G::PAD + (item >> 4), item & 15);
   };
   auto load_v = [&](int it, int j0) {
     const int item = tid + it * kThreads;
-    vreg[it] = load_rows(cat_v, j0 + (item >> 4), item & 15);
+    vreg[it] = load_cat16(cat_v, j0 + (item >> 4), item & 15);
   };
   // the two halves of a chunk's fetch on their own, for stages that give each a slot of its own
   auto load_half = [&](Cat16& r, const CatRows& c, int p, int chunk, bool blk) {
@@ -275,12 +265,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   auto store_x = [&](int it, int j0, unsigned char* Xs) {
     const int item = tid + it * kThreads;
     (void)j0;
-    *(u32x4*)(Xs + (item >> 4) * G::XSTRIDE + (item & 15) * 16) = whole(xreg[it]);
+    *(u32x4*)(Xs + (item >> 4) * G::XSTRIDE + (item & 15) * 16) = xreg[it].from_cache | xreg[it].from_blk;
   };
   auto store_v = [&](int it, int j0, unsigned char* Vs) {
     const int item = tid + it * kThreads;
     (void)j0;
-    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = whole(vreg[it]);
+    *(u32x4*)(Vs + (item >> 4) * G::VSTRIDE + (item & 15) * 16) = vreg[it].from_cache | vreg[it].from_blk;
   };
 
   // Ring of key operands of the logit MFMAs, fetched kRing-1 contraction steps ahead.  kRing
@@ -366,8 +356,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     auto sm_add = [&](int ww0, int e4) {      // 4 positions: + partials ww0 and ww0+1
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        sv[e4 * 4 + e] = ww0 == 0 ? (NORM == 0 ? part[0][e4][e] + part[1][e4][e] : bias + part[0][e4][e] + part[1][e4][e])
-                                  : sv[e4 * 4 + e] + part[ww0][e4][e] + part[ww0 + 1][e4][e];
+        sv[e4 * 4 + e] = (ww0 == 0 ? bias : sv[e4 * 4 + e]) + part[ww0][e4][e] + part[ww0 + 1][e4][e];
     };
     auto sm_exp = [&](int e) {
       sv[e] = NORM == 0 ? __builtin_amdgcn_exp2f(fmaf(sv[e], kLog2e, -mc)) : fmaxf(sv[e], 0.f);
@@ -418,13 +407,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         // With 60 slots in a stage the 15 pieces (LDS store, cache-side fetch, block-side fetch of each
         // chunk) get a slot each, in the slots the softmax leaves free at the end of the stage: one LDS
         // store or one load fits the shadow of an MFMA, a store and two loads together do not.
-        constexpr int kKinds = CONTIG ? 2 : 3;           // LDS store, fetch (one array) or cache-side and block-side fetch
-        constexpr int kPieces = kKinds * (G::XPER + G::VPER);
-        constexpr bool kSpread = kSlots - 3 * (G::XPER + G::VPER) - 1 >= kSlots * 3 / 5 + 8;   // behind the softmax and the mixing fetches
+        constexpr int kPieces = 3 * (G::XPER + G::VPER);
+        constexpr bool kSpread = kSlots - kPieces - 1 >= kSlots * 3 / 5 + 8;   // behind the softmax and the mixing fetches
         if (kSpread) {
           constexpr int Z0 = kSlots - kPieces - 1;
           if (slot >= Z0 && slot < Z0 + kPieces) {
-            const int piece = slot - Z0, it = piece / kKinds, what = piece % kKinds;
+            const int piece = slot - Z0, it = piece / 3, what = piece % 3;
             if (it < G::XPER) {
               const int item = tid + it * kThreads, jn = j0 + 4 * BN;
               if (what == 0) store_x(it, j0 + 3 * BN, Xstage);
@@ -689,11 +677,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     const int64_t prev = (int64_t)((sa.slot0 + step - 1) % sa.ring) * sa.out_stride;   // (unused for step 0)
     const uint16_t* src_k = step == 0 ? (const uint16_t*)a.cache_k : (const uint16_t*)sa.out_k + prev;
     const uint16_t* src_v = step == 0 ? (const uint16_t*)a.cache_v : (const uint16_t*)sa.out_v + prev;
-    const int64_t src_cs = step == 0 ? (a.cache_cs ? a.cache_cs : (int64_t)a.M * kD) : sa.out_cs;
-    // (one array: the "cache" rows are all T rows and there is no block side)
-    cat_k = make_cat(src_k + (int64_t)ch * src_cs, CONTIG ? T : m,
+    cat_k = make_cat(src_k + (int64_t)ch * a.M * kD, m,
                      (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + tok * a.k.st, a.k.st, Bn);
-    cat_v = make_cat(src_v + (int64_t)ch * src_cs, CONTIG ? T : m,
+    cat_v = make_cat(src_v + (int64_t)ch * a.M * kD, m,
                      (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + tok * a.v.st, a.v.st, Bn);
   }
 #pragma unroll
@@ -717,7 +703,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
 #pragma unroll
       for (int it = 0; it < G::XPER; ++it) {
         const int item = tid + it * kThreads;
-        xpro[t][it] = load_rows(cat_k, jb + t * BN - G::PAD + (item >> 4), item & 15);
+        xpro[t][it] = load_cat16(cat_k, jb + t * BN - G::PAD + (item >> 4), item & 15);
       }
 #pragma unroll
     for (int it = 0; it < G::XPER; ++it) load_x(it, jb + 3 * BN);
@@ -728,7 +714,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
 #pragma unroll
       for (int it = 0; it < G::XPER; ++it) {
         const int item = tid + it * kThreads;
-        *(u32x4*)(Xs0 + t * G::XBYTES + (item >> 4) * G::XSTRIDE + (item & 15) * 16) = whole(xpro[t][it]);
+        *(u32x4*)(Xs0 + t * G::XBYTES + (item >> 4) * G::XSTRIDE + (item & 15) * 16) =
+            xpro[t][it].from_cache | xpro[t][it].from_blk;
       }
   }
   __syncthreads();
@@ -750,41 +737,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   uint16_t* nk;
   uint16_t* nv;
   {
-    const int64_t out_at = (int64_t)((sa.slot0 + step) % sa.ring) * sa.out_stride + (int64_t)ch * sa.out_cs + (int64_t)i0 * kD;
+    const int64_t out_at = (int64_t)((sa.slot0 + step) % sa.ring) * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
     nk = (uint16_t*)sa.out_k + out_at;
     nv = (uint16_t*)sa.out_v + out_at;
-  }
-  if constexpr (CONTIG) {
-    // ---- the next block's rows go behind the rows this step writes (rows M .. of the chain's
-    // state), shared out between the slot tiles of the chain; fetched here so that they arrive
-    // while the new rows are put together
-    const int64_t tok_next = (int64_t)(step + 1) * sa.B, left = sa.tokens_left - tok_next;
-    if (left > 0) {
-      const int Bn2 = (int)(left < sa.B ? left : sa.B), b = ch / a.Hkv, hkv = ch % a.Hkv;
-      const uint16_t* bk = (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + tok_next * a.k.st;
-      const uint16_t* bv = (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + tok_next * a.v.st;
-      uint16_t* dk = nk + (int64_t)(a.M - i0) * kD;
-      uint16_t* dv = nv + (int64_t)(a.M - i0) * kD;
-      for (int e0 = (i0 / BM) * kThreads; e0 < Bn2 * 16; e0 += 4 * tiles * kThreads) {
-        u32x4 rk[4], rv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int e = e0 + u * tiles * kThreads + tid;
-          if (e < Bn2 * 16) {
-            rk[u] = *(const u32x4*)(bk + (int64_t)(e >> 4) * a.k.st + (e & 15) * 8);
-            rv[u] = *(const u32x4*)(bv + (int64_t)(e >> 4) * a.v.st + (e & 15) * 8);
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int e = e0 + u * tiles * kThreads + tid;
-          if (e < Bn2 * 16) {
-            *(u32x4*)(dk + (int64_t)(e >> 4) * kD + (e & 15) * 8) = rk[u];
-            *(u32x4*)(dv + (int64_t)(e >> 4) * kD + (e & 15) * 8) = rv[u];
-          }
-        }
-      }
-    }
   }
   if constexpr (SPLIT) {
     // ---- this part's result goes to the workspace: accumulators [slot][2 d] as they are
@@ -997,19 +952,14 @@ int position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
   while (p < 4 && grid * (2 * p) <= n_cu && M / 32 >= 4 * (2 * p)) p *= 2;
   return p;
 }
-// one array per step only for the shapes the measured workloads run on: width 15, no protected slots, no position split
-bool contig_built_for(const StepArgs& t, bool split) { return t.k_width == 15 && !t.protect && !split; }
 template <class F>
-hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, bool contig, int n_cu, F&& f) {
+hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, int n_cu, F&& f) {
   const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
   auto pick_multi = [&](auto bm, auto kw, auto norm, auto prot) {
     if constexpr (decltype(bm)::value == 32) {
-      if (split && !multi) return f(bm, kw, norm, prot, ic<0>{}, ic<1>{}, ic<0>{});
+      if (split && !multi) return f(bm, kw, norm, prot, ic<0>{}, ic<1>{});
     }
-    if constexpr (decltype(kw)::value == 15 && decltype(prot)::value == 0) {
-      if (contig) return multi ? f(bm, kw, norm, prot, ic<1>{}, ic<0>{}, ic<1>{}) : f(bm, kw, norm, prot, ic<0>{}, ic<0>{}, ic<1>{});
-    }
-    return multi ? f(bm, kw, norm, prot, ic<1>{}, ic<0>{}, ic<0>{}) : f(bm, kw, norm, prot, ic<0>{}, ic<0>{}, ic<0>{});
+    return multi ? f(bm, kw, norm, prot, ic<1>{}, ic<0>{}) : f(bm, kw, norm, prot, ic<0>{}, ic<0>{});
   };
   auto pick_prot = [&](auto bm, auto kw, auto norm) {
     return t.protect ? pick_multi(bm, kw, norm, ic<1>{}) : pick_multi(bm, kw, norm, ic<0>{});
@@ -1022,11 +972,11 @@ hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, bool co
   return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
 }
 
-template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT, int CONTIG>
+template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT>
 hipError_t prepare_kernel() {
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT, CONTIG>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<BM, KW>::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -1036,41 +986,17 @@ hipError_t prepare_kernel() {
 
 hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
   const bool multi = a.groups < a.st.batch * a.st.Hkv;
-  if (a.contig && !contig_built_for(a.st, a.psplit > 1)) return hipErrorInvalidValue;   // the caller asks compress_contig_supported() first
-  return with_instantiation(a.st, multi, a.psplit > 1, a.contig != 0, n_cu,
-                            [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ct) {
+  return with_instantiation(a.st, multi, a.psplit > 1, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
     constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
-    constexpr int CONTIG = decltype(ct)::value;
-    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT, CONTIG>();
+    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT>();
     if (e != hipSuccess) return e;
     dim3 grid((a.st.M / BM) * a.groups * (SPLIT ? a.psplit : 1));
     constexpr int kLds = Geo<BM, KW>::LDS;
-    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT, CONTIG>), grid, dim3(kThreads), kLds, s, a, wp,
+    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>), grid, dim3(kThreads), kLds, s, a, wp,
                        wp_head_stride);
     return hipGetLastError();
   });
-}
-
-// [cache rows ; block rows] of every chain as one array (see ScanArgs.contig); one thread per 16-byte chunk
-__global__ void gather_rows_k(StepArgs a, uint16_t* dst_k, uint16_t* dst_v, int64_t dst_cs, int copy_cache) {
-  const int ch = blockIdx.y, b = ch / a.Hkv, hkv = ch % a.Hkv;
-  const int64_t src_cs = a.cache_cs ? a.cache_cs : (int64_t)a.M * kD;
-  const int first = copy_cache ? 0 : a.m * 16, total = (a.m + a.Bn) * 16;
-  for (int e = first + blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
-    const int r = e >> 4, c = (e & 15) * 8;
-    const uint16_t* sk;
-    const uint16_t* sv;
-    if (r < a.m) {
-      sk = (const uint16_t*)a.cache_k + ch * src_cs + (int64_t)r * kD + c;
-      sv = (const uint16_t*)a.cache_v + ch * src_cs + (int64_t)r * kD + c;
-    } else {
-      sk = (const uint16_t*)a.k.p + b * a.k.sb + hkv * a.k.sh + (int64_t)(r - a.m) * a.k.st + c;
-      sv = (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + (int64_t)(r - a.m) * a.v.st + c;
-    }
-    *(u32x4*)(dst_k + ch * dst_cs + (int64_t)r * kD + c) = *(const u32x4*)sk;
-    *(u32x4*)(dst_v + ch * dst_cs + (int64_t)r * kD + c) = *(const u32x4*)sv;
-  }
 }
 
 }  // namespace
@@ -1113,20 +1039,6 @@ static uint32_t* psync_of(void* sync_ws, int batch, int Hkv) { return (uint32_t*
 int compress_position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
   return position_split(batch, Hkv, M, k_width, n_cu);
 }
-
-bool compress_contig_supported(const StepArgs& a, int n_cu) {
-  const int groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
-  const bool split = groups >= a.batch * a.Hkv && position_split(a.batch, a.Hkv, a.M, a.k_width, n_cu) > 1;
-  return contig_built_for(a, split);
-}
-
-hipError_t launch_gather_rows(const StepArgs& a, void* dst_k, void* dst_v, int64_t dst_cs, bool copy_cache, hipStream_t s) {
-  const int chunks = ((copy_cache ? a.m : 0) + a.Bn) * 16;
-  if (chunks <= 0) return hipSuccess;
-  hipLaunchKernelGGL(gather_rows_k, dim3((chunks + 255) / 256 > 64 ? 64 : (chunks + 255) / 256, a.batch * a.Hkv), dim3(256), 0, s,
-                     a, (uint16_t*)dst_k, (uint16_t*)dst_v, dst_cs, copy_cache ? 1 : 0);
-  return hipGetLastError();
-}
 // room for every part's result of one step: [chain][tile][part] x (32 x 2 d accumulators + 32 references + 32 sums)
 size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int n_cu) {
   const int p = position_split(batch, Hkv, M, k_width, n_cu);
@@ -1151,10 +1063,8 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.out_k = a.new_k;
   sa.out_v = a.new_v;
   sa.out_stride = 0;
-  sa.out_cs = a.new_cs ? a.new_cs : (int64_t)a.M * kD;
   sa.slot0 = 0;
   sa.ring = 1;
-  sa.contig = 0;
   sa.sync = nullptr;
   sa.status = nullptr;
   sa.spin_limit = 0;
@@ -1187,16 +1097,14 @@ int compress_scan_max_resident(const StepArgs& a, int n_cu) {
   const bool multi = groups < a.batch * a.Hkv;
   const bool split = !multi && position_split(a.batch, a.Hkv, a.M, a.k_width, n_cu) > 1;
   int per_cu = 0;
-  hipError_t e = with_instantiation(a, multi, split, contig_built_for(a, split), n_cu,
-                                    [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ct) {
+  hipError_t e = with_instantiation(a, multi, split, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
     constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
-    constexpr int CONTIG = decltype(ct)::value;
-    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT, CONTIG>();
+    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT>();
     if (e2 != hipSuccess) return e2;
     constexpr int kLds = Geo<BM, KW>::LDS;
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(
-        &per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT, CONTIG>, kThreads, kLds);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>,
+                                                        kThreads, kLds);
   });
   if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
   return per_cu * n_cu;

@@ -16,7 +16,6 @@ struct DebugOptions {
   int64_t chain_sync_device;  // 1: the slot tiles of a chain always meet with device-scope release / acquire
   int64_t logits_tiles;       // 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused MFMA path
   int64_t max_resident;       // > 0: pretend that only this many workgroups of the scan kernel fit the GPU at once
-  int64_t two_arrays;         // 1: the one-launch scan reads [cache ; block] as two arrays even where it could as one
 };
 const DebugOptions& debug_options();
 // compute units of the current device
@@ -37,7 +36,6 @@ struct StepArgs {
   const void* cache_v;
   void* new_k;             // other buffer [chains, M, d] (compress) / live buffer (fill)
   void* new_v;
-  int64_t cache_cs, new_cs;  // elements between the chains of cache_k/v and of new_k/v; 0 = M * d (fused MFMA kernel only)
   const void* conv_w;      // [M, C, k] (+ w_head_stride per kv head)
   const void* conv_b;      // [M] or null
   int64_t w_head_stride, b_head_stride;
@@ -69,10 +67,7 @@ struct ScanArgs {
   void* out_k;
   void* out_v;
   int64_t out_stride;
-  int64_t out_cs;            // elements between the chains inside a slot (>= M * d; (M + B) * d where blocks are appended)
   int32_t slot0, ring;       // ring >= 1
-  int32_t contig;            // 1: every step finds its block's rows behind the cache rows of its source state (rows
-                             // [m, m + Bn) of each chain) and appends the next block's rows behind the rows it writes
   uint32_t* sync;
   int32_t* status;
   int32_t spin_limit;
@@ -94,11 +89,9 @@ struct AttnArgs {
   View o;
   const void* cache_k;     // base cache [chains, M, d]
   const void* cache_v;
-  int64_t cache_cs;        // elements between the chains of the base cache; 0 = M * d
   const void* hist_k;      // history slots, hist_stride elements apart (may be null if unused)
   const void* hist_v;
   int64_t hist_stride;
-  int64_t hist_cs;                 // elements between the chains inside a history slot; 0 = M * d
   int32_t hist_first, hist_ring;   // hist_ring >= 1 whenever hist_k is used
   int64_t L;
   int32_t B, M, len0, n_fill, seg_first, n_seg;
@@ -170,11 +163,6 @@ hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStre
 // sync_ws / partials: compress_scan_sync_bytes() / compress_partials_bytes() of device memory
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
                                 void* partials, hipStream_t s);
-// Whether the one-launch scan of this shape can read [cache ; block] as one array (see ScanArgs.contig).
-bool compress_contig_supported(const StepArgs& a, int n_cu);
-// [cache rows ; block rows] of every chain into dst (chains dst_cs elements apart): the a.m live cache rows
-// (skipped when copy_cache is false: they are there already) followed by the a.Bn rows of the block
-hipError_t launch_gather_rows(const StepArgs& a, void* dst_k, void* dst_v, int64_t dst_cs, bool copy_cache, hipStream_t s);
 // workgroups per (chain, slot tile) that share out the positions of a step (1: no split)
 int compress_position_split(int batch, int Hkv, int M, int k_width, int n_cu);
 size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int n_cu);

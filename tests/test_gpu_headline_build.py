@@ -274,37 +274,3 @@ def test_split_generation_steps():
         lb.lococo_segment_step(cfg, sl(qd, t, t + 1), sl(kd, t, t + 1), sl(vd, t, t + 1), sl(od, t, t + 1), cwd, cbd, cache, ws1)
     torch.cuda.synchronize()
     compare_scan(w, (od.cpu(), cache.k.cpu(), cache.v.cpu(), cache.len, cache.cur), want, what="split decode")
-
-
-@pytest.mark.parametrize("case", [
-    dict(batch=2, n_q_heads=32, n_kv_heads=32, M=256, B=128, L=1024),             # 64-slot tiles, one chain per workgroup
-    dict(batch=2, n_q_heads=32, n_kv_heads=32, M=256, B=128, L=1000, window=3),   # windows: the block of the next window is appended by the last step
-    dict(M=128, B=96, L=1000, n_q_heads=4, n_kv_heads=2, batch=2),                # partly filled cache at the first compress, ragged blocks
-    dict(M=128, B=160, L=800),                                                    # block larger than the cache
-    dict(batch=12, n_q_heads=8, n_kv_heads=8, M=128, B=64, L=640, window=4),      # several chains per workgroup, two fills
-    dict(M=128, B=128, L=900, norm=1, bias_sigma=0.5, window=2),                  # relu-sum
-    dict(M=128, B=128, L=2 * 128 + 1),                                            # a last block of one token
-])
-def test_one_array_scan_equals_the_two_array_scan(case, options):
-    """In the one-launch scan every step reads [cache ; block] as one array: its block's rows lie behind
-    the cache rows of the state it starts from (gathered there for the first step, appended by the
-    step before for the others).  Same bits as reading the two arrays separately, and the oracle's result."""
-    case = dict(case)
-    G = case.pop("window", True)
-    w = _w(**case)
-    q, k, v = inputs.qkv(w)
-    cw, cb = inputs.conv_filters(w)
-    lb.lococo_timing_begin()
-    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=G)
-    ran = lb.lococo_timing_end()
-    assert "gather_rows" in ran, ran
-    options(lb.LOCOCO_OPT_TWO_ARRAYS, 1)
-    lb.lococo_timing_begin()
-    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=G)
-    ran = lb.lococo_timing_end()
-    assert "gather_rows" not in ran, ran
-    for x, y in zip(a[:3], b[:3]):
-        assert torch.equal(x, y)
-    assert a[3:] == b[3:]
-    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
-    compare_scan(w, a, want, what="one-array scan")
