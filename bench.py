@@ -304,6 +304,8 @@ def main():
     ap.add_argument("--sustain-seconds", type=float, default=2.0,
                     help="after the timed steps, run sequences back to back for at least this long and report the "
                          "steady-state rate (the chip is power-limited under matrix load; 0 = skip)")
+    ap.add_argument("--debug-option", action="append", default=[], metavar="N=V",
+                    help="set the library's test / measurement hook number N to V (lococo_debug_option) before the run")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the warm-up, so "
                          "that a rocprofv3 --pmc run has a kernel of known HBM traffic to scale "
@@ -319,6 +321,9 @@ def main():
     from paper_2406_05317_amd import binding as lb
     from paper_2406_05317_amd import inputs
     w = inputs.CONFIGS[args.workload]
+    for kv in args.debug_option:
+        n_, v_ = kv.split("=")
+        lb.lococo_debug_option(int(n_), int(v_))
     if args.conv_width:
         w = w.replace(name=f"{w.name}-k{args.conv_width}", conv_width=args.conv_width)
     if args.norm >= 0:

@@ -186,7 +186,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   float* alphas0 = (float*)(Ps0 + 2 * G::PBYTES);               // 2 x rescale factor per slot
   float* lsum = alphas0 + 2 * BM;                               // final row sums
 
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
+  // (the wave index as a scalar: everything derived from it stays on the scalar unit, and the
+  // choices between the key and the value side of the mixing are uniform branches)
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l31 = l & 31, lh = l >> 5;
   // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  The slot tiles of one chain
   // all read the same keys and values, so they are given ids that land on one XCD (one L2).
   int item = blockIdx.x;
@@ -242,6 +244,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   const int srow = w * G::RPW + l / G::LPR;
   const int sp0 = (l % G::LPR) * G::EPL;
   float m_run = 0.f, l_run = 0.f;
+  // (a softmax over the positions does not see a per-slot constant: the bias only enters the relu-sum form)
   const float bias =
       a.conv_b ? __uint_as_float((uint32_t)((const uint16_t*)a.conv_b)[hkv0 * a.b_head_stride + i0 + srow] << 16)
                : 0.f;
@@ -356,7 +359,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     auto sm_add = [&](int ww0, int e4) {      // 4 positions: + partials ww0 and ww0+1
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        sv[e4 * 4 + e] = (ww0 == 0 ? bias : sv[e4 * 4 + e]) + part[ww0][e4][e] + part[ww0 + 1][e4][e];
+        sv[e4 * 4 + e] = ww0 == 0 ? (NORM == 0 ? part[0][e4][e] + part[1][e4][e] : bias + part[0][e4][e] + part[1][e4][e])
+                                  : sv[e4 * 4 + e] + part[ww0][e4][e] + part[ww0 + 1][e4][e];
     };
     auto sm_exp = [&](int e) {
       sv[e] = NORM == 0 ? __builtin_amdgcn_exp2f(fmaf(sv[e], kLog2e, -mc)) : fmaxf(sv[e], 0.f);
