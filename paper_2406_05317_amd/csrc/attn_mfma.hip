@@ -152,7 +152,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
   const uint16_t* qb_ptr = (const uint16_t*)a.q.p + b * a.q.sb + hq * a.q.sh + start * a.q.st;
   uint16_t* ob = (uint16_t*)a.o.p + b * a.o.sb + hq * a.o.sh + start * a.o.st;
 
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l31 = l & 31, lh = l >> 5;
+  // (the wave index as a scalar: the tests on a wave's first query row are uniform branches)
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l31 = l & 31, lh = l >> 5;
   const int wq0 = q0 + 32 * w;          // first query row of this wave
   const int qrow = wq0 + l31;           // this lane's query (block-relative)
 
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
 
   // ---- tile requests.  Instruction `it` of wave w fills the cells of tile rows 16w + 4it .. + 3;
   // lane l: row 16w + 4it + l/16, cell l%16.  Past the last tile the offset is out of range: zeros.
-  const int w_uniform = __builtin_amdgcn_readfirstlane(w);     // the wave index as a scalar: M0 takes no vector register
+  const int w_uniform = w;
   const uint32_t req_row = (uint32_t)(16 * w + (l >> 4));
   const uint32_t req_cell_k = (uint32_t)(((l & 15) ^ (l >> 4)) << 4);          // it = 0; instruction it flips bits 6, 7
   const uint32_t req_cell_v = (uint32_t)(((l & 15) ^ (((l >> 4) & 3) << 2)) << 4);
