@@ -335,6 +335,34 @@ LOCOCO_API lococo_status lococo_segment_step_backward(const lococo_config* cfg, 
                                            float* d_conv_w, float* d_conv_b, void* workspace,
                                            size_t ws_bytes, void* stream);
 
+/* Backward pass of a whole scan (lococo_sequence_forward's recurrence), for training the
+ * convolution heads through Alg. 2's loop: the chain rule through every block step in reverse, the
+ * gradient w.r.t. a block's starting state being handed to the block before it as the gradient
+ * w.r.t. that block's resulting state.  The call runs the forward recurrence once more block by
+ * block (steps 3-5), keeping the state every block starts from in the workspace, then walks the
+ * blocks backwards through lococo_segment_step_backward; gradients therefore match that entry
+ * point's composed by hand, launch for launch.
+ *   seq: q, k, v of the L tokens as in the forward (o is not read); cache0: the state the scan
+ *   starts from (not modified; its attn_colsum is neither read nor written).
+ *   Gradients are fp32 device arrays, contiguous:
+ *     in   d_o [batch, n_q_heads, L, d]; d_final_k, d_final_v [batch, n_kv_heads, M, d]: gradient
+ *          w.r.t. the state after the last block, or NULL for zero;
+ *     out  d_q [batch, n_q_heads, L, d]; d_k, d_v [batch, n_kv_heads, L, d]; d_cache0_k, d_cache0_v
+ *          [batch, n_kv_heads, M, d] (rows that were not live in cache0 are zero); all overwritten;
+ *     acc  d_conv_w, d_conv_b: ADDED to, as in the step (d_conv_b may be NULL).
+ *   workspace: lococo_sequence_backward_workspace_bytes(cfg, L, B) bytes, 256-byte aligned: two
+ *   states per block (storage type) plus one step's worth of everything else.
+ * LOCOCO_FLAG_FILTERS_PREPARED is refused (the call owns its workspaces); norm = 2 is forward only. */
+LOCOCO_API lococo_status lococo_sequence_backward_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
+                                                                  size_t* out);
+LOCOCO_API lococo_status lococo_sequence_backward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L,
+                                                  int32_t B, const void* conv_w, const void* conv_b,
+                                                  const lococo_cache* cache0, const float* d_o,
+                                                  const float* d_final_k, const float* d_final_v, float* d_q,
+                                                  float* d_k, float* d_v, float* d_cache0_k, float* d_cache0_v,
+                                                  float* d_conv_w, float* d_conv_b, void* workspace,
+                                                  size_t ws_bytes, void* stream);
+
 /* Optional per-kernel timing.  Between lococo_timing_begin() and
  * lococo_timing_end() every kernel the library launches (from any thread) is
  * bracketed by a pair of HIP events recorded on the stream it is launched on.

@@ -27,7 +27,8 @@ EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_
            "lococo_version", "lococo_timing_begin", "lococo_timing_end", "lococo_scan_status",
            "lococo_prepare_filters", "lococo_backward_workspace_bytes", "lococo_segment_step_backward",
            "lococo_measure_peaks", "lococo_debug_option", "lococo_describe_path",
-           "lococo_segment_step_noalloc"]
+           "lococo_segment_step_noalloc", "lococo_sequence_backward_workspace_bytes",
+           "lococo_sequence_backward"]
 
 
 class lococo_config(C.Structure):
@@ -106,6 +107,9 @@ def lib():
         L.lococo_backward_workspace_bytes.argtypes = [cfgp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         L.lococo_segment_step_backward.argtypes = [cfgp, qp, C.c_int32, C.c_void_p, C.c_void_p, cap] + [fp] * 10 + [
             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.lococo_sequence_backward_workspace_bytes.argtypes = [cfgp, C.c_int64, C.c_int32, C.POINTER(C.c_size_t)]
+        L.lococo_sequence_backward.argtypes = [cfgp, qp, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, cap] + [
+            fp] * 10 + [C.c_void_p, C.c_size_t, C.c_void_p]
         L.lococo_measure_peaks.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double),
                                            C.POINTER(C.c_double)]
         L.lococo_debug_option.argtypes = [C.c_int32, C.c_int64]
@@ -306,6 +310,27 @@ def lococo_segment_step_backward(cfg, q, k, v, conv_w, conv_b, cache: Cache, d_o
     _check(lib().lococo_segment_step_backward(
         C.byref(cfg), C.byref(x), B, _ptr(conv_w), _ptr(conv_b), C.byref(cache.c), _ptr(d_o), _ptr(d_new_k),
         _ptr(d_new_v), _ptr(d_q), _ptr(d_k), _ptr(d_v), _ptr(d_cache_k), _ptr(d_cache_v), _ptr(d_conv_w),
+        _ptr(d_conv_b), _ptr(workspace), ws_bytes, _stream()))
+
+
+def lococo_sequence_backward_workspace_bytes(cfg, L: int, B: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().lococo_sequence_backward_workspace_bytes(C.byref(cfg), L, B, C.byref(out)))
+    return out.value
+
+
+def lococo_sequence_backward(cfg, q, k, v, B: int, conv_w, conv_b, cache: Cache, d_o, d_final_k, d_final_v, d_q,
+                             d_k, d_v, d_cache0_k, d_cache0_v, d_conv_w, d_conv_b, workspace):
+    """Gradients of a whole scan started from `cache` (left as it is).  All gradient tensors are fp32,
+    contiguous, on the device; d_final_k / d_final_v may be None (zero); d_conv_w / d_conv_b are added to."""
+    for t in (d_o, d_final_k, d_final_v, d_q, d_k, d_v, d_cache0_k, d_cache0_v, d_conv_w, d_conv_b):
+        assert t is None or (t.dtype == torch.float32 and t.is_contiguous() and t.is_cuda)
+    L = q.shape[2]
+    x = _qkvo(q, k, v, None)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lococo_sequence_backward(
+        C.byref(cfg), C.byref(x), L, B, _ptr(conv_w), _ptr(conv_b), C.byref(cache.c), _ptr(d_o), _ptr(d_final_k),
+        _ptr(d_final_v), _ptr(d_q), _ptr(d_k), _ptr(d_v), _ptr(d_cache0_k), _ptr(d_cache0_v), _ptr(d_conv_w),
         _ptr(d_conv_b), _ptr(workspace), ws_bytes, _stream()))
 
 

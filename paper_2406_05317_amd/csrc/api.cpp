@@ -1107,3 +1107,165 @@ lococo_status lococo_mix_from_logits(const lococo_config* cfg, const lococo_qkvo
 }
 
 }  // extern "C"
+
+// ---- backward of a whole scan: the forward recurrence is run once more to keep the state every block
+// started from, then the blocks are walked in reverse, each through lococo_segment_step_backward
+namespace {
+struct SeqBwdLayout {
+  size_t cache[4];        // ping-pong buffers of the recomputed forward: k0, k1, v0, v1 (storage type)
+  size_t states_k, states_v, state;   // the state BEFORE every block: n_blocks slots of `state` bytes each
+  size_t o_blk;           // attention output of one block of the recomputed forward (storage type; discarded)
+  size_t fwd_ws, fwd_ws_bytes;        // step workspace of the recomputed forward
+  size_t d_o, d_q, d_k, d_v;          // one block of gradients, contiguous fp32
+  size_t g[2][2];         // gradient w.r.t. the cache state, ping-pong: [which][k, v], fp32 [chains, M, d]
+  size_t step_ws;         // workspace of one backward step
+  size_t total;
+};
+lococo_status seq_bwd_layout(const lococo_config* c, int64_t L, int32_t B, SeqBwdLayout* out) {
+  SeqBwdLayout l;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { const size_t here = at; at += align_up(bytes, 256); return here; };
+  const size_t chains = (size_t)c->batch * c->n_kv_heads, es = esize(c->dtype);
+  l.state = align_up(chains * c->M * c->head_dim * es, 256);
+  const int64_t n = (L + B - 1) / B;
+  for (int i = 0; i < 4; ++i) l.cache[i] = take(l.state);
+  l.states_k = take((size_t)n * l.state);
+  l.states_v = take((size_t)n * l.state);
+  l.o_blk = take((size_t)c->batch * c->n_q_heads * B * c->head_dim * es);
+  Path path;
+  lococo_status st = resolve_path(c, B, &path);
+  if (st) return st;
+  l.fwd_ws_bytes = step_ws_bytes(c, path, B);
+  l.fwd_ws = take(l.fwd_ws_bytes);
+  l.d_o = take((size_t)c->batch * c->n_q_heads * B * c->head_dim * sizeof(float));
+  l.d_q = take((size_t)c->batch * c->n_q_heads * B * c->head_dim * sizeof(float));
+  l.d_k = take(chains * B * c->head_dim * sizeof(float));
+  l.d_v = take(chains * B * c->head_dim * sizeof(float));
+  for (int w = 0; w < 2; ++w)
+    for (int kv = 0; kv < 2; ++kv) l.g[w][kv] = take(chains * c->M * c->head_dim * sizeof(float));
+  size_t step = 0;                    // a step's workspace grows with the occupancy: the full cache bounds all
+  if ((st = lococo_backward_workspace_bytes(c, B, c->M, &step))) return st;
+  l.step_ws = take(step);
+  l.total = at;
+  *out = l;
+  return LOCOCO_OK;
+}
+}  // namespace
+
+extern "C" {
+
+lococo_status lococo_sequence_backward_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B, size_t* out) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if (!out) return fail(LOCOCO_EINVAL, "out is NULL");
+  if (L < 0 || B <= 0) return fail(LOCOCO_EINVAL, "need L >= 0 and B > 0");
+  SeqBwdLayout l;
+  if ((st = seq_bwd_layout(cfg, L, B, &l))) return st;
+  *out = l.total;
+  return LOCOCO_OK;
+}
+
+lococo_status lococo_sequence_backward(const lococo_config* cfg, const lococo_qkvo* seq, int64_t L, int32_t B,
+                                       const void* conv_w, const void* conv_b, const lococo_cache* cache0,
+                                       const float* d_o, const float* d_final_k, const float* d_final_v,
+                                       float* d_q, float* d_k, float* d_v, float* d_cache0_k, float* d_cache0_v,
+                                       float* d_conv_w, float* d_conv_b, void* workspace, size_t ws_bytes,
+                                       void* stream) {
+  lococo_status st;
+  if ((st = check_config(cfg))) return st;
+  if ((st = check_cache(cfg, cache0))) return st;
+  if (L <= 0) return fail(LOCOCO_EINVAL, "L must be positive");
+  if (B <= 0) return fail(LOCOCO_EINVAL, "block length B must be positive");
+  if (cfg->norm == 2) return fail(LOCOCO_EUNSUPPORTED, "norm = 2 (rectifier on the convolution input) is forward only");
+  if (!seq) return fail(LOCOCO_EINVAL, "qkvo is NULL");
+  if ((st = check_tensor(cfg, seq->q, "q", L)) || (st = check_tensor(cfg, seq->k, "k", L)) ||
+      (st = check_tensor(cfg, seq->v, "v", L)))
+    return st;
+  if ((st = check_step_shape(cfg, B, std::min<int64_t>(cfg->M, (int64_t)cache0->len + L)))) return st;
+  if (!d_o || !d_q || !d_k || !d_v || !d_cache0_k || !d_cache0_v) return fail(LOCOCO_EINVAL, "a gradient pointer is NULL");
+  if (cfg->flags & LOCOCO_FLAG_FILTERS_PREPARED)
+    return fail(LOCOCO_EINVAL, "LOCOCO_FLAG_FILTERS_PREPARED has no meaning here: the call uses workspaces of its own");
+  int64_t n = 0;
+  if ((st = lococo_plan(L, B, cfg->M, cache0->len, 0, nullptr, &n))) return st;
+  std::vector<lococo_seg> plan((size_t)n);
+  if ((st = lococo_plan(L, B, cfg->M, cache0->len, 0, plan.data(), &n))) return st;
+  bool any_compress = false;
+  for (const auto& sg : plan) any_compress |= sg.branch == 1;
+  if (any_compress && (!conv_w || !d_conv_w)) return fail(LOCOCO_EINVAL, "conv_w or d_conv_w is NULL but the scan compresses");
+  SeqBwdLayout l;
+  if ((st = seq_bwd_layout(cfg, L, B, &l))) return st;
+  if (!workspace || ws_bytes < l.total || ((uintptr_t)workspace & 255))
+    return fail(LOCOCO_EWORKSPACE, "workspace needs %zu bytes, 256-byte aligned (got %zu)", l.total,
+                workspace ? ws_bytes : (size_t)0);
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  const size_t es = esize(cfg->dtype), d = (size_t)cfg->head_dim;
+  const size_t chains = (size_t)cfg->batch * cfg->n_kv_heads, state = chains * cfg->M * d * es;
+
+  // ---- forward once more, block by block, keeping the state every block starts from
+  lococo_cache fc = *cache0;
+  fc.k[0] = ws + l.cache[0]; fc.k[1] = ws + l.cache[1];
+  fc.v[0] = ws + l.cache[2]; fc.v[1] = ws + l.cache[3];
+  fc.cur = 0;
+  fc.attn_colsum = nullptr;
+  HIP_TRY(hipMemcpyAsync(fc.k[0], cache0->k[cache0->cur], state, hipMemcpyDeviceToDevice, s), "copying the first state");
+  HIP_TRY(hipMemcpyAsync(fc.v[0], cache0->v[cache0->cur], state, hipMemcpyDeviceToDevice, s), "copying the first state");
+  for (int64_t i = 0; i < n; ++i) {
+    const lococo_seg& sg = plan[(size_t)i];
+    HIP_TRY(hipMemcpyAsync(ws + l.states_k + (size_t)i * l.state, fc.k[fc.cur], state, hipMemcpyDeviceToDevice, s), "keeping a state");
+    HIP_TRY(hipMemcpyAsync(ws + l.states_v + (size_t)i * l.state, fc.v[fc.cur], state, hipMemcpyDeviceToDevice, s), "keeping a state");
+    if (i + 1 == n) break;                                   // the last block's own update is not needed
+    lococo_qkvo blk = *seq;
+    for (lococo_tensor* t : {&blk.q, &blk.k, &blk.v}) t->p = (char*)t->p + (size_t)(sg.start * t->stride_t) * es;
+    blk.o.p = ws + l.o_blk;
+    blk.o.stride_t = (int64_t)d;
+    blk.o.stride_h = (int64_t)sg.len * (int64_t)d;
+    blk.o.stride_b = (int64_t)cfg->n_q_heads * blk.o.stride_h;
+    if ((st = segment_step_impl(cfg, &blk, sg.len, conv_w, conv_b, &fc, ws + l.fwd_ws, l.fwd_ws_bytes, s)))
+      return st;
+  }
+
+  // ---- reverse walk.  g[w] = gradient w.r.t. the state AFTER the block at hand.
+  int w = 0;
+  const size_t gbytes = chains * cfg->M * d * sizeof(float);
+  for (int kv = 0; kv < 2; ++kv) {
+    const float* src = kv ? d_final_v : d_final_k;
+    if (src) HIP_TRY(hipMemcpyAsync(ws + l.g[w][kv], src, gbytes, hipMemcpyDeviceToDevice, s), "copying the final gradient");
+    else HIP_TRY(hipMemsetAsync(ws + l.g[w][kv], 0, gbytes, s), "clearing the final gradient");
+  }
+  for (int64_t i = n - 1; i >= 0; --i) {
+    const lococo_seg& sg = plan[(size_t)i];
+    const size_t Bn = (size_t)sg.len;
+    lococo_qkvo blk = *seq;
+    for (lococo_tensor* t : {&blk.q, &blk.k, &blk.v}) t->p = (char*)t->p + (size_t)(sg.start * t->stride_t) * es;
+    lococo_cache before = fc;
+    before.k[0] = ws + l.states_k + (size_t)i * l.state;
+    before.v[0] = ws + l.states_v + (size_t)i * l.state;
+    before.k[1] = ws + l.cache[1];
+    before.v[1] = ws + l.cache[3];
+    before.cur = 0;
+    before.len = sg.len_before;
+    // the block's slice of d_o as a contiguous array; its slices of d_q, d_k, d_v go back the same way
+    const size_t row = Bn * d * sizeof(float), pitch = (size_t)L * d * sizeof(float);
+    HIP_TRY(hipMemcpy2DAsync(ws + l.d_o, row, (const char*)d_o + (size_t)sg.start * d * sizeof(float), pitch, row,
+                             (size_t)cfg->batch * cfg->n_q_heads, hipMemcpyDeviceToDevice, s), "slicing d_o");
+    if ((st = lococo_segment_step_backward(cfg, &blk, sg.len, conv_w, conv_b, &before, (const float*)(ws + l.d_o),
+                                           (const float*)(ws + l.g[w][0]), (const float*)(ws + l.g[w][1]),
+                                           (float*)(ws + l.d_q), (float*)(ws + l.d_k), (float*)(ws + l.d_v),
+                                           (float*)(ws + l.g[w ^ 1][0]), (float*)(ws + l.g[w ^ 1][1]), d_conv_w, d_conv_b,
+                                           ws + l.step_ws, l.total - l.step_ws, s)))
+      return st;
+    HIP_TRY(hipMemcpy2DAsync((char*)d_q + (size_t)sg.start * d * sizeof(float), pitch, ws + l.d_q, row, row,
+                             (size_t)cfg->batch * cfg->n_q_heads, hipMemcpyDeviceToDevice, s), "placing d_q");
+    HIP_TRY(hipMemcpy2DAsync((char*)d_k + (size_t)sg.start * d * sizeof(float), pitch, ws + l.d_k, row, row, chains,
+                             hipMemcpyDeviceToDevice, s), "placing d_k");
+    HIP_TRY(hipMemcpy2DAsync((char*)d_v + (size_t)sg.start * d * sizeof(float), pitch, ws + l.d_v, row, row, chains,
+                             hipMemcpyDeviceToDevice, s), "placing d_v");
+    w ^= 1;
+  }
+  HIP_TRY(hipMemcpyAsync(d_cache0_k, ws + l.g[w][0], gbytes, hipMemcpyDeviceToDevice, s), "returning the gradient of the first state");
+  HIP_TRY(hipMemcpyAsync(d_cache0_v, ws + l.g[w][1], gbytes, hipMemcpyDeviceToDevice, s), "returning the gradient of the first state");
+  return LOCOCO_OK;
+}
+
+}  // extern "C"

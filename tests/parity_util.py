@@ -87,3 +87,32 @@ def compare_scan(w, got, want, tol=None, what=""):
         errs["k"] = assert_close(to_np(ck_g)[:, :, :ln_w], ck_w[:, :, :ln_w], tol, what + " cache K")
         errs["v"] = assert_close(to_np(cv_g)[:, :, :ln_w], cv_w[:, :, :ln_w], tol, what + " cache V")
     return errs
+
+
+def oracle_scan_backward(w, q, k, v, cw, cb, ck0, cv0, len0, r_o, r_k, r_v, protect, state_round="none"):
+    """The oracle's step backward walked over the blocks in reverse, on the oracle's own forward states."""
+    states = [(np.asarray(ck0, np.float64), np.asarray(cv0, np.float64), len0)]
+    starts = list(range(0, q.shape[2], w.B))
+    for s0 in starts[:-1]:
+        ck, cv, m = states[-1]
+        sl = slice(s0, s0 + w.B)
+        _, nk, nv, ln = orc.sequence_forward(q[:, :, sl], k[:, :, sl], v[:, :, sl], cw, cb, B=w.B, M=w.M,
+                                             conv_in=w.conv_in, norm=w.norm, cache_k=ck, cache_v=cv, cache_len=m,
+                                             protect=protect, state_round=state_round)
+        states.append((nk, nv, ln))
+    out = dict(dq=np.zeros(q.shape), dk=np.zeros(k.shape), dv=np.zeros(k.shape),
+               d_conv_w=None if cw is None else np.zeros(cw.shape), d_conv_b=None if cb is None else np.zeros(cb.shape))
+    gk, gv = np.array(r_k, np.float64), np.array(r_v, np.float64)
+    for n in reversed(range(len(starts))):
+        sl = slice(starts[n], starts[n] + w.B)
+        ck, cv, m = states[n]
+        ref = orc.step_backward(q[:, :, sl], k[:, :, sl], v[:, :, sl], ck, cv, m, cw, cb, r_o[:, :, sl], gk, gv, M=w.M,
+                                conv_in=w.conv_in, norm=w.norm, protect=protect)
+        out["dq"][:, :, sl], out["dk"][:, :, sl], out["dv"][:, :, sl] = ref["dq"], ref["dk"], ref["dv"]
+        if cw is not None:                       # zero from a fill step
+            out["d_conv_w"] += ref["d_conv_w"]
+        if cb is not None:
+            out["d_conv_b"] += ref["d_conv_b"]
+        gk, gv = ref["d_cache_k"], ref["d_cache_v"]
+    out["d_cache0_k"], out["d_cache0_v"] = gk, gv
+    return out

@@ -91,3 +91,45 @@ def test_filter_gradients_add_over_chains_and_calls():
             parts = parts + one["d_conv_w"]
             np.testing.assert_allclose(one["dq"], whole["dq"][s], rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(whole["d_conv_w"], parts, rtol=1e-12, atol=1e-13)
+
+
+def test_the_reverse_walk_over_a_scan_against_finite_differences_of_the_scan():
+    """The composition the GPU scan backward is compared with (the step backward walked over the blocks in
+    reverse, each block's gradient w.r.t. its starting state handed to the block before) against central
+    differences of the forward oracle over the WHOLE scan: fills, compressions, a ragged last block, a
+    cache that starts half full, protected slots."""
+    from parity_util import oracle_scan_backward
+    from paper_2406_05317_amd import inputs
+    for seed, kw, len0, use_protect in (
+            (1, dict(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=8, L=41, B=8, M=14, conv_width=3), 0, False),
+            (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, head_dim=4, L=30, B=6, M=10, conv_width=3, norm=1,
+                     bias_sigma=0.4, per_head_filters=True), 7, False),
+            (3, dict(batch=1, n_q_heads=2, n_kv_heads=1, head_dim=6, L=24, B=8, M=8, conv_width=5, conv_in=1), 8, True)):
+        w = inputs.Workload(name="walk", dtype="f32", seed=seed, conv_gain=3.0, **kw)
+        rng = np.random.default_rng(seed)
+        q, k, v = (t.double().numpy() for t in inputs.qkv(w))
+        cw, cb = (t.double().numpy() for t in inputs.conv_filters(w))
+        chains = (w.batch, w.n_kv_heads, w.M, w.head_dim)
+        ck0, cv0 = rand(rng, *chains, scale=0.5), rand(rng, *chains, scale=0.5)
+        ck0[:, :, len0:], cv0[:, :, len0:] = 0, 0
+        r_o, r_k, r_v = rand(rng, *q.shape), rand(rng, *chains), rand(rng, *chains)
+        protect = (rng.random(chains[:3]) < 0.3) if use_protect else None
+        got = oracle_scan_backward(w, q, k, v, cw, cb, ck0, cv0, len0, r_o, r_k, r_v, protect)
+
+        def loss(q_, k_, v_, cw_, cb_, ck_, cv_):
+            o, ck, cv, _ = orc.sequence_forward(q_, k_, v_, cw_, cb_, B=w.B, M=w.M, conv_in=w.conv_in, norm=w.norm,
+                                                cache_k=ck_, cache_v=cv_, cache_len=len0, protect=protect)
+            return (o * r_o).sum() + (ck * r_k).sum() + (cv * r_v).sum()
+
+        args = [q, k, v, cw, cb, ck0, cv0]
+        names = ["dq", "dk", "dv", "d_conv_w", "d_conv_b", "d_cache0_k", "d_cache0_v"]
+        eps = 1e-6
+        for i, name in enumerate(names):
+            direction = rand(rng, *args[i].shape)
+            if name.startswith("d_cache0"):
+                direction[:, :, len0:] = 0              # rows that are not live are not inputs
+            hi = [a + eps * direction if j == i else a for j, a in enumerate(args)]
+            lo = [a - eps * direction if j == i else a for j, a in enumerate(args)]
+            fd = (loss(*hi) - loss(*lo)) / (2 * eps)
+            mine = float((got[name] * direction).sum())
+            assert abs(mine - fd) < 1e-6 * max(1.0, abs(fd)), (seed, name, mine, fd)
