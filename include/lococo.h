@@ -97,9 +97,9 @@ typedef struct lococo_config {
                              printed, W / sum(W), a row sum below norm_eps in magnitude replaced by
                              +-norm_eps (shape-agnostic kernels and forward only)                    */
   int32_t impl;           /* LOCOCO_IMPL_*: AUTO picks the fused MFMA kernels when the shape allows
-                             (bf16, head_dim 128, keys-only filters of width 15 or 21, M a multiple
-                             of 32), separate MFMA kernels for Eq. 5 and Eq. 4 for other bf16 /
-                             head_dim 128 compressors (odd width <= 31, [K|V] filters, any M), else
+                             (bf16, head_dim 128, filters of width 15 or 21 over the keys or over
+                             [K|V], M a multiple of 32), separate MFMA kernels for Eq. 5 and Eq. 4 for
+                             other bf16 / head_dim 128 compressors (odd width <= 31, any M), else
                              the shape-agnostic kernels; GENERIC forces the shape-agnostic kernels;
                              MFMA asks for the fused kernels and fails with LOCOCO_EUNSUPPORTED
                              when the shape does not allow them                                   */
@@ -270,8 +270,11 @@ enum {
                                        on one XCD)                                                             */
   LOCOCO_OPT_LOGITS_TILES = 4,      /* 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused
                                        MFMA path (0 = chosen from the grid size; 256 needs more than 128 slots) */
-  LOCOCO_OPT_MAX_RESIDENT = 5       /* > 0: pretend the device holds only this many workgroups of the scan
+  LOCOCO_OPT_MAX_RESIDENT = 5,      /* > 0: pretend the device holds only this many workgroups of the scan
                                        kernel at once (exercises the fall-back to one launch per step)         */
+  LOCOCO_OPT_UNFUSED_KV = 6         /* 1: filters over [K | V] go to the unfused MFMA path (Eq. 5 as a kernel
+                                       of its own, logits through the workspace) even where the fused kernel
+                                       takes them: same definition, another order of the fp32 sums            */
 };
 LOCOCO_API lococo_status lococo_debug_option(int32_t option, int64_t value);
 

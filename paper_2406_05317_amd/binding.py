@@ -20,7 +20,7 @@ LOCOCO_F32, LOCOCO_BF16 = 0, 1
 LOCOCO_IMPL_AUTO, LOCOCO_IMPL_GENERIC, LOCOCO_IMPL_MFMA = 0, 1, 2
 LOCOCO_FLAG_FILTERS_PREPARED = 1
 (LOCOCO_OPT_RESET, LOCOCO_OPT_SPIN_LIMIT, LOCOCO_OPT_SCAN_PER_STEP, LOCOCO_OPT_CHAIN_SYNC_DEVICE,
- LOCOCO_OPT_LOGITS_TILES, LOCOCO_OPT_MAX_RESIDENT) = range(6)
+ LOCOCO_OPT_LOGITS_TILES, LOCOCO_OPT_MAX_RESIDENT, LOCOCO_OPT_UNFUSED_KV) = range(7)
 
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",

@@ -20,7 +20,7 @@ using namespace lococo;
 static __device__ __align__(256) unsigned char scratch[LOCOCO_NOALLOC_SCRATCH_BYTES];
 
 namespace {
-DebugOptions g_debug = {0, 0, 0, 0, 0};
+DebugOptions g_debug = {0, 0, 0, 0, 0, 0};
 }
 namespace lococo {
 const DebugOptions& debug_options() { return g_debug; }
@@ -194,7 +194,9 @@ Path choose_path(const lococo_config* c, int32_t B, const char** why) {
   (void)B;
   const char* ignore = "";
   if (!attn_mfma_supports(c->dtype, c->head_dim, why)) return PATH_GENERIC;
-  if (compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why)) return PATH_MFMA;
+  if (compress_mfma_supports(c->dtype, c->head_dim, c->M, c->conv_width, c->conv_in, c->norm, why) &&
+      !(c->conv_in && g_debug.unfused_kv))
+    return PATH_MFMA;
   if (c->norm != 2 &&                 // the input-side rectifier exists in the shape-agnostic kernels only
       conv_logits_mfma_supports(c->dtype, c->head_dim, c->conv_width) && attn_mfma_supports(c->dtype, c->head_dim, &ignore))
     return PATH_MFMA_UNFUSED;
@@ -215,7 +217,7 @@ lococo_status resolve_path(const lococo_config* c, int32_t B, Path* out) {
 // Workspace of one step.  Generic: fp32 logits [chains, M, T], T <= M + B.
 // MFMA: the repacked filter bank.
 size_t filter_ws_bytes(const lococo_config* c) {
-  return align_up(compress_mfma_filter_bytes(c->M, c->conv_width, filter_banks(c)), 256);
+  return align_up(compress_mfma_filter_bytes(c->M, c->conv_width, c->conv_in, filter_banks(c)), 256);
 }
 // chain sync counters + status word of the one-launch scan
 size_t scan_sync_bytes(const lococo_config* c) {
@@ -234,19 +236,25 @@ size_t logits_bytes(const lococo_config* c, int32_t B) {     // rows of up to M 
 }
 // results of the parts of a split step (see compress_mfma.hip), 0 where the shape is not split
 size_t partials_ws_bytes(const lococo_config* c) {
-  return align_up(compress_partials_bytes(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count()), 256);
+  return align_up(compress_partials_bytes(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in, cu_count()), 256);
+}
+// key-side logits between the two walks of a step over [K | V] filters (see compress_mfma.hip), 0 for filters over the keys
+size_t prelogits_ws_bytes(const lococo_config* c, int32_t B) {
+  return align_up(compress_prelogits_bytes(c->batch, c->n_kv_heads, c->M, B, c->conv_in), 256);
 }
 // MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block][results of
-// the parts of a split step]; unfused MFMA path: [filters packed per tap][row statistics of one block][logits];
+// the parts of a split step][key-side logits of a step over [K | V] filters]; unfused MFMA path: [filters packed per tap][row statistics of one block][logits];
 // generic path: the logits.
 size_t step_ws_bytes(const lococo_config* c, Path path, int32_t B) {
-  if (path == PATH_MFMA) return filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B) + partials_ws_bytes(c);
+  if (path == PATH_MFMA)
+    return filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B) + partials_ws_bytes(c) + prelogits_ws_bytes(c, B);
   if (path == PATH_MFMA_UNFUSED) return packed_ws_bytes(c) + stats_bytes(c, B) + logits_bytes(c, B);
   return logits_bytes(c, B);
 }
 void* partials_of(const lococo_config* c, void* ws, int32_t B) {
   return (char*)ws + filter_ws_bytes(c) + scan_sync_bytes(c) + stats_bytes(c, B);
 }
+void* prelogits_of(const lococo_config* c, void* ws, int32_t B) { return (char*)partials_of(c, ws, B) + partials_ws_bytes(c); }
 
 // Bytes of one history slot pair member: one cache state [chains, M, d].
 size_t state_bytes(const lococo_config* c) {
@@ -313,13 +321,13 @@ void note_scan_launched(hipStream_t s) {
 // is made under the lock right before the launch.
 bool scan_fits_one_launch(const lococo_config* c, const StepArgs& a) {
   if (g_debug.scan_per_step) return false;
-  const int groups = compress_scan_groups(c->batch, c->n_kv_heads, c->M, c->conv_width,
+  const int groups = compress_scan_groups(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in,
                                           c->w_head_stride != 0 || c->b_head_stride != 0, cu_count());
   if (groups <= 0) return false;
   const int split = groups < c->batch * c->n_kv_heads
-                        ? 1 : compress_position_split(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count());
+                        ? 1 : compress_position_split(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in, cu_count());
   const int64_t grid = (int64_t)groups * split *
-                       (c->M / compress_tile_slots(c->batch, c->n_kv_heads, c->M, c->conv_width, cu_count()));
+                       (c->M / compress_tile_slots(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in, cu_count()));
   return grid <= compress_scan_max_resident(a, cu_count());
 }
 
@@ -458,7 +466,8 @@ lococo_status enqueue_repack(const lococo_config* c, Path path, const StepArgs& 
 lococo_status enqueue_compress(const lococo_config* c, Path path, StepArgs a, void* ws, int32_t B, hipStream_t s) {
   if (path == PATH_MFMA) {
     KTimer t(K_COMPRESS_MFMA, s);
-    HIP_TRY(launch_compress_mfma(a, ws, filter_banks(c), cu_count(), (char*)ws + filter_ws_bytes(c), partials_of(c, ws, B), s),
+    HIP_TRY(launch_compress_mfma(a, ws, filter_banks(c), cu_count(), (char*)ws + filter_ws_bytes(c), partials_of(c, ws, B),
+                                 prelogits_of(c, ws, B), B, s),
             "compress launch");
     return LOCOCO_OK;
   }
@@ -578,7 +587,7 @@ const char* lococo_version(void) { return "0.2.0"; }
 
 lococo_status lococo_debug_option(int32_t option, int64_t value) {
   switch (option) {
-    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0}; return LOCOCO_OK;
+    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0, 0}; return LOCOCO_OK;
     case LOCOCO_OPT_SPIN_LIMIT: g_debug.spin_limit = value; return LOCOCO_OK;
     case LOCOCO_OPT_SCAN_PER_STEP: g_debug.scan_per_step = value != 0; return LOCOCO_OK;
     case LOCOCO_OPT_CHAIN_SYNC_DEVICE: g_debug.chain_sync_device = value != 0; return LOCOCO_OK;
@@ -590,6 +599,10 @@ lococo_status lococo_debug_option(int32_t option, int64_t value) {
     case LOCOCO_OPT_MAX_RESIDENT:
       if (value < 0) return fail(LOCOCO_EINVAL, "LOCOCO_OPT_MAX_RESIDENT takes a count >= 0");
       g_debug.max_resident = value;
+      return LOCOCO_OK;
+    case LOCOCO_OPT_UNFUSED_KV:
+      if (value != 0 && value != 1) return fail(LOCOCO_EINVAL, "LOCOCO_OPT_UNFUSED_KV takes 0 or 1");
+      g_debug.unfused_kv = value;
       return LOCOCO_OK;
     default: return fail(LOCOCO_EINVAL, "unknown debug option %d", option);
   }
@@ -606,15 +619,16 @@ lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_p
   out->path = (int32_t)path;
   out->compute_units = cu_count();
   if (path == PATH_MFMA) {
-    out->tile_slots = compress_tile_slots(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cu_count());
-    out->position_split = compress_position_split(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cu_count());
+    out->tile_slots = compress_tile_slots(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cfg->conv_in, cu_count());
+    out->position_split = compress_position_split(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cfg->conv_in, cu_count());
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.batch = cfg->batch; a.Hkv = cfg->n_kv_heads; a.M = cfg->M; a.k_width = cfg->conv_width; a.norm = cfg->norm;
+    a.conv_in = cfg->conv_in;
     a.w_head_stride = cfg->w_head_stride; a.b_head_stride = cfg->b_head_stride;
     out->scan_resident_limit = compress_scan_max_resident(a, cu_count());
     if (scan_fits_one_launch(cfg, a))
-      out->scan_groups = compress_scan_groups(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width,
+      out->scan_groups = compress_scan_groups(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cfg->conv_in,
                                               cfg->w_head_stride != 0 || cfg->b_head_stride != 0, cu_count());
   }
   return LOCOCO_OK;
@@ -914,7 +928,8 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
             {
               KTimer t(K_COMPRESS_MFMA, s);
               HIP_TRY(launch_compress_scan(sa, workspace, filter_banks(cfg), cu_count(), sync_ws,
-                                           partials_of(cfg, workspace, B), s), "compress scan launch");
+                                           partials_of(cfg, workspace, B), prelogits_of(cfg, workspace, B), s),
+                      "compress scan launch");
             }
             if (!capturing) note_scan_launched(s);
             c_done += w1 - bi;

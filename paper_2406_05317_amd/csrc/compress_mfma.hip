@@ -33,9 +33,19 @@
 // inside that MFMA stream as well, so no barrier is waited for with the matrix
 // pipe idle.
 //
-// Shapes taken: head_dim = C = 128, bf16, conv_in = 0, width 15 (64- or 32-slot
-// tiles) or 21 (32-slot tiles), either normalisation, M a multiple of BM; any T
-// (tail positions are masked), any m.
+// Filters over [K | V] (C = 2d, the compressor as Eq. 5 prints it).  A slot tile's slice of such a
+// bank is twice what the registers hold, and the logit is a sum of a convolution over the keys
+// and one over the values, so the walk is done twice: with the key half of the filters resident
+// the kernel leaves the summed key-side logits of every position tile in the workspace (4 KB per
+// tile, each lane writing the four values it will read back itself); then the value half takes the
+// registers' place and the ordinary pipeline runs with the value rows as the convolution's input,
+// the stored key-side logits added where the four waves' partial sums meet.  In that second walk
+// the two row tiles swap roles (values with halo, keys without), so the accumulator's first d
+// columns are the new value rows and the pointers are swapped where the rows are written.
+//
+// Shapes taken: head_dim = 128, bf16, width 15 (64- or 32-slot tiles) or 21 (32-slot tiles) over the
+// keys, or either width over [K | V] (32-slot tiles), either normalisation, M a multiple of BM;
+// any T (tail positions are masked), any m.
 #include <type_traits>
 
 #include "lococo_internal.h"
@@ -172,11 +182,14 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // range of position tiles with the same pipeline and leaves its running reference, row sum and
 // unnormalised accumulators in the workspace; the part that arrives last merges them in a fixed
 // order (so the result does not depend on who is last) and writes the rows.
-template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT>
+// CIN = 1: filters over [K | V] (two walks, see the head of the file); wp then holds the key half of
+// every bank's slices followed by the value half, each in the order above.
+template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT, int CIN>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
   static_assert(!SPLIT || (BM == 32 && !MULTI), "the position split is built for 32-slot tiles, one chain per workgroup");
+  static_assert(!CIN || BM == 32, "[K | V] filters are built for 32-slot tiles");
   const StepArgs& a = sa.st;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Xs0 = smem;                                    // NXBUF key tiles (with halo)
@@ -217,8 +230,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // ---- this wave's slice of the filter bank, resident in registers for the whole kernel:
   // lane (slot l31 of tile rt, channels 32w + 16h + 8*lh ..) for every tap
   bf16x8 wreg[G::RT][KW][2];
-  {
-    const uint16_t* wb = wp + hkv0 * wp_head_stride;
+  // (Requesting a [K | V] bank's next half as soon as the last logit MFMA of a pass has issued, so that it
+  // arrives while the pass drains, was tried: the allocator has nowhere to keep 168 registers in flight and
+  // spills them.)
+  auto load_filters = [&](int half_of_bank) {          // 0: the bank (or its key half), 1: its value half
+    const uint16_t* wb = wp + hkv0 * wp_head_stride + (CIN ? (int64_t)half_of_bank * a.M * (KW * kD) : 0);
 #pragma unroll
     for (int rt = 0; rt < G::RT; ++rt)
 #pragma unroll
@@ -235,7 +251,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       for (int t = 0; t < KW; ++t)
 #pragma unroll
         for (int h = 0; h < 2; ++h) asm volatile("" : "+a"(wreg[rt][t][h]));
-  }
+  };
+  if (!CIN) load_filters(0);
+  // key-side logits of one tile as this lane left them in the first walk (CIN only)
+  f32x4 pre = {0.f, 0.f, 0.f, 0.f};
+  __amdgpu_buffer_rsrc_t pre_rows = __builtin_amdgcn_make_buffer_rsrc((void*)sa.prelogits, 0, 0, 0x00020000);
 
   // mixing accumulator, transposed: lane = slot rt*32 + l31, rows = columns 64w + ct*32 + (i/4)*8 + lh*4 + i%4
   f32x16 oacc[2][G::RT];
@@ -315,9 +335,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // consumed this tile's partial logits; the buffer is rewritten at the end of the stage.
   // Neither needs outstanding global loads to finish, so they are plain barriers preceded by a
   // wait on the LDS counter only.
-  auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t) {
+  // PH: 0 = the one walk of a bank over the keys; 1 = first walk of a [K | V] bank (logits of the key
+  // half only: DoSoftmax then means "sum the waves' partial logits and store them"); 2 = its second walk.
+  auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t, auto ph_t) {
     constexpr bool DoConv = decltype(do_conv)::value, DoSoftmax = decltype(do_softmax)::value;
     constexpr bool DoMix = decltype(do_mix_t)::value;
+    constexpr int PH = decltype(ph_t)::value;
     const int j0 = (SPLIT ? jbase : 0) + i * BN;
     const unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
     const unsigned char* Xnext2 = Xs0 + ((i + 2) % G::NXBUF) * G::XBYTES;
@@ -340,7 +363,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     };
     // protected positions of tile i (bits of live protected slots; BN = 32 = one mask word)
     uint32_t pmask = 0;
-    if (PROT && DoSoftmax && j0 < m) {
+    if (PROT && DoSoftmax && PH != 1 && j0 < m) {
       pmask = pwords[j0 >> 5];
       if (j0 + BN > m) pmask &= (1u << (m - j0)) - 1u;
     }
@@ -359,7 +382,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     auto sm_add = [&](int ww0, int e4) {      // 4 positions: + partials ww0 and ww0+1
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        sv[e4 * 4 + e] = ww0 == 0 ? (NORM == 0 ? part[0][e4][e] + part[1][e4][e] : bias + part[0][e4][e] + part[1][e4][e])
+        sv[e4 * 4 + e] = ww0 == 0 ? (PH == 2 ? pre[e] : 0.f) + (NORM == 0 || PH == 1 ? part[0][e4][e] + part[1][e4][e]
+                                                                                        : bias + part[0][e4][e] + part[1][e4][e])
                                   : sv[e4 * 4 + e] + part[ww0][e4][e] + part[ww0 + 1][e4][e];
     };
     auto sm_exp = [&](int e) {
@@ -413,6 +437,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         // store or one load fits the shadow of an MFMA, a store and two loads together do not.
         constexpr int kPieces = 3 * (G::XPER + G::VPER);
         constexpr bool kSpread = kSlots - kPieces - 1 >= kSlots * 3 / 5 + 8;   // behind the softmax and the mixing fetches
+        static_assert(!CIN || !kSpread, "[K | V] banks run on the 32-slot tiles' staging order");
         if (kSpread) {
           constexpr int Z0 = kSlots - kPieces - 1;
           if (slot >= Z0 && slot < Z0 + kPieces) {
@@ -428,11 +453,11 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
             }
           }
         } else {
-          if (slot >= 5 * S && slot < 5 * S + G::XPER) {
+          if ((PH != 1 || DoConv) && slot >= 5 * S && slot < 5 * S + G::XPER) {
             store_x(slot - 5 * S, j0 + 3 * BN, Xstage);
             load_x(slot - 5 * S, j0 + 4 * BN);
           }
-          if (slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) {
+          if (PH != 1 && slot >= 5 * S + G::XPER && slot < 5 * S + G::XPER + G::VPER) {
             store_v(slot - 5 * S - G::XPER, j0, Vstage);
             load_v(slot - 5 * S - G::XPER, j0 + BN);
           }
@@ -440,7 +465,15 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         if (slot >= 8 * S && slot < 8 * S + E4) sm_add(0, slot - 8 * S);
         if (slot >= 8 * S + E4 && slot < 8 * S + 2 * E4) sm_add(2, slot - 8 * S - E4);
         if (slot == 8 * S + 2 * E4) __builtin_amdgcn_s_barrier();   // B2: the partial logits have been consumed
-        if (slot == 8 * S + 2 * E4 + 1) {
+        if (PH == 1 && slot == 8 * S + 2 * E4 + 1) {
+          // first walk: this lane's four sums go to the workspace; the second walk reads them back (same lane)
+          static_assert(!CIN || E4 == 1, "one 16-byte chunk of key-side logits per lane and tile");
+          const f32x4 v = {sv[0], sv[1], sv[2], sv[3]};
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), pre_rows, ((j0 / BN) * (BM * BN) + tid * 4) * 4, 0, 0);
+        }
+        if (PH == 2 && slot == 8 * S + 2 * E4 + 1)     // the next tile's, a whole stage before they are added
+          pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, ((j0 / BN + 1) * (BM * BN) + tid * 4) * 4, 0, 0));
+        if (PH != 1 && slot == 8 * S + 2 * E4 + 1) {
           if (j0 + BN > T) {                   // tail tile: positions past T carry no weight
 #pragma unroll
             for (int e = 0; e < G::EPL; ++e)
@@ -457,8 +490,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
             for (int e = 1; e < G::EPL; ++e) mx = fmaxf(mx, sv[e]);
           }
         }
-        if (NORM == 0 && slot == 8 * S + 2 * E4 + 2) mx = group_max<G::LPR>(mx);
-        if (NORM == 0 && slot == 8 * S + 2 * E4 + 3) {
+        if (PH != 1 && NORM == 0 && slot == 8 * S + 2 * E4 + 2) mx = group_max<G::LPR>(mx);
+        if (PH != 1 && NORM == 0 && slot == 8 * S + 2 * E4 + 3) {
           // The reference only moves when the row maximum outgrows it by kLazy, so exp(s - ref)
           // stays below e^kLazy and the accumulators are rescaled rarely.  Every tile has a
           // position < T, so mx is finite -- unless all 32 positions of the tile are protected
@@ -470,21 +503,21 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
           mc = dead ? 0.f : m_new * kLog2e;
         }
         constexpr int X0 = 8 * S + 2 * E4 + 4;   // one exponential per slot
-        if (slot >= X0 && slot < X0 + G::EPL) sm_exp(slot - X0);
-        if (slot == X0 + G::EPL) {
+        if (PH != 1 && slot >= X0 && slot < X0 + G::EPL) sm_exp(slot - X0);
+        if (PH != 1 && slot == X0 + G::EPL) {
 #pragma unroll
           for (int e = 0; e < G::EPL; ++e) psum += sv[e];
         }
-        if (slot == X0 + G::EPL + 1) {
+        if (PH != 1 && slot == X0 + G::EPL + 1) {
           psum = group_sum<G::LPR>(psum);
           l_run = l_run * alpha + psum;
           m_run = m_new;
         }
-        if (slot == X0 + G::EPL + 2) {
+        if (PH != 1 && slot == X0 + G::EPL + 2) {
 #pragma unroll
           for (int e2 = 0; e2 < G::EPL / 2; ++e2) packed[e2] = pack_bf16(sv[2 * e2], sv[2 * e2 + 1]);
         }
-        if (slot == X0 + G::EPL + 3) {
+        if (PH != 1 && slot == X0 + G::EPL + 3) {
 #pragma unroll
           for (int e4 = 0; e4 < E4; ++e4) {
             const u32x2 pk = {packed[2 * e4], packed[2 * e4 + 1]};
@@ -658,11 +691,16 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   }
 
   const int n_mine = MULTI ? (n_chains - grp + groups - 1) / groups : 1;
+  // A bank over [K | V] makes two passes over the workgroup's chains per step -- every chain's first walk
+  // with the key half of the filters in the registers, then every chain's second walk with the value
+  // half -- so that a step costs two loads of a filter slice however many chains share it.
   for (int step = 0; step < sa.n_steps; ++step)
+  for (int pass = 0; pass < (CIN ? 2 : 1); ++pass) {
+  if (CIN) load_filters(pass);
   for (int ci = 0; ci < n_mine; ++ci) {
   const int ch = grp + ci * groups;
   // ---- the step reads what every slot tile of this chain wrote in the step before
-  if (step > 0 && !chain_wait(ch, step)) return;
+  if (pass == 0 && step > 0 && !chain_wait(ch, step)) return;
   // ---- this step's inputs: source state, occupancy, block
   {
     const int b = ch / a.Hkv, hkv = ch % a.Hkv;
@@ -686,20 +724,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     cat_v = make_cat(src_v + (int64_t)ch * a.M * kD, m,
                      (const uint16_t*)a.v.p + b * a.v.sb + hkv * a.v.sh + tok * a.v.st, a.v.st, Bn);
   }
-#pragma unroll
-  for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-    for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
-  m_run = -INFINITY;
-  l_run = 0.f;
-
-  // ---- prologue: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way.  All
+  // ---- prologue of a walk: key tiles 0, 1 and 2 staged; key tile 3 and value tile 0 on their way.  All
   // loads are issued before the first store (the accumulators' registers are free here), so the
-  // step starts after one memory latency, not three.
-  if (!SPLIT || NT > 0) {
-  {
+  // walk starts after one memory latency, not three.
+  auto prologue = [&](bool with_v) {
     const int jb = SPLIT ? jbase : 0;
     Cat16 xpro[3][G::XPER];
 #pragma unroll
@@ -711,8 +739,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       }
 #pragma unroll
     for (int it = 0; it < G::XPER; ++it) load_x(it, jb + 3 * BN);
+    if (with_v) {
 #pragma unroll
-    for (int it = 0; it < G::VPER; ++it) load_v(it, jb);
+      for (int it = 0; it < G::VPER; ++it) load_v(it, jb);
+    }
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
@@ -721,29 +751,68 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         *(u32x4*)(Xs0 + t * G::XBYTES + (item >> 4) * G::XSTRIDE + (item & 15) * 16) =
             xpro[t][it].from_cache | xpro[t][it].from_blk;
       }
-  }
-  __syncthreads();
+    __syncthreads();
+  };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
-  stage(-1, yes, no, no);                              // logits of tile 0 only
+  if constexpr (CIN) {
+    pre_rows = __builtin_amdgcn_make_buffer_rsrc((void*)(sa.prelogits + (int64_t)(ch * tiles + i0 / BM) * sa.pre_stride), 0,
+                                                 (int)sa.pre_stride * 4, 0x00020000);
+    if (pass == 0) {
+      // ---- first walk: the key half of the filters, the key rows; summed logits to the workspace
+      constexpr std::integral_constant<int, 1> first{};
+      if (!SPLIT || NT > 0) {
+        prologue(false);
+        stage(-1, yes, no, no, first);
+        for (int i = 0; i + 1 < NT; ++i) stage(i, yes, yes, no, first);
+        stage(NT - 1, no, yes, no, first);
+      }
+      continue;
+    }
+    // ---- second walk: the value half, the value rows where the key rows were and the other way round
+    { const CatRows t = cat_k; cat_k = cat_v; cat_v = t; }
+    pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, (((SPLIT ? jbase : 0) / BN) * (BM * BN) + tid * 4) * 4, 0, 0));
+  }
+  if (!SPLIT || NT > 0) {
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+    for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
+  m_run = -INFINITY;
+  l_run = 0.f;
+  constexpr std::integral_constant<int, CIN ? 2 : 0> ph{};
+  prologue(true);
+  stage(-1, yes, no, no, ph);                          // logits of tile 0 only
 
   // ---- pipeline fill, steady state, drain
   if (NT > 1) {
-    stage(0, yes, yes, no);
-    for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes);
-    stage(NT - 1, no, yes, yes);
+    stage(0, yes, yes, no, ph);
+    for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes, ph);
+    stage(NT - 1, no, yes, yes, ph);
   } else {
-    stage(0, no, yes, no);
+    stage(0, no, yes, no, ph);
   }
-  stage(NT, no, no, yes);
-  }  // a part with positions
+  stage(NT, no, no, yes, ph);
+  } else {                                 // a part without positions hands in an empty result
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
+  }
 
   uint16_t* nk;
   uint16_t* nv;
   {
     const int64_t out_at = (int64_t)((sa.slot0 + step) % sa.ring) * sa.out_stride + ((int64_t)ch * a.M + i0) * kD;
-    nk = (uint16_t*)sa.out_k + out_at;
-    nv = (uint16_t*)sa.out_v + out_at;
+    // (after the second walk of a [K | V] bank the accumulator's first d columns are the value rows)
+    nk = (uint16_t*)(CIN ? sa.out_v : sa.out_k) + out_at;
+    nv = (uint16_t*)(CIN ? sa.out_k : sa.out_v) + out_at;
   }
   if constexpr (SPLIT) {
     // ---- this part's result goes to the workspace: accumulators [slot][2 d] as they are
@@ -909,10 +978,13 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // the next prologue's LDS stores behind the copy-out above.)
   if (step + 1 < sa.n_steps) chain_signal(ch);
   else __syncthreads();
-  }  // step and chain loops
+  }  // chains
+  }  // steps and passes
 }
 
-// [M][C][k] per bank -> register order (see compress_mfma_k); one thread per 16-byte chunk.
+// [M][C][k] per bank -> register order (see compress_mfma_k); one thread per 16-byte chunk.  C = 128,
+// or 256 ([K | V] filters): then a bank is its key half (channels 0..127 of every slot) in that
+// order followed by its value half.
 __global__ void repack_filters_k(const uint16_t* w, uint16_t* wp, int M, int C, int KW, int banks,
                                  int64_t w_head_stride) {
   const int64_t chunks_per_bank = (int64_t)M * KW * (C / 8);
@@ -924,8 +996,9 @@ __global__ void repack_filters_k(const uint16_t* w, uint16_t* wp, int M, int C, 
     const int h = (int)(r % 2); r /= 2;
     const int t = (int)(r % KW); r /= KW;
     const int wv = (int)(r % 4); r /= 4;
-    const int slot = (int)r * 32 + (lane & 31);
-    const int c0 = 32 * wv + 16 * h + (lane >> 5) * 8;
+    const int tile = (int)(r % (M / 32)); r /= M / 32;      // r: which half of a [K | V] bank
+    const int slot = tile * 32 + (lane & 31);
+    const int c0 = (int)r * kD + 32 * wv + 16 * h + (lane >> 5) * 8;
     const uint16_t* src = w + bank * w_head_stride + ((int64_t)slot * C + c0) * KW + t;
 #pragma unroll
     for (int q = 0; q < 8; ++q) wp[e * 8 + q] = src[(int64_t)q * KW];
@@ -940,8 +1013,8 @@ __global__ void zero_words_k(uint32_t* p, int n, uint32_t* p2, int n2) {
 // The instantiation a shape runs on, handed to `f` as compile-time constants (BM, KW, NORM, PROT, MULTI).
 // 64-slot tiles when they still give every compute unit a workgroup, else 32-slot tiles; the filter
 // slice of a 64-slot tile fits the registers for width 15 only.
-bool use_big_tiles(int batch, int Hkv, int M, int k_width, int n_cu) {
-  return k_width == 15 && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
+bool use_big_tiles(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  return k_width == 15 && !conv_in && (M % 64 == 0) && (int64_t)batch * Hkv * (M / 64) >= n_cu;
 }
 template <int V> using ic = std::integral_constant<int, V>;
 // Parts the positions of a step are shared out between (1: no split).  Only with 32-slot tiles and
@@ -949,8 +1022,8 @@ template <int V> using ic = std::integral_constant<int, V>;
 // a step alone gives every part four position tiles (with fewer, handing the partial results over
 // costs more than the shorter walk saves: measured on the 3.5 K-token shape, M = 128).  A function of the shape and the device only:
 // every schedule and every block of a scan use the same number, so results do not depend on them.
-int position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
-  if (use_big_tiles(batch, Hkv, M, k_width, n_cu)) return 1;
+int position_split(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  if (use_big_tiles(batch, Hkv, M, k_width, conv_in, n_cu)) return 1;
   const int64_t grid = (int64_t)batch * Hkv * (M / 32);
   int p = 1;
   while (p < 4 && grid * (2 * p) <= n_cu && M / 32 >= 4 * (2 * p)) p *= 2;
@@ -958,12 +1031,18 @@ int position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
 }
 template <class F>
 hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, int n_cu, F&& f) {
-  const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, n_cu);
+  const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, t.conv_in, n_cu);
+  auto pick_cin = [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto spl) {
+    if constexpr (decltype(bm)::value == 32) {
+      if (t.conv_in) return f(bm, kw, norm, prot, mu, spl, ic<1>{});
+    }
+    return f(bm, kw, norm, prot, mu, spl, ic<0>{});
+  };
   auto pick_multi = [&](auto bm, auto kw, auto norm, auto prot) {
     if constexpr (decltype(bm)::value == 32) {
-      if (split && !multi) return f(bm, kw, norm, prot, ic<0>{}, ic<1>{});
+      if (split && !multi) return pick_cin(bm, kw, norm, prot, ic<0>{}, ic<1>{});
     }
-    return multi ? f(bm, kw, norm, prot, ic<1>{}, ic<0>{}) : f(bm, kw, norm, prot, ic<0>{}, ic<0>{});
+    return multi ? pick_cin(bm, kw, norm, prot, ic<1>{}, ic<0>{}) : pick_cin(bm, kw, norm, prot, ic<0>{}, ic<0>{});
   };
   auto pick_prot = [&](auto bm, auto kw, auto norm) {
     return t.protect ? pick_multi(bm, kw, norm, ic<1>{}) : pick_multi(bm, kw, norm, ic<0>{});
@@ -976,11 +1055,11 @@ hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, int n_c
   return hipErrorInvalidValue;   // compress_mfma_supports() keeps other shapes away
 }
 
-template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT>
+template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT, int CIN>
 hipError_t prepare_kernel() {
   static bool attr_set = false;   // benign race: setting it twice is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>,
+    hipError_t e = hipFuncSetAttribute((const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT, CIN>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<BM, KW>::LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -990,14 +1069,15 @@ hipError_t prepare_kernel() {
 
 hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
   const bool multi = a.groups < a.st.batch * a.st.Hkv;
-  return with_instantiation(a.st, multi, a.psplit > 1, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp) {
+  return with_instantiation(a.st, multi, a.psplit > 1, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ci) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
     constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
-    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT>();
+    constexpr int CIN = decltype(ci)::value;
+    hipError_t e = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT, CIN>();
     if (e != hipSuccess) return e;
     dim3 grid((a.st.M / BM) * a.groups * (SPLIT ? a.psplit : 1));
     constexpr int kLds = Geo<BM, KW>::LDS;
-    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>), grid, dim3(kThreads), kLds, s, a, wp,
+    hipLaunchKernelGGL((compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT, CIN>), grid, dim3(kThreads), kLds, s, a, wp,
                        wp_head_stride);
     return hipGetLastError();
   });
@@ -1009,7 +1089,7 @@ bool compress_mfma_supports(int dtype, int d, int M, int conv_width, int conv_in
                             const char** why) {
   if (dtype != LOCOCO_BF16) { *why = "the MFMA kernels take bf16 storage only"; return false; }
   if (d != kD) { *why = "the MFMA kernels take head_dim = 128 only"; return false; }
-  if (conv_in != 0) { *why = "the MFMA compression kernel takes keys-only filters (conv_in = 0)"; return false; }
+  (void)conv_in;                     // filters over the keys or over [K | V]
   if (norm != 0 && norm != 1) { *why = "unknown normalisation"; return false; }
   if (conv_width != 15 && conv_width != 21) {
     *why = "the MFMA compression kernel is built for conv_width = 15 and 21";
@@ -1019,16 +1099,24 @@ bool compress_mfma_supports(int dtype, int d, int M, int conv_width, int conv_in
   return true;
 }
 
-size_t compress_mfma_filter_bytes(int M, int conv_width, int banks) {
-  return (size_t)banks * M * conv_width * kD * 2;
+size_t compress_mfma_filter_bytes(int M, int conv_width, int conv_in, int banks) {
+  return (size_t)banks * M * conv_width * kD * (conv_in ? 2 : 1) * 2;
+}
+
+// key-side logits of the first walk of a [K | V] bank: per (chain, 32-slot tile), one 32 x 32 fp32 tile per
+// position tile of the longest step
+static int64_t prelogits_stride(int M, int B) { return (int64_t)((M + B + BN - 1) / BN) * 32 * BN; }
+size_t compress_prelogits_bytes(int batch, int Hkv, int M, int B, int conv_in) {
+  return conv_in ? (size_t)batch * Hkv * (M / 32) * prelogits_stride(M, B) * sizeof(float) : 0;
 }
 
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s) {
-  const int64_t n = (int64_t)banks * a.M * (kD / 8) * a.k_width;   // 16-byte chunks
+  const int C = a.conv_in ? 2 * kD : kD;
+  const int64_t n = (int64_t)banks * a.M * (C / 8) * a.k_width;   // 16-byte chunks
   int blocks = (int)((n + 255) / 256);
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(repack_filters_k, dim3(blocks), dim3(256), 0, s, (const uint16_t*)a.conv_w,
-                     (uint16_t*)wp, a.M, kD, a.k_width, banks, a.w_head_stride);
+                     (uint16_t*)wp, a.M, C, a.k_width, banks, a.w_head_stride);
   return hipGetLastError();
 }
 
@@ -1040,12 +1128,12 @@ size_t compress_scan_sync_bytes(int batch, int Hkv, int M) {
 }
 static uint32_t* psync_of(void* sync_ws, int batch, int Hkv) { return (uint32_t*)sync_ws + 2 * batch * Hkv + 1; }
 
-int compress_position_split(int batch, int Hkv, int M, int k_width, int n_cu) {
-  return position_split(batch, Hkv, M, k_width, n_cu);
+int compress_position_split(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  return position_split(batch, Hkv, M, k_width, conv_in, n_cu);
 }
 // room for every part's result of one step: [chain][tile][part] x (32 x 2 d accumulators + 32 references + 32 sums)
-size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int n_cu) {
-  const int p = position_split(batch, Hkv, M, k_width, n_cu);
+size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  const int p = position_split(batch, Hkv, M, k_width, conv_in, n_cu);
   return p > 1 ? (size_t)batch * Hkv * (M / 32) * p * Geo<32, 15>::PART_FLOATS * sizeof(float) : 0;
 }
 
@@ -1058,7 +1146,7 @@ hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, int M, bool
 }
 
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
-                                void* partials, hipStream_t s) {
+                                void* partials, void* prelogits, int B, hipStream_t s) {
   ScanArgs sa;
   sa.st = a;
   sa.n_steps = 1;
@@ -1075,11 +1163,13 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   sa.same_l2_allowed = debug_options().chain_sync_device ? 0 : 1;   // (only the hand-off of a split step looks at it here)
   // more (chain, tile) pairs than compute units: one resident workgroup per compute unit, each
   // taking several chains on one load of its filter slice (nothing to wait for within one step)
-  sa.groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
+  sa.groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
   if (sa.groups <= 0) sa.groups = a.batch * a.Hkv;
+  sa.prelogits = (float*)prelogits;
+  sa.pre_stride = prelogits_stride(a.M, B > a.Bn ? B : a.Bn);
   // fewer than half as many: the positions of the step are shared out between several workgroups,
   // whose count per (chain, tile) starts at zero
-  sa.psplit = sa.groups < a.batch * a.Hkv ? 1 : position_split(a.batch, a.Hkv, a.M, a.k_width, n_cu);
+  sa.psplit = sa.groups < a.batch * a.Hkv ? 1 : position_split(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu);
   sa.partials = (float*)partials;
   sa.psync = psync_of(sync_ws, a.batch, a.Hkv);
   if (sa.psplit > 1) {
@@ -1087,35 +1177,36 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD : 0;
+  const int64_t wp_head_stride = banks > 1 ? (int64_t)a.M * a.k_width * kD * (a.conv_in ? 2 : 1) : 0;
   return dispatch(sa, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
 
-int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu) {
-  return use_big_tiles(batch, Hkv, M, k_width, n_cu) ? 64 : 32;
+int compress_tile_slots(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  return use_big_tiles(batch, Hkv, M, k_width, conv_in, n_cu) ? 64 : 32;
 }
 
 int compress_scan_max_resident(const StepArgs& a, int n_cu) {
   if (debug_options().max_resident > 0) return (int)debug_options().max_resident;
-  const int groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
+  const int groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
   const bool multi = groups < a.batch * a.Hkv;
-  const bool split = !multi && position_split(a.batch, a.Hkv, a.M, a.k_width, n_cu) > 1;
+  const bool split = !multi && position_split(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu) > 1;
   int per_cu = 0;
-  hipError_t e = with_instantiation(a, multi, split, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp) {
+  hipError_t e = with_instantiation(a, multi, split, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ci) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
     constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
-    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT>();
+    constexpr int CIN = decltype(ci)::value;
+    hipError_t e2 = prepare_kernel<BM, KW, NORM, PROT, MULTI, SPLIT, CIN>();
     if (e2 != hipSuccess) return e2;
     constexpr int kLds = Geo<BM, KW>::LDS;
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT>,
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)compress_mfma_k<BM, KW, NORM, PROT, MULTI, SPLIT, CIN>,
                                                         kThreads, kLds);
   });
   if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
   return per_cu * n_cu;
 }
 
-int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, int n_cu) {
-  const int bm = use_big_tiles(batch, Hkv, M, k_width, n_cu) ? 64 : 32;
+int compress_scan_groups(int batch, int Hkv, int M, int k_width, int conv_in, bool per_head, int n_cu) {
+  const int bm = use_big_tiles(batch, Hkv, M, k_width, conv_in, n_cu) ? 64 : 32;
   const int tiles = M / bm, chains = batch * Hkv;
   // one workgroup per compute unit (LDS): every workgroup of the launch must be resident at once
   int g = n_cu / tiles;
@@ -1130,18 +1221,20 @@ int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, 
 }
 
 hipError_t launch_compress_scan(const ScanArgs& a_in, const void* wp, int banks, int n_cu,
-                                void* sync_ws, void* partials, hipStream_t s) {
+                                void* sync_ws, void* partials, void* prelogits, hipStream_t s) {
   ScanArgs a = a_in;
   const int chains = a.st.batch * a.st.Hkv;
   a.sync = (uint32_t*)sync_ws;
   a.status = (int32_t*)sync_ws + chains;
-  a.groups = compress_scan_groups(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width,
+  a.groups = compress_scan_groups(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width, a.st.conv_in,
                                   a.st.w_head_stride != 0 || a.st.b_head_stride != 0, n_cu);
+  a.prelogits = (float*)prelogits;
+  a.pre_stride = prelogits_stride(a.st.M, a.B > a.st.Bn ? a.B : a.st.Bn);
   if (a.groups <= 0) return hipErrorInvalidValue;   // the caller keeps such shapes away
-  a.psplit = a.groups < chains ? 1 : position_split(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width, n_cu);
+  a.psplit = a.groups < chains ? 1 : position_split(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width, a.st.conv_in, n_cu);
   a.partials = (float*)partials;
   a.psync = psync_of(sync_ws, a.st.batch, a.st.Hkv);
-  const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD : 0;
+  const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD * (a.st.conv_in ? 2 : 1) : 0;
   return dispatch(a, (const uint16_t*)wp, wp_head_stride, n_cu, s);
 }
 

@@ -16,6 +16,7 @@ struct DebugOptions {
   int64_t chain_sync_device;  // 1: the slot tiles of a chain always meet with device-scope release / acquire
   int64_t logits_tiles;       // 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused MFMA path
   int64_t max_resident;       // > 0: pretend that only this many workgroups of the scan kernel fit the GPU at once
+  int64_t unfused_kv;         // 1: [K | V] filters on the unfused MFMA path
 };
 const DebugOptions& debug_options();
 // compute units of the current device
@@ -76,6 +77,8 @@ struct ScanArgs {
   int32_t psplit;            // workgroups that share out the positions of a step of one (chain, slot tile); 1 = no split (launcher)
   float* partials;           // where the parts of a split step leave their results (launcher)
   uint32_t* psync;           // per (chain, 32-slot tile): parts that have handed in (launcher)
+  float* prelogits;          // [K | V] filters: key-side logits between the two walks of a step (launcher)
+  int64_t pre_stride;        // floats per (chain, 32-slot tile) there (launcher)
 };
 
 // Arguments of the MFMA attention kernel: one block, or every block of a scan
@@ -156,26 +159,30 @@ int generic_attn_max_T();
 bool compress_mfma_supports(int dtype, int d, int M, int conv_width, int conv_in, int norm,
                             const char** why);
 // bytes of the repacked filter bank ([bank][M][k][C] bf16) the kernel reads
-size_t compress_mfma_filter_bytes(int M, int conv_width, int banks);
+size_t compress_mfma_filter_bytes(int M, int conv_width, int conv_in, int banks);
+// bytes the kernel needs between the two walks of a step over a [K | V] bank (0 for filters over the keys);
+// B: the longest block of the call
+size_t compress_prelogits_bytes(int batch, int Hkv, int M, int B, int conv_in);
 // conv_w [M][C][k] (+ w_head_stride per bank) -> wp [bank][M][k][C]
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s);
 // Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
 // sync_ws / partials: compress_scan_sync_bytes() / compress_partials_bytes() of device memory
+// prelogits: compress_prelogits_bytes(.., B, ..) of device memory, B >= a.Bn
 hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
-                                void* partials, hipStream_t s);
+                                void* partials, void* prelogits, int B, hipStream_t s);
 // workgroups per (chain, slot tile) that share out the positions of a step (1: no split)
-int compress_position_split(int batch, int Hkv, int M, int k_width, int n_cu);
-size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int n_cu);
+int compress_position_split(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu);
+size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu);
 // Workgroups per slot tile with which all steps of a scan run in one launch, every workgroup
 // resident at once (each takes every groups-th chain); 0 if there is no such number.  per_head:
 // filters or biases differ between kv heads.
-int compress_scan_groups(int batch, int Hkv, int M, int k_width, bool per_head, int n_cu);
+int compress_scan_groups(int batch, int Hkv, int M, int k_width, int conv_in, bool per_head, int n_cu);
 // Workgroups of the scan kernel (the instantiation this shape runs on) the current device can hold at
 // once, from the runtime's occupancy query; <= 0 if the query failed.  The one-launch scan needs its
 // whole grid resident.
 int compress_scan_max_resident(const StepArgs& a, int n_cu);
 // cache slots per workgroup of the fused kernel for this shape on a device with n_cu compute units
-int compress_tile_slots(int batch, int Hkv, int M, int k_width, int n_cu);
+int compress_tile_slots(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu);
 // bytes of the sync counters + status word the scan launch needs
 size_t compress_scan_sync_bytes(int batch, int Hkv, int M);
 // zero them (a fill kernel, so the call may sit inside a captured graph); keep_status: only the chain
@@ -184,7 +191,7 @@ hipError_t launch_scan_sync_clear(void* sync_ws, int batch, int Hkv, int M, bool
 // the same kernel over n_steps consecutive compress steps (see ScanArgs); `sync_ws` is
 // compress_scan_sync_bytes() of device memory, cleared beforehand
 hipError_t launch_compress_scan(const ScanArgs& a, const void* wp, int banks, int n_cu, void* sync_ws,
-                                void* partials, hipStream_t s);
+                                void* partials, void* prelogits, hipStream_t s);
 
 
 // ---- attention on MFMA (attn_mfma.hip)

@@ -178,7 +178,7 @@ def test_mfma_step_by_step_equals_sequence_call():
 
 def test_mfma_is_refused_for_shapes_it_does_not_take():
     from paper_2406_05317_amd import binding as lb
-    for kw in (dict(head_dim=64), dict(conv_width=7), dict(conv_in=1), dict(conv_width=61), dict(M=100),
+    for kw in (dict(head_dim=64), dict(conv_width=7), dict(conv_in=1, conv_width=9), dict(conv_width=61), dict(M=100),
                dict(dtype="f32")):
         w = _w(**kw)
         cfg = lb.config_for(w, impl=MFMA)
@@ -294,6 +294,7 @@ def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case, optio
     cw, cb = inputs.conv_filters(w)
     protect = (np.random.default_rng(6).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
     want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    options(lb.LOCOCO_OPT_UNFUSED_KV, 1)       # (the fused kernel takes [K | V] filters of width 15 and 21: tested below)
     lb.lococo_timing_begin()
     got = gpu_forward(w, q, k, v, cw, cb, impl=0, history=True, protect=protect)
     ran = lb.lococo_timing_end()
@@ -312,6 +313,59 @@ def test_unfused_mfma_path_for_shapes_the_fused_kernel_does_not_take(case, optio
     options(lb.LOCOCO_OPT_LOGITS_TILES, 0)
     for x, y in zip(by_shape["64"][:3], by_shape["128"][:3]):
         assert torch.equal(x, y)
+
+
+KV_CASES = [
+    dict(conv_width=21, norm=1, bias_sigma=0.5, L=640),                             # the compressor as the paper prints it
+    dict(conv_width=21, L=640),                                                     # the same filters under the softmax
+    dict(conv_width=21, conv_gain=6.0, qk_gain=6.0, L=640),                         # peaked rows
+    dict(conv_width=15, M=256, B=128, L=1000, n_q_heads=8, n_kv_heads=2, per_head_filters=True, bias_sigma=0.3, norm=1, split=2),
+    dict(conv_width=21, M=256, B=128, L=640, n_q_heads=20, n_kv_heads=20),          # 160 pairs: one workgroup each, no split
+    dict(conv_width=21, M=128, B=96, L=500),                                        # partly filled cache at the first compress, ragged last block
+    dict(conv_width=21, M=96, B=200, L=640),                                        # block longer than the cache, T = 296 not a tile multiple
+    dict(conv_width=21, L=512, protect_share=0.15),                                 # protected slots
+    dict(conv_width=15, norm=1, L=512, protect_share=0.3, bias_sigma=0.5),
+    dict(conv_width=21, norm=1, batch=4, n_q_heads=32, n_kv_heads=32, L=512),       # more (chain, tile) pairs than compute units: several chains per workgroup
+    dict(conv_width=21, M=256, B=256, L=1024, n_q_heads=4, n_kv_heads=2, split=2),  # few pairs: the positions of a step shared out
+    dict(conv_width=15, M=512, B=512, L=2048, n_q_heads=2, n_kv_heads=1, norm=1, split=4, protect_share=0.1),
+    dict(conv_width=21, M=512, B=512, L=2048, n_q_heads=8, n_kv_heads=8, tok_lognormal_sigma=0.5, split=2),   # the 32 K-token shape's chains, 8 of them
+]
+
+
+@pytest.mark.parametrize("case", KV_CASES, ids=[str(i) for i in range(len(KV_CASES))])
+def test_fused_kernel_with_filters_over_keys_and_values(case, options):
+    """Eq. 5 over [K | V] (256 channels) on the fused kernel: two walks per step, the key half of the filters
+    first (summed logits through the workspace), then the value half with softmax and mixing.  Against the
+    oracle; the one-launch scan, one launch per step and lococo_segment_step give the same bits; the
+    unfused MFMA path (another order of the fp32 sums) meets the same tolerance."""
+    case = dict(case)
+    share, split = case.pop("protect_share", 0.0), case.pop("split", 1)
+    w = _w(conv_in=1, **case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    protect = (np.random.default_rng(6).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
+    cfg = lb.config_for(w, impl=MFMA)
+    info = lb.lococo_describe_path(cfg, w.B)
+    assert info["path"] == 1 and info["tile_slots"] == 32 and info["position_split"] == split, info
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    lb.lococo_timing_begin()
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    ran = lb.lococo_timing_end()
+    assert "compress_mfma" in ran and "conv_logits_mfma" not in ran and "mix_mfma" not in ran, ran
+    errs = compare_scan(w, a, want, what="fused [K | V]")
+    print(case, {n: (f"{e[0]:.2e}", f"{e[1]:.2e}") for n, e in errs.items()})
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 1)
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 0)
+    c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, step_by_step=True, protect=protect)
+    d = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=2, protect=protect)
+    for other in (b, c, d):
+        for x, y in zip(a[:3], other[:3]):
+            assert torch.equal(x, y)
+        assert a[3:] == other[3:]
+    options(lb.LOCOCO_OPT_UNFUSED_KV, 1)
+    u = gpu_forward(w, q, k, v, cw, cb, impl=0, history=True, protect=protect)
+    compare_scan(w, u, want, what="unfused [K | V]")
 
 
 def test_a_chain_wait_that_gives_up_is_reported(options):
