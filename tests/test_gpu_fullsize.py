@@ -28,8 +28,9 @@ def _check_sampled_chains(w, chains, L=None):
     for (b, h) in chains:
         qs = q[b:b + 1, h * g:(h + 1) * g]
         want = orc.sequence_forward(qs, k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1],
-                                    cw[h] if w.per_head_filters else cw, None, B=w.B, M=w.M,
-                                    state_round=w.dtype, nthreads=16)
+                                    cw[h] if w.per_head_filters else cw,
+                                    (cb[h] if w.per_head_filters else cb) if w.bias_sigma > 0 else None, B=w.B, M=w.M,
+                                    conv_in=w.conv_in, norm=w.norm, state_round=w.dtype, nthreads=16)
         # the sampled chain regenerated on its own equals its slab of the full tensors
         qc, kc, vc = inputs.chain_inputs(w, b, h, L)
         assert torch.equal(qc, qs[0]) and torch.equal(kc, k[b, h]) and torch.equal(vc, v[b, h])
@@ -63,6 +64,13 @@ def test_cfg3_all_chains_first_blocks():
     want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
     got = gpu_forward(w, q, k, v, cw, cb, history=True)
     compare_scan(w, got, want, what="cfg3 first 4 blocks")
+
+
+def test_cfg3_shape_with_the_compressor_as_printed_sampled_chains():
+    """The 32 K-token shape with Eq. 5 over [K | V], width 21, relu-sum and a bias (the fused kernel in two
+    walks, two chains per workgroup, one launch), 16 blocks; two chains recomputed by the oracle."""
+    w = inputs.CFG3.replace(name="cfg3_printed", conv_in=1, conv_width=21, norm=1, bias_sigma=0.5)
+    _check_sampled_chains(w, [(0, 3), (0, 30)], L=16 * w.B)
 
 
 def test_cfg4_full_sampled_chains():
