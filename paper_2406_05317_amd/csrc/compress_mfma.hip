@@ -466,13 +466,14 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
         if (slot >= 8 * S + E4 && slot < 8 * S + 2 * E4) sm_add(2, slot - 8 * S - E4);
         if (slot == 8 * S + 2 * E4) __builtin_amdgcn_s_barrier();   // B2: the partial logits have been consumed
         if (PH == 1 && slot == 8 * S + 2 * E4 + 1) {
-          // first walk: this lane's four sums go to the workspace; the second walk reads them back (same lane)
+          // first walk: this lane's four sums go to the workspace; the second walk reads them back (same lane,
+          // at device scope: from the L2 the store went through to, whatever this CU's L1 holds from a step ago)
           static_assert(!CIN || E4 == 1, "one 16-byte chunk of key-side logits per lane and tile");
           const f32x4 v = {sv[0], sv[1], sv[2], sv[3]};
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), pre_rows, ((j0 / BN) * (BM * BN) + tid * 4) * 4, 0, 0);
         }
         if (PH == 2 && slot == 8 * S + 2 * E4 + 1)     // the next tile's, a whole stage before they are added
-          pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, ((j0 / BN + 1) * (BM * BN) + tid * 4) * 4, 0, 0));
+          pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, ((j0 / BN + 1) * (BM * BN) + tid * 4) * 4, 0, kDeviceScope));
         if (PH != 1 && slot == 8 * S + 2 * E4 + 1) {
           if (j0 + BN > T) {                   // tail tile: positions past T carry no weight
 #pragma unroll
@@ -771,7 +772,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     }
     // ---- second walk: the value half, the value rows where the key rows were and the other way round
     { const CatRows t = cat_k; cat_k = cat_v; cat_v = t; }
-    pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, (((SPLIT ? jbase : 0) / BN) * (BM * BN) + tid * 4) * 4, 0, 0));
+    pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, (((SPLIT ? jbase : 0) / BN) * (BM * BN) + tid * 4) * 4, 0, kDeviceScope));
   }
   if (!SPLIT || NT > 0) {
 #pragma unroll

@@ -202,6 +202,8 @@ SCAN_CASES = [
          tol=3e-4),
     dict(name="f32 one block", dtype="f32", batch=1, n_q_heads=1, n_kv_heads=1, head_dim=16, L=9, B=16, M=12,
          conv_width=3, len0=8, tol=3e-4),
+    dict(name="f32 fills only", dtype="f32", batch=2, n_q_heads=2, n_kv_heads=1, head_dim=16, L=20, B=8, M=32,
+         conv_width=3, len0=4, tol=3e-4),
     # bf16 storage, the fused compression kernel in the forward, the matrix-core contractions in the
     # backward.  The forward states are rounded to bf16 on both sides (the oracle rounds the exact value,
     # the kernel an fp32 one), so a few state entries differ by one bf16 step: the tolerance is that of
