@@ -341,8 +341,8 @@ LOCOCO_API lococo_status lococo_segment_step_backward(const lococo_config* cfg, 
 /* Backward pass of a whole scan (lococo_sequence_forward's recurrence), for training the
  * convolution heads through Alg. 2's loop: the chain rule through every block step in reverse, the
  * gradient w.r.t. a block's starting state being handed to the block before it as the gradient
- * w.r.t. that block's resulting state.  The call runs the forward recurrence once more block by
- * block (steps 3-5), keeping the state every block starts from in the workspace, then walks the
+ * w.r.t. that block's resulting state.  The call runs the cache recurrence once more block by
+ * block (the fill branch or steps 4-5), keeping the state every block starts from in the workspace, then walks the
  * blocks backwards through lococo_segment_step_backward; gradients therefore match that entry
  * point's composed by hand, launch for launch.
  *   seq: q, k, v of the L tokens as in the forward (o is not read); cache0: the state the scan

@@ -1217,7 +1217,13 @@ lococo_status lococo_sequence_backward(const lococo_config* cfg, const lococo_qk
   const size_t es = esize(cfg->dtype), d = (size_t)cfg->head_dim;
   const size_t chains = (size_t)cfg->batch * cfg->n_kv_heads, state = chains * cfg->M * d * es;
 
-  // ---- forward once more, block by block, keeping the state every block starts from
+  // ---- the recurrence once more, block by block, keeping the state every block starts from: the fill
+  // branch or steps 4-5 only (the same kernels as in lococo_segment_step, so the same states); nobody reads
+  // the attention outputs of step 3 here
+  Path path;
+  if ((st = resolve_path(cfg, B, &path))) return st;
+  if ((st = check_mfma_strides(cfg, path, seq, B, false))) return st;
+  bool filters_ready = false;
   lococo_cache fc = *cache0;
   fc.k[0] = ws + l.cache[0]; fc.k[1] = ws + l.cache[1];
   fc.v[0] = ws + l.cache[2]; fc.v[1] = ws + l.cache[3];
@@ -1232,12 +1238,18 @@ lococo_status lococo_sequence_backward(const lococo_config* cfg, const lococo_qk
     if (i + 1 == n) break;                                   // the last block's own update is not needed
     lococo_qkvo blk = *seq;
     for (lococo_tensor* t : {&blk.q, &blk.k, &blk.v}) t->p = (char*)t->p + (size_t)(sg.start * t->stride_t) * es;
-    blk.o.p = ws + l.o_blk;
+    blk.o.p = ws + l.o_blk;                                  // (never written)
     blk.o.stride_t = (int64_t)d;
     blk.o.stride_h = (int64_t)sg.len * (int64_t)d;
     blk.o.stride_b = (int64_t)cfg->n_q_heads * blk.o.stride_h;
-    if ((st = segment_step_impl(cfg, &blk, sg.len, conv_w, conv_b, &fc, ws + l.fwd_ws, l.fwd_ws_bytes, s)))
-      return st;
+    const StepArgs a = make_args(cfg, &blk, 0, sg.len, &fc, conv_w, conv_b, true);
+    if (sg.branch == 1 && path != PATH_GENERIC && !filters_ready) {
+      if ((st = enqueue_repack(cfg, path, a, ws + l.fwd_ws, s))) return st;
+      filters_ready = true;
+    }
+    lococo_cache next = fc;
+    if ((st = enqueue_update(cfg, path, a, &next, ws + l.fwd_ws, B, s))) return st;
+    fc = next;
   }
 
   // ---- reverse walk.  g[w] = gradient w.r.t. the state AFTER the block at hand.
