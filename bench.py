@@ -226,6 +226,47 @@ def decode_bench(args, w, lb, inputs, torch):
     print(json.dumps(out))
 
 
+def backward_scan_bench(args, w, lb, inputs, torch):
+    """Backward of the whole scan in one call (lococo_sequence_backward): the cache recurrence recomputed,
+    then every block's step backward in reverse."""
+    dev = "cuda"
+    cfg = lb.config_for(w, impl=args.impl)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    qd, kd, vd, cwd = (t.to(dev) for t in (q, k, v, cw))
+    cache = lb.Cache(cfg, dev)
+    shape = (w.batch, w.n_kv_heads, w.M, w.head_dim)
+    f = lambda *sh: torch.randn(*sh, device=dev, dtype=torch.float32)
+    d_o, gk, gv = f(*q.shape), f(*shape), f(*shape)
+    dq, dk, dv = torch.empty_like(d_o), f(*k.shape), f(*k.shape)
+    dck, dcv = torch.empty_like(gk), torch.empty_like(gv)
+    dW = torch.zeros(cw.shape, device=dev, dtype=torch.float32)
+    ws_bytes = lb.lococo_sequence_backward_workspace_bytes(cfg, w.L, w.B)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step():
+        lb.lococo_sequence_backward(cfg, qd, kd, vd, w.B, cwd, None, cache, d_o, gk, gv, dq, dk, dv, dck, dcv, dW, None, ws)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lb.lococo_timing_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kt = lb.lococo_timing_end()
+    print(json.dumps({"metric": "backward of the whole scan, tokens/sec per layer", "value": w.batch * w.L / (ms * 1e-3),
+                      "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                      "dtype": "f32" if args.impl == 1 else "bf16", "data": "synthetic",
+                      "config": {"workload": w.name + "-backward-scan", "batch": w.batch, "n_q_heads": w.n_q_heads,
+                                 "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.L, "B": w.B, "M": w.M,
+                                 "conv_width": w.conv_width, "conv_channels": w.C, "norm": w.norm,
+                                 "workspace_bytes": ws_bytes},
+                      "forward_recompute_kernel_ms_per_step": {n: kt[n][1] / args.steps for n in kt}}))
+
+
 def backward_bench(args, w, lb, inputs, torch):
     """Backward of one compress step (full cache, one block).  --impl 1: every kernel shape-agnostic,
     fp32 vector arithmetic; default: the three Eq. 5 contractions on the matrix cores."""
@@ -293,6 +334,8 @@ def main():
                     help="protect the first N cache slots (attention sinks kept beside the compressed memory)")
     ap.add_argument("--track-attention", action="store_true",
                     help="accumulate the attention each cache slot receives (lococo_cache.attn_colsum) during the scan")
+    ap.add_argument("--backward-scan", action="store_true",
+                    help="instead of the forward scan, time lococo_sequence_backward over the whole workload")
     ap.add_argument("--backward", action="store_true",
                     help="instead of the scan, time the backward pass of ONE compress step of the workload's shape "
                          "(--impl 1: shape-agnostic fp32 kernels only)")
@@ -334,6 +377,8 @@ def main():
     torch.cuda.set_device(0)
     if args.decode_batch:
         return decode_bench(args, w, lb, inputs, torch)
+    if args.backward_scan:
+        return backward_scan_bench(args, w, lb, inputs, torch)
     if args.backward:
         return backward_bench(args, w, lb, inputs, torch)
     cfg = lb.config_for(w, impl=args.impl)
