@@ -208,3 +208,49 @@ def test_the_library_reads_no_environment_variable():
     import subprocess
     out = subprocess.run(["nm", "-D", "--undefined-only", lb.LIB_PATH], capture_output=True, text=True).stdout
     assert "getenv" not in out
+
+
+def test_size_limits_and_the_newer_entry_points_refuse_on_the_host():
+    """Block lengths and row counts beyond what the kernels hold, and the argument checks of the scan
+    backward and of the entry point that allocates nothing: all status codes, nothing dereferenced."""
+    L = lb.lib()
+    cfg = _cfg()
+    fake = [0x10000, 0x20000, 0x30000, 0x40000]
+    cache = lb.lococo_cache((C.c_void_p * 2)(fake[0], fake[1]), (C.c_void_p * 2)(fake[2], fake[3]), 0, 0)
+    t = lb.lococo_tensor(0x50000, 1 << 30, 1 << 24, 8)
+    x = lb.lococo_qkvo(t, t, t, lb.lococo_tensor(0x60000, 1 << 30, 1 << 24, 8))
+    assert L.lococo_segment_step(C.byref(cfg), C.byref(x), 70000, 0x70000, None, C.byref(cache), None, 0,
+                                 None) == lb.LOCOCO_EUNSUPPORTED
+    assert b"65535" in L.lococo_last_error()
+    assert L.lococo_attn_only(C.byref(cfg), C.byref(x), 60000, C.byref(cache), None) == lb.LOCOCO_EUNSUPPORTED
+    assert b"exceeds" in L.lococo_last_error()
+    # the entry point without allocations: prepared filters make no sense there, and a step whose scratch
+    # would not fit the library's own array is refused
+    flagged = _cfg(flags=1)
+    assert L.lococo_segment_step_noalloc(C.byref(flagged), C.byref(x), 4, 0x70000, None, C.byref(cache),
+                                         None) == lb.LOCOCO_EINVAL
+    # scan backward
+    n = C.c_size_t(0)
+    assert L.lococo_sequence_backward_workspace_bytes(C.byref(cfg), -1, 4, C.byref(n)) == lb.LOCOCO_EINVAL
+    assert L.lococo_sequence_backward_workspace_bytes(C.byref(cfg), 16, 0, C.byref(n)) == lb.LOCOCO_EINVAL
+    assert L.lococo_sequence_backward_workspace_bytes(C.byref(cfg), 16, 4, None) == lb.LOCOCO_EINVAL
+    assert L.lococo_sequence_backward_workspace_bytes(C.byref(cfg), 16, 4, C.byref(n)) == lb.LOCOCO_OK and n.value > 0
+    g = [0x100000 + 0x1000 * i for i in range(10)]
+    args = lambda **kw: dict(dict(L=16, B=4, cw=0x70000, d_o=g[0], dq=g[1], dk=g[2], dv=g[3], ck=g[4], cv=g[5], dW=g[6],
+                                  ws=0x200000, ws_bytes=1 << 40), **kw)
+
+    def call(c=cfg, **kw):
+        a = args(**kw)
+        return L.lococo_sequence_backward(C.byref(c), C.byref(x), a["L"], a["B"], a["cw"], None, C.byref(cache), a["d_o"],
+                                          None, None, a["dq"], a["dk"], a["dv"], a["ck"], a["cv"], a["dW"], None,
+                                          a["ws"], a["ws_bytes"], None)
+    assert call(L=0) == lb.LOCOCO_EINVAL
+    assert call(B=0) == lb.LOCOCO_EINVAL
+    assert call(d_o=None) == lb.LOCOCO_EINVAL and b"gradient pointer" in L.lococo_last_error()
+    assert call(ck=None) == lb.LOCOCO_EINVAL
+    assert call(cw=None) == lb.LOCOCO_EINVAL and b"compresses" in L.lococo_last_error()
+    assert call(c=flagged) == lb.LOCOCO_EINVAL
+    assert call(c=_cfg(norm=2)) == lb.LOCOCO_EUNSUPPORTED
+    assert call(ws=None) == lb.LOCOCO_EWORKSPACE
+    assert call(ws_bytes=256) == lb.LOCOCO_EWORKSPACE
+    assert call(ws=0x200010) == lb.LOCOCO_EWORKSPACE          # not 256-byte aligned
