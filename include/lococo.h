@@ -272,9 +272,13 @@ enum {
                                        MFMA path (0 = chosen from the grid size; 256 needs more than 128 slots) */
   LOCOCO_OPT_MAX_RESIDENT = 5,      /* > 0: pretend the device holds only this many workgroups of the scan
                                        kernel at once (exercises the fall-back to one launch per step)         */
-  LOCOCO_OPT_UNFUSED_KV = 6         /* 1: filters over [K | V] go to the unfused MFMA path (Eq. 5 as a kernel
+  LOCOCO_OPT_UNFUSED_KV = 6,        /* 1: filters over [K | V] go to the unfused MFMA path (Eq. 5 as a kernel
                                        of its own, logits through the workspace) even where the fused kernel
                                        takes them: same definition, another order of the fp32 sums            */
+  LOCOCO_OPT_NO_STEP_PIPELINE = 7   /* 1: shapes with at most half as many (chain, slot tile) pairs as compute
+                                       units run without the pairs of workgroups that take the steps of a scan
+                                       in turn (then the position split applies where it did before): same
+                                       definition, another order of the fp32 sums                             */
 };
 LOCOCO_API lococo_status lococo_debug_option(int32_t option, int64_t value);
 
@@ -291,7 +295,11 @@ typedef struct lococo_path_info {
   int32_t position_split;       /* path 1: workgroups that share out the positions of a step of one (chain,
                                    slot tile) where one each would leave compute units idle; 1 = no split
                                    (several chains per workgroup never split)                                  */
-  int32_t reserved[2];
+  int32_t step_pipeline;        /* path 1: 2 where two workgroups per (chain, slot tile) take the steps of a
+                                   scan in turn (shapes with at most half as many pairs as compute units:
+                                   the one whose turn is next works through the part of its step that does
+                                   not depend on the step before while its partner finishes that step); else 1 */
+  int32_t reserved;
 } lococo_path_info;
 LOCOCO_API lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_path_info* out);
 

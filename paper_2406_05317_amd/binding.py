@@ -20,7 +20,7 @@ LOCOCO_F32, LOCOCO_BF16 = 0, 1
 LOCOCO_IMPL_AUTO, LOCOCO_IMPL_GENERIC, LOCOCO_IMPL_MFMA = 0, 1, 2
 LOCOCO_FLAG_FILTERS_PREPARED = 1
 (LOCOCO_OPT_RESET, LOCOCO_OPT_SPIN_LIMIT, LOCOCO_OPT_SCAN_PER_STEP, LOCOCO_OPT_CHAIN_SYNC_DEVICE,
- LOCOCO_OPT_LOGITS_TILES, LOCOCO_OPT_MAX_RESIDENT, LOCOCO_OPT_UNFUSED_KV) = range(7)
+ LOCOCO_OPT_LOGITS_TILES, LOCOCO_OPT_MAX_RESIDENT, LOCOCO_OPT_UNFUSED_KV, LOCOCO_OPT_NO_STEP_PIPELINE) = range(8)
 
 EXPORTS = ["lococo_plan", "lococo_workspace_bytes", "lococo_attn_only", "lococo_segment_step",
            "lococo_sequence_forward", "lococo_mix_from_logits", "lococo_last_error",
@@ -69,7 +69,7 @@ class lococo_kernel_time(C.Structure):
 class lococo_path_info(C.Structure):
     _fields_ = [("path", C.c_int32), ("compute_units", C.c_int32), ("tile_slots", C.c_int32),
                 ("scan_groups", C.c_int32), ("scan_resident_limit", C.c_int32), ("position_split", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("step_pipeline", C.c_int32), ("reserved", C.c_int32)]
 
 
 class LococoError(RuntimeError):
@@ -360,7 +360,7 @@ def lococo_describe_path(cfg, B: int) -> dict:
     _check(lib().lococo_describe_path(C.byref(cfg), B, C.byref(out)))
     return {"path": out.path, "compute_units": out.compute_units, "tile_slots": out.tile_slots,
             "scan_groups": out.scan_groups, "scan_resident_limit": out.scan_resident_limit,
-            "position_split": out.position_split}
+            "position_split": out.position_split, "step_pipeline": out.step_pipeline}
 
 
 def lococo_timing_begin():

@@ -20,7 +20,7 @@ using namespace lococo;
 static __device__ __align__(256) unsigned char scratch[LOCOCO_NOALLOC_SCRATCH_BYTES];
 
 namespace {
-DebugOptions g_debug = {0, 0, 0, 0, 0, 0};
+DebugOptions g_debug = {0, 0, 0, 0, 0, 0, 0};
 }
 namespace lococo {
 const DebugOptions& debug_options() { return g_debug; }
@@ -240,7 +240,7 @@ size_t partials_ws_bytes(const lococo_config* c) {
 }
 // key-side logits between the two walks of a step over [K | V] filters (see compress_mfma.hip), 0 for filters over the keys
 size_t prelogits_ws_bytes(const lococo_config* c, int32_t B) {
-  return align_up(compress_prelogits_bytes(c->batch, c->n_kv_heads, c->M, B, c->conv_in), 256);
+  return align_up(compress_prelogits_bytes(c->batch, c->n_kv_heads, c->M, B, c->conv_in, cu_count()), 256);
 }
 // MFMA path: [repacked filters][chain sync counters + status word][row statistics of one block][results of
 // the parts of a split step][key-side logits of a step over [K | V] filters]; unfused MFMA path: [filters packed per tap][row statistics of one block][logits];
@@ -326,7 +326,9 @@ bool scan_fits_one_launch(const lococo_config* c, const StepArgs& a) {
   if (groups <= 0) return false;
   const int split = groups < c->batch * c->n_kv_heads
                         ? 1 : compress_position_split(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in, cu_count());
-  const int64_t grid = (int64_t)groups * split *
+  const int pipe = groups < c->batch * c->n_kv_heads
+                       ? 1 : compress_step_pipeline(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in, cu_count());
+  const int64_t grid = (int64_t)groups * split * pipe *
                        (c->M / compress_tile_slots(c->batch, c->n_kv_heads, c->M, c->conv_width, c->conv_in, cu_count()));
   return grid <= compress_scan_max_resident(a, cu_count());
 }
@@ -587,7 +589,7 @@ const char* lococo_version(void) { return "0.2.0"; }
 
 lococo_status lococo_debug_option(int32_t option, int64_t value) {
   switch (option) {
-    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0, 0}; return LOCOCO_OK;
+    case LOCOCO_OPT_RESET: g_debug = DebugOptions{0, 0, 0, 0, 0, 0, 0}; return LOCOCO_OK;
     case LOCOCO_OPT_SPIN_LIMIT: g_debug.spin_limit = value; return LOCOCO_OK;
     case LOCOCO_OPT_SCAN_PER_STEP: g_debug.scan_per_step = value != 0; return LOCOCO_OK;
     case LOCOCO_OPT_CHAIN_SYNC_DEVICE: g_debug.chain_sync_device = value != 0; return LOCOCO_OK;
@@ -603,6 +605,10 @@ lococo_status lococo_debug_option(int32_t option, int64_t value) {
     case LOCOCO_OPT_UNFUSED_KV:
       if (value != 0 && value != 1) return fail(LOCOCO_EINVAL, "LOCOCO_OPT_UNFUSED_KV takes 0 or 1");
       g_debug.unfused_kv = value;
+      return LOCOCO_OK;
+    case LOCOCO_OPT_NO_STEP_PIPELINE:
+      if (value != 0 && value != 1) return fail(LOCOCO_EINVAL, "LOCOCO_OPT_NO_STEP_PIPELINE takes 0 or 1");
+      g_debug.no_step_pipeline = value;
       return LOCOCO_OK;
     default: return fail(LOCOCO_EINVAL, "unknown debug option %d", option);
   }
@@ -621,6 +627,7 @@ lococo_status lococo_describe_path(const lococo_config* cfg, int32_t B, lococo_p
   if (path == PATH_MFMA) {
     out->tile_slots = compress_tile_slots(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cfg->conv_in, cu_count());
     out->position_split = compress_position_split(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cfg->conv_in, cu_count());
+    out->step_pipeline = compress_step_pipeline(cfg->batch, cfg->n_kv_heads, cfg->M, cfg->conv_width, cfg->conv_in, cu_count());
     StepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.batch = cfg->batch; a.Hkv = cfg->n_kv_heads; a.M = cfg->M; a.k_width = cfg->conv_width; a.norm = cfg->norm;

@@ -182,13 +182,21 @@ __device__ __forceinline__ Cat16 load_cat16(const CatRows& c, int p, int chunk) 
 // range of position tiles with the same pipeline and leaves its running reference, row sum and
 // unnormalised accumulators in the workspace; the part that arrives last merges them in a fixed
 // order (so the result does not depend on who is last) and writes the rows.
+// SPLIT = 2: two workgroups per (chain, slot tile) take the steps of a scan in turn.  A step of such a
+// build is walked in two legs that share the running softmax and the accumulators (the order of the
+// positions does not matter to either): first the tiles that lie wholly in the block, halo included --
+// they do not depend on the step before, so the workgroup whose turn is next works through them while
+// its partner finishes that step -- then, after the chain has been met, the tiles that touch the cache.
+// Only the second leg is on the chain's critical path.  (Single-step launches use the same build, one
+// workgroup of each pair idle, so that results do not depend on the kind of launch.)
 // CIN = 1: filters over [K | V] (two walks, see the head of the file); wp then holds the key half of
 // every bank's slices followed by the value half, each in the order above.
 template <int BM, int KW, int NORM, int PROT, int MULTI, int SPLIT, int CIN>
 __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, const uint16_t* wp,
                                                                int64_t wp_head_stride) {
   using G = Geo<BM, KW>;
-  static_assert(!SPLIT || (BM == 32 && !MULTI), "the position split is built for 32-slot tiles, one chain per workgroup");
+  static_assert(!SPLIT || (BM == 32 && !MULTI), "the splits are built for 32-slot tiles, one chain per workgroup");
+  constexpr bool PSPLIT = SPLIT == 1, PIPE = SPLIT == 2;
   static_assert(!CIN || BM == 32, "[K | V] filters are built for 32-slot tiles");
   const StepArgs& a = sa.st;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -665,7 +673,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     __syncthreads();
     return bail == 0;
   };
-  if (SPLIT && tid == 0) {
+  if (PSPLIT && tid == 0) {
     // every part registers the XCD it runs on in the census word of its (chain, tile); read at the hand-off
     const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | ((4 - 1) << 11)) & 7u;
     __hip_atomic_fetch_add(sa.psync + 2 * (grp * tiles + i0 / BM) + 1, 1u << (3u * xcd), __ATOMIC_RELAXED,
@@ -697,11 +705,15 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // half -- so that a step costs two loads of a filter slice however many chains share it.
   for (int step = 0; step < sa.n_steps; ++step)
   for (int pass = 0; pass < (CIN ? 2 : 1); ++pass) {
+  if (PIPE && (step & 1) != part) continue;            // the partner's step
   if (CIN) load_filters(pass);
   for (int ci = 0; ci < n_mine; ++ci) {
   const int ch = grp + ci * groups;
   // ---- the step reads what every slot tile of this chain wrote in the step before
-  if (pass == 0 && step > 0 && !chain_wait(ch, step)) return;
+  if (!PIPE && pass == 0 && step > 0 && !chain_wait(ch, step)) return;
+  // PIPE: the chain is met between the two legs of the walk
+  const bool meet_between = PIPE && pass == 0 && step > 0;
+  int first_blk = 0, NT_all = 0;
   // ---- this step's inputs: source state, occupancy, block
   {
     const int b = ch / a.Hkv, hkv = ch % a.Hkv;
@@ -711,7 +723,12 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     m = step == 0 ? a.m : a.M;
     T = m + Bn;
     NT = (T + BN - 1) / BN;
-    if (SPLIT) {                       // this part's range of position tiles (possibly empty)
+    if (PIPE) {                        // tiles from first_blk on read block rows only, halo included
+      NT_all = NT;
+      first_blk = (m + G::PAD + BN - 1) / BN;
+      if (first_blk > NT_all) first_blk = NT_all;
+    }
+    if (PSPLIT) {                      // this part's range of position tiles (possibly empty)
       const int per = (NT + P - 1) / P, lo = part * per;
       const int hi = lo + per < NT ? lo + per : NT;
       jbase = lo * BN;
@@ -756,6 +773,77 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
+  if constexpr (PIPE) {
+  // ---- a step in two legs (the same stages as below, as functions of the leg's range)
+  constexpr std::integral_constant<int, 1> first{};
+  constexpr std::integral_constant<int, CIN ? 2 : 0> ph{};
+  // first walk over a [K | V] bank: the key half of the filters, the key rows; summed logits to the workspace
+  auto walk_first = [&]() {
+    prologue(false);
+    stage(-1, yes, no, no, first);
+    for (int i = 0; i + 1 < NT; ++i) stage(i, yes, yes, no, first);
+    stage(NT - 1, no, yes, no, first);
+  };
+  // the walk that mixes: pipeline fill, steady state, drain
+  auto walk_main = [&]() {
+    if (CIN)
+      pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, (((SPLIT ? jbase : 0) / BN) * (BM * BN) + tid * 4) * 4, 0, kDeviceScope));
+    prologue(true);
+    stage(-1, yes, no, no, ph);                          // logits of tile 0 only
+    if (NT > 1) {
+      stage(0, yes, yes, no, ph);
+      for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes, ph);
+      stage(NT - 1, no, yes, yes, ph);
+    } else {
+      stage(0, no, yes, no, ph);
+    }
+    stage(NT, no, no, yes, ph);
+  };
+  auto zero_state = [&]() {
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[ct][rt][i] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
+  };
+  // PIPE: the range of a leg of the walk; the chain is met before the leg that touches the cache
+  auto set_leg = [&](int leg) -> bool {
+    if (leg == 0) {
+      jbase = first_blk * BN;
+      NT = NT_all - first_blk;
+    } else {
+      if (meet_between && !chain_wait(ch, step)) return false;
+      jbase = 0;
+      NT = first_blk;
+    }
+    return true;
+  };
+  if constexpr (CIN) {
+    // (the two workgroups of a pair work on different steps at the same time: an area each)
+    pre_rows = __builtin_amdgcn_make_buffer_rsrc((void*)(sa.prelogits + (int64_t)((ch * tiles + i0 / BM) * (PIPE ? 2 : 1) + (PIPE ? part : 0)) * sa.pre_stride), 0,
+                                                 (int)sa.pre_stride * 4, 0x00020000);
+    if (pass == 0) {
+      for (int leg = 0; leg < 2; ++leg) {
+        if (!set_leg(leg)) return;
+        if (NT > 0) walk_first();
+        __syncthreads();                 // the next leg's prologue writes the tiles this one read last
+      }
+      continue;
+    }
+    // ---- second walk: the value half, the value rows where the key rows were and the other way round
+    { const CatRows t = cat_k; cat_k = cat_v; cat_v = t; }
+  }
+  zero_state();
+  for (int leg = 0; leg < 2; ++leg) {
+    if (!set_leg(leg)) return;
+    if (NT > 0) walk_main();
+    if (leg == 0) __syncthreads();
+  }
+
+  } else {
   if constexpr (CIN) {
     pre_rows = __builtin_amdgcn_make_buffer_rsrc((void*)(sa.prelogits + (int64_t)(ch * tiles + i0 / BM) * sa.pre_stride), 0,
                                                  (int)sa.pre_stride * 4, 0x00020000);
@@ -807,6 +895,8 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     l_run = 0.f;
   }
 
+  }   // one walk per step
+
   uint16_t* nk;
   uint16_t* nv;
   {
@@ -815,7 +905,7 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
     nk = (uint16_t*)(CIN ? sa.out_v : sa.out_k) + out_at;
     nv = (uint16_t*)(CIN ? sa.out_k : sa.out_v) + out_at;
   }
-  if constexpr (SPLIT) {
+  if constexpr (PSPLIT) {
     // ---- this part's result goes to the workspace: accumulators [slot][2 d] as they are
     // (unnormalised, relative to this part's reference), then the references, then the row sums
     float* mine = sa.partials + ((int64_t)(ch * tiles + i0 / BM) * P + part) * G::PART_FLOATS;
@@ -1023,15 +1113,24 @@ template <int V> using ic = std::integral_constant<int, V>;
 // a step alone gives every part four position tiles (with fewer, handing the partial results over
 // costs more than the shorter walk saves: measured on the 3.5 K-token shape, M = 128).  A function of the shape and the device only:
 // every schedule and every block of a scan use the same number, so results do not depend on them.
+// Two workgroups per (chain, 32-slot tile) that take the steps of a scan in turn (SPLIT = 2 builds): whenever
+// that still fits the compute units.  A function of the shape and the device only, like the position split
+// (which it replaces where both would apply: a scan gains more from it).
+bool step_pipeline(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  if (debug_options().no_step_pipeline) return false;
+  if (use_big_tiles(batch, Hkv, M, k_width, conv_in, n_cu)) return false;
+  return (int64_t)batch * Hkv * (M / 32) * 2 <= n_cu;
+}
 int position_split(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
   if (use_big_tiles(batch, Hkv, M, k_width, conv_in, n_cu)) return 1;
+  if (step_pipeline(batch, Hkv, M, k_width, conv_in, n_cu)) return 1;
   const int64_t grid = (int64_t)batch * Hkv * (M / 32);
   int p = 1;
   while (p < 4 && grid * (2 * p) <= n_cu && M / 32 >= 4 * (2 * p)) p *= 2;
   return p;
 }
 template <class F>
-hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, int n_cu, F&& f) {
+hipError_t with_instantiation(const StepArgs& t, bool multi, int split, int n_cu, F&& f) {   // split: 0, 1 positions, 2 steps
   const bool big = use_big_tiles(t.batch, t.Hkv, t.M, t.k_width, t.conv_in, n_cu);
   auto pick_cin = [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto spl) {
     if constexpr (decltype(bm)::value == 32) {
@@ -1041,7 +1140,8 @@ hipError_t with_instantiation(const StepArgs& t, bool multi, bool split, int n_c
   };
   auto pick_multi = [&](auto bm, auto kw, auto norm, auto prot) {
     if constexpr (decltype(bm)::value == 32) {
-      if (split && !multi) return pick_cin(bm, kw, norm, prot, ic<0>{}, ic<1>{});
+      if (split == 1 && !multi) return pick_cin(bm, kw, norm, prot, ic<0>{}, ic<1>{});
+      if (split == 2 && !multi) return pick_cin(bm, kw, norm, prot, ic<0>{}, ic<2>{});
     }
     return multi ? pick_cin(bm, kw, norm, prot, ic<1>{}, ic<0>{}) : pick_cin(bm, kw, norm, prot, ic<0>{}, ic<0>{});
   };
@@ -1070,7 +1170,7 @@ hipError_t prepare_kernel() {
 
 hipError_t dispatch(const ScanArgs& a, const uint16_t* wp, int64_t wp_head_stride, int n_cu, hipStream_t s) {
   const bool multi = a.groups < a.st.batch * a.st.Hkv;
-  return with_instantiation(a.st, multi, a.psplit > 1, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ci) {
+  return with_instantiation(a.st, multi, a.pipe ? 2 : (a.psplit > 1 ? 1 : 0), n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ci) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
     constexpr int PROT = decltype(prot)::value, MULTI = decltype(mu)::value, SPLIT = decltype(sp)::value;
     constexpr int CIN = decltype(ci)::value;
@@ -1107,8 +1207,10 @@ size_t compress_mfma_filter_bytes(int M, int conv_width, int conv_in, int banks)
 // key-side logits of the first walk of a [K | V] bank: per (chain, 32-slot tile), one 32 x 32 fp32 tile per
 // position tile of the longest step
 static int64_t prelogits_stride(int M, int B) { return (int64_t)((M + B + BN - 1) / BN) * 32 * BN; }
-size_t compress_prelogits_bytes(int batch, int Hkv, int M, int B, int conv_in) {
-  return conv_in ? (size_t)batch * Hkv * (M / 32) * prelogits_stride(M, B) * sizeof(float) : 0;
+size_t compress_prelogits_bytes(int batch, int Hkv, int M, int B, int conv_in, int n_cu) {
+  const int64_t pairs = (int64_t)batch * Hkv * (M / 32);
+  const int areas = pairs * 2 <= n_cu ? 2 : 1;     // one per workgroup of a pair that takes the steps in turn
+  return conv_in ? (size_t)pairs * areas * prelogits_stride(M, B) * sizeof(float) : 0;
 }
 
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s) {
@@ -1131,6 +1233,9 @@ static uint32_t* psync_of(void* sync_ws, int batch, int Hkv) { return (uint32_t*
 
 int compress_position_split(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
   return position_split(batch, Hkv, M, k_width, conv_in, n_cu);
+}
+int compress_step_pipeline(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
+  return step_pipeline(batch, Hkv, M, k_width, conv_in, n_cu) ? 2 : 1;
 }
 // room for every part's result of one step: [chain][tile][part] x (32 x 2 d accumulators + 32 references + 32 sums)
 size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu) {
@@ -1171,9 +1276,11 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
   // fewer than half as many: the positions of the step are shared out between several workgroups,
   // whose count per (chain, tile) starts at zero
   sa.psplit = sa.groups < a.batch * a.Hkv ? 1 : position_split(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu);
+  sa.pipe = sa.groups == a.batch * a.Hkv && step_pipeline(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu) ? 1 : 0;
   sa.partials = (float*)partials;
   sa.psync = psync_of(sync_ws, a.batch, a.Hkv);
-  if (sa.psplit > 1) {
+  if (sa.pipe) sa.psplit = 2;            // (workgroups per pair; nothing is handed over)
+  if (sa.psplit > 1 && !sa.pipe) {
     hipLaunchKernelGGL(zero_words_k, dim3(1), dim3(256), 0, s, sa.psync, 2 * a.batch * a.Hkv * (a.M / 32), sa.psync, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1190,7 +1297,8 @@ int compress_scan_max_resident(const StepArgs& a, int n_cu) {
   if (debug_options().max_resident > 0) return (int)debug_options().max_resident;
   const int groups = compress_scan_groups(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, a.w_head_stride != 0 || a.b_head_stride != 0, n_cu);
   const bool multi = groups < a.batch * a.Hkv;
-  const bool split = !multi && position_split(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu) > 1;
+  const int split = multi ? 0 : step_pipeline(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu) ? 2
+                    : position_split(a.batch, a.Hkv, a.M, a.k_width, a.conv_in, n_cu) > 1 ? 1 : 0;
   int per_cu = 0;
   hipError_t e = with_instantiation(a, multi, split, n_cu, [&](auto bm, auto kw, auto norm, auto prot, auto mu, auto sp, auto ci) {
     constexpr int BM = decltype(bm)::value, KW = decltype(kw)::value, NORM = decltype(norm)::value;
@@ -1233,6 +1341,8 @@ hipError_t launch_compress_scan(const ScanArgs& a_in, const void* wp, int banks,
   a.pre_stride = prelogits_stride(a.st.M, a.B > a.st.Bn ? a.B : a.st.Bn);
   if (a.groups <= 0) return hipErrorInvalidValue;   // the caller keeps such shapes away
   a.psplit = a.groups < chains ? 1 : position_split(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width, a.st.conv_in, n_cu);
+  a.pipe = a.groups == chains && step_pipeline(a.st.batch, a.st.Hkv, a.st.M, a.st.k_width, a.st.conv_in, n_cu) ? 1 : 0;
+  if (a.pipe) a.psplit = 2;
   a.partials = (float*)partials;
   a.psync = psync_of(sync_ws, a.st.batch, a.st.Hkv);
   const int64_t wp_head_stride = banks > 1 ? (int64_t)a.st.M * a.st.k_width * kD * (a.st.conv_in ? 2 : 1) : 0;

@@ -17,6 +17,7 @@ struct DebugOptions {
   int64_t logits_tiles;       // 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused MFMA path
   int64_t max_resident;       // > 0: pretend that only this many workgroups of the scan kernel fit the GPU at once
   int64_t unfused_kv;         // 1: [K | V] filters on the unfused MFMA path
+  int64_t no_step_pipeline;   // 1: no pairs of workgroups that take the steps of a scan in turn
 };
 const DebugOptions& debug_options();
 // compute units of the current device
@@ -75,6 +76,7 @@ struct ScanArgs {
   int32_t same_l2_allowed;   // 0: always meet with device-scope release / acquire (see compress_mfma.hip)
   int32_t groups;            // workgroups per slot tile; group g runs chains g, g + groups, ... (filled in by the launcher)
   int32_t psplit;            // workgroups that share out the positions of a step of one (chain, slot tile); 1 = no split (launcher)
+  int32_t pipe;              // 1: two workgroups per (chain, slot tile) take the steps in turn (psplit = 2 then; launcher)
   float* partials;           // where the parts of a split step leave their results (launcher)
   uint32_t* psync;           // per (chain, 32-slot tile): parts that have handed in (launcher)
   float* prelogits;          // [K | V] filters: key-side logits between the two walks of a step (launcher)
@@ -162,7 +164,7 @@ bool compress_mfma_supports(int dtype, int d, int M, int conv_width, int conv_in
 size_t compress_mfma_filter_bytes(int M, int conv_width, int conv_in, int banks);
 // bytes the kernel needs between the two walks of a step over a [K | V] bank (0 for filters over the keys);
 // B: the longest block of the call
-size_t compress_prelogits_bytes(int batch, int Hkv, int M, int B, int conv_in);
+size_t compress_prelogits_bytes(int batch, int Hkv, int M, int B, int conv_in, int n_cu);
 // conv_w [M][C][k] (+ w_head_stride per bank) -> wp [bank][M][k][C]
 hipError_t launch_repack_filters(const StepArgs& a, void* wp, int banks, hipStream_t s);
 // Eq. 5 + Eq. 6 + Eq. 4a/4b in one kernel; writes a.new_k / a.new_v
@@ -172,6 +174,8 @@ hipError_t launch_compress_mfma(const StepArgs& a, const void* wp, int banks, in
                                 void* partials, void* prelogits, int B, hipStream_t s);
 // workgroups per (chain, slot tile) that share out the positions of a step (1: no split)
 int compress_position_split(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu);
+// workgroups per (chain, slot tile) that take the steps of a scan in turn: 2, or 1 where the shape does not
+int compress_step_pipeline(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu);
 size_t compress_partials_bytes(int batch, int Hkv, int M, int k_width, int conv_in, int n_cu);
 // Workgroups per slot tile with which all steps of a scan run in one launch, every workgroup
 // resident at once (each takes every groups-th chain); 0 if there is no such number.  per_head:

@@ -194,7 +194,8 @@ def test_debug_options_are_validated_and_path_description_needs_no_gpu_for_gener
     assert L.lococo_debug_option(lb.LOCOCO_OPT_LOGITS_TILES, 100) == lb.LOCOCO_EINVAL
     assert L.lococo_debug_option(lb.LOCOCO_OPT_MAX_RESIDENT, -3) == lb.LOCOCO_EINVAL
     assert L.lococo_debug_option(lb.LOCOCO_OPT_UNFUSED_KV, 2) == lb.LOCOCO_EINVAL
-    assert L.lococo_debug_option(7, 0) == lb.LOCOCO_EINVAL
+    assert L.lococo_debug_option(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 5) == lb.LOCOCO_EINVAL
+    assert L.lococo_debug_option(8, 0) == lb.LOCOCO_EINVAL
     assert L.lococo_debug_option(lb.LOCOCO_OPT_LOGITS_TILES, 128) == lb.LOCOCO_OK
     assert L.lococo_debug_option(lb.LOCOCO_OPT_RESET, 0) == lb.LOCOCO_OK
     info = lb.lococo_describe_path(_cfg(), 4)          # fp32, head_dim 8: the shape-agnostic kernels

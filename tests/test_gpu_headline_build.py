@@ -197,16 +197,20 @@ def test_one_hot_logits_select_tokens_bit_exactly_on_the_mfma_kernel(shape):
     assert torch.equal(cache.k, cat_k[:, :, perm]) and torch.equal(cache.v, cat_v[:, :, perm])
 
 
-@pytest.mark.parametrize("name,split", [("cfg2", 1), ("cfg5", 2), ("cfg3", 1), ("cfg4", 1)])
-def test_which_shapes_split_the_positions_of_a_step(name, split):
-    """The GQA workload (16 chains x 8 slot tiles) leaves half of the compute units without a (chain,
-    slot tile) pair: two workgroups share out the positions of every step.  The 3.5 K-token shape
-    (M = 128: four position tiles of cache) is too short for the hand-over to pay."""
+@pytest.mark.parametrize("name,pipe,split", [("cfg2", 2, 1), ("cfg5", 2, 2), ("cfg3", 1, 1), ("cfg4", 1, 1)])
+def test_which_shapes_use_idle_compute_units(name, pipe, split, options):
+    """The 3.5 K-token workload and the GQA workload (128 (chain, slot tile) pairs each) leave half of the
+    compute units without a pair: two workgroups per pair take the steps of the scan in turn.  Without that
+    (a test hook), two workgroups share out the positions of every step of the GQA workload; the 3.5 K-token
+    shape (M = 128: four position tiles of cache) is too short for that hand-over to pay."""
     w = inputs.CONFIGS[name]
     info = lb.lococo_describe_path(lb.config_for(w), w.B)
-    assert info["position_split"] == split, info
+    assert info["step_pipeline"] == pipe and info["position_split"] == 1, info
     if info["compute_units"] == 256:
         assert info["scan_groups"] > 0, info
+    options(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 1)
+    info = lb.lococo_describe_path(lb.config_for(w), w.B)
+    assert info["step_pipeline"] == 1 and info["position_split"] == split, info
 
 
 @pytest.mark.parametrize("case", [
@@ -229,6 +233,7 @@ def test_split_steps_match_the_oracle_and_every_schedule(case, options):
     share = case.pop("protect_share", 0.0)
     w = _w(**case)
     cfg = lb.config_for(w, impl=MFMA)
+    options(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 1)       # (by default such shapes pair their workgroups over the steps instead)
     info = lb.lococo_describe_path(cfg, w.B)
     assert info["position_split"] > 1 and info["tile_slots"] == 32, info
     q, k, v = inputs.qkv(w)
@@ -252,12 +257,69 @@ def test_split_steps_match_the_oracle_and_every_schedule(case, options):
     print(case, info["position_split"], {k_: (f"{e_[0]:.2e}", f"{e_[1]:.2e}") for k_, e_ in errs.items()})
 
 
-def test_split_generation_steps():
+PIPE_CASES = [
+    dict(M=128, B=128, L=1024),                                                          # the 3.5 K-token shape cut down: three block-only tiles, the chain met inside the prologue
+    dict(M=256, B=256, L=2048, n_q_heads=8, n_kv_heads=4, batch=2),                      # the GQA shape cut down: seven block-only tiles, met before stage 3
+    dict(M=128, B=160, L=1000),                                                          # four block-only tiles: met before stage 0; ragged last block
+    dict(M=256, B=64, L=900, n_q_heads=4, n_kv_heads=2),                                 # short blocks: one block-only tile, met at once; four fills
+    dict(M=128, B=96, L=700, qk_gain=6.0, conv_gain=4.0),                                # peaked rows; partly filled cache at the first compress
+    dict(M=256, B=200, L=1100, norm=1, bias_sigma=0.5),                                  # relu-sum, T = 456
+    dict(M=128, B=128, L=896, conv_width=21, per_head_filters=True, bias_sigma=0.5),     # width 21, per-head banks
+    dict(M=256, B=128, L=896, protect_share=0.15),                                       # protected slots
+    dict(M=128, B=128, L=896, conv_in=1, conv_width=21, norm=1, bias_sigma=0.4),         # [K | V] filters: two walks per turn
+    dict(M=512, B=512, L=3072, n_q_heads=4, n_kv_heads=4),                               # 64 pairs, 32 position tiles
+]
+
+
+@pytest.mark.parametrize("case", PIPE_CASES, ids=[str(i) for i in range(len(PIPE_CASES))])
+def test_pairs_of_workgroups_that_take_the_steps_in_turn(case, options):
+    """Shapes with at most half as many (chain, slot tile) pairs as compute units: two workgroups per pair, each
+    taking every other step of the scan and walking its step from the last position tile down, so that the
+    block-only tiles are done while the partner finishes the step before.  Equal to the oracle; bit-identical
+    between one launch per scan, one launch per step, block by block through lococo_segment_step (where one
+    workgroup of each pair idles), windows of three blocks, and either form of the chain meeting.  The same
+    shapes without the pairs (a test hook) meet the same tolerance."""
+    case = dict(case)
+    share = case.pop("protect_share", 0.0)
+    w = _w(**case)
+    cfg = lb.config_for(w, impl=MFMA)
+    info = lb.lococo_describe_path(cfg, w.B)
+    assert info["step_pipeline"] == 2 and info["position_split"] == 1 and info["tile_slots"] == 32, info
+    if info["compute_units"] == 256:
+        assert info["scan_groups"] > 0, info
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    protect = (np.random.default_rng(5).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    b = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=False, protect=protect)
+    c = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, step_by_step=True, protect=protect)
+    d = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=3, protect=protect)
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 1)
+    e = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    options(lb.LOCOCO_OPT_CHAIN_SYNC_DEVICE, 0)
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 1)
+    f = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    options(lb.LOCOCO_OPT_SCAN_PER_STEP, 0)
+    for other in (b, c, d, e, f):
+        for x, y in zip(a[:3], other[:3]):
+            assert torch.equal(x, y)
+        assert a[3:] == other[3:]
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    errs = compare_scan(w, a, want, what="steps in turn")
+    print(case, {k_: (f"{e_[0]:.2e}", f"{e_[1]:.2e}") for k_, e_ in errs.items()})
+    options(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 1)
+    assert lb.lococo_describe_path(cfg, w.B)["step_pipeline"] == 1
+    g = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+    compare_scan(w, g, want, what="without the pairs")
+
+
+def test_split_generation_steps(options):
     """B = 1 on a shape that splits: T = M + 1, the last part holds the new token's tile."""
     w = _w(M=512, B=128, L=512 + 10, n_q_heads=4, n_kv_heads=2)
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
     cfg = lb.config_for(w, impl=MFMA)
+    options(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 1)
     assert lb.lococo_describe_path(cfg, 1)["position_split"] > 1
     sl = lambda t, a_, b_: t[:, :, a_:b_]
     P = 512

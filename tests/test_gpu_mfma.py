@@ -21,7 +21,17 @@ def _w(**kw):
     return inputs.Workload(**base)
 
 
-def _run(w, **kw):
+def _run(w, pairs=True, **kw):
+    # (few chains: by default two workgroups per (chain, slot tile) take the steps in turn; pairs = False
+    # runs the plain builds, one workgroup each)
+    lb.lococo_debug_option(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 0 if pairs else 1)
+    try:
+        return _run_inner(w, **kw)
+    finally:
+        lb.lococo_debug_option(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 0)
+
+
+def _run_inner(w, **kw):
     q, k, v = inputs.qkv(w)
     cw, cb = inputs.conv_filters(w)
     want = oracle_forward(w, q, k, v, cw, cb, nthreads=16)
@@ -45,8 +55,9 @@ def _run(w, **kw):
     dict(per_head_filters=True, bias_sigma=0.5),
     dict(tok_lognormal_sigma=0.5, seed=11),
 ])
-def test_mfma_scan_matches_oracle(case):
-    errs = _run(_w(**case))
+@pytest.mark.parametrize("pairs", [True, False], ids=["pairs", "plain"])
+def test_mfma_scan_matches_oracle(case, pairs):
+    errs = _run(_w(**case), pairs=pairs)
     print(case, {k: (f"{e[0]:.2e}", f"{e[1]:.2e}") for k, e in errs.items()})
 
 
@@ -345,9 +356,16 @@ def test_fused_kernel_with_filters_over_keys_and_values(case, options):
     cw, cb = inputs.conv_filters(w)
     protect = (np.random.default_rng(6).random((w.batch, w.n_kv_heads, w.M)) < share) if share else None
     cfg = lb.config_for(w, impl=MFMA)
+    pairs = w.batch * w.n_kv_heads * (w.M // 32)
+    options(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 1)       # first without the pairs of workgroups over the steps
     info = lb.lococo_describe_path(cfg, w.B)
     assert info["path"] == 1 and info["tile_slots"] == 32 and info["position_split"] == split, info
     want = oracle_forward(w, q, k, v, cw, cb, nthreads=16, protect=protect)
+    if 2 * pairs <= info["compute_units"]:
+        plain = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
+        compare_scan(w, plain, want, what="fused [K | V], one workgroup per pair or a position split")
+        options(lb.LOCOCO_OPT_NO_STEP_PIPELINE, 0)
+        assert lb.lococo_describe_path(cfg, w.B)["step_pipeline"] == 2
     lb.lococo_timing_begin()
     a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, protect=protect)
     ran = lb.lococo_timing_end()
