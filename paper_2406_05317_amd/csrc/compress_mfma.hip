@@ -774,7 +774,10 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
   if constexpr (PIPE) {
-  // ---- a step in two legs (the same stages as below, as functions of the leg's range)
+  // ---- a step in two legs: the same sequence of stages as the one-walk form below, as functions of the
+  // leg's range.  The two forms are kept apart on purpose: the one-walk builds' register allocation is
+  // tight (all 512 registers in use) and has answered to small changes of this code with spills inside the
+  // stage loop, so they keep their code as it was.
   constexpr std::integral_constant<int, 1> first{};
   constexpr std::integral_constant<int, CIN ? 2 : 0> ph{};
   // first walk over a [K | V] bank: the key half of the filters, the key rows; summed logits to the workspace
