@@ -585,7 +585,7 @@ lococo_status scratch_on_this_device(void** out) {
 extern "C" {
 
 const char* lococo_last_error(void) { return g_err; }
-const char* lococo_version(void) { return "0.2.0"; }
+const char* lococo_version(void) { return "0.3.0"; }
 
 lococo_status lococo_debug_option(int32_t option, int64_t value) {
   switch (option) {
