@@ -213,9 +213,9 @@ LOCOCO_API lococo_status lococo_segment_step(const lococo_config* cfg, const loc
  * or event creation; the optional kernel timing of lococo_timing_begin, which creates events, must
  * be off).
  *   - A step whose lococo_workspace_bytes(cfg, B, B, 0) exceeds the array is refused with
- *     LOCOCO_EWORKSPACE (enough for every shape of the fused path: 32 heads, M = 512, width 15 needs
- *     2.1 MB, 32 heads with M = 128, whose steps are split over two workgroups per slot tile, 9 MB; not
- *     for the logits of large shapes on the other paths).
+ *     LOCOCO_EWORKSPACE (enough for the fused path with filters over the keys: 32 heads, M = 512,
+ *     width 15 needs 2.1 MB; not for the logits of large shapes on the other paths, nor for the
+ *     key-side logits of large shapes with filters over [K | V]).
  *   - LOCOCO_FLAG_FILTERS_PREPARED is refused (LOCOCO_EINVAL): the array is shared by every caller on
  *     the device and keeps whatever the last call left in it, so each call repacks the filters itself.
  *   - Calls that overlap on one GPU (two streams, two threads) race on the array: the caller must
@@ -258,8 +258,8 @@ LOCOCO_API lococo_status lococo_sequence_forward(const lococo_config* cfg, const
 LOCOCO_API lococo_status lococo_scan_status(const lococo_config* cfg, const void* workspace, int32_t* out);
 
 /* Test and measurement hooks, process-wide, not thread safe against running calls; none changes
- * what is computed except LOCOCO_OPT_LOGITS_TILES = 256, which adds up Eq. 5's fp32 sum in another
- * order.  (Nothing in the library reads environment variables.) */
+ * what is computed, and only those that say so below change the order of an fp32 sum (so the last
+ * bits).  (Nothing in the library reads environment variables.) */
 enum {
   LOCOCO_OPT_RESET = 0,             /* every option back to its default; value ignored                         */
   LOCOCO_OPT_SPIN_LIMIT = 1,        /* polls a waiting workgroup of the one-launch scan makes before it gives
@@ -269,7 +269,8 @@ enum {
                                        acquire (default: without the L2 write-back when they find themselves
                                        on one XCD)                                                             */
   LOCOCO_OPT_LOGITS_TILES = 4,      /* 64 | 128 | 256: slots per workgroup of the Eq. 5 kernel of the unfused
-                                       MFMA path (0 = chosen from the grid size; 256 needs more than 128 slots) */
+                                       MFMA path (0 = chosen from the grid size; 256 needs more than 128 slots
+                                       and adds up Eq. 5's fp32 sum in another order)                          */
   LOCOCO_OPT_MAX_RESIDENT = 5,      /* > 0: pretend the device holds only this many workgroups of the scan
                                        kernel at once (exercises the fall-back to one launch per step)         */
   LOCOCO_OPT_UNFUSED_KV = 6,        /* 1: filters over [K | V] go to the unfused MFMA path (Eq. 5 as a kernel
