@@ -948,7 +948,16 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         if ((st = enqueue_compress(cfg, path, a, workspace, B, s))) return st;
         ++c_done;
       }
-      {
+      // A block of one token (every block when B = 1, else a ragged last block) goes to the kernel of the
+      // generation stage here as in the step-by-step schedule: which kernel a block's attention runs on depends on
+      // the block, never on the schedule, so the bits do not either.  Such blocks can only end a window, and they
+      // come after the window's other blocks, as they do in time (the order matters to sums kept per slot).
+      int64_t w_batched = w1;
+      while (w_batched > w0 && path != PATH_GENERIC &&
+             attn_decode_supports(cfg->dtype, cfg->head_dim, plan[(size_t)(w_batched - 1)].len, cfg->M,
+                                  cache->attn_colsum != nullptr))
+        --w_batched;
+      if (w_batched > w0) {
         const lococo_seg& first = plan[(size_t)w0];
         StepArgs a0 = make_args(cfg, seq, first.start, B, &tmp, conv_w, conv_b, true);
         AttnArgs t = attn_args_one_block(a0);
@@ -959,11 +968,11 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         t.hist_stride = hist_stride;
         t.hist_first = (int32_t)(c0 % ring);
         t.hist_ring = (int32_t)ring;
-        t.L = std::min<int64_t>(L - first.start, (w1 - w0) * (int64_t)B);
+        t.L = std::min<int64_t>(L - first.start, (w_batched - w0) * (int64_t)B);
         t.B = B;
         t.len0 = first.len_before;
-        t.n_fill = (int32_t)fills;
-        t.n_seg = (int32_t)(w1 - w0);
+        t.n_fill = (int32_t)std::min<int64_t>(fills, w_batched - w0);
+        t.n_seg = (int32_t)(w_batched - w0);
         t.stats = cache->attn_colsum ? win_stats : nullptr;
         {
           KTimer kt(K_ATTN_MFMA, s);
@@ -972,6 +981,21 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
         if (cache->attn_colsum) {           // sums over blocks commute: one launch for all of the window's
           KTimer kt(K_ATTN_COLSUM, s);
           HIP_TRY(launch_attn_colsum_mfma(t, cache->attn_colsum, s), "attention column-sum launch");
+        }
+      }
+      if (w_batched < w1) {
+        int64_t c_before = c0;                  // compress steps ahead of block bi
+        for (int64_t bi = w0; bi < w1; ++bi) {
+          const lococo_seg& sg = plan[(size_t)bi];
+          if (bi >= w_batched) {
+            StepArgs a = make_args(cfg, seq, sg.start, sg.len, &tmp, conv_w, conv_b, true);
+            a.m = sg.len_before;
+            a.cache_k = c_before == 0 ? tmp.k[tmp.cur] : slot_k(c_before - 1);
+            a.cache_v = c_before == 0 ? tmp.v[tmp.cur] : slot_v(c_before - 1);
+            KTimer kt(K_ATTN_DECODE, s);
+            HIP_TRY(launch_attn_decode(a, s), "attention launch");
+          }
+          if (sg.branch != 0) ++c_before;
         }
       }
     }

@@ -86,6 +86,48 @@ def test_mfma_batched_attention_schedule(case):
 
 
 @pytest.mark.parametrize("case", [
+    dict(M=64, B=1, L=6, len0=64),                        # generation with known tokens, from a full cache
+    dict(M=128, B=1, L=5, len0=126, n_q_heads=8, n_kv_heads=2),   # two fills, then compressions
+    dict(M=128, B=64, L=4 * 64 + 1),                      # a ragged last block of one token
+    dict(M=128, B=64, L=4 * 64 + 1, window=2),            # ... alone in the last window
+])
+def test_blocks_of_one_token_take_the_same_kernel_in_every_schedule(case):
+    """Which kernel a block's attention runs on depends on the block alone: a block of one token goes to
+    the generation-stage kernel whether the blocks are taken one by one or their attention is batched, so
+    every schedule returns the same bits."""
+    case = dict(case)
+    len0, G = case.pop("len0", 0), case.pop("window", 3)
+    w = _w(**case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    cache = None
+    if len0:
+        gen = torch.Generator().manual_seed(3)
+        ck = (torch.randn(w.batch, w.n_kv_heads, w.M, w.head_dim, generator=gen) / 11).to(torch.bfloat16)
+        cv = (torch.randn(w.batch, w.n_kv_heads, w.M, w.head_dim, generator=gen) / 11).to(torch.bfloat16)
+        ck[:, :, len0:] = 0
+        cv[:, :, len0:] = 0
+        cache = (ck, cv, len0)
+    want = oracle_forward(w, q, k, v, cw, cb, nthreads=16,
+                          cache=None if cache is None else (ck.double().numpy(), cv.double().numpy(), len0))
+    lb.lococo_timing_begin()
+    a = gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=True, cache_init=cache)
+    ran = lb.lococo_timing_end()
+    single = w.L if w.B == 1 else int(w.L % w.B == 1)
+    assert ran.get("attn_decode", (0, 0))[0] == single, ran
+    assert (ran.get("attn_mfma", (0, 0))[0] > 0) == (w.B > 1), ran
+    assert a[3] == w.M
+    compare_scan(w, a, want, what="blocks of one token")
+    others = [gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=G, cache_init=cache),
+              gpu_forward(w, q, k, v, cw, cb, impl=MFMA, history=False, cache_init=cache),
+              gpu_forward(w, q, k, v, cw, cb, impl=MFMA, step_by_step=True, cache_init=cache)]
+    for other in others:
+        for x, y in zip(a[:3], other[:3]):
+            assert torch.equal(x, y)
+        assert a[3:] == other[3:]
+
+
+@pytest.mark.parametrize("case", [
     dict(M=128, B=64, L=1024, window=3),                               # two fills; windows of 3: fills + one compress, then compress only
     dict(M=128, B=128, L=1500, window=2),                              # ragged last block in a window of its own
     dict(M=256, B=64, L=1024, window=2, n_q_heads=8, n_kv_heads=2),    # four fills: the fill phase spans two windows
