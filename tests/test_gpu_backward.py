@@ -115,6 +115,58 @@ def test_step_backward_matches_the_oracle(case):
     print(case["name"], {n: f"{e:.1e}" for n, e in errs.items()})
 
 
+def _draw_step(i):
+    rng = np.random.default_rng(17000 + i)
+    ch = lambda xs: xs[int(rng.integers(len(xs)))]
+    dtype = ch(["bf16", "bf16", "f32"])
+    d = ch([64, 128, 128, 128]) if dtype == "bf16" else ch([8, 16, 32, 64])
+    M = ch([12, 20, 32, 48, 64, 96, 128, 160, 192, 256])
+    Hkv = ch([1, 2, 3])
+    case = dict(dtype=dtype, head_dim=d, M=M, B=ch([1, 6, 24, 33, 40, 64, 100, 128, 200]),
+                conv_width=ch([1, 3, 5, 7, 15, 21]), norm=ch([0, 0, 1]), conv_in=ch([0, 0, 1]),
+                per_head_filters=ch([False, False, True]), bias_sigma=ch([0.0, 0.4]), n_kv_heads=Hkv,
+                n_q_heads=Hkv * ch([1, 2, 4]), batch=ch([1, 2]), conv_gain=ch([1.0, 3.0]))
+    return case, ch([M, M, int(rng.integers(0, M + 1))]), ch([0, 1]), ch([False, False, True]), rng
+
+
+@pytest.mark.parametrize("i", range(40))
+def test_step_backward_on_a_drawn_case(i):
+    """A seeded sweep over storage type, sizes, occupancy, filter width, normalisation, convolution input, filter
+    sharing, grouped heads, protected slots and kernel family: every gradient against the oracle's."""
+    case, m, impl, use_protect, rng = _draw_step(i)
+    w = inputs.Workload(name=f"bwd{i}", L=case["B"], seed=17000 + i, **case)
+    q, k, v = inputs.qkv(w)
+    cw, cb = inputs.conv_filters(w)
+    chains = (w.batch, w.n_kv_heads, w.M, w.head_dim)
+    ck = torch.as_tensor(rng.standard_normal(chains) * 0.5).to(w.torch_dtype)
+    cv = torch.as_tensor(rng.standard_normal(chains) * 0.5).to(w.torch_dtype)
+    ck[:, :, m:], cv[:, :, m:] = 0, 0
+    d_o = rng.standard_normal(q.shape)
+    gk, gv = rng.standard_normal(chains), rng.standard_normal(chains)
+    ln = min(w.M, m + w.B)
+    gk[:, :, ln:], gv[:, :, ln:] = 0.0, 0.0
+    protect = (rng.random((w.batch, w.n_kv_heads, w.M)) < 0.2) if use_protect else None
+    want = orc.step_backward(q, k, v, ck, cv, m, cw, cb, d_o, gk, gv, M=w.M, conv_in=w.conv_in, norm=w.norm,
+                             protect=protect)
+    cfg = lb.config_for(w, impl=impl)
+    dW = torch.zeros(cw.shape, dtype=torch.float32, device="cuda")
+    dB = None if cb is None else torch.zeros(cb.shape, dtype=torch.float32, device="cuda")
+    got = _gpu_step_backward(w, cfg, q, k, v, cw, cb, ck, cv, m, d_o, gk, gv, dW, dB, protect)
+    got["d_conv_w"], got["d_conv_b"] = dW.cpu().numpy(), None if dB is None else dB.cpu().numpy()
+    what = f"{w} m={m} impl={impl} protect={use_protect}"
+    for n in ("dq", "dk", "dv", "d_cache_k", "d_cache_v", "d_conv_w", "d_conv_b"):
+        if want[n] is None:
+            continue
+        if m + w.B <= w.M and n in ("d_conv_w", "d_conv_b"):
+            assert not got[n].any(), (n, what)
+        elif n == "d_conv_b" and w.norm == 0:
+            assert np.abs(got[n]).max() < 1e-5 * max(np.abs(want["d_conv_w"]).max(), 1e-30), (n, what)
+        else:
+            assert np.all(np.isfinite(got[n])), (n, what)
+            assert _rel(got[n], want[n]) < 2e-4, (n, _rel(got[n], want[n]), what)
+    assert not got["d_cache_k"][:, :, m:].any() and not got["d_cache_v"][:, :, m:].any()
+
+
 def test_scan_backward_in_reverse_matches_the_oracle_and_a_directional_difference():
     """Three block steps (fill, compress, compress): forward on the GPU keeping the cache states,
     backward step by step in reverse, filter gradients collected in one buffer.  Checked against
