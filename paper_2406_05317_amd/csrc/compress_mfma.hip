@@ -345,21 +345,26 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // wait on the LDS counter only.
   // PH: 0 = the one walk of a bank over the keys; 1 = first walk of a [K | V] bank (logits of the key
   // half only: DoSoftmax then means "sum the waves' partial logits and store them"); 2 = its second walk.
-  auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t, auto ph_t) {
+  // RI: the tile index modulo the period of the buffer rings (key tiles: NXBUF; values, probabilities,
+  // rescale factors: 2) where the caller knows it at compile time, so that every buffer address of the
+  // stage is a constant; -1: computed from i.
+  auto stage = [&](int i, auto do_conv, auto do_softmax, auto do_mix_t, auto ph_t, auto ring_t) {
     constexpr bool DoConv = decltype(do_conv)::value, DoSoftmax = decltype(do_softmax)::value;
     constexpr bool DoMix = decltype(do_mix_t)::value;
     constexpr int PH = decltype(ph_t)::value;
+    constexpr int RI = decltype(ring_t)::value;
+    const int ib = RI >= 0 ? RI + 2 * G::NXBUF : i;      // (kept positive: ib - 1 enters a remainder)
     const int j0 = (SPLIT ? jbase : 0) + i * BN;
-    const unsigned char* Xnext = Xs0 + ((i + 1) % G::NXBUF) * G::XBYTES;
-    const unsigned char* Xnext2 = Xs0 + ((i + 2) % G::NXBUF) * G::XBYTES;
-    const unsigned char* Xprev = Xs0 + ((i + G::NXBUF - 1) % G::NXBUF) * G::XBYTES;
-    unsigned char* Xstage = Xs0 + ((i + 3) % G::NXBUF) * G::XBYTES;
-    const unsigned char* Vprev = Vs0 + ((i - 1) & 1) * G::VBYTES;
-    unsigned char* Vstage = Vs0 + (i & 1) * G::VBYTES;
-    unsigned char* Pcur = Ps0 + (i & 1) * G::PBYTES;
-    const unsigned char* Pprev = Ps0 + ((i - 1) & 1) * G::PBYTES;
-    float* alpha_cur = alphas0 + (i & 1) * BM;
-    const float* alpha_prev = alphas0 + ((i - 1) & 1) * BM;
+    const unsigned char* Xnext = Xs0 + ((ib + 1) % G::NXBUF) * G::XBYTES;
+    const unsigned char* Xnext2 = Xs0 + ((ib + 2) % G::NXBUF) * G::XBYTES;
+    const unsigned char* Xprev = Xs0 + ((ib + G::NXBUF - 1) % G::NXBUF) * G::XBYTES;
+    unsigned char* Xstage = Xs0 + ((ib + 3) % G::NXBUF) * G::XBYTES;
+    const unsigned char* Vprev = Vs0 + ((ib - 1) & 1) * G::VBYTES;
+    unsigned char* Vstage = Vs0 + (ib & 1) * G::VBYTES;
+    unsigned char* Pcur = Ps0 + (ib & 1) * G::PBYTES;
+    const unsigned char* Pprev = Ps0 + ((ib - 1) & 1) * G::PBYTES;
+    float* alpha_cur = alphas0 + (ib & 1) * BM;
+    const float* alpha_prev = alphas0 + ((ib - 1) & 1) * BM;
 
     // logits: operands of step st come from this stage's key tile, those of steps >= NS are the
     // first operands of the next stage's tile
@@ -773,6 +778,38 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
+  constexpr std::integral_constant<int, -1> dyn{};
+  // The steady stages with the phase of the buffer rings known at compile time: one copy of the stage per
+  // residue of the tile index modulo 2 * NXBUF, chained, so that the ring addresses are constants (about 30
+  // scalar and 14 vector instructions per stage otherwise).  Ten copies of a stage still fit the instruction
+  // cache.  Built where the register allocation takes it without spilling (32-slot tiles, width 15, filters over
+  // the keys; measured: 3 % on the smaller and 9 % on the larger of the shapes that run on pairs of workgroups);
+  // the 64-slot builds answered with spills inside the copies and ran 1.6 times as long (two copies, with only the
+  // parity of the index a constant, did not spill and gained 0.7 %, but the launch then fetched 18 % more from
+  // HBM), so they and every other build keep the one copy.
+  constexpr bool RINGU = BM == 32 && KW == 15 && !CIN && SPLIT != 1 && !(PROT && SPLIT == 2);
+  auto steady_unrolled = [&](auto ph_t) {
+    int i = 1;
+    auto one = [&](auto r_t) {
+      if (!(i + 1 < NT)) return false;
+      stage(i, yes, yes, yes, ph_t, r_t);
+      ++i;
+      return true;
+    };
+    for (;;) {
+      if (!one(std::integral_constant<int, 1>{})) break;
+      if (!one(std::integral_constant<int, 2>{})) break;
+      if (!one(std::integral_constant<int, 3>{})) break;
+      if (!one(std::integral_constant<int, 4>{})) break;
+      if (!one(std::integral_constant<int, 5>{})) break;
+      if (!one(std::integral_constant<int, 6>{})) break;
+      if (!one(std::integral_constant<int, 7>{})) break;
+      if (!one(std::integral_constant<int, 8>{})) break;
+      if (!one(std::integral_constant<int, 9>{})) break;
+      if (!one(std::integral_constant<int, 0>{})) break;
+    }
+  };
+  static_assert(G::NXBUF == 5 && G::NVBUF == 2, "the unrolled steady stages assume a ring period of ten");
   if constexpr (PIPE) {
   // ---- a step in two legs: the same sequence of stages as the one-walk form below, as functions of the
   // leg's range.  The two forms are kept apart on purpose: the one-walk builds' register allocation is
@@ -783,24 +820,36 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   // first walk over a [K | V] bank: the key half of the filters, the key rows; summed logits to the workspace
   auto walk_first = [&]() {
     prologue(false);
-    stage(-1, yes, no, no, first);
-    for (int i = 0; i + 1 < NT; ++i) stage(i, yes, yes, no, first);
-    stage(NT - 1, no, yes, no, first);
+    stage(-1, yes, no, no, first, dyn);
+    for (int i = 0; i + 1 < NT; ++i) stage(i, yes, yes, no, first, dyn);
+    stage(NT - 1, no, yes, no, first, dyn);
   };
   // the walk that mixes: pipeline fill, steady state, drain
   auto walk_main = [&]() {
     if (CIN)
       pre = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(pre_rows, (((SPLIT ? jbase : 0) / BN) * (BM * BN) + tid * 4) * 4, 0, kDeviceScope));
     prologue(true);
-    stage(-1, yes, no, no, ph);                          // logits of tile 0 only
-    if (NT > 1) {
-      stage(0, yes, yes, no, ph);
-      for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes, ph);
-      stage(NT - 1, no, yes, yes, ph);
-    } else {
-      stage(0, no, yes, no, ph);
+    if constexpr (RINGU) {
+      stage(-1, yes, no, no, ph, std::integral_constant<int, 9>{});
+      if (NT > 1) {
+        stage(0, yes, yes, no, ph, std::integral_constant<int, 0>{});
+        steady_unrolled(ph);
+        stage(NT - 1, no, yes, yes, ph, dyn);
+      } else {
+        stage(0, no, yes, no, ph, std::integral_constant<int, 0>{});
+      }
+      stage(NT, no, no, yes, ph, dyn);
+      return;
     }
-    stage(NT, no, no, yes, ph);
+    stage(-1, yes, no, no, ph, dyn);                          // logits of tile 0 only
+    if (NT > 1) {
+      stage(0, yes, yes, no, ph, dyn);
+      for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes, ph, dyn);
+      stage(NT - 1, no, yes, yes, ph, dyn);
+    } else {
+      stage(0, no, yes, no, ph, dyn);
+    }
+    stage(NT, no, no, yes, ph, dyn);
   };
   auto zero_state = [&]() {
 #pragma unroll
@@ -855,9 +904,9 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
       constexpr std::integral_constant<int, 1> first{};
       if (!SPLIT || NT > 0) {
         prologue(false);
-        stage(-1, yes, no, no, first);
-        for (int i = 0; i + 1 < NT; ++i) stage(i, yes, yes, no, first);
-        stage(NT - 1, no, yes, no, first);
+        stage(-1, yes, no, no, first, dyn);
+        for (int i = 0; i + 1 < NT; ++i) stage(i, yes, yes, no, first, dyn);
+        stage(NT - 1, no, yes, no, first, dyn);
       }
       continue;
     }
@@ -876,17 +925,29 @@ __global__ __launch_bounds__(kThreads, 1) void compress_mfma_k(ScanArgs sa, cons
   l_run = 0.f;
   constexpr std::integral_constant<int, CIN ? 2 : 0> ph{};
   prologue(true);
-  stage(-1, yes, no, no, ph);                          // logits of tile 0 only
+  if constexpr (RINGU) {
+  stage(-1, yes, no, no, ph, std::integral_constant<int, 9>{});
+  if (NT > 1) {
+    stage(0, yes, yes, no, ph, std::integral_constant<int, 0>{});
+    steady_unrolled(ph);
+    stage(NT - 1, no, yes, yes, ph, dyn);
+  } else {
+    stage(0, no, yes, no, ph, std::integral_constant<int, 0>{});
+  }
+  stage(NT, no, no, yes, ph, dyn);
+  } else {
+  stage(-1, yes, no, no, ph, dyn);                          // logits of tile 0 only
 
   // ---- pipeline fill, steady state, drain
   if (NT > 1) {
-    stage(0, yes, yes, no, ph);
-    for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes, ph);
-    stage(NT - 1, no, yes, yes, ph);
+    stage(0, yes, yes, no, ph, dyn);
+    for (int i = 1; i + 1 < NT; ++i) stage(i, yes, yes, yes, ph, dyn);
+    stage(NT - 1, no, yes, yes, ph, dyn);
   } else {
-    stage(0, no, yes, no, ph);
+    stage(0, no, yes, no, ph, dyn);
   }
-  stage(NT, no, no, yes, ph);
+  stage(NT, no, no, yes, ph, dyn);
+  }
   } else {                                 // a part without positions hands in an empty result
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
