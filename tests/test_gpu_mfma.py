@@ -85,6 +85,26 @@ def test_mfma_batched_attention_schedule(case):
     assert a[3:] == b[3:]
 
 
+@pytest.mark.parametrize("gains", [(0, 0), (1e-3, 1e-3), (30, 20), (100, 60), (300, 0), (0, 200)])
+@pytest.mark.parametrize("shape", [
+    dict(M=128, B=128), dict(M=512, B=512, n_q_heads=2, n_kv_heads=2),
+    dict(M=96, B=80, n_kv_heads=2, conv_in=1, conv_width=21),
+], ids=["32-slot tiles", "64-slot tiles", "[K|V] width 21"])
+def test_extreme_magnitudes(gains, shape):
+    """All-zero queries, keys and filters (uniform weights), and magnitudes that make both softmaxes
+    one-hot in all but name (logits in the hundreds): one compression from the same state matches the
+    oracle at the usual tolerance; a longer scan stays finite (there a selection may flip on a state
+    that the two sides rounded differently, so it is not compared)."""
+    one = (shape["M"] // shape["B"] + 1) * shape["B"]          # fills, then exactly one compression
+    w = _w(qk_gain=gains[0], conv_gain=gains[1], bias_sigma=0.5, seed=5, L=one, **shape)
+    _run(w, history=True)
+    w4 = w.replace(L=w.M + 3 * w.B)
+    q, k, v = inputs.qkv(w4)
+    cw, cb = inputs.conv_filters(w4)
+    got = gpu_forward(w4, q, k, v, cw, cb, impl=MFMA, history=True)
+    assert all(bool(torch.isfinite(t.float()).all()) for t in got[:3])
+
+
 @pytest.mark.parametrize("case", [
     dict(M=64, B=1, L=6, len0=64),                        # generation with known tokens, from a full cache
     dict(M=128, B=1, L=5, len0=126, n_q_heads=8, n_kv_heads=2),   # two fills, then compressions
