@@ -177,6 +177,8 @@ LOCOCO_API lococo_status lococo_plan(int64_t L, int32_t B, int32_t M, int32_t le
  *                all blocks' attention as one batched launch;
  *   history = G >= 2: room for a window of G blocks (G + 1 cache states): the same
  *                schedule window by window, memory independent of L.
+ * The three schedules return the same bits: which kernel a block's attention runs on depends
+ * on the block alone (a block of one token takes the generation-stage kernel in all of them).
  * May return 0. */
 LOCOCO_API lococo_status lococo_workspace_bytes(const lococo_config* cfg, int64_t L, int32_t B,
                                      int32_t history, size_t* out);
