@@ -1001,9 +1001,8 @@ lococo_status lococo_sequence_forward(const lococo_config* cfg, const lococo_qkv
     }
     const lococo_seg& last = plan.back();
     if (c_done > 0) {
-      HIP_TRY(hipMemcpyAsync(tmp.k[last.buf_after], slot_k(c_done - 1), state_bytes(cfg), hipMemcpyDeviceToDevice, s),
-              "publishing the final cache");
-      HIP_TRY(hipMemcpyAsync(tmp.v[last.buf_after], slot_v(c_done - 1), state_bytes(cfg), hipMemcpyDeviceToDevice, s),
+      HIP_TRY(launch_copy_pair(tmp.k[last.buf_after], slot_k(c_done - 1), tmp.v[last.buf_after], slot_v(c_done - 1),
+                               state_bytes(cfg), s),
               "publishing the final cache");
     }
     tmp.cur = last.buf_after;

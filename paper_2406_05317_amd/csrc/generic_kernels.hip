@@ -337,6 +337,31 @@ hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---- two device-to-device copies of the same length in one launch (the final cache state, keys and values,
+// from the scan's history to the caller's buffer: one kernel node instead of two copy nodes)
+__global__ __launch_bounds__(kThreads) void copy_pair_k(uint4* d0, const uint4* s0, uint4* d1, const uint4* s1, size_t n16) {
+  const size_t step = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += step) {
+    d0[i] = s0[i];
+    d1[i] = s1[i];
+  }
+}
+
+hipError_t launch_copy_pair(void* d0, const void* s0, void* d1, const void* s1, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const uintptr_t bits = (uintptr_t)d0 | (uintptr_t)s0 | (uintptr_t)d1 | (uintptr_t)s1 | (uintptr_t)bytes;
+  if (bits & 15) {                       // not all 16-byte aligned: the runtime's copies
+    hipError_t e = hipMemcpyAsync(d0, s0, bytes, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return e;
+    return hipMemcpyAsync(d1, s1, bytes, hipMemcpyDeviceToDevice, s);
+  }
+  const size_t n16 = bytes / 16;
+  const size_t blocks = (n16 + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL(copy_pair_k, dim3((unsigned)(blocks < 2048 ? blocks : 2048)), dim3(kThreads), 0, s, (uint4*)d0,
+                     (const uint4*)s0, (uint4*)d1, (const uint4*)s1, n16);
+  return hipGetLastError();
+}
+
 hipError_t launch_conv_logits_generic(int dtype, const StepArgs& a, float* logits, hipStream_t s) {
   const int Tn = a.m + a.Bn;
   dim3 grid((Tn + kTJ - 1) / kTJ, (a.M + kTI - 1) / kTI, a.batch * a.Hkv);
