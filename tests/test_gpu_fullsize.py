@@ -105,3 +105,42 @@ def test_results_do_not_depend_on_the_schedule_at_full_size():
     c = gpu_forward(w, q, k, v, cw, cb, history=True)
     for x, y, z in zip(a[:3], b[:3], c[:3]):
         assert torch.equal(x, y) and torch.equal(x, z)
+
+
+def test_a_sequence_of_a_million_tokens():
+    """2^20 tokens of two heads at the cfg3 block and cache sizes (2 048 blocks, 2 047 compressions): far past
+    where a 32-bit element offset into a tensor would wrap.  The windowed and the step-by-step schedule
+    agree bit for bit, a scan one block shorter is a prefix, and the last block matches the oracle run from
+    the state the GPU itself reached a block earlier."""
+    from paper_2406_05317_amd import binding as lb
+    L, B, M = 1 << 20, 512, 512
+    w = inputs.Workload(name="long", dtype="bf16", batch=1, n_q_heads=2, n_kv_heads=2, head_dim=128, L=L, B=B, M=M,
+                        conv_width=15, seed=3, qk_gain=4, conv_gain=3)
+    q, k, v = inputs.qkv(w)
+    cw, _ = inputs.conv_filters(w)
+    cfg = lb.config_for(w, impl=2)
+    qd, kd, vd, cwd = q.cuda(), k.cuda(), v.cuda(), cw.cuda().contiguous()
+
+    def run(Lx, history):
+        od = torch.full((1, 2, Lx, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+        c = lb.Cache(cfg)
+        ws = lb.workspace(cfg, Lx, B, history)
+        lb.lococo_sequence_forward(cfg, qd[:, :, :Lx], kd[:, :, :Lx], vd[:, :, :Lx], od, cwd, None, c, B, ws)
+        torch.cuda.synchronize()
+        assert lb.lococo_scan_status(cfg, ws) == 0
+        return od, c
+
+    o_win, c_win = run(L, 8)
+    o_step, c_step = run(L, 0)
+    assert bool(torch.isfinite(o_win.float()).all())
+    assert torch.equal(o_win, o_step) and torch.equal(c_win.k, c_step.k) and torch.equal(c_win.v, c_step.v)
+    del o_step
+    o_pre, c_pre = run(L - B, 8)
+    assert torch.equal(o_pre, o_win[:, :, :L - B])
+    sl = slice(L - B, L)
+    want = orc.sequence_forward(q[:, :, sl], k[:, :, sl], v[:, :, sl], cw, None, B=B, M=M, state_round="bf16",
+                                cache_k=c_pre.k.cpu().double().numpy(), cache_v=c_pre.v.cpu().double().numpy(),
+                                cache_len=M, nthreads=4)
+    assert_close(to_np(o_win[:, :, sl].cpu()), want[0], TOL["bf16"], "O of the last block")
+    assert_close(to_np(c_win.k.cpu()), want[1], TOL["bf16"], "final cache K")
+    assert_close(to_np(c_win.v.cpu()), want[2], TOL["bf16"], "final cache V")
