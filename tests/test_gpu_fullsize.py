@@ -109,7 +109,7 @@ def test_results_do_not_depend_on_the_schedule_at_full_size():
 
 def test_a_sequence_of_a_million_tokens():
     """2^20 tokens of two heads at the cfg3 block and cache sizes (2 048 blocks, 2 047 compressions): far past
-    where a 32-bit element offset into a tensor would wrap.  The windowed and the step-by-step schedule
+    with the heads of the queries and of the output more than 2^31 elements apart.  The windowed and the step-by-step schedule
     agree bit for bit, a scan one block shorter is a prefix, and the last block matches the oracle run from
     the state the GPU itself reached a block earlier."""
     from paper_2406_05317_amd import binding as lb
@@ -119,10 +119,17 @@ def test_a_sequence_of_a_million_tokens():
     q, k, v = inputs.qkv(w)
     cw, _ = inputs.conv_filters(w)
     cfg = lb.config_for(w, impl=2)
-    qd, kd, vd, cwd = q.cuda(), k.cuda(), v.cuda(), cw.cuda().contiguous()
+    kd, vd, cwd = k.cuda(), v.cuda(), cw.cuda().contiguous()
+    # the two query heads, and the two heads of the output, lie 2^31 + 2^27 elements apart in memory
+    far = (1 << 31) + (1 << 27)
+    q_store = torch.empty(far + L * 128, dtype=torch.bfloat16, device="cuda")
+    o_store = torch.empty(far + L * 128, dtype=torch.bfloat16, device="cuda")
+    qd = q_store.as_strided((1, 2, L, 128), (2 * far, far, 128, 1))
+    qd.copy_(q)
 
     def run(Lx, history):
-        od = torch.full((1, 2, Lx, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+        od = o_store.as_strided((1, 2, Lx, 128), (2 * far, far, 128, 1))
+        od.fill_(float("nan"))
         c = lb.Cache(cfg)
         ws = lb.workspace(cfg, Lx, B, history)
         lb.lococo_sequence_forward(cfg, qd[:, :, :Lx], kd[:, :, :Lx], vd[:, :, :Lx], od, cwd, None, c, B, ws)
@@ -131,10 +138,10 @@ def test_a_sequence_of_a_million_tokens():
         return od, c
 
     o_win, c_win = run(L, 8)
-    o_step, c_step = run(L, 0)
+    o_win = o_win.clone()                  # (the runs share the output store)
     assert bool(torch.isfinite(o_win.float()).all())
+    o_step, c_step = run(L, 0)
     assert torch.equal(o_win, o_step) and torch.equal(c_win.k, c_step.k) and torch.equal(c_win.v, c_step.v)
-    del o_step
     o_pre, c_pre = run(L - B, 8)
     assert torch.equal(o_pre, o_win[:, :, :L - B])
     sl = slice(L - B, L)
