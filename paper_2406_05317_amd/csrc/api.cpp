@@ -1288,7 +1288,7 @@ lococo_status lococo_sequence_backward(const lococo_config* cfg, const lococo_qk
   for (int kv = 0; kv < 2; ++kv) {
     const float* src = kv ? d_final_v : d_final_k;
     if (src) HIP_TRY(hipMemcpyAsync(ws + l.g[w][kv], src, gbytes, hipMemcpyDeviceToDevice, s), "copying the final gradient");
-    else HIP_TRY(hipMemsetAsync(ws + l.g[w][kv], 0, gbytes, s), "clearing the final gradient");
+    else HIP_TRY(launch_zero_fill(ws + l.g[w][kv], gbytes, s), "clearing the final gradient");
   }
   for (int64_t i = n - 1; i >= 0; --i) {
     const lococo_seg& sg = plan[(size_t)i];

@@ -347,6 +347,21 @@ __global__ __launch_bounds__(kThreads) void copy_pair_k(uint4* d0, const uint4* 
   }
 }
 
+// ---- zero-fill as a kernel (a memset node in a captured graph is not relied on)
+__global__ __launch_bounds__(kThreads) void zero_fill_k(uint4* p, size_t n16) {
+  const size_t step = (size_t)gridDim.x * kThreads;
+  const uint4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += step) p[i] = z;
+}
+
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if (((uintptr_t)p | (uintptr_t)bytes) & 15) return hipMemsetAsync(p, 0, bytes, s);   // (no caller here passes such a range)
+  const size_t n16 = bytes / 16, blocks = (n16 + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL(zero_fill_k, dim3((unsigned)(blocks < 2048 ? blocks : 2048)), dim3(kThreads), 0, s, (uint4*)p, n16);
+  return hipGetLastError();
+}
+
 hipError_t launch_copy_pair(void* d0, const void* s0, void* d1, const void* s1, size_t bytes, hipStream_t s) {
   if (bytes == 0) return hipSuccess;
   const uintptr_t bits = (uintptr_t)d0 | (uintptr_t)s0 | (uintptr_t)d1 | (uintptr_t)s1 | (uintptr_t)bytes;

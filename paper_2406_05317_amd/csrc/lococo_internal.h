@@ -143,6 +143,7 @@ hipError_t launch_step_backward_generic(int dtype, const BwdArgs& g, bool compre
 hipError_t launch_attn_generic(int dtype, const StepArgs& a, hipStream_t s);
 hipError_t launch_fill_generic(int dtype, const StepArgs& a, hipStream_t s);
 hipError_t launch_copy_pair(void* d0, const void* s0, void* d1, const void* s1, size_t bytes, hipStream_t s);
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s);
 // logits: fp32 [chains, M, T], T = m + Bn
 hipError_t launch_conv_logits_generic(int dtype, const StepArgs& a, float* logits, hipStream_t s);
 hipError_t launch_normalise_generic(const StepArgs& a, float* logits, hipStream_t s);

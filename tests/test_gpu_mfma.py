@@ -645,3 +645,52 @@ def test_decode_steps_replayed_from_a_hip_graph():
         got[:, :, t - 128:t - 126] = so             # eager work between replays
     assert torch.equal(got, want)
     assert torch.equal(cache.k, want_k) and torch.equal(cache.v, want_v)
+
+
+@pytest.mark.parametrize("history", [True, 2, False], ids=["whole-sequence history", "windows of two blocks", "step by step"])
+def test_a_whole_scan_replayed_from_a_hip_graph(history):
+    """lococo_sequence_forward captured once into a HIP graph (the one-launch compression scan, the batched
+    attention, the copy of the final state: kernels only, no memset node) and replayed several times on fresh
+    inputs in the static buffers, with eager work and synchronisations between the replays: every replay
+    equals the eager call on the same inputs, bit for bit."""
+    w = _w(M=128, B=128, L=128 * 5 + 40, n_q_heads=8, n_kv_heads=4, bias_sigma=0.5)
+    cfg = lb.config_for(w, impl=MFMA)
+    cw, cb = inputs.conv_filters(w)
+    cwd, cbd = cw.cuda().contiguous(), cb.cuda()
+    ws = lb.workspace(cfg, w.L, w.B, history)
+
+    def data(seed):
+        q, k, v = inputs.qkv(w.replace(seed=seed))
+        return q.cuda(), k.cuda(), v.cuda()
+
+    def eager(q, k, v):
+        o = torch.full_like(q, float("nan"))
+        cache = lb.Cache(cfg)
+        lb.lococo_sequence_forward(cfg, q, k, v, o, cwd, cbd, cache, w.B, ws)
+        torch.cuda.synchronize()
+        return o, cache.k.clone(), cache.v.clone(), cache.len, cache.cur
+
+    sq, sk, sv = data(100)
+    so = torch.zeros_like(sq)
+    cache = lb.Cache(cfg)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            lb.lococo_sequence_forward(cfg, sq, sk, sv, so, cwd, cbd, cache, w.B, ws)
+    len_after, cur_after = cache.len, cache.cur
+    for seed in (101, 102, 103, 104):
+        q, k, v = data(seed)
+        want = eager(q, k, v)                       # eager work (on the same workspace) between the replays
+        sq.copy_(q); sk.copy_(k); sv.copy_(v)
+        so.fill_(float("nan"))
+        for buf in cache.kbuf + cache.vbuf:         # the graph starts from an empty cache: occupancy is host state,
+            buf.zero_()                             # the buffers are cleared as a fresh cache's are
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert lb.lococo_scan_status(cfg, ws) == 0
+        assert torch.equal(so, want[0]), seed
+        assert torch.equal(cache.kbuf[cur_after], want[1]) and torch.equal(cache.vbuf[cur_after], want[2]), seed
+        assert (len_after, cur_after) == want[3:]
