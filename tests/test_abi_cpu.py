@@ -255,3 +255,15 @@ def test_size_limits_and_the_newer_entry_points_refuse_on_the_host():
     assert call(ws=None) == lb.LOCOCO_EWORKSPACE
     assert call(ws_bytes=256) == lb.LOCOCO_EWORKSPACE
     assert call(ws=0x200010) == lb.LOCOCO_EWORKSPACE          # not 256-byte aligned
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Everything here runs on one GPU: `bench.py --gpus N` with N above 1 exits with a message that says so."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
