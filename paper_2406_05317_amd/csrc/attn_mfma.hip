@@ -44,6 +44,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // v_cvt_p
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// A value combined with the one the lane 32 away holds (the two halves of a wave share a query): v_permlane32_swap
+// exchanges the upper half of one register with the lower half of another, so of the two results one is the lane's
+// own value and the other its partner's, in either half; a vector instruction, no trip through the LDS crossbar
+// and no wait on the LDS counter in the middle of the operand reads.  (a + b and b + a are the same bits.)
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s supplies the
 // address of 4 consecutive 16-bit elements; lane i of the group receives element (i % 4) of the
 // chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane s pointing at
@@ -273,7 +286,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_a[kt][i]);
-    mx_tile = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx_tile = max_with_other_half(mx);
   }
   tiles_landed();                      // K(1) is in; key buffer 0 is refilled in the first iteration
 
@@ -360,10 +373,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_k(AttnArgs a) {
 #pragma unroll
           for (int e = (g - 4) * 4; e < (g - 4) * 4 + 4; ++e) mxn = fmaxf(mxn, sn[e >> 4][e & 15]);
         }
-        if (g == 13) mx_tile = fmaxf(mxn, __shfl_xor(mxn, 32, 64));
+        if (g == 13) mx_tile = max_with_other_half(mxn);
         LOCOCO_SB();
       }
-      l_run += psum + __shfl_xor(psum, 32, 64);
+      l_run += sum_with_other_half(psum);
     } else {
       request(t + 2, ck, bk, k_dst, true);
       request(t + 1, cv, bv, v_dst, false);
